@@ -1,0 +1,223 @@
+/*
+ * xgm: grammar-constrained decoding masks on AMD CDNA4 (gfx950).
+ *
+ * C ABI of the data-parallel hot path of the structured-generation method of
+ * arxiv 2411.15100 ("XGrammar"): a context-free grammar is compiled on the
+ * host into a byte-level pushdown automaton (one finite automaton per rule,
+ * character edges and rule-reference edges; section 2.2 and Appendix A); once
+ * per (grammar, vocabulary) a GPU kernel classifies every vocabulary token at
+ * every automaton node as accepted / rejected / context-dependent (the token
+ * mask cache of section 3.1); per decoding step a GPU kernel produces each
+ * request's next-token bitmask from the cached bitsets and the request's live
+ * stacks (section 3.1, Algorithm 1: union over parallel stacks), and another
+ * writes -inf into the logits of disallowed tokens (section 2.1).
+ *
+ * Conventions
+ *  - Every function returns 0 (XGM_OK) or a negative xgm_status; a message is
+ *    kept per thread and read with xgm_last_error().  No C++ exception leaves
+ *    the library.
+ *  - Handles are opaque.  Every *_create / *_compile / *_build has a
+ *    *_destroy.  A cache keeps its grammar and vocabulary alive by reference
+ *    count; a matcher keeps its cache alive.  Immutable handles (vocab,
+ *    grammar, cache) may be shared between threads; a matcher may not.
+ *  - Pointers named h_* are host memory, d_* are device memory on the current
+ *    HIP device.  The caller owns every buffer it passes; the library never
+ *    frees or reallocates them.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default
+ *    stream).  Calls documented as asynchronous enqueue work on that stream
+ *    and return without waiting for it.
+ *  - Bitmask layout: row-major int32 [rows, xgm_bitmask_words(V)]; token i is
+ *    bit (i & 31) of word (i >> 5), least significant bit first; 1 = allowed;
+ *    bits at positions >= V are 0.
+ *  - The library needs a gfx950 device for everything except vocabulary and
+ *    grammar handling and the matcher's host state; there is no CPU path for
+ *    the three kernels.
+ */
+#ifndef XGM_H
+#define XGM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct xgm_vocab xgm_vocab;
+typedef struct xgm_grammar xgm_grammar;
+typedef struct xgm_cache xgm_cache;
+typedef struct xgm_matcher xgm_matcher;
+
+typedef enum {
+  XGM_OK = 0,
+  XGM_ERR_BAD_ARG = -1,          /* null pointer, bad size, bad dtype, misaligned buffer */
+  XGM_ERR_PARSE = -2,            /* grammar text is malformed */
+  XGM_ERR_UNDEFINED_RULE = -3,   /* a referenced rule (or the root) is not defined */
+  XGM_ERR_LEFT_RECURSION = -4,   /* a rule can re-enter itself without consuming a byte */
+  XGM_ERR_UNPRODUCTIVE = -5,     /* the root rule derives no string */
+  XGM_ERR_TOKEN_REJECTED = -6,   /* accept_token: token not allowed; state unchanged */
+  XGM_ERR_TERMINATED = -7,       /* accept_token after the stop token */
+  XGM_ERR_TOO_MANY_STACKS = -8,  /* more parallel stacks than XGM_MAX_STACKS; state unchanged */
+  XGM_ERR_TOO_LARGE = -9,        /* automaton, stack depth or vocabulary beyond a documented limit */
+  XGM_ERR_HIP = -10,             /* a HIP runtime call failed, or no device */
+  XGM_ERR_INTERNAL = -11
+} xgm_status;
+
+typedef enum { XGM_F32 = 0, XGM_BF16 = 1, XGM_F16 = 2 } xgm_dtype;
+
+enum {
+  XGM_MAX_STACKS = 64,       /* parallel stacks per matcher */
+  XGM_MAX_STACK_DEPTH = 4096,/* frames per stack */
+  XGM_MAX_NODES = 32767      /* automaton nodes per grammar */
+};
+
+const char* xgm_last_error(void);
+
+/* ceil(V / 32) */
+int32_t xgm_bitmask_words(int32_t V);
+
+/* ---------------------------------------------------------------- vocabulary
+ * Token i is h_bytes[h_offsets[i] .. h_offsets[i+1]) (host memory, copied).
+ * stop_ids are the end-of-generation tokens (section 3 is silent on them; the
+ * reading here: a stop token is allowed exactly when the text generated so
+ * far is a complete sentence of the grammar).  A token with zero bytes that
+ * is not a stop token is never allowed.  The library keeps, on the host and
+ * on the device, the tokens sorted by their bytes (section 3.3: neighbours in
+ * sorted order share prefixes) next to the id order.
+ * Device copies are made lazily by the first xgm_cache_build. */
+int xgm_vocab_create(const uint8_t* h_bytes, const int64_t* h_offsets, int32_t V,
+                     const int32_t* h_stop_ids, int32_t n_stop, xgm_vocab** out);
+void xgm_vocab_destroy(xgm_vocab* v);
+int32_t xgm_vocab_size(const xgm_vocab* v);
+
+/* ------------------------------------------------------------------- grammar
+ * 1. Compile a grammar (host only).  text is UTF-8 EBNF: `name ::= alt`,
+ * alternatives `|`, items "literal" (escapes \" \\ \' \/ \n \t \r \b \f \xHH
+ * \uHHHH), classes [a-z] / [^...] over Unicode scalar values, rule names,
+ * groups ( ), postfix * + ?, `#` comments.  The result is the automaton of
+ * section 2.2 / Appendix A in flattened form: every reachable rule is a
+ * minimal deterministic automaton over bytes and rule references; references
+ * to rules that can match "" may be skipped, and a rule instance always
+ * consumes at least one byte, so that no epsilon cycle exists.
+ * Errors: PARSE, UNDEFINED_RULE, LEFT_RECURSION, UNPRODUCTIVE, TOO_LARGE. */
+int xgm_grammar_compile(const char* text, size_t len, const char* root_rule, xgm_grammar** out);
+void xgm_grammar_destroy(xgm_grammar* g);
+int32_t xgm_grammar_num_nodes(const xgm_grammar* g);
+int32_t xgm_grammar_num_rules(const xgm_grammar* g);
+/* Name of rule r (0 <= r < num_rules), valid while g lives; NULL if out of range. */
+const char* xgm_grammar_rule_name(const xgm_grammar* g, int32_t r);
+/* Rule index that node n belongs to, or a negative status. */
+int32_t xgm_grammar_node_rule(const xgm_grammar* g, int32_t node);
+/* A shortest path of symbols leading from the start of the node's rule to the
+ * node: values 0..255 are bytes, 256 + r is a reference to rule r.  Writes at
+ * most cap symbols to h_out and returns the path length (or a negative
+ * status).  This names a node independently of the library's numbering. */
+int32_t xgm_grammar_node_path(const xgm_grammar* g, int32_t node, int32_t* h_out, int32_t cap);
+/* 1 if the node is accepting in its rule (the rule may end here), else 0. */
+int32_t xgm_grammar_node_is_final(const xgm_grammar* g, int32_t node);
+
+/* --------------------------------------------------------------------- cache
+ * 2. Once per (grammar, vocabulary): build the token mask cache of section
+ * 3.1 on the GPU.  For every node n and token t, starting with n alone on the
+ * stack: accepted if some path consumes all bytes of t without leaving n's
+ * frame downwards; else context-dependent ("uncertain") if some path reaches
+ * the end of n's rule while at least one byte remains; else rejected.  The
+ * result is kept on the device as one accepted bitset per node plus, per node
+ * and per block of 4096 token ids, the list of its context-dependent tokens.
+ * Synchronous: returns after the build has finished on hip_stream. */
+int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out);
+void xgm_cache_destroy(xgm_cache* c);
+int32_t xgm_cache_num_nodes(const xgm_cache* c);
+/* Copies node's accepted and context-dependent bitsets (bitmask layout, each
+ * xgm_bitmask_words(V) words) to host buffers; either pointer may be NULL. */
+int xgm_cache_copy_node_bits(const xgm_cache* c, int32_t node, int32_t* h_acc, int32_t* h_unc);
+/* Number of (node, token) pairs of the build whose walk exceeded the on-chip
+ * bounds and were classified exactly on the host instead (0 for every
+ * workload shipped with this repository). */
+int64_t xgm_cache_host_classified(const xgm_cache* c);
+/* Seconds the GPU spent in the classification kernel during the build, and
+ * the number of (node, token) pairs it classified. */
+double xgm_cache_build_kernel_seconds(const xgm_cache* c);
+
+/* The exact host routine that decides a (node, token) pair whose GPU walk
+ * exceeded its limits during xgm_cache_build: 0 rejected, 1 context-dependent,
+ * 2 accepted, negative status on error.  Exported so that this slow path can
+ * be tested without a device; nothing on the hot path calls it. */
+int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h_bytes, int32_t n);
+/* The token walk of the two GPU kernels, compiled for the host from the same
+ * source and run on the flattened tables, for tests without a device.
+ * h_stack: depth nodes, bottom first.  build != 0: depth must be 1, result is
+ * 0 rejected / 1 context-dependent / 2 accepted as in xgm_cache_build;
+ * build == 0: result is 2 (token allowed from this stack) or 0.  3 = the walk
+ * exceeded its limits (64 frames, 24 alternatives, 4096 steps, 255 bytes). */
+int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth,
+                        const uint8_t* h_bytes, int32_t n, int32_t build);
+
+/* ------------------------------------------------------------------- matcher
+ * Per-request state: the set of parallel stacks of section 2.2, each a list of
+ * automaton nodes (return nodes below, current node on top).  Host memory. */
+int xgm_matcher_create(xgm_cache* c, xgm_matcher** out);
+/* A matcher without a cache (host only; v may be NULL if only accept_bytes is
+ * used): every call below works except xgm_fill_next_token_bitmask. */
+int xgm_matcher_create_host(xgm_grammar* g, xgm_vocab* v, xgm_matcher** out);
+void xgm_matcher_destroy(xgm_matcher* m);
+int xgm_matcher_reset(xgm_matcher* m);
+/* 3. Accept a token: advance every stack over the token's bytes and keep all
+ * survivors (section 3: the sampled token updates the stack state).  A stop
+ * token terminates the matcher if the text is complete.  Errors:
+ * TOKEN_REJECTED / TOO_MANY_STACKS / TOO_LARGE (state unchanged), TERMINATED,
+ * BAD_ARG. */
+int xgm_matcher_accept_token(xgm_matcher* m, int32_t token_id);
+/* Feed raw bytes instead of a token (same semantics and errors). */
+int xgm_matcher_accept_bytes(xgm_matcher* m, const uint8_t* h_bytes, int32_t n);
+int32_t xgm_matcher_is_terminated(const xgm_matcher* m);
+/* 1 if the text accepted so far is a complete sentence. */
+int32_t xgm_matcher_can_terminate(const xgm_matcher* m);
+int32_t xgm_matcher_num_stacks(const xgm_matcher* m);
+/* Depth of stack s and (optionally) its nodes, bottom first, top last. */
+int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int32_t cap);
+
+/* ---------------------------------------------------------------------- fill
+ * 4. Fill the next-token bitmask for a batch (asynchronous).  Row b of
+ * d_bitmask ([B, xgm_bitmask_words(V)], device) becomes
+ *     OR over the stacks s of ms[b] of
+ *        accepted[top(s)]  |  { t context-dependent at top(s) : walking t's
+ *                               bytes from s with the full stack survives }
+ * plus the stop tokens iff the matcher can terminate; a terminated matcher
+ * gets a row with only the stop tokens.  All matchers must share one
+ * vocabulary; their grammars may differ.  The call packs the stacks into
+ * pinned staging owned by the library, enqueues one small host-to-device copy
+ * and the kernel, and returns.
+ * A walk that exceeds the on-chip bounds (64 frames pushed inside one token,
+ * 24 pending alternatives, 4096 steps, tokens longer than 255 bytes) is never
+ * guessed: the pair is recorded on the device, its bit is left 0, and
+ * xgm_fill_overflow_fixup() decides it exactly. */
+int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask,
+                                void* hip_stream);
+/* Synchronises hip_stream, then decides on the host every pair recorded by
+ * the most recent fill and patches that fill's d_bitmask.  Returns the number
+ * of pairs handled (>= 0) or a negative status.  Costs one stream
+ * synchronisation; callers that never see a non-zero xgm_overflow_total() may
+ * skip it. */
+int xgm_fill_overflow_fixup(void* hip_stream);
+/* Total number of pairs recorded by all fills so far (synchronises the
+ * device to read the counter). */
+int64_t xgm_overflow_total(void);
+
+/* --------------------------------------------------------------------- apply
+ * 5. Apply a bitmask to logits in place (asynchronous; section 2.1).
+ * d_logits: [B, V_logits] of dt with row stride row_stride_elems (elements).
+ * d_bitmask: [n_rows, xgm_bitmask_words(V_mask)].  If d_row_index is NULL,
+ * n_rows must equal B and bitmask row j masks logits row j; otherwise bitmask
+ * row j masks logits row d_row_index[j] (device int32, values in [0, B), no
+ * duplicates).  For every masked row: logits[i] becomes -inf where bit i is 0
+ * or i >= V_mask; every other element keeps its exact bit pattern. */
+int xgm_apply_token_bitmask_inplace(void* d_logits, xgm_dtype dt, int32_t B, int32_t V_logits,
+                                    int64_t row_stride_elems, const int32_t* d_bitmask,
+                                    int32_t V_mask, const int32_t* d_row_index, int32_t n_rows,
+                                    void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XGM_H */

@@ -1,0 +1,288 @@
+"""ctypes binding of libxgm.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (minus the
+``xgm_`` prefix).  Device buffers are passed as integer addresses
+(``tensor.data_ptr()``) and streams as integer handles
+(``torch.cuda.current_stream().cuda_stream``); torch itself is not imported.
+The library is loaded from this directory; if it has not been built the
+import of any entry point fails loudly (there is no fallback).
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libxgm.so")
+_lib = None
+
+DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
+
+# name -> (restype, argtypes); must list every symbol include/xgm.h declares
+_vp, _cp, _i32, _i64, _sz = ctypes.c_void_p, ctypes.c_char_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+_pp = ctypes.POINTER(ctypes.c_void_p)
+SIGNATURES = {
+    "xgm_last_error": (_cp, []),
+    "xgm_bitmask_words": (_i32, [_i32]),
+    "xgm_vocab_create": (_i32, [_vp, _vp, _i32, _vp, _i32, _pp]),
+    "xgm_vocab_destroy": (None, [_vp]),
+    "xgm_vocab_size": (_i32, [_vp]),
+    "xgm_grammar_compile": (_i32, [_cp, _sz, _cp, _pp]),
+    "xgm_grammar_destroy": (None, [_vp]),
+    "xgm_grammar_num_nodes": (_i32, [_vp]),
+    "xgm_grammar_num_rules": (_i32, [_vp]),
+    "xgm_grammar_rule_name": (_cp, [_vp, _i32]),
+    "xgm_grammar_node_rule": (_i32, [_vp, _i32]),
+    "xgm_grammar_node_path": (_i32, [_vp, _i32, _vp, _i32]),
+    "xgm_grammar_node_is_final": (_i32, [_vp, _i32]),
+    "xgm_debug_classify_host": (_i32, [_vp, _i32, _cp, _i32]),
+    "xgm_debug_walk_host": (_i32, [_vp, _vp, _i32, _cp, _i32, _i32]),
+    "xgm_cache_build": (_i32, [_vp, _vp, _vp, _pp]),
+    "xgm_cache_destroy": (None, [_vp]),
+    "xgm_cache_num_nodes": (_i32, [_vp]),
+    "xgm_cache_copy_node_bits": (_i32, [_vp, _i32, _vp, _vp]),
+    "xgm_cache_host_classified": (_i64, [_vp]),
+    "xgm_cache_build_kernel_seconds": (ctypes.c_double, [_vp]),
+    "xgm_matcher_create": (_i32, [_vp, _pp]),
+    "xgm_matcher_create_host": (_i32, [_vp, _vp, _pp]),
+    "xgm_matcher_destroy": (None, [_vp]),
+    "xgm_matcher_reset": (_i32, [_vp]),
+    "xgm_matcher_accept_token": (_i32, [_vp, _i32]),
+    "xgm_matcher_accept_bytes": (_i32, [_vp, _cp, _i32]),
+    "xgm_matcher_is_terminated": (_i32, [_vp]),
+    "xgm_matcher_can_terminate": (_i32, [_vp]),
+    "xgm_matcher_num_stacks": (_i32, [_vp]),
+    "xgm_matcher_stack": (_i32, [_vp, _i32, _vp, _i32]),
+    "xgm_fill_next_token_bitmask": (_i32, [_vp, _i32, _vp, _vp]),
+    "xgm_fill_overflow_fixup": (_i32, [_vp]),
+    "xgm_overflow_total": (_i64, []),
+    "xgm_apply_token_bitmask_inplace": (_i32, [_vp, _i32, _i32, _i32, _i64, _vp, _i32, _vp, _i32, _vp]),
+}
+
+STATUS_NAMES = {
+    0: "OK", -1: "BAD_ARG", -2: "PARSE", -3: "UNDEFINED_RULE", -4: "LEFT_RECURSION", -5: "UNPRODUCTIVE",
+    -6: "TOKEN_REJECTED", -7: "TERMINATED", -8: "TOO_MANY_STACKS", -9: "TOO_LARGE", -10: "HIP", -11: "INTERNAL",
+}
+
+
+class XgmError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"XGM_ERR_{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+def load_library():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2411_15100_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise XgmError(rc, load_library().xgm_last_error().decode("utf-8", "replace"))
+    return rc
+
+
+def bitmask_words(V: int) -> int:
+    return load_library().xgm_bitmask_words(V)
+
+
+class Vocab:
+    def __init__(self, data: np.ndarray, offsets: np.ndarray, stop_ids):
+        lib = load_library()
+        data = np.ascontiguousarray(data, dtype=np.uint8)
+        offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+        stops = np.ascontiguousarray(np.asarray(stop_ids, dtype=np.int32))
+        h = ctypes.c_void_p()
+        _check(lib.xgm_vocab_create(data.ctypes.data if data.size else None, offsets.ctypes.data,
+                                    int(offsets.shape[0] - 1), stops.ctypes.data if stops.size else None,
+                                    int(stops.size), ctypes.byref(h)))
+        self._h = h
+        self.size = int(offsets.shape[0] - 1)
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            load_library().xgm_vocab_destroy(self._h)
+            self._h = None
+
+
+class Grammar:
+    def __init__(self, text: str, root: str = "root"):
+        lib = load_library()
+        raw = text.encode("utf-8")
+        h = ctypes.c_void_p()
+        _check(lib.xgm_grammar_compile(raw, len(raw), root.encode(), ctypes.byref(h)))
+        self._h = h
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            load_library().xgm_grammar_destroy(self._h)
+            self._h = None
+
+    @property
+    def num_nodes(self) -> int:
+        return _check(load_library().xgm_grammar_num_nodes(self._h))
+
+    @property
+    def num_rules(self) -> int:
+        return _check(load_library().xgm_grammar_num_rules(self._h))
+
+    def rule_name(self, r: int) -> str:
+        s = load_library().xgm_grammar_rule_name(self._h, r)
+        if s is None:
+            raise XgmError(-1, "rule index out of range")
+        return s.decode()
+
+    def node_rule(self, node: int) -> int:
+        return _check(load_library().xgm_grammar_node_rule(self._h, node))
+
+    def node_is_final(self, node: int) -> bool:
+        return bool(_check(load_library().xgm_grammar_node_is_final(self._h, node)))
+
+    def node_path(self, node: int) -> list:
+        """Path from the start of the node's rule: ints are bytes, strings are rule names."""
+        lib = load_library()
+        n = _check(lib.xgm_grammar_node_path(self._h, node, None, 0))
+        buf = np.zeros(max(n, 1), dtype=np.int32)
+        _check(lib.xgm_grammar_node_path(self._h, node, buf.ctypes.data, n))
+        return [int(s) if s < 256 else self.rule_name(int(s) - 256) for s in buf[:n]]
+
+    def debug_classify_host(self, node: int, data: bytes) -> int:
+        return _check(load_library().xgm_debug_classify_host(self._h, node, data, len(data)))
+
+    def debug_walk_host(self, stack, data: bytes, build: bool) -> int:
+        arr = np.asarray(stack, dtype=np.int32)
+        return _check(load_library().xgm_debug_walk_host(self._h, arr.ctypes.data, int(arr.size), data, len(data),
+                                                         1 if build else 0))
+
+
+class Cache:
+    def __init__(self, grammar: Grammar, vocab: Vocab, stream: int = 0):
+        h = ctypes.c_void_p()
+        _check(load_library().xgm_cache_build(grammar._h, vocab._h, ctypes.c_void_p(stream), ctypes.byref(h)))
+        self._h = h
+        self.grammar = grammar
+        self.vocab = vocab
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            load_library().xgm_cache_destroy(self._h)
+            self._h = None
+
+    @property
+    def num_nodes(self) -> int:
+        return _check(load_library().xgm_cache_num_nodes(self._h))
+
+    @property
+    def host_classified(self) -> int:
+        return load_library().xgm_cache_host_classified(self._h)
+
+    @property
+    def build_kernel_seconds(self) -> float:
+        return load_library().xgm_cache_build_kernel_seconds(self._h)
+
+    def copy_node_bits(self, node: int):
+        W = bitmask_words(self.vocab.size)
+        acc = np.zeros(W, dtype=np.int32)
+        unc = np.zeros(W, dtype=np.int32)
+        _check(load_library().xgm_cache_copy_node_bits(self._h, node, acc.ctypes.data, unc.ctypes.data))
+        return acc, unc
+
+
+class Matcher:
+    def __init__(self, cache: Cache = None, grammar: Grammar = None, vocab: Vocab = None):
+        lib = load_library()
+        h = ctypes.c_void_p()
+        if cache is not None:
+            _check(lib.xgm_matcher_create(cache._h, ctypes.byref(h)))
+            self._keep = (cache,)
+        else:
+            _check(lib.xgm_matcher_create_host(grammar._h, vocab._h if vocab is not None else None, ctypes.byref(h)))
+            self._keep = (grammar, vocab)
+        self._h = h
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            load_library().xgm_matcher_destroy(self._h)
+            self._h = None
+
+    def reset(self):
+        _check(load_library().xgm_matcher_reset(self._h))
+
+    def accept_token(self, token_id: int):
+        _check(load_library().xgm_matcher_accept_token(self._h, int(token_id)))
+
+    def accept_bytes(self, data: bytes):
+        _check(load_library().xgm_matcher_accept_bytes(self._h, data, len(data)))
+
+    def try_accept_bytes(self, data: bytes) -> int:
+        return load_library().xgm_matcher_accept_bytes(self._h, data, len(data))
+
+    def try_accept_token(self, token_id: int) -> int:
+        return load_library().xgm_matcher_accept_token(self._h, int(token_id))
+
+    def is_terminated(self) -> bool:
+        return bool(_check(load_library().xgm_matcher_is_terminated(self._h)))
+
+    def can_terminate(self) -> bool:
+        return bool(_check(load_library().xgm_matcher_can_terminate(self._h)))
+
+    def num_stacks(self) -> int:
+        return _check(load_library().xgm_matcher_num_stacks(self._h))
+
+    def stack(self, s: int) -> list:
+        lib = load_library()
+        n = _check(lib.xgm_matcher_stack(self._h, s, None, 0))
+        buf = np.zeros(max(n, 1), dtype=np.int32)
+        _check(lib.xgm_matcher_stack(self._h, s, buf.ctypes.data, n))
+        return buf[:n].tolist()
+
+
+def fill_next_token_bitmask(matchers, d_bitmask: int, stream: int = 0):
+    """d_bitmask: device address of int32 [len(matchers), bitmask_words(V)]."""
+    arr = (ctypes.c_void_p * len(matchers))(*[m._h for m in matchers])
+    _check(load_library().xgm_fill_next_token_bitmask(arr, len(matchers), ctypes.c_void_p(d_bitmask),
+                                                      ctypes.c_void_p(stream)))
+
+
+class MatcherBatch:
+    """A fixed batch of matchers with the pointer array prepared once."""
+
+    def __init__(self, matchers):
+        self.matchers = list(matchers)
+        self._arr = (ctypes.c_void_p * len(self.matchers))(*[m._h for m in self.matchers])
+
+    def fill_next_token_bitmask(self, d_bitmask: int, stream: int = 0):
+        _check(load_library().xgm_fill_next_token_bitmask(self._arr, len(self.matchers), ctypes.c_void_p(d_bitmask),
+                                                          ctypes.c_void_p(stream)))
+
+
+def fill_overflow_fixup(stream: int = 0) -> int:
+    return _check(load_library().xgm_fill_overflow_fixup(ctypes.c_void_p(stream)))
+
+
+def overflow_total() -> int:
+    return _check(load_library().xgm_overflow_total())
+
+
+def apply_token_bitmask_inplace(d_logits: int, dtype: int, B: int, V_logits: int, row_stride: int, d_bitmask: int,
+                                V_mask: int, d_row_index: int = 0, n_rows: int = None, stream: int = 0):
+    if n_rows is None:
+        n_rows = B
+    _check(load_library().xgm_apply_token_bitmask_inplace(
+        ctypes.c_void_p(d_logits), dtype, B, V_logits, row_stride, ctypes.c_void_p(d_bitmask), V_mask,
+        ctypes.c_void_p(d_row_index) if d_row_index else None, n_rows, ctypes.c_void_p(stream)))

@@ -1,0 +1,727 @@
+// C ABI (include/xgm.h): handles, device memory, staging, error translation.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+#include <mutex>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "../../include/xgm.h"
+#include "automaton.hpp"
+#include "engine.hpp"
+#include "kernels.hpp"
+#include "walk.hpp"
+
+using namespace xgm;
+
+namespace {
+
+thread_local std::string g_error;
+
+void hip_check(hipError_t e, const char* what) {
+  if (e != hipSuccess) throw Failure(XGM_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_OK(call) hip_check((call), #call)
+
+template <class T>
+T* dev_alloc(size_t n) {
+  void* p = nullptr;
+  HIP_OK(hipMalloc(&p, std::max<size_t>(n, 1) * sizeof(T)));
+  return static_cast<T*>(p);
+}
+template <class T>
+T* dev_upload(const std::vector<T>& v) {
+  T* p = dev_alloc<T>(v.size());
+  if (!v.empty()) HIP_OK(hipMemcpy(p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
+  return p;
+}
+
+void require_device() {
+  int n = 0;
+  hipError_t e = hipGetDeviceCount(&n);
+  if (e != hipSuccess || n <= 0)
+    throw Failure(XGM_ERR_HIP, "no HIP device: the mask kernels have no CPU path");
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ handles
+struct xgm_vocab {
+  std::atomic<int> refs{1};
+  int32_t V = 0;
+  std::vector<uint8_t> bytes;
+  std::vector<uint32_t> off;  // [V+1]
+  std::vector<int32_t> stop;
+  std::vector<char> is_stop;
+  std::vector<int32_t> rank_of_id, id_of_rank;
+  std::mutex mu;
+  bool on_device = false;
+  DevVocab dv{};
+  std::vector<void*> dev_ptrs;
+  ~xgm_vocab() { for (void* p : dev_ptrs) (void)hipFree(p); }
+};
+struct xgm_grammar {
+  std::atomic<int> refs{1};
+  Automaton A;
+};
+struct xgm_cache {
+  std::atomic<int> refs{1};
+  xgm_grammar* g = nullptr;
+  xgm_vocab* v = nullptr;
+  DevCache host{};           // the struct as uploaded (device pointers)
+  DevCache* d_struct = nullptr;
+  std::vector<void*> dev_ptrs;
+  std::vector<uint32_t> unc_off_host;  // [n_nodes][n_chunk+1]
+  int64_t host_classified = 0;
+  double kernel_seconds = 0.0;
+};
+struct xgm_matcher {
+  xgm_cache* c = nullptr;
+  xgm_grammar* g = nullptr;
+  xgm_vocab* v = nullptr;
+  std::vector<Stack> stacks;
+  bool terminated = false;
+};
+
+namespace {
+
+void release(xgm_vocab* v) { if (v && --v->refs == 0) delete v; }
+void release(xgm_grammar* g) { if (g && --g->refs == 0) delete g; }
+void release(xgm_cache* c) {
+  if (c && --c->refs == 0) {
+    for (void* p : c->dev_ptrs) (void)hipFree(p);
+    release(c->g);
+    release(c->v);
+    delete c;
+  }
+}
+
+void vocab_to_device(xgm_vocab* v) {
+  std::lock_guard<std::mutex> lock(v->mu);
+  if (v->on_device) return;
+  require_device();
+  const int32_t V = v->V;
+  auto row_of = [&](int32_t id) {
+    uint4 r = make_uint4(0, 0, 0, 0);
+    unsigned char b[16] = {0};
+    uint32_t len = v->off[id + 1] - v->off[id];
+    for (uint32_t k = 0; k < std::min<uint32_t>(len, 15); ++k) b[k] = v->bytes[v->off[id] + k];
+    b[15] = (unsigned char)std::min<uint32_t>(len, 255);
+    std::memcpy(&r, b, 16);
+    return r;
+  };
+  std::vector<uint4> by_id(V), by_rank(V);
+  for (int32_t i = 0; i < V; ++i) by_id[i] = row_of(i);
+  for (int32_t r = 0; r < V; ++r) by_rank[r] = by_id[v->id_of_rank[r]];
+  DevVocab& d = v->dv;
+  auto keep = [&](auto* p) { v->dev_ptrs.push_back((void*)p); return p; };
+  d.tok_by_id = keep(dev_upload(by_id));
+  d.tok_by_rank = keep(dev_upload(by_rank));
+  d.off_by_id = keep(dev_upload(v->off));
+  d.bytes = keep(dev_upload(v->bytes));
+  d.rank_of_id = keep(dev_upload(v->rank_of_id));
+  d.id_of_rank = keep(dev_upload(v->id_of_rank));
+  d.stop_ids = keep(dev_upload(v->stop));
+  d.n_stop = (int32_t)v->stop.size();
+  d.V = V;
+  d.W = (V + 31) / 32;
+  d.WR = ((V + 63) / 64) * 2;
+  d.n_chunk = (d.W + kChunkWords - 1) / kChunkWords;
+  v->on_device = true;
+}
+
+// --- process-wide device context: overflow log and the fill staging ring
+struct FillSlot {
+  void* h_buf = nullptr;  // pinned
+  void* d_buf = nullptr;
+  size_t cap = 0;
+  hipEvent_t done = nullptr;
+  bool used = false;
+};
+struct Context {
+  std::mutex mu;
+  OverflowLog* d_log = nullptr;
+  uint32_t seq = 0;
+  uint32_t seen_count = 0;  // log entries already examined by a fixup
+  static constexpr int kSlots = 8;
+  FillSlot slot[kSlots];
+  int next_slot = 0;
+  // the most recent fill (for xgm_fill_overflow_fixup)
+  int last_slot = -1;
+  uint32_t last_seq = 0;
+  int32_t last_B = 0;
+  int32_t* last_bitmask = nullptr;
+  std::vector<const xgm_matcher*> last_matchers;
+  xgm_vocab* last_vocab = nullptr;
+};
+Context& ctx() {
+  static Context c;
+  return c;
+}
+OverflowLog* overflow_log() {
+  Context& c = ctx();
+  if (!c.d_log) {
+    require_device();
+    c.d_log = dev_alloc<OverflowLog>(1);
+    HIP_OK(hipMemset(c.d_log, 0, sizeof(OverflowLog)));
+  }
+  return c.d_log;
+}
+uint32_t read_overflow_count() {
+  uint32_t n = 0;
+  HIP_OK(hipMemcpy(&n, &overflow_log()->count, sizeof(n), hipMemcpyDeviceToHost));
+  return n;
+}
+
+int fail(const Failure& f) {
+  g_error = f.what();
+  return f.status;
+}
+int fail(int status, const std::string& msg) {
+  g_error = msg;
+  return status;
+}
+
+}  // namespace
+
+#define API_BEGIN try {
+#define API_END                                                                        \
+  }                                                                                    \
+  catch (const Failure& f) { return fail(f); }                                         \
+  catch (const std::bad_alloc&) { return fail(XGM_ERR_INTERNAL, "out of host memory"); } \
+  catch (const std::exception& e) { return fail(XGM_ERR_INTERNAL, e.what()); }
+
+extern "C" {
+
+const char* xgm_last_error(void) { return g_error.c_str(); }
+int32_t xgm_bitmask_words(int32_t V) { return V <= 0 ? 0 : (V + 31) / 32; }
+
+// ---------------------------------------------------------------- vocabulary
+int xgm_vocab_create(const uint8_t* h_bytes, const int64_t* h_offsets, int32_t V, const int32_t* h_stop_ids,
+                     int32_t n_stop, xgm_vocab** out) {
+  API_BEGIN
+  if (!out) return fail(XGM_ERR_BAD_ARG, "vocab_create: out is null");
+  *out = nullptr;
+  if (V <= 0 || !h_offsets) return fail(XGM_ERR_BAD_ARG, "vocab_create: V must be positive and offsets non-null");
+  if (n_stop < 0 || (n_stop > 0 && !h_stop_ids)) return fail(XGM_ERR_BAD_ARG, "vocab_create: bad stop ids");
+  if (h_offsets[0] != 0) return fail(XGM_ERR_BAD_ARG, "vocab_create: offsets[0] must be 0");
+  for (int32_t i = 0; i < V; ++i)
+    if (h_offsets[i + 1] < h_offsets[i]) return fail(XGM_ERR_BAD_ARG, "vocab_create: offsets must not decrease");
+  if (h_offsets[V] > 0 && !h_bytes) return fail(XGM_ERR_BAD_ARG, "vocab_create: bytes is null");
+  if (h_offsets[V] >= (int64_t)1 << 31) return fail(XGM_ERR_TOO_LARGE, "vocab_create: more than 2 GiB of token bytes");
+  auto v = new xgm_vocab();
+  v->V = V;
+  v->bytes.assign(h_bytes, h_bytes + h_offsets[V]);
+  v->off.resize(V + 1);
+  for (int32_t i = 0; i <= V; ++i) v->off[i] = (uint32_t)h_offsets[i];
+  v->is_stop.assign(V, 0);
+  for (int32_t k = 0; k < n_stop; ++k) {
+    if (h_stop_ids[k] < 0 || h_stop_ids[k] >= V) { delete v; return fail(XGM_ERR_BAD_ARG, "vocab_create: stop id out of range"); }
+    if (!v->is_stop[h_stop_ids[k]]) { v->is_stop[h_stop_ids[k]] = 1; v->stop.push_back(h_stop_ids[k]); }
+  }
+  v->id_of_rank.resize(V);
+  std::iota(v->id_of_rank.begin(), v->id_of_rank.end(), 0);
+  const uint8_t* base = v->bytes.data();
+  const std::vector<uint32_t>& off = v->off;
+  std::stable_sort(v->id_of_rank.begin(), v->id_of_rank.end(), [&](int32_t a, int32_t b) {
+    size_t la = off[a + 1] - off[a], lb = off[b + 1] - off[b];
+    int c = std::memcmp(base + off[a], base + off[b], std::min(la, lb));
+    return c != 0 ? c < 0 : la < lb;
+  });
+  v->rank_of_id.resize(V);
+  for (int32_t r = 0; r < V; ++r) v->rank_of_id[v->id_of_rank[r]] = r;
+  *out = v;
+  return XGM_OK;
+  API_END
+}
+void xgm_vocab_destroy(xgm_vocab* v) { release(v); }
+int32_t xgm_vocab_size(const xgm_vocab* v) { return v ? v->V : XGM_ERR_BAD_ARG; }
+
+// ------------------------------------------------------------------- grammar
+int xgm_grammar_compile(const char* text, size_t len, const char* root_rule, xgm_grammar** out) {
+  API_BEGIN
+  if (!out) return fail(XGM_ERR_BAD_ARG, "grammar_compile: out is null");
+  *out = nullptr;
+  if (!text || !root_rule) return fail(XGM_ERR_BAD_ARG, "grammar_compile: null text or root rule");
+  auto g = new xgm_grammar();
+  try {
+    g->A = compile_grammar(std::string(text, len), root_rule);
+  } catch (...) {
+    delete g;
+    throw;
+  }
+  *out = g;
+  return XGM_OK;
+  API_END
+}
+void xgm_grammar_destroy(xgm_grammar* g) { release(g); }
+int32_t xgm_grammar_num_nodes(const xgm_grammar* g) { return g ? g->A.n_nodes : XGM_ERR_BAD_ARG; }
+int32_t xgm_grammar_num_rules(const xgm_grammar* g) { return g ? (int32_t)g->A.rule_names.size() : XGM_ERR_BAD_ARG; }
+const char* xgm_grammar_rule_name(const xgm_grammar* g, int32_t r) {
+  if (!g || r < 0 || r >= (int32_t)g->A.rule_names.size()) return nullptr;
+  return g->A.rule_names[r].c_str();
+}
+int32_t xgm_grammar_node_rule(const xgm_grammar* g, int32_t node) {
+  if (!g || node < 0 || node >= g->A.n_nodes) return fail(XGM_ERR_BAD_ARG, "node out of range");
+  return g->A.node_rule[node];
+}
+int32_t xgm_grammar_node_path(const xgm_grammar* g, int32_t node, int32_t* h_out, int32_t cap) {
+  if (!g || node < 0 || node >= g->A.n_nodes || cap < 0 || (cap > 0 && !h_out)) return fail(XGM_ERR_BAD_ARG, "node_path: bad argument");
+  const auto& p = g->A.node_path[node];
+  for (int32_t k = 0; k < std::min<int32_t>(cap, (int32_t)p.size()); ++k) h_out[k] = p[k];
+  return (int32_t)p.size();
+}
+int32_t xgm_grammar_node_is_final(const xgm_grammar* g, int32_t node) {
+  if (!g || node < 0 || node >= g->A.n_nodes) return fail(XGM_ERR_BAD_ARG, "node out of range");
+  return g->A.node_final[node];
+}
+
+int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h_bytes, int32_t n) {
+  API_BEGIN
+  if (!g || node < 0 || node >= g->A.n_nodes || n < 0 || (n > 0 && !h_bytes)) return fail(XGM_ERR_BAD_ARG, "classify_host: bad argument");
+  int cls = Engine(&g->A).classify(node, h_bytes, n);
+  if (cls < 0) return fail(XGM_ERR_TOO_LARGE, "classify_host: configuration limit exceeded");
+  return cls;
+  API_END
+}
+
+int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth, const uint8_t* h_bytes,
+                        int32_t n, int32_t build) {
+  API_BEGIN
+  if (!g || !h_stack || depth < 1 || depth > XGM_MAX_STACK_DEPTH || n < 0 || (n > 0 && !h_bytes))
+    return fail(XGM_ERR_BAD_ARG, "walk_host: bad argument");
+  if (build && depth != 1) return fail(XGM_ERR_BAD_ARG, "walk_host: the classifying walk starts from a single node");
+  const Automaton& A = g->A;
+  std::vector<uint16_t> live(depth);
+  for (int32_t k = 0; k < depth; ++k) {
+    if (h_stack[k] < 0 || h_stack[k] >= A.n_nodes) return fail(XGM_ERR_BAD_ARG, "walk_host: node out of range");
+    live[k] = (uint16_t)h_stack[k];
+  }
+  if (n == 0) return kReject;
+  DevTables T{reinterpret_cast<const uint2*>(A.hdr.data()), A.cls.data(), A.rows.data(), A.alts.data(), A.n_cls};
+  unsigned char row[16] = {0};
+  std::memcpy(row, h_bytes, std::min<int32_t>(n, 15));
+  row[15] = (unsigned char)std::min<int32_t>(n, 255);
+  uint4 tk;
+  std::memcpy(&tk, row, 16);
+  return build ? walk_token<true>(T, tk, h_bytes, n, live[depth - 1], nullptr, 1u)
+               : walk_token<false>(T, tk, h_bytes, n, live[depth - 1], live.data(), (uint32_t)depth);
+  API_END
+}
+
+// --------------------------------------------------------------------- cache
+int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out) {
+  API_BEGIN
+  if (!out) return fail(XGM_ERR_BAD_ARG, "cache_build: out is null");
+  *out = nullptr;
+  if (!g || !v) return fail(XGM_ERR_BAD_ARG, "cache_build: null grammar or vocabulary");
+  require_device();
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  vocab_to_device(v);
+  const DevVocab& dv = v->dv;
+  const Automaton& A = g->A;
+  const int32_t N = A.n_nodes;
+
+  auto c = new xgm_cache();
+  c->g = g; ++g->refs;
+  c->v = v; ++v->refs;
+  std::vector<void*> temps;
+  auto cleanup_temps = [&] { for (void* p : temps) (void)hipFree(p); temps.clear(); };
+  try {
+    auto keep = [&](auto* p) { c->dev_ptrs.push_back((void*)p); return p; };
+    auto temp = [&](auto* p) { temps.push_back((void*)p); return p; };
+    // automaton tables
+    static_assert(sizeof(NodeHdr) == sizeof(uint2), "header layout");
+    std::vector<uint2> hdr(N);
+    std::memcpy(hdr.data(), A.hdr.data(), (size_t)N * sizeof(uint2));
+    DevTables tab{};
+    tab.hdr = keep(dev_upload(hdr));
+    tab.cls = keep(dev_upload(A.cls));
+    tab.rows = keep(dev_upload(A.rows));
+    tab.alts = keep(dev_upload(A.alts));
+    tab.n_cls = A.n_cls;
+    const int32_t n_rows_tab = (int32_t)(A.rows.size() / std::max(1, A.n_cls));
+    const int32_t n_alts = (int32_t)A.alts.size();
+    const size_t table_bytes = (size_t)N * 8 + (size_t)n_alts * 4 + (size_t)n_rows_tab * A.n_cls * 2 + 256;
+
+    uint32_t* acc_id = keep(dev_alloc<uint32_t>((size_t)N * dv.W));
+    uint32_t* unc_id = temp(dev_alloc<uint32_t>((size_t)N * dv.W));
+    // rank-space scratch for a batch of nodes (at most 1 GiB for both bitsets)
+    const size_t row_bytes = (size_t)dv.WR * 4;
+    int32_t batch = (int32_t)std::max<size_t>(1, std::min<size_t>((size_t)N, ((size_t)512 << 20) / row_bytes));
+    uint32_t* acc_rank = temp(dev_alloc<uint32_t>((size_t)batch * dv.WR));
+    uint32_t* unc_rank = temp(dev_alloc<uint32_t>((size_t)batch * dv.WR));
+    OverflowLog* log;
+    uint32_t seq, count_before;
+    {
+      std::lock_guard<std::mutex> lock(ctx().mu);
+      log = overflow_log();
+      seq = ++ctx().seq;
+      HIP_OK(hipStreamSynchronize(stream));
+      count_before = read_overflow_count();
+    }
+    hipEvent_t ev0, ev1;
+    HIP_OK(hipEventCreate(&ev0));
+    HIP_OK(hipEventCreate(&ev1));
+    Engine engine(&A);
+    for (int32_t node0 = 0; node0 < N; node0 += batch) {
+      const int32_t nb = std::min(batch, N - node0);
+      HIP_OK(hipEventRecord(ev0, stream));
+      launch_classify(tab, table_bytes, n_rows_tab, n_alts, N, dv, node0, nb, acc_rank, unc_rank, log, seq, stream);
+      HIP_OK(hipEventRecord(ev1, stream));
+      HIP_OK(hipGetLastError());
+      HIP_OK(hipStreamSynchronize(stream));
+      float ms = 0.f;
+      HIP_OK(hipEventElapsedTime(&ms, ev0, ev1));
+      c->kernel_seconds += ms * 1e-3;
+      // pairs that hit a limit: decide them on the host, patch the bitsets
+      uint32_t count_after = read_overflow_count();
+      uint32_t fresh = count_after - count_before;
+      if (fresh > 0) {
+        if (fresh > OverflowLog::kCap) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: too many walks exceeded the on-chip limits");
+        std::vector<uint32_t> ent((size_t)OverflowLog::kCap * 3);
+        HIP_OK(hipMemcpy(ent.data(), log->entry, ent.size() * 4, hipMemcpyDeviceToHost));
+        std::vector<uint32_t> items;
+        for (uint32_t k = 0; k < fresh; ++k) {
+          const uint32_t* e = &ent[(size_t)((count_before + k) % OverflowLog::kCap) * 3];
+          if (e[0] != seq) continue;
+          const int32_t id = v->id_of_rank[e[2]];
+          int cls = engine.classify(node0 + (int32_t)e[1], v->bytes.data() + v->off[id], (int)(v->off[id + 1] - v->off[id]));
+          if (cls < 0) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: a token walk exceeds the host limits too");
+          items.push_back(e[1]); items.push_back(e[2]); items.push_back((uint32_t)cls);
+          ++c->host_classified;
+        }
+        if (!items.empty()) {
+          uint32_t* d_items = dev_upload(items);
+          launch_patch_classes(dv, d_items, (int32_t)(items.size() / 3), acc_rank, unc_rank, stream);
+          HIP_OK(hipStreamSynchronize(stream));
+          (void)hipFree(d_items);
+        }
+        count_before = count_after;
+        std::lock_guard<std::mutex> lock(ctx().mu);
+        ctx().seen_count = count_after;
+      }
+      launch_permute(dv, nb, acc_rank, unc_rank, acc_id + (size_t)node0 * dv.W, unc_id + (size_t)node0 * dv.W, stream);
+      HIP_OK(hipGetLastError());
+      HIP_OK(hipStreamSynchronize(stream));
+    }
+    (void)hipEventDestroy(ev0);
+    (void)hipEventDestroy(ev1);
+    // context-dependent lists
+    uint32_t* d_counts = temp(dev_alloc<uint32_t>((size_t)N * dv.n_chunk));
+    launch_count_uncertain(dv, N, unc_id, d_counts, stream);
+    HIP_OK(hipGetLastError());
+    HIP_OK(hipStreamSynchronize(stream));
+    std::vector<uint32_t> counts((size_t)N * dv.n_chunk);
+    HIP_OK(hipMemcpy(counts.data(), d_counts, counts.size() * 4, hipMemcpyDeviceToHost));
+    c->unc_off_host.assign((size_t)N * (dv.n_chunk + 1), 0);
+    uint64_t total = 0;
+    for (int32_t n = 0; n < N; ++n) {
+      for (int32_t k = 0; k < dv.n_chunk; ++k) {
+        c->unc_off_host[(size_t)n * (dv.n_chunk + 1) + k] = (uint32_t)total;
+        total += counts[(size_t)n * dv.n_chunk + k];
+      }
+      c->unc_off_host[(size_t)n * (dv.n_chunk + 1) + dv.n_chunk] = (uint32_t)total;
+      if (total >= ((uint64_t)1 << 32)) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: context-dependent lists exceed 2^32 entries");
+    }
+    uint32_t* d_off = keep(dev_upload(c->unc_off_host));
+    uint16_t* d_list = keep(dev_alloc<uint16_t>((size_t)total));
+    launch_list_uncertain(dv, N, unc_id, d_off, d_list, stream);
+    HIP_OK(hipGetLastError());
+    HIP_OK(hipStreamSynchronize(stream));
+    cleanup_temps();
+
+    c->host.tab = tab;
+    c->host.acc = acc_id;
+    c->host.unc_off = d_off;
+    c->host.unc_list = d_list;
+    c->host.n_nodes = N;
+    c->d_struct = keep(dev_alloc<DevCache>(1));
+    HIP_OK(hipMemcpy(c->d_struct, &c->host, sizeof(DevCache), hipMemcpyHostToDevice));
+  } catch (...) {
+    cleanup_temps();
+    release(c);
+    throw;
+  }
+  *out = c;
+  return XGM_OK;
+  API_END
+}
+void xgm_cache_destroy(xgm_cache* c) { release(c); }
+int32_t xgm_cache_num_nodes(const xgm_cache* c) { return c ? c->host.n_nodes : XGM_ERR_BAD_ARG; }
+int64_t xgm_cache_host_classified(const xgm_cache* c) { return c ? c->host_classified : XGM_ERR_BAD_ARG; }
+double xgm_cache_build_kernel_seconds(const xgm_cache* c) { return c ? c->kernel_seconds : -1.0; }
+
+int xgm_cache_copy_node_bits(const xgm_cache* c, int32_t node, int32_t* h_acc, int32_t* h_unc) {
+  API_BEGIN
+  if (!c || node < 0 || node >= c->host.n_nodes) return fail(XGM_ERR_BAD_ARG, "copy_node_bits: bad cache or node");
+  const DevVocab& dv = c->v->dv;
+  if (h_acc) HIP_OK(hipMemcpy(h_acc, c->host.acc + (size_t)node * dv.W, (size_t)dv.W * 4, hipMemcpyDeviceToHost));
+  if (h_unc) {
+    std::memset(h_unc, 0, (size_t)dv.W * 4);
+    const uint32_t* off = &c->unc_off_host[(size_t)node * (dv.n_chunk + 1)];
+    const uint32_t n = off[dv.n_chunk] - off[0];
+    std::vector<uint16_t> list(n);
+    if (n) HIP_OK(hipMemcpy(list.data(), c->host.unc_list + off[0], (size_t)n * 2, hipMemcpyDeviceToHost));
+    for (int32_t k = 0; k < dv.n_chunk; ++k)
+      for (uint32_t j = off[k]; j < off[k + 1]; ++j) {
+        const uint32_t id = (uint32_t)k * kChunkTokens + list[j - off[0]];
+        reinterpret_cast<uint32_t*>(h_unc)[id >> 5] |= 1u << (id & 31);
+      }
+  }
+  return XGM_OK;
+  API_END
+}
+
+// ------------------------------------------------------------------- matcher
+static int matcher_new(xgm_cache* c, xgm_grammar* g, xgm_vocab* v, xgm_matcher** out) {
+  auto m = new xgm_matcher();
+  m->c = c; if (c) ++c->refs;
+  m->g = g; ++g->refs;
+  m->v = v; if (v) ++v->refs;
+  m->stacks = {Stack{g->A.rule_start[g->A.root_rule]}};
+  *out = m;
+  return XGM_OK;
+}
+int xgm_matcher_create(xgm_cache* c, xgm_matcher** out) {
+  API_BEGIN
+  if (!c || !out) return fail(XGM_ERR_BAD_ARG, "matcher_create: null argument");
+  return matcher_new(c, c->g, c->v, out);
+  API_END
+}
+int xgm_matcher_create_host(xgm_grammar* g, xgm_vocab* v, xgm_matcher** out) {
+  API_BEGIN
+  if (!g || !out) return fail(XGM_ERR_BAD_ARG, "matcher_create_host: null argument");
+  return matcher_new(nullptr, g, v, out);
+  API_END
+}
+void xgm_matcher_destroy(xgm_matcher* m) {
+  if (!m) return;
+  release(m->c);
+  release(m->g);
+  release(m->v);
+  delete m;
+}
+int xgm_matcher_reset(xgm_matcher* m) {
+  if (!m) return fail(XGM_ERR_BAD_ARG, "matcher_reset: null matcher");
+  m->stacks = {Stack{m->g->A.rule_start[m->g->A.root_rule]}};
+  m->terminated = false;
+  return XGM_OK;
+}
+int xgm_matcher_accept_bytes(xgm_matcher* m, const uint8_t* h_bytes, int32_t n) {
+  API_BEGIN
+  if (!m || n < 0 || (n > 0 && !h_bytes)) return fail(XGM_ERR_BAD_ARG, "accept_bytes: bad argument");
+  if (m->terminated) return fail(XGM_ERR_TERMINATED, "accept: the matcher has terminated");
+  if (n == 0) return XGM_OK;
+  Engine e(&m->g->A);
+  std::vector<Stack> next;
+  int rc = e.advance(m->stacks, h_bytes, n, &next, nullptr, XGM_MAX_STACKS);
+  if (rc == XGM_ERR_TOKEN_REJECTED) return fail(rc, "accept: the bytes are not allowed here");
+  if (rc == XGM_ERR_TOO_MANY_STACKS) return fail(rc, "accept: more than 64 parallel stacks");
+  if (rc != XGM_OK) return fail(rc, "accept: stack depth or configuration limit exceeded");
+  m->stacks.swap(next);
+  return XGM_OK;
+  API_END
+}
+int xgm_matcher_accept_token(xgm_matcher* m, int32_t token_id) {
+  API_BEGIN
+  if (!m || !m->v) return fail(XGM_ERR_BAD_ARG, "accept_token: matcher has no vocabulary");
+  if (token_id < 0 || token_id >= m->v->V) return fail(XGM_ERR_BAD_ARG, "accept_token: token id out of range");
+  if (m->terminated) return fail(XGM_ERR_TERMINATED, "accept: the matcher has terminated");
+  const xgm_vocab& v = *m->v;
+  if (v.is_stop[token_id]) {
+    if (!Engine(&m->g->A).can_terminate(m->stacks)) return fail(XGM_ERR_TOKEN_REJECTED, "accept: stop token before the text is complete");
+    m->terminated = true;
+    return XGM_OK;
+  }
+  const int32_t n = (int32_t)(v.off[token_id + 1] - v.off[token_id]);
+  if (n == 0) return fail(XGM_ERR_TOKEN_REJECTED, "accept: a token without bytes is never allowed");
+  return xgm_matcher_accept_bytes(m, v.bytes.data() + v.off[token_id], n);
+  API_END
+}
+int32_t xgm_matcher_is_terminated(const xgm_matcher* m) { return m ? (m->terminated ? 1 : 0) : XGM_ERR_BAD_ARG; }
+int32_t xgm_matcher_can_terminate(const xgm_matcher* m) {
+  if (!m) return XGM_ERR_BAD_ARG;
+  return (!m->terminated && Engine(&m->g->A).can_terminate(m->stacks)) ? 1 : 0;
+}
+int32_t xgm_matcher_num_stacks(const xgm_matcher* m) { return m ? (m->terminated ? 0 : (int32_t)m->stacks.size()) : XGM_ERR_BAD_ARG; }
+int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int32_t cap) {
+  if (!m || s < 0 || s >= (int32_t)m->stacks.size() || cap < 0 || (cap > 0 && !h_nodes)) return fail(XGM_ERR_BAD_ARG, "matcher_stack: bad argument");
+  const Stack& st = m->stacks[s];
+  for (int32_t k = 0; k < std::min<int32_t>(cap, (int32_t)st.size()); ++k) h_nodes[k] = st[k];
+  return (int32_t)st.size();
+}
+
+// ---------------------------------------------------------------------- fill
+int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream) {
+  API_BEGIN
+  if (!ms || B <= 0 || !d_bitmask) return fail(XGM_ERR_BAD_ARG, "fill: null argument or empty batch");
+  xgm_vocab* v = nullptr;
+  size_t n_stacks = 0, n_frames = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    const xgm_matcher* m = ms[b];
+    if (!m || !m->c) return fail(XGM_ERR_BAD_ARG, "fill: matcher is null or has no cache");
+    if (v && m->v != v) return fail(XGM_ERR_BAD_ARG, "fill: all matchers must share one vocabulary");
+    v = m->v;
+    if (m->terminated) continue;
+    n_stacks += m->stacks.size();
+    for (auto& s : m->stacks) {
+      if (s.size() > XGM_MAX_STACK_DEPTH) return fail(XGM_ERR_TOO_LARGE, "fill: stack deeper than 4096 frames");
+      n_frames += s.size();
+    }
+  }
+  require_device();
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const size_t off_stacks = (size_t)B * sizeof(RowDesc);
+  const size_t off_frames = off_stacks + n_stacks * sizeof(StackDesc);
+  const size_t bytes = ((off_frames + n_frames * 2 + 63) / 64) * 64;
+
+  Context& C = ctx();
+  std::lock_guard<std::mutex> lock(C.mu);
+  OverflowLog* log = overflow_log();
+  FillSlot& slot = C.slot[C.next_slot];
+  if (slot.used) HIP_OK(hipEventSynchronize(slot.done));
+  if (slot.cap < bytes) {
+    if (slot.h_buf) (void)hipHostFree(slot.h_buf);
+    if (slot.d_buf) (void)hipFree(slot.d_buf);
+    slot.h_buf = slot.d_buf = nullptr;
+    slot.cap = std::max<size_t>(bytes * 2, 1 << 16);
+    HIP_OK(hipHostMalloc(&slot.h_buf, slot.cap, hipHostMallocDefault));
+    HIP_OK(hipMalloc(&slot.d_buf, slot.cap));
+  }
+  if (!slot.done) HIP_OK(hipEventCreateWithFlags(&slot.done, hipEventDisableTiming));
+  auto* rows = reinterpret_cast<RowDesc*>(slot.h_buf);
+  auto* stacks = reinterpret_cast<StackDesc*>((char*)slot.h_buf + off_stacks);
+  auto* frames = reinterpret_cast<uint16_t*>((char*)slot.h_buf + off_frames);
+  uint32_t si = 0, fi = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    const xgm_matcher* m = ms[b];
+    RowDesc& r = rows[b];
+    r.pad = 0;
+    r.stack_begin = si;
+    if (m->terminated) {
+      r.cache = nullptr;
+      r.n_stacks = 0;
+      r.flags = 1;
+      continue;
+    }
+    r.cache = m->c->d_struct;
+    r.n_stacks = (uint32_t)m->stacks.size();
+    r.flags = Engine(&m->g->A).can_terminate(m->stacks) ? 1u : 0u;
+    for (auto& s : m->stacks) {
+      stacks[si].frame_off = fi;
+      stacks[si].depth = (uint32_t)s.size();
+      ++si;
+      for (int32_t n : s) frames[fi++] = (uint16_t)n;
+    }
+  }
+  HIP_OK(hipMemcpyAsync(slot.d_buf, slot.h_buf, bytes, hipMemcpyHostToDevice, stream));
+  const uint32_t seq = ++C.seq;
+  launch_fill(reinterpret_cast<const RowDesc*>(slot.d_buf),
+              reinterpret_cast<const StackDesc*>((char*)slot.d_buf + off_stacks),
+              reinterpret_cast<const uint16_t*>((char*)slot.d_buf + off_frames), B, v->dv,
+              reinterpret_cast<uint32_t*>(d_bitmask), log, seq, stream);
+  HIP_OK(hipGetLastError());
+  HIP_OK(hipEventRecord(slot.done, stream));
+  slot.used = true;
+  C.last_slot = C.next_slot;
+  C.next_slot = (C.next_slot + 1) % Context::kSlots;
+  C.last_seq = seq;
+  C.last_B = B;
+  C.last_bitmask = d_bitmask;
+  C.last_vocab = v;
+  C.last_matchers.assign(ms, ms + B);
+  return XGM_OK;
+  API_END
+}
+
+int xgm_fill_overflow_fixup(void* hip_stream) {
+  API_BEGIN
+  Context& C = ctx();
+  std::lock_guard<std::mutex> lock(C.mu);
+  if (C.last_slot < 0) return 0;
+  HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+  const uint32_t count = read_overflow_count();
+  const uint32_t fresh = count - C.seen_count;
+  if (fresh == 0) return 0;
+  if (fresh > OverflowLog::kCap) return fail(XGM_ERR_TOO_LARGE, "fixup: more recorded walks than the log holds");
+  std::vector<uint32_t> ent((size_t)OverflowLog::kCap * 3);
+  HIP_OK(hipMemcpy(ent.data(), overflow_log()->entry, ent.size() * 4, hipMemcpyDeviceToHost));
+  // the staging blob of the last fill still holds that fill's stacks
+  const FillSlot& slot = C.slot[C.last_slot];
+  const auto* rows = reinterpret_cast<const RowDesc*>(slot.h_buf);
+  const auto* stacks = reinterpret_cast<const StackDesc*>((const char*)slot.h_buf + (size_t)C.last_B * sizeof(RowDesc));
+  size_t n_stacks = 0;
+  for (int32_t b = 0; b < C.last_B; ++b) n_stacks += rows[b].n_stacks;
+  const auto* frames = reinterpret_cast<const uint16_t*>((const char*)stacks + n_stacks * sizeof(StackDesc));
+  const xgm_vocab& v = *C.last_vocab;
+  const int32_t W = v.dv.W;
+  int handled = 0;
+  for (uint32_t k = 0; k < fresh; ++k) {
+    const uint32_t* e = &ent[(size_t)((C.seen_count + k) % OverflowLog::kCap) * 3];
+    if (e[0] != C.last_seq) continue;
+    const int32_t b = (int32_t)e[1], id = (int32_t)e[2];
+    const xgm_matcher* m = C.last_matchers[b];
+    Engine engine(&m->g->A);
+    bool ok = false;
+    for (uint32_t s = 0; s < rows[b].n_stacks && !ok; ++s) {
+      const StackDesc& sd = stacks[rows[b].stack_begin + s];
+      Stack st(frames + sd.frame_off, frames + sd.frame_off + sd.depth);
+      std::vector<Stack> out;
+      int rc = engine.advance({st}, v.bytes.data() + v.off[id], (int)(v.off[id + 1] - v.off[id]), &out, nullptr, (size_t)-1);
+      if (rc == XGM_OK) ok = true;
+      else if (rc != XGM_ERR_TOKEN_REJECTED) return fail(rc, "fixup: a token walk exceeds the host limits too");
+    }
+    if (ok) {
+      uint32_t word = 0;
+      int32_t* p = C.last_bitmask + (size_t)b * W + (id >> 5);
+      HIP_OK(hipMemcpy(&word, p, 4, hipMemcpyDeviceToHost));
+      word |= 1u << (id & 31);
+      HIP_OK(hipMemcpy(p, &word, 4, hipMemcpyHostToDevice));
+    }
+    ++handled;
+  }
+  C.seen_count = count;
+  return handled;
+  API_END
+}
+
+int64_t xgm_overflow_total(void) {
+  try {
+    std::lock_guard<std::mutex> lock(ctx().mu);
+    HIP_OK(hipDeviceSynchronize());
+    return (int64_t)read_overflow_count();
+  } catch (const Failure& f) { return fail(f); }
+}
+
+// --------------------------------------------------------------------- apply
+int xgm_apply_token_bitmask_inplace(void* d_logits, xgm_dtype dt, int32_t B, int32_t V_logits, int64_t row_stride_elems,
+                                    const int32_t* d_bitmask, int32_t V_mask, const int32_t* d_row_index,
+                                    int32_t n_rows, void* hip_stream) {
+  API_BEGIN
+  if (!d_logits || !d_bitmask) return fail(XGM_ERR_BAD_ARG, "apply: null logits or bitmask");
+  if (B <= 0 || V_logits <= 0 || V_mask <= 0 || n_rows < 0) return fail(XGM_ERR_BAD_ARG, "apply: sizes must be positive");
+  if (row_stride_elems < V_logits) return fail(XGM_ERR_BAD_ARG, "apply: row stride smaller than the row");
+  if (!d_row_index && n_rows != B) return fail(XGM_ERR_BAD_ARG, "apply: without a row index n_rows must equal B");
+  if (d_row_index && n_rows > B) return fail(XGM_ERR_BAD_ARG, "apply: more mask rows than logits rows");
+  int esize;
+  uint32_t ninf;
+  switch (dt) {
+    case XGM_F32: esize = 4; ninf = 0xFF800000u; break;
+    case XGM_BF16: esize = 2; ninf = 0xFF80u; break;
+    case XGM_F16: esize = 2; ninf = 0xFC00u; break;
+    default: return fail(XGM_ERR_BAD_ARG, "apply: unknown dtype");
+  }
+  if (reinterpret_cast<uintptr_t>(d_logits) % esize != 0) return fail(XGM_ERR_BAD_ARG, "apply: logits pointer is not aligned to its element size");
+  require_device();
+  launch_apply(d_logits, esize, ninf, V_logits, row_stride_elems, reinterpret_cast<const uint32_t*>(d_bitmask), V_mask,
+               d_row_index, n_rows, static_cast<hipStream_t>(hip_stream));
+  HIP_OK(hipGetLastError());
+  return XGM_OK;
+  API_END
+}
+
+}  // extern "C"
