@@ -131,6 +131,8 @@ int32_t xgm_cache_num_nodes(const xgm_cache* c);
 /* Copies node's accepted and context-dependent bitsets (bitmask layout, each
  * xgm_bitmask_words(V) words) to host buffers; either pointer may be NULL. */
 int xgm_cache_copy_node_bits(const xgm_cache* c, int32_t node, int32_t* h_acc, int32_t* h_unc);
+/* Number of context-dependent tokens cached for a node (or a negative status). */
+int32_t xgm_cache_num_uncertain(const xgm_cache* c, int32_t node);
 /* Number of (node, token) pairs of the build whose walk exceeded the on-chip
  * bounds and were classified exactly on the host instead (0 for every
  * workload shipped with this repository). */

@@ -11,6 +11,7 @@
 #include <bitset>
 #include <cstdint>
 #include <map>
+#include <mutex>
 #include <utility>
 #include <vector>
 
@@ -34,7 +35,20 @@ inline int encode_utf8(uint32_t cp, unsigned char out[4]) {
   return 4;
 }
 
+inline ByteDag class_to_dag_uncached(const std::vector<std::pair<uint32_t, uint32_t>>& ranges, bool negated);
+
+// The result depends only on the class, so it is computed once per process.
 inline ByteDag class_to_dag(const std::vector<std::pair<uint32_t, uint32_t>>& ranges, bool negated) {
+  static std::mutex mu;
+  static std::map<std::pair<std::vector<std::pair<uint32_t, uint32_t>>, bool>, ByteDag> memo;
+  std::lock_guard<std::mutex> lock(mu);
+  auto key = std::make_pair(ranges, negated);
+  auto it = memo.find(key);
+  if (it == memo.end()) it = memo.emplace(key, class_to_dag_uncached(ranges, negated)).first;
+  return it->second;
+}
+
+inline ByteDag class_to_dag_uncached(const std::vector<std::pair<uint32_t, uint32_t>>& ranges, bool negated) {
   // membership table over all code points
   std::vector<bool> in(0x110000, false);
   for (auto& r : ranges)

@@ -44,6 +44,7 @@ SIGNATURES = {
     "xgm_cache_destroy": (None, [_vp]),
     "xgm_cache_num_nodes": (_i32, [_vp]),
     "xgm_cache_copy_node_bits": (_i32, [_vp, _i32, _vp, _vp]),
+    "xgm_cache_num_uncertain": (_i32, [_vp, _i32]),
     "xgm_cache_host_classified": (_i64, [_vp]),
     "xgm_cache_build_kernel_seconds": (ctypes.c_double, [_vp]),
     "xgm_matcher_create": (_i32, [_vp, _pp]),
@@ -74,6 +75,25 @@ class XgmError(RuntimeError):
         self.status = status
 
 
+def _preload_hip_runtime():
+    """One process must hold one HIP runtime.  PyTorch ships its own copy of
+    libamdhip64 and loads it by file path; if this library were loaded first it
+    would pull in the system copy under the same soname and the process would
+    end up with two runtimes that do not see each other's devices or memory.
+    So, when PyTorch is installed, its copy is loaded first (without importing
+    torch); libxgm's dependency then resolves to it by soname."""
+    import importlib.util
+    import sys
+    if "torch" in sys.modules:
+        return
+    spec = importlib.util.find_spec("torch")
+    if spec is None or not spec.origin:
+        return
+    path = os.path.join(os.path.dirname(spec.origin), "lib", "libamdhip64.so")
+    if os.path.exists(path):
+        ctypes.CDLL(path, mode=ctypes.RTLD_GLOBAL)
+
+
 def load_library():
     global _lib
     if _lib is not None:
@@ -82,6 +102,7 @@ def load_library():
         raise ImportError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2411_15100_amd.build` "
             "(there is no fallback implementation)")
+    _preload_hip_runtime()
     lib = ctypes.CDLL(_LIB_PATH)
     for name, (res, args) in SIGNATURES.items():
         fn = getattr(lib, name)
@@ -186,6 +207,9 @@ class Cache:
     @property
     def num_nodes(self) -> int:
         return _check(load_library().xgm_cache_num_nodes(self._h))
+
+    def num_uncertain(self, node: int) -> int:
+        return _check(load_library().xgm_cache_num_uncertain(self._h, node))
 
     @property
     def host_classified(self) -> int:

@@ -452,6 +452,12 @@ int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** 
 }
 void xgm_cache_destroy(xgm_cache* c) { release(c); }
 int32_t xgm_cache_num_nodes(const xgm_cache* c) { return c ? c->host.n_nodes : XGM_ERR_BAD_ARG; }
+int32_t xgm_cache_num_uncertain(const xgm_cache* c, int32_t node) {
+  if (!c || node < 0 || node >= c->host.n_nodes) return fail(XGM_ERR_BAD_ARG, "num_uncertain: bad cache or node");
+  const int32_t nc = c->v->dv.n_chunk;
+  const uint32_t* off = &c->unc_off_host[(size_t)node * (nc + 1)];
+  return (int32_t)(off[nc] - off[0]);
+}
 int64_t xgm_cache_host_classified(const xgm_cache* c) { return c ? c->host_classified : XGM_ERR_BAD_ARG; }
 double xgm_cache_build_kernel_seconds(const xgm_cache* c) { return c ? c->kernel_seconds : -1.0; }
 

@@ -18,7 +18,7 @@ from .grammars import (
     random_schema,
 )
 from .logits import make_logits
-from .walks import pick_token, STRUCTURAL_BYTES
+from .walks import pick_token, pick_tokens, STRUCTURAL_BYTES
 
 __all__ = [
     "make_vocab",
@@ -31,5 +31,6 @@ __all__ = [
     "random_schema",
     "make_logits",
     "pick_token",
+    "pick_tokens",
     "STRUCTURAL_BYTES",
 ]

@@ -37,3 +37,37 @@ def pick_token(rng: np.random.Generator, allowed: np.ndarray, first_bytes: np.nd
         if m.any():
             non_stop = non_stop[m]
     return int(non_stop[int(rng.integers(0, non_stop.size))])
+
+
+def pick_tokens(rng: np.random.Generator, allowed: np.ndarray, structural: np.ndarray, is_stop: np.ndarray,
+                structural_bias: float = 0.0) -> np.ndarray:
+    """Batched version of :func:`pick_token` for ``allowed`` of shape [B, V].
+
+    One vector of random priorities is drawn per call and shared by all rows
+    (rows are independent requests with different masks); each row takes its
+    allowed token of highest priority.  ``structural`` / ``is_stop``: bool [V].
+    Returns int64 [B]; -1 where nothing is allowed; a stop token only where
+    nothing else is allowed.
+    """
+    B, V = allowed.shape
+    keys = rng.random(V, dtype=np.float32) + np.float32(1e-6)
+    use_struct = rng.random(B) < structural_bias
+    out = np.full(B, -1, dtype=np.int64)
+    non_stop = allowed & ~is_stop[None, :]
+    score = non_stop * keys[None, :]
+    if structural_bias > 0.0:
+        s_score = score * structural[None, :]
+        s_best = s_score.argmax(axis=1)
+        s_ok = s_score[np.arange(B), s_best] > 0
+    best = score.argmax(axis=1)
+    ok = score[np.arange(B), best] > 0
+    for b in range(B):
+        if structural_bias > 0.0 and use_struct[b] and s_ok[b]:
+            out[b] = s_best[b]
+        elif ok[b]:
+            out[b] = best[b]
+        else:
+            stops = np.flatnonzero(allowed[b] & is_stop)
+            if stops.size:
+                out[b] = stops[0]
+    return out

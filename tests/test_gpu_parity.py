@@ -1,0 +1,388 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle,
+bit for bit, on the five workloads and on edge cases.  Every expected value
+comes from `oracle/`; nothing here is read from a file written by the GPU."""
+
+import sys
+import zlib
+
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def xgm():
+    import paper_2411_15100_amd as lib
+    lib.load_library()
+    return lib
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_2411_15100_amd import workloads
+    return workloads
+
+
+def _stream():
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+@pytest.fixture
+def no_overflow(xgm):
+    """The test must not record a single walk that exceeded the on-chip limits
+    (so no result in it came from the host slow path)."""
+    before = xgm.overflow_total()
+    yield
+    assert xgm.overflow_total() == before
+
+
+def _apply_and_check(xgm, logits_np, dtype_code, torch_dtype, neg_inf_bits, d_mask, allowed, V):
+    """Apply on the GPU and compare raw bit patterns with the oracle's apply."""
+    B = logits_np.shape[0]
+    t = torch.from_numpy(logits_np).to("cuda").to(torch_dtype).contiguous()
+    view = torch.int32 if torch_dtype == torch.float32 else torch.int16
+    before = t.view(view).cpu().numpy().view(np.uint32 if view == torch.int32 else np.uint16)
+    xgm.apply_token_bitmask_inplace(t.data_ptr(), dtype_code, B, t.shape[1], t.stride(0), d_mask.data_ptr(), V,
+                                    stream=_stream())
+    after = t.view(view).cpu().numpy().view(before.dtype)
+    want = oracle.apply_mask(before, allowed, neg_inf_bits)
+    assert np.array_equal(after, want)
+    return after
+
+
+# --------------------------------------------------------------------------
+# workload 1: arithmetic grammar, vocabulary 1024, batch 1, 64 steps, fp32
+# --------------------------------------------------------------------------
+def test_workload1_arith_every_step(xgm, wl, no_overflow):
+    say("workload 1: arith V=1024 B=1 steps=64")
+    vocab = si.make_vocab("arith", 1024, 0)
+    g = xgm.Grammar(si.ARITH_GRAMMAR, "expr")
+    cache = xgm.Cache(g, wl.make_xgm_vocab(vocab))
+    assert cache.host_classified == 0
+    walker = wl.BatchWalker([cache], vocab, seed=0, structural_bias=0.0)
+    og = oracle.Grammar(si.ARITH_GRAMMAR, "expr")
+    om = oracle.EarleyMatcher(og)
+    toks = vocab.tokens()
+    for step in range(64):
+        words = walker.fill()
+        want = om.mask(vocab)
+        assert np.array_equal(words, oracle.pack_bitmask(want)[None, :]), f"step {step}"
+        logits = si.make_logits(1, 1024, seed=1000 + step)
+        _apply_and_check(xgm, logits, xgm.DTYPE_F32, torch.float32, 0xFF800000, walker.d_mask, want[None, :], 1024)
+        t = int(walker.step(words)[0])
+        if not walker.history[0]:      # the request terminated and was re-seeded
+            om = oracle.EarleyMatcher(og)
+        else:
+            assert om.advance(toks[t])
+
+
+# --------------------------------------------------------------------------
+# workload 2: JSON, vocabulary 32000, batch 1, 256 steps, fp32
+# --------------------------------------------------------------------------
+def test_workload2_json_every_step(xgm, wl, no_overflow):
+    say("workload 2: json V=32000 B=1 steps=256")
+    vocab = si.make_vocab("bpe", 32000, 0)
+    g = xgm.Grammar(si.JSON_GRAMMAR, "root")
+    cache = xgm.Cache(g, wl.make_xgm_vocab(vocab))
+    assert cache.host_classified == 0
+    walker = wl.BatchWalker([cache], vocab, seed=2, structural_bias=0.35)
+    og = oracle.Grammar(si.JSON_GRAMMAR, "root")
+    om = oracle.EarleyMatcher(og)
+    toks = vocab.tokens()
+    n_multi = 0
+    for step in range(256):
+        words = walker.fill()
+        want = om.mask(vocab)
+        assert np.array_equal(words, oracle.pack_bitmask(want)[None, :]), f"step {step}"
+        n_multi += walker.matchers[0].num_stacks() > 1
+        if step % 16 == 0:
+            logits = si.make_logits(1, 32000, seed=2000 + step)
+            _apply_and_check(xgm, logits, xgm.DTYPE_F32, torch.float32, 0xFF800000, walker.d_mask, want[None, :], 32000)
+        t = int(walker.step(words)[0])
+        if not walker.history[0]:
+            om = oracle.EarleyMatcher(og)
+        else:
+            assert om.advance(toks[t])
+    say(f"  steps with several parallel stacks: {n_multi}")
+
+
+# --------------------------------------------------------------------------
+# workload 3: schema grammar, vocabulary 128256, batch 16, 512 steps, bf16
+# --------------------------------------------------------------------------
+def test_workload3_schema_batch16(xgm, wl, no_overflow):
+    say("workload 3: schema V=128256 B=16 steps=512 (oracle on every 32nd step of every row)")
+    vocab = si.make_vocab("bpe", 128256, 0)
+    text = si.make_schema_grammar(0)
+    g = xgm.Grammar(text, "root")
+    cache = xgm.Cache(g, wl.make_xgm_vocab(vocab))
+    assert cache.host_classified == 0
+    B = 16
+    walker = wl.BatchWalker([cache] * B, vocab, seed=3, structural_bias=0.35)
+    og = oracle.Grammar(text, "root")
+    oms = [oracle.EarleyMatcher(og) for _ in range(B)]
+    toks = vocab.tokens()
+    checked = 0
+    for step in range(512):
+        words = walker.fill()
+        if step % 32 == 0:
+            want = np.stack([om.mask(vocab) for om in oms])
+            assert np.array_equal(words, oracle.pack_bitmask(want)), f"step {step}"
+            checked += B
+            logits = si.make_logits(B, 128256, seed=3000 + step, sigma=2.0)
+            _apply_and_check(xgm, logits, xgm.DTYPE_BF16, torch.bfloat16, 0xFF80, walker.d_mask, want, 128256)
+            say(f"  step {step}: {B} rows bit-exact")
+        picks = walker.step(words)
+        for b in range(B):
+            if not walker.history[b]:
+                oms[b] = oracle.EarleyMatcher(og)
+            else:
+                assert oms[b].advance(toks[int(picks[b])])
+    assert checked == 256
+
+
+# --------------------------------------------------------------------------
+# workload 4: mask-cache build, 128256 tokens at every node
+# --------------------------------------------------------------------------
+def _check_cache_classes(xgm, cache, g, og, vocab, nodes):
+    V = vocab.size
+    for node in nodes:
+        want = og.classify(g.rule_name(g.node_rule(node)), g.node_path(node), vocab)
+        acc, unc = cache.copy_node_bits(node)
+        assert np.array_equal(acc, oracle.pack_bitmask(want == 2)), ("accepted", node, g.node_path(node))
+        assert np.array_equal(unc, oracle.pack_bitmask(want == 1)), ("uncertain", node, g.node_path(node))
+        assert cache.num_uncertain(node) == int((want == 1).sum())
+
+
+def test_workload4_cache_build_json_all_nodes(xgm, wl, no_overflow):
+    say("workload 4(i): json cache, V=128256, every node")
+    vocab = si.make_vocab("bpe", 128256, 0)
+    g = xgm.Grammar(si.JSON_GRAMMAR, "root")
+    cache = xgm.Cache(g, wl.make_xgm_vocab(vocab))
+    assert cache.host_classified == 0
+    og = oracle.Grammar(si.JSON_GRAMMAR, "root")
+    _check_cache_classes(xgm, cache, g, og, vocab, range(g.num_nodes))
+    say(f"  {g.num_nodes} nodes x {vocab.size} tokens bit-exact; kernel {cache.build_kernel_seconds*1e3:.2f} ms")
+
+
+def test_workload4_cache_build_csql_sample(xgm, wl):
+    say("workload 4(ii): C/SQL-like cache, V=128256, seeded 4% of the nodes")
+    vocab = si.make_vocab("bpe", 128256, 0)
+    g = xgm.Grammar(si.CSQL_GRAMMAR, "root")
+    cache = xgm.Cache(g, wl.make_xgm_vocab(vocab))
+    say(f"  pairs decided on the host after exceeding a walk limit: {cache.host_classified}")
+    og = oracle.Grammar(si.CSQL_GRAMMAR, "root")
+    rng = np.random.Generator(np.random.PCG64(44))
+    nodes = sorted(set(int(n) for n in rng.integers(0, g.num_nodes, size=30)))
+    _check_cache_classes(xgm, cache, g, og, vocab, nodes)
+    say(f"  {len(nodes)} of {g.num_nodes} nodes bit-exact; kernel {cache.build_kernel_seconds*1e3:.2f} ms")
+
+
+# --------------------------------------------------------------------------
+# workload 5 (reduced batch; the full batch-128 configuration is checked in
+# test_gpu_serving.py): distinct string-heavy schema grammars, V = 151936
+# --------------------------------------------------------------------------
+def test_workload5_distinct_grammars_batch8(xgm, wl, no_overflow):
+    say("workload 5 (8 distinct grammars): V=151936 bf16")
+    vocab = si.make_vocab("bpe", 151936, 0)
+    xv = wl.make_xgm_vocab(vocab)
+    texts = [si.make_schema_grammar(s, string_heavy=True) for s in range(8)]
+    caches = [xgm.Cache(xgm.Grammar(t, "root"), xv) for t in texts]
+    walker = wl.BatchWalker(caches, vocab, seed=5, structural_bias=0.35)
+    ogs = [oracle.Grammar(t, "root") for t in texts]
+    oms = [oracle.EarleyMatcher(o) for o in ogs]
+    toks = vocab.tokens()
+    for step in range(40):
+        words = walker.fill()
+        if step % 8 == 7:
+            want = np.stack([om.mask(vocab) for om in oms])
+            assert np.array_equal(words, oracle.pack_bitmask(want)), f"step {step}"
+            logits = si.make_logits(8, 151936, seed=5000 + step)
+            _apply_and_check(xgm, logits, xgm.DTYPE_BF16, torch.bfloat16, 0xFF80, walker.d_mask, want, 151936)
+            say(f"  step {step}: 8 rows bit-exact; uncertain fraction at the tops "
+                f"{wl.uncertain_fraction(walker, caches).mean():.3f}")
+        picks = walker.step(words)
+        for b in range(8):
+            if not walker.history[b]:
+                oms[b] = oracle.EarleyMatcher(ogs[b])
+            else:
+                assert oms[b].advance(toks[int(picks[b])])
+
+
+# --------------------------------------------------------------------------
+# apply: dtypes, ragged sizes, row subsets, strides, special values
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype_name", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("V,Vl", [(1000, 1000), (1003, 1003), (37, 41), (4097, 4100), (64, 64)])
+def test_apply_shapes_and_special_values(xgm, dtype_name, V, Vl):
+    code, tdt, ninf, udt = {
+        "f32": (xgm.DTYPE_F32, torch.float32, 0xFF800000, np.uint32),
+        "bf16": (xgm.DTYPE_BF16, torch.bfloat16, 0xFF80, np.uint16),
+        "f16": (xgm.DTYPE_F16, torch.float16, 0xFC00, np.uint16),
+    }[dtype_name]
+    rng = np.random.Generator(np.random.PCG64(V * 7 + Vl))
+    B = 5
+    allowed = rng.random((B, V)) < 0.5
+    allowed[0] = True
+    allowed[1] = False
+    allowed[2, : V // 2] = True
+    # raw bit patterns, including NaNs, infinities, zeros and subnormals
+    bits = rng.integers(0, 2 ** (16 if udt == np.uint16 else 32), size=(B, Vl), dtype=np.uint64).astype(udt)
+    view = torch.int32 if udt == np.uint32 else torch.int16
+    sview = np.int32 if udt == np.uint32 else np.int16
+    for stride in (Vl, Vl + 3, ((Vl + 7) // 8) * 8):
+        buf = torch.zeros((B, stride), dtype=view, device="cuda")
+        buf[:, :Vl] = torch.from_numpy(bits.view(sview)).cuda()
+        t = buf.view(tdt)
+        d_mask = torch.from_numpy(oracle.pack_bitmask(allowed)).cuda()
+        xgm.apply_token_bitmask_inplace(t.data_ptr(), code, B, Vl, stride, d_mask.data_ptr(), V, stream=_stream())
+        got = buf[:, :Vl].cpu().numpy().view(udt)
+        assert np.array_equal(got, oracle.apply_mask(bits, allowed, ninf)), (dtype_name, V, Vl, stride)
+        assert (buf[:, Vl:].cpu().numpy() == 0).all()  # padding beyond the row is never written
+
+
+def test_apply_row_subset(xgm):
+    V, B = 5000, 6
+    rng = np.random.Generator(np.random.PCG64(17))
+    allowed = rng.random((3, V)) < 0.3
+    bits = rng.integers(0, 2 ** 16, size=(B, V), dtype=np.uint64).astype(np.uint16)
+    t = torch.from_numpy(bits.view(np.int16)).cuda()
+    rows = np.array([4, 0, 3], dtype=np.int32)
+    d_rows = torch.from_numpy(rows).cuda()
+    d_mask = torch.from_numpy(oracle.pack_bitmask(allowed)).cuda()
+    xgm.apply_token_bitmask_inplace(t.data_ptr(), xgm.DTYPE_BF16, B, V, V, d_mask.data_ptr(), V,
+                                    d_row_index=d_rows.data_ptr(), n_rows=3, stream=_stream())
+    got = t.cpu().numpy().view(np.uint16)
+    want = bits.copy()
+    for j, r in enumerate(rows):
+        want[r] = oracle.apply_mask(bits[r:r + 1], allowed[j:j + 1], 0xFF80)[0]
+    assert np.array_equal(got, want)
+
+
+def test_apply_argument_errors(xgm):
+    t = torch.zeros((2, 64), dtype=torch.float32, device="cuda")
+    m = torch.zeros((2, 2), dtype=torch.int32, device="cuda")
+    for kwargs in [dict(d_logits=0), dict(dtype=7), dict(V_logits=0), dict(row_stride=10), dict(n_rows=1)]:
+        args = dict(d_logits=t.data_ptr(), dtype=xgm.DTYPE_F32, B=2, V_logits=64, row_stride=64,
+                    d_bitmask=m.data_ptr(), V_mask=64, n_rows=2)
+        args.update(kwargs)
+        with pytest.raises(xgm.XgmError) as e:
+            xgm.apply_token_bitmask_inplace(**args)
+        assert e.value.status == -1
+
+
+# --------------------------------------------------------------------------
+# fill: edge cases
+# --------------------------------------------------------------------------
+def test_fill_terminated_rows_ragged_vocab_and_stop_tokens(xgm, wl):
+    # vocabulary size not a multiple of 32, two stop tokens
+    toks = [b"1", b"2", b"+", b"*", b"(", b")", b" ", b"12", b"+1", b")*", b"", b"((", b"1)", b"", b"3 "] + \
+           [bytes([48 + k % 10]) * (1 + k % 3) + b"+" for k in range(28)]
+    V = len(toks)
+    assert V % 32 != 0
+
+    class V_:  # minimal vocabulary object for both sides
+        data = np.frombuffer(b"".join(toks), dtype=np.uint8).copy()
+        offsets = np.concatenate([[0], np.cumsum([len(t) for t in toks])]).astype(np.int64)
+        stop_ids = np.array([10, 13], dtype=np.int32)
+
+    xv = xgm.Vocab(V_.data, V_.offsets, V_.stop_ids)
+    g = xgm.Grammar(si.ARITH_GRAMMAR, "expr")
+    cache = xgm.Cache(g, xv)
+    og = oracle.Grammar(si.ARITH_GRAMMAR, "expr")
+    ms = [xgm.Matcher(cache=cache) for _ in range(4)]
+    oms = [oracle.EarleyMatcher(og) for _ in range(4)]
+    for m, om, text in zip(ms, oms, [b"", b"1", b"(1+2", b"1 "]):
+        if text:
+            m.accept_bytes(text)
+            assert om.advance(text)
+    ms[1].accept_token(10)  # stop: row 1 is terminated now
+    W = xgm.bitmask_words(V)
+    d = torch.full((4, W), -1, dtype=torch.int32, device="cuda")
+    xgm.fill_next_token_bitmask(ms, d.data_ptr(), _stream())
+    got = d.cpu().numpy()
+    want = np.stack([om.mask(V_) for om in oms])
+    want[1] = False
+    want[1, [10, 13]] = True  # a terminated request allows only the stop tokens
+    assert np.array_equal(got, oracle.pack_bitmask(want))
+    assert not want[0, 10] and want[3].sum() > 0
+    with pytest.raises(xgm.XgmError):
+        xgm.fill_next_token_bitmask([], d.data_ptr(), _stream())
+
+
+def test_fill_deep_stacks_and_many_parallel_stacks(xgm, wl, no_overflow):
+    vocab = si.make_vocab("bpe", 32000, 0)
+    xv = wl.make_xgm_vocab(vocab)
+    g = xgm.Grammar(si.JSON_GRAMMAR, "root")
+    cache = xgm.Cache(g, xv)
+    og = oracle.Grammar(si.JSON_GRAMMAR, "root")
+    text = b"[" * 300 + b'{"a":' + b"[" * 200 + b"1"
+    m = xgm.Matcher(cache=cache)
+    m.accept_bytes(text)
+    assert len(m.stack(0)) > 1000
+    om = oracle.EarleyMatcher(og)
+    assert om.advance(text)
+    # ambiguous grammar: 64 parallel stacks
+    amb = 'root ::= a | b\na ::= "x" root? "p"\nb ::= "x" root? "q"'
+    ga = xgm.Grammar(amb, "root")
+    ca = xgm.Cache(ga, xv)
+    ma = xgm.Matcher(cache=ca)
+    ma.accept_bytes(b"xxxxxx")
+    assert ma.num_stacks() == 64
+    oa = oracle.EarleyMatcher(oracle.Grammar(amb, "root"))
+    assert oa.advance(b"xxxxxx")
+    W = xgm.bitmask_words(32000)
+    d = torch.zeros((2, W), dtype=torch.int32, device="cuda")
+    xgm.fill_next_token_bitmask([m, ma], d.data_ptr(), _stream())
+    got = d.cpu().numpy()
+    assert np.array_equal(got[0], oracle.pack_bitmask(om.mask(vocab)))
+    assert np.array_equal(got[1], oracle.pack_bitmask(oa.mask(vocab)))
+
+
+def test_walk_limits_are_reported_and_fixed_up_exactly(xgm, wl):
+    """Tokens that exceed the on-chip limits (here: longer than 255 bytes, and
+    30 nested parentheses = more than 64 frames) are decided exactly by the
+    host slow path, at build time and at fill time."""
+    toks = [b"1", b"(", b")", b"+", b"1" * 300, b"(" * 30, b"1" * 20, b")" * 40, b""]
+    V = len(toks)
+
+    class V_:
+        data = np.frombuffer(b"".join(toks), dtype=np.uint8).copy()
+        offsets = np.concatenate([[0], np.cumsum([len(t) for t in toks])]).astype(np.int64)
+        stop_ids = np.array([8], dtype=np.int32)
+
+    xv = xgm.Vocab(V_.data, V_.offsets, V_.stop_ids)
+    g = xgm.Grammar(si.ARITH_GRAMMAR, "expr")
+    before = xgm.overflow_total()
+    cache = xgm.Cache(g, xv)
+    assert cache.host_classified > 0
+    og = oracle.Grammar(si.ARITH_GRAMMAR, "expr")
+    for node in range(g.num_nodes):
+        want = og.classify(g.rule_name(g.node_rule(node)), g.node_path(node), V_)
+        acc, unc = cache.copy_node_bits(node)
+        assert np.array_equal(acc, oracle.pack_bitmask(want == 2)), node
+        assert np.array_equal(unc, oracle.pack_bitmask(want == 1)), node
+    # fill: after "(" * 41 + "1", the token ")" * 40 pops 40 x 3 live frames (fine on chip);
+    # the 300-digit token is context-dependent at a digit node and exceeds the byte limit
+    m = xgm.Matcher(cache=cache)
+    om = oracle.EarleyMatcher(og)
+    text = b"(" * 41 + b"1"
+    m.accept_bytes(text)
+    assert om.advance(text)
+    d = torch.zeros((1, 1), dtype=torch.int32, device="cuda")
+    xgm.fill_next_token_bitmask([m], d.data_ptr(), _stream())
+    n_fixed = xgm.fill_overflow_fixup(_stream())
+    got = d.cpu().numpy()
+    assert np.array_equal(got[0], oracle.pack_bitmask(om.mask(V_)))
+    say(f"  build: {cache.host_classified} pairs on the host; fill: {n_fixed} pairs fixed up; "
+        f"log grew by {xgm.overflow_total() - before}")
