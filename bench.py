@@ -1,0 +1,195 @@
+"""Benchmark of the constrained-decoding mask hot path on one MI355X.
+
+A step = one pass of the whole per-step path over one batch: batched mask
+fill (kernel b) + in-place -inf apply (kernel c) for the serving workload
+(batch 128, vocabulary 151936, 128 distinct string-heavy schema grammars,
+bf16 logits).  The mask caches (kernel a) are built during set-up and their
+throughput is reported beside it.  Prints ONE JSON line on stdout.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0                      # MI355X HBM3E, published
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-ops/s (32-bit integer)
+OPS_PER_AUTOMATON_STEP = 24                # arithmetic model of one walk step, see the design doc
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--rows", type=int, default=128, help="batch size (default: the serving workload's 128)")
+    ap.add_argument("--vocab", type=int, default=151936)
+    ap.add_argument("--pool", type=int, default=16, help="number of pre-walked state sets cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-build-bench", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on one GPU (rows and vocabulary slices are independent; "
+              "nothing is exchanged between devices). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2411_15100_amd as xgm
+    import synth_inputs as si
+    from paper_2411_15100_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = wl.current_stream()
+    t_setup = time.time()
+    work = wl.ServingWorkload(n_rows=args.rows, vocab_size=args.vocab, pool=args.pool, log=log)
+    B, V, W = work.B, work.V, work.W
+    log(f"set-up done in {time.time() - t_setup:.1f} s; context-dependent fraction at the stack tops "
+        f"{work.uncertain_fraction:.3f}")
+
+    # ---- warm-up, then the timed region: exactly K steps between two synchronisations
+    for k in range(args.warmup):
+        work.step(k, stream)
+    torch.cuda.synchronize()
+    work.refresh_logits()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        work.step(k, stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    overflow = xgm.overflow_total()
+
+    # ---- the same K steps again with HIP events around each kernel (same stream)
+    work.refresh_logits()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for k in range(args.steps):
+        ev[k][0].record()
+        work.fill(k, stream)
+        ev[k][1].record()
+        work.apply(k, stream)
+        ev[k][2].record()
+    torch.cuda.synchronize()
+    fill_us = np.array([e[0].elapsed_time(e[1]) for e in ev]) * 1e3
+    apply_us = np.array([e[1].elapsed_time(e[2]) for e in ev]) * 1e3
+
+    # ---- algorithmic work per launch (averaged over the state sets in use)
+    n_sets = len(work.sets)
+    rejected, acc_words, unc_tokens, steps_count = [], [], [], []
+    for k in range(n_sets):
+        work.fill(k, stream)
+        torch.cuda.synchronize()
+        words = work.d_mask.cpu().numpy()
+        allowed = int(np.unpackbits(words.view(np.uint8)).sum())
+        rejected.append(B * V - allowed)
+        w = work.sets[k]
+        n_stacks = sum(m.num_stacks() for m in w.matchers)
+        acc_words.append(n_stacks * W)
+        unc_tokens.append(sum(c.num_uncertain(m.stack(s)[-1]) for m, c in zip(w.matchers, work.caches)
+                              for s in range(m.num_stacks())))
+        steps_count.append(xgm.debug_fill_count_steps(w.batch, work.d_mask.data_ptr(), stream))
+    apply_bytes = 4.0 * B * W + 2.0 * float(np.mean(rejected))
+    fill_stream_bytes = 4.0 * float(np.mean(acc_words)) + 4.0 * B * W
+    fill_walk_bytes = 18.0 * float(np.mean(unc_tokens))          # 2 B list entry + 16 B token row per walk
+    fill_us_avg, apply_us_avg = float(fill_us.mean()), float(apply_us.mean())
+    fill_is_dominant = fill_us_avg >= apply_us_avg
+    roof_apply = {"kernel": "apply_kernel<2>", "bound": "hbm", "achieved": apply_bytes / (apply_us_avg * 1e-6) / 1e9,
+                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None}
+    roof_apply["frac"] = roof_apply["achieved"] / HBM_PEAK_GBS
+    auto_steps = float(np.mean(steps_count))
+    roof_fill = {"kernel": "fill_kernel", "bound": "alu",
+                 "achieved": auto_steps * OPS_PER_AUTOMATON_STEP / (fill_us_avg * 1e-6) / 1e12,
+                 "peak": ALU_PEAK_TOPS, "unit": "TOP/s (32-bit integer lane-ops)", "traffic": None,
+                 "automaton_steps_per_launch": auto_steps, "walks_per_launch": float(np.mean(unc_tokens)),
+                 "bytes_per_launch": fill_stream_bytes + fill_walk_bytes,
+                 "hbm_equivalent_GBs": (fill_stream_bytes + fill_walk_bytes) / (fill_us_avg * 1e-6) / 1e9}
+    roof_fill["frac"] = roof_fill["achieved"] / ALU_PEAK_TOPS
+
+    # ---- cache build throughput (kernel a), generic JSON and the C/SQL-like grammar at V = 128256
+    cache_build = None
+    if not args.no_build_bench:
+        v128 = si.make_vocab("bpe", 128256, 0)
+        xv128 = wl.make_xgm_vocab(v128)
+        cache_build = {}
+        for name, text in (("json", si.JSON_GRAMMAR), ("csql", si.CSQL_GRAMMAR)):
+            g = xgm.Grammar(text, "root")
+            best = None
+            for _ in range(3):
+                c = xgm.Cache(g, xv128, stream)
+                best = c.build_kernel_seconds if best is None else min(best, c.build_kernel_seconds)
+                hostc = c.host_classified
+                del c
+            cache_build[name] = {"positions": g.num_nodes, "tokens": 128256, "kernel_ms": best * 1e3,
+                                 "pairs_per_s": g.num_nodes * 128256 / best, "host_classified_pairs": hostc}
+        cache_build["serving_set_up"] = {"pairs": work.build_pairs, "kernel_s": work.build_kernel_seconds,
+                                         "pairs_per_s": work.build_pairs / max(work.build_kernel_seconds, 1e-12)}
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        toks = work.vocab.tokens()
+        threads = oracle.default_threads()
+        n_sample = min(B, 24)
+        spent, checks = 0.0, 0
+        w0 = work.sets[0]
+        for b in range(n_sample):
+            og = oracle.Grammar(work.texts[b], "root")
+            om = oracle.EarleyMatcher(og)
+            for t in w0.history[b]:
+                assert om.advance(toks[t])
+            tt = time.perf_counter()
+            om.mask(work.vocab, threads)
+            spent += time.perf_counter() - tt
+            checks += V
+            if spent > 25.0:
+                break
+        cpu_baseline = {"value": checks / spent, "unit": "token checks/s", "cores": threads, "kind": "oracle",
+                        "sample": f"Earley brute-force masks for the first {checks // V} rows of state set 0 "
+                                  f"({checks} token checks, {spent:.1f} s)",
+                        "us_per_mask": spent / (checks / V) * 1e6}
+
+    out = {
+        "metric": "vocab token checks/sec (per-step bitmask fill + in-place -inf apply, batch x vocab)",
+        "value": B * V / (ms_per_step * 1e-3),
+        "unit": "token checks/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "fill_plus_apply_us": ms_per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 masks / bf16 logits (integer automaton walk; no floating-point arithmetic)",
+        "data": "synthetic",
+        "config": {"workload": f"serving decode step: batch {B} x vocab {V}, {B} distinct string-heavy schema "
+                               f"grammars, bf16 logits [{B},{V}], {n_sets} pre-walked state sets, "
+                               f"{len(work.logits)} rotating logits buffers",
+                   "batch": B, "vocab": V,
+                   "context_dependent_fraction_at_tops": work.uncertain_fraction},
+        "kernel_us": {"fill_mean": fill_us_avg, "fill_p50": float(np.median(fill_us)), "fill_p99": float(np.percentile(fill_us, 99)),
+                      "apply_mean": apply_us_avg, "apply_p50": float(np.median(apply_us)), "apply_p99": float(np.percentile(apply_us, 99))},
+        "roofline": roof_fill if fill_is_dominant else roof_apply,
+        "roofline_other": roof_apply if fill_is_dominant else roof_fill,
+        "fill_stream_part": {"bytes_per_launch": fill_stream_bytes},
+        "walks_on_host_slow_path": int(overflow),
+        "cache_build": cache_build,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

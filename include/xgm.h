@@ -196,6 +196,11 @@ int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int
  * xgm_fill_overflow_fixup() decides it exactly. */
 int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask,
                                 void* hip_stream);
+/* Instrumentation for benchmarks: the same fill (same result in d_bitmask)
+ * with a kernel instantiation that also counts the automaton steps of all
+ * walks; synchronous; *h_steps receives the count.  Not for the hot path. */
+int xgm_debug_fill_count_steps(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask,
+                               void* hip_stream, int64_t* h_steps);
 /* Synchronises hip_stream, then decides on the host every pair recorded by
  * the most recent fill and patches that fill's d_bitmask.  Returns the number
  * of pairs handled (>= 0) or a negative status.  Costs one stream

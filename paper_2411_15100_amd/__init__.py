@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     Matcher,
     fill_next_token_bitmask,
     fill_overflow_fixup,
+    debug_fill_count_steps,
+    MatcherBatch,
     overflow_total,
     apply_token_bitmask_inplace,
     bitmask_words,

@@ -58,6 +58,7 @@ SIGNATURES = {
     "xgm_matcher_num_stacks": (_i32, [_vp]),
     "xgm_matcher_stack": (_i32, [_vp, _i32, _vp, _i32]),
     "xgm_fill_next_token_bitmask": (_i32, [_vp, _i32, _vp, _vp]),
+    "xgm_debug_fill_count_steps": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_fill_overflow_fixup": (_i32, [_vp]),
     "xgm_overflow_total": (_i64, []),
     "xgm_apply_token_bitmask_inplace": (_i32, [_vp, _i32, _i32, _i32, _i64, _vp, _i32, _vp, _i32, _vp]),
@@ -293,6 +294,14 @@ class MatcherBatch:
     def fill_next_token_bitmask(self, d_bitmask: int, stream: int = 0):
         _check(load_library().xgm_fill_next_token_bitmask(self._arr, len(self.matchers), ctypes.c_void_p(d_bitmask),
                                                           ctypes.c_void_p(stream)))
+
+
+def debug_fill_count_steps(batch: "MatcherBatch", d_bitmask: int, stream: int = 0) -> int:
+    """Automaton steps taken by all walks of one fill of this batch (instrumentation)."""
+    n = ctypes.c_int64(0)
+    _check(load_library().xgm_debug_fill_count_steps(batch._arr, len(batch.matchers), ctypes.c_void_p(d_bitmask),
+                                                     ctypes.c_void_p(stream), ctypes.byref(n)))
+    return int(n.value)
 
 
 def fill_overflow_fixup(stream: int = 0) -> int:

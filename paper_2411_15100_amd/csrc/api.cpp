@@ -562,7 +562,8 @@ int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int
 }
 
 // ---------------------------------------------------------------------- fill
-int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream) {
+static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream,
+                     unsigned long long* d_step_counter) {
   API_BEGIN
   if (!ms || B <= 0 || !d_bitmask) return fail(XGM_ERR_BAD_ARG, "fill: null argument or empty batch");
   xgm_vocab* v = nullptr;
@@ -629,7 +630,7 @@ int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bi
   launch_fill(reinterpret_cast<const RowDesc*>(slot.d_buf),
               reinterpret_cast<const StackDesc*>((char*)slot.d_buf + off_stacks),
               reinterpret_cast<const uint16_t*>((char*)slot.d_buf + off_frames), B, v->dv,
-              reinterpret_cast<uint32_t*>(d_bitmask), log, seq, stream);
+              reinterpret_cast<uint32_t*>(d_bitmask), log, seq, d_step_counter, stream);
   HIP_OK(hipGetLastError());
   HIP_OK(hipEventRecord(slot.done, stream));
   slot.used = true;
@@ -641,6 +642,35 @@ int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bi
   C.last_vocab = v;
   C.last_matchers.assign(ms, ms + B);
   return XGM_OK;
+  API_END
+}
+
+int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream) {
+  return fill_impl(ms, B, d_bitmask, hip_stream, nullptr);
+}
+
+int xgm_debug_fill_count_steps(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream,
+                               int64_t* h_steps) {
+  API_BEGIN
+  if (!h_steps) return fail(XGM_ERR_BAD_ARG, "count_steps: null output");
+  require_device();
+  unsigned long long* d_counter = dev_alloc<unsigned long long>(1);
+  int rc = XGM_OK;
+  try {
+    HIP_OK(hipMemset(d_counter, 0, sizeof(unsigned long long)));
+    rc = fill_impl(ms, B, d_bitmask, hip_stream, d_counter);
+    if (rc == XGM_OK) {
+      HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+      unsigned long long n = 0;
+      HIP_OK(hipMemcpy(&n, d_counter, sizeof(n), hipMemcpyDeviceToHost));
+      *h_steps = (int64_t)n;
+    }
+  } catch (...) {
+    (void)hipFree(d_counter);
+    throw;
+  }
+  (void)hipFree(d_counter);
+  return rc;
   API_END
 }
 

@@ -182,10 +182,15 @@ constexpr int kFillThreads = 256;
 // context-dependent tokens against each full stack and ORs in the survivors
 // with LDS atomics, adds the stop tokens, and stores the words once,
 // coalesced.  No global atomics, no second pass.
+// COUNT = true additionally sums the automaton steps of all walks into
+// *step_counter (instrumentation for the benchmark; never used on the hot path).
+template <bool COUNT>
 __global__ __launch_bounds__(kFillThreads) void fill_kernel(const RowDesc* __restrict__ rows,
                                                             const StackDesc* __restrict__ stacks,
                                                             const uint16_t* __restrict__ frames, DevVocab voc,
-                                                            uint32_t* __restrict__ out, OverflowLog* log, uint32_t seq) {
+                                                            uint32_t* __restrict__ out, OverflowLog* log, uint32_t seq,
+                                                            unsigned long long* step_counter) {
+  unsigned long long my_steps = 0;
   __shared__ uint32_t words[kChunkWords];
   const int32_t b = blockIdx.y, chunk = blockIdx.x;
   const int32_t w0 = chunk * kChunkWords;
@@ -214,7 +219,9 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(const RowDesc* __res
           ext = voc.bytes + voc.off_by_id[id];
           if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
         }
-        const int res = walk_token<false>(C.tab, tk, ext, len, top, live, sd.depth);
+        uint32_t n_steps = 0;
+        const int res = walk_token<false>(C.tab, tk, ext, len, top, live, sd.depth, COUNT ? &n_steps : nullptr);
+        if (COUNT) my_steps += n_steps;
         if (res == kAccept) atomicOr(&words[lid >> 5], 1u << (lid & 31));
         else if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, (uint32_t)id);
       }
@@ -229,6 +236,7 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(const RowDesc* __res
     __syncthreads();
   }
   if ((int)threadIdx.x < nw) out[(size_t)b * voc.W + w0 + threadIdx.x] = words[threadIdx.x];
+  if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
 }
 
 // ---------------------------------------------------------------- kernel (c)
@@ -353,10 +361,14 @@ void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_
 }
 
 void launch_fill(const RowDesc* rows, const StackDesc* stacks, const uint16_t* frames, int32_t B, const DevVocab& voc,
-                 uint32_t* out, OverflowLog* log, uint32_t seq, hipStream_t stream) {
+                 uint32_t* out, OverflowLog* log, uint32_t seq, unsigned long long* step_counter, hipStream_t stream) {
   if (B <= 0 || voc.n_chunk <= 0) return;
-  hipLaunchKernelGGL(fill_kernel, dim3(voc.n_chunk, B), dim3(kFillThreads), 0, stream, rows, stacks, frames, voc, out,
-                     log, seq);
+  if (step_counter)
+    hipLaunchKernelGGL(fill_kernel<true>, dim3(voc.n_chunk, B), dim3(kFillThreads), 0, stream, rows, stacks, frames,
+                       voc, out, log, seq, step_counter);
+  else
+    hipLaunchKernelGGL(fill_kernel<false>, dim3(voc.n_chunk, B), dim3(kFillThreads), 0, stream, rows, stacks, frames,
+                       voc, out, log, seq, step_counter);
 }
 
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,

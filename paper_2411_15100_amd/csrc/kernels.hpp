@@ -98,8 +98,10 @@ void launch_list_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_i
 void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items,
                           uint32_t* acc_rank, uint32_t* unc_rank, hipStream_t stream);
 // (b) batched mask fill
+// step_counter: null on the hot path; otherwise the counting instantiation is launched
 void launch_fill(const RowDesc* rows, const StackDesc* stacks, const uint16_t* frames, int32_t B,
-                 const DevVocab& voc, uint32_t* out, OverflowLog* log, uint32_t seq, hipStream_t stream);
+                 const DevVocab& voc, uint32_t* out, OverflowLog* log, uint32_t seq,
+                 unsigned long long* step_counter, hipStream_t stream);
 // (c) apply; returns false if the buffer layout needs the element-wise kernel
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,
                   const uint32_t* bitmask, int32_t V_mask, const int32_t* row_index, int32_t n_rows,

@@ -46,9 +46,11 @@ XGM_HD uint32_t token_byte(const uint4& tk, const uint8_t* ext, int i) {
 // BUILD = false: frames below are live[0 .. depth-2]; result kAccept (token
 //                allowed) or kReject.
 // kOverflow: a limit was hit; the caller records the pair.
+// `steps_out` (may be null) receives the number of automaton steps taken.
 template <bool BUILD>
 XGM_HD int walk_token(const DevTables& T, const uint4 tk, const uint8_t* ext, const int len,
-                                          const uint32_t start_node, const uint16_t* live, const uint32_t depth) {
+                      const uint32_t start_node, const uint16_t* live, const uint32_t depth,
+                      uint32_t* steps_out = nullptr) {
   if (len > kMaxTokenLen) return kOverflow;
   uint32_t arena[kArenaFrames];  // ret | parent handle << 16
   uint2 choice[kChoicePoints];   // x = node | sp << 16 ; y = i | alt << 8 | top << 16 | f << 24
@@ -56,6 +58,7 @@ XGM_HD int walk_token(const DevTables& T, const uint4 tk, const uint8_t* ext, co
   int i = 0;
   bool left_frame = false;
   for (int steps = 0;; ++steps) {
+    if (steps_out) *steps_out = (uint32_t)steps;
     if (i == len) return kAccept;
     if (steps >= kMaxSteps) return kOverflow;
     const uint32_t c = token_byte(tk, ext, i);
