@@ -13,7 +13,8 @@ What it computes (arxiv 2411.15100):
 * ``PdaMatcher`` / ``classify`` (O2): the pushdown automaton of Appendix A
   simulated literally on Thompson NFAs (sets of (state, stack) with a visited
   set), and from it the accepted / rejected / context-dependent token classes
-  of section 3.1 for a position inside a rule.
+  of section 3.1 for a position inside a rule, plus their narrowing by one
+  byte of context (section 3.2 in its smallest form: FOLLOW sets).
 * ``apply_mask``: section 2.1, logits of disallowed tokens become -inf, all
   other logits keep their bit pattern.
 
@@ -63,6 +64,7 @@ def _load():
         "orc_grammar_free": (None, [vp]),
         "orc_rule_index": (i32, [vp, cp]),
         "orc_num_rules": (i32, [vp]),
+        "orc_follow": (i32, [vp, i32, vp]),
         "orc_recognize": (i32, [vp, cp, i64]),
         "orc_recognize_pda": (i32, [vp, cp, i64]),
         "orc_earley_new": (vp, [vp]),
@@ -146,10 +148,20 @@ class Grammar:
             raise OracleError(_err())
         return r
 
+    def follow(self, rule: str) -> set:
+        """Bytes that can come right after an instance of ``rule`` in some context."""
+        out = np.zeros(256, dtype=np.uint8)
+        if _load().orc_follow(self._h, self.rule_index(rule), out.ctypes.data) < 0:
+            raise OracleError(f"unknown rule {rule!r}")
+        return set(int(c) for c in np.flatnonzero(out))
+
     def classify(self, rule: str, path, vocab, nthreads: int | None = None) -> np.ndarray:
-        """Token classes (0 rejected, 1 context-dependent, 2 accepted) at the
-        position of ``rule`` reached from its start by ``path``: a list whose
-        items are ints (bytes) or rule names (references)."""
+        """Token classes at the position of ``rule`` reached from its start by
+        ``path`` (a list whose items are ints = bytes or rule names =
+        references): 0 rejected, 2 accepted, 1 context-dependent, 4
+        context-dependent by section 3.1 alone but refused in every context
+        by the one-byte narrowing (so: section 3.1's class is {1, 4}, the
+        narrowed class is {1})."""
         lib = _load()
         r = self.rule_index(rule)
         if r < 0:

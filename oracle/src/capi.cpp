@@ -30,6 +30,7 @@ struct PdaBox {
   orc::ConfigSet cur;
 };
 struct PosBox {
+  int rule;
   std::set<int> pos;
 };
 
@@ -75,6 +76,13 @@ int orc_rule_index(void* g, const char* name) {
   return it == m.end() ? -1 : it->second;
 }
 int orc_num_rules(void* g) { return (int)((GrammarBox*)g)->g.rule_names.size(); }
+// 256 flags: out[c] = 1 iff byte c can come right after an instance of the rule
+int orc_follow(void* g, int rule, unsigned char* out) {
+  auto& f = ((GrammarBox*)g)->nfa.follow;
+  if (rule < 0 || rule >= (int)f.size()) return -1;
+  for (int c = 0; c < 256; ++c) out[c] = f[rule].test(c) ? 1 : 0;
+  return 0;
+}
 
 // 0 = not a viable prefix, 1 = viable prefix but not a sentence, 2 = sentence
 int orc_recognize(void* g, const unsigned char* bytes, int64_t n) {
@@ -188,20 +196,22 @@ void* orc_positions(void* g, int rule, const int32_t* symbols, int n) {
   ORC_TRY
   auto* gb = (GrammarBox*)g;
   orc::Pda pda(&gb->nfa);
-  return new PosBox{pda.positions(rule, symbols, n)};
+  return new PosBox{rule, pda.positions(rule, symbols, n)};
   ORC_CATCH(nullptr)
 }
 void orc_positions_free(void* p) { delete (PosBox*)p; }
 int orc_positions_size(void* p) { return (int)((PosBox*)p)->pos.size(); }
-// out[i]: 0 rejected, 1 uncertain (context-dependent), 2 accepted
+// out[i]: 0 rejected, 2 accepted, 1 uncertain (context-dependent) also after the
+// one-byte narrowing, 4 uncertain by section 3.1 alone
 int orc_classify(void* g, void* p, const unsigned char* data, const int64_t* offsets, int64_t V,
                  unsigned char* out, int nthreads) {
   ORC_TRY
   auto* gb = (GrammarBox*)g;
   orc::Pda pda(&gb->nfa);
   const std::set<int>& pos = ((PosBox*)p)->pos;
+  const int rule = ((PosBox*)p)->rule;
   for_tokens(V, nthreads, [&](int64_t i) {
-    out[i] = (unsigned char)pda.classify(pos, data + offsets[i], (int)(offsets[i + 1] - offsets[i]));
+    out[i] = (unsigned char)pda.classify(rule, pos, data + offsets[i], (int)(offsets[i + 1] - offsets[i]));
   });
   return 0;
   ORC_CATCH(-1)

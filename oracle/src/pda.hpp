@@ -17,6 +17,14 @@
 //   uncertain  (context-dependent) if not accepted and some path pops the
 //              marker while at least one byte is still unconsumed,
 //   rejected   otherwise.
+// A one-byte form of the context expansion of section 3.2 narrows the
+// uncertain class: the byte that comes right after leaving the rule must be
+// able to follow that rule in at least one context (its FOLLOW set: whatever
+// can be consumed at the return state of some reference to the rule, plus, if
+// the referencing rule can end there without consuming anything, whatever
+// follows that rule).  classify() reports both: 1 = uncertain also after the
+// narrowing, 4 = uncertain by section 3.1 alone (no exit in front of a byte
+// that could ever follow the rule, so the token is refused in every context).
 // Dead parts (unproductive rules, states that cannot reach their rule's end)
 // are removed first, so "a configuration survives" means "can be completed".
 #pragma once
@@ -42,6 +50,8 @@ struct Nfa {
   std::vector<bool> live;          // state can reach its rule's accepting state
   std::vector<bool> rule_ok;       // rule derives at least one string
   std::vector<bool> nullable;      // rule derives ""
+  std::vector<ByteSet> first;      // per rule: bytes its sentences can start with
+  std::vector<ByteSet> follow;     // per rule: bytes that can come right after an instance
   int root = -1;
 };
 
@@ -216,6 +226,61 @@ class NfaBuilder {
       }
     }
     if (!n_.rule_ok[n_.root]) throw std::runtime_error("the root rule derives no string");
+    first_and_follow();
+  }
+  // states reachable from q without consuming a byte, staying inside q's rule
+  // (epsilon edges, and references to rules that can match "")
+  std::vector<int> silent_reach(int q) const {
+    std::vector<int> seen{q}, work{q};
+    std::vector<bool> mark(n_.out.size(), false);
+    mark[q] = true;
+    while (!work.empty()) {
+      int s = work.back();
+      work.pop_back();
+      for (auto& e : n_.out[s]) {
+        bool silent = e.kind == Nfa::EPS || (e.kind == Nfa::CALL && n_.rule_ok[e.arg] && n_.nullable[e.arg]);
+        if (silent && n_.live[e.to] && !mark[e.to]) { mark[e.to] = true; seen.push_back(e.to); work.push_back(e.to); }
+      }
+    }
+    return seen;
+  }
+  // bytes that can be consumed next from state q (inside its rule or in a rule it calls)
+  ByteSet next_bytes(int q) const {
+    ByteSet b;
+    for (int s : silent_reach(q))
+      for (auto& e : n_.out[s]) {
+        if (!n_.live[e.to]) continue;
+        if (e.kind == Nfa::BYTE) b |= n_.sets[e.arg];
+        else if (e.kind == Nfa::CALL && n_.rule_ok[e.arg]) b |= n_.first[e.arg];
+      }
+    return b;
+  }
+  void first_and_follow() {
+    int R = (int)n_.start.size();
+    n_.first.assign(R, ByteSet());
+    for (bool changed = true; changed;) {
+      changed = false;
+      for (int r = 0; r < R; ++r) {
+        if (!n_.rule_ok[r]) continue;
+        ByteSet b = next_bytes(n_.start[r]);
+        if (b != n_.first[r]) { n_.first[r] = b; changed = true; }
+      }
+    }
+    n_.follow.assign(R, ByteSet());
+    for (bool changed = true; changed;) {
+      changed = false;
+      for (size_t q = 0; q < n_.out.size(); ++q) {
+        if (!n_.live[q]) continue;
+        for (auto& e : n_.out[q]) {
+          if (e.kind != Nfa::CALL || !n_.rule_ok[e.arg] || !n_.live[e.to]) continue;
+          ByteSet f = n_.follow[e.arg] | next_bytes(e.to);
+          int caller = n_.rule_of[q];
+          for (int s : silent_reach(e.to))
+            if (s == n_.accept[caller]) f |= n_.follow[caller];  // the caller may end right after the call
+          if (f != n_.follow[e.arg]) { n_.follow[e.arg] = f; changed = true; }
+        }
+      }
+    }
   }
 };
 
@@ -316,15 +381,25 @@ class Pda {
     }
     return cur;
   }
-  // 0 = rejected, 1 = uncertain (context-dependent), 2 = accepted
-  int classify(const std::set<int>& pos, const unsigned char* bytes, int n) const {
+  // 0 = rejected, 2 = accepted, 1 = uncertain (context-dependent) also after
+  // the one-byte narrowing, 4 = uncertain by section 3.1 alone.  All
+  // positions belong to `rule`.
+  int classify(int rule, const std::set<int>& pos, const unsigned char* bytes, int n) const {
     if (n == 0) return 0;  // a token without bytes is never allowed
     ConfigSet cur;
     for (int q : pos) cur.insert({std::vector<int>{BOTTOM}, q});
-    bool popped = false;
-    for (int i = 0; i < n && !cur.empty(); ++i) cur = step(closure(cur, &popped), bytes[i]);
+    bool left = false, left_with_follower = false;
+    for (int i = 0; i < n && !cur.empty(); ++i) {
+      bool popped = false;
+      ConfigSet closed = closure(cur, &popped);
+      if (popped) {  // the rule ended here with bytes[i..] still to come
+        left = true;
+        if (n_->follow[rule].test(bytes[i])) left_with_follower = true;
+      }
+      cur = step(closed, bytes[i]);
+    }
     if (!cur.empty()) return 2;
-    return popped ? 1 : 0;
+    return left_with_follower ? 1 : (left ? 4 : 0);
   }
 
  private:

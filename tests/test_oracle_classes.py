@@ -11,6 +11,13 @@ own frame and deeper ones only).  Token t is
   rejected  otherwise.
 The enumerator below works on a hand-written Python structure of the same
 tiny grammars, not on the oracle's parser or automata.
+
+The narrowing by one byte of context (section 3.2 in its smallest form) has a
+plain definition too: FOLLOW(R) is the set of bytes found right after some
+instance of R in some sentence, read off a brute-force enumeration of all
+derivations; an uncertain token stays uncertain (class 1) iff one of the
+proper prefixes in X is followed, inside the token, by a byte of FOLLOW(R),
+otherwise it is uncertain by section 3.1 alone (class 4).
 """
 
 import itertools
@@ -87,14 +94,48 @@ def residuals(gr, rule, path):
     return out
 
 
-def want_class(X, t):
+def derivations(gr, symbols):
+    """All (string, [(rule, end offset), ...]) a symbol sequence derives."""
+    out = [(b"", [])]
+    for s in symbols:
+        nxt = []
+        if isinstance(s, bytes):
+            nxt = [(x + s, inst) for x, inst in out]
+        else:
+            subs = []
+            for alt in gr[s]:
+                subs.extend(derivations(gr, alt))
+            for x, inst in out:
+                for y, inst2 in subs:
+                    moved = [(r, len(x) + e) for r, e in inst2]
+                    nxt.append((x + y, inst + moved + [(s, len(x) + len(y))]))
+        out = nxt
+    return out
+
+
+def brute_force_follow(gr, root):
+    follow = {r: set() for r in gr}
+    for text, instances in derivations(gr, [root]):
+        for rule, end in instances:
+            if end < len(text):
+                follow[rule].add(text[end])
+    return follow
+
+
+def want_class(X, t, follow=None):
+    """0 rejected, 2 accepted, 1 uncertain; with `follow` (bytes that may come
+    after the rule) an uncertain token none of whose exits is in front of such
+    a byte is 4."""
     if len(t) == 0:
         return 0
     if any(x.startswith(t) for x in X):
         return 2
-    if any(t.startswith(x) and len(x) < len(t) for x in X):
+    exits = [len(x) for x in X if t.startswith(x) and len(x) < len(t)]
+    if not exits:
+        return 0
+    if follow is None or any(t[k] in follow for k in exits):
         return 1
-    return 0
+    return 4
 
 
 POSITIONS = [
@@ -111,15 +152,22 @@ def test_classes_against_language_level_definition():
     alphabet = b"<>/ab12"
     toks = [bytes(t) for n in range(1, 5) for t in itertools.product(alphabet, repeat=n)] + [b""]
     vocab = TinyVocab(toks)
+    follow = brute_force_follow(G1, "root")
+    assert follow == {"root": set(), "word": {ord(">")}, "word2": {ord(">")}, "num": {ord("/")}}
+    for rule in G1:
+        assert g.follow(rule) == follow[rule], rule
     seen = set()
     for rule, path in POSITIONS:
         X = residuals(G1, rule, path)
         assert X, (rule, path)
         got = g.classify(rule, path, vocab)
         for t, c in zip(toks, got):
-            assert c == want_class(X, t), (rule, path, t, int(c), want_class(X, t))
+            # section 3.1 alone: classes 1 and 4 together are "uncertain"
+            assert {0: 0, 1: 1, 2: 2, 4: 1}[int(c)] == want_class(X, t), (rule, path, t, int(c))
+            # with the one-byte narrowing
+            assert c == want_class(X, t, follow[rule]), (rule, path, t, int(c), want_class(X, t, follow[rule]))
         seen |= set(int(c) for c in got)
-    assert seen == {0, 1, 2}
+    assert seen == {0, 1, 2, 4}
 
 
 def test_hand_values():
@@ -127,13 +175,17 @@ def test_hand_values():
     g = oracle.Grammar('root ::= "<" word ">"\nword ::= [ab]+', "root")
     toks = [b"ab", b"a>", b">", b"c", b"ca", b"b", b"a>x", b"<", b"<a", b"<>", b""]
     vocab = TinyVocab(toks)
-    REJ, UNC, ACC = 0, 1, 2
-    # inside word after one letter: the rule may end here
-    assert list(g.classify("word", [ord("a")], vocab)) == [ACC, UNC, UNC, UNC, UNC, ACC, UNC, UNC, UNC, UNC, REJ]
+    REJ, UNC, ACC, UN4 = 0, 1, 2, 4
+    # only ">" can come after word, and nothing after root
+    assert g.follow("word") == {ord(">")} and g.follow("root") == set()
+    # inside word after one letter: the rule may end here; leaving it in front
+    # of anything but ">" is hopeless in every context (4)
+    assert list(g.classify("word", [ord("a")], vocab)) == [ACC, UNC, UNC, UN4, UN4, ACC, UNC, UN4, UN4, UN4, REJ]
     # at the start of word: it cannot end yet
     assert list(g.classify("word", [], vocab)) == [ACC, UNC, REJ, REJ, REJ, ACC, UNC, REJ, REJ, REJ, REJ]
-    # in root after "<": leaving word returns into root's own frame, which is known
-    assert list(g.classify("root", [ord("<")], vocab)) == [ACC, ACC, REJ, REJ, REJ, ACC, UNC, REJ, REJ, REJ, REJ]
+    # in root after "<": leaving word returns into root's own frame, which is known;
+    # "a>x" leaves root itself in front of "x"
+    assert list(g.classify("root", [ord("<")], vocab)) == [ACC, ACC, REJ, REJ, REJ, ACC, UN4, REJ, REJ, REJ, REJ]
     # at root's start
     assert list(g.classify("root", [], vocab)) == [REJ, REJ, REJ, REJ, REJ, REJ, REJ, ACC, ACC, REJ, REJ]
 
@@ -156,7 +208,7 @@ def test_classes_consistent_with_masks_on_json():
         (b'{', "object", [ord("{")]),
         (b'["a"', "string", [ord('"'), "char", ord('"')]),
     ]
-    n_unc_allowed = n_unc_refused = 0
+    n_unc_allowed = n_unc_refused = n_narrowed = 0
     for text, rule, path in cases:
         cls = g.classify(rule, path, vocab)
         m = oracle.EarleyMatcher(g)
@@ -165,6 +217,8 @@ def test_classes_consistent_with_masks_on_json():
         mask[vocab.stop_ids] = False
         assert mask[cls == 2].all(), (text, rule)
         assert not mask[cls == 0].any(), (text, rule)
+        assert not mask[cls == 4].any(), (text, rule)   # the narrowing only drops tokens no context allows
         n_unc_allowed += int(mask[cls == 1].sum())
         n_unc_refused += int((~mask[cls == 1]).sum())
-    assert n_unc_allowed > 0 and n_unc_refused > 0
+        n_narrowed += int((cls == 4).sum())
+    assert n_unc_allowed > 0 and n_unc_refused > 0 and n_narrowed > 1000
