@@ -178,7 +178,8 @@ def main():
                                f"grammars, bf16 logits [{B},{V}], {n_sets} pre-walked state sets, "
                                f"{len(work.logits)} rotating logits buffers",
                    "batch": B, "vocab": V,
-                   "context_dependent_fraction_at_tops": work.uncertain_fraction},
+                   "context_dependent_fraction_at_tops": work.uncertain_fraction,
+                   "context_dependent_fraction_after_narrowing": work.uncertain_fraction_narrowed},
         "kernel_us": {"fill_mean": fill_us_avg, "fill_p50": float(np.median(fill_us)), "fill_p99": float(np.percentile(fill_us, 99)),
                       "apply_mean": apply_us_avg, "apply_p50": float(np.median(apply_us)), "apply_p99": float(np.percentile(apply_us, 99))},
         "roofline": roof_fill if fill_is_dominant else roof_apply,

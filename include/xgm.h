@@ -121,11 +121,24 @@ int32_t xgm_grammar_node_is_final(const xgm_grammar* g, int32_t node);
  * 3.1 on the GPU.  For every node n and token t, starting with n alone on the
  * stack: accepted if some path consumes all bytes of t without leaving n's
  * frame downwards; else context-dependent ("uncertain") if some path reaches
- * the end of n's rule while at least one byte remains; else rejected.  The
- * result is kept on the device as one accepted bitset per node plus, per node
- * and per block of 4096 token ids, the list of its context-dependent tokens.
- * Synchronous: returns after the build has finished on hip_stream. */
+ * the end of n's rule while at least one byte remains; else rejected.
+ * The context-dependent class is then narrowed with one byte of context, a
+ * small form of the context expansion of section 3.2: an exit from n's rule
+ * R only counts if the byte that comes next can follow an instance of R in
+ * some context (the FOLLOW set of R: what can be consumed at the return node
+ * of any reference to R, and, where the referencing rule may end there, what
+ * can follow that rule).  A token all of whose exits fail this test is
+ * rejected in every context, so it is stored as rejected ("plain-only"
+ * context-dependent tokens are counted, and kept with XGM_CACHE_KEEP_PLAIN);
+ * final masks are unchanged.
+ * The result is kept on the device as one accepted bitset per node plus, per
+ * node and per block of 4096 token ids, the list of its context-dependent
+ * tokens.  Synchronous: returns after the build has finished on hip_stream. */
 int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out);
+enum { XGM_CACHE_KEEP_PLAIN = 1 };
+/* Same, with flags: XGM_CACHE_KEEP_PLAIN also keeps, per node, the bitset of
+ * the plain-only context-dependent tokens (for xgm_cache_copy_node_plain). */
+int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t flags, xgm_cache** out);
 void xgm_cache_destroy(xgm_cache* c);
 int32_t xgm_cache_num_nodes(const xgm_cache* c);
 /* Copies node's accepted and context-dependent bitsets (bitmask layout, each
@@ -133,6 +146,12 @@ int32_t xgm_cache_num_nodes(const xgm_cache* c);
 int xgm_cache_copy_node_bits(const xgm_cache* c, int32_t node, int32_t* h_acc, int32_t* h_unc);
 /* Number of context-dependent tokens cached for a node (or a negative status). */
 int32_t xgm_cache_num_uncertain(const xgm_cache* c, int32_t node);
+/* Number of tokens that section 3.1 alone calls context-dependent at the node
+ * but that the one-byte context refinement rejects (so: num_uncertain +
+ * num_uncertain_plain = size of the class of section 3.1). */
+int32_t xgm_cache_num_uncertain_plain(const xgm_cache* c, int32_t node);
+/* The bitset of those tokens (needs XGM_CACHE_KEEP_PLAIN at build time). */
+int xgm_cache_copy_node_plain(const xgm_cache* c, int32_t node, int32_t* h_plain);
 /* Number of (node, token) pairs of the build whose walk exceeded the on-chip
  * bounds and were classified exactly on the host instead (0 for every
  * workload shipped with this repository). */
@@ -144,16 +163,19 @@ double xgm_cache_build_kernel_seconds(const xgm_cache* c);
 /* The exact host routine that decides a (node, token) pair whose GPU walk
  * exceeded its limits during xgm_cache_build: 0 rejected, 1 context-dependent,
  * 2 accepted, negative status on error.  Exported so that this slow path can
- * be tested without a device; nothing on the hot path calls it. */
+ * be tested without a device; nothing on the hot path calls it.  4 = context-
+ * dependent by section 3.1 alone, rejected by the one-byte context refinement. */
 int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h_bytes, int32_t n);
 /* The token walk of the two GPU kernels, compiled for the host from the same
  * source and run on the flattened tables, for tests without a device.
  * h_stack: depth nodes, bottom first.  build != 0: depth must be 1, result is
- * 0 rejected / 1 context-dependent / 2 accepted as in xgm_cache_build;
+ * 0 rejected / 1 context-dependent / 2 accepted / 4 plain-only context-
+ * dependent, as in xgm_cache_build;
  * build == 0: result is 2 (token allowed from this stack) or 0.  3 = the walk
- * exceeded its limits (64 frames, 24 alternatives, 4096 steps, 255 bytes). */
+ * exceeded its limits (64 frames, 24 alternatives, 4096 steps, 255 bytes).
+ * h_steps (may be NULL) receives the number of automaton steps taken. */
 int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth,
-                        const uint8_t* h_bytes, int32_t n, int32_t build);
+                        const uint8_t* h_bytes, int32_t n, int32_t build, int32_t* h_steps);
 
 /* ------------------------------------------------------------------- matcher
  * Per-request state: the set of parallel stacks of section 2.2, each a list of

@@ -39,8 +39,11 @@ SIGNATURES = {
     "xgm_grammar_node_path": (_i32, [_vp, _i32, _vp, _i32]),
     "xgm_grammar_node_is_final": (_i32, [_vp, _i32]),
     "xgm_debug_classify_host": (_i32, [_vp, _i32, _cp, _i32]),
-    "xgm_debug_walk_host": (_i32, [_vp, _vp, _i32, _cp, _i32, _i32]),
+    "xgm_debug_walk_host": (_i32, [_vp, _vp, _i32, _cp, _i32, _i32, _vp]),
     "xgm_cache_build": (_i32, [_vp, _vp, _vp, _pp]),
+    "xgm_cache_build_ex": (_i32, [_vp, _vp, _vp, ctypes.c_uint32, _pp]),
+    "xgm_cache_num_uncertain_plain": (_i32, [_vp, _i32]),
+    "xgm_cache_copy_node_plain": (_i32, [_vp, _i32, _vp]),
     "xgm_cache_destroy": (None, [_vp]),
     "xgm_cache_num_nodes": (_i32, [_vp]),
     "xgm_cache_copy_node_bits": (_i32, [_vp, _i32, _vp, _vp]),
@@ -110,7 +113,23 @@ def load_library():
         fn.restype = res
         fn.argtypes = args
     _lib = lib
+    _handles["lib"] = lib
     return lib
+
+
+_handles = {"lib": None}  # filled by load_library(); bound into _destroy so that it survives module teardown
+
+
+def _destroy(fn_name: str, obj, _state=_handles) -> None:
+    """Release a handle; safe during interpreter shutdown, when module globals may be gone."""
+    try:
+        h = obj.__dict__.get("_h")
+        lib = _state["lib"]
+        if h and lib is not None:
+            getattr(lib, fn_name)(h)
+        obj.__dict__["_h"] = None
+    except Exception:
+        pass
 
 
 def _check(rc: int) -> int:
@@ -136,10 +155,8 @@ class Vocab:
         self._h = h
         self.size = int(offsets.shape[0] - 1)
 
-    def __del__(self):
-        if getattr(self, "_h", None):
-            load_library().xgm_vocab_destroy(self._h)
-            self._h = None
+    def __del__(self, _destroy=_destroy):
+        _destroy("xgm_vocab_destroy", self)
 
 
 class Grammar:
@@ -150,10 +167,8 @@ class Grammar:
         _check(lib.xgm_grammar_compile(raw, len(raw), root.encode(), ctypes.byref(h)))
         self._h = h
 
-    def __del__(self):
-        if getattr(self, "_h", None):
-            load_library().xgm_grammar_destroy(self._h)
-            self._h = None
+    def __del__(self, _destroy=_destroy):
+        _destroy("xgm_grammar_destroy", self)
 
     @property
     def num_nodes(self) -> int:
@@ -186,24 +201,25 @@ class Grammar:
     def debug_classify_host(self, node: int, data: bytes) -> int:
         return _check(load_library().xgm_debug_classify_host(self._h, node, data, len(data)))
 
-    def debug_walk_host(self, stack, data: bytes, build: bool) -> int:
+    def debug_walk_host(self, stack, data: bytes, build: bool, with_steps: bool = False):
         arr = np.asarray(stack, dtype=np.int32)
-        return _check(load_library().xgm_debug_walk_host(self._h, arr.ctypes.data, int(arr.size), data, len(data),
-                                                         1 if build else 0))
+        steps = ctypes.c_int32(0)
+        rc = _check(load_library().xgm_debug_walk_host(self._h, arr.ctypes.data, int(arr.size), data, len(data),
+                                                       1 if build else 0, ctypes.byref(steps)))
+        return (rc, int(steps.value)) if with_steps else rc
 
 
 class Cache:
-    def __init__(self, grammar: Grammar, vocab: Vocab, stream: int = 0):
+    def __init__(self, grammar: Grammar, vocab: Vocab, stream: int = 0, keep_plain: bool = False):
         h = ctypes.c_void_p()
-        _check(load_library().xgm_cache_build(grammar._h, vocab._h, ctypes.c_void_p(stream), ctypes.byref(h)))
+        _check(load_library().xgm_cache_build_ex(grammar._h, vocab._h, ctypes.c_void_p(stream),
+                                                 1 if keep_plain else 0, ctypes.byref(h)))
         self._h = h
         self.grammar = grammar
         self.vocab = vocab
 
-    def __del__(self):
-        if getattr(self, "_h", None):
-            load_library().xgm_cache_destroy(self._h)
-            self._h = None
+    def __del__(self, _destroy=_destroy):
+        _destroy("xgm_cache_destroy", self)
 
     @property
     def num_nodes(self) -> int:
@@ -211,6 +227,14 @@ class Cache:
 
     def num_uncertain(self, node: int) -> int:
         return _check(load_library().xgm_cache_num_uncertain(self._h, node))
+
+    def num_uncertain_plain(self, node: int) -> int:
+        return _check(load_library().xgm_cache_num_uncertain_plain(self._h, node))
+
+    def copy_node_plain(self, node: int):
+        plain = np.zeros(bitmask_words(self.vocab.size), dtype=np.int32)
+        _check(load_library().xgm_cache_copy_node_plain(self._h, node, plain.ctypes.data))
+        return plain
 
     @property
     def host_classified(self) -> int:
@@ -240,10 +264,8 @@ class Matcher:
             self._keep = (grammar, vocab)
         self._h = h
 
-    def __del__(self):
-        if getattr(self, "_h", None):
-            load_library().xgm_matcher_destroy(self._h)
-            self._h = None
+    def __del__(self, _destroy=_destroy):
+        _destroy("xgm_matcher_destroy", self)
 
     def reset(self):
         _check(load_library().xgm_matcher_reset(self._h))

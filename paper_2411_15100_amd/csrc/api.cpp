@@ -39,6 +39,69 @@ T* dev_upload(const std::vector<T>& v) {
   return p;
 }
 
+// Long-lived device data (vocabulary arrays, automaton tables, cache bitsets
+// and lists) is carved out of 256 MiB slabs instead of one hipMalloc per
+// array: the small tables of many grammars then sit side by side in memory
+// that the driver maps with large pages, so the token walks' scattered table
+// reads do not thrash the GPU's address translation caches.  A slab is freed
+// when the last array in it has been released.
+class SlabAllocator {
+ public:
+  static constexpr size_t kSlab = (size_t)256 << 20;
+  void* alloc(size_t bytes) {
+    bytes = std::max<size_t>((bytes + 255) & ~(size_t)255, 256);
+    std::lock_guard<std::mutex> lock(mu_);
+    if (bytes > kSlab / 2) {  // big arrays get their own allocation (large pages anyway)
+      void* p = nullptr;
+      hip_check(hipMalloc(&p, bytes), "hipMalloc");
+      slabs_.push_back({(char*)p, bytes, bytes, 1});
+      return p;
+    }
+    if (cur_ < 0 || slabs_[cur_].used + bytes > slabs_[cur_].size) {
+      void* p = nullptr;
+      hip_check(hipMalloc(&p, kSlab), "hipMalloc");
+      slabs_.push_back({(char*)p, kSlab, 0, 0});
+      cur_ = (int)slabs_.size() - 1;
+    }
+    Slab& s = slabs_[cur_];
+    void* out = s.base + s.used;
+    s.used += bytes;
+    ++s.live;
+    return out;
+  }
+  void release(void* ptr) {
+    std::lock_guard<std::mutex> lock(mu_);
+    for (size_t k = 0; k < slabs_.size(); ++k) {
+      Slab& s = slabs_[k];
+      if ((char*)ptr < s.base || (char*)ptr >= s.base + s.size) continue;
+      if (--s.live > 0) return;
+      if ((int)k == cur_) { s.used = 0; return; }  // keep the current slab for reuse
+      (void)hipFree(s.base);
+      slabs_.erase(slabs_.begin() + k);
+      if (cur_ > (int)k) --cur_;
+      return;
+    }
+  }
+
+ private:
+  struct Slab { char* base; size_t size, used; int live; };
+  std::mutex mu_;
+  std::vector<Slab> slabs_;
+  int cur_ = -1;
+};
+SlabAllocator& slab() {
+  static SlabAllocator a;
+  return a;
+}
+template <class T>
+T* slab_alloc(size_t n) { return static_cast<T*>(slab().alloc(std::max<size_t>(n, 1) * sizeof(T))); }
+template <class T>
+T* slab_upload(const std::vector<T>& v) {
+  T* p = slab_alloc<T>(v.size());
+  if (!v.empty()) HIP_OK(hipMemcpy(p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
+  return p;
+}
+
 void require_device() {
   int n = 0;
   hipError_t e = hipGetDeviceCount(&n);
@@ -61,7 +124,7 @@ struct xgm_vocab {
   bool on_device = false;
   DevVocab dv{};
   std::vector<void*> dev_ptrs;
-  ~xgm_vocab() { for (void* p : dev_ptrs) (void)hipFree(p); }
+  ~xgm_vocab();
 };
 struct xgm_grammar {
   std::atomic<int> refs{1};
@@ -75,6 +138,8 @@ struct xgm_cache {
   DevCache* d_struct = nullptr;
   std::vector<void*> dev_ptrs;
   std::vector<uint32_t> unc_off_host;  // [n_nodes][n_chunk+1]
+  std::vector<uint32_t> plain_count;   // [n_nodes] tokens that only section 3.1 calls context-dependent
+  uint32_t* d_plain_id = nullptr;      // [n_nodes][W] their bitsets, if kept
   int64_t host_classified = 0;
   double kernel_seconds = 0.0;
 };
@@ -86,13 +151,15 @@ struct xgm_matcher {
   bool terminated = false;
 };
 
+xgm_vocab::~xgm_vocab() { for (void* p : dev_ptrs) slab().release(p); }
+
 namespace {
 
 void release(xgm_vocab* v) { if (v && --v->refs == 0) delete v; }
 void release(xgm_grammar* g) { if (g && --g->refs == 0) delete g; }
 void release(xgm_cache* c) {
   if (c && --c->refs == 0) {
-    for (void* p : c->dev_ptrs) (void)hipFree(p);
+    for (void* p : c->dev_ptrs) slab().release(p);
     release(c->g);
     release(c->v);
     delete c;
@@ -118,13 +185,17 @@ void vocab_to_device(xgm_vocab* v) {
   for (int32_t r = 0; r < V; ++r) by_rank[r] = by_id[v->id_of_rank[r]];
   DevVocab& d = v->dv;
   auto keep = [&](auto* p) { v->dev_ptrs.push_back((void*)p); return p; };
-  d.tok_by_id = keep(dev_upload(by_id));
-  d.tok_by_rank = keep(dev_upload(by_rank));
-  d.off_by_id = keep(dev_upload(v->off));
-  d.bytes = keep(dev_upload(v->bytes));
-  d.rank_of_id = keep(dev_upload(v->rank_of_id));
-  d.id_of_rank = keep(dev_upload(v->id_of_rank));
-  d.stop_ids = keep(dev_upload(v->stop));
+  d.tok_by_id = keep(slab_upload(by_id));
+  d.tok_by_rank = keep(slab_upload(by_rank));
+  d.off_by_id = keep(slab_upload(v->off));
+  d.bytes = keep(slab_upload(v->bytes));
+  std::vector<uint8_t> first(V, 0);
+  for (int32_t i = 0; i < V; ++i)
+    if (v->off[i + 1] > v->off[i]) first[i] = v->bytes[v->off[i]];
+  d.first_by_id = keep(slab_upload(first));
+  d.rank_of_id = keep(slab_upload(v->rank_of_id));
+  d.id_of_rank = keep(slab_upload(v->id_of_rank));
+  d.stop_ids = keep(slab_upload(v->stop));
   d.n_stop = (int32_t)v->stop.size();
   d.V = V;
   d.W = (V + 31) / 32;
@@ -289,7 +360,7 @@ int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h
 }
 
 int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth, const uint8_t* h_bytes,
-                        int32_t n, int32_t build) {
+                        int32_t n, int32_t build, int32_t* h_steps) {
   API_BEGIN
   if (!g || !h_stack || depth < 1 || depth > XGM_MAX_STACK_DEPTH || n < 0 || (n > 0 && !h_bytes))
     return fail(XGM_ERR_BAD_ARG, "walk_host: bad argument");
@@ -301,19 +372,28 @@ int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t de
     live[k] = (uint16_t)h_stack[k];
   }
   if (n == 0) return kReject;
-  DevTables T{reinterpret_cast<const uint2*>(A.hdr.data()), A.cls.data(), A.rows.data(), A.alts.data(), A.n_cls};
+  const CompactTab T{TabView{reinterpret_cast<const uint2*>(A.hdr.data()), A.n_nodes,
+                             reinterpret_cast<const uint2*>(A.hdr.data()), A.cls.data(), A.shapes.data(),
+                             A.targets.data(), A.alts.data(), A.follow_words.data(), A.n_cls}};
   unsigned char row[16] = {0};
   std::memcpy(row, h_bytes, std::min<int32_t>(n, 15));
   row[15] = (unsigned char)std::min<int32_t>(n, 255);
   uint4 tk;
   std::memcpy(&tk, row, 16);
-  return build ? walk_token<true>(T, tk, h_bytes, n, live[depth - 1], nullptr, 1u)
-               : walk_token<false>(T, tk, h_bytes, n, live[depth - 1], live.data(), (uint32_t)depth);
+  uint32_t steps = 0;
+  const int rc = build ? walk_token<true>(T, tk, h_bytes, n, live[depth - 1], nullptr, 1u, &steps, T.follow_of(live[depth - 1]))
+                       : walk_token<false>(T, tk, h_bytes, n, live[depth - 1], live.data(), (uint32_t)depth, &steps);
+  if (h_steps) *h_steps = (int32_t)steps;
+  return rc;
   API_END
 }
 
 // --------------------------------------------------------------------- cache
 int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out) {
+  return xgm_cache_build_ex(g, v, hip_stream, 0, out);
+}
+
+int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t flags, xgm_cache** out) {
   API_BEGIN
   if (!out) return fail(XGM_ERR_BAD_ARG, "cache_build: out is null");
   *out = nullptr;
@@ -338,22 +418,36 @@ int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** 
     std::vector<uint2> hdr(N);
     std::memcpy(hdr.data(), A.hdr.data(), (size_t)N * sizeof(uint2));
     DevTables tab{};
-    tab.hdr = keep(dev_upload(hdr));
-    tab.cls = keep(dev_upload(A.cls));
-    tab.rows = keep(dev_upload(A.rows));
-    tab.alts = keep(dev_upload(A.alts));
+    tab.hdr = keep(slab_upload(hdr));
+    tab.cls = keep(slab_upload(A.cls));
+    tab.shapes = keep(slab_upload(A.shapes));
+    tab.targets = keep(slab_upload(A.targets));
+    tab.alts = keep(slab_upload(A.alts));
+    tab.follow_rules = keep(slab_upload(A.follow_words));
+    tab.n_rules = (int32_t)A.rule_names.size();
     tab.n_cls = A.n_cls;
-    const int32_t n_rows_tab = (int32_t)(A.rows.size() / std::max(1, A.n_cls));
-    const int32_t n_alts = (int32_t)A.alts.size();
-    const size_t table_bytes = (size_t)N * 8 + (size_t)n_alts * 4 + (size_t)n_rows_tab * A.n_cls * 2 + 256;
+    tab.n_nodes = N;
+    tab.n_shapes = (int32_t)(A.shapes.size() / std::max(1, A.n_cls));
+    tab.n_targets = (int32_t)A.targets.size();
+    tab.n_alts = (int32_t)A.alts.size();
+    {
+      const size_t aux = (size_t)tab.n_alts * 4 + (size_t)tab.n_rules * 32 + (size_t)((tab.n_targets + 1) & ~1) * 2 +
+                         (size_t)tab.n_shapes * A.n_cls + 256;
+      tab.aux_bytes = aux <= 24 * 1024 ? (int32_t)aux : 0;
+    }
 
-    uint32_t* acc_id = keep(dev_alloc<uint32_t>((size_t)N * dv.W));
+    uint32_t* acc_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W));
     uint32_t* unc_id = temp(dev_alloc<uint32_t>((size_t)N * dv.W));
     // rank-space scratch for a batch of nodes (at most 1 GiB for both bitsets)
     const size_t row_bytes = (size_t)dv.WR * 4;
     int32_t batch = (int32_t)std::max<size_t>(1, std::min<size_t>((size_t)N, ((size_t)512 << 20) / row_bytes));
     uint32_t* acc_rank = temp(dev_alloc<uint32_t>((size_t)batch * dv.WR));
     uint32_t* unc_rank = temp(dev_alloc<uint32_t>((size_t)batch * dv.WR));
+    const bool keep_plain = (flags & XGM_CACHE_KEEP_PLAIN) != 0;
+    uint32_t* plain_rank = keep_plain ? temp(dev_alloc<uint32_t>((size_t)batch * dv.WR)) : nullptr;
+    if (keep_plain) c->d_plain_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W));
+    uint32_t* d_plain_count = temp(dev_alloc<uint32_t>((size_t)N));
+    HIP_OK(hipMemsetAsync(d_plain_count, 0, (size_t)N * 4, stream));
     OverflowLog* log;
     uint32_t seq, count_before;
     {
@@ -367,10 +461,11 @@ int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** 
     HIP_OK(hipEventCreate(&ev0));
     HIP_OK(hipEventCreate(&ev1));
     Engine engine(&A);
+    std::vector<int32_t> host_plain;  // nodes of host-decided pairs that are context-dependent by section 3.1 alone
     for (int32_t node0 = 0; node0 < N; node0 += batch) {
       const int32_t nb = std::min(batch, N - node0);
       HIP_OK(hipEventRecord(ev0, stream));
-      launch_classify(tab, table_bytes, n_rows_tab, n_alts, N, dv, node0, nb, acc_rank, unc_rank, log, seq, stream);
+      launch_classify(tab, dv, node0, nb, acc_rank, unc_rank, plain_rank, d_plain_count, log, seq, stream);
       HIP_OK(hipEventRecord(ev1, stream));
       HIP_OK(hipGetLastError());
       HIP_OK(hipStreamSynchronize(stream));
@@ -392,11 +487,12 @@ int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** 
           int cls = engine.classify(node0 + (int32_t)e[1], v->bytes.data() + v->off[id], (int)(v->off[id + 1] - v->off[id]));
           if (cls < 0) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: a token walk exceeds the host limits too");
           items.push_back(e[1]); items.push_back(e[2]); items.push_back((uint32_t)cls);
+          if (cls == kUncertainPlain) host_plain.push_back(node0 + (int32_t)e[1]);
           ++c->host_classified;
         }
         if (!items.empty()) {
           uint32_t* d_items = dev_upload(items);
-          launch_patch_classes(dv, d_items, (int32_t)(items.size() / 3), acc_rank, unc_rank, stream);
+          launch_patch_classes(dv, d_items, (int32_t)(items.size() / 3), acc_rank, unc_rank, plain_rank, stream);
           HIP_OK(hipStreamSynchronize(stream));
           (void)hipFree(d_items);
         }
@@ -405,11 +501,17 @@ int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** 
         ctx().seen_count = count_after;
       }
       launch_permute(dv, nb, acc_rank, unc_rank, acc_id + (size_t)node0 * dv.W, unc_id + (size_t)node0 * dv.W, stream);
+      if (keep_plain)
+        launch_permute(dv, nb, plain_rank, plain_rank, c->d_plain_id + (size_t)node0 * dv.W,
+                       c->d_plain_id + (size_t)node0 * dv.W, stream);
       HIP_OK(hipGetLastError());
       HIP_OK(hipStreamSynchronize(stream));
     }
     (void)hipEventDestroy(ev0);
     (void)hipEventDestroy(ev1);
+    c->plain_count.resize(N);
+    HIP_OK(hipMemcpy(c->plain_count.data(), d_plain_count, (size_t)N * 4, hipMemcpyDeviceToHost));
+    for (int32_t n : host_plain) ++c->plain_count[n];
     // context-dependent lists
     uint32_t* d_counts = temp(dev_alloc<uint32_t>((size_t)N * dv.n_chunk));
     launch_count_uncertain(dv, N, unc_id, d_counts, stream);
@@ -427,9 +529,10 @@ int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** 
       c->unc_off_host[(size_t)n * (dv.n_chunk + 1) + dv.n_chunk] = (uint32_t)total;
       if (total >= ((uint64_t)1 << 32)) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: context-dependent lists exceed 2^32 entries");
     }
-    uint32_t* d_off = keep(dev_upload(c->unc_off_host));
-    uint16_t* d_list = keep(dev_alloc<uint16_t>((size_t)total));
+    uint32_t* d_off = keep(slab_upload(c->unc_off_host));
+    uint32_t* d_list = keep(slab_alloc<uint32_t>((size_t)total));
     launch_list_uncertain(dv, N, unc_id, d_off, d_list, stream);
+    launch_annotate_lists(tab, dv, N, d_off, d_list, stream);
     HIP_OK(hipGetLastError());
     HIP_OK(hipStreamSynchronize(stream));
     cleanup_temps();
@@ -439,7 +542,8 @@ int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** 
     c->host.unc_off = d_off;
     c->host.unc_list = d_list;
     c->host.n_nodes = N;
-    c->d_struct = keep(dev_alloc<DevCache>(1));
+    c->host.n_near_fill = near_headers(tab, kFillLdsBudget);
+    c->d_struct = keep(slab_alloc<DevCache>(1));
     HIP_OK(hipMemcpy(c->d_struct, &c->host, sizeof(DevCache), hipMemcpyHostToDevice));
   } catch (...) {
     cleanup_temps();
@@ -458,6 +562,19 @@ int32_t xgm_cache_num_uncertain(const xgm_cache* c, int32_t node) {
   const uint32_t* off = &c->unc_off_host[(size_t)node * (nc + 1)];
   return (int32_t)(off[nc] - off[0]);
 }
+int32_t xgm_cache_num_uncertain_plain(const xgm_cache* c, int32_t node) {
+  if (!c || node < 0 || node >= c->host.n_nodes) return fail(XGM_ERR_BAD_ARG, "num_uncertain_plain: bad cache or node");
+  return (int32_t)c->plain_count[node];
+}
+int xgm_cache_copy_node_plain(const xgm_cache* c, int32_t node, int32_t* h_plain) {
+  API_BEGIN
+  if (!c || !h_plain || node < 0 || node >= c->host.n_nodes) return fail(XGM_ERR_BAD_ARG, "copy_node_plain: bad argument");
+  if (!c->d_plain_id) return fail(XGM_ERR_BAD_ARG, "copy_node_plain: the cache was built without XGM_CACHE_KEEP_PLAIN");
+  const int32_t W = c->v->dv.W;
+  HIP_OK(hipMemcpy(h_plain, c->d_plain_id + (size_t)node * W, (size_t)W * 4, hipMemcpyDeviceToHost));
+  return XGM_OK;
+  API_END
+}
 int64_t xgm_cache_host_classified(const xgm_cache* c) { return c ? c->host_classified : XGM_ERR_BAD_ARG; }
 double xgm_cache_build_kernel_seconds(const xgm_cache* c) { return c ? c->kernel_seconds : -1.0; }
 
@@ -470,11 +587,11 @@ int xgm_cache_copy_node_bits(const xgm_cache* c, int32_t node, int32_t* h_acc, i
     std::memset(h_unc, 0, (size_t)dv.W * 4);
     const uint32_t* off = &c->unc_off_host[(size_t)node * (dv.n_chunk + 1)];
     const uint32_t n = off[dv.n_chunk] - off[0];
-    std::vector<uint16_t> list(n);
-    if (n) HIP_OK(hipMemcpy(list.data(), c->host.unc_list + off[0], (size_t)n * 2, hipMemcpyDeviceToHost));
+    std::vector<uint32_t> list(n);
+    if (n) HIP_OK(hipMemcpy(list.data(), c->host.unc_list + off[0], (size_t)n * 4, hipMemcpyDeviceToHost));
     for (int32_t k = 0; k < dv.n_chunk; ++k)
       for (uint32_t j = off[k]; j < off[k + 1]; ++j) {
-        const uint32_t id = (uint32_t)k * kChunkTokens + list[j - off[0]];
+        const uint32_t id = (uint32_t)k * kChunkTokens + (list[j - off[0]] & 0xFFFu);
         reinterpret_cast<uint32_t*>(h_unc)[id >> 5] |= 1u << (id & 31);
       }
   }
@@ -582,8 +699,10 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   }
   require_device();
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int32_t n_chunk = v->dv.n_chunk;
+  const size_t hdr_words = kStackHdrWords + (size_t)n_chunk + 1;
   const size_t off_stacks = (size_t)B * sizeof(RowDesc);
-  const size_t off_frames = off_stacks + n_stacks * sizeof(StackDesc);
+  const size_t off_frames = off_stacks + n_stacks * hdr_words * 4;
   const size_t bytes = ((off_frames + n_frames * 2 + 63) / 64) * 64;
 
   Context& C = ctx();
@@ -601,7 +720,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   }
   if (!slot.done) HIP_OK(hipEventCreateWithFlags(&slot.done, hipEventDisableTiming));
   auto* rows = reinterpret_cast<RowDesc*>(slot.h_buf);
-  auto* stacks = reinterpret_cast<StackDesc*>((char*)slot.h_buf + off_stacks);
+  auto* hdrs = reinterpret_cast<uint32_t*>((char*)slot.h_buf + off_stacks);
   auto* frames = reinterpret_cast<uint16_t*>((char*)slot.h_buf + off_frames);
   uint32_t si = 0, fi = 0;
   for (int32_t b = 0; b < B; ++b) {
@@ -615,12 +734,33 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
       r.flags = 1;
       continue;
     }
+    const Automaton& A = m->g->A;
     r.cache = m->c->d_struct;
     r.n_stacks = (uint32_t)m->stacks.size();
-    r.flags = Engine(&m->g->A).can_terminate(m->stacks) ? 1u : 0u;
+    r.flags = Engine(&A).can_terminate(m->stacks) ? 1u : 0u;
     for (auto& s : m->stacks) {
-      stacks[si].frame_off = fi;
-      stacks[si].depth = (uint32_t)s.size();
+      uint32_t* h = hdrs + (size_t)si * hdr_words;
+      const int32_t top = s.back();
+      h[kStackHdrTop] = (uint32_t)top;
+      h[kStackHdrDepth] = (uint32_t)s.size();
+      h[kStackHdrFrames] = fi;
+      h[3] = 0;
+      // bytes that can be consumed from this stack: at the top node, or - as
+      // long as the frames passed so far may all end here - at the frames
+      // below; and the same for the stack without its top frame
+      for (int below = 0; below < 2; ++below) {
+        std::bitset<256> ok;
+        for (size_t k = s.size() - below; k-- > 0;) {
+          ok |= A.node_first[s[k]];
+          if (!A.node_final[s[k]]) break;
+        }
+        for (int w = 0; w < 8; ++w) {
+          uint32_t bits = 0;
+          for (int k = 0; k < 32; ++k) bits |= (uint32_t)ok.test(w * 32 + k) << k;
+          h[(below ? kStackHdrBelow : kStackHdrFirst) + w] = bits;
+        }
+      }
+      std::memcpy(h + kStackHdrWords, &m->c->unc_off_host[(size_t)top * (n_chunk + 1)], (size_t)(n_chunk + 1) * 4);
       ++si;
       for (int32_t n : s) frames[fi++] = (uint16_t)n;
     }
@@ -628,7 +768,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   HIP_OK(hipMemcpyAsync(slot.d_buf, slot.h_buf, bytes, hipMemcpyHostToDevice, stream));
   const uint32_t seq = ++C.seq;
   launch_fill(reinterpret_cast<const RowDesc*>(slot.d_buf),
-              reinterpret_cast<const StackDesc*>((char*)slot.d_buf + off_stacks),
+              reinterpret_cast<const uint32_t*>((char*)slot.d_buf + off_stacks),
               reinterpret_cast<const uint16_t*>((char*)slot.d_buf + off_frames), B, v->dv,
               reinterpret_cast<uint32_t*>(d_bitmask), log, seq, d_step_counter, stream);
   HIP_OK(hipGetLastError());
@@ -689,11 +829,12 @@ int xgm_fill_overflow_fixup(void* hip_stream) {
   // the staging blob of the last fill still holds that fill's stacks
   const FillSlot& slot = C.slot[C.last_slot];
   const auto* rows = reinterpret_cast<const RowDesc*>(slot.h_buf);
-  const auto* stacks = reinterpret_cast<const StackDesc*>((const char*)slot.h_buf + (size_t)C.last_B * sizeof(RowDesc));
+  const xgm_vocab& v = *C.last_vocab;
+  const size_t hdr_words = kStackHdrWords + (size_t)v.dv.n_chunk + 1;
+  const auto* hdrs = reinterpret_cast<const uint32_t*>((const char*)slot.h_buf + (size_t)C.last_B * sizeof(RowDesc));
   size_t n_stacks = 0;
   for (int32_t b = 0; b < C.last_B; ++b) n_stacks += rows[b].n_stacks;
-  const auto* frames = reinterpret_cast<const uint16_t*>((const char*)stacks + n_stacks * sizeof(StackDesc));
-  const xgm_vocab& v = *C.last_vocab;
+  const auto* frames = reinterpret_cast<const uint16_t*>(hdrs + n_stacks * hdr_words);
   const int32_t W = v.dv.W;
   int handled = 0;
   for (uint32_t k = 0; k < fresh; ++k) {
@@ -704,8 +845,8 @@ int xgm_fill_overflow_fixup(void* hip_stream) {
     Engine engine(&m->g->A);
     bool ok = false;
     for (uint32_t s = 0; s < rows[b].n_stacks && !ok; ++s) {
-      const StackDesc& sd = stacks[rows[b].stack_begin + s];
-      Stack st(frames + sd.frame_off, frames + sd.frame_off + sd.depth);
+      const uint32_t* h = hdrs + (size_t)(rows[b].stack_begin + s) * hdr_words;
+      Stack st(frames + h[kStackHdrFrames], frames + h[kStackHdrFrames] + h[kStackHdrDepth]);
       std::vector<Stack> out;
       int rc = engine.advance({st}, v.bytes.data() + v.off[id], (int)(v.off[id + 1] - v.off[id]), &out, nullptr, (size_t)-1);
       if (rc == XGM_OK) ok = true;

@@ -541,7 +541,7 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
     dfa[r] = std::move(m);
   }
 
-  // rules reachable from the root, numbered in discovery order
+  // rules reachable from the root
   std::vector<int> new_index(R, -1), order;
   {
     std::vector<int> work{root_rule};
@@ -556,8 +556,14 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
     }
   }
 
+  // Small rules first: the rules shared by many call sites (strings, numbers,
+  // white space) are small, and the kernels keep the headers of the lowest
+  // node ids on chip.
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return dfa[a].size() < dfa[b].size(); });
+  for (size_t k = 0; k < order.size(); ++k) new_index[order[k]] = (int)k;
+
   Automaton A;
-  A.root_rule = 0;
+  A.root_rule = new_index[root_rule];
   int total = 0;
   for (int r : order) { A.rule_start.push_back(total); total += (int)dfa[r].size(); A.rule_names.push_back(parser.names_[r]); }
   if (total > XGM_MAX_NODES) throw Failure(XGM_ERR_TOO_LARGE, "grammar: automaton has " + std::to_string(total) + " nodes (limit 32767)");
@@ -616,6 +622,26 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
     }
   }
 
+  A.node_first.assign(total, {});
+  for (int n = 0; n < total; ++n) {
+    for (auto& e : A.bedges[n]) for (int c = e.lo; c <= e.hi; ++c) A.node_first[n].set(c);
+    for (auto& e : A.redges[n]) A.node_first[n] |= A.first[e.rule];
+  }
+
+  // FOLLOW sets: what can be consumed at the return node of some reference to
+  // the rule, and, if the referencing rule may end there, what can follow it.
+  // Nothing follows the root rule itself (end of the text).
+  A.follow.assign(NR, {});
+  for (bool changed = true; changed;) {
+    changed = false;
+    for (int n = 0; n < total; ++n)
+      for (auto& e : A.redges[n]) {
+        std::bitset<256> f = A.follow[e.rule] | A.node_first[e.to];
+        if (A.node_final[e.to]) f |= A.follow[A.node_rule[n]];
+        if (f != A.follow[e.rule]) { A.follow[e.rule] = f; changed = true; }
+      }
+  }
+
   // witness paths (breadth-first from each rule start)
   A.node_path.assign(total, {});
   for (int r = 0; r < NR; ++r) {
@@ -635,7 +661,7 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
   }
 
   // ---- flatten for the device
-  // byte classes: bytes that no row node and no FIRST set tells apart
+  // byte classes: bytes that no node's edges and no FIRST set tell apart
   std::vector<int> row_nodes;
   for (int n = 0; n < total; ++n)
     if (!(A.redges[n].empty() && A.bedges[n].size() <= 1)) row_nodes.push_back(n);
@@ -648,7 +674,7 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
     std::map<std::string, int> key_id;
     for (int c = 0; c < 256; ++c) {
       std::string key;
-      for (int n : row_nodes) { int t = byte_target(n, c); key += (char)(t & 0xFF); key += (char)((t >> 8) & 0xFF); key += (char)((t >> 16) & 0xFF); }
+      for (int n = 0; n < total; ++n) { int t = byte_target(n, c); key += (char)(t & 0xFF); key += (char)((t >> 8) & 0xFF); key += (char)((t >> 16) & 0xFF); }
       for (int r = 0; r < NR; ++r) key += A.first[r].test(c) ? '1' : '0';
       auto it = key_id.find(key);
       if (it == key_id.end()) it = key_id.emplace(key, (int)key_id.size()).first;
@@ -659,28 +685,62 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
   std::vector<int> cls_rep(A.n_cls, -1);
   for (int c = 255; c >= 0; --c) cls_rep[A.cls[c]] = c;
 
-  A.hdr.assign(total, NodeHdr{1, 0, 0, kNoRow, 0});
+  A.node_dead_end.assign(total, 0);
+  for (int n = 0; n < total; ++n)
+    A.node_dead_end[n] = A.node_final[n] && A.bedges[n].empty() && A.redges[n].empty();
+
+  // Alternatives of node n on byte c, in the order the walk tries them:
+  //  * the byte edge;
+  //  * for every reference whose callee can start with c: enter the callee.
+  //    - If the return node is a dead end (accepting, no outgoing edges) no
+  //      frame is needed: returning there could only be followed by another
+  //      return, so the callee returns straight to the caller's parent.
+  //    - If the callee does nothing with c but consume it and end (a single
+  //      byte edge from its start into a dead end, no reference of its own
+  //      that could start with c), the whole call is the move "consume c, go
+  //      to the return node"; the frame would be pushed and popped unseen.
+  //    Both are exact for the token classes too: neither changes which bytes
+  //    are consumed inside the frame the walk started in.
+  auto alternatives = [&](int n, int c) {
+    std::vector<uint32_t> list;
+    int t = byte_target(n, c);
+    if (t >= 0) list.push_back((kMoveTag << 16) | (uint32_t)t);
+    for (auto& e : A.redges[n]) {
+      if (!A.first[e.rule].test(c)) continue;
+      const int s = A.rule_start[e.rule];
+      const int m = byte_target(s, c);
+      bool callee_refs = false;
+      for (auto& e2 : A.redges[s]) callee_refs = callee_refs || A.first[e2.rule].test(c);
+      uint32_t alt;
+      if (m >= 0 && A.node_dead_end[m] && !callee_refs) alt = (kMoveTag << 16) | (uint32_t)e.to;
+      else if (A.node_dead_end[e.to]) alt = (kTailTag << 16) | (uint32_t)s;
+      else alt = ((uint32_t)e.to << 16) | (uint32_t)s;
+      if (std::find(list.begin(), list.end(), alt) == list.end()) list.push_back(alt);
+    }
+    return list;
+  };
+
+  // Branching nodes: for every byte class one of the node's few outcomes.
+  // Which class leads to which outcome index is the node's "shape" (shared by
+  // many nodes, e.g. every  ws "," ws  position); the outcomes themselves are
+  // the node's own slice of `targets`.
+  A.hdr.assign(total, NodeHdr{1, 0, 0, 0});
   std::map<std::vector<uint32_t>, uint32_t> alt_ids;
-  int n_rows = 0;
+  std::map<std::vector<uint8_t>, uint32_t> shape_ids;
   for (int n = 0; n < total; ++n) {
     NodeHdr& h = A.hdr[n];
-    h.flags = A.node_final[n] ? 1 : 0;
+    h.flags = A.node_final[n] ? kFlagFinal : 0;
     if (A.redges[n].empty() && A.bedges[n].size() <= 1) {
       if (A.bedges[n].size() == 1) { h.lo = A.bedges[n][0].lo; h.hi = A.bedges[n][0].hi; h.target = (uint16_t)A.bedges[n][0].to; }
       continue;
     }
-    h.row = (uint16_t)n_rows++;
-    if (n_rows >= 0xFFFF) throw Failure(XGM_ERR_TOO_LARGE, "grammar: too many branching nodes");
+    std::vector<uint8_t> shape(A.n_cls, kDeadShape);
+    std::vector<uint16_t> outcomes;
     for (int k = 0; k < A.n_cls; ++k) {
-      int c = cls_rep[k];
-      int t = byte_target(n, c);
-      std::vector<uint32_t> list;
-      if (t >= 0) list.push_back((kMoveTag << 16) | (uint32_t)t);
-      for (auto& e : A.redges[n])
-        if (A.first[e.rule].test(c)) list.push_back(((uint32_t)e.to << 16) | (uint32_t)A.rule_start[e.rule]);
+      std::vector<uint32_t> list = alternatives(n, cls_rep[k]);
+      if (list.empty()) continue;
       uint16_t entry;
-      if (list.empty()) entry = kDead;
-      else if (list.size() == 1 && t >= 0) entry = (uint16_t)t;
+      if (list.size() == 1 && (list[0] >> 16) == kMoveTag) entry = (uint16_t)(list[0] & 0xFFFF);
       else {
         if (list.size() > 250) throw Failure(XGM_ERR_TOO_LARGE, "grammar: too many alternatives at one node");
         auto it = alt_ids.find(list);
@@ -694,11 +754,33 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
         entry = (uint16_t)(kAltFlag | it->second);
         A.max_alts = std::max<int>(A.max_alts, (int)list.size());
       }
-      A.rows.push_back(entry);
+      size_t idx = std::find(outcomes.begin(), outcomes.end(), entry) - outcomes.begin();
+      if (idx == outcomes.size()) outcomes.push_back(entry);
+      if (idx >= kDeadShape) throw Failure(XGM_ERR_TOO_LARGE, "grammar: too many distinct outcomes at one node");
+      shape[k] = (uint8_t)idx;
     }
+    auto it = shape_ids.find(shape);
+    if (it == shape_ids.end()) {
+      uint32_t id = (uint32_t)shape_ids.size();
+      if (id >= 0xFFFF) throw Failure(XGM_ERR_TOO_LARGE, "grammar: too many node shapes");
+      A.shapes.insert(A.shapes.end(), shape.begin(), shape.end());
+      it = shape_ids.emplace(shape, id).first;
+    }
+    if (A.targets.size() + outcomes.size() > 0xFFFF) throw Failure(XGM_ERR_TOO_LARGE, "grammar: outcome table is full");
+    h.flags |= kFlagBranching;
+    h.lo = (uint8_t)(it->second & 0xFF);          // shape id, low and high byte
+    h.hi = (uint8_t)(it->second >> 8);
+    h.target = (uint16_t)A.targets.size();        // start of this node's outcomes
+    A.targets.insert(A.targets.end(), outcomes.begin(), outcomes.end());
   }
+  A.n_shapes = (int32_t)shape_ids.size();
+  for (int n = 0; n < total; ++n) A.hdr[n].flags |= (uint32_t)A.node_rule[n] << 16;
+  A.follow_words.assign((size_t)NR * 8, 0u);
+  for (int r = 0; r < NR; ++r)
+    for (int c = 0; c < 256; ++c) A.follow_words[(size_t)r * 8 + (c >> 5)] |= (uint32_t)A.follow[r].test(c) << (c & 31);
   if (A.alts.empty()) A.alts.push_back(0);
-  if (A.rows.empty()) A.rows.push_back(kDead);
+  if (A.shapes.empty()) A.shapes.assign(A.n_cls, kDeadShape);
+  if (A.targets.empty()) A.targets.push_back(0);
   return A;
 }
 

@@ -18,32 +18,41 @@ struct Failure : std::runtime_error {
 struct ByteEdge { uint8_t lo, hi; int32_t to; };
 struct RefEdge { int32_t rule; int32_t to; };
 
-// Device header of one node (8 bytes).  If lo <= hi the node has a "primary"
-// byte edge [lo, hi] -> target that is tested first; `row` (if not kNoRow)
-// selects a dense row indexed by byte class for everything else.
+// Device header of one node (8 bytes).
+//  * plain node (at most one byte edge, no references): [lo, hi] -> target,
+//    lo > hi if it has no edge at all;
+//  * branching node (kFlagBranching): lo | hi << 8 is its shape id and
+//    `target` the start of its outcomes in `targets`; for byte c the outcome
+//    is targets[target + shapes[shape * n_cls + cls[c]]] unless that shape
+//    entry is kDeadShape.
 struct NodeHdr {
   uint8_t lo, hi;
   uint16_t target;
-  uint16_t row;
-  uint16_t flags;  // bit 0: the rule may end at this node
+  uint32_t flags;  // kFlagFinal | kFlagBranching | rule index << 16
 };
 static_assert(sizeof(NodeHdr) == 8, "NodeHdr must be 8 bytes");
 
-constexpr uint16_t kNoRow = 0xFFFF;
-constexpr uint16_t kDead = 0xFFFF;      // row entry: nothing to do for this byte
-constexpr uint16_t kAltFlag = 0x8000;   // row entry: index into the alternatives pool
-constexpr uint32_t kMoveTag = 0xFFFF;   // alternative (tag << 16 | node): byte move
+constexpr uint32_t kFlagFinal = 1;      // the rule may end at this node
+constexpr uint32_t kFlagBranching = 2;
+constexpr uint8_t kDeadShape = 0xFF;    // shape entry: nothing to do for this byte class
+constexpr uint16_t kAltFlag = 0x8000;   // outcome: index into the alternatives pool (else: move to that node)
+constexpr uint32_t kMoveTag = 0xFFFF;   // alternative (tag << 16 | node): consume the byte, go to node
+constexpr uint32_t kTailTag = 0xFFFE;   // alternative: enter the callee at `node` without pushing a frame
+                                        // (any other tag is the return node to push)
 
 struct Automaton {
   // structured form (host engine)
   int32_t n_nodes = 0;
   std::vector<int32_t> node_rule;
   std::vector<uint8_t> node_final;
+  std::vector<uint8_t> node_dead_end;         // accepting and without outgoing edges: all it can do is return
   std::vector<std::vector<ByteEdge>> bedges;  // sorted, disjoint
   std::vector<std::vector<RefEdge>> redges;
   std::vector<int32_t> rule_start;            // per rule: global node id
   std::vector<std::string> rule_names;
   std::vector<std::bitset<256>> first;        // per rule: bytes an instance can start with
+  std::vector<std::bitset<256>> node_first;   // per node: bytes that can be consumed at the node inside its frame
+  std::vector<std::bitset<256>> follow;       // per rule: bytes that can come right after an instance, in any context
   int32_t root_rule = 0;
   std::vector<std::vector<int32_t>> node_path;  // witness path from the rule start
 
@@ -51,7 +60,10 @@ struct Automaton {
   std::vector<NodeHdr> hdr;        // [n_nodes]
   std::vector<uint8_t> cls;        // [256] byte -> class
   int32_t n_cls = 0;
-  std::vector<uint16_t> rows;      // [n_rows * n_cls]
+  std::vector<uint8_t> shapes;     // [n_shapes * n_cls]
+  int32_t n_shapes = 0;
+  std::vector<uint16_t> targets;   // outcomes of the branching nodes, node after node
+  std::vector<uint32_t> follow_words;  // [n_rules][8]: `follow` as 256-bit sets
   std::vector<uint32_t> alts;      // pool: count, then count entries (tag << 16 | node)
   int32_t max_alts = 0;
 };

@@ -12,7 +12,7 @@ constexpr size_t kMaxConfigs = 1 << 16;  // configurations explored per byte
 }
 
 int Engine::advance(const std::vector<Stack>& in, const uint8_t* bytes, int n, std::vector<Stack>* out,
-                    bool* left_frame, size_t max_out) const {
+                    int* left_frame, size_t max_out, int32_t follow_rule) const {
   const Automaton& A = *A_;
   std::set<Stack> cur(in.begin(), in.end());
   for (int i = 0; i < n; ++i) {
@@ -38,15 +38,19 @@ int Engine::advance(const std::vector<Stack>& in, const uint8_t* bytes, int n, s
         if (A.first[e.rule].test(c)) {
           if ((int)st.size() + 1 > XGM_MAX_STACK_DEPTH) return XGM_ERR_TOO_LARGE;
           Stack s2 = st;
-          s2.back() = e.to;                       // return node
-          s2.push_back(A.rule_start[e.rule]);     // enter the callee
+          if (A.node_dead_end[e.to]) {
+            s2.back() = A.rule_start[e.rule];     // returning to a dead end = returning to our parent
+          } else {
+            s2.back() = e.to;                     // return node
+            s2.push_back(A.rule_start[e.rule]);   // enter the callee
+          }
           std::pair<Stack, bool> c2{std::move(s2), false};
           if (seen.insert(c2).second) work.push_back(std::move(c2));
         }
       // the rule may end here; an instance must have consumed a byte
       if (A.node_final[node] && cfg.second && st.size() >= 2) {
         if (st[st.size() - 2] == kBottom) {
-          if (left_frame) *left_frame = true;
+          if (left_frame) *left_frame |= (follow_rule >= 0 && A.follow[follow_rule].test(c)) ? 3 : 1;
         } else {
           Stack s2(st.begin(), st.end() - 1);
           std::pair<Stack, bool> c2{std::move(s2), true};
@@ -58,6 +62,16 @@ int Engine::advance(const std::vector<Stack>& in, const uint8_t* bytes, int n, s
     if (next.empty()) return XGM_ERR_TOKEN_REJECTED;
     cur.swap(next);
   }
+  // A top node that can only return is returned from right away, so that the
+  // stack top is always a node with something of its own to say about the
+  // next token (and equal states get equal representations).
+  std::set<Stack> norm;
+  for (auto& s : cur) {
+    Stack t = s;
+    while (t.size() >= 2 && t[t.size() - 2] != kBottom && A.node_dead_end[t.back()]) t.pop_back();
+    norm.insert(std::move(t));
+  }
+  cur.swap(norm);
   if (cur.size() > max_out) return XGM_ERR_TOO_MANY_STACKS;
   out->assign(cur.begin(), cur.end());
   return XGM_OK;
@@ -76,10 +90,10 @@ bool Engine::can_terminate(const std::vector<Stack>& stacks) const {
 int Engine::classify(int32_t node, const uint8_t* bytes, int n) const {
   if (n == 0) return 0;
   std::vector<Stack> in{Stack{kBottom, node}}, out;
-  bool left = false;
-  int rc = advance(in, bytes, n, &out, &left, (size_t)-1);
+  int left = 0;
+  int rc = advance(in, bytes, n, &out, &left, (size_t)-1, A_->node_rule[node]);
   if (rc == XGM_OK) return 2;
-  if (rc == XGM_ERR_TOKEN_REJECTED) return left ? 1 : 0;
+  if (rc == XGM_ERR_TOKEN_REJECTED) return (left & 2) ? 1 : (left & 1) ? 4 : 0;
   return -1;
 }
 

@@ -2,6 +2,8 @@
 // context-dependent lists, batched mask fill, -inf apply.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "kernels.hpp"
 #include "walk.hpp"
 
@@ -17,6 +19,46 @@ __device__ __forceinline__ void record_overflow(OverflowLog* log, uint32_t seq, 
   log->entry[slot][2] = b;
 }
 
+// Copy a grammar's small tables and its first `n_near` node headers into LDS
+// (all threads of the workgroup call this; a barrier must follow).  With
+// n_near == 0 nothing is copied and the walk reads global memory.
+// LDS layout: [headers][alts][follow sets][targets, padded to 4 bytes][shapes][cls].
+__device__ __forceinline__ TabView stage_tables(const DevTables& tab, int32_t n_near, unsigned char* smem, int nthreads) {
+  TabView T;
+  T.hdr_far = tab.hdr;
+  T.n_cls = tab.n_cls;
+  if (n_near <= 0) {
+    T.hdr_near = tab.hdr;
+    T.n_near = 0;
+    T.cls = tab.cls;
+    T.shapes = tab.shapes;
+    T.targets = tab.targets;
+    T.alts = tab.alts;
+    T.follow_rules = tab.follow_rules;
+    return T;
+  }
+  uint2* s_hdr = reinterpret_cast<uint2*>(smem);
+  uint32_t* s_alts = reinterpret_cast<uint32_t*>(s_hdr + n_near);
+  uint32_t* s_follow = s_alts + tab.n_alts;
+  uint16_t* s_targets = reinterpret_cast<uint16_t*>(s_follow + tab.n_rules * 8);
+  uint8_t* s_shapes = reinterpret_cast<uint8_t*>(s_targets + ((tab.n_targets + 1) & ~1));
+  uint8_t* s_cls = s_shapes + tab.n_shapes * tab.n_cls;
+  for (int k = threadIdx.x; k < n_near; k += nthreads) s_hdr[k] = tab.hdr[k];
+  for (int k = threadIdx.x; k < tab.n_alts; k += nthreads) s_alts[k] = tab.alts[k];
+  for (int k = threadIdx.x; k < tab.n_rules * 8; k += nthreads) s_follow[k] = tab.follow_rules[k];
+  for (int k = threadIdx.x; k < tab.n_targets; k += nthreads) s_targets[k] = tab.targets[k];
+  for (int k = threadIdx.x; k < tab.n_shapes * tab.n_cls; k += nthreads) s_shapes[k] = tab.shapes[k];
+  for (int k = threadIdx.x; k < 256; k += nthreads) s_cls[k] = tab.cls[k];
+  T.hdr_near = s_hdr;
+  T.n_near = n_near;
+  T.cls = s_cls;
+  T.shapes = s_shapes;
+  T.targets = s_targets;
+  T.alts = s_alts;
+  T.follow_rules = s_follow;
+  return T;
+}
+
 // ---------------------------------------------------------------- kernel (a)
 constexpr int kClassifyThreads = 256;
 constexpr int kNodesPerBlock = 16;
@@ -25,30 +67,15 @@ constexpr int kNodesPerBlock = 16;
 // neighbours in the sorted vocabulary and mostly share prefixes and control
 // flow) and classifies it at kNodesPerBlock nodes, the token staying in
 // registers.  Each wave packs its 64 results per node with a ballot into two
-// mask words of the rank-space bitsets.  With LDS = true the automaton tables
-// are first copied into shared memory.
-template <bool LDS>
+// mask words of the rank-space bitsets.  The automaton tables (as many node
+// headers as `n_near`) are first copied into shared memory.
 __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
-    DevTables tab, int32_t n_nodes_total, int32_t n_rows_tab, int32_t n_alts, DevVocab voc, int32_t node0,
-    int32_t n_nodes, uint32_t* __restrict__ acc_rank, uint32_t* __restrict__ unc_rank, OverflowLog* log,
-    uint32_t seq) {
+    DevTables tab, int32_t n_near, DevVocab voc, int32_t node0, int32_t n_nodes, uint32_t* __restrict__ acc_rank,
+    uint32_t* __restrict__ unc_rank, uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
+    OverflowLog* log, uint32_t seq) {
   extern __shared__ __align__(16) unsigned char smem[];
-  DevTables T = tab;
-  if (LDS) {
-    uint2* s_hdr = reinterpret_cast<uint2*>(smem);
-    uint32_t* s_alts = reinterpret_cast<uint32_t*>(s_hdr + n_nodes_total);
-    uint16_t* s_rows = reinterpret_cast<uint16_t*>(s_alts + n_alts);
-    uint8_t* s_cls = reinterpret_cast<uint8_t*>(s_rows + (size_t)n_rows_tab * tab.n_cls);
-    for (int k = threadIdx.x; k < n_nodes_total; k += kClassifyThreads) s_hdr[k] = tab.hdr[k];
-    for (int k = threadIdx.x; k < n_alts; k += kClassifyThreads) s_alts[k] = tab.alts[k];
-    for (int k = threadIdx.x; k < n_rows_tab * tab.n_cls; k += kClassifyThreads) s_rows[k] = tab.rows[k];
-    for (int k = threadIdx.x; k < 256; k += kClassifyThreads) s_cls[k] = tab.cls[k];
-    __syncthreads();
-    T.hdr = s_hdr;
-    T.alts = s_alts;
-    T.rows = s_rows;
-    T.cls = s_cls;
-  }
+  const CompactTab T{stage_tables(tab, n_near, smem, kClassifyThreads)};
+  __syncthreads();
   const int32_t r = blockIdx.x * kClassifyThreads + threadIdx.x;
   const bool live_lane = r < voc.V;
   uint4 tk = make_uint4(0, 0, 0, 0);
@@ -69,11 +96,12 @@ __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
   for (int32_t k = n_begin; k < n_end; ++k) {
     int res = kReject;
     if (live_lane && len > 0) {
-      res = walk_token<true>(T, tk, ext, len, (uint32_t)(node0 + k), nullptr, 1u);
+      res = walk_token<true>(T, tk, ext, len, (uint32_t)(node0 + k), nullptr, 1u, nullptr, T.follow_of(node0 + k));
       if (res == kOverflow) { record_overflow(log, seq, (uint32_t)k, (uint32_t)r); res = kReject; }
     }
     const unsigned long long a = __ballot(res == kAccept);
     const unsigned long long u = __ballot(res == kUncertain);
+    const unsigned long long p = __ballot(res == kUncertainPlain);
     if ((threadIdx.x & 63) == 0 && word < voc.WR) {
       uint32_t* pa = acc_rank + (size_t)k * voc.WR + word;
       uint32_t* pu = unc_rank + (size_t)k * voc.WR + word;
@@ -81,6 +109,12 @@ __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
       pa[1] = (uint32_t)(a >> 32);
       pu[0] = (uint32_t)u;
       pu[1] = (uint32_t)(u >> 32);
+      if (plain_rank) {
+        uint32_t* pp = plain_rank + (size_t)k * voc.WR + word;
+        pp[0] = (uint32_t)p;
+        pp[1] = (uint32_t)(p >> 32);
+      }
+      if (p) atomicAdd(&plain_count[node0 + k], (uint32_t)__popcll(p));
     }
   }
 }
@@ -138,7 +172,7 @@ __global__ void count_uncertain_kernel(DevVocab voc, const uint32_t* __restrict_
 }
 
 __global__ void list_uncertain_kernel(DevVocab voc, const uint32_t* __restrict__ unc_id, const uint32_t* __restrict__ off,
-                                      uint16_t* __restrict__ list) {
+                                      uint32_t* __restrict__ list) {
   __shared__ uint32_t s[kChunkWords];
   const size_t node = blockIdx.y;
   const int32_t w = blockIdx.x * kChunkWords + threadIdx.x;
@@ -156,12 +190,65 @@ __global__ void list_uncertain_kernel(DevVocab voc, const uint32_t* __restrict__
   while (bits) {
     const uint32_t b = __ffs(bits) - 1;
     bits &= bits - 1;
-    list[pos++] = (uint16_t)(threadIdx.x * 32 + b);
+    list[pos++] = threadIdx.x * 32 + b;
+  }
+}
+
+// One workgroup per (chunk, node) list: every entry's token is walked once
+// more from the node to find where it leaves the node's frame (the walk reads
+// the tables from global memory: most lists are empty or short, staging would
+// cost more), then the list is sorted by the number of bytes left after that
+// position, so that neighbouring lanes of the fill kernel get walks of
+// similar length.
+constexpr int kAnnotateThreads = 256;
+__global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTables tab, DevVocab voc, int32_t node0,
+                                                                          const uint32_t* __restrict__ off,
+                                                                          uint32_t* __restrict__ list) {
+  __shared__ uint32_t seg[kChunkTokens];
+  __shared__ uint32_t bucket[16];
+  const int32_t node = node0 + blockIdx.y, chunk = blockIdx.x;
+  const uint32_t j0 = off[(size_t)node * (voc.n_chunk + 1) + chunk], j1 = off[(size_t)node * (voc.n_chunk + 1) + chunk + 1];
+  const uint32_t n = j1 - j0;
+  if (n == 0) return;
+  if (threadIdx.x < 16) bucket[threadIdx.x] = 0u;
+  __syncthreads();
+  const CompactTab T{stage_tables(tab, 0, nullptr, kAnnotateThreads)};
+  for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
+    const uint32_t lid = list[j0 + e] & 0xFFFu;
+    const int32_t id = chunk * kChunkTokens + (int32_t)lid;
+    const uint4 tk = voc.tok_by_id[id];
+    int len = (int)(tk.w >> 24);
+    const uint8_t* ext = voc.bytes;
+    if (len >= 15) {
+      ext = voc.bytes + voc.off_by_id[id];
+      if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
+    }
+    uint32_t exits = 0;
+    const int res = walk_token<true>(T, tk, ext, len, (uint32_t)node, nullptr, 1u, nullptr, T.follow_of(node), 0, &exits);
+    uint32_t meta = kEntryFullWalk, pos = 0;
+    if (res != kOverflow && exits != 0u && (exits & (exits - 1u)) == 0u && !(exits & 0x8000u)) {
+      meta = __ffs(exits) - 1;  // the single exit position, 0..14
+      pos = meta;
+    }
+    const uint32_t key_byte = token_byte(tk, ext, (int)pos);
+    const uint32_t rem = min(15, len - (int)pos);
+    seg[e] = lid | (meta << 12) | (key_byte << 16) | (rem << 24);
+    atomicAdd(&bucket[rem], 1u);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {  // exclusive scan of the 16 bucket sizes
+    uint32_t run = 0;
+    for (int k = 0; k < 16; ++k) { const uint32_t c = bucket[k]; bucket[k] = run; run += c; }
+  }
+  __syncthreads();
+  for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
+    const uint32_t v = seg[e];
+    list[j0 + atomicAdd(&bucket[(v >> 24) & 15u], 1u)] = v;
   }
 }
 
 __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ items, int32_t n_items,
-                                     uint32_t* acc_rank, uint32_t* unc_rank) {
+                                     uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank) {
   const int32_t k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k >= n_items) return;
   const size_t node = items[3 * k];
@@ -171,131 +258,243 @@ __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ 
   uint32_t* pu = unc_rank + node * voc.WR + (r >> 5);
   if (cls == (uint32_t)kAccept) atomicOr(pa, bit); else atomicAnd(pa, ~bit);
   if (cls == (uint32_t)kUncertain) atomicOr(pu, bit); else atomicAnd(pu, ~bit);
+  if (plain_rank) {
+    uint32_t* pp = plain_rank + node * voc.WR + (r >> 5);
+    if (cls == (uint32_t)kUncertainPlain) atomicOr(pp, bit); else atomicAnd(pp, ~bit);
+  }
 }
 
 // ---------------------------------------------------------------- kernel (b)
-constexpr int kFillThreads = 256;
+constexpr int kFillThreads = 1024;
+constexpr int kFillMaxChunks = 24;              // chunks of 4096 token ids one workgroup may own
+constexpr int kFillQueue = 4096;                // survivors walked per round
+constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
 
-// One workgroup owns the 128 mask words of one (request, chunk of 4096 token
-// ids): it ORs the accepted bitsets of the tops of the request's stacks
-// (Algorithm 1: union over parallel stacks), then walks that chunk's
-// context-dependent tokens against each full stack and ORs in the survivors
-// with LDS atomics, adds the stop tokens, and stores the words once,
-// coalesced.  No global atomics, no second pass.
+// One workgroup of 16 waves serves one request and a contiguous range of its
+// chunks of 4096 token ids (the launch has about two workgroups per compute
+// unit).  Once per workgroup the request's automaton tables and live stacks
+// are copied into LDS; from then on a step of a token walk costs LDS lookups
+// only.  The workgroup owns its mask words in LDS:
+//   1. every word = OR of the accepted bitsets of the tops of all stacks
+//      (Algorithm 1: the result is the union over the parallel stacks);
+//   2. per stack, the context-dependent lists of its chunks are read once,
+//      coalesced; a token whose first byte cannot be consumed from the stack
+//      (a 256-bit set the host packed next to the stack) cannot be allowed -
+//      an exact test that needs only the list entry; the survivors are
+//      compacted into an LDS queue (one LDS atomic per wave);
+//   3. the queue is walked with all lanes busy; allowed tokens are ORed into
+//      the words with LDS atomics;
+//   4. the stop tokens are added and the words stored once, coalesced.
+// No global atomics, no second pass over the mask.
 // COUNT = true additionally sums the automaton steps of all walks into
 // *step_counter (instrumentation for the benchmark; never used on the hot path).
 template <bool COUNT>
 __global__ __launch_bounds__(kFillThreads) void fill_kernel(const RowDesc* __restrict__ rows,
-                                                            const StackDesc* __restrict__ stacks,
+                                                            const uint32_t* __restrict__ stack_hdrs,
                                                             const uint16_t* __restrict__ frames, DevVocab voc,
                                                             uint32_t* __restrict__ out, OverflowLog* log, uint32_t seq,
                                                             unsigned long long* step_counter) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ uint32_t words[kFillMaxChunks * kChunkWords];
+  __shared__ uint32_t queue[kFillQueue];     // (chunk - c0) << 16 | exit position << 12 | local id
+  __shared__ uint16_t live_lds[kFillFramesLds];
+  __shared__ uint32_t first_ok[16];          // 2 x 256 bits: bytes consumable from the current stack / from it
+                                             // without its top frame
+  __shared__ uint32_t queue_n;
   unsigned long long my_steps = 0;
-  __shared__ uint32_t words[kChunkWords];
-  const int32_t b = blockIdx.y, chunk = blockIdx.x;
-  const int32_t w0 = chunk * kChunkWords;
-  const int32_t nw = min(kChunkWords, voc.W - w0);
+  const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
+  const int32_t b = blockIdx.y;
+  // this workgroup's chunks [c0, c1)
+  const int32_t c0 = (int32_t)(((int64_t)blockIdx.x * voc.n_chunk) / gridDim.x);
+  const int32_t c1 = (int32_t)(((int64_t)(blockIdx.x + 1) * voc.n_chunk) / gridDim.x);
+  const int32_t w_begin = c0 * kChunkWords;
+  const int32_t n_words = min(c1 * kChunkWords, voc.W) - w_begin;
   const RowDesc rd = rows[b];
-  if (threadIdx.x < kChunkWords) words[threadIdx.x] = 0u;
-  __syncthreads();
-  if (rd.cache != nullptr) {
-    const DevCache C = *rd.cache;
-    for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-      const StackDesc sd = stacks[rd.stack_begin + s];
-      const uint16_t* live = frames + sd.frame_off;
-      const uint32_t top = live[sd.depth - 1];
-      if ((int)threadIdx.x < nw) words[threadIdx.x] |= C.acc[(size_t)top * voc.W + w0 + threadIdx.x];
-      __syncthreads();
-      const uint32_t* po = C.unc_off + (size_t)top * (voc.n_chunk + 1) + chunk;
-      const uint32_t j0 = po[0], j1 = po[1];
-      for (uint32_t j = j0 + threadIdx.x; j < j1; j += kFillThreads) {
-        const uint32_t lid = C.unc_list[j];
-        if ((words[lid >> 5] >> (lid & 31)) & 1u) continue;  // already allowed by another stack
-        const int32_t id = chunk * kChunkTokens + (int32_t)lid;
-        const uint4 tk = voc.tok_by_id[id];
-        int len = (int)(tk.w >> 24);
-        const uint8_t* ext = voc.bytes;
-        if (len >= 15) {
-          ext = voc.bytes + voc.off_by_id[id];
-          if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
-        }
-        uint32_t n_steps = 0;
-        const int res = walk_token<false>(C.tab, tk, ext, len, top, live, sd.depth, COUNT ? &n_steps : nullptr);
-        if (COUNT) my_steps += n_steps;
-        if (res == kAccept) atomicOr(&words[lid >> 5], 1u << (lid & 31));
-        else if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, (uint32_t)id);
+  const bool has_cache = rd.cache != nullptr && rd.n_stacks > 0;
+  const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
+  DevCache C;
+  CompactTab T;
+  uint32_t frame0 = 0, n_frames = 0;
+  if (has_cache) {
+    C = *rd.cache;
+    T.v = stage_tables(C.tab, C.n_near_fill, smem, kFillThreads);
+    const uint32_t* first = stack_hdrs + (size_t)rd.stack_begin * hdr_stride;
+    const uint32_t* last = stack_hdrs + (size_t)(rd.stack_begin + rd.n_stacks - 1) * hdr_stride;
+    frame0 = first[kStackHdrFrames];
+    n_frames = last[kStackHdrFrames] + last[kStackHdrDepth] - frame0;  // the request's stacks are contiguous
+    if (n_frames <= kFillFramesLds)
+      for (uint32_t k = tid; k < n_frames; k += kFillThreads) live_lds[k] = frames[frame0 + k];
+  }
+  const bool frames_in_lds = n_frames <= kFillFramesLds;
+  // 1. accepted words
+  for (int32_t w = tid; w < n_words; w += kFillThreads) {
+    uint32_t x = 0u;
+    if (has_cache)
+      for (uint32_t s = 0; s < rd.n_stacks; ++s) {
+        const uint32_t top = stack_hdrs[(size_t)(rd.stack_begin + s) * hdr_stride + kStackHdrTop];
+        x |= C.acc[(size_t)top * voc.W + w_begin + w];
       }
+    words[w] = x;
+  }
+  if (tid == 0) queue_n = 0u;
+  __syncthreads();
+  if (has_cache) {
+    for (uint32_t s = 0; s < rd.n_stacks; ++s) {
+      const uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + s) * hdr_stride;
+      const uint32_t top = sh[kStackHdrTop], depth = sh[kStackHdrDepth];
+      const uint16_t* live = frames_in_lds ? live_lds + (sh[kStackHdrFrames] - frame0) : frames + sh[kStackHdrFrames];
+      if (sh[kStackHdrWords + c1] == sh[kStackHdrWords + c0]) continue;  // nothing listed here (uniform)
+      if (tid < 16) first_ok[tid] = sh[kStackHdrFirst + tid];
       __syncthreads();
+      // rounds of chunks whose lists together fit the queue (one chunk always fits)
+      for (int32_t ca = c0; ca < c1;) {
+        int32_t cb = ca + 1;
+        while (cb < c1 && sh[kStackHdrWords + cb + 1] - sh[kStackHdrWords + ca] <= (uint32_t)kFillQueue) ++cb;
+        // 2. filter + compact
+        for (int32_t chunk = ca; chunk < cb; ++chunk) {
+          const uint32_t j0 = sh[kStackHdrWords + chunk], j1 = sh[kStackHdrWords + chunk + 1];
+          const uint32_t* wchunk = words + (chunk - c0) * kChunkWords;
+          for (uint32_t j = j0 + (tid & ~63u); j < j1; j += kFillThreads) {
+            const uint32_t jj = j + lane;
+            bool keep = false;
+            uint32_t lid = 0, meta = 0;
+            if (jj < j1) {
+              const uint32_t e = C.unc_list[jj];
+              lid = e & 0xFFFu;
+              meta = (e >> 12) & 15u;
+              const uint32_t kb = (e >> 16) & 0xFFu;
+              // the byte at the exit must be consumable below the top frame (or, for a full walk,
+              // the first byte from the whole stack)
+              const uint32_t* ok = first_ok + (meta == kEntryFullWalk ? 0 : 8);
+              keep = ((ok[kb >> 5] >> (kb & 31)) & 1u) && !((wchunk[lid >> 5] >> (lid & 31)) & 1u);
+            }
+            const unsigned long long m = __ballot(keep);
+            if (m) {
+              uint32_t base = 0;
+              if (lane == 0) base = atomicAdd(&queue_n, (uint32_t)__popcll(m));
+              base = __shfl(base, 0, 64);
+              if (keep) queue[base + __popcll(m & ((1ull << lane) - 1ull))] = ((uint32_t)(chunk - c0) << 16) | (meta << 12) | lid;
+            }
+          }
+        }
+        __syncthreads();
+        // 3. walk the survivors
+        const uint32_t nq = queue_n;
+        for (uint32_t q = tid; q < nq; q += kFillThreads) {
+          const uint32_t e = queue[q];
+          const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, cl = e >> 16;
+          const int32_t id = (c0 + (int32_t)cl) * kChunkTokens + (int32_t)lid;
+          const uint4 tk = voc.tok_by_id[id];
+          int len = (int)(tk.w >> 24);
+          const uint8_t* ext = voc.bytes;
+          if (len >= 15) {
+            ext = voc.bytes + voc.off_by_id[id];
+            if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
+          }
+          uint32_t n_steps = 0;
+          // a token with a single exit continues right there, in the frame below the top
+          const int res = (meta == kEntryFullWalk)
+                              ? walk_token<false>(T, tk, ext, len, top, live, depth, COUNT ? &n_steps : nullptr)
+                              : walk_token<false>(T, tk, ext, len, live[depth - 2], live, depth - 1,
+                                                  COUNT ? &n_steps : nullptr, nullptr, (int)meta);
+          if (COUNT) my_steps += n_steps;
+          if (res == kAccept) atomicOr(&words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
+          else if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, (uint32_t)id);
+        }
+        __syncthreads();
+        if (tid == 0) queue_n = 0u;
+        __syncthreads();
+        ca = cb;
+      }
     }
   }
   if (rd.flags & 1u) {
-    for (int32_t k = threadIdx.x; k < voc.n_stop; k += kFillThreads) {
-      const int32_t rel = voc.stop_ids[k] - chunk * kChunkTokens;
-      if (rel >= 0 && rel < nw * 32) atomicOr(&words[rel >> 5], 1u << (rel & 31));
+    for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
+      const int32_t rel = voc.stop_ids[k] - w_begin * 32;
+      if (rel >= 0 && rel < n_words * 32) atomicOr(&words[rel >> 5], 1u << (rel & 31));
     }
-    __syncthreads();
   }
-  if ((int)threadIdx.x < nw) out[(size_t)b * voc.W + w0 + threadIdx.x] = words[threadIdx.x];
+  __syncthreads();
+  for (int32_t w = tid; w < n_words; w += kFillThreads) out[(size_t)b * voc.W + w_begin + w] = words[w];
   if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
 }
 
 // ---------------------------------------------------------------- kernel (c)
 constexpr int kApplyThreads = 256;
+constexpr int kApplyGroups = 8;  // 16-byte groups per thread
 
-// Section 2.1: logits of disallowed tokens become -inf.  One thread owns 16
-// bytes of a logits row (8 bf16/fp16 or 4 fp32 elements) and the matching mask
-// bits.  All allowed: nothing is touched.  None allowed: one 16-byte store of
-// the -inf pattern, no read.  Mixed: read, blend, write.  ESIZE = bytes per
-// element.
+// Section 2.1: logits of disallowed tokens become -inf.  A group is 16 bytes
+// of a logits row (8 bf16/fp16 or 4 fp32 elements) with its mask bits.  All
+// allowed: nothing is touched.  None allowed: one 16-byte store of the -inf
+// pattern, no read.  Mixed: read (all such reads of a thread are issued before
+// its first store), blend, write.  A wave owns a contiguous run
+// of 64 * kApplyGroups groups and walks it 64 groups (1 KiB) at a time, so
+// every store instruction of a wave covers whole cache lines; a thread first
+// fetches the mask bits of all its groups, then issues its stores back to
+// back.  ESIZE = bytes per element.
 template <int ESIZE>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(unsigned char* __restrict__ logits, int64_t row_stride,
                                                               const uint32_t* __restrict__ bitmask, int32_t W_mask,
                                                               int32_t V_logits, int32_t V_mask,
                                                               const int32_t* __restrict__ row_index, uint32_t neg_inf) {
-  constexpr int EPT = 16 / ESIZE;  // elements per thread
+  constexpr int EPT = 16 / ESIZE;            // elements per group
+  constexpr uint32_t kAll = (1u << EPT) - 1u;
   const int32_t j = blockIdx.y;
   const int64_t lrow = row_index ? row_index[j] : j;
-  const int32_t g = blockIdx.x * kApplyThreads + threadIdx.x;
-  const int32_t e0 = g * EPT;
-  if (e0 >= V_logits) return;
-  uint32_t m = 0;
-  if (e0 < V_mask) {
-    m = (bitmask[(size_t)j * W_mask + (e0 >> 5)] >> (e0 & 31)) & ((1u << EPT) - 1u);
-    if (e0 + EPT > V_mask) m &= (1u << (V_mask - e0)) - 1u;
+  const int32_t wave_base = (blockIdx.x * (kApplyThreads / 64) + (threadIdx.x >> 6)) * 64 * kApplyGroups;
+  const int32_t lane = threadIdx.x & 63;
+  const uint32_t* mrow = bitmask + (size_t)j * W_mask;
+  unsigned char* lbase = logits + (size_t)lrow * row_stride * ESIZE;
+  uint32_t m[kApplyGroups];
+#pragma unroll
+  for (int k = 0; k < kApplyGroups; ++k) {
+    const int32_t e0 = (wave_base + k * 64 + lane) * EPT;
+    m[k] = 0u;
+    if (e0 < V_mask && e0 < V_logits) {
+      m[k] = (mrow[e0 >> 5] >> (e0 & 31)) & kAll;
+      if (e0 + EPT > V_mask) m[k] &= (1u << (V_mask - e0)) - 1u;
+    }
   }
-  unsigned char* p = logits + ((size_t)lrow * row_stride + e0) * ESIZE;
-  if (e0 + EPT <= V_logits) {
-    if (m == (1u << EPT) - 1u) return;
-    uint4 v;
-    if (ESIZE == 2) {
-      const uint32_t two = neg_inf | (neg_inf << 16);
-      if (m == 0) v = make_uint4(two, two, two, two);
-      else {
-        v = *reinterpret_cast<const uint4*>(p);
+  const uint32_t two = neg_inf | (neg_inf << 16);
+  // mixed groups need their old contents: fetch them all before the first store
+  uint4 old[kApplyGroups];
+#pragma unroll
+  for (int k = 0; k < kApplyGroups; ++k) {
+    const int32_t e0 = (wave_base + k * 64 + lane) * EPT;
+    old[k] = make_uint4(0, 0, 0, 0);
+    if (e0 + EPT <= V_logits && m[k] != 0u && m[k] != kAll)
+      old[k] = *reinterpret_cast<const uint4*>(lbase + (size_t)e0 * ESIZE);
+  }
+#pragma unroll
+  for (int k = 0; k < kApplyGroups; ++k) {
+    const int32_t e0 = (wave_base + k * 64 + lane) * EPT;
+    if (e0 >= V_logits) continue;
+    unsigned char* p = lbase + (size_t)e0 * ESIZE;
+    const uint32_t mk = m[k];
+    if (e0 + EPT <= V_logits) {
+      if (mk == kAll) continue;
+      uint4 v = old[k];
+      if (ESIZE == 2) {
         uint32_t* q = reinterpret_cast<uint32_t*>(&v);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const uint32_t keep = ((m >> (2 * k)) & 1u ? 0x0000FFFFu : 0u) | ((m >> (2 * k + 1)) & 1u ? 0xFFFF0000u : 0u);
-          q[k] = (q[k] & keep) | (two & ~keep);
+        for (int h = 0; h < 4; ++h) {
+          const uint32_t keep = ((mk >> (2 * h)) & 1u ? 0x0000FFFFu : 0u) | ((mk >> (2 * h + 1)) & 1u ? 0xFFFF0000u : 0u);
+          q[h] = (q[h] & keep) | (two & ~keep);
         }
+      } else {
+        if (!(mk & 1u)) v.x = neg_inf;
+        if (!(mk & 2u)) v.y = neg_inf;
+        if (!(mk & 4u)) v.z = neg_inf;
+        if (!(mk & 8u)) v.w = neg_inf;
       }
+      *reinterpret_cast<uint4*>(p) = v;
     } else {
-      if (m == 0) v = make_uint4(neg_inf, neg_inf, neg_inf, neg_inf);
-      else {
-        v = *reinterpret_cast<const uint4*>(p);
-        if (!(m & 1u)) v.x = neg_inf;
-        if (!(m & 2u)) v.y = neg_inf;
-        if (!(m & 4u)) v.z = neg_inf;
-        if (!(m & 8u)) v.w = neg_inf;
-      }
+      for (int h = 0; e0 + h < V_logits; ++h)
+        if (!((mk >> h) & 1u)) {
+          if (ESIZE == 2) reinterpret_cast<uint16_t*>(p)[h] = (uint16_t)neg_inf;
+          else reinterpret_cast<uint32_t*>(p)[h] = neg_inf;
+        }
     }
-    *reinterpret_cast<uint4*>(p) = v;
-  } else {
-    for (int k = 0; e0 + k < V_logits; ++k)
-      if (!((m >> k) & 1u)) {
-        if (ESIZE == 2) reinterpret_cast<uint16_t*>(p)[k] = (uint16_t)neg_inf;
-        else reinterpret_cast<uint32_t*>(p)[k] = neg_inf;
-      }
   }
 }
 
@@ -319,18 +518,15 @@ __global__ void apply_elementwise_kernel(unsigned char* __restrict__ logits, int
 }  // namespace
 
 // ------------------------------------------------------------------ launchers
-void launch_classify(const DevTables& tab, size_t table_bytes, int32_t n_rows_tab, int32_t n_alts,
-                     int32_t n_nodes_total, const DevVocab& voc, int32_t node0, int32_t n, uint32_t* acc_rank,
-                     uint32_t* unc_rank, OverflowLog* log, uint32_t seq, hipStream_t stream) {
+void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, int32_t n, uint32_t* acc_rank,
+                     uint32_t* unc_rank, uint32_t* plain_rank, uint32_t* plain_count, OverflowLog* log, uint32_t seq,
+                     hipStream_t stream) {
   if (n <= 0 || voc.V <= 0) return;
   dim3 grid((voc.V + kClassifyThreads - 1) / kClassifyThreads, (n + kNodesPerBlock - 1) / kNodesPerBlock);
-  if (table_bytes <= 64 * 1024) {
-    hipLaunchKernelGGL(classify_kernel<true>, grid, dim3(kClassifyThreads), table_bytes, stream, tab, n_nodes_total,
-                       n_rows_tab, n_alts, voc, node0, n, acc_rank, unc_rank, log, seq);
-  } else {
-    hipLaunchKernelGGL(classify_kernel<false>, grid, dim3(kClassifyThreads), 0, stream, tab, n_nodes_total,
-                       n_rows_tab, n_alts, voc, node0, n, acc_rank, unc_rank, log, seq);
-  }
+  const int32_t n_near = near_headers(tab, kClassifyLdsBudget);
+  const size_t lds = n_near > 0 ? (size_t)tab.aux_bytes + (size_t)n_near * 8 : 0;
+  hipLaunchKernelGGL(classify_kernel, grid, dim3(kClassifyThreads), lds, stream, tab, n_near, voc, node0, n, acc_rank,
+                     unc_rank, plain_rank, plain_count, log, seq);
 }
 
 void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* acc_rank, const uint32_t* unc_rank,
@@ -348,26 +544,41 @@ void launch_count_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_
 }
 
 void launch_list_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_id, const uint32_t* off,
-                           uint16_t* list, hipStream_t stream) {
+                           uint32_t* list, hipStream_t stream) {
   if (n <= 0) return;
   hipLaunchKernelGGL(list_uncertain_kernel, dim3(voc.n_chunk, n), dim3(kChunkWords), 0, stream, voc, unc_id, off, list);
 }
 
-void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items, uint32_t* acc_rank,
-                          uint32_t* unc_rank, hipStream_t stream) {
-  if (n_items <= 0) return;
-  hipLaunchKernelGGL(patch_classes_kernel, dim3((n_items + 255) / 256), dim3(256), 0, stream, voc, items, n_items,
-                     acc_rank, unc_rank);
+void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n, const uint32_t* off, uint32_t* list,
+                           hipStream_t stream) {
+  for (int32_t node0 = 0; node0 < n; node0 += 32768) {  // grid.y limit
+    const int32_t nb = std::min(32768, n - node0);
+    hipLaunchKernelGGL(annotate_lists_kernel, dim3(voc.n_chunk, nb), dim3(kAnnotateThreads), 0, stream, tab, voc,
+                       node0, off, list);
+  }
 }
 
-void launch_fill(const RowDesc* rows, const StackDesc* stacks, const uint16_t* frames, int32_t B, const DevVocab& voc,
-                 uint32_t* out, OverflowLog* log, uint32_t seq, unsigned long long* step_counter, hipStream_t stream) {
+void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items, uint32_t* acc_rank,
+                          uint32_t* unc_rank, uint32_t* plain_rank, hipStream_t stream) {
+  if (n_items <= 0) return;
+  hipLaunchKernelGGL(patch_classes_kernel, dim3((n_items + 255) / 256), dim3(256), 0, stream, voc, items, n_items,
+                     acc_rank, unc_rank, plain_rank);
+}
+
+void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames, int32_t B,
+                 const DevVocab& voc, uint32_t* out, OverflowLog* log, uint32_t seq, unsigned long long* step_counter,
+                 hipStream_t stream) {
   if (B <= 0 || voc.n_chunk <= 0) return;
+  // about two workgroups per compute unit; each owns at most kFillMaxChunks chunks of a request
+  int32_t per_row = (2 * 256 + B - 1) / B;
+  per_row = std::max(per_row, (voc.n_chunk + kFillMaxChunks - 1) / kFillMaxChunks);
+  per_row = std::min(per_row, voc.n_chunk);
+  const dim3 grid(per_row, B);
   if (step_counter)
-    hipLaunchKernelGGL(fill_kernel<true>, dim3(voc.n_chunk, B), dim3(kFillThreads), 0, stream, rows, stacks, frames,
+    hipLaunchKernelGGL(fill_kernel<true>, grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
                        voc, out, log, seq, step_counter);
   else
-    hipLaunchKernelGGL(fill_kernel<false>, dim3(voc.n_chunk, B), dim3(kFillThreads), 0, stream, rows, stacks, frames,
+    hipLaunchKernelGGL(fill_kernel<false>, grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
                        voc, out, log, seq, step_counter);
 }
 
@@ -381,7 +592,8 @@ void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logit
   if (aligned) {
     const int ept = 16 / elem_size;
     const int32_t groups = (V_logits + ept - 1) / ept;
-    dim3 grid((groups + kApplyThreads - 1) / kApplyThreads, n_rows);
+    const int32_t per_block = kApplyThreads * kApplyGroups;
+    dim3 grid((groups + per_block - 1) / per_block, n_rows);
     if (elem_size == 2)
       hipLaunchKernelGGL(apply_kernel<2>, grid, dim3(kApplyThreads), 0, stream, p, row_stride, bitmask, W_mask,
                          V_logits, V_mask, row_index, neg_inf);

@@ -17,11 +17,42 @@
 
 namespace xgm {
 
-constexpr uint32_t kNoRowD = 0xFFFF;
-constexpr uint32_t kDeadD = 0xFFFF;
 constexpr uint32_t kAltFlagD = 0x8000;
 constexpr uint32_t kMoveTagD = 0xFFFF;
+constexpr uint32_t kTailTagD = 0xFFFE;
 constexpr uint32_t kLiveBase = 0x8000;  // stack handles >= this refer to the request's live frames
+
+// Table access for the walk: at node n on byte c, how many move / call
+// alternatives are there (k), which (a single packed one, or k entries in the
+// alternatives pool from `base`), may the rule end at n (fin), and can c come
+// right after an instance of n's rule at all (after).
+struct CompactTab {
+  TabView v;
+  XGM_HD void lookup(uint32_t n, uint32_t c, uint32_t& k, uint32_t& single, uint32_t& base, bool& pooled,
+                     uint32_t& fin, uint32_t& after) const {
+    const uint2 h = (n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n];
+    k = 0; single = 0; base = 0; pooled = false;
+    fin = h.y & 1u;
+    after = (v.follow_rules[(h.y >> 16) * 8 + (c >> 5)] >> (c & 31)) & 1u;
+    if (h.y & 2u) {
+      const uint32_t si = v.shapes[(h.x & 0xFFFFu) * v.n_cls + v.cls[c]];
+      if (si != 0xFFu) {
+        const uint32_t a = v.targets[(h.x >> 16) + si];
+        if (a < 0x8000u) { k = 1; single = (0xFFFFu << 16) | a; }
+        else { base = a & 0x7FFFu; k = v.alts[base]; pooled = true; }
+      }
+    } else {
+      const uint32_t lo = h.x & 0xFFu, hi = (h.x >> 8) & 0xFFu;
+      if (c >= lo && c <= hi) { k = 1; single = (0xFFFFu << 16) | (h.x >> 16); }
+    }
+  }
+  XGM_HD uint32_t alt(uint32_t idx) const { return v.alts[idx]; }
+  // the 256-bit FOLLOW set of node n's rule
+  XGM_HD const uint32_t* follow_of(uint32_t n) const {
+    const uint2 h = (n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n];
+    return v.follow_rules + (h.y >> 16) * 8;
+  }
+};
 
 XGM_HD uint32_t token_byte(const uint4& tk, const uint8_t* ext, int i) {
   if (i < 15) {
@@ -37,46 +68,49 @@ XGM_HD uint32_t token_byte(const uint4& tk, const uint8_t* ext, int i) {
 // the byte edge, the rule references whose callee can start with the next
 // byte (push the return node, enter the callee), and - if the node is
 // accepting and a byte was consumed since the last push - the return to the
-// frame below.  Frames pushed during the walk live in a small arena with
+// frame below.  When the walk only has to decide whether the token is allowed
+// (BUILD = false), a return in front of a byte that can never follow the
+// node's rule is not tried at all: it cannot lead anywhere, and leaving it out
+// keeps runs like the inside of a string free of pending alternatives.  Frames pushed during the walk live in a small arena with
 // parent links, so that backing up to a pending alternative never copies a
 // stack (the persistent stack of section 3.3, in miniature).
 //
 // BUILD = true:  nothing is known below the start frame (depth must be 1);
-//                result kAccept / kUncertain / kReject as in section 3.1.
+//                result kAccept / kUncertain / kReject as in section 3.1,
+//                refined by one byte of context (section 3.2 in miniature):
+//                leaving the start frame while bytes remain only counts if
+//                the next byte is in `follow` (256-bit set: the bytes that can
+//                come right after an instance of the start node's rule in any
+//                context); a token that left the frame only in front of other
+//                bytes is kUncertainPlain: context-dependent by section 3.1
+//                alone, rejected in every context by the refinement.
 // BUILD = false: frames below are live[0 .. depth-2]; result kAccept (token
 //                allowed) or kReject.
 // kOverflow: a limit was hit; the caller records the pair.
 // `steps_out` (may be null) receives the number of automaton steps taken.
-template <bool BUILD>
-XGM_HD int walk_token(const DevTables& T, const uint4 tk, const uint8_t* ext, const int len,
+// `i0`: index of the first byte to consume (the walk may start inside the token).
+// `exits_out` (BUILD only, may be null): bit min(k, 15) is set for every
+// position k at which the start frame is left in front of a byte of `follow`.
+template <bool BUILD, class Tab>
+XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const int len,
                       const uint32_t start_node, const uint16_t* live, const uint32_t depth,
-                      uint32_t* steps_out = nullptr) {
+                      uint32_t* steps_out = nullptr, const uint32_t* follow = nullptr, const int i0 = 0,
+                      uint32_t* exits_out = nullptr) {
   if (len > kMaxTokenLen) return kOverflow;
   uint32_t arena[kArenaFrames];  // ret | parent handle << 16
   uint2 choice[kChoicePoints];   // x = node | sp << 16 ; y = i | alt << 8 | top << 16 | f << 24
   uint32_t n = start_node, sp = kLiveBase + depth - 1, f = 1, alt = 0, top = 0, csp = 0;
-  int i = 0;
-  bool left_frame = false;
+  int i = i0;
+  bool left_frame = false, left_frame_follow = false;
   for (int steps = 0;; ++steps) {
     if (steps_out) *steps_out = (uint32_t)steps;
     if (i == len) return kAccept;
     if (steps >= kMaxSteps) return kOverflow;
     const uint32_t c = token_byte(tk, ext, i);
-    const uint2 h = T.hdr[n];
-    const uint32_t lo = h.x & 0xFFu, hi = (h.x >> 8) & 0xFFu, row = h.y & 0xFFFFu;
-    uint32_t k = 0, single = 0, base = 0;
-    bool pooled = false;
-    if (c >= lo && c <= hi) {
-      k = 1;
-      single = (kMoveTagD << 16) | (h.x >> 16);
-    } else if (row != kNoRowD) {
-      const uint32_t a = T.rows[row * T.n_cls + T.cls[c]];
-      if (a != kDeadD) {
-        if (a < kAltFlagD) { k = 1; single = (kMoveTagD << 16) | a; }
-        else { base = a & 0x7FFFu; k = T.alts[base]; pooled = true; }
-      }
-    }
-    const uint32_t can_pop = (h.y >> 16) & f & 1u;
+    uint32_t k, single, base, fin, after;
+    bool pooled;
+    T.lookup(n, c, k, single, base, pooled, fin, after);
+    const uint32_t can_pop = fin & f & (BUILD ? 1u : after);
     const uint32_t total = k + can_pop;
     bool advanced = false;
     if (alt < total) {
@@ -86,9 +120,10 @@ XGM_HD int walk_token(const DevTables& T, const uint4 tk, const uint8_t* ext, co
         choice[csp++] = make_uint2(n | (sp << 16), (uint32_t)i | ((alt + 1) << 8) | (top << 16) | (f << 24));
       }
       if (alt < k) {
-        const uint32_t e = pooled ? T.alts[base + 1 + alt] : single;
+        const uint32_t e = pooled ? T.alt(base + 1 + alt) : single;
         const uint32_t tag = e >> 16, dst = e & 0xFFFFu;
         if (tag == kMoveTagD) { n = dst; ++i; f = 1; }
+        else if (tag == kTailTagD) { n = dst; f = 0; }  // enter the callee, it returns to our parent
         else {
           if (top == kArenaFrames) return kOverflow;
           arena[top] = tag | (sp << 16);
@@ -105,7 +140,13 @@ XGM_HD int walk_token(const DevTables& T, const uint4 tk, const uint8_t* ext, co
       } else {                       // return into a live frame
         const uint32_t d = sp - kLiveBase;
         if (d == 0) {                // nothing below: end of the start frame (BUILD) or of the root rule
-          if (BUILD) left_frame = true;
+          if (BUILD) {
+            left_frame = true;
+            if ((follow[c >> 5] >> (c & 31)) & 1u) {
+              left_frame_follow = true;
+              if (exits_out) *exits_out |= 1u << (i < 15 ? i : 15);
+            }
+          }
           ok = false;
         } else {
           n = live[d - 1];
@@ -125,7 +166,8 @@ XGM_HD int walk_token(const DevTables& T, const uint4 tk, const uint8_t* ext, co
       f = (ch.y >> 24) & 1u;
     }
   }
-  return (BUILD && left_frame) ? kUncertain : kReject;
+  if (BUILD && left_frame) return left_frame_follow ? kUncertain : kUncertainPlain;
+  return kReject;
 }
 
 }  // namespace xgm

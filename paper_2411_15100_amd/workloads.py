@@ -104,13 +104,19 @@ class BatchWalker:
         return picks
 
 
-def uncertain_fraction(walker: BatchWalker, caches) -> np.ndarray:
-    """Per row: mean over its stacks of |context-dependent tokens at the top node| / V."""
+def uncertain_fraction(walker: BatchWalker, caches, plain: bool = False) -> np.ndarray:
+    """Per row: mean over its stacks of |context-dependent tokens at the top node| / V.
+
+    plain=True counts the context-dependent class of section 3.1 alone (what a
+    cache without any context expansion would have to resolve at run time);
+    plain=False what is left after the one-byte narrowing done at build time.
+    """
     out = np.zeros(walker.B)
     for b, (m, c) in enumerate(zip(walker.matchers, caches)):
         n = m.num_stacks()
         if n:
-            out[b] = np.mean([c.num_uncertain(m.stack(s)[-1]) for s in range(n)]) / walker.V
+            tops = [m.stack(s)[-1] for s in range(n)]
+            out[b] = np.mean([c.num_uncertain(t) + (c.num_uncertain_plain(t) if plain else 0) for t in tops]) / walker.V
     return out
 
 
@@ -123,9 +129,10 @@ class ServingWorkload:
     string_heavy=True); state set k: rows walk with the structural-bias policy
     (seed 5000 + k) and freeze at the first step where their deepest stack has
     d_b + 1 frames, d_b ~ U{1..6}, or after 40 steps; then, while the mean
-    fraction of context-dependent tokens at the stack tops is below
-    `min_uncertain`, the quarter of rows with the lowest fraction keeps
-    walking until it reaches a top with a fraction of at least one half.
+    fraction of context-dependent tokens (section 3.1's class, before any
+    narrowing by context) at the stack tops is below `min_uncertain`, the
+    quarter of rows with the lowest fraction keeps walking until it reaches a
+    top with a fraction of at least one half.
     """
 
     def __init__(self, n_rows: int = 128, vocab_size: int = 151936, pool: int = 16, n_logit_buffers: int = 8,
@@ -148,7 +155,7 @@ class ServingWorkload:
             if i % 16 == 15:
                 log(f"built {i + 1} mask caches ({self.build_pairs / max(self.build_kernel_seconds, 1e-9) / 1e9:.1f} G pairs/s in the kernel)")
         self.sets = []
-        fractions = []
+        fractions, narrowed = [], []
         for k in range(pool):
             w = BatchWalker(self.caches, self.vocab, seed=5000 + k, structural_bias=0.35)
             rng = np.random.Generator(np.random.PCG64(7000 + k))
@@ -162,21 +169,26 @@ class ServingWorkload:
                 w.step()
             w.frozen[:] = True
             for _ in range(60):
-                frac = uncertain_fraction(w, self.caches)
+                frac = uncertain_fraction(w, self.caches, plain=True)
                 if frac.mean() >= min_uncertain:
                     break
                 low = np.argsort(frac)[: max(1, n_rows // 4)]
                 w.frozen[low] = False
                 w.step()
-                frac = uncertain_fraction(w, self.caches)
+                frac = uncertain_fraction(w, self.caches, plain=True)
                 for b in low:
                     w.frozen[b] = frac[b] >= 0.5
                 # rows still walking stay unfrozen for the next round
             w.frozen[:] = True
-            fractions.append(uncertain_fraction(w, self.caches))
+            fractions.append(uncertain_fraction(w, self.caches, plain=True))
+            narrowed.append(uncertain_fraction(w, self.caches, plain=False))
             self.sets.append(w)
-            log(f"state set {k}: mean context-dependent fraction {fractions[-1].mean():.3f}")
+            log(f"state set {k}: mean context-dependent fraction {fractions[-1].mean():.3f} "
+                f"(after the one-byte narrowing {narrowed[-1].mean():.3f})")
         self.uncertain_fraction = float(np.mean(fractions))
+        self.uncertain_fraction_narrowed = float(np.mean(narrowed))
+        if self.uncertain_fraction < min_uncertain:
+            raise RuntimeError(f"state pool has only {self.uncertain_fraction:.3f} context-dependent tokens per row")
         self.W = xgm.bitmask_words(vocab_size)
         self.d_mask = torch.zeros((n_rows, self.W), dtype=torch.int32, device="cuda")
         gen = torch.Generator(device="cuda")

@@ -110,7 +110,7 @@ def _classes_for_all_nodes(text, root, vocab, nodes=None):
 
 def test_host_classes_match_oracle_arith_all_nodes():
     vocab = si.make_vocab("arith", 1024, 0)
-    assert _classes_for_all_nodes(si.ARITH_GRAMMAR, "expr", vocab) == {0, 1, 2}
+    assert _classes_for_all_nodes(si.ARITH_GRAMMAR, "expr", vocab) == {0, 1, 2, 4}
 
 
 def test_host_classes_match_oracle_json_all_nodes():
@@ -120,7 +120,7 @@ def test_host_classes_match_oracle_json_all_nodes():
     toks = [b"".join(t) for n in (1, 2) for t in itertools.product(alphabet, repeat=n)]
     toks += [b"true", b"null", b"fals", b'"ab"', b'":', b'",', b'"}', b"\\u00e9", b"1.5e3", b"", b"\xe4\xb8\xad", b"\xe4\xb8"]
     vocab = TinyVocab(toks)
-    assert _classes_for_all_nodes(si.JSON_GRAMMAR, "root", vocab) == {0, 1, 2}
+    assert _classes_for_all_nodes(si.JSON_GRAMMAR, "root", vocab) == {0, 1, 2, 4}
 
 
 def test_host_classes_match_oracle_csql_sample():
@@ -314,9 +314,10 @@ def test_kernel_walk_masks_match_oracle_along_walks(name):
 
 def test_kernel_walk_reports_overflow_instead_of_guessing():
     g = xgm.Grammar(si.ARITH_GRAMMAR, "expr")
+    start = [n for n in range(g.num_nodes) if g.rule_name(g.node_rule(n)) == "expr" and g.node_path(n) == []][0]
     # every "(" pushes three frames (expr, term, factor): 64 frames are used up
-    assert g.debug_walk_host([0], b"(" * 30, True) == 3
-    assert g.debug_classify_host(0, b"(" * 30) == 2
-    assert g.debug_walk_host([0], b"(" * 15, True) == 2
-    assert g.debug_walk_host([0], b"1" * 300, True) == 3     # longer than 255 bytes
-    assert g.debug_classify_host(0, b"1" * 300) == 2
+    assert g.debug_walk_host([start], b"(" * 30, True) == 3
+    assert g.debug_classify_host(start, b"(" * 30) == 2
+    assert g.debug_walk_host([start], b"(" * 15, True) == 2
+    assert g.debug_walk_host([start], b"1" * 300, True) == 3     # longer than 255 bytes
+    assert g.debug_classify_host(start, b"1" * 300) == 2
