@@ -134,8 +134,7 @@ struct xgm_cache {
   std::atomic<int> refs{1};
   xgm_grammar* g = nullptr;
   xgm_vocab* v = nullptr;
-  DevCache host{};           // the struct as uploaded (device pointers)
-  DevCache* d_struct = nullptr;
+  DevCache host{};           // device pointers and table layout
   std::vector<void*> dev_ptrs;
   std::vector<uint32_t> unc_off_host;  // [n_nodes][n_chunk+1]
   std::vector<uint32_t> plain_count;   // [n_nodes] tokens that only section 3.1 calls context-dependent
@@ -227,6 +226,9 @@ struct Context {
   int32_t* last_bitmask = nullptr;
   std::vector<const xgm_matcher*> last_matchers;
   xgm_vocab* last_vocab = nullptr;
+  // scratch of the workgroup planner (kept to avoid per-step allocation)
+  std::vector<uint64_t> plan_entries;
+  int32_t resident_blocks = 0;  // fill workgroups the device holds at once (two per compute unit)
 };
 Context& ctx() {
   static Context c;
@@ -381,7 +383,7 @@ int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t de
   uint4 tk;
   std::memcpy(&tk, row, 16);
   uint32_t steps = 0;
-  const int rc = build ? walk_token<true>(T, tk, h_bytes, n, live[depth - 1], nullptr, 1u, &steps, T.follow_of(live[depth - 1]))
+  const int rc = build ? walk_token<true>(T, tk, h_bytes, n, live[depth - 1], (const uint16_t*)nullptr, 1u, &steps, T.follow_of(live[depth - 1]))
                        : walk_token<false>(T, tk, h_bytes, n, live[depth - 1], live.data(), (uint32_t)depth, &steps);
   if (h_steps) *h_steps = (int32_t)steps;
   return rc;
@@ -415,25 +417,31 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     auto temp = [&](auto* p) { temps.push_back((void*)p); return p; };
     // automaton tables
     static_assert(sizeof(NodeHdr) == sizeof(uint2), "header layout");
-    std::vector<uint2> hdr(N);
-    std::memcpy(hdr.data(), A.hdr.data(), (size_t)N * sizeof(uint2));
+    static_assert(sizeof(NodeHdr) == sizeof(uint2), "header layout");
     DevTables tab{};
-    tab.hdr = keep(slab_upload(hdr));
-    tab.cls = keep(slab_upload(A.cls));
-    tab.shapes = keep(slab_upload(A.shapes));
-    tab.targets = keep(slab_upload(A.targets));
-    tab.alts = keep(slab_upload(A.alts));
-    tab.follow_rules = keep(slab_upload(A.follow_words));
-    tab.n_rules = (int32_t)A.rule_names.size();
-    tab.n_cls = A.n_cls;
-    tab.n_nodes = N;
-    tab.n_shapes = (int32_t)(A.shapes.size() / std::max(1, A.n_cls));
-    tab.n_targets = (int32_t)A.targets.size();
-    tab.n_alts = (int32_t)A.alts.size();
     {
-      const size_t aux = (size_t)tab.n_alts * 4 + (size_t)tab.n_rules * 32 + (size_t)((tab.n_targets + 1) & ~1) * 2 +
-                         (size_t)tab.n_shapes * A.n_cls + 256;
-      tab.aux_bytes = aux <= 24 * 1024 ? (int32_t)aux : 0;
+      std::vector<unsigned char> img;
+      auto put = [&](const void* src, size_t bytes, size_t align) {
+        img.resize((img.size() + align - 1) / align * align, 0);
+        const size_t at = img.size();
+        img.insert(img.end(), (const unsigned char*)src, (const unsigned char*)src + bytes);
+        return (uint32_t)at;
+      };
+      if (A.cls.size() != 256 || A.follow_words.size() != A.rule_names.size() * 8)
+        throw Failure(XGM_ERR_INTERNAL, "cache_build: inconsistent automaton tables");
+      put(A.alts.data(), A.alts.size() * 4, 4);
+      tab.off_follow = put(A.follow_words.data(), A.follow_words.size() * 4, 4);
+      tab.off_targets = put(A.targets.data(), A.targets.size() * 2, 4);
+      tab.off_shapes = put(A.shapes.data(), A.shapes.size(), 4);
+      tab.off_cls = put(A.cls.data(), 256, 4);
+      tab.off_hdr = put(A.hdr.data(), (size_t)N * sizeof(uint2), 16);
+      img.resize((img.size() + 15) / 16 * 16, 0);
+      std::vector<uint4> image(img.size() / 16);
+      std::memcpy(image.data(), img.data(), img.size());
+      tab.image = keep(slab_upload(image));
+      tab.n_rules = (int32_t)A.rule_names.size();
+      tab.n_cls = A.n_cls;
+      tab.n_nodes = N;
     }
 
     uint32_t* acc_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W));
@@ -537,14 +545,11 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     HIP_OK(hipStreamSynchronize(stream));
     cleanup_temps();
 
-    c->host.tab = tab;
+    c->host.tab = staged_for(tab, kFillLdsBudget);
     c->host.acc = acc_id;
     c->host.unc_off = d_off;
     c->host.unc_list = d_list;
     c->host.n_nodes = N;
-    c->host.n_near_fill = near_headers(tab, kFillLdsBudget);
-    c->d_struct = keep(slab_alloc<DevCache>(1));
-    HIP_OK(hipMemcpy(c->d_struct, &c->host, sizeof(DevCache), hipMemcpyHostToDevice));
   } catch (...) {
     cleanup_temps();
     release(c);
@@ -703,11 +708,18 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   const size_t hdr_words = kStackHdrWords + (size_t)n_chunk + 1;
   const size_t off_stacks = (size_t)B * sizeof(RowDesc);
   const size_t off_frames = off_stacks + n_stacks * hdr_words * 4;
-  const size_t bytes = ((off_frames + n_frames * 2 + 63) / 64) * 64;
+  const size_t off_plan = ((off_frames + n_frames * 2 + 63) / 64) * 64;
+  const size_t bytes = off_plan + (size_t)B * n_chunk * sizeof(FillBlock);  // capacity: one block per (row, chunk)
 
   Context& C = ctx();
   std::lock_guard<std::mutex> lock(C.mu);
   OverflowLog* log = overflow_log();
+  if (C.resident_blocks == 0) {
+    int dev = 0, cus = 0;
+    HIP_OK(hipGetDevice(&dev));
+    HIP_OK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    C.resident_blocks = 2 * std::max(1, cus);
+  }
   FillSlot& slot = C.slot[C.next_slot];
   if (slot.used) HIP_OK(hipEventSynchronize(slot.done));
   if (slot.cap < bytes) {
@@ -729,13 +741,16 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     r.pad = 0;
     r.stack_begin = si;
     if (m->terminated) {
-      r.cache = nullptr;
+      r.tab = DevTables{};
+      r.acc = r.unc_list = nullptr;
       r.n_stacks = 0;
       r.flags = 1;
       continue;
     }
     const Automaton& A = m->g->A;
-    r.cache = m->c->d_struct;
+    r.tab = m->c->host.tab;
+    r.acc = m->c->host.acc;
+    r.unc_list = m->c->host.unc_list;
     r.n_stacks = (uint32_t)m->stacks.size();
     r.flags = Engine(&A).can_terminate(m->stacks) ? 1u : 0u;
     for (auto& s : m->stacks) {
@@ -749,15 +764,12 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
       // long as the frames passed so far may all end here - at the frames
       // below; and the same for the stack without its top frame
       for (int below = 0; below < 2; ++below) {
-        std::bitset<256> ok;
+        uint32_t* ok = h + (below ? kStackHdrBelow : kStackHdrFirst);
+        for (int w = 0; w < 8; ++w) ok[w] = 0;
         for (size_t k = s.size() - below; k-- > 0;) {
-          ok |= A.node_first[s[k]];
+          const uint32_t* fw = &A.node_first_words[(size_t)s[k] * 8];
+          for (int w = 0; w < 8; ++w) ok[w] |= fw[w];
           if (!A.node_final[s[k]]) break;
-        }
-        for (int w = 0; w < 8; ++w) {
-          uint32_t bits = 0;
-          for (int k = 0; k < 32; ++k) bits |= (uint32_t)ok.test(w * 32 + k) << k;
-          h[(below ? kStackHdrBelow : kStackHdrFirst) + w] = bits;
         }
       }
       std::memcpy(h + kStackHdrWords, &m->c->unc_off_host[(size_t)top * (n_chunk + 1)], (size_t)(n_chunk + 1) * 4);
@@ -765,11 +777,58 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
       for (int32_t n : s) frames[fi++] = (uint16_t)n;
     }
   }
-  HIP_OK(hipMemcpyAsync(slot.d_buf, slot.h_buf, bytes, hipMemcpyHostToDevice, stream));
+  // Plan the workgroups.  The work that depends on a request's state is the
+  // number of entries in the context-dependent lists of its stack tops.  All
+  // workgroups of a launch should be resident together (two per compute unit),
+  // so the budget of workgroups is shared out in proportion to that number:
+  // every request gets at least as many as its mask words need, and its chunks
+  // are cut where the running entry count passes equal shares.
+  auto* plan = reinterpret_cast<FillBlock*>((char*)slot.h_buf + off_plan);
+  int32_t n_blocks = 0;
+  {
+    const int32_t min_blocks = (n_chunk + kFillMaxChunks - 1) / kFillMaxChunks;
+    const int32_t budget = std::max(B * min_blocks, C.resident_blocks);
+    uint64_t total = 0;
+    std::vector<uint64_t>& row_entries = C.plan_entries;
+    row_entries.assign(B, 0);
+    for (int32_t b = 0; b < B; ++b) {
+      for (uint32_t s = 0; s < rows[b].n_stacks; ++s) {
+        const uint32_t* off = hdrs + (size_t)(rows[b].stack_begin + s) * hdr_words + kStackHdrWords;
+        row_entries[b] += off[n_chunk] - off[0];
+      }
+      total += row_entries[b];
+    }
+    const int32_t spare = budget - B * min_blocks;
+    for (int32_t b = 0; b < B; ++b) {
+      int32_t k = min_blocks;
+      if (total) k += (int32_t)((uint64_t)spare * row_entries[b] / total);
+      k = std::min(k, n_chunk);
+      // cut after chunk c when the entries up to and including c reach the next share
+      const uint32_t* off0 = hdrs + (size_t)rows[b].stack_begin * hdr_words + kStackHdrWords;
+      int32_t c0 = 0, made = 0;
+      for (int32_t c = 0; c < n_chunk; ++c) {
+        bool cut = c + 1 == n_chunk || c + 1 - c0 == kFillMaxChunks;
+        if (!cut && made + 1 < k && row_entries[b]) {
+          uint64_t run = 0;  // entries of chunks 0 .. c
+          for (uint32_t s = 0; s < rows[b].n_stacks; ++s)
+            run += off0[(size_t)s * hdr_words + c + 1] - off0[(size_t)s * hdr_words];
+          cut = run * (uint64_t)k >= row_entries[b] * (uint64_t)(made + 1);
+        }
+        if (cut) {
+          plan[n_blocks++] = FillBlock{(uint32_t)b, (uint32_t)c0 | ((uint32_t)(c + 1) << 16)};
+          c0 = c + 1;
+          ++made;
+        }
+      }
+    }
+  }
+  HIP_OK(hipMemcpyAsync(slot.d_buf, slot.h_buf, off_plan + (size_t)n_blocks * sizeof(FillBlock), hipMemcpyHostToDevice,
+                        stream));
   const uint32_t seq = ++C.seq;
   launch_fill(reinterpret_cast<const RowDesc*>(slot.d_buf),
               reinterpret_cast<const uint32_t*>((char*)slot.d_buf + off_stacks),
-              reinterpret_cast<const uint16_t*>((char*)slot.d_buf + off_frames), B, v->dv,
+              reinterpret_cast<const uint16_t*>((char*)slot.d_buf + off_frames),
+              reinterpret_cast<const FillBlock*>((char*)slot.d_buf + off_plan), n_blocks, v->dv,
               reinterpret_cast<uint32_t*>(d_bitmask), log, seq, d_step_counter, stream);
   HIP_OK(hipGetLastError());
   HIP_OK(hipEventRecord(slot.done, stream));

@@ -627,6 +627,10 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
     for (auto& e : A.bedges[n]) for (int c = e.lo; c <= e.hi; ++c) A.node_first[n].set(c);
     for (auto& e : A.redges[n]) A.node_first[n] |= A.first[e.rule];
   }
+  A.node_first_words.assign((size_t)total * 8, 0u);
+  for (int n = 0; n < total; ++n)
+    for (int c = 0; c < 256; ++c)
+      if (A.node_first[n].test(c)) A.node_first_words[(size_t)n * 8 + (c >> 5)] |= 1u << (c & 31);
 
   // FOLLOW sets: what can be consumed at the return node of some reference to
   // the rule, and, if the referencing rule may end there, what can follow it.

@@ -52,6 +52,7 @@ struct Automaton {
   std::vector<std::string> rule_names;
   std::vector<std::bitset<256>> first;        // per rule: bytes an instance can start with
   std::vector<std::bitset<256>> node_first;   // per node: bytes that can be consumed at the node inside its frame
+  std::vector<uint32_t> node_first_words;     // [n_nodes][8] the same sets as machine words
   std::vector<std::bitset<256>> follow;       // per rule: bytes that can come right after an instance, in any context
   int32_t root_rule = 0;
   std::vector<std::vector<int32_t>> node_path;  // witness path from the rule start

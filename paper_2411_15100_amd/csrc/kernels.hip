@@ -19,45 +19,85 @@ __device__ __forceinline__ void record_overflow(OverflowLog* log, uint32_t seq, 
   log->entry[slot][2] = b;
 }
 
-// Copy a grammar's small tables and its first `n_near` node headers into LDS
-// (all threads of the workgroup call this; a barrier must follow).  With
-// n_near == 0 nothing is copied and the walk reads global memory.
-// LDS layout: [headers][alts][follow sets][targets, padded to 4 bytes][shapes][cls].
-__device__ __forceinline__ TabView stage_tables(const DevTables& tab, int32_t n_near, unsigned char* smem, int nthreads) {
+// Copy the staged part of a grammar's table image (its small tables and its
+// first n_near node headers) into LDS, 16 bytes per load (all threads of the
+// workgroup call this; a barrier must follow).  With stage_bytes == 0 nothing
+// is copied and the walk reads global memory.
+__device__ __forceinline__ TabView stage_tables(const DevTables& tab, unsigned char* smem, int nthreads) {
+  const unsigned char* base = reinterpret_cast<const unsigned char*>(tab.image);
   TabView T;
-  T.hdr_far = tab.hdr;
+  T.hdr_far = reinterpret_cast<const uint2*>(base + tab.off_hdr);
   T.n_cls = tab.n_cls;
-  if (n_near <= 0) {
-    T.hdr_near = tab.hdr;
-    T.n_near = 0;
-    T.cls = tab.cls;
-    T.shapes = tab.shapes;
-    T.targets = tab.targets;
-    T.alts = tab.alts;
-    T.follow_rules = tab.follow_rules;
-    return T;
+  T.n_near = (int32_t)tab.n_near;
+  if (tab.stage_bytes) {
+    uint4* dst = reinterpret_cast<uint4*>(smem);
+    for (uint32_t k = threadIdx.x; k < tab.stage_bytes / 16; k += nthreads) dst[k] = tab.image[k];
+    base = smem;
   }
-  uint2* s_hdr = reinterpret_cast<uint2*>(smem);
-  uint32_t* s_alts = reinterpret_cast<uint32_t*>(s_hdr + n_near);
-  uint32_t* s_follow = s_alts + tab.n_alts;
-  uint16_t* s_targets = reinterpret_cast<uint16_t*>(s_follow + tab.n_rules * 8);
-  uint8_t* s_shapes = reinterpret_cast<uint8_t*>(s_targets + ((tab.n_targets + 1) & ~1));
-  uint8_t* s_cls = s_shapes + tab.n_shapes * tab.n_cls;
-  for (int k = threadIdx.x; k < n_near; k += nthreads) s_hdr[k] = tab.hdr[k];
-  for (int k = threadIdx.x; k < tab.n_alts; k += nthreads) s_alts[k] = tab.alts[k];
-  for (int k = threadIdx.x; k < tab.n_rules * 8; k += nthreads) s_follow[k] = tab.follow_rules[k];
-  for (int k = threadIdx.x; k < tab.n_targets; k += nthreads) s_targets[k] = tab.targets[k];
-  for (int k = threadIdx.x; k < tab.n_shapes * tab.n_cls; k += nthreads) s_shapes[k] = tab.shapes[k];
-  for (int k = threadIdx.x; k < 256; k += nthreads) s_cls[k] = tab.cls[k];
-  T.hdr_near = s_hdr;
-  T.n_near = n_near;
-  T.cls = s_cls;
-  T.shapes = s_shapes;
-  T.targets = s_targets;
-  T.alts = s_alts;
-  T.follow_rules = s_follow;
+  T.hdr_near = reinterpret_cast<const uint2*>(base + tab.off_hdr);
+  T.alts = reinterpret_cast<const uint32_t*>(base);
+  T.follow_rules = reinterpret_cast<const uint32_t*>(base + tab.off_follow);
+  T.targets = reinterpret_cast<const uint16_t*>(base + tab.off_targets);
+  T.shapes = base + tab.off_shapes;
+  T.cls = base + tab.off_cls;
   return T;
 }
+
+// The same table access as CompactTab, for tables staged by stage_tables():
+// the pointers carry their address space, so that a lookup is a handful of
+// LDS reads (a pointer that may point to LDS or to global memory would make
+// every one of them a much slower flat access).
+#define XGM_LDS __attribute__((address_space(3)))
+#define XGM_GLOBAL __attribute__((address_space(1)))
+struct LdsTab {
+  const XGM_LDS unsigned char* base;  // the staged image
+  const XGM_GLOBAL unsigned long long* hdr_far;  // all headers (uint2 each), global memory
+  uint32_t n_near, n_cls, off_follow, off_targets, off_shapes, off_cls, off_hdr;
+  __device__ __forceinline__ LdsTab(const DevTables& t, unsigned char* smem)
+      : base((const XGM_LDS unsigned char*)smem),
+        hdr_far((const XGM_GLOBAL unsigned long long*)(reinterpret_cast<const unsigned char*>(t.image) + t.off_hdr)),
+        n_near(t.n_near), n_cls((uint32_t)t.n_cls), off_follow(t.off_follow), off_targets(t.off_targets),
+        off_shapes(t.off_shapes), off_cls(t.off_cls), off_hdr(t.off_hdr) {}
+  __device__ __forceinline__ uint2 header(uint32_t n) const {
+    unsigned long long h;  // one 8-byte read
+    if (n < n_near) h = *(const XGM_LDS unsigned long long*)(base + off_hdr + n * 8u);
+    else h = hdr_far[n];
+    return make_uint2((uint32_t)h, (uint32_t)(h >> 32));
+  }
+  __device__ __forceinline__ void lookup(uint32_t n, uint32_t c, uint32_t& k, uint32_t& single, uint32_t& base_out,
+                                         bool& pooled, uint32_t& fin, uint32_t& after) const {
+    const uint2 h = header(n);
+    k = 0; single = 0; base_out = 0; pooled = false;
+    fin = h.y & 1u;
+    after = (*(const XGM_LDS uint32_t*)(base + off_follow + ((h.y >> 16) * 8u + (c >> 5)) * 4u) >> (c & 31)) & 1u;
+    if (h.y & 2u) {
+      const uint32_t cl = base[off_cls + c];
+      const uint32_t si = base[off_shapes + (h.x & 0xFFFFu) * n_cls + cl];
+      if (si != 0xFFu) {
+        const uint32_t a = *(const XGM_LDS uint16_t*)(base + off_targets + ((h.x >> 16) + si) * 2u);
+        if (a < 0x8000u) { k = 1; single = (0xFFFFu << 16) | a; }
+        else { base_out = a & 0x7FFFu; k = alt(base_out); pooled = true; }
+      }
+    } else {
+      const uint32_t lo = h.x & 0xFFu, hi = (h.x >> 8) & 0xFFu;
+      if (c >= lo && c <= hi) { k = 1; single = (0xFFFFu << 16) | (h.x >> 16); }
+    }
+  }
+  __device__ __forceinline__ uint32_t alt(uint32_t idx) const { return *(const XGM_LDS uint32_t*)(base + idx * 4u); }
+  // generic pointer to the 256-bit FOLLOW set of node n's rule (read on the rare exit from the start frame)
+  __device__ __forceinline__ const uint32_t* follow_of(uint32_t n) const {
+    return (const uint32_t*)(const XGM_LDS uint32_t*)(base + off_follow + (header(n).y >> 16) * 32u);
+  }
+};
+
+// The live frames of a request for the fill kernel: the topmost ones in LDS,
+// deeper ones (stacks deeper than the LDS window) in global memory.
+struct LiveView {
+  const XGM_LDS uint16_t* lds;       // frames [lo, ..) of this stack
+  const XGM_GLOBAL uint16_t* glob;   // all frames of this stack
+  uint32_t lo;
+  __device__ __forceinline__ uint32_t operator[](uint32_t k) const { return k >= lo ? lds[k - lo] : glob[k]; }
+};
 
 // ---------------------------------------------------------------- kernel (a)
 constexpr int kClassifyThreads = 256;
@@ -69,13 +109,12 @@ constexpr int kNodesPerBlock = 16;
 // registers.  Each wave packs its 64 results per node with a ballot into two
 // mask words of the rank-space bitsets.  The automaton tables (as many node
 // headers as `n_near`) are first copied into shared memory.
-__global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
-    DevTables tab, int32_t n_near, DevVocab voc, int32_t node0, int32_t n_nodes, uint32_t* __restrict__ acc_rank,
-    uint32_t* __restrict__ unc_rank, uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
-    OverflowLog* log, uint32_t seq) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  const CompactTab T{stage_tables(tab, n_near, smem, kClassifyThreads)};
-  __syncthreads();
+template <class Tab>
+__device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc, int32_t node0, int32_t n_nodes,
+                                              uint32_t* __restrict__ acc_rank, uint32_t* __restrict__ unc_rank,
+                                              uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
+                                              OverflowLog* log, uint32_t seq) {
+
   const int32_t r = blockIdx.x * kClassifyThreads + threadIdx.x;
   const bool live_lane = r < voc.V;
   uint4 tk = make_uint4(0, 0, 0, 0);
@@ -96,7 +135,7 @@ __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
   for (int32_t k = n_begin; k < n_end; ++k) {
     int res = kReject;
     if (live_lane && len > 0) {
-      res = walk_token<true>(T, tk, ext, len, (uint32_t)(node0 + k), nullptr, 1u, nullptr, T.follow_of(node0 + k));
+      res = walk_token<true>(T, tk, ext, len, (uint32_t)(node0 + k), (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node0 + k));
       if (res == kOverflow) { record_overflow(log, seq, (uint32_t)k, (uint32_t)r); res = kReject; }
     }
     const unsigned long long a = __ballot(res == kAccept);
@@ -117,6 +156,20 @@ __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
       if (p) atomicAdd(&plain_count[node0 + k], (uint32_t)__popcll(p));
     }
   }
+}
+
+
+__global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
+    DevTables tab, DevVocab voc, int32_t node0, int32_t n_nodes, uint32_t* __restrict__ acc_rank,
+    uint32_t* __restrict__ unc_rank, uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
+    OverflowLog* log, uint32_t seq) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const TabView v = stage_tables(tab, smem, kClassifyThreads);
+  __syncthreads();
+  if (tab.stage_bytes)  // uniform for the launch
+    classify_body(LdsTab(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
+  else
+    classify_body(CompactTab{v}, voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
 }
 
 // Rank space -> id space: bit id of the output = bit rank_of_id[id] of the
@@ -212,7 +265,7 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
   if (n == 0) return;
   if (threadIdx.x < 16) bucket[threadIdx.x] = 0u;
   __syncthreads();
-  const CompactTab T{stage_tables(tab, 0, nullptr, kAnnotateThreads)};
+  const CompactTab T{stage_tables(tab, nullptr, kAnnotateThreads)};  // launched with nothing staged
   for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
     const uint32_t lid = list[j0 + e] & 0xFFFu;
     const int32_t id = chunk * kChunkTokens + (int32_t)lid;
@@ -224,7 +277,7 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
       if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
     }
     uint32_t exits = 0;
-    const int res = walk_token<true>(T, tk, ext, len, (uint32_t)node, nullptr, 1u, nullptr, T.follow_of(node), 0, &exits);
+    const int res = walk_token<true>(T, tk, ext, len, (uint32_t)node, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node), 0, &exits);
     uint32_t meta = kEntryFullWalk, pos = 0;
     if (res != kOverflow && exits != 0u && (exits & (exits - 1u)) == 0u && !(exits & 0x8000u)) {
       meta = __ffs(exits) - 1;  // the single exit position, 0..14
@@ -266,156 +319,185 @@ __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ 
 
 // ---------------------------------------------------------------- kernel (b)
 constexpr int kFillThreads = 1024;
-constexpr int kFillMaxChunks = 24;              // chunks of 4096 token ids one workgroup may own
 constexpr int kFillQueue = 4096;                // survivors walked per round
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
 
 // One workgroup of 16 waves serves one request and a contiguous range of its
-// chunks of 4096 token ids (the launch has about two workgroups per compute
-// unit).  Once per workgroup the request's automaton tables and live stacks
-// are copied into LDS; from then on a step of a token walk costs LDS lookups
-// only.  The workgroup owns its mask words in LDS:
+// chunks of 4096 token ids, as planned by the host (FillBlock).  Once per
+// workgroup the request's automaton tables and live stacks are copied into
+// LDS; from then on a step of a token walk costs LDS lookups only.  The
+// workgroup owns its mask words in LDS:
 //   1. every word = OR of the accepted bitsets of the tops of all stacks
 //      (Algorithm 1: the result is the union over the parallel stacks);
 //   2. per stack, the context-dependent lists of its chunks are read once,
-//      coalesced; a token whose first byte cannot be consumed from the stack
-//      (a 256-bit set the host packed next to the stack) cannot be allowed -
-//      an exact test that needs only the list entry; the survivors are
-//      compacted into an LDS queue (one LDS atomic per wave);
+//      coalesced.  An entry names the one byte that decides whether its token
+//      can get anywhere: the byte at which the token leaves the top frame
+//      (tested against the bytes the rest of the stack can consume) or, for a
+//      token that has to be walked from the top, its first byte (tested
+//      against the bytes the whole stack can consume); both 256-bit sets come
+//      from the host with the stack.  The test is exact and needs only the
+//      list entry; survivors are compacted into an LDS queue (one LDS atomic
+//      per wave);
 //   3. the queue is walked with all lanes busy; allowed tokens are ORed into
 //      the words with LDS atomics;
 //   4. the stop tokens are added and the words stored once, coalesced.
 // No global atomics, no second pass over the mask.
 // COUNT = true additionally sums the automaton steps of all walks into
 // *step_counter (instrumentation for the benchmark; never used on the hot path).
+struct FillShared {
+  uint32_t words[kFillMaxChunks * kChunkWords];
+  uint32_t queue[kFillQueue];     // (chunk - c0) << 16 | exit position << 12 | local id
+  uint16_t live[kFillFramesLds];
+  uint32_t first_ok[16];          // 2 x 256 bits: bytes consumable from the current stack / without its top frame
+  uint32_t queue_n;
+};
+
+template <bool COUNT, class Tab>
+__device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b,
+                                           const int32_t c0, const int32_t c1, const uint32_t frame0,
+                                           const bool frames_in_lds,
+                                           const XGM_GLOBAL uint32_t* __restrict__ stack_hdrs,
+                                           const XGM_GLOBAL uint16_t* __restrict__ frames, const DevVocab& voc,
+                                           OverflowLog* log, uint32_t seq, unsigned long long& my_steps) {
+  const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
+  const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
+  const XGM_GLOBAL uint32_t* unc_list = (const XGM_GLOBAL uint32_t*)rd.unc_list;
+  for (uint32_t s = 0; s < rd.n_stacks; ++s) {
+    const XGM_GLOBAL uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + s) * hdr_stride;
+    if (sh[kStackHdrWords + c1] == sh[kStackHdrWords + c0]) continue;  // nothing listed here (uniform)
+    const uint32_t top = sh[kStackHdrTop], depth = sh[kStackHdrDepth];
+    LiveView live;
+    live.lds = (const XGM_LDS uint16_t*)sm.live + (sh[kStackHdrFrames] - frame0);
+    live.glob = frames + sh[kStackHdrFrames];
+    live.lo = frames_in_lds ? 0u : 0xFFFFFFFFu;
+    const uint32_t below = depth >= 2 ? live[depth - 2] : 0u;
+    if (tid < 16) sm.first_ok[tid] = sh[kStackHdrFirst + tid];
+    __syncthreads();
+    // rounds of chunks whose lists together fit the queue (one chunk always fits)
+    for (int32_t ca = c0; ca < c1;) {
+      int32_t cb = ca + 1;
+      while (cb < c1 && sh[kStackHdrWords + cb + 1] - sh[kStackHdrWords + ca] <= (uint32_t)kFillQueue) ++cb;
+      // 2. filter + compact
+      for (int32_t chunk = ca; chunk < cb; ++chunk) {
+        const uint32_t j0 = sh[kStackHdrWords + chunk], j1 = sh[kStackHdrWords + chunk + 1];
+        const uint32_t* wchunk = sm.words + (chunk - c0) * kChunkWords;
+        for (uint32_t j = j0 + (tid & ~63u); j < j1; j += kFillThreads) {
+          const uint32_t jj = j + lane;
+          bool keep = false;
+          uint32_t lid = 0, meta = 0;
+          if (jj < j1) {
+            const uint32_t e = unc_list[jj];
+            lid = e & 0xFFFu;
+            meta = (e >> 12) & 15u;
+            const uint32_t kb = (e >> 16) & 0xFFu;
+            const uint32_t* ok = sm.first_ok + (meta == kEntryFullWalk ? 0 : 8);
+            keep = ((ok[kb >> 5] >> (kb & 31)) & 1u) && !((wchunk[lid >> 5] >> (lid & 31)) & 1u);
+          }
+          const unsigned long long m = __ballot(keep);
+          if (m) {
+            uint32_t base = 0;
+            if (lane == 0) base = atomicAdd(&sm.queue_n, (uint32_t)__popcll(m));
+            base = __shfl(base, 0, 64);
+            if (keep)
+              sm.queue[base + __popcll(m & ((1ull << lane) - 1ull))] = ((uint32_t)(chunk - c0) << 16) | (meta << 12) | lid;
+          }
+        }
+      }
+      __syncthreads();
+      // 3. walk the survivors
+      const uint32_t nq = sm.queue_n;
+      for (uint32_t q = tid; q < nq; q += kFillThreads) {
+        const uint32_t e = sm.queue[q];
+        const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, cl = e >> 16;
+        const int32_t id = (c0 + (int32_t)cl) * kChunkTokens + (int32_t)lid;
+        const uint4 tk = voc.tok_by_id[id];
+        int len = (int)(tk.w >> 24);
+        const uint8_t* ext = voc.bytes;
+        if (len >= 15) {
+          ext = voc.bytes + voc.off_by_id[id];
+          if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
+        }
+        uint32_t n_steps = 0;
+        // a token with a single exit continues right there, in the frame below the top
+        const bool full = meta == kEntryFullWalk;
+        const int res = walk_token<false>(T, tk, ext, len, full ? top : below, live, full ? depth : depth - 1,
+                                          COUNT ? &n_steps : nullptr, (const uint32_t*)nullptr, full ? 0 : (int)meta);
+        if (COUNT) my_steps += n_steps;
+        if (res == kAccept) atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
+        else if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, (uint32_t)id);
+      }
+      __syncthreads();
+      if (tid == 0) sm.queue_n = 0u;
+      __syncthreads();
+      ca = cb;
+    }
+  }
+}
+
+// Two workgroups of 16 waves per compute unit need 8 waves per SIMD: the second
+// launch bound keeps the kernel within the 96 scalar and 64 vector registers
+// per wave that this takes.
 template <bool COUNT>
-__global__ __launch_bounds__(kFillThreads) void fill_kernel(const RowDesc* __restrict__ rows,
-                                                            const uint32_t* __restrict__ stack_hdrs,
-                                                            const uint16_t* __restrict__ frames, DevVocab voc,
+__global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __restrict__ rows,
+                                                            const uint32_t* __restrict__ stack_hdrs_,
+                                                            const uint16_t* __restrict__ frames_,
+                                                            const FillBlock* __restrict__ plan, DevVocab voc,
                                                             uint32_t* __restrict__ out, OverflowLog* log, uint32_t seq,
                                                             unsigned long long* step_counter) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ uint32_t words[kFillMaxChunks * kChunkWords];
-  __shared__ uint32_t queue[kFillQueue];     // (chunk - c0) << 16 | exit position << 12 | local id
-  __shared__ uint16_t live_lds[kFillFramesLds];
-  __shared__ uint32_t first_ok[16];          // 2 x 256 bits: bytes consumable from the current stack / from it
-                                             // without its top frame
-  __shared__ uint32_t queue_n;
+  __shared__ FillShared sm;
+  const XGM_GLOBAL uint32_t* stack_hdrs = (const XGM_GLOBAL uint32_t*)stack_hdrs_;
+  const XGM_GLOBAL uint16_t* frames = (const XGM_GLOBAL uint16_t*)frames_;
   unsigned long long my_steps = 0;
-  const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
-  const int32_t b = blockIdx.y;
-  // this workgroup's chunks [c0, c1)
-  const int32_t c0 = (int32_t)(((int64_t)blockIdx.x * voc.n_chunk) / gridDim.x);
-  const int32_t c1 = (int32_t)(((int64_t)(blockIdx.x + 1) * voc.n_chunk) / gridDim.x);
+  const uint32_t tid = threadIdx.x;
+  const FillBlock blk = plan[blockIdx.x];
+  const int32_t b = (int32_t)blk.row;
+  const int32_t c0 = (int32_t)(blk.c0c1 & 0xFFFFu), c1 = (int32_t)(blk.c0c1 >> 16);  // this workgroup's chunks
   const int32_t w_begin = c0 * kChunkWords;
   const int32_t n_words = min(c1 * kChunkWords, voc.W) - w_begin;
   const RowDesc rd = rows[b];
-  const bool has_cache = rd.cache != nullptr && rd.n_stacks > 0;
+  const bool has_cache = rd.n_stacks > 0;
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
-  DevCache C;
-  CompactTab T;
   uint32_t frame0 = 0, n_frames = 0;
+  TabView tv{};
   if (has_cache) {
-    C = *rd.cache;
-    T.v = stage_tables(C.tab, C.n_near_fill, smem, kFillThreads);
-    const uint32_t* first = stack_hdrs + (size_t)rd.stack_begin * hdr_stride;
-    const uint32_t* last = stack_hdrs + (size_t)(rd.stack_begin + rd.n_stacks - 1) * hdr_stride;
+    tv = stage_tables(rd.tab, smem, kFillThreads);
+    const XGM_GLOBAL uint32_t* first = stack_hdrs + (size_t)rd.stack_begin * hdr_stride;
+    const XGM_GLOBAL uint32_t* last = stack_hdrs + (size_t)(rd.stack_begin + rd.n_stacks - 1) * hdr_stride;
     frame0 = first[kStackHdrFrames];
     n_frames = last[kStackHdrFrames] + last[kStackHdrDepth] - frame0;  // the request's stacks are contiguous
     if (n_frames <= kFillFramesLds)
-      for (uint32_t k = tid; k < n_frames; k += kFillThreads) live_lds[k] = frames[frame0 + k];
+      for (uint32_t k = tid; k < n_frames; k += kFillThreads) sm.live[k] = frames[frame0 + k];
   }
   const bool frames_in_lds = n_frames <= kFillFramesLds;
   // 1. accepted words
+  const XGM_GLOBAL uint32_t* acc = (const XGM_GLOBAL uint32_t*)rd.acc;
   for (int32_t w = tid; w < n_words; w += kFillThreads) {
     uint32_t x = 0u;
-    if (has_cache)
-      for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-        const uint32_t top = stack_hdrs[(size_t)(rd.stack_begin + s) * hdr_stride + kStackHdrTop];
-        x |= C.acc[(size_t)top * voc.W + w_begin + w];
-      }
-    words[w] = x;
+    for (uint32_t s = 0; s < rd.n_stacks; ++s) {
+      const uint32_t top = stack_hdrs[(size_t)(rd.stack_begin + s) * hdr_stride + kStackHdrTop];
+      x |= acc[(size_t)top * voc.W + w_begin + w];
+    }
+    sm.words[w] = x;
   }
-  if (tid == 0) queue_n = 0u;
+  if (tid == 0) sm.queue_n = 0u;
   __syncthreads();
   if (has_cache) {
-    for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-      const uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + s) * hdr_stride;
-      const uint32_t top = sh[kStackHdrTop], depth = sh[kStackHdrDepth];
-      const uint16_t* live = frames_in_lds ? live_lds + (sh[kStackHdrFrames] - frame0) : frames + sh[kStackHdrFrames];
-      if (sh[kStackHdrWords + c1] == sh[kStackHdrWords + c0]) continue;  // nothing listed here (uniform)
-      if (tid < 16) first_ok[tid] = sh[kStackHdrFirst + tid];
-      __syncthreads();
-      // rounds of chunks whose lists together fit the queue (one chunk always fits)
-      for (int32_t ca = c0; ca < c1;) {
-        int32_t cb = ca + 1;
-        while (cb < c1 && sh[kStackHdrWords + cb + 1] - sh[kStackHdrWords + ca] <= (uint32_t)kFillQueue) ++cb;
-        // 2. filter + compact
-        for (int32_t chunk = ca; chunk < cb; ++chunk) {
-          const uint32_t j0 = sh[kStackHdrWords + chunk], j1 = sh[kStackHdrWords + chunk + 1];
-          const uint32_t* wchunk = words + (chunk - c0) * kChunkWords;
-          for (uint32_t j = j0 + (tid & ~63u); j < j1; j += kFillThreads) {
-            const uint32_t jj = j + lane;
-            bool keep = false;
-            uint32_t lid = 0, meta = 0;
-            if (jj < j1) {
-              const uint32_t e = C.unc_list[jj];
-              lid = e & 0xFFFu;
-              meta = (e >> 12) & 15u;
-              const uint32_t kb = (e >> 16) & 0xFFu;
-              // the byte at the exit must be consumable below the top frame (or, for a full walk,
-              // the first byte from the whole stack)
-              const uint32_t* ok = first_ok + (meta == kEntryFullWalk ? 0 : 8);
-              keep = ((ok[kb >> 5] >> (kb & 31)) & 1u) && !((wchunk[lid >> 5] >> (lid & 31)) & 1u);
-            }
-            const unsigned long long m = __ballot(keep);
-            if (m) {
-              uint32_t base = 0;
-              if (lane == 0) base = atomicAdd(&queue_n, (uint32_t)__popcll(m));
-              base = __shfl(base, 0, 64);
-              if (keep) queue[base + __popcll(m & ((1ull << lane) - 1ull))] = ((uint32_t)(chunk - c0) << 16) | (meta << 12) | lid;
-            }
-          }
-        }
-        __syncthreads();
-        // 3. walk the survivors
-        const uint32_t nq = queue_n;
-        for (uint32_t q = tid; q < nq; q += kFillThreads) {
-          const uint32_t e = queue[q];
-          const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, cl = e >> 16;
-          const int32_t id = (c0 + (int32_t)cl) * kChunkTokens + (int32_t)lid;
-          const uint4 tk = voc.tok_by_id[id];
-          int len = (int)(tk.w >> 24);
-          const uint8_t* ext = voc.bytes;
-          if (len >= 15) {
-            ext = voc.bytes + voc.off_by_id[id];
-            if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
-          }
-          uint32_t n_steps = 0;
-          // a token with a single exit continues right there, in the frame below the top
-          const int res = (meta == kEntryFullWalk)
-                              ? walk_token<false>(T, tk, ext, len, top, live, depth, COUNT ? &n_steps : nullptr)
-                              : walk_token<false>(T, tk, ext, len, live[depth - 2], live, depth - 1,
-                                                  COUNT ? &n_steps : nullptr, nullptr, (int)meta);
-          if (COUNT) my_steps += n_steps;
-          if (res == kAccept) atomicOr(&words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
-          else if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, (uint32_t)id);
-        }
-        __syncthreads();
-        if (tid == 0) queue_n = 0u;
-        __syncthreads();
-        ca = cb;
-      }
-    }
+    if (rd.tab.stage_bytes)
+      fill_lists<COUNT>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc, log, seq,
+                        my_steps);
+    else
+      fill_lists<COUNT>(CompactTab{tv}, sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc, log, seq,
+                        my_steps);
   }
   if (rd.flags & 1u) {
     for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
       const int32_t rel = voc.stop_ids[k] - w_begin * 32;
-      if (rel >= 0 && rel < n_words * 32) atomicOr(&words[rel >> 5], 1u << (rel & 31));
+      if (rel >= 0 && rel < n_words * 32) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31));
     }
   }
   __syncthreads();
-  for (int32_t w = tid; w < n_words; w += kFillThreads) out[(size_t)b * voc.W + w_begin + w] = words[w];
+  for (int32_t w = tid; w < n_words; w += kFillThreads) out[(size_t)b * voc.W + w_begin + w] = sm.words[w];
   if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
 }
 
@@ -523,9 +605,8 @@ void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, i
                      hipStream_t stream) {
   if (n <= 0 || voc.V <= 0) return;
   dim3 grid((voc.V + kClassifyThreads - 1) / kClassifyThreads, (n + kNodesPerBlock - 1) / kNodesPerBlock);
-  const int32_t n_near = near_headers(tab, kClassifyLdsBudget);
-  const size_t lds = n_near > 0 ? (size_t)tab.aux_bytes + (size_t)n_near * 8 : 0;
-  hipLaunchKernelGGL(classify_kernel, grid, dim3(kClassifyThreads), lds, stream, tab, n_near, voc, node0, n, acc_rank,
+  const DevTables st = staged_for(tab, kClassifyLdsBudget);
+  hipLaunchKernelGGL(classify_kernel, grid, dim3(kClassifyThreads), st.stage_bytes, stream, st, voc, node0, n, acc_rank,
                      unc_rank, plain_rank, plain_count, log, seq);
 }
 
@@ -553,8 +634,8 @@ void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n,
                            hipStream_t stream) {
   for (int32_t node0 = 0; node0 < n; node0 += 32768) {  // grid.y limit
     const int32_t nb = std::min(32768, n - node0);
-    hipLaunchKernelGGL(annotate_lists_kernel, dim3(voc.n_chunk, nb), dim3(kAnnotateThreads), 0, stream, tab, voc,
-                       node0, off, list);
+    hipLaunchKernelGGL(annotate_lists_kernel, dim3(voc.n_chunk, nb), dim3(kAnnotateThreads), 0, stream,
+                       staged_for(tab, 0), voc, node0, off, list);
   }
 }
 
@@ -565,21 +646,17 @@ void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_
                      acc_rank, unc_rank, plain_rank);
 }
 
-void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames, int32_t B,
-                 const DevVocab& voc, uint32_t* out, OverflowLog* log, uint32_t seq, unsigned long long* step_counter,
-                 hipStream_t stream) {
-  if (B <= 0 || voc.n_chunk <= 0) return;
-  // about two workgroups per compute unit; each owns at most kFillMaxChunks chunks of a request
-  int32_t per_row = (2 * 256 + B - 1) / B;
-  per_row = std::max(per_row, (voc.n_chunk + kFillMaxChunks - 1) / kFillMaxChunks);
-  per_row = std::min(per_row, voc.n_chunk);
-  const dim3 grid(per_row, B);
+void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,
+                 const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log,
+                 uint32_t seq, unsigned long long* step_counter, hipStream_t stream) {
+  if (n_blocks <= 0) return;
+  const dim3 grid(n_blocks);
   if (step_counter)
     hipLaunchKernelGGL(fill_kernel<true>, grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
-                       voc, out, log, seq, step_counter);
+                       plan, voc, out, log, seq, step_counter);
   else
     hipLaunchKernelGGL(fill_kernel<false>, grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
-                       voc, out, log, seq, step_counter);
+                       plan, voc, out, log, seq, step_counter);
 }
 
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,

@@ -22,16 +22,23 @@ constexpr int kChunkTokens = kChunkWords * 32;
 // walk results
 enum : int { kReject = 0, kUncertain = 1, kAccept = 2, kOverflow = 3, kUncertainPlain = 4 };
 
-// automaton tables of one grammar in device memory (see NodeHdr in automaton.hpp)
+// Automaton tables of one grammar in device memory (see NodeHdr in
+// automaton.hpp): one contiguous image, laid out as a workgroup keeps it in
+// LDS, so that staging it is a single copy of 16-byte words:
+//   [0, off_follow)         alts     uint32 pool: count, then count entries (tag << 16 | node)
+//   [off_follow, ..)        follow   [n_rules][8] uint32: bytes that can come right after an instance of the rule
+//   [off_targets, ..)       targets  uint16
+//   [off_shapes, ..)        shapes   [n_shapes][n_cls] uint8
+//   [off_cls, off_cls+256)  cls      byte -> class
+//   [off_hdr, ..)           headers  [n_nodes] uint2: x = lo | hi<<8 | target<<16, y = flags | rule<<16
+// off_hdr is a multiple of 16 and the image is padded to a multiple of 16 bytes.
 struct DevTables {
-  const uint2* hdr;              // [n_nodes] x = lo | hi<<8 | target<<16, y = flags | rule<<16
-  const uint8_t* cls;            // [256] byte -> class
-  const uint8_t* shapes;         // [n_shapes * n_cls]
-  const uint16_t* targets;       // [n_targets]
-  const uint32_t* alts;          // [n_alts] pool: count, then count entries (tag << 16 | node)
-  const uint32_t* follow_rules;  // [n_rules][8] bytes that can come right after an instance of the rule
-  int32_t n_cls, n_nodes, n_shapes, n_targets, n_alts, n_rules;
-  int32_t aux_bytes;             // LDS bytes for everything but the headers; 0 = too big, tables stay in global memory
+  const uint4* image;
+  uint32_t off_follow, off_targets, off_shapes, off_cls, off_hdr;
+  int32_t n_cls, n_nodes, n_rules;
+  // set per kernel by staged_for(): the leading stage_bytes of the image (the
+  // small tables and the first n_near headers) go to LDS; 0 = nothing is staged
+  uint32_t stage_bytes, n_near;
 };
 
 // what the walk reads: the first n_near node headers and the small tables may
@@ -51,11 +58,15 @@ struct TabView {
 // LDS budgets (bytes of dynamic shared memory) for the staged tables
 constexpr int32_t kClassifyLdsBudget = 56 * 1024;
 constexpr int32_t kFillLdsBudget = 40 * 1024;
-// how many leading node headers fit beside the small tables (0: stage nothing)
-inline int32_t near_headers(const DevTables& t, int32_t budget) {
-  if (t.aux_bytes <= 0 || t.aux_bytes + 8 > budget) return 0;
-  const int32_t k = (budget - t.aux_bytes) / 8;
-  return k < t.n_nodes ? k : t.n_nodes;
+constexpr uint32_t kMaxSmallTables = 24 * 1024;  // larger small tables stay in global memory
+// the tables with the staging split for a kernel that has `budget` bytes of LDS for them
+inline DevTables staged_for(DevTables t, int32_t budget) {
+  t.stage_bytes = t.n_near = 0;
+  if (t.off_hdr > kMaxSmallTables || t.off_hdr + 8 > (uint32_t)budget) return t;
+  const uint32_t k = ((uint32_t)budget - t.off_hdr) / 8;
+  t.n_near = k < (uint32_t)t.n_nodes ? k : (uint32_t)t.n_nodes;
+  t.stage_bytes = (t.off_hdr + t.n_near * 8 + 15u) & ~15u;
+  return t;
 }
 
 // vocabulary on the device.  A token row is 16 bytes: bytes 0..14 are the
@@ -79,11 +90,10 @@ struct DevVocab {
 
 // one mask cache on the device
 struct DevCache {
-  DevTables tab;
+  DevTables tab;             // staging split for the fill kernel
   const uint32_t* acc;       // [n_nodes][W] accepted tokens, id space
   const uint32_t* unc_off;   // [n_nodes][n_chunk+1] offsets into unc_list
   const uint32_t* unc_list;  // context-dependent tokens, grouped by (node, chunk); see kEntry*
-  int32_t n_near_fill;       // node headers the fill kernel keeps in LDS
   int32_t n_nodes;
 };
 
@@ -96,12 +106,14 @@ struct DevCache {
 //   bits 24..27  min(15, bytes left after that position): entries of a list are sorted by it
 constexpr uint32_t kEntryFullWalk = 15;
 
-// per-step upload of the live stacks: [RowDesc x B][stack headers][frames]
+// per-step upload of the live stacks: [RowDesc x B][stack headers][frames][FillBlock x n_blocks]
 struct RowDesc {
-  const DevCache* cache;  // null: terminated row (only stop bits)
-  uint32_t stack_begin;   // first stack header of this request
-  uint32_t n_stacks;
-  uint32_t flags;         // bit 0: the text so far is a complete sentence
+  DevTables tab;             // the request's grammar (copied in, so that a workgroup needs no further lookup)
+  const uint32_t* acc;       // DevCache::acc
+  const uint32_t* unc_list;  // DevCache::unc_list
+  uint32_t stack_begin;      // first stack header of this request
+  uint32_t n_stacks;         // 0: terminated row (only stop bits)
+  uint32_t flags;            // bit 0: the text so far is a complete sentence
   uint32_t pad;
 };
 // A stack header is kStackHdrWords + n_chunk + 1 uint32 words:
@@ -113,6 +125,17 @@ struct RowDesc {
 //   (c = 0 .. n_chunk; entry n_chunk is the end of the last list).
 constexpr uint32_t kStackHdrTop = 0, kStackHdrDepth = 1, kStackHdrFrames = 2, kStackHdrFirst = 4, kStackHdrBelow = 12,
                    kStackHdrWords = 20;
+
+// One workgroup of the fill kernel: request `row`, chunks [c0, c1) of its
+// token ids.  The host cuts every request into such ranges of about equal
+// numbers of context-dependent list entries and orders them heaviest first,
+// so that a request in a state with many such tokens is spread over many
+// compute units instead of serialising on a few.
+struct FillBlock {
+  uint32_t row;
+  uint32_t c0c1;  // c0 | c1 << 16
+};
+constexpr int32_t kFillMaxChunks = 24;  // chunks one workgroup may own (its mask words live in LDS)
 
 // pairs whose walk exceeded the limits
 struct OverflowLog {
@@ -146,8 +169,8 @@ void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_
                           uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank, hipStream_t stream);
 // (b) batched mask fill
 // step_counter: null on the hot path; otherwise the counting instantiation is launched
-void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames, int32_t B,
-                 const DevVocab& voc, uint32_t* out, OverflowLog* log, uint32_t seq,
+void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,
+                 const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log, uint32_t seq,
                  unsigned long long* step_counter, hipStream_t stream);
 // (c) apply; returns false if the buffer layout needs the element-wise kernel
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,

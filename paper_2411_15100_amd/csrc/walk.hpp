@@ -54,13 +54,24 @@ struct CompactTab {
   }
 };
 
-XGM_HD uint32_t token_byte(const uint4& tk, const uint8_t* ext, int i) {
+// The first 15 bytes of a token as four plain words (kept in registers: the
+// byte at a run-time index is picked with selects, never through memory).
+struct TokenWords {
+  uint32_t w0, w1, w2, w3;
+  XGM_HD explicit TokenWords(const uint4& tk) : w0(tk.x), w1(tk.y), w2(tk.z), w3(tk.w) {}
+};
+XGM_HD uint32_t token_byte(const TokenWords& t, const uint8_t* ext, int i) {
   if (i < 15) {
-    uint32_t w = (i < 8) ? ((i < 4) ? tk.x : tk.y) : ((i < 12) ? tk.z : tk.w);
-    return (w >> ((i & 3) * 8)) & 0xFFu;
+    // bit masks instead of selects: a select between loaded values invites the
+    // compiler to index a copy in scratch memory
+    const uint32_t m4 = 0u - (((uint32_t)i >> 2) & 1u), m8 = 0u - (((uint32_t)i >> 3) & 1u);
+    const uint32_t lo = (t.w1 & m4) | (t.w0 & ~m4), hi = (t.w3 & m4) | (t.w2 & ~m4);
+    const uint32_t w = (hi & m8) | (lo & ~m8);
+    return (w >> (((uint32_t)i & 3u) * 8u)) & 0xFFu;
   }
   return ext[i];
 }
+XGM_HD uint32_t token_byte(const uint4& tk, const uint8_t* ext, int i) { return token_byte(TokenWords(tk), ext, i); }
 
 // Depth-first walk of one token through the pushdown automaton (section 2.2,
 // Appendix A) from the configuration (node on top, `depth - 1` live frames
@@ -91,12 +102,15 @@ XGM_HD uint32_t token_byte(const uint4& tk, const uint8_t* ext, int i) {
 // `i0`: index of the first byte to consume (the walk may start inside the token).
 // `exits_out` (BUILD only, may be null): bit min(k, 15) is set for every
 // position k at which the start frame is left in front of a byte of `follow`.
-template <bool BUILD, class Tab>
+// `Live` is anything indexable that yields the live frames (a plain pointer,
+// or a view that knows which of them sit in LDS).
+template <bool BUILD, class Tab, class Live>
 XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const int len,
-                      const uint32_t start_node, const uint16_t* live, const uint32_t depth,
+                      const uint32_t start_node, const Live& live, const uint32_t depth,
                       uint32_t* steps_out = nullptr, const uint32_t* follow = nullptr, const int i0 = 0,
                       uint32_t* exits_out = nullptr) {
   if (len > kMaxTokenLen) return kOverflow;
+  const TokenWords tw(tk);
   uint32_t arena[kArenaFrames];  // ret | parent handle << 16
   uint2 choice[kChoicePoints];   // x = node | sp << 16 ; y = i | alt << 8 | top << 16 | f << 24
   uint32_t n = start_node, sp = kLiveBase + depth - 1, f = 1, alt = 0, top = 0, csp = 0;
@@ -106,7 +120,7 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
     if (steps_out) *steps_out = (uint32_t)steps;
     if (i == len) return kAccept;
     if (steps >= kMaxSteps) return kOverflow;
-    const uint32_t c = token_byte(tk, ext, i);
+    const uint32_t c = token_byte(tw, ext, i);
     uint32_t k, single, base, fin, after;
     bool pooled;
     T.lookup(n, c, k, single, base, pooled, fin, after);
