@@ -206,6 +206,7 @@ void vocab_to_device(xgm_vocab* v) {
 // --- process-wide device context: overflow log and the fill staging ring
 struct FillSlot {
   void* h_buf = nullptr;  // pinned
+  void* h_dev = nullptr;  // the same memory as the device addresses it
   void* d_buf = nullptr;
   size_t cap = 0;
   hipEvent_t done = nullptr;
@@ -727,7 +728,8 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     if (slot.d_buf) (void)hipFree(slot.d_buf);
     slot.h_buf = slot.d_buf = nullptr;
     slot.cap = std::max<size_t>(bytes * 2, 1 << 16);
-    HIP_OK(hipHostMalloc(&slot.h_buf, slot.cap, hipHostMallocDefault));
+    HIP_OK(hipHostMalloc(&slot.h_buf, slot.cap, hipHostMallocMapped));
+    HIP_OK(hipHostGetDevicePointer(&slot.h_dev, slot.h_buf, 0));
     HIP_OK(hipMalloc(&slot.d_buf, slot.cap));
   }
   if (!slot.done) HIP_OK(hipEventCreateWithFlags(&slot.done, hipEventDisableTiming));
@@ -822,8 +824,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
       }
     }
   }
-  HIP_OK(hipMemcpyAsync(slot.d_buf, slot.h_buf, off_plan + (size_t)n_blocks * sizeof(FillBlock), hipMemcpyHostToDevice,
-                        stream));
+  launch_upload(slot.h_dev, slot.d_buf, off_plan + (size_t)n_blocks * sizeof(FillBlock), stream);
   const uint32_t seq = ++C.seq;
   launch_fill(reinterpret_cast<const RowDesc*>(slot.d_buf),
               reinterpret_cast<const uint32_t*>((char*)slot.d_buf + off_stacks),

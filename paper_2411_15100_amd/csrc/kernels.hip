@@ -318,6 +318,17 @@ __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ 
 }
 
 // ---------------------------------------------------------------- kernel (b)
+// The per-step stack upload: a plain copy from pinned host memory (which the
+// device reads over the bus) into device memory, as a kernel on the caller's
+// stream.  For the few tens of kilobytes of a step this takes a fraction of
+// the time a copy-engine transfer with its cross-queue synchronisation does.
+constexpr int kUploadThreads = 256;
+__global__ __launch_bounds__(kUploadThreads) void upload_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                                uint32_t n16) {
+  const uint32_t i = blockIdx.x * kUploadThreads + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+
 constexpr int kFillThreads = 1024;
 constexpr int kFillQueue = 4096;                // survivors walked per round
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
@@ -348,7 +359,9 @@ struct FillShared {
   uint32_t words[kFillMaxChunks * kChunkWords];
   uint32_t queue[kFillQueue];     // (chunk - c0) << 16 | exit position << 12 | local id
   uint16_t live[kFillFramesLds];
-  uint32_t first_ok[16];          // 2 x 256 bits: bytes consumable from the current stack / without its top frame
+  uint32_t hdr[kStackHdrWords];   // the current stack's header: top, depth, frame offset, and 2 x 256 bits: the
+                                  // bytes consumable from the stack / from the stack without its top frame
+  uint32_t off[kFillMaxChunks + 1];  // list offsets of the current stack's top for chunks c0 .. c1
   uint32_t queue_n;
 };
 
@@ -362,24 +375,28 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
   const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
   const XGM_GLOBAL uint32_t* unc_list = (const XGM_GLOBAL uint32_t*)rd.unc_list;
+  const uint32_t* first_ok = sm.hdr + kStackHdrFirst;
   for (uint32_t s = 0; s < rd.n_stacks; ++s) {
+    // the stack's header and its list offsets go to LDS with one coalesced read
     const XGM_GLOBAL uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + s) * hdr_stride;
-    if (sh[kStackHdrWords + c1] == sh[kStackHdrWords + c0]) continue;  // nothing listed here (uniform)
-    const uint32_t top = sh[kStackHdrTop], depth = sh[kStackHdrDepth];
+    __syncthreads();  // the previous stack's header is no longer in use
+    if (tid < kStackHdrWords) sm.hdr[tid] = sh[tid];
+    else if (tid - kStackHdrWords <= (uint32_t)(c1 - c0)) sm.off[tid - kStackHdrWords] = sh[kStackHdrWords + c0 + tid - kStackHdrWords];
+    __syncthreads();
+    if (sm.off[c1 - c0] == sm.off[0]) continue;  // nothing listed here (uniform)
+    const uint32_t top = sm.hdr[kStackHdrTop], depth = sm.hdr[kStackHdrDepth];
     LiveView live;
-    live.lds = (const XGM_LDS uint16_t*)sm.live + (sh[kStackHdrFrames] - frame0);
-    live.glob = frames + sh[kStackHdrFrames];
+    live.lds = (const XGM_LDS uint16_t*)sm.live + (sm.hdr[kStackHdrFrames] - frame0);
+    live.glob = frames + sm.hdr[kStackHdrFrames];
     live.lo = frames_in_lds ? 0u : 0xFFFFFFFFu;
     const uint32_t below = depth >= 2 ? live[depth - 2] : 0u;
-    if (tid < 16) sm.first_ok[tid] = sh[kStackHdrFirst + tid];
-    __syncthreads();
     // rounds of chunks whose lists together fit the queue (one chunk always fits)
     for (int32_t ca = c0; ca < c1;) {
       int32_t cb = ca + 1;
-      while (cb < c1 && sh[kStackHdrWords + cb + 1] - sh[kStackHdrWords + ca] <= (uint32_t)kFillQueue) ++cb;
+      while (cb < c1 && sm.off[cb + 1 - c0] - sm.off[ca - c0] <= (uint32_t)kFillQueue) ++cb;
       // 2. filter + compact
       for (int32_t chunk = ca; chunk < cb; ++chunk) {
-        const uint32_t j0 = sh[kStackHdrWords + chunk], j1 = sh[kStackHdrWords + chunk + 1];
+        const uint32_t j0 = sm.off[chunk - c0], j1 = sm.off[chunk + 1 - c0];
         const uint32_t* wchunk = sm.words + (chunk - c0) * kChunkWords;
         for (uint32_t j = j0 + (tid & ~63u); j < j1; j += kFillThreads) {
           const uint32_t jj = j + lane;
@@ -390,7 +407,7 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
             lid = e & 0xFFFu;
             meta = (e >> 12) & 15u;
             const uint32_t kb = (e >> 16) & 0xFFu;
-            const uint32_t* ok = sm.first_ok + (meta == kEntryFullWalk ? 0 : 8);
+            const uint32_t* ok = first_ok + (meta == kEntryFullWalk ? 0 : 8);
             keep = ((ok[kb >> 5] >> (kb & 31)) & 1u) && !((wchunk[lid >> 5] >> (lid & 31)) & 1u);
           }
           const unsigned long long m = __ballot(keep);
@@ -644,6 +661,13 @@ void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_
   if (n_items <= 0) return;
   hipLaunchKernelGGL(patch_classes_kernel, dim3((n_items + 255) / 256), dim3(256), 0, stream, voc, items, n_items,
                      acc_rank, unc_rank, plain_rank);
+}
+
+void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t stream) {
+  const uint32_t n16 = (uint32_t)((bytes + 15) / 16);
+  if (n16 == 0) return;
+  hipLaunchKernelGGL(upload_kernel, dim3((n16 + kUploadThreads - 1) / kUploadThreads), dim3(kUploadThreads), 0, stream,
+                     reinterpret_cast<const uint4*>(pinned_src), reinterpret_cast<uint4*>(dst), n16);
 }
 
 void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,

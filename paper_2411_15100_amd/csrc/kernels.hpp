@@ -167,6 +167,8 @@ void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n,
 // set / clear single bits of rank-space rows: items = (node - node0, rank, class)
 void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items,
                           uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank, hipStream_t stream);
+// copy `bytes` (rounded up to 16; both buffers must hold that) from device-visible pinned host memory
+void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t stream);
 // (b) batched mask fill
 // step_counter: null on the hot path; otherwise the counting instantiation is launched
 void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,
