@@ -176,6 +176,14 @@ int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h
  * h_steps (may be NULL) receives the number of automaton steps taken. */
 int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth,
                         const uint8_t* h_bytes, int32_t n, int32_t build, int32_t* h_steps);
+/* The table the fill kernel builds per stack to test two bytes at once, on the
+ * host: the 256-bit set (8 words: byte c is bit c & 31 of word
+ * c >> 5) of the bytes that can be consumed right after `byte` from the
+ * stack h_stack (depth nodes, bottom first); all zero if `byte` itself cannot
+ * be consumed.  Same source as the kernel's enumerating walk, for tests without
+ * a device.  XGM_ERR_TOO_LARGE if the walk exceeded its limits. */
+int xgm_debug_next_bytes_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth, int32_t byte,
+                              uint32_t* h_set8);
 
 /* ------------------------------------------------------------------- matcher
  * Per-request state: the set of parallel stacks of section 2.2, each a list of

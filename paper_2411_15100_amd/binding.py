@@ -40,6 +40,7 @@ SIGNATURES = {
     "xgm_grammar_node_is_final": (_i32, [_vp, _i32]),
     "xgm_debug_classify_host": (_i32, [_vp, _i32, _cp, _i32]),
     "xgm_debug_walk_host": (_i32, [_vp, _vp, _i32, _cp, _i32, _i32, _vp]),
+    "xgm_debug_next_bytes_host": (_i32, [_vp, _vp, _i32, _i32, _vp]),
     "xgm_cache_build": (_i32, [_vp, _vp, _vp, _pp]),
     "xgm_cache_build_ex": (_i32, [_vp, _vp, _vp, ctypes.c_uint32, _pp]),
     "xgm_cache_num_uncertain_plain": (_i32, [_vp, _i32]),
@@ -207,6 +208,15 @@ class Grammar:
         rc = _check(load_library().xgm_debug_walk_host(self._h, arr.ctypes.data, int(arr.size), data, len(data),
                                                        1 if build else 0, ctypes.byref(steps)))
         return (rc, int(steps.value)) if with_steps else rc
+
+
+    def debug_next_bytes_host(self, stack, byte: int) -> np.ndarray:
+        """256 flags: which bytes can be consumed right after `byte` from the stack."""
+        arr = np.asarray(stack, dtype=np.int32)
+        out = np.zeros(8, dtype=np.uint32)
+        _check(load_library().xgm_debug_next_bytes_host(self._h, arr.ctypes.data, int(arr.size), int(byte),
+                                                        out.ctypes.data))
+        return np.unpackbits(out.view(np.uint8), bitorder="little").astype(bool)
 
 
 class Cache:

@@ -362,6 +362,39 @@ int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h
   API_END
 }
 
+namespace {
+struct HostSetAcc {
+  uint32_t* words;
+  void add(uint32_t w, uint32_t bits) { words[w] |= bits; }
+};
+}  // namespace
+
+int xgm_debug_next_bytes_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth, int32_t byte,
+                              uint32_t* h_set8) {
+  API_BEGIN
+  if (!g || !h_stack || !h_set8 || depth < 1 || depth > XGM_MAX_STACK_DEPTH || byte < 0 || byte > 255)
+    return fail(XGM_ERR_BAD_ARG, "next_bytes_host: bad argument");
+  const Automaton& A = g->A;
+  std::vector<uint16_t> live(depth);
+  for (int32_t k = 0; k < depth; ++k) {
+    if (h_stack[k] < 0 || h_stack[k] >= A.n_nodes) return fail(XGM_ERR_BAD_ARG, "next_bytes_host: node out of range");
+    live[k] = (uint16_t)h_stack[k];
+  }
+  const CompactTab T{TabView{reinterpret_cast<const uint2*>(A.hdr.data()), A.n_nodes,
+                             reinterpret_cast<const uint2*>(A.hdr.data()), A.cls.data(), A.shapes.data(),
+                             A.targets.data(), A.alts.data(), A.follow_words.data(), A.n_cls}};
+  for (int w = 0; w < 8; ++w) h_set8[w] = 0u;
+  HostSetAcc acc{h_set8};
+  const CollectNextBytes<CompactTab, HostSetAcc> collect{&T, A.node_first_words.data(), &acc};
+  const uint8_t b = (uint8_t)byte;
+  const int rc = walk_token<false>(T, make_uint4((uint32_t)byte, 0u, 0u, 1u << 24), &b, 1, live[depth - 1], live.data(),
+                                   (uint32_t)depth, (uint32_t*)nullptr, (const uint32_t*)nullptr, 0, (uint32_t*)nullptr,
+                                   collect);
+  if (rc == kOverflow) return fail(XGM_ERR_TOO_LARGE, "next_bytes_host: the walk exceeded its limits");
+  return XGM_OK;
+  API_END
+}
+
 int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth, const uint8_t* h_bytes,
                         int32_t n, int32_t build, int32_t* h_steps) {
   API_BEGIN
@@ -436,6 +469,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       tab.off_shapes = put(A.shapes.data(), A.shapes.size(), 4);
       tab.off_cls = put(A.cls.data(), 256, 4);
       tab.off_hdr = put(A.hdr.data(), (size_t)N * sizeof(uint2), 16);
+      tab.off_first = put(A.node_first_words.data(), A.node_first_words.size() * 4, 16);
       img.resize((img.size() + 15) / 16 * 16, 0);
       std::vector<uint4> image(img.size() / 16);
       std::memcpy(image.data(), img.data(), img.size());

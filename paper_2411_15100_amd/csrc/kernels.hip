@@ -84,6 +84,7 @@ struct LdsTab {
     }
   }
   __device__ __forceinline__ uint32_t alt(uint32_t idx) const { return *(const XGM_LDS uint32_t*)(base + idx * 4u); }
+  __device__ __forceinline__ bool is_final(uint32_t n) const { return header(n).y & 1u; }
   // generic pointer to the 256-bit FOLLOW set of node n's rule (read on the rare exit from the start frame)
   __device__ __forceinline__ const uint32_t* follow_of(uint32_t n) const {
     return (const uint32_t*)(const XGM_LDS uint32_t*)(base + off_follow + (header(n).y >> 16) * 32u);
@@ -258,6 +259,7 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
                                                                           const uint32_t* __restrict__ off,
                                                                           uint32_t* __restrict__ list) {
   __shared__ uint32_t seg[kChunkTokens];
+  __shared__ uint8_t rem_of[kChunkTokens];
   __shared__ uint32_t bucket[16];
   const int32_t node = node0 + blockIdx.y, chunk = blockIdx.x;
   const uint32_t j0 = off[(size_t)node * (voc.n_chunk + 1) + chunk], j1 = off[(size_t)node * (voc.n_chunk + 1) + chunk + 1];
@@ -280,12 +282,17 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
     const int res = walk_token<true>(T, tk, ext, len, (uint32_t)node, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node), 0, &exits);
     uint32_t meta = kEntryFullWalk, pos = 0;
     if (res != kOverflow && exits != 0u && (exits & (exits - 1u)) == 0u && !(exits & 0x8000u)) {
-      meta = __ffs(exits) - 1;  // the single exit position, 0..14
-      pos = meta;
+      const uint32_t k = __ffs(exits) - 1;  // the single exit position, 0..14
+      const uint32_t suffix = (uint32_t)len - k;
+      if (suffix == 1u) { meta = kEntrySuffix1; pos = k; }
+      else if (suffix == 2u) { meta = kEntrySuffix2; pos = k; }
+      else if (k <= 12u) { meta = k; pos = k; }
     }
-    const uint32_t key_byte = token_byte(tk, ext, (int)pos);
+    const uint32_t b1 = token_byte(tk, ext, (int)pos);
+    const uint32_t b2 = (meta != kEntryFullWalk && (int)pos + 1 < len) ? token_byte(tk, ext, (int)pos + 1) : 0u;
     const uint32_t rem = min(15, len - (int)pos);
-    seg[e] = lid | (meta << 12) | (key_byte << 16) | (rem << 24);
+    seg[e] = lid | (meta << 12) | (b1 << 16) | (b2 << 24);
+    rem_of[e] = (uint8_t)rem;
     atomicAdd(&bucket[rem], 1u);
   }
   __syncthreads();
@@ -295,8 +302,7 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
   }
   __syncthreads();
   for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
-    const uint32_t v = seg[e];
-    list[j0 + atomicAdd(&bucket[(v >> 24) & 15u], 1u)] = v;
+    list[j0 + atomicAdd(&bucket[rem_of[e]], 1u)] = seg[e];
   }
 }
 
@@ -332,6 +338,13 @@ __global__ __launch_bounds__(kUploadThreads) void upload_kernel(const uint4* __r
 constexpr int kFillThreads = 1024;
 constexpr int kFillQueue = 4096;                // survivors walked per round
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
+constexpr uint32_t kFillPairMinEntries = 128;   // lists shorter than this are filtered on one byte only
+
+// accumulates a 256-bit set into 8 LDS words
+struct LdsSetAcc {
+  uint32_t* words;
+  __device__ __forceinline__ void add(uint32_t w, uint32_t bits) { if (bits) atomicOr(words + w, bits); }
+};
 
 // One workgroup of 16 waves serves one request and a contiguous range of its
 // chunks of 4096 token ids, as planned by the host (FillBlock).  Once per
@@ -341,14 +354,17 @@ constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deep
 //   1. every word = OR of the accepted bitsets of the tops of all stacks
 //      (Algorithm 1: the result is the union over the parallel stacks);
 //   2. per stack, the context-dependent lists of its chunks are read once,
-//      coalesced.  An entry names the one byte that decides whether its token
-//      can get anywhere: the byte at which the token leaves the top frame
-//      (tested against the bytes the rest of the stack can consume) or, for a
-//      token that has to be walked from the top, its first byte (tested
-//      against the bytes the whole stack can consume); both 256-bit sets come
-//      from the host with the stack.  The test is exact and needs only the
-//      list entry; survivors are compacted into an LDS queue (one LDS atomic
-//      per wave);
+//      coalesced.  Most entries name the suffix of their token that is left
+//      when the token leaves the top frame, and carry its first two bytes.
+//      Whether the rest of the stack can consume those two bytes is looked up
+//      in a 256 x 256-bit table that the workgroup first computes for the
+//      stack (one lane per first byte: an enumerating walk of that byte
+//      collects the bytes that can follow it); a suffix of one or two bytes
+//      is thereby decided outright, a longer one is dropped or queued.
+//      Entries that need a walk from the top are tested on their first byte
+//      against a 256-bit set the host packed with the stack.  All these tests
+//      are exact and need only the list entry; survivors are compacted into
+//      an LDS queue (one LDS atomic per wave);
 //   3. the queue is walked with all lanes busy; allowed tokens are ORed into
 //      the words with LDS atomics;
 //   4. the stop tokens are added and the words stored once, coalesced.
@@ -362,6 +378,7 @@ struct FillShared {
   uint32_t hdr[kStackHdrWords];   // the current stack's header: top, depth, frame offset, and 2 x 256 bits: the
                                   // bytes consumable from the stack / from the stack without its top frame
   uint32_t off[kFillMaxChunks + 1];  // list offsets of the current stack's top for chunks c0 .. c1
+  uint32_t pair[256 * 8];         // per first byte: the bytes that can follow it, from the stack without its top frame
   uint32_t queue_n;
 };
 
@@ -375,6 +392,7 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
   const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
   const XGM_GLOBAL uint32_t* unc_list = (const XGM_GLOBAL uint32_t*)rd.unc_list;
+  const uint32_t* node_first = reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(rd.tab.image) + rd.tab.off_first);
   const uint32_t* first_ok = sm.hdr + kStackHdrFirst;
   for (uint32_t s = 0; s < rd.n_stacks; ++s) {
     // the stack's header and its list offsets go to LDS with one coalesced read
@@ -390,34 +408,64 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
     live.glob = frames + sm.hdr[kStackHdrFrames];
     live.lo = frames_in_lds ? 0u : 0xFFFFFFFFu;
     const uint32_t below = depth >= 2 ? live[depth - 2] : 0u;
+    // the two-byte table of the stack below the top frame
+    const bool use_pair = depth >= 2 && sm.off[c1 - c0] - sm.off[0] >= kFillPairMinEntries;
+    if (use_pair) {
+      for (uint32_t k = tid; k < 256u * 8u; k += kFillThreads) sm.pair[k] = 0u;
+      __syncthreads();
+      if (tid < 256u && ((first_ok[8 + (tid >> 5)] >> (tid & 31u)) & 1u)) {
+        LdsSetAcc acc{sm.pair + tid * 8u};
+        const CollectNextBytes<Tab, LdsSetAcc> collect{&T, node_first, &acc};
+        const int res = walk_token<false>(T, make_uint4(tid, 0u, 0u, 1u << 24), voc.bytes, 1, below, live, depth - 1,
+                                          (uint32_t*)nullptr, (const uint32_t*)nullptr, 0, (uint32_t*)nullptr, collect);
+        if (res == kOverflow)  // leave the decision to the walks
+          for (uint32_t w = 0; w < 8u; ++w) sm.pair[tid * 8u + w] = 0xFFFFFFFFu;
+      }
+      __syncthreads();
+    }
     // rounds of chunks whose lists together fit the queue (one chunk always fits)
     for (int32_t ca = c0; ca < c1;) {
       int32_t cb = ca + 1;
       while (cb < c1 && sm.off[cb + 1 - c0] - sm.off[ca - c0] <= (uint32_t)kFillQueue) ++cb;
-      // 2. filter + compact
-      for (int32_t chunk = ca; chunk < cb; ++chunk) {
-        const uint32_t j0 = sm.off[chunk - c0], j1 = sm.off[chunk + 1 - c0];
-        const uint32_t* wchunk = sm.words + (chunk - c0) * kChunkWords;
-        for (uint32_t j = j0 + (tid & ~63u); j < j1; j += kFillThreads) {
-          const uint32_t jj = j + lane;
-          bool keep = false;
-          uint32_t lid = 0, meta = 0;
-          if (jj < j1) {
-            const uint32_t e = unc_list[jj];
-            lid = e & 0xFFFu;
-            meta = (e >> 12) & 15u;
-            const uint32_t kb = (e >> 16) & 0xFFu;
-            const uint32_t* ok = first_ok + (meta == kEntryFullWalk ? 0 : 8);
-            keep = ((ok[kb >> 5] >> (kb & 31)) & 1u) && !((wchunk[lid >> 5] >> (lid & 31)) & 1u);
+      // 2. filter + compact: the lists of consecutive chunks are contiguous, so one flat pass reads them all
+      const uint32_t j_begin = sm.off[ca - c0], j_end = sm.off[cb - c0];
+      for (uint32_t j = j_begin + (tid & ~63u); j < j_end; j += kFillThreads) {
+        const uint32_t jj = j + lane;
+        bool keep = false;
+        uint32_t lid = 0, meta = 0, cl = 0;
+        if (jj < j_end) {
+          const uint32_t e = unc_list[jj];
+          // the entry's chunk: the last one whose list starts at or before jj
+          uint32_t lo = (uint32_t)(ca - c0), hi = (uint32_t)(cb - c0);
+          while (hi - lo > 1u) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (sm.off[mid] <= jj) lo = mid; else hi = mid;
           }
-          const unsigned long long m = __ballot(keep);
-          if (m) {
-            uint32_t base = 0;
-            if (lane == 0) base = atomicAdd(&sm.queue_n, (uint32_t)__popcll(m));
-            base = __shfl(base, 0, 64);
-            if (keep)
-              sm.queue[base + __popcll(m & ((1ull << lane) - 1ull))] = ((uint32_t)(chunk - c0) << 16) | (meta << 12) | lid;
+          cl = lo;
+          uint32_t* wchunk = sm.words + cl * kChunkWords;
+          lid = e & 0xFFFu;
+          meta = (e >> 12) & 15u;
+          const uint32_t b1 = (e >> 16) & 0xFFu, b2 = e >> 24;
+          const bool seen = (wchunk[lid >> 5] >> (lid & 31)) & 1u;  // already allowed through another stack
+          if (meta == kEntryFullWalk) {
+            keep = !seen && ((first_ok[b1 >> 5] >> (b1 & 31)) & 1u);
+          } else {
+            const bool ok1 = (first_ok[8 + (b1 >> 5)] >> (b1 & 31)) & 1u;
+            const bool ok2 = use_pair ? ((sm.pair[b1 * 8u + (b2 >> 5)] >> (b2 & 31)) & 1u) : ok1;
+            const bool decided = meta == kEntrySuffix1 || (use_pair && meta == kEntrySuffix2);
+            if (decided) {
+              if (!seen && (meta == kEntrySuffix1 ? ok1 : ok2)) atomicOr(&wchunk[lid >> 5], 1u << (lid & 31));
+            } else {
+              keep = !seen && ok2;
+            }
           }
+        }
+        const unsigned long long m = __ballot(keep);
+        if (m) {
+          uint32_t base = 0;
+          if (lane == 0) base = atomicAdd(&sm.queue_n, (uint32_t)__popcll(m));
+          base = __shfl(base, 0, 64);
+          if (keep) sm.queue[base + __popcll(m & ((1ull << lane) - 1ull))] = (cl << 16) | (meta << 12) | lid;
         }
       }
       __syncthreads();
@@ -437,8 +485,9 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
         uint32_t n_steps = 0;
         // a token with a single exit continues right there, in the frame below the top
         const bool full = meta == kEntryFullWalk;
+        const int i0 = full ? 0 : (meta == kEntrySuffix2 ? len - 2 : (int)meta);
         const int res = walk_token<false>(T, tk, ext, len, full ? top : below, live, full ? depth : depth - 1,
-                                          COUNT ? &n_steps : nullptr, (const uint32_t*)nullptr, full ? 0 : (int)meta);
+                                          COUNT ? &n_steps : nullptr, (const uint32_t*)nullptr, i0);
         if (COUNT) my_steps += n_steps;
         if (res == kAccept) atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
         else if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, (uint32_t)id);

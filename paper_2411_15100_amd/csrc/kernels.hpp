@@ -31,10 +31,11 @@ enum : int { kReject = 0, kUncertain = 1, kAccept = 2, kOverflow = 3, kUncertain
 //   [off_shapes, ..)        shapes   [n_shapes][n_cls] uint8
 //   [off_cls, off_cls+256)  cls      byte -> class
 //   [off_hdr, ..)           headers  [n_nodes] uint2: x = lo | hi<<8 | target<<16, y = flags | rule<<16
+//   [off_first, ..)         first    [n_nodes][8] uint32: bytes a node can consume inside its frame (never staged)
 // off_hdr is a multiple of 16 and the image is padded to a multiple of 16 bytes.
 struct DevTables {
   const uint4* image;
-  uint32_t off_follow, off_targets, off_shapes, off_cls, off_hdr;
+  uint32_t off_follow, off_targets, off_shapes, off_cls, off_hdr, off_first;
   int32_t n_cls, n_nodes, n_rules;
   // set per kernel by staged_for(): the leading stage_bytes of the image (the
   // small tables and the first n_near headers) go to LDS; 0 = nothing is staged
@@ -97,14 +98,18 @@ struct DevCache {
   int32_t n_nodes;
 };
 
-// A list entry describes one context-dependent token of a node:
+// A list entry describes one context-dependent token of a node.  If there is
+// exactly one position k at which a walk from the node can leave the node's
+// frame, what remains of the token from k on (its suffix) is the business of
+// the frames below (section 3.2), and the entry says so:
 //   bits  0..11  token id - chunk * 4096
-//   bits 12..15  the only position k (0..14) at which a walk from the node can leave the node's
-//                frame (section 3.2: what remains of the token is then the parent's business), or
-//                kEntryFullWalk if there are several such positions or the position is beyond 14
-//   bits 16..23  the byte at that position (for kEntryFullWalk: the token's first byte)
-//   bits 24..27  min(15, bytes left after that position): entries of a list are sorted by it
-constexpr uint32_t kEntryFullWalk = 15;
+//   bits 12..15  kind: 0..12 = k, the suffix has three or more bytes;
+//                kEntrySuffix2 / kEntrySuffix1 = the suffix has two bytes / one byte (k = length - that);
+//                kEntryFullWalk = several such positions, or k > 12 with a longer suffix: walk from the node
+//   bits 16..23  first byte of the suffix (kEntryFullWalk: of the token)
+//   bits 24..31  second byte of the suffix (0 if there is none; kEntryFullWalk: 0)
+// Entries of a (node, chunk) list are sorted by the length of what remains to be walked.
+constexpr uint32_t kEntrySuffix2 = 13, kEntrySuffix1 = 14, kEntryFullWalk = 15;
 
 // per-step upload of the live stacks: [RowDesc x B][stack headers][frames][FillBlock x n_blocks]
 struct RowDesc {

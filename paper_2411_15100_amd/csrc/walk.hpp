@@ -47,6 +47,7 @@ struct CompactTab {
     }
   }
   XGM_HD uint32_t alt(uint32_t idx) const { return v.alts[idx]; }
+  XGM_HD bool is_final(uint32_t n) const { return ((n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n]).y & 1u; }
   // the 256-bit FOLLOW set of node n's rule
   XGM_HD const uint32_t* follow_of(uint32_t n) const {
     const uint2 h = (n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n];
@@ -104,11 +105,21 @@ XGM_HD uint32_t token_byte(const uint4& tk, const uint8_t* ext, int i) { return 
 // position k at which the start frame is left in front of a byte of `follow`.
 // `Live` is anything indexable that yields the live frames (a plain pointer,
 // or a view that knows which of them sit in LDS).
-template <bool BUILD, class Tab, class Live>
+// `End` decides what the end of the token means.  The default returns kAccept
+// at the first path that consumes every byte.  An enumerating End is instead
+// called with every configuration (node, stack handle, arena, live frames) in
+// which the token can end, and the walk goes on to the next path; the result
+// is then kReject (or kOverflow).
+struct FirstPathEnds {
+  static constexpr bool kEnumerate = false;
+  template <class Live>
+  XGM_HD void operator()(uint32_t, uint32_t, const uint32_t*, const Live&) const {}
+};
+template <bool BUILD, class Tab, class Live, class End = FirstPathEnds>
 XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const int len,
                       const uint32_t start_node, const Live& live, const uint32_t depth,
                       uint32_t* steps_out = nullptr, const uint32_t* follow = nullptr, const int i0 = 0,
-                      uint32_t* exits_out = nullptr) {
+                      uint32_t* exits_out = nullptr, const End& at_end = End()) {
   if (len > kMaxTokenLen) return kOverflow;
   const TokenWords tw(tk);
   uint32_t arena[kArenaFrames];  // ret | parent handle << 16
@@ -118,56 +129,60 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
   bool left_frame = false, left_frame_follow = false;
   for (int steps = 0;; ++steps) {
     if (steps_out) *steps_out = (uint32_t)steps;
-    if (i == len) return kAccept;
+    if (i == len && !End::kEnumerate) return kAccept;
     if (steps >= kMaxSteps) return kOverflow;
-    const uint32_t c = token_byte(tw, ext, i);
-    uint32_t k, single, base, fin, after;
-    bool pooled;
-    T.lookup(n, c, k, single, base, pooled, fin, after);
-    const uint32_t can_pop = fin & f & (BUILD ? 1u : after);
-    const uint32_t total = k + can_pop;
     bool advanced = false;
-    if (alt < total) {
-      bool ok = true;
-      if (alt + 1 < total) {
-        if (csp == kChoicePoints) return kOverflow;
-        choice[csp++] = make_uint2(n | (sp << 16), (uint32_t)i | ((alt + 1) << 8) | (top << 16) | (f << 24));
-      }
-      if (alt < k) {
-        const uint32_t e = pooled ? T.alt(base + 1 + alt) : single;
-        const uint32_t tag = e >> 16, dst = e & 0xFFFFu;
-        if (tag == kMoveTagD) { n = dst; ++i; f = 1; }
-        else if (tag == kTailTagD) { n = dst; f = 0; }  // enter the callee, it returns to our parent
-        else {
-          if (top == kArenaFrames) return kOverflow;
-          arena[top] = tag | (sp << 16);
-          sp = top++;
-          n = dst;
-          f = 0;
+    if (i == len) {
+      at_end(n, sp, arena, live);      // then on to the next path
+    } else {
+      const uint32_t c = token_byte(tw, ext, i);
+      uint32_t k, single, base, fin, after;
+      bool pooled;
+      T.lookup(n, c, k, single, base, pooled, fin, after);
+      const uint32_t can_pop = fin & f & (BUILD ? 1u : after);
+      const uint32_t total = k + can_pop;
+      if (alt < total) {
+        bool ok = true;
+        if (alt + 1 < total) {
+          if (csp == kChoicePoints) return kOverflow;
+          choice[csp++] = make_uint2(n | (sp << 16), (uint32_t)i | ((alt + 1) << 8) | (top << 16) | (f << 24));
         }
-      } else if (sp < kLiveBase) {   // return into a frame pushed during this walk
-        const uint32_t fr = arena[sp], old = sp;
-        n = fr & 0xFFFFu;
-        sp = fr >> 16;
-        // frames from `old` upwards are garbage unless a pending alternative still needs them
-        if (csp == 0 || ((choice[csp - 1].y >> 16) & 0xFFu) <= old) top = old;
-      } else {                       // return into a live frame
-        const uint32_t d = sp - kLiveBase;
-        if (d == 0) {                // nothing below: end of the start frame (BUILD) or of the root rule
-          if (BUILD) {
-            left_frame = true;
-            if ((follow[c >> 5] >> (c & 31)) & 1u) {
-              left_frame_follow = true;
-              if (exits_out) *exits_out |= 1u << (i < 15 ? i : 15);
-            }
+        if (alt < k) {
+          const uint32_t e = pooled ? T.alt(base + 1 + alt) : single;
+          const uint32_t tag = e >> 16, dst = e & 0xFFFFu;
+          if (tag == kMoveTagD) { n = dst; ++i; f = 1; }
+          else if (tag == kTailTagD) { n = dst; f = 0; }  // enter the callee, it returns to our parent
+          else {
+            if (top == kArenaFrames) return kOverflow;
+            arena[top] = tag | (sp << 16);
+            sp = top++;
+            n = dst;
+            f = 0;
           }
-          ok = false;
-        } else {
-          n = live[d - 1];
-          sp = kLiveBase + d - 1;
+        } else if (sp < kLiveBase) {   // return into a frame pushed during this walk
+          const uint32_t fr = arena[sp], old = sp;
+          n = fr & 0xFFFFu;
+          sp = fr >> 16;
+          // frames from `old` upwards are garbage unless a pending alternative still needs them
+          if (csp == 0 || ((choice[csp - 1].y >> 16) & 0xFFu) <= old) top = old;
+        } else {                       // return into a live frame
+          const uint32_t d = sp - kLiveBase;
+          if (d == 0) {                // nothing below: end of the start frame (BUILD) or of the root rule
+            if (BUILD) {
+              left_frame = true;
+              if ((follow[c >> 5] >> (c & 31)) & 1u) {
+                left_frame_follow = true;
+                if (exits_out) *exits_out |= 1u << (i < 15 ? i : 15);
+              }
+            }
+            ok = false;
+          } else {
+            n = live[d - 1];
+            sp = kLiveBase + d - 1;
+          }
         }
+        if (ok) { alt = 0; advanced = true; }
       }
-      if (ok) { alt = 0; advanced = true; }
     }
     if (!advanced) {                 // back up to the most recent pending alternative
       if (csp == 0) break;
@@ -183,5 +198,42 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
   if (BUILD && left_frame) return left_frame_follow ? kUncertain : kUncertainPlain;
   return kReject;
 }
+
+// The bytes that can be consumed next from a configuration: what the node
+// itself can consume (byte edges and the first bytes of the rules it refers
+// to) and, as long as the nodes passed may end their rule instance, the same
+// for the frames below.  `acc.add(word, bits)` receives the 256-bit set.
+template <class Tab, class Live, class Acc>
+XGM_HD void config_next_bytes(const Tab& T, const uint32_t* node_first_words, uint32_t n, uint32_t sp,
+                              const uint32_t* arena, const Live& live, Acc& acc) {
+  for (;;) {
+    const uint32_t* fw = node_first_words + (size_t)n * 8;
+    for (uint32_t w = 0; w < 8; ++w) acc.add(w, fw[w]);
+    if (!T.is_final(n)) return;
+    if (sp < kLiveBase) {
+      const uint32_t fr = arena[sp];
+      n = fr & 0xFFFFu;
+      sp = fr >> 16;
+    } else {
+      const uint32_t d = sp - kLiveBase;
+      if (d == 0) return;
+      n = live[d - 1];
+      sp = kLiveBase + d - 1;
+    }
+  }
+}
+
+// End policy that collects the next-byte sets of all configurations a string can end in.
+template <class Tab, class Acc>
+struct CollectNextBytes {
+  static constexpr bool kEnumerate = true;
+  const Tab* T;
+  const uint32_t* node_first_words;
+  Acc* acc;
+  template <class Live>
+  XGM_HD void operator()(uint32_t n, uint32_t sp, const uint32_t* arena, const Live& live) const {
+    config_next_bytes(*T, node_first_words, n, sp, arena, live, *acc);
+  }
+};
 
 }  // namespace xgm

@@ -312,6 +312,45 @@ def test_kernel_walk_masks_match_oracle_along_walks(name):
         assert om.advance(toks[t])
 
 
+@pytest.mark.parametrize("name", ["arith", "json", "schema"])
+def test_next_byte_sets_match_oracle(name):
+    """The fill kernel's two-byte table, computed by the same source on the
+    host: byte c2 is in the set of (stack, c1) iff the oracle can consume c1
+    and then c2 from the same state.  Checked for every stack of the state
+    (union over the stacks == the oracle's answer) and on the full stack as
+    well as on the stack without its top frame being consistent with it."""
+    text, root, alphabet = GRAMMARS[name]
+    vocab = si.make_vocab("arith", 1024, 0) if name == "arith" else si.make_vocab("bpe", 4000, 3)
+    toks = vocab.tokens()
+    first = np.array([t[0] if t else -1 for t in toks], dtype=np.int16)
+    g = xgm.Grammar(text, root)
+    og = oracle.Grammar(text, root)
+    v = xgm.Vocab(vocab.data, vocab.offsets, vocab.stop_ids)
+    m = xgm.Matcher(grammar=g, vocab=v)
+    om = oracle.EarleyMatcher(og)
+    rng = np.random.Generator(np.random.PCG64(zlib.crc32(name.encode()) + 77))
+    probes = sorted(set(alphabet) | {0, 255})
+    for step in range(10):
+        stacks = [m.stack(s) for s in range(m.num_stacks())]
+        for c1 in probes:
+            got = np.zeros(256, dtype=bool)
+            for st in stacks:
+                got |= g.debug_next_bytes_host(st, c1)
+            after = om.clone()
+            if not after.advance(bytes([c1])):
+                assert not got.any(), (name, step, c1)
+                continue
+            for c2 in probes:
+                probe = after.clone()
+                assert bool(got[c2]) == bool(probe.advance(bytes([c2]))), (name, step, c1, c2)
+        want = om.mask(vocab)
+        t = si.pick_token(rng, want, first, vocab.stop_ids, structural_bias=0.4)
+        if t < 0 or t == int(vocab.stop_ids[0]):
+            break
+        m.accept_token(t)
+        assert om.advance(toks[t])
+
+
 def test_kernel_walk_reports_overflow_instead_of_guessing():
     g = xgm.Grammar(si.ARITH_GRAMMAR, "expr")
     start = [n for n in range(g.num_nodes) if g.rule_name(g.node_rule(n)) == "expr" and g.node_path(n) == []][0]
