@@ -569,17 +569,14 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
 
 // ---------------------------------------------------------------- kernel (c)
 constexpr int kApplyThreads = 256;
-constexpr int kApplyGroups = 8;  // 16-byte groups per thread
 
-// Section 2.1: logits of disallowed tokens become -inf.  A group is 16 bytes
-// of a logits row (8 bf16/fp16 or 4 fp32 elements) with its mask bits.  All
-// allowed: nothing is touched.  None allowed: one 16-byte store of the -inf
-// pattern, no read.  Mixed: read (all such reads of a thread are issued before
-// its first store), blend, write.  A wave owns a contiguous run
-// of 64 * kApplyGroups groups and walks it 64 groups (1 KiB) at a time, so
-// every store instruction of a wave covers whole cache lines; a thread first
-// fetches the mask bits of all its groups, then issues its stores back to
-// back.  ESIZE = bytes per element.
+// Section 2.1: logits of disallowed tokens become -inf.  A thread owns one
+// group: 16 bytes of a logits row (8 bf16/fp16 or 4 fp32 elements) with its
+// mask bits; the 64 groups of a wave are contiguous (1 KiB).  All allowed:
+// nothing is touched.  None allowed: one 16-byte store of the -inf pattern.
+// Mixed: only the disallowed elements are stored (pairs of 16-bit elements as
+// one 32-bit store where both go).  The logits are never read: the bytes that
+// stay are simply not written.  ESIZE = bytes per element.
 template <int ESIZE>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(unsigned char* __restrict__ logits, int64_t row_stride,
                                                               const uint32_t* __restrict__ bitmask, int32_t W_mask,
@@ -589,60 +586,33 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(unsigned char* __r
   constexpr uint32_t kAll = (1u << EPT) - 1u;
   const int32_t j = blockIdx.y;
   const int64_t lrow = row_index ? row_index[j] : j;
-  const int32_t wave_base = (blockIdx.x * (kApplyThreads / 64) + (threadIdx.x >> 6)) * 64 * kApplyGroups;
-  const int32_t lane = threadIdx.x & 63;
-  const uint32_t* mrow = bitmask + (size_t)j * W_mask;
-  unsigned char* lbase = logits + (size_t)lrow * row_stride * ESIZE;
-  uint32_t m[kApplyGroups];
-#pragma unroll
-  for (int k = 0; k < kApplyGroups; ++k) {
-    const int32_t e0 = (wave_base + k * 64 + lane) * EPT;
-    m[k] = 0u;
-    if (e0 < V_mask && e0 < V_logits) {
-      m[k] = (mrow[e0 >> 5] >> (e0 & 31)) & kAll;
-      if (e0 + EPT > V_mask) m[k] &= (1u << (V_mask - e0)) - 1u;
-    }
+  const int32_t e0 = (blockIdx.x * kApplyThreads + threadIdx.x) * EPT;
+  if (e0 >= V_logits) return;
+  uint32_t mk = 0u;
+  if (e0 < V_mask) {
+    mk = (bitmask[(size_t)j * W_mask + (e0 >> 5)] >> (e0 & 31)) & kAll;
+    if (e0 + EPT > V_mask) mk &= (1u << (V_mask - e0)) - 1u;
   }
+  if (mk == kAll) return;
+  unsigned char* p = logits + ((size_t)lrow * row_stride + e0) * ESIZE;
   const uint32_t two = neg_inf | (neg_inf << 16);
-  // mixed groups need their old contents: fetch them all before the first store
-  uint4 old[kApplyGroups];
+  if (mk == 0u && e0 + EPT <= V_logits) {
+    *reinterpret_cast<uint4*>(p) = ESIZE == 2 ? make_uint4(two, two, two, two) : make_uint4(neg_inf, neg_inf, neg_inf, neg_inf);
+  } else if (ESIZE == 2) {
 #pragma unroll
-  for (int k = 0; k < kApplyGroups; ++k) {
-    const int32_t e0 = (wave_base + k * 64 + lane) * EPT;
-    old[k] = make_uint4(0, 0, 0, 0);
-    if (e0 + EPT <= V_logits && m[k] != 0u && m[k] != kAll)
-      old[k] = *reinterpret_cast<const uint4*>(lbase + (size_t)e0 * ESIZE);
-  }
-#pragma unroll
-  for (int k = 0; k < kApplyGroups; ++k) {
-    const int32_t e0 = (wave_base + k * 64 + lane) * EPT;
-    if (e0 >= V_logits) continue;
-    unsigned char* p = lbase + (size_t)e0 * ESIZE;
-    const uint32_t mk = m[k];
-    if (e0 + EPT <= V_logits) {
-      if (mk == kAll) continue;
-      uint4 v = old[k];
-      if (ESIZE == 2) {
-        uint32_t* q = reinterpret_cast<uint32_t*>(&v);
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-          const uint32_t keep = ((mk >> (2 * h)) & 1u ? 0x0000FFFFu : 0u) | ((mk >> (2 * h + 1)) & 1u ? 0xFFFF0000u : 0u);
-          q[h] = (q[h] & keep) | (two & ~keep);
-        }
+    for (int h = 0; h < 4; ++h) {
+      const uint32_t b = (mk >> (2 * h)) & 3u;
+      if (e0 + 2 * h + 1 < V_logits && b == 0u) {
+        reinterpret_cast<uint32_t*>(p)[h] = two;
       } else {
-        if (!(mk & 1u)) v.x = neg_inf;
-        if (!(mk & 2u)) v.y = neg_inf;
-        if (!(mk & 4u)) v.z = neg_inf;
-        if (!(mk & 8u)) v.w = neg_inf;
+        if (e0 + 2 * h < V_logits && !(b & 1u)) reinterpret_cast<uint16_t*>(p)[2 * h] = (uint16_t)neg_inf;
+        if (e0 + 2 * h + 1 < V_logits && !(b & 2u)) reinterpret_cast<uint16_t*>(p)[2 * h + 1] = (uint16_t)neg_inf;
       }
-      *reinterpret_cast<uint4*>(p) = v;
-    } else {
-      for (int h = 0; e0 + h < V_logits; ++h)
-        if (!((mk >> h) & 1u)) {
-          if (ESIZE == 2) reinterpret_cast<uint16_t*>(p)[h] = (uint16_t)neg_inf;
-          else reinterpret_cast<uint32_t*>(p)[h] = neg_inf;
-        }
     }
+  } else {
+#pragma unroll
+    for (int h = 0; h < EPT; ++h)
+      if (e0 + h < V_logits && !((mk >> h) & 1u)) reinterpret_cast<uint32_t*>(p)[h] = neg_inf;
   }
 }
 
@@ -742,7 +712,7 @@ void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logit
   if (aligned) {
     const int ept = 16 / elem_size;
     const int32_t groups = (V_logits + ept - 1) / ept;
-    const int32_t per_block = kApplyThreads * kApplyGroups;
+    const int32_t per_block = kApplyThreads;
     dim3 grid((groups + per_block - 1) / per_block, n_rows);
     if (elem_size == 2)
       hipLaunchKernelGGL(apply_kernel<2>, grid, dim3(kApplyThreads), 0, stream, p, row_stride, bitmask, W_mask,
