@@ -231,6 +231,10 @@ int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bi
  * walks; synchronous; *h_steps receives the count.  Not for the hot path. */
 int xgm_debug_fill_count_steps(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask,
                                void* hip_stream, int64_t* h_steps);
+/* Instrumentation for the benchmark: the same fill, with HIP events recorded on
+ * hip_stream around its two kernels; waits for them.  h_us2[0] = microseconds
+ * of the stack upload kernel, h_us2[1] = of the fill kernel (host array of 2). */
+int xgm_debug_fill_timed(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream, float* h_us2);
 /* Synchronises hip_stream, then decides on the host every pair recorded by
  * the most recent fill and patches that fill's d_bitmask.  Returns the number
  * of pairs handled (>= 0) or a negative status.  Costs one stream

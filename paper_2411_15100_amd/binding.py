@@ -63,6 +63,7 @@ SIGNATURES = {
     "xgm_matcher_stack": (_i32, [_vp, _i32, _vp, _i32]),
     "xgm_fill_next_token_bitmask": (_i32, [_vp, _i32, _vp, _vp]),
     "xgm_debug_fill_count_steps": (_i32, [_vp, _i32, _vp, _vp, _vp]),
+    "xgm_debug_fill_timed": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_fill_overflow_fixup": (_i32, [_vp]),
     "xgm_overflow_total": (_i64, []),
     "xgm_apply_token_bitmask_inplace": (_i32, [_vp, _i32, _i32, _i32, _i64, _vp, _i32, _vp, _i32, _vp]),
@@ -334,6 +335,14 @@ def debug_fill_count_steps(batch: "MatcherBatch", d_bitmask: int, stream: int = 
     _check(load_library().xgm_debug_fill_count_steps(batch._arr, len(batch.matchers), ctypes.c_void_p(d_bitmask),
                                                      ctypes.c_void_p(stream), ctypes.byref(n)))
     return int(n.value)
+
+
+def debug_fill_timed(batch: "MatcherBatch", d_bitmask: int, stream: int = 0):
+    """One fill with HIP events around its kernels: (upload kernel us, fill kernel us)."""
+    us = (ctypes.c_float * 2)()
+    _check(load_library().xgm_debug_fill_timed(batch._arr, len(batch.matchers), ctypes.c_void_p(d_bitmask),
+                                               ctypes.c_void_p(stream), us))
+    return float(us[0]), float(us[1])
 
 
 def fill_overflow_fixup(stream: int = 0) -> int:

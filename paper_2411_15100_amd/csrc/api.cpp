@@ -719,8 +719,10 @@ int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int
 }
 
 // ---------------------------------------------------------------------- fill
+// `timing` (may be null): three events recorded on the stream before the upload
+// kernel, between the two kernels and after the fill kernel.
 static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream,
-                     unsigned long long* d_step_counter) {
+                     unsigned long long* d_step_counter, hipEvent_t* timing = nullptr) {
   API_BEGIN
   if (!ms || B <= 0 || !d_bitmask) return fail(XGM_ERR_BAD_ARG, "fill: null argument or empty batch");
   xgm_vocab* v = nullptr;
@@ -858,7 +860,9 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
       }
     }
   }
+  if (timing) HIP_OK(hipEventRecord(timing[0], stream));
   launch_upload(slot.h_dev, slot.d_buf, off_plan + (size_t)n_blocks * sizeof(FillBlock), stream);
+  if (timing) HIP_OK(hipEventRecord(timing[1], stream));
   const uint32_t seq = ++C.seq;
   launch_fill(reinterpret_cast<const RowDesc*>(slot.d_buf),
               reinterpret_cast<const uint32_t*>((char*)slot.d_buf + off_stacks),
@@ -866,6 +870,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
               reinterpret_cast<const FillBlock*>((char*)slot.d_buf + off_plan), n_blocks, v->dv,
               reinterpret_cast<uint32_t*>(d_bitmask), log, seq, d_step_counter, stream);
   HIP_OK(hipGetLastError());
+  if (timing) HIP_OK(hipEventRecord(timing[2], stream));
   HIP_OK(hipEventRecord(slot.done, stream));
   slot.used = true;
   C.last_slot = C.next_slot;
@@ -904,6 +909,32 @@ int xgm_debug_fill_count_steps(xgm_matcher* const* ms, int32_t B, int32_t* d_bit
     throw;
   }
   (void)hipFree(d_counter);
+  return rc;
+  API_END
+}
+
+int xgm_debug_fill_timed(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream, float* h_us2) {
+  API_BEGIN
+  if (!h_us2) return fail(XGM_ERR_BAD_ARG, "fill_timed: null output");
+  require_device();
+  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  int rc = XGM_OK;
+  try {
+    for (auto& e : ev) HIP_OK(hipEventCreate(&e));
+    rc = fill_impl(ms, B, d_bitmask, hip_stream, nullptr, ev);
+    if (rc == XGM_OK) {
+      HIP_OK(hipEventSynchronize(ev[2]));
+      float ms01 = 0.f, ms12 = 0.f;
+      HIP_OK(hipEventElapsedTime(&ms01, ev[0], ev[1]));
+      HIP_OK(hipEventElapsedTime(&ms12, ev[1], ev[2]));
+      h_us2[0] = ms01 * 1e3f;
+      h_us2[1] = ms12 * 1e3f;
+    }
+  } catch (...) {
+    for (auto& e : ev) if (e) (void)hipEventDestroy(e);
+    throw;
+  }
+  for (auto& e : ev) if (e) (void)hipEventDestroy(e);
   return rc;
   API_END
 }
