@@ -176,6 +176,13 @@ int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h
  * h_steps (may be NULL) receives the number of automaton steps taken. */
 int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth,
                         const uint8_t* h_bytes, int32_t n, int32_t build, int32_t* h_steps);
+/* A frame whose current node is `top` can only sit on one of the few nodes that
+ * follow a reference to top's rule (directly, or through references in tail
+ * position).  Returns the index of `below` among them (what the fill kernel
+ * uses to look up per-context token classes), -1001 if the rule has more than
+ * 16 such nodes (no per-context classes are kept), -1000 if `below` is not one
+ * of them (never the case for a stack the matcher produced). */
+int32_t xgm_debug_context_index(const xgm_grammar* g, int32_t top, int32_t below);
 /* The table the fill kernel builds per stack to test two bytes at once, on the
  * host: the 256-bit set (8 words: byte c is bit c & 31 of word
  * c >> 5) of the bytes that can be consumed right after `byte` from the

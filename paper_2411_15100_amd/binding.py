@@ -41,6 +41,7 @@ SIGNATURES = {
     "xgm_debug_classify_host": (_i32, [_vp, _i32, _cp, _i32]),
     "xgm_debug_walk_host": (_i32, [_vp, _vp, _i32, _cp, _i32, _i32, _vp]),
     "xgm_debug_next_bytes_host": (_i32, [_vp, _vp, _i32, _i32, _vp]),
+    "xgm_debug_context_index": (_i32, [_vp, _i32, _i32]),
     "xgm_cache_build": (_i32, [_vp, _vp, _vp, _pp]),
     "xgm_cache_build_ex": (_i32, [_vp, _vp, _vp, ctypes.c_uint32, _pp]),
     "xgm_cache_num_uncertain_plain": (_i32, [_vp, _i32]),
@@ -210,6 +211,10 @@ class Grammar:
                                                        1 if build else 0, ctypes.byref(steps)))
         return (rc, int(steps.value)) if with_steps else rc
 
+
+    def debug_context_index(self, top: int, below: int) -> int:
+        """Index of `below` among the contexts of top's rule; -1001 too many contexts, -1000 not a context."""
+        return int(load_library().xgm_debug_context_index(self._h, int(top), int(below)))
 
     def debug_next_bytes_host(self, stack, byte: int) -> np.ndarray:
         """256 flags: which bytes can be consumed right after `byte` from the stack."""

@@ -362,6 +362,16 @@ int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h
   API_END
 }
 
+int32_t xgm_debug_context_index(const xgm_grammar* g, int32_t top, int32_t below) {
+  if (!g || top < 0 || top >= g->A.n_nodes || below < 0 || below >= g->A.n_nodes)
+    return fail(XGM_ERR_BAD_ARG, "context_index: bad argument");
+  const auto& ctx = g->A.contexts[g->A.node_rule[top]];
+  auto it = std::lower_bound(ctx.begin(), ctx.end(), below);
+  if (it == ctx.end() || *it != below) return -1000;
+  if (ctx.size() > kCtxMax) return -1001;
+  return (int32_t)(it - ctx.begin());
+}
+
 namespace {
 struct HostSetAcc {
   uint32_t* words;
@@ -574,8 +584,20 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     }
     uint32_t* d_off = keep(slab_upload(c->unc_off_host));
     uint32_t* d_list = keep(slab_alloc<uint32_t>((size_t)total));
+    uint32_t* d_list_ctx = keep(slab_alloc<uint32_t>((size_t)total));
+    // contexts of the rules that have few enough of them
+    std::vector<uint32_t> ctx_off(A.rule_names.size() + 1, 0);
+    std::vector<uint16_t> ctx_node;
+    for (size_t r = 0; r < A.rule_names.size(); ++r) {
+      if (A.contexts[r].size() <= kCtxMax)
+        for (int32_t n : A.contexts[r]) ctx_node.push_back((uint16_t)n);
+      ctx_off[r + 1] = (uint32_t)ctx_node.size();
+    }
+    if (ctx_node.empty()) ctx_node.push_back(0);
+    uint32_t* d_ctx_off = temp(dev_upload(ctx_off));
+    uint16_t* d_ctx_node = temp(dev_upload(ctx_node));
     launch_list_uncertain(dv, N, unc_id, d_off, d_list, stream);
-    launch_annotate_lists(tab, dv, N, d_off, d_list, stream);
+    launch_annotate_lists(tab, dv, N, d_off, d_list, d_list_ctx, d_ctx_off, d_ctx_node, stream);
     HIP_OK(hipGetLastError());
     HIP_OK(hipStreamSynchronize(stream));
     cleanup_temps();
@@ -584,6 +606,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     c->host.acc = acc_id;
     c->host.unc_off = d_off;
     c->host.unc_list = d_list;
+    c->host.unc_ctx = d_list_ctx;
     c->host.n_nodes = N;
   } catch (...) {
     cleanup_temps();
@@ -780,7 +803,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     r.stack_begin = si;
     if (m->terminated) {
       r.tab = DevTables{};
-      r.acc = r.unc_list = nullptr;
+      r.acc = r.unc_list = r.unc_ctx = nullptr;
       r.n_stacks = 0;
       r.flags = 1;
       continue;
@@ -789,6 +812,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     r.tab = m->c->host.tab;
     r.acc = m->c->host.acc;
     r.unc_list = m->c->host.unc_list;
+    r.unc_ctx = m->c->host.unc_ctx;
     r.n_stacks = (uint32_t)m->stacks.size();
     r.flags = Engine(&A).can_terminate(m->stacks) ? 1u : 0u;
     for (auto& s : m->stacks) {
@@ -797,7 +821,14 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
       h[kStackHdrTop] = (uint32_t)top;
       h[kStackHdrDepth] = (uint32_t)s.size();
       h[kStackHdrFrames] = fi;
-      h[3] = 0;
+      h[kStackHdrCtx] = kCtxNone;
+      if (s.size() >= 2) {
+        const auto& ctx = A.contexts[A.node_rule[top]];
+        if (ctx.size() <= kCtxMax) {
+          auto it = std::lower_bound(ctx.begin(), ctx.end(), s[s.size() - 2]);
+          if (it != ctx.end() && *it == s[s.size() - 2]) h[kStackHdrCtx] = (uint32_t)(it - ctx.begin());
+        }
+      }
       // bytes that can be consumed from this stack: at the top node, or - as
       // long as the frames passed so far may all end here - at the frames
       // below; and the same for the stack without its top frame

@@ -693,6 +693,24 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
   for (int n = 0; n < total; ++n)
     A.node_dead_end[n] = A.node_final[n] && A.bedges[n].empty() && A.redges[n].empty();
 
+  // contexts of every rule (see automaton.hpp)
+  {
+    std::vector<std::set<int32_t>> ctx(NR);
+    for (bool changed = true; changed;) {
+      changed = false;
+      for (int n = 0; n < total; ++n)
+        for (auto& e : A.redges[n]) {
+          auto& c = ctx[e.rule];
+          const size_t before = c.size();
+          if (!A.node_dead_end[e.to]) c.insert(e.to);
+          else if (e.rule != A.node_rule[n]) { const auto& p = ctx[A.node_rule[n]]; c.insert(p.begin(), p.end()); }
+          if (c.size() != before) changed = true;
+        }
+    }
+    A.contexts.assign(NR, {});
+    for (int r = 0; r < NR; ++r) A.contexts[r].assign(ctx[r].begin(), ctx[r].end());
+  }
+
   // Alternatives of node n on byte c, in the order the walk tries them:
   //  * the byte edge;
   //  * for every reference whose callee can start with c: enter the callee.

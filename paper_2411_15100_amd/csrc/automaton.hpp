@@ -54,6 +54,9 @@ struct Automaton {
   std::vector<std::bitset<256>> node_first;   // per node: bytes that can be consumed at the node inside its frame
   std::vector<uint32_t> node_first_words;     // [n_nodes][8] the same sets as machine words
   std::vector<std::bitset<256>> follow;       // per rule: bytes that can come right after an instance, in any context
+  // per rule: the nodes that can sit right below a frame of that rule (return nodes of the references to it;
+  // a reference in tail position hands on the contexts of the referring rule), sorted
+  std::vector<std::vector<int32_t>> contexts;
   int32_t root_rule = 0;
   std::vector<std::vector<int32_t>> node_path;  // witness path from the rule start
 

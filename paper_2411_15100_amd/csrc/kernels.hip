@@ -257,8 +257,12 @@ __global__ void list_uncertain_kernel(DevVocab voc, const uint32_t* __restrict__
 constexpr int kAnnotateThreads = 256;
 __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTables tab, DevVocab voc, int32_t node0,
                                                                           const uint32_t* __restrict__ off,
-                                                                          uint32_t* __restrict__ list) {
+                                                                          uint32_t* __restrict__ list,
+                                                                          uint32_t* __restrict__ list_ctx,
+                                                                          const uint32_t* __restrict__ ctx_off,
+                                                                          const uint16_t* __restrict__ ctx_node) {
   __shared__ uint32_t seg[kChunkTokens];
+  __shared__ uint32_t seg_ctx[kChunkTokens];
   __shared__ uint8_t rem_of[kChunkTokens];
   __shared__ uint32_t bucket[16];
   const int32_t node = node0 + blockIdx.y, chunk = blockIdx.x;
@@ -268,6 +272,8 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
   if (threadIdx.x < 16) bucket[threadIdx.x] = 0u;
   __syncthreads();
   const CompactTab T{stage_tables(tab, nullptr, kAnnotateThreads)};  // launched with nothing staged
+  const uint32_t rule = T.v.hdr_far[node].y >> 16;
+  const uint32_t ctx0 = ctx_off[rule], n_ctx = ctx_off[rule + 1] - ctx0;  // 0 .. kCtxMax
   for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
     const uint32_t lid = list[j0 + e] & 0xFFFu;
     const int32_t id = chunk * kChunkTokens + (int32_t)lid;
@@ -291,6 +297,18 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
     const uint32_t b1 = token_byte(tk, ext, (int)pos);
     const uint32_t b2 = (meta != kEntryFullWalk && (int)pos + 1 < len) ? token_byte(tk, ext, (int)pos + 1) : 0u;
     const uint32_t rem = min(15, len - (int)pos);
+    // what the suffix does in each context of the node's rule, with nothing known below that context
+    uint32_t classes = 0u;
+    for (uint32_t i = 0; i < kCtxMax; ++i) {
+      uint32_t code = kCtxWalk;
+      if (meta != kEntryFullWalk && i < n_ctx) {
+        const uint32_t r = ctx_node[ctx0 + i];
+        const int c = walk_token<true>(T, tk, ext, len, r, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r), (int)pos);
+        code = c == kAccept ? kCtxAccept : (c == kUncertain || c == kOverflow) ? kCtxWalk : kCtxReject;
+      }
+      classes |= code << (2u * i);
+    }
+    seg_ctx[e] = classes;
     seg[e] = lid | (meta << 12) | (b1 << 16) | (b2 << 24);
     rem_of[e] = (uint8_t)rem;
     atomicAdd(&bucket[rem], 1u);
@@ -302,7 +320,9 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
   }
   __syncthreads();
   for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
-    list[j0 + atomicAdd(&bucket[rem_of[e]], 1u)] = seg[e];
+    const uint32_t at = j0 + atomicAdd(&bucket[rem_of[e]], 1u);
+    list[at] = seg[e];
+    list_ctx[at] = seg_ctx[e];
   }
 }
 
@@ -392,6 +412,7 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
   const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
   const XGM_GLOBAL uint32_t* unc_list = (const XGM_GLOBAL uint32_t*)rd.unc_list;
+  const XGM_GLOBAL uint32_t* unc_ctx = (const XGM_GLOBAL uint32_t*)rd.unc_ctx;
   const uint32_t* node_first = reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(rd.tab.image) + rd.tab.off_first);
   const uint32_t* first_ok = sm.hdr + kStackHdrFirst;
   for (uint32_t s = 0; s < rd.n_stacks; ++s) {
@@ -403,6 +424,7 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
     __syncthreads();
     if (sm.off[c1 - c0] == sm.off[0]) continue;  // nothing listed here (uniform)
     const uint32_t top = sm.hdr[kStackHdrTop], depth = sm.hdr[kStackHdrDepth];
+    const uint32_t ctx = sm.hdr[kStackHdrCtx];  // which context of the top's rule the frame below is, or kCtxNone
     LiveView live;
     live.lds = (const XGM_LDS uint16_t*)sm.live + (sm.hdr[kStackHdrFrames] - frame0);
     live.glob = frames + sm.hdr[kStackHdrFrames];
@@ -435,6 +457,7 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
         uint32_t lid = 0, meta = 0, cl = 0;
         if (jj < j_end) {
           const uint32_t e = unc_list[jj];
+          const uint32_t in_ctx = ctx != kCtxNone ? (unc_ctx[jj] >> (2u * ctx)) & 3u : kCtxWalk;
           // the entry's chunk: the last one whose list starts at or before jj
           uint32_t lo = (uint32_t)(ca - c0), hi = (uint32_t)(cb - c0);
           while (hi - lo > 1u) {
@@ -452,9 +475,10 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
           } else {
             const bool ok1 = (first_ok[8 + (b1 >> 5)] >> (b1 & 31)) & 1u;
             const bool ok2 = use_pair ? ((sm.pair[b1 * 8u + (b2 >> 5)] >> (b2 & 31)) & 1u) : ok1;
-            const bool decided = meta == kEntrySuffix1 || (use_pair && meta == kEntrySuffix2);
+            const bool decided = in_ctx != kCtxWalk || meta == kEntrySuffix1 || (use_pair && meta == kEntrySuffix2);
             if (decided) {
-              if (!seen && (meta == kEntrySuffix1 ? ok1 : ok2)) atomicOr(&wchunk[lid >> 5], 1u << (lid & 31));
+              const bool allowed = in_ctx != kCtxWalk ? in_ctx == kCtxAccept : (meta == kEntrySuffix1 ? ok1 : ok2);
+              if (!seen && allowed) atomicOr(&wchunk[lid >> 5], 1u << (lid & 31));
             } else {
               keep = !seen && ok2;
             }
@@ -667,11 +691,11 @@ void launch_list_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_i
 }
 
 void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n, const uint32_t* off, uint32_t* list,
-                           hipStream_t stream) {
+                           uint32_t* list_ctx, const uint32_t* ctx_off, const uint16_t* ctx_node, hipStream_t stream) {
   for (int32_t node0 = 0; node0 < n; node0 += 32768) {  // grid.y limit
     const int32_t nb = std::min(32768, n - node0);
     hipLaunchKernelGGL(annotate_lists_kernel, dim3(voc.n_chunk, nb), dim3(kAnnotateThreads), 0, stream,
-                       staged_for(tab, 0), voc, node0, off, list);
+                       staged_for(tab, 0), voc, node0, off, list, list_ctx, ctx_off, ctx_node);
   }
 }
 

@@ -95,6 +95,7 @@ struct DevCache {
   const uint32_t* acc;       // [n_nodes][W] accepted tokens, id space
   const uint32_t* unc_off;   // [n_nodes][n_chunk+1] offsets into unc_list
   const uint32_t* unc_list;  // context-dependent tokens, grouped by (node, chunk); see kEntry*
+  const uint32_t* unc_ctx;   // parallel to unc_list: the entry's class in each context of its node's rule; see kCtx*
   int32_t n_nodes;
 };
 
@@ -110,12 +111,23 @@ struct DevCache {
 //   bits 24..31  second byte of the suffix (0 if there is none; kEntryFullWalk: 0)
 // Entries of a (node, chunk) list are sorted by the length of what remains to be walked.
 constexpr uint32_t kEntrySuffix2 = 13, kEntrySuffix1 = 14, kEntryFullWalk = 15;
+// Beside every entry sits a word of per-context classes (section 3.2 taken per
+// call site): a frame of rule R can only sit on one of the few nodes that
+// follow a reference to R (Automaton::contexts).  For a rule with at most
+// kCtxMax of them, bits 2i..2i+1 of the word say what the entry's suffix does
+// when it is walked from context node i with nothing known below it:
+// kCtxReject, kCtxWalk (it leaves that frame too, or the walk hit a limit:
+// decide at run time) or kCtxAccept.  Rules with more contexts, and entries
+// of kind kEntryFullWalk, have kCtxWalk everywhere.
+constexpr uint32_t kCtxMax = 16, kCtxReject = 0, kCtxWalk = 1, kCtxAccept = 2;
+constexpr uint32_t kCtxNone = 0xFFFFFFFFu;  // stack header: the frame below is not a listed context
 
 // per-step upload of the live stacks: [RowDesc x B][stack headers][frames][FillBlock x n_blocks]
 struct RowDesc {
   DevTables tab;             // the request's grammar (copied in, so that a workgroup needs no further lookup)
   const uint32_t* acc;       // DevCache::acc
   const uint32_t* unc_list;  // DevCache::unc_list
+  const uint32_t* unc_ctx;   // DevCache::unc_ctx
   uint32_t stack_begin;      // first stack header of this request
   uint32_t n_stacks;         // 0: terminated row (only stop bits)
   uint32_t flags;            // bit 0: the text so far is a complete sentence
@@ -124,11 +136,12 @@ struct RowDesc {
 // A stack header is kStackHdrWords + n_chunk + 1 uint32 words:
 //   [kStackHdrTop] top node, [kStackHdrDepth] number of frames,
 //   [kStackHdrFrames] offset of its frames (bottom first) in the uint16 frame array,
+//   [kStackHdrCtx] index of the node below the top frame among the contexts of the top node's rule, or kCtxNone,
 //   [kStackHdrFirst .. +8) 256-bit set of the bytes that can be consumed from this stack,
 //   [kStackHdrBelow .. +8) the same for the stack without its top frame,
 //   [kStackHdrWords + c] offset of chunk c's context-dependent list of the top node
 //   (c = 0 .. n_chunk; entry n_chunk is the end of the last list).
-constexpr uint32_t kStackHdrTop = 0, kStackHdrDepth = 1, kStackHdrFrames = 2, kStackHdrFirst = 4, kStackHdrBelow = 12,
+constexpr uint32_t kStackHdrTop = 0, kStackHdrDepth = 1, kStackHdrFrames = 2, kStackHdrCtx = 3, kStackHdrFirst = 4, kStackHdrBelow = 12,
                    kStackHdrWords = 20;
 
 // One workgroup of the fill kernel: request `row`, chunks [c0, c1) of its
@@ -167,8 +180,10 @@ void launch_count_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_
 void launch_list_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_id, const uint32_t* off,
                            uint32_t* list, hipStream_t stream);
 // find each entry's exit position (a walk per entry) and sort every (node, chunk) list by remaining length
+// ctx_off [n_rules+1], ctx_node: the contexts of every rule that has at most kCtxMax (others: empty range)
 void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n, const uint32_t* off,
-                           uint32_t* list, hipStream_t stream);
+                           uint32_t* list, uint32_t* list_ctx, const uint32_t* ctx_off, const uint16_t* ctx_node,
+                           hipStream_t stream);
 // set / clear single bits of rank-space rows: items = (node - node0, rank, class)
 void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items,
                           uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank, hipStream_t stream);

@@ -351,6 +351,38 @@ def test_next_byte_sets_match_oracle(name):
         assert om.advance(toks[t])
 
 
+@pytest.mark.parametrize("name", ["arith", "json", "csql", "schema"])
+def test_frame_below_is_always_a_listed_context(name):
+    """Along random walks, the node below the top frame of every stack is one
+    of the contexts the compiler lists for the top node's rule."""
+    text, root, _ = GRAMMARS[name]
+    vocab = si.make_vocab("arith", 1024, 0) if name == "arith" else si.make_vocab("bpe", 4000, 3)
+    toks = vocab.tokens()
+    first = np.array([t[0] if t else -1 for t in toks], dtype=np.int16)
+    g = xgm.Grammar(text, root)
+    og = oracle.Grammar(text, root)
+    v = xgm.Vocab(vocab.data, vocab.offsets, vocab.stop_ids)
+    seen = 0
+    for seed in range(3):
+        m = xgm.Matcher(grammar=g, vocab=v)
+        om = oracle.EarleyMatcher(og)
+        rng = np.random.Generator(np.random.PCG64(zlib.crc32(name.encode()) + 31 * seed))
+        for step in range(40):
+            for s in range(m.num_stacks()):
+                st = m.stack(s)
+                if len(st) >= 2:
+                    idx = g.debug_context_index(st[-1], st[-2])
+                    assert idx >= 0 or idx == -1001, (name, seed, step, st)
+                    seen += 1
+            want = om.mask(vocab)
+            t = si.pick_token(rng, want, first, vocab.stop_ids, structural_bias=0.4)
+            if t < 0 or t == int(vocab.stop_ids[0]):
+                break
+            m.accept_token(t)
+            assert om.advance(toks[t])
+    assert seen > 10
+
+
 def test_kernel_walk_reports_overflow_instead_of_guessing():
     g = xgm.Grammar(si.ARITH_GRAMMAR, "expr")
     start = [n for n in range(g.num_nodes) if g.rule_name(g.node_rule(n)) == "expr" and g.node_path(n) == []][0]
