@@ -286,24 +286,26 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
     }
     uint32_t exits = 0;
     const int res = walk_token<true>(T, tk, ext, len, (uint32_t)node, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node), 0, &exits);
-    uint32_t meta = kEntryFullWalk, pos = 0;
-    if (res != kOverflow && exits != 0u && (exits & (exits - 1u)) == 0u && !(exits & 0x8000u)) {
-      const uint32_t k = __ffs(exits) - 1;  // the single exit position, 0..14
+    uint32_t meta = kEntryFullWalk, pos = 0, late = 0;
+    if (res != kOverflow && exits != 0u && (exits & (exits - 1u)) == 0u && !(exits & 0x80000000u)) {
+      const uint32_t k = __ffs(exits) - 1;  // the single exit position, 0..30
       const uint32_t suffix = (uint32_t)len - k;
       if (suffix == 1u) { meta = kEntrySuffix1; pos = k; }
       else if (suffix == 2u) { meta = kEntrySuffix2; pos = k; }
       else if (k <= 12u) { meta = k; pos = k; }
+      else late = k;                        // kind stays kEntryFullWalk, the position goes into the second byte field
     }
     const uint32_t b1 = token_byte(tk, ext, (int)pos);
-    const uint32_t b2 = (meta != kEntryFullWalk && (int)pos + 1 < len) ? token_byte(tk, ext, (int)pos + 1) : 0u;
-    const uint32_t rem = min(15, len - (int)pos);
+    const uint32_t b2 = meta == kEntryFullWalk ? late : ((int)pos + 1 < len ? token_byte(tk, ext, (int)pos + 1) : 0u);
+    const int from = (int)(late ? late : pos);  // where the suffix starts
+    const uint32_t rem = min(15, len - from);
     // what the suffix does in each context of the node's rule, with nothing known below that context
     uint32_t classes = 0u;
     for (uint32_t i = 0; i < kCtxMax; ++i) {
       uint32_t code = kCtxWalk;
-      if (meta != kEntryFullWalk && i < n_ctx) {
+      if ((meta != kEntryFullWalk || late) && i < n_ctx) {
         const uint32_t r = ctx_node[ctx0 + i];
-        const int c = walk_token<true>(T, tk, ext, len, r, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r), (int)pos);
+        const int c = walk_token<true>(T, tk, ext, len, r, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r), from);
         code = c == kAccept ? kCtxAccept : (c == kUncertain || c == kOverflow) ? kCtxWalk : kCtxReject;
       }
       classes |= code << (2u * i);
@@ -393,7 +395,7 @@ struct LdsSetAcc {
 // *step_counter (instrumentation for the benchmark; never used on the hot path).
 struct FillShared {
   uint32_t words[kFillMaxChunks * kChunkWords];
-  uint32_t queue[kFillQueue];     // (chunk - c0) << 16 | exit position << 12 | local id
+  uint32_t queue[kFillQueue];     // late exit position << 24 | (chunk - c0) << 16 | kind << 12 | local id
   uint16_t live[kFillFramesLds];
   uint32_t hdr[kStackHdrWords];   // the current stack's header: top, depth, frame offset, and 2 x 256 bits: the
                                   // bytes consumable from the stack / from the stack without its top frame
@@ -454,7 +456,7 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
       for (uint32_t j = j_begin + (tid & ~63u); j < j_end; j += kFillThreads) {
         const uint32_t jj = j + lane;
         bool keep = false;
-        uint32_t lid = 0, meta = 0, cl = 0;
+        uint32_t lid = 0, meta = 0, cl = 0, late_exit = 0;
         if (jj < j_end) {
           const uint32_t e = unc_list[jj];
           const uint32_t in_ctx = ctx != kCtxNone ? (unc_ctx[jj] >> (2u * ctx)) & 3u : kCtxWalk;
@@ -471,7 +473,15 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
           const uint32_t b1 = (e >> 16) & 0xFFu, b2 = e >> 24;
           const bool seen = (wchunk[lid >> 5] >> (lid & 31)) & 1u;  // already allowed through another stack
           if (meta == kEntryFullWalk) {
-            keep = !seen && ((first_ok[b1 >> 5] >> (b1 & 31)) & 1u);
+            // b2 != 0: a single exit at position b2 after all; the context class may settle it
+            const bool ok0 = (first_ok[b1 >> 5] >> (b1 & 31)) & 1u;
+            const bool has_exit = b2 != 0u && depth >= 2u;
+            if (has_exit && in_ctx != kCtxWalk) {
+              if (!seen && ok0 && in_ctx == kCtxAccept) atomicOr(&wchunk[lid >> 5], 1u << (lid & 31));
+            } else {
+              keep = !seen && ok0;
+              late_exit = has_exit ? b2 : 0u;
+            }
           } else {
             const bool ok1 = (first_ok[8 + (b1 >> 5)] >> (b1 & 31)) & 1u;
             const bool ok2 = use_pair ? ((sm.pair[b1 * 8u + (b2 >> 5)] >> (b2 & 31)) & 1u) : ok1;
@@ -489,7 +499,8 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
           uint32_t base = 0;
           if (lane == 0) base = atomicAdd(&sm.queue_n, (uint32_t)__popcll(m));
           base = __shfl(base, 0, 64);
-          if (keep) sm.queue[base + __popcll(m & ((1ull << lane) - 1ull))] = (cl << 16) | (meta << 12) | lid;
+          if (keep)
+            sm.queue[base + __popcll(m & ((1ull << lane) - 1ull))] = (late_exit << 24) | (cl << 16) | (meta << 12) | lid;
         }
       }
       __syncthreads();
@@ -497,7 +508,7 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
       const uint32_t nq = sm.queue_n;
       for (uint32_t q = tid; q < nq; q += kFillThreads) {
         const uint32_t e = sm.queue[q];
-        const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, cl = e >> 16;
+        const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, cl = (e >> 16) & 0xFFu, late_exit = e >> 24;
         const int32_t id = (c0 + (int32_t)cl) * kChunkTokens + (int32_t)lid;
         const uint4 tk = voc.tok_by_id[id];
         int len = (int)(tk.w >> 24);
@@ -508,8 +519,8 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
         }
         uint32_t n_steps = 0;
         // a token with a single exit continues right there, in the frame below the top
-        const bool full = meta == kEntryFullWalk;
-        const int i0 = full ? 0 : (meta == kEntrySuffix2 ? len - 2 : (int)meta);
+        const bool full = meta == kEntryFullWalk && late_exit == 0u;
+        const int i0 = full ? 0 : late_exit ? (int)late_exit : (meta == kEntrySuffix2 ? len - 2 : (int)meta);
         const int res = walk_token<false>(T, tk, ext, len, full ? top : below, live, full ? depth : depth - 1,
                                           COUNT ? &n_steps : nullptr, (const uint32_t*)nullptr, i0);
         if (COUNT) my_steps += n_steps;

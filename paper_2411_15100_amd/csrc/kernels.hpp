@@ -106,9 +106,10 @@ struct DevCache {
 //   bits  0..11  token id - chunk * 4096
 //   bits 12..15  kind: 0..12 = k, the suffix has three or more bytes;
 //                kEntrySuffix2 / kEntrySuffix1 = the suffix has two bytes / one byte (k = length - that);
-//                kEntryFullWalk = several such positions, or k > 12 with a longer suffix: walk from the node
+//                kEntryFullWalk = several such positions (walk from the node), or k > 12 with a longer suffix
 //   bits 16..23  first byte of the suffix (kEntryFullWalk: of the token)
-//   bits 24..31  second byte of the suffix (0 if there is none; kEntryFullWalk: 0)
+//   bits 24..31  second byte of the suffix (0 if there is none); kEntryFullWalk: k if there is a single
+//                exit position after all (13..30), else 0
 // Entries of a (node, chunk) list are sorted by the length of what remains to be walked.
 constexpr uint32_t kEntrySuffix2 = 13, kEntrySuffix1 = 14, kEntryFullWalk = 15;
 // Beside every entry sits a word of per-context classes (section 3.2 taken per

@@ -101,7 +101,7 @@ XGM_HD uint32_t token_byte(const uint4& tk, const uint8_t* ext, int i) { return 
 // kOverflow: a limit was hit; the caller records the pair.
 // `steps_out` (may be null) receives the number of automaton steps taken.
 // `i0`: index of the first byte to consume (the walk may start inside the token).
-// `exits_out` (BUILD only, may be null): bit min(k, 15) is set for every
+// `exits_out` (BUILD only, may be null): bit min(k, 31) is set for every
 // position k at which the start frame is left in front of a byte of `follow`.
 // `Live` is anything indexable that yields the live frames (a plain pointer,
 // or a view that knows which of them sit in LDS).
@@ -172,7 +172,7 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
               left_frame = true;
               if ((follow[c >> 5] >> (c & 31)) & 1u) {
                 left_frame_follow = true;
-                if (exits_out) *exits_out |= 1u << (i < 15 ? i : 15);
+                if (exits_out) *exits_out |= 1u << (i < 31 ? i : 31);
               }
             }
             ok = false;
