@@ -233,6 +233,18 @@ int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int
  * xgm_fill_overflow_fixup() decides it exactly. */
 int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask,
                                 void* hip_stream);
+/* 4 + 5 in one launch (asynchronous): fills d_bitmask exactly as
+ * xgm_fill_next_token_bitmask does and applies row b of the result to logits
+ * row b as xgm_apply_token_bitmask_inplace does (section 2.1): d_logits is
+ * [B, V_logits] of dt (device), V_logits >= the vocabulary size (wider columns
+ * are masked), row stride row_stride_elems; the base address and the row pitch
+ * must be multiples of 16 bytes (XGM_ERR_BAD_ARG otherwise: use the two
+ * calls).  A token whose walk exceeded the on-chip limits is left allowed
+ * (bit set, logit untouched) by this call; if xgm_overflow_total() moved,
+ * xgm_fill_overflow_fixup() makes the bitmask exact and the caller applies it
+ * once more with xgm_apply_token_bitmask_inplace. */
+int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* d_logits, xgm_dtype dt,
+                       int32_t V_logits, int64_t row_stride_elems, void* hip_stream);
 /* Instrumentation for benchmarks: the same fill (same result in d_bitmask)
  * with a kernel instantiation that also counts the automaton steps of all
  * walks; synchronous; *h_steps receives the count.  Not for the hot path. */
@@ -243,7 +255,7 @@ int xgm_debug_fill_count_steps(xgm_matcher* const* ms, int32_t B, int32_t* d_bit
  * of the stack upload kernel, h_us2[1] = of the fill kernel (host array of 2). */
 int xgm_debug_fill_timed(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream, float* h_us2);
 /* Synchronises hip_stream, then decides on the host every pair recorded by
- * the most recent fill and patches that fill's d_bitmask.  Returns the number
+ * the most recent fill and writes the exact bits into that fill's d_bitmask.  Returns the number
  * of pairs handled (>= 0) or a negative status.  Costs one stream
  * synchronisation; callers that never see a non-zero xgm_overflow_total() may
  * skip it. */

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     fill_next_token_bitmask,
     fill_overflow_fixup,
     debug_fill_count_steps,
+    fill_and_apply,
     debug_fill_timed,
     MatcherBatch,
     overflow_total,

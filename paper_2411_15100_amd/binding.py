@@ -63,6 +63,7 @@ SIGNATURES = {
     "xgm_matcher_num_stacks": (_i32, [_vp]),
     "xgm_matcher_stack": (_i32, [_vp, _i32, _vp, _i32]),
     "xgm_fill_next_token_bitmask": (_i32, [_vp, _i32, _vp, _vp]),
+    "xgm_fill_and_apply": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
     "xgm_debug_fill_count_steps": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_debug_fill_timed": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_fill_overflow_fixup": (_i32, [_vp]),
@@ -332,6 +333,15 @@ class MatcherBatch:
     def fill_next_token_bitmask(self, d_bitmask: int, stream: int = 0):
         _check(load_library().xgm_fill_next_token_bitmask(self._arr, len(self.matchers), ctypes.c_void_p(d_bitmask),
                                                           ctypes.c_void_p(stream)))
+
+
+def fill_and_apply(matchers, d_bitmask: int, d_logits: int, dtype: int, v_logits: int, row_stride: int,
+                   stream: int = 0):
+    """Fill the bitmask and mask the logits in one launch (rows 16-byte aligned)."""
+    batch = matchers if isinstance(matchers, MatcherBatch) else MatcherBatch(matchers)
+    _check(load_library().xgm_fill_and_apply(batch._arr, len(batch.matchers), ctypes.c_void_p(d_bitmask),
+                                             ctypes.c_void_p(d_logits), int(dtype), int(v_logits), int(row_stride),
+                                             ctypes.c_void_p(stream)))
 
 
 def debug_fill_count_steps(batch: "MatcherBatch", d_bitmask: int, stream: int = 0) -> int:

@@ -744,8 +744,17 @@ int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int
 // ---------------------------------------------------------------------- fill
 // `timing` (may be null): three events recorded on the stream before the upload
 // kernel, between the two kernels and after the fill kernel.
+// `fused` (may be null): logits to mask in the same launch.
+struct FusedLogits {
+  void* d_logits;
+  int esize;
+  uint32_t neg_inf;
+  int32_t V_logits;
+  int64_t row_stride;
+};
 static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream,
-                     unsigned long long* d_step_counter, hipEvent_t* timing = nullptr) {
+                     unsigned long long* d_step_counter, hipEvent_t* timing = nullptr,
+                     const FusedLogits* fused = nullptr) {
   API_BEGIN
   if (!ms || B <= 0 || !d_bitmask) return fail(XGM_ERR_BAD_ARG, "fill: null argument or empty batch");
   xgm_vocab* v = nullptr;
@@ -899,7 +908,9 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
               reinterpret_cast<const uint32_t*>((char*)slot.d_buf + off_stacks),
               reinterpret_cast<const uint16_t*>((char*)slot.d_buf + off_frames),
               reinterpret_cast<const FillBlock*>((char*)slot.d_buf + off_plan), n_blocks, v->dv,
-              reinterpret_cast<uint32_t*>(d_bitmask), log, seq, d_step_counter, stream);
+              reinterpret_cast<uint32_t*>(d_bitmask), log, seq, d_step_counter, stream,
+              fused ? fused->d_logits : nullptr, fused ? fused->esize : 0, fused ? fused->neg_inf : 0u,
+              fused ? fused->V_logits : 0, fused ? fused->row_stride : 0);
   HIP_OK(hipGetLastError());
   if (timing) HIP_OK(hipEventRecord(timing[2], stream));
   HIP_OK(hipEventRecord(slot.done, stream));
@@ -917,6 +928,26 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
 
 int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream) {
   return fill_impl(ms, B, d_bitmask, hip_stream, nullptr);
+}
+
+int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* d_logits, xgm_dtype dt,
+                       int32_t V_logits, int64_t row_stride_elems, void* hip_stream) {
+  API_BEGIN
+  if (!d_logits) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: null logits");
+  if (!ms || B <= 0 || !ms[0] || !ms[0]->v) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: null argument or empty batch");
+  if (V_logits < ms[0]->v->V) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: logits rows are narrower than the vocabulary");
+  if (row_stride_elems < V_logits) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: row stride smaller than the row");
+  FusedLogits f{d_logits, 0, 0u, V_logits, row_stride_elems};
+  switch (dt) {
+    case XGM_F32: f.esize = 4; f.neg_inf = 0xFF800000u; break;
+    case XGM_BF16: f.esize = 2; f.neg_inf = 0xFF80u; break;
+    case XGM_F16: f.esize = 2; f.neg_inf = 0xFC00u; break;
+    default: return fail(XGM_ERR_BAD_ARG, "fill_and_apply: unknown dtype");
+  }
+  if (reinterpret_cast<uintptr_t>(d_logits) % 16 != 0 || (row_stride_elems * f.esize) % 16 != 0)
+    return fail(XGM_ERR_BAD_ARG, "fill_and_apply: logits rows must be 16-byte aligned (use the two separate calls)");
+  return fill_impl(ms, B, d_bitmask, hip_stream, nullptr, nullptr, &f);
+  API_END
 }
 
 int xgm_debug_fill_count_steps(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream,
@@ -1008,11 +1039,11 @@ int xgm_fill_overflow_fixup(void* hip_stream) {
       if (rc == XGM_OK) ok = true;
       else if (rc != XGM_ERR_TOKEN_REJECTED) return fail(rc, "fixup: a token walk exceeds the host limits too");
     }
-    if (ok) {
+    {  // the exact bit, either way (a fused fill leaves such a token allowed until now)
       uint32_t word = 0;
       int32_t* p = C.last_bitmask + (size_t)b * W + (id >> 5);
       HIP_OK(hipMemcpy(&word, p, 4, hipMemcpyDeviceToHost));
-      word |= 1u << (id & 31);
+      if (ok) word |= 1u << (id & 31); else word &= ~(1u << (id & 31));
       HIP_OK(hipMemcpy(p, &word, 4, hipMemcpyHostToDevice));
     }
     ++handled;

@@ -345,6 +345,38 @@ __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ 
   }
 }
 
+// One 16-byte group of a logits row (section 2.1): `mk` holds the mask bits of
+// its EPT = 16 / ESIZE elements, e0 is the index of its first element.  All
+// allowed: nothing is touched.  None allowed: one 16-byte store of the -inf
+// pattern.  Mixed: only the disallowed elements are stored (pairs of 16-bit
+// elements as one 32-bit store where both go).  The logits are never read:
+// the bytes that stay are simply not written.
+template <int ESIZE>
+__device__ __forceinline__ void apply_group(unsigned char* p, uint32_t mk, int32_t e0, int32_t V_logits, uint32_t neg_inf) {
+  constexpr int EPT = 16 / ESIZE;
+  constexpr uint32_t kAll = (1u << EPT) - 1u;
+  if (mk == kAll) return;
+  const uint32_t two = neg_inf | (neg_inf << 16);
+  if (mk == 0u && e0 + EPT <= V_logits) {
+    *reinterpret_cast<uint4*>(p) = ESIZE == 2 ? make_uint4(two, two, two, two) : make_uint4(neg_inf, neg_inf, neg_inf, neg_inf);
+  } else if (ESIZE == 2) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const uint32_t b = (mk >> (2 * h)) & 3u;
+      if (e0 + 2 * h + 1 < V_logits && b == 0u) {
+        reinterpret_cast<uint32_t*>(p)[h] = two;
+      } else {
+        if (e0 + 2 * h < V_logits && !(b & 1u)) reinterpret_cast<uint16_t*>(p)[2 * h] = (uint16_t)neg_inf;
+        if (e0 + 2 * h + 1 < V_logits && !(b & 2u)) reinterpret_cast<uint16_t*>(p)[2 * h + 1] = (uint16_t)neg_inf;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int h = 0; h < EPT; ++h)
+      if (e0 + h < V_logits && !((mk >> h) & 1u)) reinterpret_cast<uint32_t*>(p)[h] = neg_inf;
+  }
+}
+
 // ---------------------------------------------------------------- kernel (b)
 // The per-step stack upload: a plain copy from pinned host memory (which the
 // device reads over the bus) into device memory, as a kernel on the caller's
@@ -404,7 +436,7 @@ struct FillShared {
   uint32_t queue_n;
 };
 
-template <bool COUNT, class Tab>
+template <bool COUNT, bool KEEP_UNDECIDED, class Tab>
 __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b,
                                            const int32_t c0, const int32_t c1, const uint32_t frame0,
                                            const bool frames_in_lds,
@@ -525,7 +557,10 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
                                           COUNT ? &n_steps : nullptr, (const uint32_t*)nullptr, i0);
         if (COUNT) my_steps += n_steps;
         if (res == kAccept) atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
-        else if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, (uint32_t)id);
+        else if (res == kOverflow) {
+          record_overflow(log, seq, (uint32_t)b, (uint32_t)id);
+          if (KEEP_UNDECIDED) atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
+        }
       }
       __syncthreads();
       if (tid == 0) sm.queue_n = 0u;
@@ -538,13 +573,25 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
 // Two workgroups of 16 waves per compute unit need 8 waves per SIMD: the second
 // launch bound keeps the kernel within the 96 scalar and 64 vector registers
 // per wave that this takes.
-template <bool COUNT>
+// APPLY = 0: the mask only.  APPLY = 2 / 4 (bytes per logit): the workgroup
+// also writes -inf into the logits of its (row, chunk range) straight from its
+// LDS words (section 2.1), which saves a launch and the re-read of the mask.
+// A token whose walk exceeded the limits is then left allowed (bit set, logit
+// untouched) until the host has decided it.
+struct FusedApply {
+  unsigned char* logits;  // [B][row_stride] elements of APPLY bytes; 16-byte aligned rows
+  int64_t row_stride;     // elements
+  int32_t V_logits;
+  uint32_t neg_inf;
+};
+
+template <bool COUNT, int APPLY>
 __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __restrict__ rows,
                                                             const uint32_t* __restrict__ stack_hdrs_,
                                                             const uint16_t* __restrict__ frames_,
                                                             const FillBlock* __restrict__ plan, DevVocab voc,
                                                             uint32_t* __restrict__ out, OverflowLog* log, uint32_t seq,
-                                                            unsigned long long* step_counter) {
+                                                            unsigned long long* step_counter, FusedApply fa) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ FillShared sm;
   const XGM_GLOBAL uint32_t* stack_hdrs = (const XGM_GLOBAL uint32_t*)stack_hdrs_;
@@ -585,11 +632,11 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   __syncthreads();
   if (has_cache) {
     if (rd.tab.stage_bytes)
-      fill_lists<COUNT>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc, log, seq,
-                        my_steps);
+      fill_lists<COUNT, (APPLY != 0)>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames,
+                                      voc, log, seq, my_steps);
     else
-      fill_lists<COUNT>(CompactTab{tv}, sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc, log, seq,
-                        my_steps);
+      fill_lists<COUNT, (APPLY != 0)>(CompactTab{tv}, sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc,
+                                      log, seq, my_steps);
   }
   if (rd.flags & 1u) {
     for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
@@ -599,6 +646,22 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   }
   __syncthreads();
   for (int32_t w = tid; w < n_words; w += kFillThreads) out[(size_t)b * voc.W + w_begin + w] = sm.words[w];
+  if (APPLY != 0) {
+    constexpr int EPT = 16 / (APPLY ? APPLY : 2);
+    constexpr uint32_t kAll = (1u << EPT) - 1u;
+    // this workgroup's logits: its chunks; the last workgroup of a row also takes the columns beyond the vocabulary
+    const int32_t e_begin = w_begin * 32;
+    const int32_t e_end = c1 == voc.n_chunk ? fa.V_logits : min(c1 * kChunkTokens, fa.V_logits);
+    unsigned char* lrow = fa.logits + (size_t)b * fa.row_stride * (APPLY ? APPLY : 2);
+    for (int32_t e0 = e_begin + (int32_t)tid * EPT; e0 < e_end; e0 += kFillThreads * EPT) {
+      uint32_t mk = 0u;
+      if (e0 < voc.V) {
+        mk = (sm.words[(e0 - e_begin) >> 5] >> (e0 & 31)) & kAll;
+        if (e0 + EPT > voc.V) mk &= (1u << (voc.V - e0)) - 1u;
+      }
+      apply_group<(APPLY ? APPLY : 2)>(lrow + (size_t)e0 * (APPLY ? APPLY : 2), mk, e0, fa.V_logits, fa.neg_inf);
+    }
+  }
   if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
 }
 
@@ -607,11 +670,8 @@ constexpr int kApplyThreads = 256;
 
 // Section 2.1: logits of disallowed tokens become -inf.  A thread owns one
 // group: 16 bytes of a logits row (8 bf16/fp16 or 4 fp32 elements) with its
-// mask bits; the 64 groups of a wave are contiguous (1 KiB).  All allowed:
-// nothing is touched.  None allowed: one 16-byte store of the -inf pattern.
-// Mixed: only the disallowed elements are stored (pairs of 16-bit elements as
-// one 32-bit store where both go).  The logits are never read: the bytes that
-// stay are simply not written.  ESIZE = bytes per element.
+// mask bits; the 64 groups of a wave are contiguous (1 KiB); see apply_group.
+// ESIZE = bytes per element.
 template <int ESIZE>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(unsigned char* __restrict__ logits, int64_t row_stride,
                                                               const uint32_t* __restrict__ bitmask, int32_t W_mask,
@@ -628,27 +688,7 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(unsigned char* __r
     mk = (bitmask[(size_t)j * W_mask + (e0 >> 5)] >> (e0 & 31)) & kAll;
     if (e0 + EPT > V_mask) mk &= (1u << (V_mask - e0)) - 1u;
   }
-  if (mk == kAll) return;
-  unsigned char* p = logits + ((size_t)lrow * row_stride + e0) * ESIZE;
-  const uint32_t two = neg_inf | (neg_inf << 16);
-  if (mk == 0u && e0 + EPT <= V_logits) {
-    *reinterpret_cast<uint4*>(p) = ESIZE == 2 ? make_uint4(two, two, two, two) : make_uint4(neg_inf, neg_inf, neg_inf, neg_inf);
-  } else if (ESIZE == 2) {
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const uint32_t b = (mk >> (2 * h)) & 3u;
-      if (e0 + 2 * h + 1 < V_logits && b == 0u) {
-        reinterpret_cast<uint32_t*>(p)[h] = two;
-      } else {
-        if (e0 + 2 * h < V_logits && !(b & 1u)) reinterpret_cast<uint16_t*>(p)[2 * h] = (uint16_t)neg_inf;
-        if (e0 + 2 * h + 1 < V_logits && !(b & 2u)) reinterpret_cast<uint16_t*>(p)[2 * h + 1] = (uint16_t)neg_inf;
-      }
-    }
-  } else {
-#pragma unroll
-    for (int h = 0; h < EPT; ++h)
-      if (e0 + h < V_logits && !((mk >> h) & 1u)) reinterpret_cast<uint32_t*>(p)[h] = neg_inf;
-  }
+  apply_group<ESIZE>(logits + ((size_t)lrow * row_stride + e0) * ESIZE, mk, e0, V_logits, neg_inf);
 }
 
 // any alignment, any stride: one element per thread
@@ -726,15 +766,23 @@ void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t 
 
 void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,
                  const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log,
-                 uint32_t seq, unsigned long long* step_counter, hipStream_t stream) {
+                 uint32_t seq, unsigned long long* step_counter, hipStream_t stream, void* logits, int elem_size,
+                 uint32_t neg_inf, int32_t V_logits, int64_t row_stride) {
   if (n_blocks <= 0) return;
   const dim3 grid(n_blocks);
-  if (step_counter)
-    hipLaunchKernelGGL(fill_kernel<true>, grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
-                       plan, voc, out, log, seq, step_counter);
+  const FusedApply fa{static_cast<unsigned char*>(logits), row_stride, V_logits, neg_inf};
+  if (logits && elem_size == 2)
+    hipLaunchKernelGGL((fill_kernel<false, 2>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
+                       plan, voc, out, log, seq, step_counter, fa);
+  else if (logits)
+    hipLaunchKernelGGL((fill_kernel<false, 4>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
+                       plan, voc, out, log, seq, step_counter, fa);
+  else if (step_counter)
+    hipLaunchKernelGGL((fill_kernel<true, 0>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
+                       plan, voc, out, log, seq, step_counter, fa);
   else
-    hipLaunchKernelGGL(fill_kernel<false>, grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
-                       plan, voc, out, log, seq, step_counter);
+    hipLaunchKernelGGL((fill_kernel<false, 0>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
+                       plan, voc, out, log, seq, step_counter, fa);
 }
 
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,

@@ -191,10 +191,13 @@ void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_
 // copy `bytes` (rounded up to 16; both buffers must hold that) from device-visible pinned host memory
 void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t stream);
 // (b) batched mask fill
-// step_counter: null on the hot path; otherwise the counting instantiation is launched
+// step_counter: null on the hot path; otherwise the counting instantiation is launched.
+// logits != null: the fused instantiation also applies each row's mask to its logits row
+// (elem_size 2 or 4, rows 16-byte aligned; a walk over the limits leaves its token allowed).
 void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,
-                 const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log, uint32_t seq,
-                 unsigned long long* step_counter, hipStream_t stream);
+                 const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log,
+                 uint32_t seq, unsigned long long* step_counter, hipStream_t stream, void* logits = nullptr,
+                 int elem_size = 0, uint32_t neg_inf = 0, int32_t V_logits = 0, int64_t row_stride = 0);
 // (c) apply; returns false if the buffer layout needs the element-wise kernel
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,
                   const uint32_t* bitmask, int32_t V_mask, const int32_t* row_index, int32_t n_rows,

@@ -208,6 +208,12 @@ class ServingWorkload:
         self.fill(k, stream)
         self.apply(k, stream)
 
+    def fused_step(self, k: int, stream: int):
+        """Fill and apply in one launch."""
+        t = self.logits[k % len(self.logits)]
+        xgm.fill_and_apply(self.sets[k % len(self.sets)].batch, self.d_mask.data_ptr(), t.data_ptr(), xgm.DTYPE_BF16,
+                           self.V, t.stride(0), stream=stream)
+
     def refresh_logits(self):
         """Masked entries are -inf after a step; draw the buffers again."""
         gen = torch.Generator(device="cuda")

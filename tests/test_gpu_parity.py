@@ -229,6 +229,66 @@ def test_workload5_distinct_grammars_batch8(xgm, wl, no_overflow):
 
 
 # --------------------------------------------------------------------------
+# fused fill + apply: same masks, same logits as the two calls / as the oracle
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype_name,V,pad", [("bf16", 4100, 0), ("f32", 4100, 0), ("f16", 4099, 13), ("bf16", 9000, 24)])
+def test_fused_fill_and_apply_matches_oracle(xgm, wl, no_overflow, dtype_name, V, pad):
+    say(f"fused fill+apply: json V={V} logits width {V + pad} {dtype_name}")
+    tdt, code, ninf, view, npv = {"f32": (torch.float32, xgm.DTYPE_F32, 0xFF800000, torch.int32, np.uint32),
+                                  "bf16": (torch.bfloat16, xgm.DTYPE_BF16, 0xFF80, torch.int16, np.uint16),
+                                  "f16": (torch.float16, xgm.DTYPE_F16, 0xFC00, torch.int16, np.uint16)}[dtype_name]
+    vocab = si.make_vocab("bpe", V, 1)
+    xv = wl.make_xgm_vocab(vocab)
+    texts = [si.JSON_GRAMMAR, si.make_schema_grammar(2, string_heavy=True), si.JSON_GRAMMAR]
+    roots = ["root"] * 3
+    caches = [xgm.Cache(xgm.Grammar(t, r), xv) for t, r in zip(texts, roots)]
+    walker = wl.BatchWalker(caches, vocab, seed=11, structural_bias=0.35)
+    oms = [oracle.EarleyMatcher(oracle.Grammar(t, r)) for t, r in zip(texts, roots)]
+    toks = vocab.tokens()
+    B, W = 3, xgm.bitmask_words(V)
+    Vl = V + pad
+    stride = ((Vl * (4 if dtype_name == "f32" else 2) + 15) // 16 * 16) // (4 if dtype_name == "f32" else 2)
+    d_mask = torch.zeros((B, W), dtype=torch.int32, device="cuda")
+    for step in range(24):
+        words = walker.fill()
+        if step % 4 == 3:
+            want = np.stack([om.mask(vocab) for om in oms])
+            buf = torch.zeros((B, stride), dtype=tdt, device="cuda")
+            buf[:, :Vl] = torch.from_numpy(si.make_logits(B, Vl, seed=900 + step)).to("cuda").to(tdt)
+            before = buf.view(view).cpu().numpy().view(npv).copy()
+            d_mask.fill_(-1)
+            xgm.fill_and_apply(walker.batch, d_mask.data_ptr(), buf.data_ptr(), code, Vl, stride, stream=_stream())
+            torch.cuda.synchronize()
+            assert np.array_equal(d_mask.cpu().numpy(), oracle.pack_bitmask(want)), f"step {step}"
+            after = buf.view(view).cpu().numpy().view(npv)
+            expect = before.copy()
+            expect[:, :Vl] = oracle.apply_mask(before[:, :Vl], want, ninf)
+            assert np.array_equal(after, expect), f"step {step}"      # the padding of the rows is untouched, too
+        picks = walker.step(words)
+        for b in range(B):
+            if not walker.history[b]:
+                oms[b] = oracle.EarleyMatcher(oracle.Grammar(texts[b], roots[b]))
+            else:
+                assert oms[b].advance(toks[int(picks[b])])
+
+
+def test_fused_fill_and_apply_argument_errors(xgm, wl):
+    vocab = si.make_vocab("arith", 1024, 0)
+    cache = xgm.Cache(xgm.Grammar(si.ARITH_GRAMMAR, "expr"), wl.make_xgm_vocab(vocab))
+    m = xgm.Matcher(cache=cache)
+    d_mask = torch.zeros((1, 32), dtype=torch.int32, device="cuda")
+    buf = torch.zeros((1, 1040), dtype=torch.float32, device="cuda")
+    with pytest.raises(xgm.XgmError):      # rows narrower than the vocabulary
+        xgm.fill_and_apply([m], d_mask.data_ptr(), buf.data_ptr(), xgm.DTYPE_F32, 1000, 1040, stream=_stream())
+    with pytest.raises(xgm.XgmError):      # misaligned base
+        xgm.fill_and_apply([m], d_mask.data_ptr(), buf.data_ptr() + 4, xgm.DTYPE_F32, 1024, 1032, stream=_stream())
+    with pytest.raises(xgm.XgmError):      # row pitch not a multiple of 16 bytes
+        xgm.fill_and_apply([m], d_mask.data_ptr(), buf.data_ptr(), xgm.DTYPE_F32, 1024, 1025, stream=_stream())
+    with pytest.raises(xgm.XgmError):
+        xgm.fill_and_apply([m], d_mask.data_ptr(), 0, xgm.DTYPE_F32, 1024, 1024, stream=_stream())
+
+
+# --------------------------------------------------------------------------
 # apply: dtypes, ragged sizes, row subsets, strides, special values
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype_name", ["f32", "bf16", "f16"])
@@ -391,3 +451,56 @@ def test_walk_limits_are_reported_and_fixed_up_exactly(xgm, wl):
     assert np.array_equal(got[0], oracle.pack_bitmask(om.mask(V_)))
     say(f"  build: {cache.host_classified} pairs on the host; fill: {n_fixed} pairs fixed up; "
         f"log grew by {xgm.overflow_total() - before}")
+
+
+def test_fused_path_leaves_undecided_tokens_allowed_until_the_fixup(xgm, wl):
+    """Walks over the on-chip limits in the fused call: the token's logit is
+    left untouched and its bit set; the fixup then writes the exact bit, set
+    (token 4, allowed) or cleared (token 5, not allowed), and a second apply
+    finishes the logits."""
+    deep = b")+" + b"(" * 30          # closes one level, then opens 30: more than 64 frames in one token
+    toks = [b"1", b"(", b")", b"+", deep, deep + b"+", b"1" * 20, b")" * 40, b""]
+    V = len(toks)
+
+    class V_:
+        data = np.frombuffer(b"".join(toks), dtype=np.uint8).copy()
+        offsets = np.concatenate([[0], np.cumsum([len(t) for t in toks])]).astype(np.int64)
+        stop_ids = np.array([8], dtype=np.int32)
+
+    xv = xgm.Vocab(V_.data, V_.offsets, V_.stop_ids)
+    g = xgm.Grammar(si.ARITH_GRAMMAR, "expr")
+    cache = xgm.Cache(g, xv)
+    og = oracle.Grammar(si.ARITH_GRAMMAR, "expr")
+    m = xgm.Matcher(cache=cache)
+    om = oracle.EarleyMatcher(og)
+    text = b"(" * 41 + b"1"
+    m.accept_bytes(text)
+    assert om.advance(text)
+    want = om.mask(V_)
+    assert want[4] and not want[5]
+    d = torch.zeros((1, 1), dtype=torch.int32, device="cuda")
+    logits = torch.arange(1, 17, dtype=torch.float32, device="cuda").reshape(1, 16).contiguous()
+    before = xgm.overflow_total()
+    xgm.fill_and_apply([m], d.data_ptr(), logits.data_ptr(), xgm.DTYPE_F32, 16, 16, stream=_stream())
+    torch.cuda.synchronize()
+    assert xgm.overflow_total() - before == 2
+    out = logits.cpu().numpy()[0]
+    for i in range(V):
+        if want[i] or i in (4, 5):     # allowed, or undecided so far
+            assert out[i] == float(i + 1), i
+        else:
+            assert out[i] == float("-inf"), i
+    assert np.all(out[V:] == float("-inf"))          # columns beyond the vocabulary are masked
+    assert xgm.fill_overflow_fixup(_stream()) == 2
+    assert np.array_equal(d.cpu().numpy()[0], oracle.pack_bitmask(want))
+    xgm.apply_token_bitmask_inplace(logits.data_ptr(), xgm.DTYPE_F32, 1, 16, 16, d.data_ptr(), V, stream=_stream())
+    out = logits.cpu().numpy()[0]
+    for i in range(V):
+        assert (out[i] == float(i + 1)) == bool(want[i]), i
+    # the two-call path on the same state: undecided tokens are not allowed until the fixup
+    d.zero_()
+    xgm.fill_next_token_bitmask([m], d.data_ptr(), _stream())
+    got = d.cpu().numpy()[0].copy()
+    assert not (int(got[0]) >> 4) & 1 and not (int(got[0]) >> 5) & 1
+    assert xgm.fill_overflow_fixup(_stream()) == 2
+    assert np.array_equal(d.cpu().numpy()[0], oracle.pack_bitmask(want))

@@ -68,4 +68,13 @@ def test_serving_step_full_size_sampled_rows():
     new = view.cpu().numpy().view(np.uint16)
     want = oracle.apply_mask(old, bits[:, :V].astype(bool), 0xFF80)
     assert np.array_equal(new, want)
+    # the fused call on fresh logits: same mask, same logits
+    work.refresh_logits()
+    torch.cuda.synchronize()
+    old = view.cpu().numpy().view(np.uint16).copy()
+    d_mask2 = torch.full_like(work.d_mask, -1)
+    xgm.fill_and_apply(w.batch, d_mask2.data_ptr(), t.data_ptr(), xgm.DTYPE_BF16, V, t.stride(0), stream=stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_mask2.cpu().numpy(), words)
+    assert np.array_equal(view.cpu().numpy().view(np.uint16), oracle.apply_mask(old, bits[:, :V].astype(bool), 0xFF80))
     assert xgm.overflow_total() == before
