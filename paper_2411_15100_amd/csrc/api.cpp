@@ -473,11 +473,11 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       };
       if (A.cls.size() != 256 || A.follow_words.size() != A.rule_names.size() * 8)
         throw Failure(XGM_ERR_INTERNAL, "cache_build: inconsistent automaton tables");
-      put(A.alts.data(), A.alts.size() * 4, 4);
-      tab.off_follow = put(A.follow_words.data(), A.follow_words.size() * 4, 4);
-      tab.off_targets = put(A.targets.data(), A.targets.size() * 2, 4);
+      put(A.cls.data(), 256, 4);
       tab.off_shapes = put(A.shapes.data(), A.shapes.size(), 4);
-      tab.off_cls = put(A.cls.data(), 256, 4);
+      tab.off_targets = put(A.targets.data(), A.targets.size() * 2, 4);
+      tab.off_follow = put(A.follow_words.data(), A.follow_words.size() * 4, 4);
+      tab.off_alts = put(A.alts.data(), A.alts.size() * 4, 4);
       tab.off_hdr = put(A.hdr.data(), (size_t)N * sizeof(uint2), 16);
       tab.off_first = put(A.node_first_words.data(), A.node_first_words.size() * 4, 16);
       img.resize((img.size() + 15) / 16 * 16, 0);

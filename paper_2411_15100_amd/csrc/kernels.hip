@@ -19,49 +19,44 @@ __device__ __forceinline__ void record_overflow(OverflowLog* log, uint32_t seq, 
   log->entry[slot][2] = b;
 }
 
-// Copy the staged part of a grammar's table image (its small tables and its
-// first n_near node headers) into LDS, 16 bytes per load (all threads of the
-// workgroup call this; a barrier must follow).  With stage_bytes == 0 nothing
-// is copied and the walk reads global memory.
-__device__ __forceinline__ TabView stage_tables(const DevTables& tab, unsigned char* smem, int nthreads) {
-  const unsigned char* base = reinterpret_cast<const unsigned char*>(tab.image);
-  TabView T;
-  T.hdr_far = reinterpret_cast<const uint2*>(base + tab.off_hdr);
-  T.n_cls = tab.n_cls;
-  T.n_near = (int32_t)tab.n_near;
-  if (tab.stage_bytes) {
-    uint4* dst = reinterpret_cast<uint4*>(smem);
-    for (uint32_t k = threadIdx.x; k < tab.stage_bytes / 16; k += nthreads) dst[k] = tab.image[k];
-    base = smem;
-  }
-  T.hdr_near = reinterpret_cast<const uint2*>(base + tab.off_hdr);
-  T.alts = reinterpret_cast<const uint32_t*>(base);
-  T.follow_rules = reinterpret_cast<const uint32_t*>(base + tab.off_follow);
-  T.targets = reinterpret_cast<const uint16_t*>(base + tab.off_targets);
-  T.shapes = base + tab.off_shapes;
-  T.cls = base + tab.off_cls;
-  return T;
+// Copy the staged part of a grammar's table image into LDS, 16 bytes per load
+// (all threads of the workgroup call this; a barrier must follow).
+__device__ __forceinline__ void stage_tables(const DevTables& tab, unsigned char* smem, int nthreads) {
+  uint4* dst = reinterpret_cast<uint4*>(smem);
+  for (uint32_t k = threadIdx.x; k < tab.stage_bytes / 16; k += nthreads) dst[k] = tab.image[k];
 }
 
-// The same table access as CompactTab, for tables staged by stage_tables():
-// the pointers carry their address space, so that a lookup is a handful of
-// LDS reads (a pointer that may point to LDS or to global memory would make
-// every one of them a much slower flat access).
+// The table access of the walk (same answers as CompactTab in walk.hpp) on a
+// table image of which bytes [0, lds_end) have been staged by stage_tables().
+// Every pointer carries its address space, so that a lookup in a staged
+// section is an LDS read and one in an unstaged section a global load (a
+// pointer that may point to either would make every access a much slower flat
+// one).  Sections are staged whole, so "is it in LDS" is uniform per section.
 #define XGM_LDS __attribute__((address_space(3)))
 #define XGM_GLOBAL __attribute__((address_space(1)))
 struct LdsTab {
-  const XGM_LDS unsigned char* base;  // the staged image
-  const XGM_GLOBAL unsigned long long* hdr_far;  // all headers (uint2 each), global memory
-  uint32_t n_near, n_cls, off_follow, off_targets, off_shapes, off_cls, off_hdr;
+  const XGM_LDS unsigned char* lds;     // the staged part of the image
+  const XGM_GLOBAL unsigned char* img;  // the whole image
+  uint32_t n_near, n_cls, off_shapes, off_targets, off_follow, off_alts, off_hdr;
+  bool cls_lds, shapes_lds, targets_lds, follow_lds, alts_lds;
   __device__ __forceinline__ LdsTab(const DevTables& t, unsigned char* smem)
-      : base((const XGM_LDS unsigned char*)smem),
-        hdr_far((const XGM_GLOBAL unsigned long long*)(reinterpret_cast<const unsigned char*>(t.image) + t.off_hdr)),
-        n_near(t.n_near), n_cls((uint32_t)t.n_cls), off_follow(t.off_follow), off_targets(t.off_targets),
-        off_shapes(t.off_shapes), off_cls(t.off_cls), off_hdr(t.off_hdr) {}
+      : lds((const XGM_LDS unsigned char*)smem),
+        img((const XGM_GLOBAL unsigned char*)reinterpret_cast<const unsigned char*>(t.image)),
+        n_near(t.n_near), n_cls((uint32_t)t.n_cls), off_shapes(t.off_shapes), off_targets(t.off_targets),
+        off_follow(t.off_follow), off_alts(t.off_alts), off_hdr(t.off_hdr),
+        cls_lds(t.lds_end >= 256u), shapes_lds(t.lds_end >= t.off_targets), targets_lds(t.lds_end >= t.off_follow),
+        follow_lds(t.lds_end >= t.off_alts), alts_lds(t.lds_end >= t.off_hdr) {}
+  __device__ __forceinline__ uint32_t rd8(uint32_t off, bool in_lds) const { return in_lds ? (uint32_t)lds[off] : (uint32_t)img[off]; }
+  __device__ __forceinline__ uint32_t rd16(uint32_t off, bool in_lds) const {
+    return in_lds ? (uint32_t)*(const XGM_LDS uint16_t*)(lds + off) : (uint32_t)*(const XGM_GLOBAL uint16_t*)(img + off);
+  }
+  __device__ __forceinline__ uint32_t rd32(uint32_t off, bool in_lds) const {
+    return in_lds ? *(const XGM_LDS uint32_t*)(lds + off) : *(const XGM_GLOBAL uint32_t*)(img + off);
+  }
   __device__ __forceinline__ uint2 header(uint32_t n) const {
     unsigned long long h;  // one 8-byte read
-    if (n < n_near) h = *(const XGM_LDS unsigned long long*)(base + off_hdr + n * 8u);
-    else h = hdr_far[n];
+    if (n < n_near) h = *(const XGM_LDS unsigned long long*)(lds + off_hdr + n * 8u);
+    else h = *(const XGM_GLOBAL unsigned long long*)(img + off_hdr + (size_t)n * 8u);
     return make_uint2((uint32_t)h, (uint32_t)(h >> 32));
   }
   __device__ __forceinline__ void lookup(uint32_t n, uint32_t c, uint32_t& k, uint32_t& single, uint32_t& base_out,
@@ -69,12 +64,12 @@ struct LdsTab {
     const uint2 h = header(n);
     k = 0; single = 0; base_out = 0; pooled = false;
     fin = h.y & 1u;
-    after = (*(const XGM_LDS uint32_t*)(base + off_follow + ((h.y >> 16) * 8u + (c >> 5)) * 4u) >> (c & 31)) & 1u;
+    after = (rd32(off_follow + ((h.y >> 16) * 8u + (c >> 5)) * 4u, follow_lds) >> (c & 31)) & 1u;
     if (h.y & 2u) {
-      const uint32_t cl = base[off_cls + c];
-      const uint32_t si = base[off_shapes + (h.x & 0xFFFFu) * n_cls + cl];
+      const uint32_t cl = rd8(c, cls_lds);
+      const uint32_t si = rd8(off_shapes + (h.x & 0xFFFFu) * n_cls + cl, shapes_lds);
       if (si != 0xFFu) {
-        const uint32_t a = *(const XGM_LDS uint16_t*)(base + off_targets + ((h.x >> 16) + si) * 2u);
+        const uint32_t a = rd16(off_targets + ((h.x >> 16) + si) * 2u, targets_lds);
         if (a < 0x8000u) { k = 1; single = (0xFFFFu << 16) | a; }
         else { base_out = a & 0x7FFFu; k = alt(base_out); pooled = true; }
       }
@@ -83,11 +78,13 @@ struct LdsTab {
       if (c >= lo && c <= hi) { k = 1; single = (0xFFFFu << 16) | (h.x >> 16); }
     }
   }
-  __device__ __forceinline__ uint32_t alt(uint32_t idx) const { return *(const XGM_LDS uint32_t*)(base + idx * 4u); }
+  __device__ __forceinline__ uint32_t alt(uint32_t idx) const { return rd32(off_alts + idx * 4u, alts_lds); }
   __device__ __forceinline__ bool is_final(uint32_t n) const { return header(n).y & 1u; }
   // generic pointer to the 256-bit FOLLOW set of node n's rule (read on the rare exit from the start frame)
   __device__ __forceinline__ const uint32_t* follow_of(uint32_t n) const {
-    return (const uint32_t*)(const XGM_LDS uint32_t*)(base + off_follow + (header(n).y >> 16) * 32u);
+    const uint32_t off = off_follow + (header(n).y >> 16) * 32u;
+    return follow_lds ? (const uint32_t*)(const XGM_LDS uint32_t*)(lds + off)
+                      : (const uint32_t*)(const XGM_GLOBAL uint32_t*)(img + off);
   }
 };
 
@@ -165,12 +162,9 @@ __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
     uint32_t* __restrict__ unc_rank, uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
     OverflowLog* log, uint32_t seq) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const TabView v = stage_tables(tab, smem, kClassifyThreads);
+  stage_tables(tab, smem, kClassifyThreads);
   __syncthreads();
-  if (tab.stage_bytes)  // uniform for the launch
-    classify_body(LdsTab(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
-  else
-    classify_body(CompactTab{v}, voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
+  classify_body(LdsTab(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
 }
 
 // Rank space -> id space: bit id of the output = bit rank_of_id[id] of the
@@ -271,8 +265,8 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
   if (n == 0) return;
   if (threadIdx.x < 16) bucket[threadIdx.x] = 0u;
   __syncthreads();
-  const CompactTab T{stage_tables(tab, nullptr, kAnnotateThreads)};  // launched with nothing staged
-  const uint32_t rule = T.v.hdr_far[node].y >> 16;
+  const LdsTab T(tab, nullptr);  // launched with nothing staged
+  const uint32_t rule = T.header(node).y >> 16;
   const uint32_t ctx0 = ctx_off[rule], n_ctx = ctx_off[rule + 1] - ctx0;  // 0 .. kCtxMax
   for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
     const uint32_t lid = list[j0 + e] & 0xFFFu;
@@ -607,9 +601,8 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   const bool has_cache = rd.n_stacks > 0;
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
   uint32_t frame0 = 0, n_frames = 0;
-  TabView tv{};
   if (has_cache) {
-    tv = stage_tables(rd.tab, smem, kFillThreads);
+    stage_tables(rd.tab, smem, kFillThreads);
     const XGM_GLOBAL uint32_t* first = stack_hdrs + (size_t)rd.stack_begin * hdr_stride;
     const XGM_GLOBAL uint32_t* last = stack_hdrs + (size_t)(rd.stack_begin + rd.n_stacks - 1) * hdr_stride;
     frame0 = first[kStackHdrFrames];
@@ -631,12 +624,8 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   if (tid == 0) sm.queue_n = 0u;
   __syncthreads();
   if (has_cache) {
-    if (rd.tab.stage_bytes)
-      fill_lists<COUNT, (APPLY != 0)>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames,
-                                      voc, log, seq, my_steps);
-    else
-      fill_lists<COUNT, (APPLY != 0)>(CompactTab{tv}, sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc,
-                                      log, seq, my_steps);
+    fill_lists<COUNT, (APPLY != 0)>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc,
+                                    log, seq, my_steps);
   }
   if (rd.flags & 1u) {
     for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {

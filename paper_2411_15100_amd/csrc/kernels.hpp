@@ -23,23 +23,25 @@ constexpr int kChunkTokens = kChunkWords * 32;
 enum : int { kReject = 0, kUncertain = 1, kAccept = 2, kOverflow = 3, kUncertainPlain = 4 };
 
 // Automaton tables of one grammar in device memory (see NodeHdr in
-// automaton.hpp): one contiguous image, laid out as a workgroup keeps it in
-// LDS, so that staging it is a single copy of 16-byte words:
-//   [0, off_follow)         alts     uint32 pool: count, then count entries (tag << 16 | node)
-//   [off_follow, ..)        follow   [n_rules][8] uint32: bytes that can come right after an instance of the rule
-//   [off_targets, ..)       targets  uint16
+// automaton.hpp): one contiguous image whose leading part a workgroup keeps in
+// LDS (a single copy of 16-byte words).  Sections, in the order of how much a
+// walk step depends on them:
+//   [0, 256)                cls      byte -> class
 //   [off_shapes, ..)        shapes   [n_shapes][n_cls] uint8
-//   [off_cls, off_cls+256)  cls      byte -> class
+//   [off_targets, ..)       targets  uint16
+//   [off_follow, ..)        follow   [n_rules][8] uint32: bytes that can come right after an instance of the rule
+//   [off_alts, ..)          alts     uint32 pool: count, then count entries (tag << 16 | node)
 //   [off_hdr, ..)           headers  [n_nodes] uint2: x = lo | hi<<8 | target<<16, y = flags | rule<<16
 //   [off_first, ..)         first    [n_nodes][8] uint32: bytes a node can consume inside its frame (never staged)
-// off_hdr is a multiple of 16 and the image is padded to a multiple of 16 bytes.
+// Every offset is a multiple of 4, off_hdr of 16; the image is padded to a multiple of 16 bytes.
 struct DevTables {
   const uint4* image;
-  uint32_t off_follow, off_targets, off_shapes, off_cls, off_hdr, off_first;
+  uint32_t off_shapes, off_targets, off_follow, off_alts, off_hdr, off_first;
   int32_t n_cls, n_nodes, n_rules;
-  // set per kernel by staged_for(): the leading stage_bytes of the image (the
-  // small tables and the first n_near headers) go to LDS; 0 = nothing is staged
-  uint32_t stage_bytes, n_near;
+  // set per kernel by staged_for(): bytes [0, lds_end) of the image are in LDS
+  // (whole sections, then the first n_near headers); stage_bytes = lds_end
+  // rounded up to 16 is what gets copied; 0 = nothing is staged
+  uint32_t lds_end, stage_bytes, n_near;
 };
 
 // what the walk reads: the first n_near node headers and the small tables may
@@ -59,14 +61,19 @@ struct TabView {
 // LDS budgets (bytes of dynamic shared memory) for the staged tables
 constexpr int32_t kClassifyLdsBudget = 56 * 1024;
 constexpr int32_t kFillLdsBudget = 40 * 1024;
-constexpr uint32_t kMaxSmallTables = 24 * 1024;  // larger small tables stay in global memory
-// the tables with the staging split for a kernel that has `budget` bytes of LDS for them
+// The staging split for a kernel that has `budget` bytes of LDS for the tables:
+// as many whole sections as fit, then as many headers as fit.
 inline DevTables staged_for(DevTables t, int32_t budget) {
-  t.stage_bytes = t.n_near = 0;
-  if (t.off_hdr > kMaxSmallTables || t.off_hdr + 8 > (uint32_t)budget) return t;
-  const uint32_t k = ((uint32_t)budget - t.off_hdr) / 8;
-  t.n_near = k < (uint32_t)t.n_nodes ? k : (uint32_t)t.n_nodes;
-  t.stage_bytes = (t.off_hdr + t.n_near * 8 + 15u) & ~15u;
+  const uint32_t ends[5] = {256u, t.off_targets, t.off_follow, t.off_alts, t.off_hdr};  // section ends in image order
+  t.lds_end = t.stage_bytes = t.n_near = 0;
+  for (uint32_t e : ends)
+    if (e <= (uint32_t)budget) t.lds_end = e;
+  if (t.lds_end == t.off_hdr) {
+    const uint32_t k = ((uint32_t)budget - t.off_hdr) / 8;
+    t.n_near = k < (uint32_t)t.n_nodes ? k : (uint32_t)t.n_nodes;
+    t.lds_end = t.off_hdr + t.n_near * 8;
+  }
+  t.stage_bytes = (t.lds_end + 15u) & ~15u;
   return t;
 }
 
