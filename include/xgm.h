@@ -159,6 +159,10 @@ int64_t xgm_cache_host_classified(const xgm_cache* c);
 /* Seconds the GPU spent in the classification kernel during the build, and
  * the number of (node, token) pairs it classified. */
 double xgm_cache_build_kernel_seconds(const xgm_cache* c);
+/* Seconds the whole xgm_cache_build call took on the host clock (all kernels,
+ * the copies of sizes back to the host, allocation; the vocabulary upload only
+ * on the first build that uses it). */
+double xgm_cache_build_seconds(const xgm_cache* c);
 
 /* The exact host routine that decides a (node, token) pair whose GPU walk
  * exceeded its limits during xgm_cache_build: 0 rejected, 1 context-dependent,

@@ -52,6 +52,7 @@ SIGNATURES = {
     "xgm_cache_num_uncertain": (_i32, [_vp, _i32]),
     "xgm_cache_host_classified": (_i64, [_vp]),
     "xgm_cache_build_kernel_seconds": (ctypes.c_double, [_vp]),
+    "xgm_cache_build_seconds": (ctypes.c_double, [_vp]),
     "xgm_matcher_create": (_i32, [_vp, _pp]),
     "xgm_matcher_create_host": (_i32, [_vp, _vp, _pp]),
     "xgm_matcher_destroy": (None, [_vp]),
@@ -260,6 +261,10 @@ class Cache:
     @property
     def build_kernel_seconds(self) -> float:
         return load_library().xgm_cache_build_kernel_seconds(self._h)
+
+    @property
+    def build_seconds(self) -> float:
+        return load_library().xgm_cache_build_seconds(self._h)
 
     def copy_node_bits(self, node: int):
         W = bitmask_words(self.vocab.size)

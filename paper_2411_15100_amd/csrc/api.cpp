@@ -3,6 +3,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <cstring>
 #include <mutex>
 #include <numeric>
@@ -141,6 +142,7 @@ struct xgm_cache {
   uint32_t* d_plain_id = nullptr;      // [n_nodes][W] their bitsets, if kept
   int64_t host_classified = 0;
   double kernel_seconds = 0.0;
+  double build_seconds = 0.0;
 };
 struct xgm_matcher {
   xgm_cache* c = nullptr;
@@ -445,6 +447,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
   *out = nullptr;
   if (!g || !v) return fail(XGM_ERR_BAD_ARG, "cache_build: null grammar or vocabulary");
   require_device();
+  const auto t_build0 = std::chrono::steady_clock::now();
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   vocab_to_device(v);
   const DevVocab& dv = v->dv;
@@ -460,7 +463,6 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     auto keep = [&](auto* p) { c->dev_ptrs.push_back((void*)p); return p; };
     auto temp = [&](auto* p) { temps.push_back((void*)p); return p; };
     // automaton tables
-    static_assert(sizeof(NodeHdr) == sizeof(uint2), "header layout");
     static_assert(sizeof(NodeHdr) == sizeof(uint2), "header layout");
     DevTables tab{};
     {
@@ -607,6 +609,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     c->host.unc_off = d_off;
     c->host.unc_list = d_list;
     c->host.unc_ctx = d_list_ctx;
+    c->build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_build0).count();
     c->host.n_nodes = N;
   } catch (...) {
     cleanup_temps();
@@ -640,6 +643,7 @@ int xgm_cache_copy_node_plain(const xgm_cache* c, int32_t node, int32_t* h_plain
 }
 int64_t xgm_cache_host_classified(const xgm_cache* c) { return c ? c->host_classified : XGM_ERR_BAD_ARG; }
 double xgm_cache_build_kernel_seconds(const xgm_cache* c) { return c ? c->kernel_seconds : -1.0; }
+double xgm_cache_build_seconds(const xgm_cache* c) { return c ? c->build_seconds : -1.0; }
 
 int xgm_cache_copy_node_bits(const xgm_cache* c, int32_t node, int32_t* h_acc, int32_t* h_unc) {
   API_BEGIN

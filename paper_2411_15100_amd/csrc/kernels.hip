@@ -342,32 +342,41 @@ __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ 
 // One 16-byte group of a logits row (section 2.1): `mk` holds the mask bits of
 // its EPT = 16 / ESIZE elements, e0 is the index of its first element.  All
 // allowed: nothing is touched.  None allowed: one 16-byte store of the -inf
-// pattern.  Mixed: only the disallowed elements are stored (pairs of 16-bit
-// elements as one 32-bit store where both go).  The logits are never read:
-// the bytes that stay are simply not written.
+// pattern.  One or two disallowed: those elements are stored by themselves,
+// nothing is read.  More: the group is read, blended and stored whole (many
+// small stores cost more than the read).
 template <int ESIZE>
 __device__ __forceinline__ void apply_group(unsigned char* p, uint32_t mk, int32_t e0, int32_t V_logits, uint32_t neg_inf) {
   constexpr int EPT = 16 / ESIZE;
   constexpr uint32_t kAll = (1u << EPT) - 1u;
   if (mk == kAll) return;
   const uint32_t two = neg_inf | (neg_inf << 16);
-  if (mk == 0u && e0 + EPT <= V_logits) {
+  const bool whole = e0 + EPT <= V_logits;
+  if (mk == 0u && whole) {
     *reinterpret_cast<uint4*>(p) = ESIZE == 2 ? make_uint4(two, two, two, two) : make_uint4(neg_inf, neg_inf, neg_inf, neg_inf);
-  } else if (ESIZE == 2) {
+  } else if (whole && EPT - __popc(mk) > 2) {
+    uint4 v = *reinterpret_cast<const uint4*>(p);
+    if (ESIZE == 2) {
+      uint32_t* q = reinterpret_cast<uint32_t*>(&v);
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const uint32_t b = (mk >> (2 * h)) & 3u;
-      if (e0 + 2 * h + 1 < V_logits && b == 0u) {
-        reinterpret_cast<uint32_t*>(p)[h] = two;
-      } else {
-        if (e0 + 2 * h < V_logits && !(b & 1u)) reinterpret_cast<uint16_t*>(p)[2 * h] = (uint16_t)neg_inf;
-        if (e0 + 2 * h + 1 < V_logits && !(b & 2u)) reinterpret_cast<uint16_t*>(p)[2 * h + 1] = (uint16_t)neg_inf;
+      for (int h = 0; h < 4; ++h) {
+        const uint32_t keep = ((mk >> (2 * h)) & 1u ? 0x0000FFFFu : 0u) | ((mk >> (2 * h + 1)) & 1u ? 0xFFFF0000u : 0u);
+        q[h] = (q[h] & keep) | (two & ~keep);
       }
+    } else {
+      if (!(mk & 1u)) v.x = neg_inf;
+      if (!(mk & 2u)) v.y = neg_inf;
+      if (!(mk & 4u)) v.z = neg_inf;
+      if (!(mk & 8u)) v.w = neg_inf;
     }
+    *reinterpret_cast<uint4*>(p) = v;
   } else {
 #pragma unroll
     for (int h = 0; h < EPT; ++h)
-      if (e0 + h < V_logits && !((mk >> h) & 1u)) reinterpret_cast<uint32_t*>(p)[h] = neg_inf;
+      if (e0 + h < V_logits && !((mk >> h) & 1u)) {
+        if (ESIZE == 2) reinterpret_cast<uint16_t*>(p)[h] = (uint16_t)neg_inf;
+        else reinterpret_cast<uint32_t*>(p)[h] = neg_inf;
+      }
   }
 }
 
