@@ -37,13 +37,13 @@ __device__ __forceinline__ void stage_tables(const DevTables& tab, unsigned char
 struct LdsTab {
   const XGM_LDS unsigned char* lds;     // the staged part of the image
   const XGM_GLOBAL unsigned char* img;  // the whole image
-  uint32_t n_near, n_cls, off_shapes, off_targets, off_follow, off_alts, off_hdr;
+  uint32_t n_near, n_cls, off_shapes, off_targets, off_follow, off_alts, off_hdr, off_first;
   bool cls_lds, shapes_lds, targets_lds, follow_lds, alts_lds;
   __device__ __forceinline__ LdsTab(const DevTables& t, unsigned char* smem)
       : lds((const XGM_LDS unsigned char*)smem),
         img((const XGM_GLOBAL unsigned char*)reinterpret_cast<const unsigned char*>(t.image)),
         n_near(t.n_near), n_cls((uint32_t)t.n_cls), off_shapes(t.off_shapes), off_targets(t.off_targets),
-        off_follow(t.off_follow), off_alts(t.off_alts), off_hdr(t.off_hdr),
+        off_follow(t.off_follow), off_alts(t.off_alts), off_hdr(t.off_hdr), off_first(t.off_first),
         cls_lds(t.lds_end >= 256u), shapes_lds(t.lds_end >= t.off_targets), targets_lds(t.lds_end >= t.off_follow),
         follow_lds(t.lds_end >= t.off_alts), alts_lds(t.lds_end >= t.off_hdr) {}
   __device__ __forceinline__ uint32_t rd8(uint32_t off, bool in_lds) const { return in_lds ? (uint32_t)lds[off] : (uint32_t)img[off]; }
@@ -80,6 +80,14 @@ struct LdsTab {
   }
   __device__ __forceinline__ uint32_t alt(uint32_t idx) const { return rd32(off_alts + idx * 4u, alts_lds); }
   __device__ __forceinline__ bool is_final(uint32_t n) const { return header(n).y & 1u; }
+  // can byte c be consumed at node n inside its frame (byte edge, or first byte of a rule it refers to)?
+  __device__ __forceinline__ bool can_start(uint32_t n, uint32_t c) const {
+    return (*(const XGM_GLOBAL uint32_t*)(img + off_first + ((size_t)n * 8u + (c >> 5)) * 4u) >> (c & 31)) & 1u;
+  }
+  // can byte c come right after an instance of node n's rule (h = header(n))?
+  __device__ __forceinline__ bool can_follow(const uint2& h, uint32_t c) const {
+    return (rd32(off_follow + ((h.y >> 16) * 8u + (c >> 5)) * 4u, follow_lds) >> (c & 31)) & 1u;
+  }
   // generic pointer to the 256-bit FOLLOW set of node n's rule (read on the rare exit from the start frame)
   __device__ __forceinline__ const uint32_t* follow_of(uint32_t n) const {
     const uint32_t off = off_follow + (header(n).y >> 16) * 32u;
@@ -130,11 +138,25 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
   const int32_t word = (blockIdx.x * kClassifyThreads + (threadIdx.x & ~63)) >> 5;  // even
   const int32_t n_begin = blockIdx.y * kNodesPerBlock;
   const int32_t n_end = min(n_begin + kNodesPerBlock, n_nodes);
+  // Most pairs are settled by the token's first byte: if the node cannot
+  // consume it inside its frame, the token is rejected - or, at a node where
+  // the rule may end, leaves the frame at position 0.  One bit per node of the
+  // block says whether a walk is needed at all (the loads are issued together).
+  const uint32_t c0 = tk.x & 0xFFu;
+  uint32_t needs_walk = 0u;
+  if (live_lane && len > 0)
+    for (int32_t k = n_begin; k < n_end; ++k)
+      needs_walk |= (uint32_t)T.can_start((uint32_t)(node0 + k), c0) << (k - n_begin);
   for (int32_t k = n_begin; k < n_end; ++k) {
     int res = kReject;
     if (live_lane && len > 0) {
-      res = walk_token<true>(T, tk, ext, len, (uint32_t)(node0 + k), (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node0 + k));
-      if (res == kOverflow) { record_overflow(log, seq, (uint32_t)k, (uint32_t)r); res = kReject; }
+      if ((needs_walk >> (k - n_begin)) & 1u) {
+        res = walk_token<true>(T, tk, ext, len, (uint32_t)(node0 + k), (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node0 + k));
+        if (res == kOverflow) { record_overflow(log, seq, (uint32_t)k, (uint32_t)r); res = kReject; }
+      } else {
+        const uint2 h = T.header((uint32_t)(node0 + k));
+        if (h.y & 1u) res = T.can_follow(h, c0) ? kUncertain : kUncertainPlain;
+      }
     }
     const unsigned long long a = __ballot(res == kAccept);
     const unsigned long long u = __ballot(res == kUncertain);
@@ -168,38 +190,45 @@ __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
 }
 
 // Rank space -> id space: bit id of the output = bit rank_of_id[id] of the
-// input.  One workgroup per node row; the two rank-space rows sit in LDS so
-// that the random bit lookups never leave the CU.
-constexpr int kPermuteThreads = 256;
-__global__ __launch_bounds__(kPermuteThreads) void permute_kernel(DevVocab voc, const uint32_t* __restrict__ acc_rank,
+// input.  One workgroup serves up to kPermuteNodes node rows: their rank-space
+// rows sit in LDS so that the random bit lookups never leave the CU, and the
+// id -> rank table is read once for all of them.
+constexpr int kPermuteThreads = 1024;
+constexpr int kPermuteNodes = 4;
+__global__ __launch_bounds__(kPermuteThreads) void permute_kernel(DevVocab voc, int32_t n_nodes, int32_t per_block,
+                                                                  const uint32_t* __restrict__ acc_rank,
                                                                   const uint32_t* __restrict__ unc_rank,
                                                                   uint32_t* __restrict__ acc_id,
                                                                   uint32_t* __restrict__ unc_id) {
   extern __shared__ __align__(16) unsigned char smem[];
-  uint32_t* s_acc = reinterpret_cast<uint32_t*>(smem);
-  uint32_t* s_unc = s_acc + voc.WR;
-  const size_t node = blockIdx.x;
-  for (int k = threadIdx.x; k < voc.WR; k += kPermuteThreads) {
-    s_acc[k] = acc_rank[node * voc.WR + k];
-    s_unc[k] = unc_rank[node * voc.WR + k];
-  }
+  uint32_t* rows = reinterpret_cast<uint32_t*>(smem);  // [per_block][2][WR]
+  const int32_t first = blockIdx.x * per_block;
+  const int32_t nb = min(per_block, n_nodes - first);
+  for (int32_t q = 0; q < nb; ++q)
+    for (int k = threadIdx.x; k < voc.WR; k += kPermuteThreads) {
+      rows[(size_t)(2 * q) * voc.WR + k] = acc_rank[(size_t)(first + q) * voc.WR + k];
+      rows[(size_t)(2 * q + 1) * voc.WR + k] = unc_rank[(size_t)(first + q) * voc.WR + k];
+    }
   __syncthreads();
   const int32_t v64 = (voc.V + 63) & ~63;
   for (int32_t id = threadIdx.x; id < v64; id += kPermuteThreads) {
-    bool a = false, u = false;
-    if (id < voc.V) {
-      const uint32_t r = (uint32_t)voc.rank_of_id[id];
-      a = (s_acc[r >> 5] >> (r & 31)) & 1u;
-      u = (s_unc[r >> 5] >> (r & 31)) & 1u;
-    }
-    const unsigned long long ba = __ballot(a), bu = __ballot(u);
-    if ((threadIdx.x & 63) == 0) {
-      const int32_t w = id >> 5;
-      acc_id[node * voc.W + w] = (uint32_t)ba;
-      unc_id[node * voc.W + w] = (uint32_t)bu;
-      if (w + 1 < voc.W) {
-        acc_id[node * voc.W + w + 1] = (uint32_t)(ba >> 32);
-        unc_id[node * voc.W + w + 1] = (uint32_t)(bu >> 32);
+    const bool in = id < voc.V;
+    const uint32_t r = in ? (uint32_t)voc.rank_of_id[id] : 0u;
+    const int32_t w = id >> 5;
+#pragma unroll
+    for (int32_t q = 0; q < kPermuteNodes; ++q) {
+      if (q >= nb) break;
+      const bool a = in && ((rows[(size_t)(2 * q) * voc.WR + (r >> 5)] >> (r & 31)) & 1u);
+      const bool u = in && ((rows[(size_t)(2 * q + 1) * voc.WR + (r >> 5)] >> (r & 31)) & 1u);
+      const unsigned long long ba = __ballot(a), bu = __ballot(u);
+      if ((threadIdx.x & 63) == 0) {
+        const size_t node = (size_t)(first + q);
+        acc_id[node * voc.W + w] = (uint32_t)ba;
+        unc_id[node * voc.W + w] = (uint32_t)bu;
+        if (w + 1 < voc.W) {
+          acc_id[node * voc.W + w + 1] = (uint32_t)(ba >> 32);
+          unc_id[node * voc.W + w + 1] = (uint32_t)(bu >> 32);
+        }
       }
     }
   }
@@ -722,9 +751,12 @@ void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, i
 void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* acc_rank, const uint32_t* unc_rank,
                     uint32_t* acc_id, uint32_t* unc_id, hipStream_t stream) {
   if (n <= 0) return;
-  size_t lds = (size_t)voc.WR * 8;
-  hipLaunchKernelGGL(permute_kernel, dim3(n), dim3(kPermuteThreads), lds, stream, voc, acc_rank, unc_rank, acc_id,
-                     unc_id);
+  const size_t row_pair = (size_t)voc.WR * 8;  // LDS bytes per node
+  int32_t per_block = (int32_t)std::min<size_t>(kPermuteNodes, std::max<size_t>(1, (size_t)(144 * 1024) / row_pair));
+  // enough workgroups to fill the device before rows are grouped
+  while (per_block > 1 && (n + per_block - 1) / per_block < 512) --per_block;
+  hipLaunchKernelGGL(permute_kernel, dim3((n + per_block - 1) / per_block), dim3(kPermuteThreads),
+                     row_pair * per_block, stream, voc, n, per_block, acc_rank, unc_rank, acc_id, unc_id);
 }
 
 void launch_count_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_id, uint32_t* counts,
