@@ -599,7 +599,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     uint32_t* d_ctx_off = temp(dev_upload(ctx_off));
     uint16_t* d_ctx_node = temp(dev_upload(ctx_node));
     launch_list_uncertain(dv, N, unc_id, d_off, d_list, stream);
-    launch_annotate_lists(tab, dv, N, d_off, d_list, d_list_ctx, d_ctx_off, d_ctx_node, stream);
+    launch_annotate_lists(tab, dv, N, d_off, (uint32_t)total, d_list, d_list_ctx, d_ctx_off, d_ctx_node, stream);
     HIP_OK(hipGetLastError());
     HIP_OK(hipStreamSynchronize(stream));
     cleanup_temps();

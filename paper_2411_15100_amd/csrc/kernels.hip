@@ -280,12 +280,8 @@ __global__ void list_uncertain_kernel(DevVocab voc, const uint32_t* __restrict__
 constexpr int kAnnotateThreads = 256;
 __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTables tab, DevVocab voc, int32_t node0,
                                                                           const uint32_t* __restrict__ off,
-                                                                          uint32_t* __restrict__ list,
-                                                                          uint32_t* __restrict__ list_ctx,
-                                                                          const uint32_t* __restrict__ ctx_off,
-                                                                          const uint16_t* __restrict__ ctx_node) {
+                                                                          uint32_t* __restrict__ list) {
   __shared__ uint32_t seg[kChunkTokens];
-  __shared__ uint32_t seg_ctx[kChunkTokens];
   __shared__ uint8_t rem_of[kChunkTokens];
   __shared__ uint32_t bucket[16];
   const int32_t node = node0 + blockIdx.y, chunk = blockIdx.x;
@@ -295,8 +291,6 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
   if (threadIdx.x < 16) bucket[threadIdx.x] = 0u;
   __syncthreads();
   const LdsTab T(tab, nullptr);  // launched with nothing staged
-  const uint32_t rule = T.header(node).y >> 16;
-  const uint32_t ctx0 = ctx_off[rule], n_ctx = ctx_off[rule + 1] - ctx0;  // 0 .. kCtxMax
   for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
     const uint32_t lid = list[j0 + e] & 0xFFFu;
     const int32_t id = chunk * kChunkTokens + (int32_t)lid;
@@ -320,20 +314,7 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
     }
     const uint32_t b1 = token_byte(tk, ext, (int)pos);
     const uint32_t b2 = meta == kEntryFullWalk ? late : ((int)pos + 1 < len ? token_byte(tk, ext, (int)pos + 1) : 0u);
-    const int from = (int)(late ? late : pos);  // where the suffix starts
-    const uint32_t rem = min(15, len - from);
-    // what the suffix does in each context of the node's rule, with nothing known below that context
-    uint32_t classes = 0u;
-    for (uint32_t i = 0; i < kCtxMax; ++i) {
-      uint32_t code = kCtxWalk;
-      if ((meta != kEntryFullWalk || late) && i < n_ctx) {
-        const uint32_t r = ctx_node[ctx0 + i];
-        const int c = walk_token<true>(T, tk, ext, len, r, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r), from);
-        code = c == kAccept ? kCtxAccept : (c == kUncertain || c == kOverflow) ? kCtxWalk : kCtxReject;
-      }
-      classes |= code << (2u * i);
-    }
-    seg_ctx[e] = classes;
+    const uint32_t rem = min(15, len - (int)(late ? late : pos));
     seg[e] = lid | (meta << 12) | (b1 << 16) | (b2 << 24);
     rem_of[e] = (uint8_t)rem;
     atomicAdd(&bucket[rem], 1u);
@@ -345,10 +326,62 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
   }
   __syncthreads();
   for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
-    const uint32_t at = j0 + atomicAdd(&bucket[rem_of[e]], 1u);
-    list[at] = seg[e];
-    list_ctx[at] = seg_ctx[e];
+    list[j0 + atomicAdd(&bucket[rem_of[e]], 1u)] = seg[e];
   }
+}
+
+// The per-context classes of every list entry (see kCtx*): one thread per
+// entry over all lists of the grammar, tables staged as in the classify
+// kernel.  For each context node of the entry's rule the entry's suffix is
+// walked from that node with nothing known below it.
+constexpr int kContextThreads = 256;
+__global__ __launch_bounds__(kContextThreads) void context_classes_kernel(DevTables tab, DevVocab voc, int32_t n_nodes,
+                                                                          uint32_t total,
+                                                                          const uint32_t* __restrict__ off,
+                                                                          const uint32_t* __restrict__ list,
+                                                                          uint32_t* __restrict__ list_ctx,
+                                                                          const uint32_t* __restrict__ ctx_off,
+                                                                          const uint16_t* __restrict__ ctx_node) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  stage_tables(tab, smem, kContextThreads);
+  __syncthreads();
+  const LdsTab T(tab, smem);
+  const uint32_t j = blockIdx.x * kContextThreads + threadIdx.x;
+  if (j >= total) return;
+  // the entry's (node, chunk): the last slot of `off` that starts at or before j
+  const uint32_t stride = (uint32_t)voc.n_chunk + 1u;
+  uint32_t lo = 0u, hi = (uint32_t)n_nodes * stride;  // off[lo] <= j < off[hi - 1 + 1 ...]; the last slot equals total
+  while (hi - lo > 1u) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (off[mid] <= j) lo = mid; else hi = mid;
+  }
+  const uint32_t node = lo / stride, chunk = lo % stride;
+  const uint32_t e = list[j];
+  const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, b2 = e >> 24;
+  const int32_t id = (int32_t)(chunk * kChunkTokens + lid);
+  const uint4 tk = voc.tok_by_id[id];
+  int len = (int)(tk.w >> 24);
+  const uint8_t* ext = voc.bytes;
+  if (len >= 15) {
+    ext = voc.bytes + voc.off_by_id[id];
+    if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
+  }
+  // where the suffix starts (-1: the entry has several exits)
+  const int from = meta <= 12u ? (int)meta : meta == kEntrySuffix2 ? len - 2 : meta == kEntrySuffix1 ? len - 1
+                                                                                : (b2 != 0u ? (int)b2 : -1);
+  const uint32_t rule = T.header(node).y >> 16;
+  const uint32_t ctx0 = ctx_off[rule], n_ctx = ctx_off[rule + 1] - ctx0;  // 0 .. kCtxMax
+  uint32_t classes = 0u;
+  for (uint32_t i = 0; i < kCtxMax; ++i) {
+    uint32_t code = kCtxWalk;
+    if (from >= 0 && i < n_ctx) {
+      const uint32_t r = ctx_node[ctx0 + i];
+      const int c = walk_token<true>(T, tk, ext, len, r, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r), from);
+      code = c == kAccept ? kCtxAccept : (c == kUncertain || c == kOverflow) ? kCtxWalk : kCtxReject;
+    }
+    classes |= code << (2u * i);
+  }
+  list_ctx[j] = classes;
 }
 
 __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ items, int32_t n_items,
@@ -771,13 +804,18 @@ void launch_list_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_i
   hipLaunchKernelGGL(list_uncertain_kernel, dim3(voc.n_chunk, n), dim3(kChunkWords), 0, stream, voc, unc_id, off, list);
 }
 
-void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n, const uint32_t* off, uint32_t* list,
-                           uint32_t* list_ctx, const uint32_t* ctx_off, const uint16_t* ctx_node, hipStream_t stream) {
+void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n, const uint32_t* off, uint32_t total,
+                           uint32_t* list, uint32_t* list_ctx, const uint32_t* ctx_off, const uint16_t* ctx_node,
+                           hipStream_t stream) {
   for (int32_t node0 = 0; node0 < n; node0 += 32768) {  // grid.y limit
     const int32_t nb = std::min(32768, n - node0);
     hipLaunchKernelGGL(annotate_lists_kernel, dim3(voc.n_chunk, nb), dim3(kAnnotateThreads), 0, stream,
-                       staged_for(tab, 0), voc, node0, off, list, list_ctx, ctx_off, ctx_node);
+                       staged_for(tab, 0), voc, node0, off, list);
   }
+  if (total == 0) return;
+  const DevTables st = staged_for(tab, kClassifyLdsBudget);
+  hipLaunchKernelGGL(context_classes_kernel, dim3((total + kContextThreads - 1) / kContextThreads), dim3(kContextThreads),
+                     st.stage_bytes, stream, st, voc, n, total, off, list, list_ctx, ctx_off, ctx_node);
 }
 
 void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items, uint32_t* acc_rank,

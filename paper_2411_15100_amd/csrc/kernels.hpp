@@ -187,9 +187,10 @@ void launch_count_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_
 // write the context-dependent lists; off = [n][n_chunk+1] offsets relative to list
 void launch_list_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_id, const uint32_t* off,
                            uint32_t* list, hipStream_t stream);
-// find each entry's exit position (a walk per entry) and sort every (node, chunk) list by remaining length
+// find each entry's exit position (a walk per entry), sort every (node, chunk) list by remaining length, then
+// classify every entry's suffix in the contexts of its rule (total = number of entries of all lists)
 // ctx_off [n_rules+1], ctx_node: the contexts of every rule that has at most kCtxMax (others: empty range)
-void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n, const uint32_t* off,
+void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n, const uint32_t* off, uint32_t total,
                            uint32_t* list, uint32_t* list_ctx, const uint32_t* ctx_off, const uint16_t* ctx_node,
                            hipStream_t stream);
 // set / clear single bits of rank-space rows: items = (node - node0, rank, class)
