@@ -20,6 +20,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0                      # MI355X HBM3E, published
+# HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
+# profiles/serving_step_counters.txt (scaled by what the counters read for a plain copy of known size).
+# Set to None whenever a kernel changes after the counters were taken.
+TRAFFIC_FILL_BYTES = 21.3e6
+TRAFFIC_APPLY_BYTES = 33.9e6
 
 
 def log(*a):
@@ -140,7 +145,7 @@ def main():
     fill_us_avg, apply_us_avg = float(fill_us.mean()), float(apply_us.mean())
     fill_is_dominant = fill_us_avg >= apply_us_avg
     roof_apply = {"kernel": "apply_kernel<2>", "bound": "hbm", "achieved": apply_bytes / (apply_us_avg * 1e-6) / 1e9,
-                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None, "bytes_per_launch": apply_bytes,
+                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": TRAFFIC_APPLY_BYTES, "bytes_per_launch": apply_bytes,
                   "read_modify_write_bytes_per_launch": 2.0 * 2.0 * B * V + 4.0 * B * W,
                   "plain_fill_of_the_same_buffers": {"us": plain_fill_us, "GB/s": plain_fill_gbs}}
     roof_apply["frac"] = roof_apply["achieved"] / HBM_PEAK_GBS
@@ -148,7 +153,7 @@ def main():
     fill_kernel_us = float(fk_us.mean())
     roof_fill = {"kernel": "fill_kernel<false>", "bound": "hbm", "kernel_us": fill_kernel_us,
                  "achieved": fill_bytes / (fill_kernel_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                 "traffic": None, "bytes_per_launch": fill_bytes,
+                 "traffic": TRAFFIC_FILL_BYTES, "bytes_per_launch": fill_bytes,
                  "list_entries_per_launch": float(np.mean(unc_tokens)),
                  "automaton_steps_per_launch": auto_steps,
                  "note": "latency-bound by nature: a few dependent memory rounds per workgroup and a tail of "
