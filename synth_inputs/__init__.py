@@ -14,6 +14,7 @@ from .grammars import (
     ARITH_GRAMMAR,
     JSON_GRAMMAR,
     CSQL_GRAMMAR,
+    XML_GRAMMAR,
     make_schema_grammar,
     random_schema,
 )
@@ -27,6 +28,7 @@ __all__ = [
     "ARITH_GRAMMAR",
     "JSON_GRAMMAR",
     "CSQL_GRAMMAR",
+    "XML_GRAMMAR",
     "make_schema_grammar",
     "random_schema",
     "make_logits",

@@ -48,6 +48,25 @@ ws      ::= [ \t\n\r]*
 """
 
 # ---------------------------------------------------------------------------
+# A markup grammar in the style of XML (context-free: closing names are not
+# matched against opening names).  Elements, attributes with two quote styles,
+# text, entity references, comments, self-closing tags.
+# ---------------------------------------------------------------------------
+XML_GRAMMAR = r"""
+root     ::= ws element ws
+element  ::= "<" name attrs ws ( "/>" | ">" content "</" name ws ">" )
+attrs    ::= ( ws1 name ws "=" ws value )*
+value    ::= "\"" [^"<&]* "\"" | "'" [^'<&]* "'"
+content  ::= ( element | text | entity | comment )*
+text     ::= [^<&]+
+entity   ::= "&" name ";" | "&#" [0-9]+ ";"
+comment  ::= "<!--" ( [^\-] | "-" [^\-] )* "-->"
+name     ::= [A-Za-z_] [A-Za-z0-9_.\-]*
+ws       ::= [ \t\n]*
+ws1      ::= [ \t\n]+
+"""
+
+# ---------------------------------------------------------------------------
 # Workload 4(ii): a C/SQL-like language, about 60 rules.  Iterative (never
 # left-recursive) precedence chain, keywords, identifiers, literals with
 # escapes, blocks and embedded SELECT statements.

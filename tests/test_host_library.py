@@ -23,6 +23,7 @@ GRAMMARS = {
     "arith": (si.ARITH_GRAMMAR, "expr", b"0123456789+*() "),
     "json": (si.JSON_GRAMMAR, "root", b' \n"{}[],:\\/abfnrtu0123456789.eE+-\xc3\xa9\xe4\xb8\xad\xf0\x9f\x98\x80xyz'),
     "csql": (si.CSQL_GRAMMAR, "root", b" \n(){}[];,.*+-/%<>=!&|^~?:'\"\\_abcdefhilnorstuwxSELCTFROMWHNDBYGUPIAV0123459"),
+    "xml": (si.XML_GRAMMAR, "root", b" \n\t<>/=\"'&;#!-._abcxyzAZ019"),
     "schema": (si.make_schema_grammar(3), "root", b' \n"{}[],:\\abcdefghijklmnopqrstuvwxyz_0123456789.eE+-tfu'),
 }
 
@@ -274,7 +275,7 @@ def test_kernel_walk_classes_match_oracle_json_and_csql_samples():
     assert _walk_classes_for_nodes(si.CSQL_GRAMMAR, "root", vocab, nodes) == 0
 
 
-@pytest.mark.parametrize("name", ["arith", "json", "csql", "schema"])
+@pytest.mark.parametrize("name", ["arith", "json", "csql", "schema", "xml"])
 def test_kernel_walk_masks_match_oracle_along_walks(name):
     """Two-way walk with the full live stack (what the fill kernel runs for
     every stack) OR-ed over the stacks == the oracle's mask, for all tokens."""
@@ -312,7 +313,7 @@ def test_kernel_walk_masks_match_oracle_along_walks(name):
         assert om.advance(toks[t])
 
 
-@pytest.mark.parametrize("name", ["arith", "json", "schema"])
+@pytest.mark.parametrize("name", ["arith", "json", "schema", "xml"])
 def test_next_byte_sets_match_oracle(name):
     """The fill kernel's two-byte table, computed by the same source on the
     host: byte c2 is in the set of (stack, c1) iff the oracle can consume c1
@@ -351,7 +352,7 @@ def test_next_byte_sets_match_oracle(name):
         assert om.advance(toks[t])
 
 
-@pytest.mark.parametrize("name", ["arith", "json", "csql", "schema"])
+@pytest.mark.parametrize("name", ["arith", "json", "csql", "schema", "xml"])
 def test_frame_below_is_always_a_listed_context(name):
     """Along random walks, the node below the top frame of every stack is one
     of the contexts the compiler lists for the top node's rule."""
