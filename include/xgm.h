@@ -249,6 +249,11 @@ int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bi
  * once more with xgm_apply_token_bitmask_inplace. */
 int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* d_logits, xgm_dtype dt,
                        int32_t V_logits, int64_t row_stride_elems, void* hip_stream);
+/* Test knob (process-wide): a fill workgroup builds its two-byte table for a
+ * stack only if its lists for that stack hold at least `entries` entries
+ * (default 2048; negative restores the default).  The masks do not depend on
+ * it; tests set 1 to force that path at small sizes.  Returns the old value. */
+int32_t xgm_debug_set_fill_pair_threshold(int32_t entries);
 /* Instrumentation for benchmarks: the same fill (same result in d_bitmask)
  * with a kernel instantiation that also counts the automaton steps of all
  * walks; synchronous; *h_steps receives the count.  Not for the hot path. */

@@ -66,6 +66,7 @@ SIGNATURES = {
     "xgm_fill_next_token_bitmask": (_i32, [_vp, _i32, _vp, _vp]),
     "xgm_fill_and_apply": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
     "xgm_debug_fill_count_steps": (_i32, [_vp, _i32, _vp, _vp, _vp]),
+    "xgm_debug_set_fill_pair_threshold": (_i32, [_i32]),
     "xgm_debug_fill_timed": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_fill_overflow_fixup": (_i32, [_vp]),
     "xgm_overflow_total": (_i64, []),
@@ -355,6 +356,11 @@ def debug_fill_count_steps(batch: "MatcherBatch", d_bitmask: int, stream: int = 
     _check(load_library().xgm_debug_fill_count_steps(batch._arr, len(batch.matchers), ctypes.c_void_p(d_bitmask),
                                                      ctypes.c_void_p(stream), ctypes.byref(n)))
     return int(n.value)
+
+
+def debug_set_fill_pair_threshold(entries: int) -> int:
+    """Test knob: minimum list length for the two-byte table (negative: default); returns the old value."""
+    return int(load_library().xgm_debug_set_fill_pair_threshold(int(entries)))
 
 
 def debug_fill_timed(batch: "MatcherBatch", d_bitmask: int, stream: int = 0):

@@ -231,6 +231,7 @@ struct Context {
   xgm_vocab* last_vocab = nullptr;
   // scratch of the workgroup planner (kept to avoid per-step allocation)
   std::vector<uint64_t> plan_entries;
+  uint32_t pair_min_entries = kFillPairMinEntries;
   int32_t resident_blocks = 0;  // fill workgroups the device holds at once (two per compute unit)
 };
 Context& ctx() {
@@ -914,7 +915,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
               reinterpret_cast<const FillBlock*>((char*)slot.d_buf + off_plan), n_blocks, v->dv,
               reinterpret_cast<uint32_t*>(d_bitmask), log, seq, d_step_counter, stream,
               fused ? fused->d_logits : nullptr, fused ? fused->esize : 0, fused ? fused->neg_inf : 0u,
-              fused ? fused->V_logits : 0, fused ? fused->row_stride : 0);
+              fused ? fused->V_logits : 0, fused ? fused->row_stride : 0, C.pair_min_entries);
   HIP_OK(hipGetLastError());
   if (timing) HIP_OK(hipEventRecord(timing[2], stream));
   HIP_OK(hipEventRecord(slot.done, stream));
@@ -952,6 +953,14 @@ int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, vo
     return fail(XGM_ERR_BAD_ARG, "fill_and_apply: logits rows must be 16-byte aligned (use the two separate calls)");
   return fill_impl(ms, B, d_bitmask, hip_stream, nullptr, nullptr, &f);
   API_END
+}
+
+int32_t xgm_debug_set_fill_pair_threshold(int32_t entries) {
+  Context& C = ctx();
+  std::lock_guard<std::mutex> lock(C.mu);
+  const int32_t old = (int32_t)C.pair_min_entries;
+  C.pair_min_entries = entries < 0 ? kFillPairMinEntries : (uint32_t)entries;
+  return old;
 }
 
 int xgm_debug_fill_count_steps(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream,

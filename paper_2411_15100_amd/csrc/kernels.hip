@@ -457,7 +457,6 @@ __global__ __launch_bounds__(kUploadThreads) void upload_kernel(const uint4* __r
 constexpr int kFillThreads = 1024;
 constexpr int kFillQueue = 4096;                // survivors walked per round
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
-constexpr uint32_t kFillPairMinEntries = 128;   // lists shorter than this are filtered on one byte only
 
 // accumulates a 256-bit set into 8 LDS words
 struct LdsSetAcc {
@@ -507,7 +506,8 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
                                            const bool frames_in_lds,
                                            const XGM_GLOBAL uint32_t* __restrict__ stack_hdrs,
                                            const XGM_GLOBAL uint16_t* __restrict__ frames, const DevVocab& voc,
-                                           OverflowLog* log, uint32_t seq, unsigned long long& my_steps) {
+                                           OverflowLog* log, uint32_t seq, unsigned long long& my_steps,
+                                           const uint32_t pair_min_entries) {
   const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
   const XGM_GLOBAL uint32_t* unc_list = (const XGM_GLOBAL uint32_t*)rd.unc_list;
@@ -530,7 +530,7 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
     live.lo = frames_in_lds ? 0u : 0xFFFFFFFFu;
     const uint32_t below = depth >= 2 ? live[depth - 2] : 0u;
     // the two-byte table of the stack below the top frame
-    const bool use_pair = depth >= 2 && sm.off[c1 - c0] - sm.off[0] >= kFillPairMinEntries;
+    const bool use_pair = depth >= 2 && sm.off[c1 - c0] - sm.off[0] >= pair_min_entries;
     if (use_pair) {
       for (uint32_t k = tid; k < 256u * 8u; k += kFillThreads) sm.pair[k] = 0u;
       __syncthreads();
@@ -648,6 +648,7 @@ struct FusedApply {
   int64_t row_stride;     // elements
   int32_t V_logits;
   uint32_t neg_inf;
+  uint32_t pair_min_entries;  // (rides along) lists shorter than this are filtered on one byte only
 };
 
 template <bool COUNT, int APPLY>
@@ -696,7 +697,7 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   __syncthreads();
   if (has_cache) {
     fill_lists<COUNT, (APPLY != 0)>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc,
-                                    log, seq, my_steps);
+                                    log, seq, my_steps, fa.pair_min_entries);
   }
   if (rd.flags & 1u) {
     for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
@@ -835,10 +836,10 @@ void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t 
 void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,
                  const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log,
                  uint32_t seq, unsigned long long* step_counter, hipStream_t stream, void* logits, int elem_size,
-                 uint32_t neg_inf, int32_t V_logits, int64_t row_stride) {
+                 uint32_t neg_inf, int32_t V_logits, int64_t row_stride, uint32_t pair_min_entries) {
   if (n_blocks <= 0) return;
   const dim3 grid(n_blocks);
-  const FusedApply fa{static_cast<unsigned char*>(logits), row_stride, V_logits, neg_inf};
+  const FusedApply fa{static_cast<unsigned char*>(logits), row_stride, V_logits, neg_inf, pair_min_entries};
   if (logits && elem_size == 2)
     hipLaunchKernelGGL((fill_kernel<false, 2>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
                        plan, voc, out, log, seq, step_counter, fa);

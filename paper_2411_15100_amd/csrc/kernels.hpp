@@ -162,6 +162,9 @@ struct FillBlock {
   uint32_t c0c1;  // c0 | c1 << 16
 };
 constexpr int32_t kFillMaxChunks = 24;  // chunks one workgroup may own (its mask words live in LDS)
+// A workgroup builds the two-byte table of a stack only if its lists for that stack have at least this many
+// entries: building it costs about as much as one queue round of walks.
+constexpr uint32_t kFillPairMinEntries = 2048;
 
 // pairs whose walk exceeded the limits
 struct OverflowLog {
@@ -205,7 +208,8 @@ void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t 
 void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,
                  const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log,
                  uint32_t seq, unsigned long long* step_counter, hipStream_t stream, void* logits = nullptr,
-                 int elem_size = 0, uint32_t neg_inf = 0, int32_t V_logits = 0, int64_t row_stride = 0);
+                 int elem_size = 0, uint32_t neg_inf = 0, int32_t V_logits = 0, int64_t row_stride = 0,
+                 uint32_t pair_min_entries = kFillPairMinEntries);
 // (c) apply; returns false if the buffer layout needs the element-wise kernel
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,
                   const uint32_t* bitmask, int32_t V_mask, const int32_t* row_index, int32_t n_rows,

@@ -47,6 +47,15 @@ def no_overflow(xgm):
     assert xgm.overflow_total() == before
 
 
+@pytest.fixture(params=["default", "two-byte table everywhere"])
+def pair_table(request, xgm):
+    """Runs a test twice: with the default threshold for the two-byte table of
+    the fill kernel, and with the table forced for every list."""
+    old = xgm.debug_set_fill_pair_threshold(1 if request.param != "default" else -1)
+    yield request.param
+    xgm.debug_set_fill_pair_threshold(old)
+
+
 def _apply_and_check(xgm, logits_np, dtype_code, torch_dtype, neg_inf_bits, d_mask, allowed, V):
     """Apply on the GPU and compare raw bit patterns with the oracle's apply."""
     B = logits_np.shape[0]
@@ -90,7 +99,7 @@ def test_workload1_arith_every_step(xgm, wl, no_overflow):
 # --------------------------------------------------------------------------
 # workload 2: JSON, vocabulary 32000, batch 1, 256 steps, fp32
 # --------------------------------------------------------------------------
-def test_workload2_json_every_step(xgm, wl, no_overflow):
+def test_workload2_json_every_step(xgm, wl, no_overflow, pair_table):
     say("workload 2: json V=32000 B=1 steps=256")
     vocab = si.make_vocab("bpe", 32000, 0)
     g = xgm.Grammar(si.JSON_GRAMMAR, "root")
@@ -201,7 +210,7 @@ def test_workload4_cache_build_csql_sample(xgm, wl):
 # workload 5 (reduced batch; the full batch-128 configuration is checked in
 # test_gpu_serving.py): distinct string-heavy schema grammars, V = 151936
 # --------------------------------------------------------------------------
-def test_workload5_distinct_grammars_batch8(xgm, wl, no_overflow):
+def test_workload5_distinct_grammars_batch8(xgm, wl, no_overflow, pair_table):
     say("workload 5 (8 distinct grammars): V=151936 bf16")
     vocab = si.make_vocab("bpe", 151936, 0)
     xv = wl.make_xgm_vocab(vocab)
@@ -427,7 +436,7 @@ def test_fill_terminated_rows_ragged_vocab_and_stop_tokens(xgm, wl):
         xgm.fill_next_token_bitmask([], d.data_ptr(), _stream())
 
 
-def test_fill_deep_stacks_and_many_parallel_stacks(xgm, wl, no_overflow):
+def test_fill_deep_stacks_and_many_parallel_stacks(xgm, wl, no_overflow, pair_table):
     vocab = si.make_vocab("bpe", 32000, 0)
     xv = wl.make_xgm_vocab(vocab)
     g = xgm.Grammar(si.JSON_GRAMMAR, "root")
