@@ -815,6 +815,8 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     RowDesc& r = rows[b];
     r.pad = 0;
     r.stack_begin = si;
+    r.frame_begin = fi;
+    r.n_frames = 0;
     if (m->terminated) {
       r.tab = DevTables{};
       r.acc = r.unc_list = r.unc_ctx = nullptr;
@@ -858,6 +860,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
       std::memcpy(h + kStackHdrWords, &m->c->unc_off_host[(size_t)top * (n_chunk + 1)], (size_t)(n_chunk + 1) * 4);
       ++si;
       for (int32_t n : s) frames[fi++] = (uint16_t)n;
+      r.n_frames += (uint32_t)s.size();
     }
   }
   // Plan the workgroups.  The work that depends on a request's state is the

@@ -500,6 +500,13 @@ struct FillShared {
   uint32_t queue_n;
 };
 
+// the header of one stack and its list offsets for chunks c0 .. c1 -> LDS (a barrier must follow)
+__device__ __forceinline__ void stage_stack_header(FillShared& sm, const XGM_GLOBAL uint32_t* sh, int32_t c0, int32_t c1) {
+  const uint32_t tid = threadIdx.x;
+  if (tid < kStackHdrWords) sm.hdr[tid] = sh[tid];
+  else if (tid - kStackHdrWords <= (uint32_t)(c1 - c0)) sm.off[tid - kStackHdrWords] = sh[kStackHdrWords + c0 + tid - kStackHdrWords];
+}
+
 template <bool COUNT, bool KEEP_UNDECIDED, class Tab>
 __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b,
                                            const int32_t c0, const int32_t c1, const uint32_t frame0,
@@ -515,12 +522,12 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
   const uint32_t* node_first = reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(rd.tab.image) + rd.tab.off_first);
   const uint32_t* first_ok = sm.hdr + kStackHdrFirst;
   for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-    // the stack's header and its list offsets go to LDS with one coalesced read
-    const XGM_GLOBAL uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + s) * hdr_stride;
-    __syncthreads();  // the previous stack's header is no longer in use
-    if (tid < kStackHdrWords) sm.hdr[tid] = sh[tid];
-    else if (tid - kStackHdrWords <= (uint32_t)(c1 - c0)) sm.off[tid - kStackHdrWords] = sh[kStackHdrWords + c0 + tid - kStackHdrWords];
-    __syncthreads();
+    // the stack's header and its list offsets go to LDS with one coalesced read (the first stack's are there already)
+    if (s > 0) {
+      __syncthreads();  // the previous stack's header is no longer in use
+      stage_stack_header(sm, stack_hdrs + (size_t)(rd.stack_begin + s) * hdr_stride, c0, c1);
+      __syncthreads();
+    }
     if (sm.off[c1 - c0] == sm.off[0]) continue;  // nothing listed here (uniform)
     const uint32_t top = sm.hdr[kStackHdrTop], depth = sm.hdr[kStackHdrDepth];
     const uint32_t ctx = sm.hdr[kStackHdrCtx];  // which context of the top's rule the frame below is, or kCtxNone
@@ -672,17 +679,16 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   const RowDesc rd = rows[b];
   const bool has_cache = rd.n_stacks > 0;
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
-  uint32_t frame0 = 0, n_frames = 0;
+  // everything the row descriptor points to is fetched in one go: tables, live frames, the first stack's
+  // header with its list offsets, and (below) the accepted words
+  const uint32_t frame0 = rd.frame_begin, n_frames = rd.n_frames;
+  const bool frames_in_lds = n_frames <= kFillFramesLds;
   if (has_cache) {
     stage_tables(rd.tab, smem, kFillThreads);
-    const XGM_GLOBAL uint32_t* first = stack_hdrs + (size_t)rd.stack_begin * hdr_stride;
-    const XGM_GLOBAL uint32_t* last = stack_hdrs + (size_t)(rd.stack_begin + rd.n_stacks - 1) * hdr_stride;
-    frame0 = first[kStackHdrFrames];
-    n_frames = last[kStackHdrFrames] + last[kStackHdrDepth] - frame0;  // the request's stacks are contiguous
-    if (n_frames <= kFillFramesLds)
+    if (frames_in_lds)
       for (uint32_t k = tid; k < n_frames; k += kFillThreads) sm.live[k] = frames[frame0 + k];
+    stage_stack_header(sm, stack_hdrs + (size_t)rd.stack_begin * hdr_stride, c0, c1);
   }
-  const bool frames_in_lds = n_frames <= kFillFramesLds;
   // 1. accepted words
   const XGM_GLOBAL uint32_t* acc = (const XGM_GLOBAL uint32_t*)rd.acc;
   for (int32_t w = tid; w < n_words; w += kFillThreads) {

@@ -139,6 +139,8 @@ struct RowDesc {
   uint32_t stack_begin;      // first stack header of this request
   uint32_t n_stacks;         // 0: terminated row (only stop bits)
   uint32_t flags;            // bit 0: the text so far is a complete sentence
+  uint32_t frame_begin;      // the request's frames: [frame_begin, frame_begin + n_frames) of the frame array,
+  uint32_t n_frames;         // stack after stack
   uint32_t pad;
 };
 // A stack header is kStackHdrWords + n_chunk + 1 uint32 words:
