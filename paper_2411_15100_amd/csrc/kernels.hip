@@ -106,7 +106,12 @@ struct LiveView {
 };
 
 // ---------------------------------------------------------------- kernel (a)
-constexpr int kClassifyThreads = 256;
+// Workgroup size of the classify kernel.  A grammar whose staged tables are
+// small runs with 256 threads (many workgroups per compute unit, short tails);
+// one that needs most of the LDS budget runs with 768, so that two workgroups
+// per compute unit still give 6 waves per SIMD.
+constexpr int kClassifyThreadsSmall = 256, kClassifyThreadsLarge = 768;
+constexpr uint32_t kClassifySmallStage = 24 * 1024;
 constexpr int kNodesPerBlock = 16;
 
 // One thread owns one token (byte-sorted order, so a wave's 64 tokens are
@@ -115,7 +120,7 @@ constexpr int kNodesPerBlock = 16;
 // registers.  Each wave packs its 64 results per node with a ballot into two
 // mask words of the rank-space bitsets.  The automaton tables (as many node
 // headers as `n_near`) are first copied into shared memory.
-template <class Tab>
+template <int kClassifyThreads, class Tab>
 __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc, int32_t node0, int32_t n_nodes,
                                               uint32_t* __restrict__ acc_rank, uint32_t* __restrict__ unc_rank,
                                               uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
@@ -179,6 +184,7 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
 }
 
 
+template <int kClassifyThreads>
 __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
     DevTables tab, DevVocab voc, int32_t node0, int32_t n_nodes, uint32_t* __restrict__ acc_rank,
     uint32_t* __restrict__ unc_rank, uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
@@ -186,7 +192,8 @@ __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
   extern __shared__ __align__(16) unsigned char smem[];
   stage_tables(tab, smem, kClassifyThreads);
   __syncthreads();
-  classify_body(LdsTab(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
+  classify_body<kClassifyThreads>(LdsTab(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count, log,
+                                  seq);
 }
 
 // Rank space -> id space: bit id of the output = bit rank_of_id[id] of the
@@ -334,7 +341,7 @@ __global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTab
 // entry over all lists of the grammar, tables staged as in the classify
 // kernel.  For each context node of the entry's rule the entry's suffix is
 // walked from that node with nothing known below it.
-constexpr int kContextThreads = 256;
+constexpr int kContextThreads = 768;
 __global__ __launch_bounds__(kContextThreads) void context_classes_kernel(DevTables tab, DevVocab voc, int32_t n_nodes,
                                                                           uint32_t total,
                                                                           const uint32_t* __restrict__ off,
@@ -782,10 +789,16 @@ void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, i
                      uint32_t* unc_rank, uint32_t* plain_rank, uint32_t* plain_count, OverflowLog* log, uint32_t seq,
                      hipStream_t stream) {
   if (n <= 0 || voc.V <= 0) return;
-  dim3 grid((voc.V + kClassifyThreads - 1) / kClassifyThreads, (n + kNodesPerBlock - 1) / kNodesPerBlock);
   const DevTables st = staged_for(tab, kClassifyLdsBudget);
-  hipLaunchKernelGGL(classify_kernel, grid, dim3(kClassifyThreads), st.stage_bytes, stream, st, voc, node0, n, acc_rank,
-                     unc_rank, plain_rank, plain_count, log, seq);
+  const int32_t ny = (n + kNodesPerBlock - 1) / kNodesPerBlock;
+  if (st.stage_bytes <= kClassifySmallStage)
+    hipLaunchKernelGGL(classify_kernel<kClassifyThreadsSmall>,
+                       dim3((voc.V + kClassifyThreadsSmall - 1) / kClassifyThreadsSmall, ny), dim3(kClassifyThreadsSmall),
+                       st.stage_bytes, stream, st, voc, node0, n, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
+  else
+    hipLaunchKernelGGL(classify_kernel<kClassifyThreadsLarge>,
+                       dim3((voc.V + kClassifyThreadsLarge - 1) / kClassifyThreadsLarge, ny), dim3(kClassifyThreadsLarge),
+                       st.stage_bytes, stream, st, voc, node0, n, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
 }
 
 void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* acc_rank, const uint32_t* unc_rank,

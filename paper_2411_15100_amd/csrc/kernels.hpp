@@ -59,7 +59,7 @@ struct TabView {
 };
 
 // LDS budgets (bytes of dynamic shared memory) for the staged tables
-constexpr int32_t kClassifyLdsBudget = 56 * 1024;
+constexpr int32_t kClassifyLdsBudget = 76 * 1024;
 constexpr int32_t kFillLdsBudget = 40 * 1024;
 // The staging split for a kernel that has `budget` bytes of LDS for the tables:
 // as many whole sections as fit, then as many headers as fit.
