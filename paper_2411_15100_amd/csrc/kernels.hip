@@ -112,11 +112,13 @@ struct LiveView {
 // per compute unit still give 6 waves per SIMD.
 constexpr int kClassifyThreadsSmall = 256, kClassifyThreadsLarge = 768;
 constexpr uint32_t kClassifySmallStage = 24 * 1024;
-constexpr int kNodesPerBlock = 16;
+// nodes a thread classifies its token at, one after the other: few for small tables (more, shorter-lived
+// workgroups: the slowest walks weigh less), more where every workgroup has a large table image to stage
+constexpr int kNodesPerBlockSmall = 4, kNodesPerBlockLarge = 16;
 
 // One thread owns one token (byte-sorted order, so a wave's 64 tokens are
 // neighbours in the sorted vocabulary and mostly share prefixes and control
-// flow) and classifies it at kNodesPerBlock nodes, the token staying in
+// flow) and classifies it at several nodes, the token staying in
 // registers.  Each wave packs its 64 results per node with a ballot into two
 // mask words of the rank-space bitsets.  The automaton tables (as many node
 // headers as `n_near`) are first copied into shared memory.
@@ -124,8 +126,7 @@ template <int kClassifyThreads, class Tab>
 __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc, int32_t node0, int32_t n_nodes,
                                               uint32_t* __restrict__ acc_rank, uint32_t* __restrict__ unc_rank,
                                               uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
-                                              OverflowLog* log, uint32_t seq) {
-
+                                              OverflowLog* log, uint32_t seq, int32_t nodes_per_block) {
   const int32_t r = blockIdx.x * kClassifyThreads + threadIdx.x;
   const bool live_lane = r < voc.V;
   uint4 tk = make_uint4(0, 0, 0, 0);
@@ -141,8 +142,8 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
     }
   }
   const int32_t word = (blockIdx.x * kClassifyThreads + (threadIdx.x & ~63)) >> 5;  // even
-  const int32_t n_begin = blockIdx.y * kNodesPerBlock;
-  const int32_t n_end = min(n_begin + kNodesPerBlock, n_nodes);
+  const int32_t n_begin = blockIdx.y * nodes_per_block;
+  const int32_t n_end = min(n_begin + nodes_per_block, n_nodes);
   // Most pairs are settled by the token's first byte: if the node cannot
   // consume it inside its frame, the token is rejected - or, at a node where
   // the rule may end, leaves the frame at position 0.  One bit per node of the
@@ -188,12 +189,12 @@ template <int kClassifyThreads>
 __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
     DevTables tab, DevVocab voc, int32_t node0, int32_t n_nodes, uint32_t* __restrict__ acc_rank,
     uint32_t* __restrict__ unc_rank, uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
-    OverflowLog* log, uint32_t seq) {
+    OverflowLog* log, uint32_t seq, int32_t nodes_per_block) {
   extern __shared__ __align__(16) unsigned char smem[];
   stage_tables(tab, smem, kClassifyThreads);
   __syncthreads();
   classify_body<kClassifyThreads>(LdsTab(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count, log,
-                                  seq);
+                                  seq, nodes_per_block);
 }
 
 // Rank space -> id space: bit id of the output = bit rank_of_id[id] of the
@@ -790,15 +791,19 @@ void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, i
                      hipStream_t stream) {
   if (n <= 0 || voc.V <= 0) return;
   const DevTables st = staged_for(tab, kClassifyLdsBudget);
-  const int32_t ny = (n + kNodesPerBlock - 1) / kNodesPerBlock;
-  if (st.stage_bytes <= kClassifySmallStage)
+  if (st.stage_bytes <= kClassifySmallStage) {
+    const int32_t ny = (n + kNodesPerBlockSmall - 1) / kNodesPerBlockSmall;
     hipLaunchKernelGGL(classify_kernel<kClassifyThreadsSmall>,
                        dim3((voc.V + kClassifyThreadsSmall - 1) / kClassifyThreadsSmall, ny), dim3(kClassifyThreadsSmall),
-                       st.stage_bytes, stream, st, voc, node0, n, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
-  else
+                       st.stage_bytes, stream, st, voc, node0, n, acc_rank, unc_rank, plain_rank, plain_count, log, seq,
+                       kNodesPerBlockSmall);
+  } else {
+    const int32_t ny = (n + kNodesPerBlockLarge - 1) / kNodesPerBlockLarge;
     hipLaunchKernelGGL(classify_kernel<kClassifyThreadsLarge>,
                        dim3((voc.V + kClassifyThreadsLarge - 1) / kClassifyThreadsLarge, ny), dim3(kClassifyThreadsLarge),
-                       st.stage_bytes, stream, st, voc, node0, n, acc_rank, unc_rank, plain_rank, plain_count, log, seq);
+                       st.stage_bytes, stream, st, voc, node0, n, acc_rank, unc_rank, plain_rank, plain_count, log, seq,
+                       kNodesPerBlockLarge);
+  }
 }
 
 void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* acc_rank, const uint32_t* unc_rank,
