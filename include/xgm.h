@@ -133,7 +133,13 @@ int32_t xgm_grammar_node_is_final(const xgm_grammar* g, int32_t node);
  * final masks are unchanged.
  * The result is kept on the device as one accepted bitset per node plus, per
  * node and per block of 4096 token ids, the list of its context-dependent
- * tokens.  Synchronous: returns after the build has finished on hip_stream. */
+ * tokens.  Each list entry also records where its token leaves the node's
+ * frame (if there is exactly one such position), the first two bytes of what
+ * is left of the token there, and - for rules that can sit on at most 16
+ * different nodes - what that rest does when walked from each of those nodes
+ * (accepted / rejected / leaves that frame too): section 3.2 taken per call
+ * site.  The fill call uses these to settle most entries without a walk.
+ * Synchronous: returns after the build has finished on hip_stream. */
 int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out);
 enum { XGM_CACHE_KEEP_PLAIN = 1 };
 /* Same, with flags: XGM_CACHE_KEEP_PLAIN also keeps, per node, the bitset of
@@ -228,9 +234,9 @@ int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int
  *                               bytes from s with the full stack survives }
  * plus the stop tokens iff the matcher can terminate; a terminated matcher
  * gets a row with only the stop tokens.  All matchers must share one
- * vocabulary; their grammars may differ.  The call packs the stacks into
- * pinned staging owned by the library, enqueues one small host-to-device copy
- * and the kernel, and returns.
+ * vocabulary; their grammars may differ.  The call packs the stacks and a plan
+ * of workgroups into pinned staging owned by the library (a ring of 8 slots),
+ * enqueues a small copy kernel and the fill kernel on hip_stream, and returns.
  * A walk that exceeds the on-chip bounds (64 frames pushed inside one token,
  * 24 pending alternatives, 4096 steps, tokens longer than 255 bytes) is never
  * guessed: the pair is recorded on the device, its bit is left 0, and
