@@ -186,6 +186,14 @@ int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h
  * h_steps (may be NULL) receives the number of automaton steps taken. */
 int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth,
                         const uint8_t* h_bytes, int32_t n, int32_t build, int32_t* h_steps);
+/* The host routine that cuts a batch into the fill kernel's workgroups, for
+ * tests without a device.  h_upto: [B][n_chunk + 1], h_upto[b][c] = number of
+ * context-dependent list entries of request b in its first c blocks of 4096
+ * token ids (non-decreasing, h_upto[b][0] = 0).  budget: workgroups the device
+ * holds at once.  h_out: cap >= B * n_chunk triples (request, first chunk,
+ * end chunk).  Returns the number of workgroups, or a negative status. */
+int32_t xgm_debug_plan_workgroups(const uint32_t* h_upto, int32_t B, int32_t n_chunk, int32_t budget, uint32_t* h_out,
+                                  int32_t cap);
 /* A frame whose current node is `top` can only sit on one of the few nodes that
  * follow a reference to top's rule (directly, or through references in tail
  * position).  Returns the index of `below` among them (what the fill kernel

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     debug_fill_count_steps,
     fill_and_apply,
     debug_fill_timed,
+    debug_plan_workgroups,
     debug_set_fill_pair_threshold,
     MatcherBatch,
     overflow_total,

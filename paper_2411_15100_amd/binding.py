@@ -42,6 +42,7 @@ SIGNATURES = {
     "xgm_debug_walk_host": (_i32, [_vp, _vp, _i32, _cp, _i32, _i32, _vp]),
     "xgm_debug_next_bytes_host": (_i32, [_vp, _vp, _i32, _i32, _vp]),
     "xgm_debug_context_index": (_i32, [_vp, _i32, _i32]),
+    "xgm_debug_plan_workgroups": (_i32, [_vp, _i32, _i32, _i32, _vp, _i32]),
     "xgm_cache_build": (_i32, [_vp, _vp, _vp, _pp]),
     "xgm_cache_build_ex": (_i32, [_vp, _vp, _vp, ctypes.c_uint32, _pp]),
     "xgm_cache_num_uncertain_plain": (_i32, [_vp, _i32]),
@@ -356,6 +357,16 @@ def debug_fill_count_steps(batch: "MatcherBatch", d_bitmask: int, stream: int = 
     _check(load_library().xgm_debug_fill_count_steps(batch._arr, len(batch.matchers), ctypes.c_void_p(d_bitmask),
                                                      ctypes.c_void_p(stream), ctypes.byref(n)))
     return int(n.value)
+
+
+def debug_plan_workgroups(upto: np.ndarray, budget: int) -> np.ndarray:
+    """upto: uint32 [B, n_chunk + 1] cumulative list entries; returns int array [n, 3] of (row, c0, c1)."""
+    upto = np.ascontiguousarray(upto, dtype=np.uint32)
+    B, nc1 = upto.shape
+    out = np.zeros((B * (nc1 - 1), 3), dtype=np.uint32)
+    n = _check(load_library().xgm_debug_plan_workgroups(upto.ctypes.data, B, nc1 - 1, int(budget), out.ctypes.data,
+                                                        out.shape[0]))
+    return out[:n].astype(np.int64)
 
 
 def debug_set_fill_pair_threshold(entries: int) -> int:

@@ -13,6 +13,7 @@
 #include "../../include/xgm.h"
 #include "automaton.hpp"
 #include "engine.hpp"
+#include "plan.hpp"
 #include "kernels.hpp"
 #include "walk.hpp"
 
@@ -230,7 +231,6 @@ struct Context {
   std::vector<const xgm_matcher*> last_matchers;
   xgm_vocab* last_vocab = nullptr;
   // scratch of the workgroup planner (kept to avoid per-step allocation)
-  std::vector<uint64_t> plan_entries;
   uint32_t pair_min_entries = kFillPairMinEntries;
   int32_t resident_blocks = 0;  // fill workgroups the device holds at once (two per compute unit)
 };
@@ -362,6 +362,24 @@ int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h
   int cls = Engine(&g->A).classify(node, h_bytes, n);
   if (cls < 0) return fail(XGM_ERR_TOO_LARGE, "classify_host: configuration limit exceeded");
   return cls;
+  API_END
+}
+
+int32_t xgm_debug_plan_workgroups(const uint32_t* h_upto, int32_t B, int32_t n_chunk, int32_t budget, uint32_t* h_out,
+                                  int32_t cap) {
+  API_BEGIN
+  if (!h_upto || !h_out || B <= 0 || n_chunk <= 0 || n_chunk > 65535 || budget < 0 || (int64_t)cap < (int64_t)B * n_chunk)
+    return fail(XGM_ERR_BAD_ARG, "plan_workgroups: bad argument (cap must be at least B * n_chunk)");
+  std::vector<FillBlock> plan((size_t)B * n_chunk);
+  const int32_t n = plan_workgroups(
+      B, n_chunk, budget, [&](int32_t b, int32_t c) { return (uint64_t)h_upto[(size_t)b * (n_chunk + 1) + c]; },
+      plan.data());
+  for (int32_t k = 0; k < n; ++k) {
+    h_out[3 * k] = plan[k].row;
+    h_out[3 * k + 1] = plan[k].c0c1 & 0xFFFFu;
+    h_out[3 * k + 2] = plan[k].c0c1 >> 16;
+  }
+  return n;
   API_END
 }
 
@@ -863,51 +881,17 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
       r.n_frames += (uint32_t)s.size();
     }
   }
-  // Plan the workgroups.  The work that depends on a request's state is the
-  // number of entries in the context-dependent lists of its stack tops.  All
-  // workgroups of a launch should be resident together (two per compute unit),
-  // so the budget of workgroups is shared out in proportion to that number:
-  // every request gets at least as many as its mask words need, and its chunks
-  // are cut where the running entry count passes equal shares.
+  // Plan the workgroups (plan.hpp): two per compute unit are resident at once.
   auto* plan = reinterpret_cast<FillBlock*>((char*)slot.h_buf + off_plan);
-  int32_t n_blocks = 0;
-  {
-    const int32_t min_blocks = (n_chunk + kFillMaxChunks - 1) / kFillMaxChunks;
-    const int32_t budget = std::max(B * min_blocks, C.resident_blocks);
-    uint64_t total = 0;
-    std::vector<uint64_t>& row_entries = C.plan_entries;
-    row_entries.assign(B, 0);
-    for (int32_t b = 0; b < B; ++b) {
-      for (uint32_t s = 0; s < rows[b].n_stacks; ++s) {
-        const uint32_t* off = hdrs + (size_t)(rows[b].stack_begin + s) * hdr_words + kStackHdrWords;
-        row_entries[b] += off[n_chunk] - off[0];
-      }
-      total += row_entries[b];
-    }
-    const int32_t spare = budget - B * min_blocks;
-    for (int32_t b = 0; b < B; ++b) {
-      int32_t k = min_blocks;
-      if (total) k += (int32_t)((uint64_t)spare * row_entries[b] / total);
-      k = std::min(k, n_chunk);
-      // cut after chunk c when the entries up to and including c reach the next share
-      const uint32_t* off0 = hdrs + (size_t)rows[b].stack_begin * hdr_words + kStackHdrWords;
-      int32_t c0 = 0, made = 0;
-      for (int32_t c = 0; c < n_chunk; ++c) {
-        bool cut = c + 1 == n_chunk || c + 1 - c0 == kFillMaxChunks;
-        if (!cut && made + 1 < k && row_entries[b]) {
-          uint64_t run = 0;  // entries of chunks 0 .. c
-          for (uint32_t s = 0; s < rows[b].n_stacks; ++s)
-            run += off0[(size_t)s * hdr_words + c + 1] - off0[(size_t)s * hdr_words];
-          cut = run * (uint64_t)k >= row_entries[b] * (uint64_t)(made + 1);
-        }
-        if (cut) {
-          plan[n_blocks++] = FillBlock{(uint32_t)b, (uint32_t)c0 | ((uint32_t)(c + 1) << 16)};
-          c0 = c + 1;
-          ++made;
-        }
-      }
-    }
-  }
+  const int32_t n_blocks = plan_workgroups(
+      B, n_chunk, C.resident_blocks,
+      [&](int32_t b, int32_t c) {
+        uint64_t run = 0;
+        const uint32_t* off0 = hdrs + (size_t)rows[b].stack_begin * hdr_words + kStackHdrWords;
+        for (uint32_t s = 0; s < rows[b].n_stacks; ++s) run += off0[(size_t)s * hdr_words + c] - off0[(size_t)s * hdr_words];
+        return run;
+      },
+      plan);
   if (timing) HIP_OK(hipEventRecord(timing[0], stream));
   launch_upload(slot.h_dev, slot.d_buf, off_plan + (size_t)n_blocks * sizeof(FillBlock), stream);
   if (timing) HIP_OK(hipEventRecord(timing[1], stream));

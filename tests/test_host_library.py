@@ -393,3 +393,39 @@ def test_kernel_walk_reports_overflow_instead_of_guessing():
     assert g.debug_walk_host([start], b"(" * 15, True) == 2
     assert g.debug_walk_host([start], b"1" * 300, True) == 3     # longer than 255 bytes
     assert g.debug_classify_host(start, b"1" * 300) == 2
+
+
+def test_workgroup_plan_covers_every_chunk_once_and_follows_the_load():
+    """The fill kernel's workgroups: every (request, chunk) in exactly one,
+    at most 24 chunks each, rows in order; a request with most of the list
+    entries gets most of the spare workgroups; the total stays near the budget."""
+    rng = np.random.Generator(np.random.PCG64(5))
+    for B, n_chunk, budget in [(1, 1, 512), (3, 38, 512), (128, 38, 512), (16, 32, 512), (7, 100, 64), (128, 38, 0), (5, 250, 512)]:
+        per_chunk = rng.integers(0, 50, size=(B, n_chunk)).astype(np.uint64)
+        heavy = int(rng.integers(0, B))
+        per_chunk[heavy] += 3000          # one request in a state with long lists
+        if B > 2:
+            per_chunk[(heavy + 1) % B] = 0  # and one with none
+        upto = np.zeros((B, n_chunk + 1), dtype=np.uint32)
+        upto[:, 1:] = np.cumsum(per_chunk, axis=1)
+        plan = xgm.debug_plan_workgroups(upto, budget)
+        covered = np.zeros((B, n_chunk), dtype=np.int32)
+        last = (-1, 0)
+        for row, c0, c1 in plan:
+            assert 0 <= c0 < c1 <= n_chunk and c1 - c0 <= 24
+            assert (row, c0) >= last
+            last = (row, c1)
+            covered[row, c0:c1] += 1
+        assert (covered == 1).all()
+        min_blocks = -(-n_chunk // 24)
+        counts = np.bincount(plan[:, 0], minlength=B)
+        assert (counts >= min_blocks).all()
+        assert len(plan) <= max(budget, B * min_blocks) + B * min_blocks
+        if B > 1 and budget >= 4 * B * min_blocks:
+            assert counts[heavy] == counts.max() and counts[heavy] > 2 * np.median(counts)
+        if B > 2:
+            assert counts[(heavy + 1) % B] == min_blocks
+        # the heavy request's workgroups carry about equal numbers of entries
+        if counts[heavy] >= 4:
+            loads = [int(upto[heavy, c1] - upto[heavy, c0]) for row, c0, c1 in plan if row == heavy]
+            assert max(loads) <= 2 * (sum(loads) / len(loads)) + 3100
