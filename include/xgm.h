@@ -68,7 +68,8 @@ typedef enum { XGM_F32 = 0, XGM_BF16 = 1, XGM_F16 = 2 } xgm_dtype;
 enum {
   XGM_MAX_STACKS = 64,       /* parallel stacks per matcher */
   XGM_MAX_STACK_DEPTH = 4096,/* frames per stack */
-  XGM_MAX_NODES = 32767      /* automaton nodes per grammar */
+  XGM_MAX_NODES = 32767,     /* automaton nodes per grammar */
+  XGM_MAX_VOCAB = 589824     /* tokens per vocabulary (two bitset rows of a node must fit the LDS of one workgroup) */
 };
 
 const char* xgm_last_error(void);

@@ -283,6 +283,7 @@ int xgm_vocab_create(const uint8_t* h_bytes, const int64_t* h_offsets, int32_t V
   if (!out) return fail(XGM_ERR_BAD_ARG, "vocab_create: out is null");
   *out = nullptr;
   if (V <= 0 || !h_offsets) return fail(XGM_ERR_BAD_ARG, "vocab_create: V must be positive and offsets non-null");
+  if (V > XGM_MAX_VOCAB) return fail(XGM_ERR_TOO_LARGE, "vocab_create: more than XGM_MAX_VOCAB tokens");
   if (n_stop < 0 || (n_stop > 0 && !h_stop_ids)) return fail(XGM_ERR_BAD_ARG, "vocab_create: bad stop ids");
   if (h_offsets[0] != 0) return fail(XGM_ERR_BAD_ARG, "vocab_create: offsets[0] must be 0");
   for (int32_t i = 0; i < V; ++i)

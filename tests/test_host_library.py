@@ -395,6 +395,13 @@ def test_kernel_walk_reports_overflow_instead_of_guessing():
     assert g.debug_classify_host(start, b"1" * 300) == 2
 
 
+def test_vocabulary_size_limit():
+    n = 589825
+    with pytest.raises(xgm.XgmError) as e:
+        xgm.Vocab(np.zeros(1, dtype=np.uint8), np.zeros(n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32))
+    assert e.value.args[0] == -10 or "MAX_VOCAB" in str(e.value)
+
+
 def test_workgroup_plan_covers_every_chunk_once_and_follows_the_load():
     """The fill kernel's workgroups: every (request, chunk) in exactly one,
     at most 24 chunks each, rows in order; a request with most of the list
