@@ -216,7 +216,7 @@ def main():
                         "us_per_mask": spent / (checks / V) * 1e6}
 
     out = {
-        "metric": "vocab token checks/sec (per-step bitmask fill + in-place -inf apply, batch x vocab)",
+        "metric": "vocab token checks/sec + per-step bitmask fill+apply \u00b5s (batch\u00d7vocab)",
         "value": B * V / (ms_per_step * 1e-3),
         "unit": "token checks/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -224,7 +224,8 @@ def main():
         "fill_plus_apply_us": ms_per_step * 1e3,
         "fused_fill_and_apply_us": fused_us,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32 masks / bf16 logits (integer automaton walk; no floating-point arithmetic)",
+        "dtype": "u32",
+        "logits_dtype": "bf16 (only -inf patterns are stored; no floating-point arithmetic anywhere on the path)",
         "data": "synthetic",
         "config": {"workload": f"serving decode step: batch {B} x vocab {V}, {B} distinct string-heavy schema "
                                f"grammars, bf16 logits [{B},{V}], {n_sets} pre-walked state sets, "
