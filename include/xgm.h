@@ -47,6 +47,7 @@ typedef struct xgm_vocab xgm_vocab;
 typedef struct xgm_grammar xgm_grammar;
 typedef struct xgm_cache xgm_cache;
 typedef struct xgm_matcher xgm_matcher;
+typedef struct xgm_batch xgm_batch;
 
 typedef enum {
   XGM_OK = 0,
@@ -69,7 +70,11 @@ enum {
   XGM_MAX_STACKS = 64,       /* parallel stacks per matcher */
   XGM_MAX_STACK_DEPTH = 4096,/* frames per stack */
   XGM_MAX_NODES = 32767,     /* automaton nodes per grammar */
-  XGM_MAX_VOCAB = 589824     /* tokens per vocabulary (two bitset rows of a node must fit the LDS of one workgroup) */
+  XGM_MAX_VOCAB = 589824,    /* tokens per vocabulary (two bitset rows of a node must fit the LDS of one workgroup) */
+  XGM_BATCH_MAX_HISTORY = 63,/* older states a row of an xgm_batch can keep */
+  XGM_BATCH_MAX_STACKS = 16, /* parallel stacks per row of an xgm_batch */
+  XGM_BATCH_MAX_DEPTH = 128, /* frames per stack in an xgm_batch */
+  XGM_BATCH_MAX_ROWS = 1024  /* rows of an xgm_batch */
 };
 
 const char* xgm_last_error(void);
@@ -287,6 +292,68 @@ int xgm_fill_overflow_fixup(void* hip_stream);
 /* Total number of pairs recorded by all fills so far (synchronises the
  * device to read the counter). */
 int64_t xgm_overflow_total(void);
+
+/* ------------------------------------------- states that live on the device
+ * 4b. The matcher states of a fixed batch of requests kept in device memory
+ * (section 3.3: the persistent stack and its rollback, here as a ring of
+ * states per row in HBM).  The sampled token ids never leave the device: a
+ * kernel moves every row's stacks on by its token and writes the row's next
+ * state in the layout the fill kernel reads, another plans the workgroups of
+ * the next fill; a fill is then a single launch without any host packing or
+ * upload.  Going back k tokens (speculative decoding, section 3.3) re-points a
+ * row k states back.  Calls on one batch must be ordered by the caller (one
+ * stream, or events).
+ *
+ * xgm_batch_create: row b starts in the current state of ms[b] (host
+ * matchers with mask caches over one vocabulary; they are not referenced
+ * afterwards, their caches are).  history: how many older states each row
+ * keeps (0 .. XGM_BATCH_MAX_HISTORY).  Device limits per row:
+ * XGM_BATCH_MAX_STACKS parallel stacks of XGM_BATCH_MAX_DEPTH frames
+ * (XGM_ERR_TOO_MANY_STACKS / XGM_ERR_TOO_LARGE at creation; at run time such
+ * a row reports the code in its status and keeps its state, see
+ * xgm_batch_get_row / xgm_batch_set_row for the way through the host).
+ * B <= XGM_BATCH_MAX_ROWS and B * (vocabulary chunks of 4096 ids + 1) <= 32768.
+ * Synchronises hip_stream. */
+int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* hip_stream, xgm_batch** out);
+void xgm_batch_destroy(xgm_batch* bt);
+int32_t xgm_batch_size(const xgm_batch* bt);
+/* Asynchronous.  d_token_ids: [B] device int32; row b accepts token
+ * d_token_ids[b] exactly as xgm_matcher_accept_token would (same resulting
+ * stacks, in the same order); a negative id leaves the row and its status
+ * alone.  Per-row result in the status array: XGM_OK, XGM_ERR_TOKEN_REJECTED,
+ * XGM_ERR_TERMINATED, XGM_ERR_BAD_ARG (id >= V), XGM_ERR_TOO_MANY_STACKS or
+ * XGM_ERR_TOO_LARGE (device limits, or the walk's limits: 64 frames pushed
+ * inside one token, 24 pending alternatives, 4096 steps, 32 end
+ * configurations); on any error the row keeps its state. */
+int xgm_batch_accept_tokens(xgm_batch* bt, const int32_t* d_token_ids, void* hip_stream);
+/* Asynchronous.  d_steps: [B] device int32; row b goes back d_steps[b] accepted
+ * tokens (<= 0: stays).  More than the row still holds: XGM_ERR_BAD_ARG in its
+ * status, state unchanged. */
+int xgm_batch_rollback(xgm_batch* bt, const int32_t* d_steps, void* hip_stream);
+/* Synchronises hip_stream and copies the per-row status of the last accept /
+ * rollback into h_status[B] (host).  Returns the number of rows whose status
+ * is not XGM_OK, or a negative status of the call itself. */
+int xgm_batch_status(xgm_batch* bt, int32_t* h_status, void* hip_stream);
+/* The way through the host for a row that hit a device limit (both
+ * synchronise hip_stream): get_row copies the row's current state into the
+ * host matcher m (which must belong to the row's mask cache); set_row makes
+ * m's state the row's next state (it counts as one accepted token for
+ * rollback). */
+int xgm_batch_get_row(xgm_batch* bt, int32_t row, xgm_matcher* m, void* hip_stream);
+int xgm_batch_set_row(xgm_batch* bt, int32_t row, const xgm_matcher* m, void* hip_stream);
+/* As xgm_fill_next_token_bitmask / xgm_fill_and_apply for the batch's current
+ * states: one kernel launch, nothing packed or uploaded.  Walks that exceed
+ * the on-chip limits are recorded and decided by xgm_fill_overflow_fixup() as
+ * for the host-state calls. */
+int xgm_batch_fill_next_token_bitmask(xgm_batch* bt, int32_t* d_bitmask, void* hip_stream);
+int xgm_batch_fill_and_apply(xgm_batch* bt, int32_t* d_bitmask, void* d_logits, xgm_dtype dt, int32_t V_logits,
+                             int64_t row_stride_elems, void* hip_stream);
+/* For tests without a device: accept a token with the routine the device uses
+ * (a depth-first walk over the flattened tables that writes out every stack
+ * the token can end in) instead of the host engine.  Same results and errors
+ * as xgm_matcher_accept_token, plus XGM_ERR_TOO_LARGE when the walk's limits
+ * are hit. */
+int xgm_debug_matcher_accept_token_walk(xgm_matcher* m, int32_t token_id);
 
 /* --------------------------------------------------------------------- apply
  * 5. Apply a bitmask to logits in place (asynchronous; section 2.1).

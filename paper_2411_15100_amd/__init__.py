@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     debug_plan_workgroups,
     debug_set_fill_pair_threshold,
     MatcherBatch,
+    DeviceBatch,
     overflow_total,
     apply_token_bitmask_inplace,
     bitmask_words,

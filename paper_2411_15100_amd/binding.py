@@ -69,6 +69,17 @@ SIGNATURES = {
     "xgm_debug_fill_count_steps": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_debug_set_fill_pair_threshold": (_i32, [_i32]),
     "xgm_debug_fill_timed": (_i32, [_vp, _i32, _vp, _vp, _vp]),
+    "xgm_batch_create": (_i32, [_vp, _i32, _i32, _vp, _pp]),
+    "xgm_batch_destroy": (None, [_vp]),
+    "xgm_batch_size": (_i32, [_vp]),
+    "xgm_batch_accept_tokens": (_i32, [_vp, _vp, _vp]),
+    "xgm_batch_rollback": (_i32, [_vp, _vp, _vp]),
+    "xgm_batch_status": (_i32, [_vp, _vp, _vp]),
+    "xgm_batch_get_row": (_i32, [_vp, _i32, _vp, _vp]),
+    "xgm_batch_set_row": (_i32, [_vp, _i32, _vp, _vp]),
+    "xgm_batch_fill_next_token_bitmask": (_i32, [_vp, _vp, _vp]),
+    "xgm_batch_fill_and_apply": (_i32, [_vp, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
+    "xgm_debug_matcher_accept_token_walk": (_i32, [_vp, _i32]),
     "xgm_fill_overflow_fixup": (_i32, [_vp]),
     "xgm_overflow_total": (_i64, []),
     "xgm_apply_token_bitmask_inplace": (_i32, [_vp, _i32, _i32, _i32, _i64, _vp, _i32, _vp, _i32, _vp]),
@@ -306,6 +317,10 @@ class Matcher:
     def try_accept_token(self, token_id: int) -> int:
         return load_library().xgm_matcher_accept_token(self._h, int(token_id))
 
+    def debug_try_accept_token_walk(self, token_id: int) -> int:
+        """accept_token through the depth-first walk the device uses (status code)."""
+        return load_library().xgm_debug_matcher_accept_token_walk(self._h, int(token_id))
+
     def is_terminated(self) -> bool:
         return bool(_check(load_library().xgm_matcher_is_terminated(self._h)))
 
@@ -340,6 +355,51 @@ class MatcherBatch:
     def fill_next_token_bitmask(self, d_bitmask: int, stream: int = 0):
         _check(load_library().xgm_fill_next_token_bitmask(self._arr, len(self.matchers), ctypes.c_void_p(d_bitmask),
                                                           ctypes.c_void_p(stream)))
+
+
+class DeviceBatch:
+    """Matcher states of a fixed batch kept in device memory (xgm_batch_*).
+
+    All pointer arguments are device addresses (ints); token ids and rollback
+    steps are int32 [B] device arrays."""
+
+    def __init__(self, matchers, history: int = 8, stream: int = 0):
+        lib = load_library()
+        arr = (ctypes.c_void_p * len(matchers))(*[m._h for m in matchers])
+        h = ctypes.c_void_p()
+        _check(lib.xgm_batch_create(arr, len(matchers), int(history), ctypes.c_void_p(stream), ctypes.byref(h)))
+        self._h = h
+        self.size = len(matchers)
+
+    def __del__(self, _destroy=_destroy):
+        _destroy("xgm_batch_destroy", self)
+
+    def accept_tokens(self, d_token_ids: int, stream: int = 0):
+        _check(load_library().xgm_batch_accept_tokens(self._h, ctypes.c_void_p(d_token_ids), ctypes.c_void_p(stream)))
+
+    def rollback(self, d_steps: int, stream: int = 0):
+        _check(load_library().xgm_batch_rollback(self._h, ctypes.c_void_p(d_steps), ctypes.c_void_p(stream)))
+
+    def status(self, stream: int = 0) -> np.ndarray:
+        out = np.zeros(self.size, dtype=np.int32)
+        _check(load_library().xgm_batch_status(self._h, out.ctypes.data, ctypes.c_void_p(stream)))
+        return out
+
+    def get_row(self, row: int, matcher: "Matcher", stream: int = 0):
+        _check(load_library().xgm_batch_get_row(self._h, int(row), matcher._h, ctypes.c_void_p(stream)))
+
+    def set_row(self, row: int, matcher: "Matcher", stream: int = 0):
+        _check(load_library().xgm_batch_set_row(self._h, int(row), matcher._h, ctypes.c_void_p(stream)))
+
+    def fill_next_token_bitmask(self, d_bitmask: int, stream: int = 0):
+        _check(load_library().xgm_batch_fill_next_token_bitmask(self._h, ctypes.c_void_p(d_bitmask),
+                                                                ctypes.c_void_p(stream)))
+
+    def fill_and_apply(self, d_bitmask: int, d_logits: int, dtype: int, v_logits: int, row_stride: int,
+                       stream: int = 0):
+        _check(load_library().xgm_batch_fill_and_apply(self._h, ctypes.c_void_p(d_bitmask), ctypes.c_void_p(d_logits),
+                                                       int(dtype), int(v_logits), int(row_stride),
+                                                       ctypes.c_void_p(stream)))
 
 
 def fill_and_apply(matchers, d_bitmask: int, d_logits: int, dtype: int, v_logits: int, row_stride: int,

@@ -8,6 +8,7 @@
 #include <mutex>
 #include <numeric>
 #include <string>
+#include <set>
 #include <vector>
 
 #include "../../include/xgm.h"
@@ -153,6 +154,15 @@ struct xgm_matcher {
   bool terminated = false;
 };
 
+// device-resident states of a fixed batch of requests
+struct xgm_batch {
+  int32_t B = 0, H = 0;
+  xgm_vocab* v = nullptr;
+  std::vector<xgm_cache*> caches;  // one per row (referenced)
+  DevBatch dev{};
+  std::vector<void*> dev_ptrs;
+};
+
 xgm_vocab::~xgm_vocab() { for (void* p : dev_ptrs) slab().release(p); }
 
 namespace {
@@ -230,6 +240,7 @@ struct Context {
   int32_t* last_bitmask = nullptr;
   std::vector<const xgm_matcher*> last_matchers;
   xgm_vocab* last_vocab = nullptr;
+  const struct xgm_batch* last_batch = nullptr;  // set instead of last_slot when the fill read device-resident states
   // scratch of the workgroup planner (kept to avoid per-step allocation)
   uint32_t pair_min_entries = kFillPairMinEntries;
   int32_t resident_blocks = 0;  // fill workgroups the device holds at once (two per compute unit)
@@ -456,6 +467,61 @@ int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t de
   API_END
 }
 
+namespace {
+struct HostStackSink {
+  uint16_t* frames;
+  uint32_t* depth;
+  uint32_t* count;
+  uint32_t* overflow;
+  uint32_t capacity, max_depth;
+  uint32_t claim() { return (*count)++; }
+};
+}  // namespace
+
+int xgm_debug_matcher_accept_token_walk(xgm_matcher* m, int32_t token_id) {
+  API_BEGIN
+  if (!m || !m->v) return fail(XGM_ERR_BAD_ARG, "accept_token_walk: matcher has no vocabulary");
+  if (token_id < 0 || token_id >= m->v->V) return fail(XGM_ERR_BAD_ARG, "accept_token_walk: token id out of range");
+  if (m->terminated) return fail(XGM_ERR_TERMINATED, "accept: the matcher has terminated");
+  const xgm_vocab& v = *m->v;
+  const Automaton& A = m->g->A;
+  if (v.is_stop[token_id]) {
+    if (!Engine(&A).can_terminate(m->stacks)) return fail(XGM_ERR_TOKEN_REJECTED, "accept: stop token before the text is complete");
+    m->terminated = true;
+    return XGM_OK;
+  }
+  const int32_t n = (int32_t)(v.off[token_id + 1] - v.off[token_id]);
+  if (n == 0) return fail(XGM_ERR_TOKEN_REJECTED, "accept: a token without bytes is never allowed");
+  const uint8_t* bytes = v.bytes.data() + v.off[token_id];
+  const CompactTab T{TabView{reinterpret_cast<const uint2*>(A.hdr.data()), A.n_nodes,
+                             reinterpret_cast<const uint2*>(A.hdr.data()), A.cls.data(), A.shapes.data(),
+                             A.targets.data(), A.alts.data(), A.follow_words.data(), A.n_cls}};
+  unsigned char row[16] = {0};
+  std::memcpy(row, bytes, std::min<int32_t>(n, 15));
+  row[15] = (unsigned char)std::min<int32_t>(n, 255);
+  uint4 tk;
+  std::memcpy(&tk, row, 16);
+  std::vector<uint16_t> cand((size_t)kBatchMaxCandidates * kBatchMaxDepth);
+  std::vector<uint32_t> depth(kBatchMaxCandidates);
+  uint32_t count = 0, overflow = 0;
+  HostStackSink sink{cand.data(), depth.data(), &count, &overflow, kBatchMaxCandidates, kBatchMaxDepth};
+  const CollectStacks<CompactTab, HostStackSink> collect{&T, &sink};
+  std::set<Stack> next;
+  for (const Stack& s : m->stacks) {
+    std::vector<uint16_t> live(s.begin(), s.end());
+    count = 0;
+    const int rc = walk_token<false>(T, tk, bytes, n, live.back(), live.data(), (uint32_t)live.size(), (uint32_t*)nullptr,
+                                     (const uint32_t*)nullptr, 0, (uint32_t*)nullptr, collect);
+    if (rc == kOverflow || overflow) return fail(XGM_ERR_TOO_LARGE, "accept_token_walk: the walk exceeded its limits");
+    for (uint32_t k = 0; k < count; ++k)
+      next.insert(Stack(cand.begin() + (size_t)k * kBatchMaxDepth, cand.begin() + (size_t)k * kBatchMaxDepth + depth[k]));
+  }
+  if (next.empty()) return fail(XGM_ERR_TOKEN_REJECTED, "accept: the bytes are not allowed here");
+  m->stacks.assign(next.begin(), next.end());
+  return XGM_OK;
+  API_END
+}
+
 // --------------------------------------------------------------------- cache
 int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out) {
   return xgm_cache_build_ex(g, v, hip_stream, 0, out);
@@ -616,8 +682,8 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       ctx_off[r + 1] = (uint32_t)ctx_node.size();
     }
     if (ctx_node.empty()) ctx_node.push_back(0);
-    uint32_t* d_ctx_off = temp(dev_upload(ctx_off));
-    uint16_t* d_ctx_node = temp(dev_upload(ctx_node));
+    uint32_t* d_ctx_off = keep(slab_upload(ctx_off));
+    uint16_t* d_ctx_node = keep(slab_upload(ctx_node));
     launch_list_uncertain(dv, N, unc_id, d_off, d_list, stream);
     launch_annotate_lists(tab, dv, N, d_off, (uint32_t)total, d_list, d_list_ctx, d_ctx_off, d_ctx_node, stream);
     HIP_OK(hipGetLastError());
@@ -629,6 +695,8 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     c->host.unc_off = d_off;
     c->host.unc_list = d_list;
     c->host.unc_ctx = d_list_ctx;
+    c->host.ctx_off = d_ctx_off;
+    c->host.ctx_node = d_ctx_node;
     c->build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_build0).count();
     c->host.n_nodes = N;
   } catch (...) {
@@ -776,6 +844,37 @@ struct FusedLogits {
   int32_t V_logits;
   int64_t row_stride;
 };
+// One stack header as the fill kernel reads it (see kStackHdr* in kernels.hpp);
+// `frame_offset`: where the stack's frames start in the frame array.
+static void pack_stack_header(const Automaton& A, const xgm_cache& c, const Stack& s, uint32_t frame_offset, uint32_t* h) {
+  const int32_t n_chunk = c.v->dv.n_chunk;
+  const int32_t top = s.back();
+  h[kStackHdrTop] = (uint32_t)top;
+  h[kStackHdrDepth] = (uint32_t)s.size();
+  h[kStackHdrFrames] = frame_offset;
+  h[kStackHdrCtx] = kCtxNone;
+  if (s.size() >= 2) {
+    const auto& ctx = A.contexts[A.node_rule[top]];
+    if (ctx.size() <= kCtxMax) {
+      auto it = std::lower_bound(ctx.begin(), ctx.end(), s[s.size() - 2]);
+      if (it != ctx.end() && *it == s[s.size() - 2]) h[kStackHdrCtx] = (uint32_t)(it - ctx.begin());
+    }
+  }
+  // bytes that can be consumed from this stack: at the top node, or - as
+  // long as the frames passed so far may all end here - at the frames
+  // below; and the same for the stack without its top frame
+  for (int below = 0; below < 2; ++below) {
+    uint32_t* ok = h + (below ? kStackHdrBelow : kStackHdrFirst);
+    for (int w = 0; w < 8; ++w) ok[w] = 0;
+    for (size_t k = s.size() - below; k-- > 0;) {
+      const uint32_t* fw = &A.node_first_words[(size_t)s[k] * 8];
+      for (int w = 0; w < 8; ++w) ok[w] |= fw[w];
+      if (!A.node_final[s[k]]) break;
+    }
+  }
+  std::memcpy(h + kStackHdrWords, &c.unc_off_host[(size_t)top * (n_chunk + 1)], (size_t)(n_chunk + 1) * 4);
+}
+
 static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream,
                      unsigned long long* d_step_counter, hipEvent_t* timing = nullptr,
                      const FusedLogits* fused = nullptr) {
@@ -851,32 +950,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     r.n_stacks = (uint32_t)m->stacks.size();
     r.flags = Engine(&A).can_terminate(m->stacks) ? 1u : 0u;
     for (auto& s : m->stacks) {
-      uint32_t* h = hdrs + (size_t)si * hdr_words;
-      const int32_t top = s.back();
-      h[kStackHdrTop] = (uint32_t)top;
-      h[kStackHdrDepth] = (uint32_t)s.size();
-      h[kStackHdrFrames] = fi;
-      h[kStackHdrCtx] = kCtxNone;
-      if (s.size() >= 2) {
-        const auto& ctx = A.contexts[A.node_rule[top]];
-        if (ctx.size() <= kCtxMax) {
-          auto it = std::lower_bound(ctx.begin(), ctx.end(), s[s.size() - 2]);
-          if (it != ctx.end() && *it == s[s.size() - 2]) h[kStackHdrCtx] = (uint32_t)(it - ctx.begin());
-        }
-      }
-      // bytes that can be consumed from this stack: at the top node, or - as
-      // long as the frames passed so far may all end here - at the frames
-      // below; and the same for the stack without its top frame
-      for (int below = 0; below < 2; ++below) {
-        uint32_t* ok = h + (below ? kStackHdrBelow : kStackHdrFirst);
-        for (int w = 0; w < 8; ++w) ok[w] = 0;
-        for (size_t k = s.size() - below; k-- > 0;) {
-          const uint32_t* fw = &A.node_first_words[(size_t)s[k] * 8];
-          for (int w = 0; w < 8; ++w) ok[w] |= fw[w];
-          if (!A.node_final[s[k]]) break;
-        }
-      }
-      std::memcpy(h + kStackHdrWords, &m->c->unc_off_host[(size_t)top * (n_chunk + 1)], (size_t)(n_chunk + 1) * 4);
+      pack_stack_header(A, *m->c, s, fi, hdrs + (size_t)si * hdr_words);
       ++si;
       for (int32_t n : s) frames[fi++] = (uint16_t)n;
       r.n_frames += (uint32_t)s.size();
@@ -909,6 +983,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   HIP_OK(hipEventRecord(slot.done, stream));
   slot.used = true;
   C.last_slot = C.next_slot;
+  C.last_batch = nullptr;
   C.next_slot = (C.next_slot + 1) % Context::kSlots;
   C.last_seq = seq;
   C.last_B = B;
@@ -923,22 +998,30 @@ int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bi
   return fill_impl(ms, B, d_bitmask, hip_stream, nullptr);
 }
 
+// checks the logits arguments of a fused call and fills in `f`
+static int fused_logits(void* d_logits, xgm_dtype dt, int32_t V_logits, int64_t row_stride_elems, int32_t V, FusedLogits* f) {
+  if (V_logits < V) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: logits rows are narrower than the vocabulary");
+  if (row_stride_elems < V_logits) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: row stride smaller than the row");
+  *f = FusedLogits{d_logits, 0, 0u, V_logits, row_stride_elems};
+  switch (dt) {
+    case XGM_F32: f->esize = 4; f->neg_inf = 0xFF800000u; break;
+    case XGM_BF16: f->esize = 2; f->neg_inf = 0xFF80u; break;
+    case XGM_F16: f->esize = 2; f->neg_inf = 0xFC00u; break;
+    default: return fail(XGM_ERR_BAD_ARG, "fill_and_apply: unknown dtype");
+  }
+  if (reinterpret_cast<uintptr_t>(d_logits) % 16 != 0 || (row_stride_elems * f->esize) % 16 != 0)
+    return fail(XGM_ERR_BAD_ARG, "fill_and_apply: logits rows must be 16-byte aligned (use the two separate calls)");
+  return XGM_OK;
+}
+
 int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* d_logits, xgm_dtype dt,
                        int32_t V_logits, int64_t row_stride_elems, void* hip_stream) {
   API_BEGIN
   if (!d_logits) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: null logits");
   if (!ms || B <= 0 || !ms[0] || !ms[0]->v) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: null argument or empty batch");
-  if (V_logits < ms[0]->v->V) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: logits rows are narrower than the vocabulary");
-  if (row_stride_elems < V_logits) return fail(XGM_ERR_BAD_ARG, "fill_and_apply: row stride smaller than the row");
-  FusedLogits f{d_logits, 0, 0u, V_logits, row_stride_elems};
-  switch (dt) {
-    case XGM_F32: f.esize = 4; f.neg_inf = 0xFF800000u; break;
-    case XGM_BF16: f.esize = 2; f.neg_inf = 0xFF80u; break;
-    case XGM_F16: f.esize = 2; f.neg_inf = 0xFC00u; break;
-    default: return fail(XGM_ERR_BAD_ARG, "fill_and_apply: unknown dtype");
-  }
-  if (reinterpret_cast<uintptr_t>(d_logits) % 16 != 0 || (row_stride_elems * f.esize) % 16 != 0)
-    return fail(XGM_ERR_BAD_ARG, "fill_and_apply: logits rows must be 16-byte aligned (use the two separate calls)");
+  FusedLogits f{};
+  const int rc = fused_logits(d_logits, dt, V_logits, row_stride_elems, ms[0]->v->V, &f);
+  if (rc != XGM_OK) return rc;
   return fill_impl(ms, B, d_bitmask, hip_stream, nullptr, nullptr, &f);
   API_END
 }
@@ -1002,11 +1085,35 @@ int xgm_debug_fill_timed(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, 
   API_END
 }
 
+// the state of one row of a batch, read back from the device (the stream must be idle)
+static void read_row_state(const xgm_batch& bt, int32_t row, bool* terminated, std::vector<Stack>* stacks) {
+  int32_t head = 0;
+  HIP_OK(hipMemcpy(&head, bt.dev.head + row, 4, hipMemcpyDeviceToHost));
+  SlotMeta m{};
+  HIP_OK(hipMemcpy(&m, bt.dev.meta + (size_t)row * bt.H + head, sizeof(m), hipMemcpyDeviceToHost));
+  *terminated = (m.flags & 2u) != 0;
+  stacks->clear();
+  if (m.n_stacks == 0) return;
+  const size_t hdr_words = kStackHdrWords + (size_t)bt.dev.n_chunk + 1;
+  const size_t slot = (size_t)row * bt.H + head;
+  std::vector<uint32_t> hdrs((size_t)m.n_stacks * hdr_words);
+  HIP_OK(hipMemcpy(hdrs.data(), bt.dev.hdrs + slot * kBatchMaxStacks * hdr_words, hdrs.size() * 4, hipMemcpyDeviceToHost));
+  std::vector<uint16_t> frames(kBatchRowFrames);
+  HIP_OK(hipMemcpy(frames.data(), bt.dev.frames + slot * kBatchRowFrames, frames.size() * 2, hipMemcpyDeviceToHost));
+  for (uint32_t k = 0; k < m.n_stacks; ++k) {
+    const uint32_t* h = &hdrs[k * hdr_words];
+    const size_t f0 = h[kStackHdrFrames] - slot * kBatchRowFrames;
+    if (h[kStackHdrDepth] == 0 || f0 + h[kStackHdrDepth] > kBatchRowFrames)
+      throw Failure(XGM_ERR_INTERNAL, "batch: a device-resident stack header is out of range");
+    stacks->emplace_back(frames.begin() + f0, frames.begin() + f0 + h[kStackHdrDepth]);
+  }
+}
+
 int xgm_fill_overflow_fixup(void* hip_stream) {
   API_BEGIN
   Context& C = ctx();
   std::lock_guard<std::mutex> lock(C.mu);
-  if (C.last_slot < 0) return 0;
+  if (C.last_slot < 0 && !C.last_batch) return 0;
   HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
   const uint32_t count = read_overflow_count();
   const uint32_t fresh = count - C.seen_count;
@@ -1014,29 +1121,40 @@ int xgm_fill_overflow_fixup(void* hip_stream) {
   if (fresh > OverflowLog::kCap) return fail(XGM_ERR_TOO_LARGE, "fixup: more recorded walks than the log holds");
   std::vector<uint32_t> ent((size_t)OverflowLog::kCap * 3);
   HIP_OK(hipMemcpy(ent.data(), overflow_log()->entry, ent.size() * 4, hipMemcpyDeviceToHost));
-  // the staging blob of the last fill still holds that fill's stacks
-  const FillSlot& slot = C.slot[C.last_slot];
-  const auto* rows = reinterpret_cast<const RowDesc*>(slot.h_buf);
   const xgm_vocab& v = *C.last_vocab;
-  const size_t hdr_words = kStackHdrWords + (size_t)v.dv.n_chunk + 1;
-  const auto* hdrs = reinterpret_cast<const uint32_t*>((const char*)slot.h_buf + (size_t)C.last_B * sizeof(RowDesc));
-  size_t n_stacks = 0;
-  for (int32_t b = 0; b < C.last_B; ++b) n_stacks += rows[b].n_stacks;
-  const auto* frames = reinterpret_cast<const uint16_t*>(hdrs + n_stacks * hdr_words);
+  // the stacks of that fill: in its staging blob, or (device-resident states) read back from the device
+  auto stacks_of = [&](int32_t b, std::vector<Stack>* out) {
+    if (C.last_batch) {
+      bool terminated = false;
+      read_row_state(*C.last_batch, b, &terminated, out);
+      return;
+    }
+    const FillSlot& slot = C.slot[C.last_slot];
+    const auto* rows = reinterpret_cast<const RowDesc*>(slot.h_buf);
+    const size_t hdr_words = kStackHdrWords + (size_t)v.dv.n_chunk + 1;
+    const auto* hdrs = reinterpret_cast<const uint32_t*>((const char*)slot.h_buf + (size_t)C.last_B * sizeof(RowDesc));
+    size_t n_stacks = 0;
+    for (int32_t r = 0; r < C.last_B; ++r) n_stacks += rows[r].n_stacks;
+    const auto* frames = reinterpret_cast<const uint16_t*>(hdrs + n_stacks * hdr_words);
+    out->clear();
+    for (uint32_t s = 0; s < rows[b].n_stacks; ++s) {
+      const uint32_t* h = hdrs + (size_t)(rows[b].stack_begin + s) * hdr_words;
+      out->emplace_back(frames + h[kStackHdrFrames], frames + h[kStackHdrFrames] + h[kStackHdrDepth]);
+    }
+  };
   const int32_t W = v.dv.W;
   int handled = 0;
   for (uint32_t k = 0; k < fresh; ++k) {
     const uint32_t* e = &ent[(size_t)((C.seen_count + k) % OverflowLog::kCap) * 3];
     if (e[0] != C.last_seq) continue;
     const int32_t b = (int32_t)e[1], id = (int32_t)e[2];
-    const xgm_matcher* m = C.last_matchers[b];
-    Engine engine(&m->g->A);
+    Engine engine(C.last_batch ? &C.last_batch->caches[b]->g->A : &C.last_matchers[b]->g->A);
+    std::vector<Stack> stacks;
+    stacks_of(b, &stacks);
     bool ok = false;
-    for (uint32_t s = 0; s < rows[b].n_stacks && !ok; ++s) {
-      const uint32_t* h = hdrs + (size_t)(rows[b].stack_begin + s) * hdr_words;
-      Stack st(frames + h[kStackHdrFrames], frames + h[kStackHdrFrames] + h[kStackHdrDepth]);
+    for (size_t s = 0; s < stacks.size() && !ok; ++s) {
       std::vector<Stack> out;
-      int rc = engine.advance({st}, v.bytes.data() + v.off[id], (int)(v.off[id + 1] - v.off[id]), &out, nullptr, (size_t)-1);
+      int rc = engine.advance({stacks[s]}, v.bytes.data() + v.off[id], (int)(v.off[id + 1] - v.off[id]), &out, nullptr, (size_t)-1);
       if (rc == XGM_OK) ok = true;
       else if (rc != XGM_ERR_TOKEN_REJECTED) return fail(rc, "fixup: a token walk exceeds the host limits too");
     }
@@ -1051,6 +1169,247 @@ int xgm_fill_overflow_fixup(void* hip_stream) {
   }
   C.seen_count = count;
   return handled;
+  API_END
+}
+
+// ------------------------------------------------- device-resident states
+namespace {
+// what the matcher's current state looks like in slot `slot` of row `row`
+struct PackedState {
+  SlotMeta meta{};
+  std::vector<uint32_t> hdrs;
+  std::vector<uint16_t> frames;
+  RowDesc row{};
+};
+PackedState pack_state(const xgm_batch& bt, int32_t row, int32_t slot, const xgm_matcher& m) {
+  const xgm_cache& c = *bt.caches[row];
+  const Automaton& A = c.g->A;
+  const size_t hdr_words = kStackHdrWords + (size_t)bt.dev.n_chunk + 1;
+  const size_t at = (size_t)row * bt.H + slot;
+  PackedState p;
+  p.row.tab = c.host.tab;
+  p.row.acc = c.host.acc;
+  p.row.unc_list = c.host.unc_list;
+  p.row.unc_ctx = c.host.unc_ctx;
+  p.row.stack_begin = (uint32_t)(at * kBatchMaxStacks);
+  p.row.frame_begin = (uint32_t)(at * kBatchRowFrames);
+  if (m.terminated) {
+    p.meta.flags = 3u;
+  } else {
+    if (m.stacks.size() > kBatchMaxStacks) throw Failure(XGM_ERR_TOO_MANY_STACKS, "batch: more than 16 parallel stacks in a row");
+    p.hdrs.assign(m.stacks.size() * hdr_words, 0u);
+    uint32_t fi = 0;
+    for (size_t k = 0; k < m.stacks.size(); ++k) {
+      const Stack& s = m.stacks[k];
+      if (s.size() > kBatchMaxDepth) throw Failure(XGM_ERR_TOO_LARGE, "batch: a stack deeper than 128 frames");
+      pack_stack_header(A, c, s, p.row.frame_begin + fi, &p.hdrs[k * hdr_words]);
+      for (int32_t n : s) p.frames.push_back((uint16_t)n);
+      fi += (uint32_t)s.size();
+    }
+    p.meta.n_stacks = (uint32_t)m.stacks.size();
+    p.meta.n_frames = fi;
+    p.meta.flags = Engine(&A).can_terminate(m.stacks) ? 1u : 0u;
+  }
+  p.row.n_stacks = p.meta.n_stacks;
+  p.row.n_frames = p.meta.n_frames;
+  p.row.flags = p.meta.flags & 1u;
+  return p;
+}
+void write_state(const xgm_batch& bt, int32_t row, int32_t slot, const PackedState& p) {
+  const size_t hdr_words = kStackHdrWords + (size_t)bt.dev.n_chunk + 1;
+  const size_t at = (size_t)row * bt.H + slot;
+  HIP_OK(hipMemcpy(bt.dev.meta + at, &p.meta, sizeof(SlotMeta), hipMemcpyHostToDevice));
+  if (!p.hdrs.empty()) HIP_OK(hipMemcpy(bt.dev.hdrs + at * kBatchMaxStacks * hdr_words, p.hdrs.data(), p.hdrs.size() * 4, hipMemcpyHostToDevice));
+  if (!p.frames.empty()) HIP_OK(hipMemcpy(bt.dev.frames + at * kBatchRowFrames, p.frames.data(), p.frames.size() * 2, hipMemcpyHostToDevice));
+  HIP_OK(hipMemcpy(bt.dev.rows + row, &p.row, sizeof(RowDesc), hipMemcpyHostToDevice));
+}
+}  // namespace
+
+int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* hip_stream, xgm_batch** out) {
+  API_BEGIN
+  if (!ms || !out || B <= 0) return fail(XGM_ERR_BAD_ARG, "batch_create: null argument or empty batch");
+  if (history < 0 || history > XGM_BATCH_MAX_HISTORY) return fail(XGM_ERR_BAD_ARG, "batch_create: history out of range");
+  if (B > (int32_t)kBatchMaxRows) return fail(XGM_ERR_TOO_LARGE, "batch_create: more than 1024 rows");
+  xgm_vocab* v = nullptr;
+  for (int32_t b = 0; b < B; ++b) {
+    if (!ms[b] || !ms[b]->c) return fail(XGM_ERR_BAD_ARG, "batch_create: matcher is null or has no cache");
+    if (v && ms[b]->v != v) return fail(XGM_ERR_BAD_ARG, "batch_create: all matchers must share one vocabulary");
+    v = ms[b]->v;
+  }
+  const int32_t n_chunk = v->dv.n_chunk;
+  if ((size_t)B * (n_chunk + 1) * 4 > (size_t)128 * 1024)
+    return fail(XGM_ERR_TOO_LARGE, "batch_create: rows x vocabulary chunks beyond what the device planner holds");
+  require_device();
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  auto* bt = new xgm_batch();
+  try {
+    bt->B = B;
+    bt->H = history + 1;
+    bt->v = v;
+    ++v->refs;
+    for (int32_t b = 0; b < B; ++b) { bt->caches.push_back(ms[b]->c); ++ms[b]->c->refs; }
+    auto keep = [&](auto* p) { bt->dev_ptrs.push_back((void*)p); return p; };
+    const size_t hdr_words = kStackHdrWords + (size_t)n_chunk + 1;
+    const size_t slots = (size_t)B * bt->H;
+    DevBatch& d = bt->dev;
+    d.B = B;
+    d.H = bt->H;
+    d.n_chunk = n_chunk;
+    {
+      Context& C = ctx();
+      std::lock_guard<std::mutex> lock(C.mu);
+      if (C.resident_blocks == 0) {
+        int dev = 0, cus = 0;
+        HIP_OK(hipGetDevice(&dev));
+        HIP_OK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        C.resident_blocks = 2 * std::max(1, cus);
+      }
+      d.budget = C.resident_blocks;
+    }
+    std::vector<DevCache> caches(B);
+    for (int32_t b = 0; b < B; ++b) caches[b] = ms[b]->c->host;
+    d.cache = keep(dev_upload(caches));
+    d.rows = keep(dev_alloc<RowDesc>(B));
+    d.meta = keep(dev_alloc<SlotMeta>(slots));
+    d.hdrs = keep(dev_alloc<uint32_t>(slots * kBatchMaxStacks * hdr_words));
+    d.frames = keep(dev_alloc<uint16_t>(slots * kBatchRowFrames));
+    d.head = keep(dev_alloc<int32_t>(B));
+    d.older = keep(dev_alloc<int32_t>(B));
+    d.status = keep(dev_alloc<int32_t>(B));
+    d.plan_cap = batch_plan_cap(B, n_chunk, d.budget);
+    d.plan = keep(dev_alloc<FillBlock>(d.plan_cap));
+    HIP_OK(hipMemset(d.meta, 0, slots * sizeof(SlotMeta)));
+    HIP_OK(hipMemset(d.head, 0, (size_t)B * 4));
+    HIP_OK(hipMemset(d.older, 0, (size_t)B * 4));
+    HIP_OK(hipMemset(d.status, 0, (size_t)B * 4));
+    for (int32_t b = 0; b < B; ++b) write_state(*bt, b, 0, pack_state(*bt, b, 0, *ms[b]));
+    launch_batch_plan(d, stream);
+    HIP_OK(hipGetLastError());
+    HIP_OK(hipStreamSynchronize(stream));
+  } catch (...) {
+    xgm_batch_destroy(bt);
+    throw;
+  }
+  *out = bt;
+  return XGM_OK;
+  API_END
+}
+
+void xgm_batch_destroy(xgm_batch* bt) {
+  if (!bt) return;
+  {
+    Context& C = ctx();
+    std::lock_guard<std::mutex> lock(C.mu);
+    if (C.last_batch == bt) C.last_batch = nullptr;
+  }
+  for (void* p : bt->dev_ptrs) (void)hipFree(p);
+  for (xgm_cache* c : bt->caches) release(c);
+  release(bt->v);
+  delete bt;
+}
+
+int32_t xgm_batch_size(const xgm_batch* bt) { return bt ? bt->B : XGM_ERR_BAD_ARG; }
+
+int xgm_batch_accept_tokens(xgm_batch* bt, const int32_t* d_token_ids, void* hip_stream) {
+  API_BEGIN
+  if (!bt || !d_token_ids) return fail(XGM_ERR_BAD_ARG, "batch_accept_tokens: null argument");
+  launch_batch_accept(bt->dev, bt->v->dv, d_token_ids, static_cast<hipStream_t>(hip_stream));
+  HIP_OK(hipGetLastError());
+  return XGM_OK;
+  API_END
+}
+
+int xgm_batch_rollback(xgm_batch* bt, const int32_t* d_steps, void* hip_stream) {
+  API_BEGIN
+  if (!bt || !d_steps) return fail(XGM_ERR_BAD_ARG, "batch_rollback: null argument");
+  launch_batch_rollback(bt->dev, d_steps, static_cast<hipStream_t>(hip_stream));
+  HIP_OK(hipGetLastError());
+  return XGM_OK;
+  API_END
+}
+
+int xgm_batch_status(xgm_batch* bt, int32_t* h_status, void* hip_stream) {
+  API_BEGIN
+  if (!bt || !h_status) return fail(XGM_ERR_BAD_ARG, "batch_status: null argument");
+  HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+  HIP_OK(hipMemcpy(h_status, bt->dev.status, (size_t)bt->B * 4, hipMemcpyDeviceToHost));
+  int bad = 0;
+  for (int32_t b = 0; b < bt->B; ++b) bad += h_status[b] != XGM_OK;
+  return bad;
+  API_END
+}
+
+int xgm_batch_get_row(xgm_batch* bt, int32_t row, xgm_matcher* m, void* hip_stream) {
+  API_BEGIN
+  if (!bt || !m || row < 0 || row >= bt->B) return fail(XGM_ERR_BAD_ARG, "batch_get_row: bad argument");
+  if (m->c != bt->caches[row]) return fail(XGM_ERR_BAD_ARG, "batch_get_row: the matcher belongs to another mask cache");
+  HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+  bool terminated = false;
+  std::vector<Stack> stacks;
+  read_row_state(*bt, row, &terminated, &stacks);
+  m->terminated = terminated;
+  if (!terminated) m->stacks.swap(stacks);
+  return XGM_OK;
+  API_END
+}
+
+int xgm_batch_set_row(xgm_batch* bt, int32_t row, const xgm_matcher* m, void* hip_stream) {
+  API_BEGIN
+  if (!bt || !m || row < 0 || row >= bt->B) return fail(XGM_ERR_BAD_ARG, "batch_set_row: bad argument");
+  if (m->c != bt->caches[row]) return fail(XGM_ERR_BAD_ARG, "batch_set_row: the matcher belongs to another mask cache");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  HIP_OK(hipStreamSynchronize(stream));
+  int32_t head = 0, older = 0;
+  HIP_OK(hipMemcpy(&head, bt->dev.head + row, 4, hipMemcpyDeviceToHost));
+  HIP_OK(hipMemcpy(&older, bt->dev.older + row, 4, hipMemcpyDeviceToHost));
+  const int32_t next = (head + 1) % bt->H;
+  write_state(*bt, row, next, pack_state(*bt, row, next, *m));
+  older = std::min(older + 1, bt->H - 1);
+  const int32_t ok = XGM_OK;
+  HIP_OK(hipMemcpy(bt->dev.head + row, &next, 4, hipMemcpyHostToDevice));
+  HIP_OK(hipMemcpy(bt->dev.older + row, &older, 4, hipMemcpyHostToDevice));
+  HIP_OK(hipMemcpy(bt->dev.status + row, &ok, 4, hipMemcpyHostToDevice));
+  launch_batch_plan(bt->dev, stream);
+  HIP_OK(hipGetLastError());
+  return XGM_OK;
+  API_END
+}
+
+static int batch_fill_impl(xgm_batch* bt, int32_t* d_bitmask, void* hip_stream, const FusedLogits* fused) {
+  if (!bt || !d_bitmask) return fail(XGM_ERR_BAD_ARG, "batch_fill: null argument");
+  Context& C = ctx();
+  std::lock_guard<std::mutex> lock(C.mu);
+  OverflowLog* log = overflow_log();
+  const uint32_t seq = ++C.seq;
+  const DevBatch& d = bt->dev;
+  launch_fill(d.rows, d.hdrs, d.frames, d.plan, (int32_t)d.plan_cap, bt->v->dv, reinterpret_cast<uint32_t*>(d_bitmask), log, seq,
+              nullptr, static_cast<hipStream_t>(hip_stream), fused ? fused->d_logits : nullptr, fused ? fused->esize : 0,
+              fused ? fused->neg_inf : 0u, fused ? fused->V_logits : 0, fused ? fused->row_stride : 0, C.pair_min_entries);
+  HIP_OK(hipGetLastError());
+  C.last_slot = -1;
+  C.last_batch = bt;
+  C.last_seq = seq;
+  C.last_B = bt->B;
+  C.last_bitmask = d_bitmask;
+  C.last_vocab = bt->v;
+  C.last_matchers.clear();
+  return XGM_OK;
+}
+
+int xgm_batch_fill_next_token_bitmask(xgm_batch* bt, int32_t* d_bitmask, void* hip_stream) {
+  API_BEGIN
+  return batch_fill_impl(bt, d_bitmask, hip_stream, nullptr);
+  API_END
+}
+
+int xgm_batch_fill_and_apply(xgm_batch* bt, int32_t* d_bitmask, void* d_logits, xgm_dtype dt, int32_t V_logits,
+                             int64_t row_stride_elems, void* hip_stream) {
+  API_BEGIN
+  if (!bt || !d_logits) return fail(XGM_ERR_BAD_ARG, "batch_fill_and_apply: null argument");
+  FusedLogits f{};
+  const int rc = fused_logits(d_logits, dt, V_logits, row_stride_elems, bt->v->V, &f);
+  if (rc != XGM_OK) return rc;
+  return batch_fill_impl(bt, d_bitmask, hip_stream, &f);
   API_END
 }
 

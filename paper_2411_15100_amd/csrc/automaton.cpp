@@ -717,7 +717,7 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
   //    - If the return node is a dead end (accepting, no outgoing edges) no
   //      frame is needed: returning there could only be followed by another
   //      return, so the callee returns straight to the caller's parent.
-  //    - If the callee does nothing with c but consume it and end (a single
+  //    - Otherwise, if the callee does nothing with c but consume it and end (a single
   //      byte edge from its start into a dead end, no reference of its own
   //      that could start with c), the whole call is the move "consume c, go
   //      to the return node"; the frame would be pushed and popped unseen.
@@ -734,8 +734,8 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
       bool callee_refs = false;
       for (auto& e2 : A.redges[s]) callee_refs = callee_refs || A.first[e2.rule].test(c);
       uint32_t alt;
-      if (m >= 0 && A.node_dead_end[m] && !callee_refs) alt = (kMoveTag << 16) | (uint32_t)e.to;
-      else if (A.node_dead_end[e.to]) alt = (kTailTag << 16) | (uint32_t)s;
+      if (A.node_dead_end[e.to]) alt = (kTailTag << 16) | (uint32_t)s;
+      else if (m >= 0 && A.node_dead_end[m] && !callee_refs) alt = (kMoveTag << 16) | (uint32_t)e.to;
       else alt = ((uint32_t)e.to << 16) | (uint32_t)s;
       if (std::find(list.begin(), list.end(), alt) == list.end()) list.push_back(alt);
     }
@@ -751,7 +751,7 @@ Automaton compile_grammar(const std::string& text, const std::string& root) {
   std::map<std::vector<uint8_t>, uint32_t> shape_ids;
   for (int n = 0; n < total; ++n) {
     NodeHdr& h = A.hdr[n];
-    h.flags = A.node_final[n] ? kFlagFinal : 0;
+    h.flags = (A.node_final[n] ? kFlagFinal : 0) | (A.node_dead_end[n] ? kFlagDeadEnd : 0);
     if (A.redges[n].empty() && A.bedges[n].size() <= 1) {
       if (A.bedges[n].size() == 1) { h.lo = A.bedges[n][0].lo; h.hi = A.bedges[n][0].hi; h.target = (uint16_t)A.bedges[n][0].to; }
       continue;

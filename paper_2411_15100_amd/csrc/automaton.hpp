@@ -28,12 +28,13 @@ struct RefEdge { int32_t rule; int32_t to; };
 struct NodeHdr {
   uint8_t lo, hi;
   uint16_t target;
-  uint32_t flags;  // kFlagFinal | kFlagBranching | rule index << 16
+  uint32_t flags;  // kFlagFinal | kFlagBranching | kFlagDeadEnd | rule index << 16
 };
 static_assert(sizeof(NodeHdr) == 8, "NodeHdr must be 8 bytes");
 
 constexpr uint32_t kFlagFinal = 1;      // the rule may end at this node
 constexpr uint32_t kFlagBranching = 2;
+constexpr uint32_t kFlagDeadEnd = 4;    // accepting and without outgoing edges: all it can do is return
 constexpr uint8_t kDeadShape = 0xFF;    // shape entry: nothing to do for this byte class
 constexpr uint16_t kAltFlag = 0x8000;   // outcome: index into the alternatives pool (else: move to that node)
 constexpr uint32_t kMoveTag = 0xFFFF;   // alternative (tag << 16 | node): consume the byte, go to node

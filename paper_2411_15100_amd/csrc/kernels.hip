@@ -5,6 +5,7 @@
 #include <algorithm>
 
 #include "kernels.hpp"
+#include "plan.hpp"
 #include "walk.hpp"
 
 namespace xgm {
@@ -80,6 +81,7 @@ struct LdsTab {
   }
   __device__ __forceinline__ uint32_t alt(uint32_t idx) const { return rd32(off_alts + idx * 4u, alts_lds); }
   __device__ __forceinline__ bool is_final(uint32_t n) const { return header(n).y & 1u; }
+  __device__ __forceinline__ bool is_dead_end(uint32_t n) const { return header(n).y & 4u; }
   // can byte c be consumed at node n inside its frame (byte edge, or first byte of a rule it refers to)?
   __device__ __forceinline__ bool can_start(uint32_t n, uint32_t c) const {
     return (*(const XGM_GLOBAL uint32_t*)(img + off_first + ((size_t)n * 8u + (c >> 5)) * 4u) >> (c & 31)) & 1u;
@@ -680,6 +682,7 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   unsigned long long my_steps = 0;
   const uint32_t tid = threadIdx.x;
   const FillBlock blk = plan[blockIdx.x];
+  if (blk.row == kNoRow) return;  // padding of a plan made on the device
   const int32_t b = (int32_t)blk.row;
   const int32_t c0 = (int32_t)(blk.c0c1 & 0xFFFFu), c1 = (int32_t)(blk.c0c1 >> 16);  // this workgroup's chunks
   const int32_t w_begin = c0 * kChunkWords;
@@ -738,6 +741,269 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
     }
   }
   if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
+}
+
+
+// ------------------------------------------------- device-resident states
+// Candidate stacks of one row in LDS (see CollectStacks).
+struct LdsStackSink {
+  uint16_t* frames;
+  uint32_t* depth;
+  uint32_t* count;
+  uint32_t* overflow;
+  uint32_t capacity, max_depth;
+  __device__ __forceinline__ uint32_t claim() { return atomicAdd(count, 1u); }
+};
+
+constexpr int kAcceptThreads = 256;
+constexpr int kErrTokenRejected = -6, kErrTerminated = -7, kErrTooManyStacks = -8, kErrTooLarge = -9, kErrBadArg = -1;
+
+// is stack a (depth da) ordered before stack b?  element by element, the shorter first (the host's order of stacks)
+__device__ __forceinline__ int compare_stacks(const uint16_t* a, uint32_t da, const uint16_t* b, uint32_t db) {
+  const uint32_t m = da < db ? da : db;
+  for (uint32_t k = 0; k < m; ++k)
+    if (a[k] != b[k]) return a[k] < b[k] ? -1 : 1;
+  return da == db ? 0 : (da < db ? -1 : 1);
+}
+
+// Section 3.3 on the device: one workgroup per row moves the row's stacks on
+// by the row's token.  Lane s of the first wave walks the token from stack s
+// and writes out every stack it can end in; duplicates are removed, the rest
+// is put in the host's order and packed as the next state of the row's ring,
+// in the layout the fill kernel reads (stack headers with their first-byte
+// sets, context index and list offsets; frames).  A row whose token is not
+// allowed, or whose new state does not fit the device limits, keeps its state
+// and gets an error code in `status`.
+__global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch bt, DevVocab voc,
+                                                                      const int32_t* __restrict__ tokens) {
+  __shared__ uint16_t cand[kBatchMaxCandidates * kBatchMaxDepth];
+  __shared__ uint32_t cdepth[kBatchMaxCandidates];
+  __shared__ uint32_t order[kBatchMaxCandidates];  // rank among the distinct stacks, or kNoRow for a duplicate
+  __shared__ uint32_t foff[kBatchMaxStacks + 1];
+  __shared__ uint32_t slot_of[kBatchMaxStacks];    // candidate index per rank
+  __shared__ uint32_t ccount, coverflow, n_new, can_end;
+  const uint32_t tid = threadIdx.x;
+  const int32_t b = blockIdx.x;
+  const int32_t tok = tokens[b];
+  if (tok < 0) return;  // this row is left alone (its status too)
+  const int32_t head = bt.head[b];
+  const SlotMeta cur = bt.meta[(size_t)b * bt.H + head];
+  const DevCache dc = bt.cache[b];
+  const uint32_t hdr_stride = kStackHdrWords + (uint32_t)bt.n_chunk + 1u;
+  const int32_t next = (head + 1) % bt.H;
+  const uint32_t sb = ((uint32_t)b * bt.H + next) * kBatchMaxStacks;
+  const uint32_t fb = ((uint32_t)b * bt.H + next) * kBatchRowFrames;
+  int32_t status = 0;
+  bool stop = false;
+  if (tok >= voc.V) status = kErrBadArg;
+  else if (cur.flags & 2u) status = kErrTerminated;
+  else {
+    for (int32_t k = 0; k < voc.n_stop; ++k) stop = stop || voc.stop_ids[k] == tok;
+    if (stop && !(cur.flags & 1u)) status = kErrTokenRejected;
+  }
+  if (status != 0) {
+    if (tid == 0) bt.status[b] = status;
+    return;
+  }
+  if (tid == 0) { ccount = 0u; coverflow = 0u; n_new = 0u; can_end = 0u; }
+  __syncthreads();
+  DevTables tab = dc.tab;
+  tab.lds_end = tab.stage_bytes = tab.n_near = 0u;  // the walks read the tables where they are
+  const LdsTab T(tab, nullptr);
+  if (!stop) {
+    const uint4 tk = voc.tok_by_id[tok];
+    int len = (int)(tk.w >> 24);
+    const uint8_t* ext = voc.bytes;
+    if (len >= 15) {
+      ext = voc.bytes + voc.off_by_id[tok];
+      if (len == 255) len = (int)(voc.off_by_id[tok + 1] - voc.off_by_id[tok]);
+    }
+    if (len == 0) {
+      if (tid == 0) bt.status[b] = kErrTokenRejected;
+      return;
+    }
+    if (tid < cur.n_stacks) {
+      const uint32_t* h = bt.hdrs + (size_t)(((uint32_t)b * bt.H + head) * kBatchMaxStacks + tid) * hdr_stride;
+      const uint16_t* fr = bt.frames + h[kStackHdrFrames];
+      LdsStackSink sink{cand, cdepth, &ccount, &coverflow, kBatchMaxCandidates, kBatchMaxDepth};
+      const CollectStacks<LdsTab, LdsStackSink> collect{&T, &sink};
+      const int res = walk_token<false>(T, tk, ext, len, h[kStackHdrTop], fr, h[kStackHdrDepth], (uint32_t*)nullptr,
+                                        (const uint32_t*)nullptr, 0, (uint32_t*)nullptr, collect);
+      if (res == kOverflow) coverflow = 1u;
+    }
+    __syncthreads();
+    if (coverflow || ccount > kBatchMaxCandidates) status = kErrTooLarge;
+    else if (ccount == 0u) status = kErrTokenRejected;
+    if (status != 0) {
+      if (tid == 0) bt.status[b] = status;
+      return;
+    }
+    const uint32_t nc = ccount;
+    // duplicates out, the rest in order
+    if (tid < nc) {
+      bool dup = false;
+      for (uint32_t j = 0; j < tid; ++j)
+        dup = dup || compare_stacks(cand + j * kBatchMaxDepth, cdepth[j], cand + tid * kBatchMaxDepth, cdepth[tid]) == 0;
+      order[tid] = dup ? kNoRow : 0u;
+      if (!dup) atomicAdd(&n_new, 1u);
+    }
+    __syncthreads();
+    uint32_t before = 0u;
+    if (tid < nc && order[tid] != kNoRow)
+      for (uint32_t j = 0; j < nc; ++j)
+        if (j != tid && order[j] != kNoRow &&
+            compare_stacks(cand + j * kBatchMaxDepth, cdepth[j], cand + tid * kBatchMaxDepth, cdepth[tid]) < 0)
+          ++before;
+    __syncthreads();
+    if (tid < nc && order[tid] != kNoRow) order[tid] = before;
+    __syncthreads();
+    if (n_new > kBatchMaxStacks) {
+      if (tid == 0) bt.status[b] = kErrTooManyStacks;
+      return;
+    }
+    if (tid < nc && order[tid] != kNoRow) slot_of[order[tid]] = tid;
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t run = 0;
+      for (uint32_t r = 0; r < n_new; ++r) { foff[r] = run; run += cdepth[slot_of[r]]; }
+      foff[n_new] = run;
+    }
+    __syncthreads();
+    const uint32_t ns = n_new;
+    // frames
+    for (uint32_t r = 0; r < ns; ++r) {
+      const uint32_t ci = slot_of[r], d = cdepth[ci];
+      for (uint32_t k = tid; k < d; k += kAcceptThreads) bt.frames[fb + foff[r] + k] = cand[ci * kBatchMaxDepth + k];
+    }
+    // headers: scalars, context index, whether the stack can end the text
+    if (tid < ns) {
+      const uint32_t ci = slot_of[tid], d = cdepth[ci];
+      const uint16_t* st = cand + ci * kBatchMaxDepth;
+      uint32_t* h = bt.hdrs + (size_t)(sb + tid) * hdr_stride;
+      const uint32_t top = st[d - 1];
+      h[kStackHdrTop] = top;
+      h[kStackHdrDepth] = d;
+      h[kStackHdrFrames] = fb + foff[tid];
+      uint32_t ctx = kCtxNone;
+      if (d >= 2u) {
+        const uint32_t rule = T.header(top).y >> 16, below = st[d - 2];
+        for (uint32_t i = dc.ctx_off[rule]; i < dc.ctx_off[rule + 1]; ++i)
+          if (dc.ctx_node[i] == below) ctx = i - dc.ctx_off[rule];
+      }
+      h[kStackHdrCtx] = ctx;
+      bool all_final = true;
+      for (uint32_t k = 0; k < d; ++k) all_final = all_final && T.is_final(st[k]);
+      if (all_final) can_end = 1u;
+    }
+    // headers: the two first-byte sets, one thread per (stack, set, word)
+    for (uint32_t item = tid; item < ns * 16u; item += kAcceptThreads) {
+      const uint32_t r = item >> 4, below = (item >> 3) & 1u, w = item & 7u;
+      const uint32_t ci = slot_of[r], d = cdepth[ci];
+      const uint16_t* st = cand + ci * kBatchMaxDepth;
+      uint32_t acc = 0u;
+      for (uint32_t k = d - below; k-- > 0u;) {
+        acc |= *(const XGM_GLOBAL uint32_t*)(T.img + T.off_first + ((size_t)st[k] * 8u + w) * 4u);
+        if (!T.is_final(st[k])) break;
+      }
+      bt.hdrs[(size_t)(sb + r) * hdr_stride + (below ? kStackHdrBelow : kStackHdrFirst) + w] = acc;
+    }
+    // headers: list offsets of the top node
+    for (uint32_t item = tid; item < ns * ((uint32_t)bt.n_chunk + 1u); item += kAcceptThreads) {
+      const uint32_t r = item / ((uint32_t)bt.n_chunk + 1u), c = item % ((uint32_t)bt.n_chunk + 1u);
+      const uint32_t ci = slot_of[r], top = cand[ci * kBatchMaxDepth + cdepth[ci] - 1u];
+      bt.hdrs[(size_t)(sb + r) * hdr_stride + kStackHdrWords + c] = dc.unc_off[(size_t)top * ((uint32_t)bt.n_chunk + 1u) + c];
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    SlotMeta m;
+    m.n_stacks = stop ? 0u : n_new;
+    m.n_frames = stop ? 0u : foff[n_new];
+    m.flags = stop ? 3u : can_end;
+    m.pad = 0u;
+    bt.meta[(size_t)b * bt.H + next] = m;
+    RowDesc r;
+    r.tab = dc.tab;
+    r.acc = dc.acc;
+    r.unc_list = dc.unc_list;
+    r.unc_ctx = dc.unc_ctx;
+    r.stack_begin = sb;
+    r.n_stacks = m.n_stacks;
+    r.flags = m.flags & 1u;
+    r.frame_begin = fb;
+    r.n_frames = m.n_frames;
+    r.pad = 0u;
+    bt.rows[b] = r;
+    bt.head[b] = next;
+    const int32_t o = bt.older[b] + 1;
+    bt.older[b] = o < bt.H - 1 ? o : bt.H - 1;
+    bt.status[b] = 0;
+  }
+}
+
+// going back: one thread per row
+__global__ void batch_rollback_kernel(DevBatch bt, const int32_t* __restrict__ steps) {
+  const int32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= bt.B) return;
+  const int32_t k = steps[b];
+  if (k <= 0) return;
+  if (k > bt.older[b]) { bt.status[b] = kErrBadArg; return; }
+  const int32_t head = ((bt.head[b] - k) % bt.H + bt.H) % bt.H;
+  const SlotMeta m = bt.meta[(size_t)b * bt.H + head];
+  RowDesc r = bt.rows[b];
+  r.stack_begin = ((uint32_t)b * bt.H + head) * kBatchMaxStacks;
+  r.frame_begin = ((uint32_t)b * bt.H + head) * kBatchRowFrames;
+  r.n_stacks = m.n_stacks;
+  r.n_frames = m.n_frames;
+  r.flags = m.flags & 1u;
+  bt.rows[b] = r;
+  bt.head[b] = head;
+  bt.older[b] -= k;
+  bt.status[b] = 0;
+}
+
+// The plan of the next fill for the batch's current states (plan.hpp), by one
+// workgroup: the per-(row, chunk) running entry counts go to LDS, then one
+// thread per row cuts its row.
+constexpr int kPlanThreads = 1024;
+__global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint32_t* upto = reinterpret_cast<uint32_t*>(smem);  // [B][n_chunk + 1]
+  __shared__ unsigned long long total;
+  __shared__ uint32_t count[kBatchMaxRows];
+  const uint32_t tid = threadIdx.x, stride = (uint32_t)bt.n_chunk + 1u;
+  const uint32_t hdr_stride = kStackHdrWords + stride;
+  if (tid == 0) total = 0ull;
+  for (uint32_t item = tid; item < (uint32_t)bt.B * stride; item += kPlanThreads) {
+    const uint32_t b = item / stride, c = item % stride;
+    const uint32_t s0 = bt.rows[b].stack_begin, ns = bt.rows[b].n_stacks;
+    uint32_t run = 0u;
+    for (uint32_t s = 0; s < ns; ++s) {
+      const uint32_t* off = bt.hdrs + (size_t)(s0 + s) * hdr_stride + kStackHdrWords;
+      run += off[c] - off[0];
+    }
+    upto[item] = run;
+  }
+  __syncthreads();
+  if (tid < (uint32_t)bt.B) atomicAdd(&total, (unsigned long long)upto[tid * stride + bt.n_chunk]);
+  __syncthreads();
+  int32_t k = 0;
+  const uint32_t* mine = upto + tid * stride;
+  if (tid < (uint32_t)bt.B) {
+    k = plan_row_share(bt.B, bt.n_chunk, bt.budget, mine[bt.n_chunk], total);
+    count[tid] = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; }, (FillBlock*)nullptr);
+  }
+  __syncthreads();
+  if (tid == 0) {  // exclusive scan
+    uint32_t run = 0u;
+    for (int32_t b = 0; b < bt.B; ++b) { const uint32_t c = count[b]; count[b] = run; run += c; }
+    total = run;
+  }
+  __syncthreads();
+  const uint32_t n_blocks = (uint32_t)total;
+  if (tid < (uint32_t)bt.B && count[tid] + (uint32_t)(k + plan_min_blocks(bt.n_chunk)) <= bt.plan_cap)
+    plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; }, bt.plan + count[tid]);
+  for (uint32_t j = n_blocks + tid; j < bt.plan_cap; j += kPlanThreads) bt.plan[j] = FillBlock{kNoRow, 0u};
 }
 
 // ---------------------------------------------------------------- kernel (c)
@@ -876,6 +1142,20 @@ void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t
   else
     hipLaunchKernelGGL((fill_kernel<false, 0>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
                        plan, voc, out, log, seq, step_counter, fa);
+}
+
+void launch_batch_plan(const DevBatch& bt, hipStream_t stream) {
+  hipLaunchKernelGGL(batch_plan_kernel, dim3(1), dim3(kPlanThreads), (size_t)bt.B * (bt.n_chunk + 1) * 4, stream, bt);
+}
+
+void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, hipStream_t stream) {
+  hipLaunchKernelGGL(batch_accept_kernel, dim3(bt.B), dim3(kAcceptThreads), 0, stream, bt, voc, d_tokens);
+  launch_batch_plan(bt, stream);
+}
+
+void launch_batch_rollback(const DevBatch& bt, const int32_t* d_steps, hipStream_t stream) {
+  hipLaunchKernelGGL(batch_rollback_kernel, dim3((bt.B + 255) / 256), dim3(256), 0, stream, bt, d_steps);
+  launch_batch_plan(bt, stream);
 }
 
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,

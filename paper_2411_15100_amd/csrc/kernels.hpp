@@ -103,6 +103,8 @@ struct DevCache {
   const uint32_t* unc_off;   // [n_nodes][n_chunk+1] offsets into unc_list
   const uint32_t* unc_list;  // context-dependent tokens, grouped by (node, chunk); see kEntry*
   const uint32_t* unc_ctx;   // parallel to unc_list: the entry's class in each context of its node's rule; see kCtx*
+  const uint32_t* ctx_off;   // [n_rules+1] ranges of ctx_node: the contexts of every rule that has at most kCtxMax
+  const uint16_t* ctx_node;  // context nodes, sorted within a rule
   int32_t n_nodes;
 };
 
@@ -168,6 +170,44 @@ constexpr int32_t kFillMaxChunks = 24;  // chunks one workgroup may own (its mas
 // entries: building it costs about as much as one queue round of walks.
 constexpr uint32_t kFillPairMinEntries = 2048;
 
+constexpr uint32_t kNoRow = 0xFFFFFFFFu;  // FillBlock::row of a workgroup that has nothing to do
+
+// ---- matcher states that live on the device (section 3.3 on the GPU: the
+// sampled tokens move the stacks on without a round trip to the host).
+// A batch holds, for each of its B rows, a ring of H states.  A state is what
+// the fill kernel reads: up to kBatchMaxStacks stack headers and their frames,
+// stack after stack.  The row's current state is named by its RowDesc;
+// accepting a token writes the next slot of the ring and points the RowDesc
+// there, so that going back k tokens is a matter of pointing it k slots back.
+constexpr uint32_t kBatchMaxStacks = 16;      // parallel stacks per row
+constexpr uint32_t kBatchMaxDepth = 128;      // frames per stack
+constexpr uint32_t kBatchMaxCandidates = 32;  // stacks a token may end in before duplicates are removed
+constexpr uint32_t kBatchRowFrames = kBatchMaxStacks * kBatchMaxDepth;
+constexpr uint32_t kBatchMaxRows = 1024;
+struct SlotMeta {
+  uint32_t n_stacks, n_frames;
+  uint32_t flags;  // bit 0: the text so far is a complete sentence; bit 1: the stop token has been accepted
+  uint32_t pad;
+};
+struct DevBatch {
+  int32_t B, H, n_chunk, budget;
+  const DevCache* cache;  // [B] each row's mask cache (tables staged as for the fill kernel)
+  RowDesc* rows;          // [B] current states
+  SlotMeta* meta;         // [B][H]
+  uint32_t* hdrs;         // [B][H][kBatchMaxStacks] stack headers
+  uint16_t* frames;       // [B][H][kBatchRowFrames]
+  int32_t* head;          // [B] slot of the current state
+  int32_t* older;         // [B] how many older states are still in the ring
+  int32_t* status;        // [B] result of the last accept / rollback per row (XGM_OK or an error code)
+  FillBlock* plan;        // [plan_cap] workgroups of the next fill, padded with kNoRow
+  uint32_t plan_cap;
+};
+// workgroups a plan can have at most (see plan.hpp)
+inline uint32_t batch_plan_cap(int32_t B, int32_t n_chunk, int32_t budget) {
+  const int32_t min_blocks = (n_chunk + kFillMaxChunks - 1) / kFillMaxChunks;
+  return (uint32_t)((budget > B * min_blocks ? budget : B * min_blocks) + B * min_blocks);
+}
+
 // pairs whose walk exceeded the limits
 struct OverflowLog {
   static constexpr uint32_t kCap = 1 << 16;
@@ -212,6 +252,12 @@ void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t
                  uint32_t seq, unsigned long long* step_counter, hipStream_t stream, void* logits = nullptr,
                  int elem_size = 0, uint32_t neg_inf = 0, int32_t V_logits = 0, int64_t row_stride = 0,
                  uint32_t pair_min_entries = kFillPairMinEntries);
+// device-resident states: move every row on by its token (ids < 0 leave a row alone), then plan the next fill
+void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, hipStream_t stream);
+// go back d_steps[b] tokens in every row (<= 0 leaves a row alone), then plan
+void launch_batch_rollback(const DevBatch& bt, const int32_t* d_steps, hipStream_t stream);
+// plan only (after the host has written states)
+void launch_batch_plan(const DevBatch& bt, hipStream_t stream);
 // (c) apply; returns false if the buffer layout needs the element-wise kernel
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,
                   const uint32_t* bitmask, int32_t V_mask, const int32_t* row_index, int32_t n_rows,

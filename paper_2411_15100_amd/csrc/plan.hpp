@@ -1,9 +1,17 @@
-// Host-side planning of the fill kernel's workgroups (no device code).
+// Planning of the fill kernel's workgroups.  The arithmetic is plain C++ that
+// compiles for the host (xgm_fill_next_token_bitmask plans there, per call)
+// and for the device (a batch of device-resident states is planned by a small
+// kernel after every change of state).
 #pragma once
-#include <algorithm>
 #include <cstdint>
 
 #include "kernels.hpp"
+
+#if defined(__HIPCC__) || defined(__HIP__)
+#define XGM_PLAN_HD __host__ __device__ inline
+#else
+#define XGM_PLAN_HD inline
+#endif
 
 namespace xgm {
 
@@ -14,36 +22,53 @@ namespace xgm {
 // proportion to that number: every row gets at least as many as its mask
 // words need (a workgroup owns at most kFillMaxChunks chunks), and its chunks
 // are cut where the running entry count passes equal shares.
-//   upto(b, c): entries of row b in chunks [0, c), all its stacks together
-//               (non-decreasing in c, upto(b, 0) == 0);
+
+// workgroups every row needs at least
+XGM_PLAN_HD int32_t plan_min_blocks(int32_t n_chunk) { return (n_chunk + kFillMaxChunks - 1) / kFillMaxChunks; }
+
+// the share of a row with `row_entries` of the batch's `total` entries
+XGM_PLAN_HD int32_t plan_row_share(int32_t B, int32_t n_chunk, int32_t budget, uint64_t row_entries, uint64_t total) {
+  const int32_t min_blocks = plan_min_blocks(n_chunk);
+  if (budget < B * min_blocks) budget = B * min_blocks;
+  const int32_t spare = budget - B * min_blocks;
+  int32_t k = min_blocks;
+  if (total) k += (int32_t)((uint64_t)spare * row_entries / total);
+  return k < n_chunk ? k : n_chunk;
+}
+
+// Cuts row b into (at most k + plan_min_blocks) workgroups; upto(c) = entries
+// of the row in chunks [0, c), all its stacks together (non-decreasing,
+// upto(0) == 0).  Writes them to `out` if it is not null; returns their number.
+template <class Upto>
+XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, FillBlock* out) {
+  const uint64_t row_entries = upto(n_chunk);
+  int32_t c0 = 0, made = 0;
+  for (int32_t c = 0; c < n_chunk; ++c) {
+    bool cut = c + 1 == n_chunk || c + 1 - c0 == kFillMaxChunks;
+    // cut after chunk c when the entries up to and including c reach the next share
+    if (!cut && made + 1 < k && row_entries)
+      cut = upto(c + 1) * (uint64_t)k >= row_entries * (uint64_t)(made + 1);
+    if (cut) {
+      if (out) out[made] = FillBlock{(uint32_t)b, (uint32_t)c0 | ((uint32_t)(c + 1) << 16)};
+      c0 = c + 1;
+      ++made;
+    }
+  }
+  return made;
+}
+
+//   upto(b, c): as above for row b;
 //   out:        room for B * n_chunk workgroups.
 // Returns the number of workgroups written.  Every (row, chunk) is covered by
 // exactly one of them; rows appear in order, chunk ranges ascending.
 template <class Upto>
 inline int32_t plan_workgroups(int32_t B, int32_t n_chunk, int32_t budget, Upto upto, FillBlock* out) {
-  const int32_t min_blocks = (n_chunk + kFillMaxChunks - 1) / kFillMaxChunks;
-  budget = std::max(budget, B * min_blocks);
   uint64_t total = 0;
   for (int32_t b = 0; b < B; ++b) total += upto(b, n_chunk);
-  const int32_t spare = budget - B * min_blocks;
   int32_t n_blocks = 0;
   for (int32_t b = 0; b < B; ++b) {
-    const uint64_t row_entries = upto(b, n_chunk);
-    int32_t k = min_blocks;
-    if (total) k += (int32_t)((uint64_t)spare * row_entries / total);
-    k = std::min(k, n_chunk);
-    int32_t c0 = 0, made = 0;
-    for (int32_t c = 0; c < n_chunk; ++c) {
-      bool cut = c + 1 == n_chunk || c + 1 - c0 == kFillMaxChunks;
-      // cut after chunk c when the entries up to and including c reach the next share
-      if (!cut && made + 1 < k && row_entries)
-        cut = upto(b, c + 1) * (uint64_t)k >= row_entries * (uint64_t)(made + 1);
-      if (cut) {
-        out[n_blocks++] = FillBlock{(uint32_t)b, (uint32_t)c0 | ((uint32_t)(c + 1) << 16)};
-        c0 = c + 1;
-        ++made;
-      }
-    }
+    const int32_t k = plan_row_share(B, n_chunk, budget, upto(b, n_chunk), total);
+    n_blocks += plan_row(b, n_chunk, k, [&](int32_t c) { return upto(b, c); }, out + n_blocks);
   }
   return n_blocks;
 }

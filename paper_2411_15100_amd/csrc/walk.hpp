@@ -48,6 +48,7 @@ struct CompactTab {
   }
   XGM_HD uint32_t alt(uint32_t idx) const { return v.alts[idx]; }
   XGM_HD bool is_final(uint32_t n) const { return ((n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n]).y & 1u; }
+  XGM_HD bool is_dead_end(uint32_t n) const { return ((n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n]).y & 4u; }
   // the 256-bit FOLLOW set of node n's rule
   XGM_HD const uint32_t* follow_of(uint32_t n) const {
     const uint2 h = (n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n];
@@ -233,6 +234,50 @@ struct CollectNextBytes {
   template <class Live>
   XGM_HD void operator()(uint32_t n, uint32_t sp, const uint32_t* arena, const Live& live) const {
     config_next_bytes(*T, node_first_words, n, sp, arena, live, *acc);
+  }
+};
+
+// End policy that writes out the stack of every configuration a token can end
+// in (section 3.3: the sampled token moves every parallel stack on).  A top
+// node that can only return is returned from first, so that equal states get
+// equal stacks.  A stack goes to the slot that `sink.claim()` hands out:
+//   sink.frames  [capacity][max_depth] uint16, bottom frame first, the current node last
+//   sink.depth   [capacity]
+// A stack deeper than max_depth, or more stacks than capacity, set *sink.overflow.
+// The same stack may be written more than once (several paths): the caller
+// removes duplicates.
+template <class Tab, class Sink>
+struct CollectStacks {
+  static constexpr bool kEnumerate = true;
+  const Tab* T;
+  Sink* sink;
+  template <class Live>
+  XGM_HD void operator()(uint32_t n, uint32_t sp, const uint32_t* arena, const Live& live) const {
+    while (T->is_dead_end(n)) {
+      if (sp < kLiveBase) {
+        const uint32_t fr = arena[sp];
+        n = fr & 0xFFFFu;
+        sp = fr >> 16;
+      } else {
+        const uint32_t d = sp - kLiveBase;
+        if (d == 0) break;
+        n = live[d - 1];
+        sp = kLiveBase + d - 1;
+      }
+    }
+    uint32_t depth = 1, h = sp;
+    for (; h < kLiveBase; h = arena[h] >> 16) ++depth;
+    const uint32_t d = h - kLiveBase;  // live frames kept
+    depth += d;
+    if (depth > sink->max_depth) { *sink->overflow = 1u; return; }
+    const uint32_t idx = sink->claim();
+    if (idx >= sink->capacity) { *sink->overflow = 1u; return; }
+    auto* out = sink->frames + (size_t)idx * sink->max_depth;
+    out[depth - 1] = (uint16_t)n;
+    uint32_t k = depth - 1;
+    for (h = sp; h < kLiveBase; h = arena[h] >> 16) out[--k] = (uint16_t)(arena[h] & 0xFFFFu);
+    for (uint32_t j = 0; j < d; ++j) out[j] = (uint16_t)live[j];
+    sink->depth[idx] = depth;
   }
 };
 

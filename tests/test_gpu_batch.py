@@ -1,0 +1,414 @@
+"""GPU parity of the device-resident matcher states (xgm_batch_*): tokens are
+accepted by a kernel, the fill reads the states where they are.  Expected
+masks come from the CPU oracle; expected stacks and status codes from the
+library's host matchers, which the CPU suite pins to the oracle."""
+
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def xgm():
+    import paper_2411_15100_amd as lib
+    lib.load_library()
+    return lib
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_2411_15100_amd import workloads
+    return workloads
+
+
+def _stream():
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _stacks(m):
+    return None if m.is_terminated() else [m.stack(s) for s in range(m.num_stacks())]
+
+
+def _dev(values):
+    return torch.tensor(list(values), dtype=torch.int32, device="cuda")
+
+
+class _Rows:
+    """B rows over one vocabulary: host matchers, oracle matchers, a device batch."""
+
+    def __init__(self, xgm, wl, specs, vocab, history):
+        self.vocab = vocab
+        self.xv = wl.make_xgm_vocab(vocab)
+        self.caches = [xgm.Cache(xgm.Grammar(t, r), self.xv) for t, r in specs]
+        self.ogs = [oracle.Grammar(t, r) for t, r in specs]
+        self.ms = [xgm.Matcher(cache=c) for c in self.caches]
+        self.scratch = [xgm.Matcher(cache=c) for c in self.caches]
+        self.oms = [oracle.EarleyMatcher(o) for o in self.ogs]
+        self.B = len(specs)
+        self.W = xgm.bitmask_words(vocab.size)
+        self.batch = xgm.DeviceBatch(self.ms, history=history, stream=_stream())
+        self.d_dev = torch.zeros((self.B, self.W), dtype=torch.int32, device="cuda")
+        self.d_host = torch.zeros((self.B, self.W), dtype=torch.int32, device="cuda")
+
+    def masks(self, xgm):
+        """(mask from the device states, mask from the host matchers), both packed on the host;
+        walks over the on-chip limits (the markup grammar has a few) are decided after each fill."""
+        self.d_dev.fill_(-1)
+        self.batch.fill_next_token_bitmask(self.d_dev.data_ptr(), _stream())
+        xgm.fill_overflow_fixup(_stream())
+        xgm.fill_next_token_bitmask(self.ms, self.d_host.data_ptr(), _stream())
+        xgm.fill_overflow_fixup(_stream())
+        return self.d_dev.cpu().numpy(), self.d_host.cpu().numpy()
+
+    def check_states(self):
+        for b in range(self.B):
+            self.batch.get_row(b, self.scratch[b], _stream())
+            assert _stacks(self.scratch[b]) == _stacks(self.ms[b]), f"row {b}"
+
+
+MIXED = [(si.JSON_GRAMMAR, "root"), (si.CSQL_GRAMMAR, "root"), (si.XML_GRAMMAR, "root"), (si.ARITH_GRAMMAR, "expr"),
+         (si.make_schema_grammar(0, string_heavy=True), "root"), (si.make_schema_grammar(1), "root"),
+         (si.JSON_GRAMMAR, "root"), (si.make_schema_grammar(2, string_heavy=True), "root")]
+
+
+def test_device_accept_follows_host_matchers_and_oracle(xgm, wl):
+    vocab = si.make_vocab("bpe", 32000, 0)
+    rows = _Rows(xgm, wl, MIXED, vocab, history=4)
+    info = wl.TokenInfo(vocab)
+    toks = vocab.tokens()
+    nonempty = np.array([len(t) > 0 for t in toks])
+    rng = np.random.Generator(np.random.PCG64(2024))
+    n_ok = n_rejected = n_skipped = n_stopped = n_after_stop = n_host = 0
+    fresh_overflow = xgm.overflow_total()
+    for step in range(60):
+        got, host = rows.masks(xgm)
+        assert np.array_equal(got, host), f"step {step}: rows {np.flatnonzero((got != host).any(axis=1))}"
+        if step % 6 == 0:
+            want = np.stack([np.zeros(vocab.size, dtype=bool) if m.is_terminated() else om.mask(vocab)
+                             for m, om in zip(rows.ms, rows.oms)])
+            for b, m in enumerate(rows.ms):
+                if m.is_terminated():
+                    want[b, vocab.stop_ids] = True
+            assert np.array_equal(got, oracle.pack_bitmask(want)), f"step {step}"
+        allowed = wl.unpack_rows(got, vocab.size)
+        picks = si.pick_tokens(rng, allowed, info.structural, info.is_stop, 0.35)
+        tokens = np.array(picks, dtype=np.int64)
+        for b in range(rows.B):
+            u = rng.random()
+            if rows.ms[b].is_terminated():
+                tokens[b] = int(rng.integers(0, vocab.size))      # anything: the row reports that it has terminated
+            elif u < 0.12:
+                bad = np.flatnonzero(~allowed[b] & nonempty)
+                tokens[b] = int(bad[rng.integers(0, bad.size)])
+            elif u < 0.2:
+                tokens[b] = -1
+        status_before = rows.batch.status(_stream())
+        rows.batch.accept_tokens(_dev(tokens).data_ptr(), _stream())
+        status = rows.batch.status(_stream())
+        for b in range(rows.B):
+            t = int(tokens[b])
+            if t < 0:
+                assert status[b] == status_before[b]
+                n_skipped += 1
+                continue
+            rc = rows.ms[b].try_accept_token(t)
+            if rc == 0 and status[b] in (-8, -9):
+                # beyond what the device holds or walks: the host's state becomes the row's next state
+                rows.batch.set_row(b, rows.ms[b], _stream())
+                n_host += 1
+            else:
+                assert status[b] == rc, (step, b, toks[t], status[b], rc)
+            if rc == 0 and rows.ms[b].is_terminated():
+                n_stopped += 1
+            elif rc == 0:
+                assert rows.oms[b].advance(toks[t])
+                n_ok += 1
+            elif rc == -7:
+                n_after_stop += 1
+                # start the row again, through the host
+                rows.ms[b].reset()
+                rows.oms[b] = oracle.EarleyMatcher(rows.ogs[b])
+                rows.batch.set_row(b, rows.ms[b], _stream())
+            else:
+                assert rc == -6
+                n_rejected += 1
+        rows.check_states()
+    say(f"  accepted {n_ok}, rejected {n_rejected}, skipped {n_skipped}, stop tokens {n_stopped}, "
+        f"tokens after the stop {n_after_stop}, through the host {n_host}; walks over the limits in these fills: {xgm.overflow_total() - fresh_overflow}")
+    assert n_ok > 250 and n_rejected > 20 and n_skipped > 10 and n_host < 10
+
+
+def test_rollback_returns_to_earlier_states(xgm, wl):
+    vocab = si.make_vocab("bpe", 32000, 0)
+    specs = [(si.JSON_GRAMMAR, "root"), (si.make_schema_grammar(3, string_heavy=True), "root"),
+             (si.CSQL_GRAMMAR, "root"), (si.JSON_GRAMMAR, "root")]
+    rows = _Rows(xgm, wl, specs, vocab, history=5)
+    info = wl.TokenInfo(vocab)
+    toks = vocab.tokens()
+    rng = np.random.Generator(np.random.PCG64(77))
+    accepted = [[] for _ in range(rows.B)]
+
+    def advance(n_steps):
+        for _ in range(n_steps):
+            got, host = rows.masks(xgm)
+            assert np.array_equal(got, host)
+            allowed = wl.unpack_rows(got, vocab.size)
+            allowed[:, vocab.stop_ids] = False
+            picks = si.pick_tokens(rng, allowed, info.structural, info.is_stop, 0.35)
+            rows.batch.accept_tokens(_dev(picks).data_ptr(), _stream())
+            assert not rows.batch.status(_stream()).any()
+            for b in range(rows.B):
+                rows.ms[b].accept_token(int(picks[b]))
+                accepted[b].append(int(picks[b]))
+
+    def replay():
+        for b in range(rows.B):
+            rows.ms[b].reset()
+            rows.oms[b] = oracle.EarleyMatcher(rows.ogs[b])
+            for t in accepted[b]:
+                rows.ms[b].accept_token(t)
+                assert rows.oms[b].advance(toks[t])
+
+    advance(7)
+    back = [0, 2, 5, 6]          # the ring keeps 5 older states: row 3 asks for too much
+    rows.batch.rollback(_dev(back).data_ptr(), _stream())
+    status = rows.batch.status(_stream())
+    assert list(status) == [0, 0, 0, -1]
+    for b, k in enumerate(back[:3]):
+        accepted[b] = accepted[b][: len(accepted[b]) - k]
+    replay()
+    rows.check_states()
+    got, host = rows.masks(xgm)
+    assert np.array_equal(got, host)
+    want = np.stack([om.mask(vocab) for om in rows.oms])
+    assert np.array_equal(got, oracle.pack_bitmask(want))
+    # going on from the restored states, then back again by what the ring holds now
+    advance(3)
+    rows.check_states()
+    rows.batch.rollback(_dev([3, 1, 0, 3]).data_ptr(), _stream())
+    assert not rows.batch.status(_stream()).any()
+    for b, k in enumerate([3, 1, 0, 3]):
+        accepted[b] = accepted[b][: len(accepted[b]) - k]
+    replay()
+    rows.check_states()
+    got, host = rows.masks(xgm)
+    assert np.array_equal(got, host)
+    want = np.stack([om.mask(vocab) for om in rows.oms])
+    assert np.array_equal(got, oracle.pack_bitmask(want))
+
+
+@pytest.mark.parametrize("dtype_name", ["bf16", "f32"])
+def test_batch_fused_fill_and_apply(xgm, wl, dtype_name):
+    vocab = si.make_vocab("bpe", 9000, 0)
+    specs = [(si.JSON_GRAMMAR, "root"), (si.make_schema_grammar(4, string_heavy=True), "root"), (si.ARITH_GRAMMAR, "expr")]
+    rows = _Rows(xgm, wl, specs, vocab, history=0)
+    for m, om, text in zip(rows.ms, rows.oms, [b'{"a', b"{", b"(1+"]):
+        m.accept_bytes(text)
+        assert om.advance(text)
+    for b in range(rows.B):
+        rows.batch.set_row(b, rows.ms[b], _stream())
+    tdt, code, ninf = (torch.bfloat16, xgm.DTYPE_BF16, 0xFF80) if dtype_name == "bf16" else (torch.float32, xgm.DTYPE_F32, 0xFF800000)
+    Vl = 9008
+    logits = torch.from_numpy(si.make_logits(rows.B, Vl, seed=9)).to("cuda").to(tdt).contiguous()
+    before = logits.clone()
+    rows.batch.fill_and_apply(rows.d_dev.data_ptr(), logits.data_ptr(), code, Vl, logits.stride(0), _stream())
+    want = np.stack([om.mask(vocab) for om in rows.oms])
+    assert np.array_equal(rows.d_dev.cpu().numpy(), oracle.pack_bitmask(want))
+    raw = lambda t: t.view(torch.int16 if tdt == torch.bfloat16 else torch.int32).cpu().numpy()
+    out, src = raw(logits), raw(before)
+    full = np.zeros((rows.B, Vl), dtype=bool)
+    full[:, : vocab.size] = want
+    ninf_signed = np.array(ninf, dtype=np.uint16 if tdt == torch.bfloat16 else np.uint32).view(out.dtype)
+    assert np.array_equal(out, np.where(full, src, ninf_signed))
+    with pytest.raises(xgm.XgmError):
+        rows.batch.fill_and_apply(rows.d_dev.data_ptr(), logits.data_ptr(), code, 100, logits.stride(0), _stream())
+
+
+def test_device_limits_are_reported_and_the_host_takes_over(xgm, wl):
+    toks = [b"x", b"p", b"q", b"xx", b"[", b"]", b"1", b","] + [b""]
+    V = len(toks)
+
+    class V_:
+        data = np.frombuffer(b"".join(toks), dtype=np.uint8).copy()
+        offsets = np.concatenate([[0], np.cumsum([len(t) for t in toks])]).astype(np.int64)
+        stop_ids = np.array([8], dtype=np.int32)
+        size = V
+
+    xv = xgm.Vocab(V_.data, V_.offsets, V_.stop_ids)
+    amb = 'root ::= a | b\na ::= "x" root? "p"\nb ::= "x" root? "q"'
+    nest = 'root ::= "[" (root ("," root)*)? "]" | "1"'
+    ca, cn = xgm.Cache(xgm.Grammar(amb, "root"), xv), xgm.Cache(xgm.Grammar(nest, "root"), xv)
+    ma, mn = xgm.Matcher(cache=ca), xgm.Matcher(cache=cn)
+    oa, on = oracle.EarleyMatcher(oracle.Grammar(amb, "root")), oracle.EarleyMatcher(oracle.Grammar(nest, "root"))
+    batch = xgm.DeviceBatch([ma, mn], history=2, stream=_stream())
+    d = torch.zeros((2, 1), dtype=torch.int32, device="cuda")
+    # row 0 doubles its stacks with every "x" (2, 4, 8, 16, then 32: over the device limit of 16);
+    # row 1 nests deeper with every "[" until a stack passes 128 frames
+    depth_hit = None
+    for step in range(140):
+        batch.accept_tokens(_dev([0 if step < 5 else -1, 4]).data_ptr(), _stream())
+        st = batch.status(_stream())
+        if step < 4:
+            assert st[0] == 0
+            ma.accept_token(0)
+            assert oa.advance(b"x")
+        elif step == 4:
+            assert st[0] == -8            # too many stacks for the device: the row keeps its 16
+        if st[1] == 0:
+            mn.accept_token(4)
+            assert on.advance(b"[")
+        else:
+            assert st[1] == -9
+            depth_hit = step
+            break
+    assert depth_hit is not None and max(len(s) for s in _stacks(mn)) >= 127
+    say(f"  row 1 reached the device's depth limit after {depth_hit} tokens")
+    batch.fill_next_token_bitmask(d.data_ptr(), _stream())
+    got = d.cpu().numpy()
+    assert np.array_equal(got[0], oracle.pack_bitmask(oa.mask(V_)))
+    assert np.array_equal(got[1], oracle.pack_bitmask(on.mask(V_)))
+    sa, sn = xgm.Matcher(cache=ca), xgm.Matcher(cache=cn)
+    batch.get_row(0, sa, _stream())
+    batch.get_row(1, sn, _stream())
+    assert _stacks(sa) == _stacks(ma) and ma.num_stacks() == 16
+    assert _stacks(sn) == _stacks(mn)
+    # the host can go on where the device cannot, but such a state does not go back to the device
+    sa.accept_token(0)
+    assert sa.num_stacks() == 32
+    with pytest.raises(xgm.XgmError):
+        batch.set_row(0, sa, _stream())
+    sn.accept_token(4)
+    with pytest.raises(xgm.XgmError):
+        batch.set_row(1, sn, _stream())
+    # a state within the limits does: close one level on the host, hand it back
+    sn.accept_token(6)
+    sn.accept_token(5)
+    sn.accept_token(5)
+    assert on.advance(b"[1]]")
+    batch.set_row(1, sn, _stream())
+    batch.fill_next_token_bitmask(d.data_ptr(), _stream())
+    assert np.array_equal(d.cpu().numpy()[1], oracle.pack_bitmask(on.mask(V_)))
+    # creation refuses what the device cannot hold, and bad arguments
+    with pytest.raises(xgm.XgmError):
+        xgm.DeviceBatch([sa], history=2, stream=_stream())
+    with pytest.raises(xgm.XgmError):
+        xgm.DeviceBatch([ma], history=64, stream=_stream())
+    with pytest.raises(xgm.XgmError):
+        xgm.DeviceBatch([xgm.Matcher(grammar=xgm.Grammar(nest, "root"), vocab=xv)], history=1, stream=_stream())
+
+
+def test_batch_fill_walks_over_the_limits_are_fixed_up(xgm, wl):
+    """A token that pushes more than 64 frames: the fill records it, the fixup
+    decides it on the host from the state read back from the device; accepting
+    it on the device reports the limit and the host takes the row over."""
+    deep = b")+" + b"(" * 30
+    toks = [b"1", b"(", b")", b"+", deep, deep + b"+", b"1" * 20, b")" * 4, b""]
+    V = len(toks)
+
+    class V_:
+        data = np.frombuffer(b"".join(toks), dtype=np.uint8).copy()
+        offsets = np.concatenate([[0], np.cumsum([len(t) for t in toks])]).astype(np.int64)
+        stop_ids = np.array([8], dtype=np.int32)
+        size = V
+
+    xv = xgm.Vocab(V_.data, V_.offsets, V_.stop_ids)
+    cache = xgm.Cache(xgm.Grammar(si.ARITH_GRAMMAR, "expr"), xv)
+    og = oracle.Grammar(si.ARITH_GRAMMAR, "expr")
+    m = xgm.Matcher(cache=cache)
+    om = oracle.EarleyMatcher(og)
+    text = b"(" * 5 + b"1"
+    m.accept_bytes(text)
+    assert om.advance(text)
+    want = om.mask(V_)
+    assert want[4] and not want[5]
+    batch = xgm.DeviceBatch([m], history=1, stream=_stream())
+    d = torch.zeros((1, 1), dtype=torch.int32, device="cuda")
+    before = xgm.overflow_total()
+    batch.fill_next_token_bitmask(d.data_ptr(), _stream())
+    torch.cuda.synchronize()
+    assert xgm.overflow_total() - before == 2
+    assert xgm.fill_overflow_fixup(_stream()) == 2
+    assert np.array_equal(d.cpu().numpy()[0], oracle.pack_bitmask(want))
+    batch.accept_tokens(_dev([4]).data_ptr(), _stream())
+    assert list(batch.status(_stream())) == [-9]
+    m.accept_token(4)
+    assert om.advance(deep)
+    batch.set_row(0, m, _stream())
+    batch.fill_next_token_bitmask(d.data_ptr(), _stream())
+    xgm.fill_overflow_fixup(_stream())
+    assert np.array_equal(d.cpu().numpy()[0], oracle.pack_bitmask(om.mask(V_)))
+
+
+def test_stop_token_and_termination_on_the_device(xgm, wl):
+    toks = [b"1", b"2", b"+", b"*", b"(", b")", b" ", b"12", b"+1", b")*", b"", b"((", b"1)", b"", b"3 "]
+    V = len(toks)
+
+    class V_:
+        data = np.frombuffer(b"".join(toks), dtype=np.uint8).copy()
+        offsets = np.concatenate([[0], np.cumsum([len(t) for t in toks])]).astype(np.int64)
+        stop_ids = np.array([10, 13], dtype=np.int32)
+        size = V
+
+    xv = xgm.Vocab(V_.data, V_.offsets, V_.stop_ids)
+    cache = xgm.Cache(xgm.Grammar(si.ARITH_GRAMMAR, "expr"), xv)
+    og = oracle.Grammar(si.ARITH_GRAMMAR, "expr")
+    ms = [xgm.Matcher(cache=cache) for _ in range(3)]
+    oms = [oracle.EarleyMatcher(og) for _ in range(3)]
+    batch = xgm.DeviceBatch(ms, history=3, stream=_stream())
+    d = torch.zeros((3, 1), dtype=torch.int32, device="cuda")
+
+    def expect():
+        want = np.stack([om.mask(V_) for om in oms])
+        for b, m in enumerate(ms):
+            if m.is_terminated():
+                want[b] = False
+                want[b, [10, 13]] = True
+        batch.fill_next_token_bitmask(d.data_ptr(), _stream())
+        assert np.array_equal(d.cpu().numpy(), oracle.pack_bitmask(want))
+
+    # stop before anything is written: rejected; a token without bytes that is no stop token: id 10/13 are both stops,
+    # so use an id beyond the vocabulary for the argument check
+    batch.accept_tokens(_dev([10, 0, V]).data_ptr(), _stream())
+    assert list(batch.status(_stream())) == [-6, 0, -1]
+    ms[1].accept_token(0)
+    assert oms[1].advance(b"1")
+    expect()
+    # row 1 may stop now (second stop id), row 0 writes "(", row 2 "12"
+    batch.accept_tokens(_dev([4, 13, 7]).data_ptr(), _stream())
+    assert list(batch.status(_stream())) == [0, 0, 0]
+    ms[0].accept_token(4)
+    ms[1].accept_token(13)
+    ms[2].accept_token(7)
+    assert oms[0].advance(b"(") and oms[2].advance(b"12")
+    assert ms[1].is_terminated()
+    expect()
+    s = xgm.Matcher(cache=cache)
+    batch.get_row(1, s, _stream())
+    assert s.is_terminated()
+    # after the stop token nothing is accepted, not even another stop
+    batch.accept_tokens(_dev([-1, 10, 10]).data_ptr(), _stream())
+    assert list(batch.status(_stream())) == [0, -7, 0]
+    ms[2].accept_token(10)
+    expect()
+    # one step back: rows 1 and 2 are open again
+    batch.rollback(_dev([0, 1, 1]).data_ptr(), _stream())
+    assert list(batch.status(_stream())) == [0, 0, 0]
+    for b, text in ((1, b"1"), (2, b"12")):
+        ms[b].reset()
+        ms[b].accept_bytes(text)
+    expect()
+    batch.get_row(1, s, _stream())
+    assert not s.is_terminated() and _stacks(s) == _stacks(ms[1])

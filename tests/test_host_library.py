@@ -436,3 +436,66 @@ def test_workgroup_plan_covers_every_chunk_once_and_follows_the_load():
         if counts[heavy] >= 4:
             loads = [int(upto[heavy, c1] - upto[heavy, c0]) for row, c0, c1 in plan if row == heavy]
             assert max(loads) <= 2 * (sum(loads) / len(loads)) + 3100
+
+
+AMBIGUOUS_GRAMMAR = 'root ::= a | b | c\na ::= "a"* "x"\nb ::= "a"* "y" tail\nc ::= ("a" "a")* "z"\ntail ::= "(" root ")" | ""\n'
+
+
+def _same_state(m1, m2):
+    assert m1.is_terminated() == m2.is_terminated()
+    if m1.is_terminated():
+        return
+    s1 = [m1.stack(s) for s in range(m1.num_stacks())]
+    s2 = [m2.stack(s) for s in range(m2.num_stacks())]
+    assert s1 == s2
+
+
+@pytest.mark.parametrize("name", ["arith", "json", "csql", "schema", "xml", "ambiguous"])
+def test_depth_first_accept_gives_the_engines_stacks(name):
+    """The routine the device uses to move stacks on by a token (an enumerating
+    depth-first walk over the flattened tables) against the host engine (a
+    breadth-first run of the structured automaton): same verdict for every
+    token tried and the same set of stacks, in the same order, after every
+    accepted one."""
+    if name == "ambiguous":
+        text, root = AMBIGUOUS_GRAMMAR, "root"
+        vocab = TinyVocab([b"a", b"aa", b"aaa", b"x", b"y", b"z", b"ax", b"aay(", b"(", b")", b"y(a", b"))", b"az", b""], [13])
+        toks = vocab.toks
+    else:
+        text, root, _ = GRAMMARS[name]
+        vocab = si.make_vocab("arith", 1024, 0) if name == "arith" else si.make_vocab("bpe", 4000, 3)
+        toks = vocab.tokens()
+    first = np.array([t[0] if t else -1 for t in toks], dtype=np.int16)
+    g = xgm.Grammar(text, root)
+    og = oracle.Grammar(text, root)
+    v = xgm.Vocab(vocab.data, vocab.offsets, vocab.stop_ids)
+    n_ok = n_rejected = n_multi = 0
+    for seed in range(20 if name == "ambiguous" else 3):
+        m1, m2 = xgm.Matcher(grammar=g, vocab=v), xgm.Matcher(grammar=g, vocab=v)
+        om = oracle.EarleyMatcher(og)
+        rng = np.random.Generator(np.random.PCG64(zlib.crc32(name.encode()) + 77 * seed))
+        for step in range(40):
+            want = om.mask(vocab)
+            # a few random tokens, allowed or not: same verdict, and a rejection leaves the state alone
+            for t in rng.integers(0, len(toks), 6):
+                if want[t] or not toks[t]:
+                    continue
+                assert m1.try_accept_token(int(t)) == -6
+                assert m2.debug_try_accept_token_walk(int(t)) == -6
+                n_rejected += 1
+                _same_state(m1, m2)
+            t = si.pick_token(rng, want, first, vocab.stop_ids, structural_bias=0.4)
+            if t < 0:
+                break
+            assert m1.try_accept_token(t) == 0
+            assert m2.debug_try_accept_token_walk(t) == 0, (name, seed, step, toks[t])
+            _same_state(m1, m2)
+            n_ok += 1
+            if m1.is_terminated():
+                assert m2.debug_try_accept_token_walk(t) == -7
+                break
+            n_multi += m1.num_stacks() > 1
+            assert om.advance(toks[t])
+    assert n_ok > 20 and n_rejected > 20, (n_ok, n_rejected)
+    if name == "ambiguous":
+        assert n_multi > 3
