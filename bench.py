@@ -3,8 +3,13 @@
 A step = one pass of the whole per-step path over one batch: batched mask
 fill (kernel b) + in-place -inf apply (kernel c) for the serving workload
 (batch 128, vocabulary 151936, 128 distinct string-heavy schema grammars,
-bf16 logits).  The mask caches (kernel a) are built during set-up and their
-throughput is reported beside it.  Prints ONE JSON line on stdout.
+bf16 logits), with everything it reads resident in device memory: the mask
+caches, the logits and the matcher states (xgm_batch_*).  The same step from
+host-side matcher states (stacks packed on the host and uploaded every step)
+is timed beside it, and so are the fused one-launch variants and the kernel
+that accepts a token per row on the device.  The mask caches (kernel a) are
+built during set-up and their throughput is reported too.  Prints ONE JSON
+line on stdout.
 """
 
 from __future__ import annotations
@@ -65,17 +70,28 @@ def main():
 
     # ---- warm-up, then the timed region: exactly K steps between two synchronisations
     for k in range(args.warmup):
-        work.step(k, stream)
+        work.step_device(k, stream)
     torch.cuda.synchronize()
     work.refresh_logits()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        work.step(k, stream)
+        work.step_device(k, stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     overflow = xgm.overflow_total()
+
+    # ---- the same K steps from host-side matcher states (pack + upload over PCIe every step)
+    for k in range(min(args.warmup, 10)):
+        work.step(k, stream)
+    work.refresh_logits()
+    torch.cuda.synchronize()
+    t0h = time.perf_counter()
+    for k in range(args.steps):
+        work.step(k, stream)
+    torch.cuda.synchronize()
+    host_state_us = (time.perf_counter() - t0h) * 1e6 / args.steps
 
     # ---- the same K steps again with HIP events around each kernel (same stream)
     work.refresh_logits()
@@ -83,7 +99,7 @@ def main():
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     for k in range(args.steps):
         ev[k][0].record()
-        work.fill(k, stream)
+        work.fill_device(k, stream)
         ev[k][1].record()
         work.apply(k, stream)
         ev[k][2].record()
@@ -96,9 +112,39 @@ def main():
     torch.cuda.synchronize()
     t0f = time.perf_counter()
     for k in range(args.steps):
-        work.fused_step(k, stream)
+        work.fused_step_device(k, stream)
     torch.cuda.synchronize()
     fused_us = (time.perf_counter() - t0f) * 1e6 / args.steps
+    work.refresh_logits()
+    torch.cuda.synchronize()
+    t0f = time.perf_counter()
+    for k in range(args.steps):
+        work.fused_step(k, stream)
+    torch.cuda.synchronize()
+    host_state_fused_us = (time.perf_counter() - t0f) * 1e6 / args.steps
+
+    # ---- accepting one token per row on the device (accept kernel + plan kernel), then one step back
+    accept_us = []
+    w0 = work.sets[0]
+    work.fill(0, stream)
+    torch.cuda.synchronize()
+    allowed0 = wl.unpack_rows(work.d_mask.cpu().numpy(), V)
+    allowed0[:, work.vocab.stop_ids] = False
+    picks = si.pick_tokens(np.random.Generator(np.random.PCG64(1)), allowed0, w0.info.structural, w0.info.is_stop, 0.35)
+    d_picks = torch.tensor(picks, dtype=torch.int32, device="cuda")
+    d_back = torch.tensor((picks >= 0).astype(np.int32), dtype=torch.int32, device="cuda")
+    accept_batch = xgm.DeviceBatch(w0.matchers, history=1, stream=stream)
+    for k in range(40):
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        accept_batch.accept_tokens(d_picks.data_ptr(), stream)
+        a1.record()
+        accept_batch.rollback(d_back.data_ptr(), stream)
+        torch.cuda.synchronize()
+        if k >= 8:
+            accept_us.append(a0.elapsed_time(a1) * 1e3)
+    assert not accept_batch.status(stream).any()
+    del accept_batch
 
     # ---- what this box writes at best: a plain fill of the same rotating logits buffers
     for t in work.logits:
@@ -223,13 +269,18 @@ def main():
         "ms_per_step": ms_per_step,
         "fill_plus_apply_us": ms_per_step * 1e3,
         "fused_fill_and_apply_us": fused_us,
+        "host_state_path": {"fill_plus_apply_us": host_state_us, "fused_fill_and_apply_us": host_state_fused_us,
+                            "note": "matcher states kept on the host: stacks packed and uploaded over PCIe every step"},
+        "device_accept_us": {"mean": float(np.mean(accept_us)), "p50": float(np.median(accept_us)),
+                             "note": "one token per row accepted by the accept kernel + the plan kernel "
+                                     "(events around the call); outside the fill+apply step"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32",
         "logits_dtype": "bf16 (only -inf patterns are stored; no floating-point arithmetic anywhere on the path)",
         "data": "synthetic",
         "config": {"workload": f"serving decode step: batch {B} x vocab {V}, {B} distinct string-heavy schema "
-                               f"grammars, bf16 logits [{B},{V}], {n_sets} pre-walked state sets, "
-                               f"{len(work.logits)} rotating logits buffers",
+                               f"grammars, bf16 logits [{B},{V}], {n_sets} pre-walked state sets resident on the "
+                               f"device, {len(work.logits)} rotating logits buffers",
                    "batch": B, "vocab": V,
                    "context_dependent_fraction_at_tops": work.uncertain_fraction,
                    "context_dependent_fraction_after_narrowing": work.uncertain_fraction_narrowed},

@@ -196,8 +196,24 @@ class ServingWorkload:
         self.logits = [torch.randn((n_rows, vocab_size), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
                        for _ in range(n_logit_buffers)]
 
+        # the same state sets resident on the device (no per-step packing or upload)
+        self.device_sets = [xgm.DeviceBatch(w.matchers, history=0, stream=current_stream()) for w in self.sets]
+
     def fill(self, k: int, stream: int):
         self.sets[k % len(self.sets)].batch.fill_next_token_bitmask(self.d_mask.data_ptr(), stream)
+
+    def fill_device(self, k: int, stream: int):
+        """Fill from the device-resident copy of state set k."""
+        self.device_sets[k % len(self.device_sets)].fill_next_token_bitmask(self.d_mask.data_ptr(), stream)
+
+    def step_device(self, k: int, stream: int):
+        self.fill_device(k, stream)
+        self.apply(k, stream)
+
+    def fused_step_device(self, k: int, stream: int):
+        t = self.logits[k % len(self.logits)]
+        self.device_sets[k % len(self.device_sets)].fill_and_apply(self.d_mask.data_ptr(), t.data_ptr(), xgm.DTYPE_BF16,
+                                                                    self.V, t.stride(0), stream=stream)
 
     def apply(self, k: int, stream: int):
         t = self.logits[k % len(self.logits)]
