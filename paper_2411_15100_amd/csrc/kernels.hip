@@ -970,7 +970,7 @@ __global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint32_t* upto = reinterpret_cast<uint32_t*>(smem);  // [B][n_chunk + 1]
   __shared__ unsigned long long total;
-  __shared__ uint32_t count[kBatchMaxRows];
+  __shared__ uint32_t count[kPlanThreads];
   const uint32_t tid = threadIdx.x, stride = (uint32_t)bt.n_chunk + 1u;
   const uint32_t hdr_stride = kStackHdrWords + stride;
   if (tid == 0) total = 0ull;
@@ -989,20 +989,22 @@ __global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
   __syncthreads();
   int32_t k = 0;
   const uint32_t* mine = upto + tid * stride;
+  uint32_t my_count = 0u;
   if (tid < (uint32_t)bt.B) {
     k = plan_row_share(bt.B, bt.n_chunk, bt.budget, mine[bt.n_chunk], total);
-    count[tid] = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; }, (FillBlock*)nullptr);
+    my_count = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; }, (FillBlock*)nullptr);
   }
+  count[tid] = my_count;
   __syncthreads();
-  if (tid == 0) {  // exclusive scan
-    uint32_t run = 0u;
-    for (int32_t b = 0; b < bt.B; ++b) { const uint32_t c = count[b]; count[b] = run; run += c; }
-    total = run;
+  for (uint32_t d = 1; d < (uint32_t)kPlanThreads; d <<= 1) {  // inclusive scan of the rows' workgroup counts
+    const uint32_t v = tid >= d ? count[tid - d] : 0u;
+    __syncthreads();
+    count[tid] += v;
+    __syncthreads();
   }
-  __syncthreads();
-  const uint32_t n_blocks = (uint32_t)total;
-  if (tid < (uint32_t)bt.B && count[tid] + (uint32_t)(k + plan_min_blocks(bt.n_chunk)) <= bt.plan_cap)
-    plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; }, bt.plan + count[tid]);
+  const uint32_t n_blocks = count[kPlanThreads - 1], first = count[tid] - my_count;
+  if (tid < (uint32_t)bt.B && first + (uint32_t)(k + plan_min_blocks(bt.n_chunk)) <= bt.plan_cap)
+    plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; }, bt.plan + first);
   for (uint32_t j = n_blocks + tid; j < bt.plan_cap; j += kPlanThreads) bt.plan[j] = FillBlock{kNoRow, 0u};
 }
 
