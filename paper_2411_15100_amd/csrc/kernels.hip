@@ -33,26 +33,33 @@ __device__ __forceinline__ void stage_tables(const DevTables& tab, unsigned char
 // section is an LDS read and one in an unstaged section a global load (a
 // pointer that may point to either would make every access a much slower flat
 // one).  Sections are staged whole, so "is it in LDS" is uniform per section.
+// kSmallInLds = true: every section in front of the headers is known to be
+// staged, so their reads carry no test at all (a lone wave pays for every
+// branch of a walk step with its latency).
 #define XGM_LDS __attribute__((address_space(3)))
 #define XGM_GLOBAL __attribute__((address_space(1)))
-struct LdsTab {
+template <bool kSmallInLds>
+struct LdsTabT {
   const XGM_LDS unsigned char* lds;     // the staged part of the image
   const XGM_GLOBAL unsigned char* img;  // the whole image
   uint32_t n_near, n_cls, off_shapes, off_targets, off_follow, off_alts, off_hdr, off_first;
   bool cls_lds, shapes_lds, targets_lds, follow_lds, alts_lds;
-  __device__ __forceinline__ LdsTab(const DevTables& t, unsigned char* smem)
+  __device__ __forceinline__ LdsTabT(const DevTables& t, unsigned char* smem)
       : lds((const XGM_LDS unsigned char*)smem),
         img((const XGM_GLOBAL unsigned char*)reinterpret_cast<const unsigned char*>(t.image)),
         n_near(t.n_near), n_cls((uint32_t)t.n_cls), off_shapes(t.off_shapes), off_targets(t.off_targets),
         off_follow(t.off_follow), off_alts(t.off_alts), off_hdr(t.off_hdr), off_first(t.off_first),
         cls_lds(t.lds_end >= 256u), shapes_lds(t.lds_end >= t.off_targets), targets_lds(t.lds_end >= t.off_follow),
         follow_lds(t.lds_end >= t.off_alts), alts_lds(t.lds_end >= t.off_hdr) {}
-  __device__ __forceinline__ uint32_t rd8(uint32_t off, bool in_lds) const { return in_lds ? (uint32_t)lds[off] : (uint32_t)img[off]; }
+  __device__ __forceinline__ uint32_t rd8(uint32_t off, bool in_lds) const {
+    return (kSmallInLds || in_lds) ? (uint32_t)lds[off] : (uint32_t)img[off];
+  }
   __device__ __forceinline__ uint32_t rd16(uint32_t off, bool in_lds) const {
-    return in_lds ? (uint32_t)*(const XGM_LDS uint16_t*)(lds + off) : (uint32_t)*(const XGM_GLOBAL uint16_t*)(img + off);
+    return (kSmallInLds || in_lds) ? (uint32_t)*(const XGM_LDS uint16_t*)(lds + off)
+                                   : (uint32_t)*(const XGM_GLOBAL uint16_t*)(img + off);
   }
   __device__ __forceinline__ uint32_t rd32(uint32_t off, bool in_lds) const {
-    return in_lds ? *(const XGM_LDS uint32_t*)(lds + off) : *(const XGM_GLOBAL uint32_t*)(img + off);
+    return (kSmallInLds || in_lds) ? *(const XGM_LDS uint32_t*)(lds + off) : *(const XGM_GLOBAL uint32_t*)(img + off);
   }
   __device__ __forceinline__ uint2 header(uint32_t n) const {
     unsigned long long h;  // one 8-byte read
@@ -93,10 +100,13 @@ struct LdsTab {
   // generic pointer to the 256-bit FOLLOW set of node n's rule (read on the rare exit from the start frame)
   __device__ __forceinline__ const uint32_t* follow_of(uint32_t n) const {
     const uint32_t off = off_follow + (header(n).y >> 16) * 32u;
-    return follow_lds ? (const uint32_t*)(const XGM_LDS uint32_t*)(lds + off)
-                      : (const uint32_t*)(const XGM_GLOBAL uint32_t*)(img + off);
+    return (kSmallInLds || follow_lds) ? (const uint32_t*)(const XGM_LDS uint32_t*)(lds + off)
+                                       : (const uint32_t*)(const XGM_GLOBAL uint32_t*)(img + off);
   }
 };
+using LdsTab = LdsTabT<false>;
+// are all sections in front of the headers staged?
+__device__ __forceinline__ bool small_sections_staged(const DevTables& t) { return t.lds_end >= t.off_hdr; }
 
 // The live frames of a request for the fill kernel: the topmost ones in LDS,
 // deeper ones (stacks deeper than the LDS window) in global memory.
@@ -195,8 +205,12 @@ __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
   extern __shared__ __align__(16) unsigned char smem[];
   stage_tables(tab, smem, kClassifyThreads);
   __syncthreads();
-  classify_body<kClassifyThreads>(LdsTab(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count, log,
-                                  seq, nodes_per_block);
+  if (small_sections_staged(tab))
+    classify_body<kClassifyThreads>(LdsTabT<true>(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank,
+                                    plain_count, log, seq, nodes_per_block);
+  else
+    classify_body<kClassifyThreads>(LdsTab(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count,
+                                    log, seq, nodes_per_block);
 }
 
 // Rank space -> id space: bit id of the output = bit rank_of_id[id] of the
@@ -355,43 +369,46 @@ __global__ __launch_bounds__(kContextThreads) void context_classes_kernel(DevTab
   extern __shared__ __align__(16) unsigned char smem[];
   stage_tables(tab, smem, kContextThreads);
   __syncthreads();
-  const LdsTab T(tab, smem);
-  const uint32_t j = blockIdx.x * kContextThreads + threadIdx.x;
-  if (j >= total) return;
-  // the entry's (node, chunk): the last slot of `off` that starts at or before j
-  const uint32_t stride = (uint32_t)voc.n_chunk + 1u;
-  uint32_t lo = 0u, hi = (uint32_t)n_nodes * stride;  // off[lo] <= j < off[hi - 1 + 1 ...]; the last slot equals total
-  while (hi - lo > 1u) {
-    const uint32_t mid = (lo + hi) >> 1;
-    if (off[mid] <= j) lo = mid; else hi = mid;
-  }
-  const uint32_t node = lo / stride, chunk = lo % stride;
-  const uint32_t e = list[j];
-  const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, b2 = e >> 24;
-  const int32_t id = (int32_t)(chunk * kChunkTokens + lid);
-  const uint4 tk = voc.tok_by_id[id];
-  int len = (int)(tk.w >> 24);
-  const uint8_t* ext = voc.bytes;
-  if (len >= 15) {
-    ext = voc.bytes + voc.off_by_id[id];
-    if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
-  }
-  // where the suffix starts (-1: the entry has several exits)
-  const int from = meta <= 12u ? (int)meta : meta == kEntrySuffix2 ? len - 2 : meta == kEntrySuffix1 ? len - 1
-                                                                                : (b2 != 0u ? (int)b2 : -1);
-  const uint32_t rule = T.header(node).y >> 16;
-  const uint32_t ctx0 = ctx_off[rule], n_ctx = ctx_off[rule + 1] - ctx0;  // 0 .. kCtxMax
-  uint32_t classes = 0u;
-  for (uint32_t i = 0; i < kCtxMax; ++i) {
-    uint32_t code = kCtxWalk;
-    if (from >= 0 && i < n_ctx) {
-      const uint32_t r = ctx_node[ctx0 + i];
-      const int c = walk_token<true>(T, tk, ext, len, r, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r), from);
-      code = c == kAccept ? kCtxAccept : (c == kUncertain || c == kOverflow) ? kCtxWalk : kCtxReject;
+  auto body = [&](const auto& T) {
+    const uint32_t j = blockIdx.x * kContextThreads + threadIdx.x;
+    if (j >= total) return;
+    // the entry's (node, chunk): the last slot of `off` that starts at or before j
+    const uint32_t stride = (uint32_t)voc.n_chunk + 1u;
+    uint32_t lo = 0u, hi = (uint32_t)n_nodes * stride;  // off[lo] <= j < off[hi - 1 + 1 ...]; the last slot equals total
+    while (hi - lo > 1u) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (off[mid] <= j) lo = mid; else hi = mid;
     }
-    classes |= code << (2u * i);
-  }
-  list_ctx[j] = classes;
+    const uint32_t node = lo / stride, chunk = lo % stride;
+    const uint32_t e = list[j];
+    const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, b2 = e >> 24;
+    const int32_t id = (int32_t)(chunk * kChunkTokens + lid);
+    const uint4 tk = voc.tok_by_id[id];
+    int len = (int)(tk.w >> 24);
+    const uint8_t* ext = voc.bytes;
+    if (len >= 15) {
+      ext = voc.bytes + voc.off_by_id[id];
+      if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
+    }
+    // where the suffix starts (-1: the entry has several exits)
+    const int from = meta <= 12u ? (int)meta : meta == kEntrySuffix2 ? len - 2 : meta == kEntrySuffix1 ? len - 1
+                                                                                  : (b2 != 0u ? (int)b2 : -1);
+    const uint32_t rule = T.header(node).y >> 16;
+    const uint32_t ctx0 = ctx_off[rule], n_ctx = ctx_off[rule + 1] - ctx0;  // 0 .. kCtxMax
+    uint32_t classes = 0u;
+    for (uint32_t i = 0; i < kCtxMax; ++i) {
+      uint32_t code = kCtxWalk;
+      if (from >= 0 && i < n_ctx) {
+        const uint32_t r = ctx_node[ctx0 + i];
+        const int c = walk_token<true>(T, tk, ext, len, r, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r), from);
+        code = c == kAccept ? kCtxAccept : (c == kUncertain || c == kOverflow) ? kCtxWalk : kCtxReject;
+      }
+      classes |= code << (2u * i);
+    }
+    list_ctx[j] = classes;
+  };
+  if (small_sections_staged(tab)) body(LdsTabT<true>(tab, smem));
+  else body(LdsTab(tab, smem));
 }
 
 __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ items, int32_t n_items,
@@ -713,8 +730,12 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   if (tid == 0) sm.queue_n = 0u;
   __syncthreads();
   if (has_cache) {
-    fill_lists<COUNT, (APPLY != 0)>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc,
-                                    log, seq, my_steps, fa.pair_min_entries);
+    if (small_sections_staged(rd.tab))
+      fill_lists<COUNT, (APPLY != 0)>(LdsTabT<true>(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs,
+                                      frames, voc, log, seq, my_steps, fa.pair_min_entries);
+    else
+      fill_lists<COUNT, (APPLY != 0)>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc,
+                                      log, seq, my_steps, fa.pair_min_entries);
   }
   if (rd.flags & 1u) {
     for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
