@@ -931,7 +931,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   for (int32_t b = 0; b < B; ++b) {
     const xgm_matcher* m = ms[b];
     RowDesc& r = rows[b];
-    r.pad = 0;
+    r.pair_mask = 0;
     r.stack_begin = si;
     r.frame_begin = fi;
     r.n_frames = 0;
@@ -1174,6 +1174,12 @@ int xgm_fill_overflow_fixup(void* hip_stream) {
 
 // ------------------------------------------------- device-resident states
 namespace {
+uint32_t pair_threshold() {
+  Context& C = ctx();
+  std::lock_guard<std::mutex> lock(C.mu);
+  return C.pair_min_entries;
+}
+
 // what the matcher's current state looks like in slot `slot` of row `row`
 struct PackedState {
   SlotMeta meta{};
@@ -1278,12 +1284,13 @@ int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* h
     d.status = keep(dev_alloc<int32_t>(B));
     d.plan_cap = batch_plan_cap(B, n_chunk, d.budget);
     d.plan = keep(dev_alloc<FillBlock>(d.plan_cap));
+    d.pair = keep(dev_alloc<uint32_t>((size_t)B * kBatchMaxStacks * kPairWords));
     HIP_OK(hipMemset(d.meta, 0, slots * sizeof(SlotMeta)));
     HIP_OK(hipMemset(d.head, 0, (size_t)B * 4));
     HIP_OK(hipMemset(d.older, 0, (size_t)B * 4));
     HIP_OK(hipMemset(d.status, 0, (size_t)B * 4));
     for (int32_t b = 0; b < B; ++b) write_state(*bt, b, 0, pack_state(*bt, b, 0, *ms[b]));
-    launch_batch_plan(d, stream);
+    launch_batch_plan(d, v->dv, pair_threshold(), stream);
     HIP_OK(hipGetLastError());
     HIP_OK(hipStreamSynchronize(stream));
   } catch (...) {
@@ -1313,7 +1320,7 @@ int32_t xgm_batch_size(const xgm_batch* bt) { return bt ? bt->B : XGM_ERR_BAD_AR
 int xgm_batch_accept_tokens(xgm_batch* bt, const int32_t* d_token_ids, void* hip_stream) {
   API_BEGIN
   if (!bt || !d_token_ids) return fail(XGM_ERR_BAD_ARG, "batch_accept_tokens: null argument");
-  launch_batch_accept(bt->dev, bt->v->dv, d_token_ids, static_cast<hipStream_t>(hip_stream));
+  launch_batch_accept(bt->dev, bt->v->dv, d_token_ids, pair_threshold(), static_cast<hipStream_t>(hip_stream));
   HIP_OK(hipGetLastError());
   return XGM_OK;
   API_END
@@ -1322,7 +1329,7 @@ int xgm_batch_accept_tokens(xgm_batch* bt, const int32_t* d_token_ids, void* hip
 int xgm_batch_rollback(xgm_batch* bt, const int32_t* d_steps, void* hip_stream) {
   API_BEGIN
   if (!bt || !d_steps) return fail(XGM_ERR_BAD_ARG, "batch_rollback: null argument");
-  launch_batch_rollback(bt->dev, d_steps, static_cast<hipStream_t>(hip_stream));
+  launch_batch_rollback(bt->dev, bt->v->dv, d_steps, pair_threshold(), static_cast<hipStream_t>(hip_stream));
   HIP_OK(hipGetLastError());
   return XGM_OK;
   API_END
@@ -1369,7 +1376,7 @@ int xgm_batch_set_row(xgm_batch* bt, int32_t row, const xgm_matcher* m, void* hi
   HIP_OK(hipMemcpy(bt->dev.head + row, &next, 4, hipMemcpyHostToDevice));
   HIP_OK(hipMemcpy(bt->dev.older + row, &older, 4, hipMemcpyHostToDevice));
   HIP_OK(hipMemcpy(bt->dev.status + row, &ok, 4, hipMemcpyHostToDevice));
-  launch_batch_plan(bt->dev, stream);
+  launch_batch_plan(bt->dev, bt->v->dv, pair_threshold(), stream);
   HIP_OK(hipGetLastError());
   return XGM_OK;
   API_END
@@ -1384,7 +1391,7 @@ static int batch_fill_impl(xgm_batch* bt, int32_t* d_bitmask, void* hip_stream, 
   const DevBatch& d = bt->dev;
   launch_fill(d.rows, d.hdrs, d.frames, d.plan, (int32_t)d.plan_cap, bt->v->dv, reinterpret_cast<uint32_t*>(d_bitmask), log, seq,
               nullptr, static_cast<hipStream_t>(hip_stream), fused ? fused->d_logits : nullptr, fused ? fused->esize : 0,
-              fused ? fused->neg_inf : 0u, fused ? fused->V_logits : 0, fused ? fused->row_stride : 0, C.pair_min_entries);
+              fused ? fused->neg_inf : 0u, fused ? fused->V_logits : 0, fused ? fused->row_stride : 0, C.pair_min_entries, d.pair);
   HIP_OK(hipGetLastError());
   C.last_slot = -1;
   C.last_batch = bt;

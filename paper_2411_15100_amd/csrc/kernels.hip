@@ -527,6 +527,30 @@ struct FillShared {
   uint32_t queue_n;
 };
 
+// The two-byte table of a stack without its top frame, into LDS (all threads of
+// the workgroup call this; it ends with a barrier): one lane per first byte
+// that the stack can consume at all (`first_ok`, 256 bits) runs an enumerating
+// walk of that byte from `below` (the node under the top frame; `depth` counts
+// the top frame) and collects the bytes that can follow it.  A walk over the
+// limits leaves its row all ones: the decision then falls to the token walks.
+template <int kThreads, class Tab, class Live>
+__device__ __forceinline__ void build_pair_table(const Tab& T, uint32_t* pair, const uint32_t* first_ok, uint32_t below,
+                                                 const Live& live, uint32_t depth, const uint32_t* node_first,
+                                                 const DevVocab& voc) {
+  const uint32_t tid = threadIdx.x;
+  for (uint32_t k = tid; k < kPairWords; k += kThreads) pair[k] = 0u;
+  __syncthreads();
+  if (tid < 256u && ((first_ok[tid >> 5] >> (tid & 31u)) & 1u)) {
+    LdsSetAcc acc{pair + tid * 8u};
+    const CollectNextBytes<Tab, LdsSetAcc> collect{&T, node_first, &acc};
+    const int res = walk_token<false>(T, make_uint4(tid, 0u, 0u, 1u << 24), voc.bytes, 1, below, live, depth - 1,
+                                      (uint32_t*)nullptr, (const uint32_t*)nullptr, 0, (uint32_t*)nullptr, collect);
+    if (res == kOverflow)
+      for (uint32_t w = 0; w < 8u; ++w) pair[tid * 8u + w] = 0xFFFFFFFFu;
+  }
+  __syncthreads();
+}
+
 // the header of one stack and its list offsets for chunks c0 .. c1 -> LDS (a barrier must follow)
 __device__ __forceinline__ void stage_stack_header(FillShared& sm, const XGM_GLOBAL uint32_t* sh, int32_t c0, int32_t c1) {
   const uint32_t tid = threadIdx.x;
@@ -541,7 +565,8 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
                                            const XGM_GLOBAL uint32_t* __restrict__ stack_hdrs,
                                            const XGM_GLOBAL uint16_t* __restrict__ frames, const DevVocab& voc,
                                            OverflowLog* log, uint32_t seq, unsigned long long& my_steps,
-                                           const uint32_t pair_min_entries) {
+                                           const uint32_t pair_min_entries,
+                                           const XGM_GLOBAL uint32_t* __restrict__ pair_tables) {
   const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
   const XGM_GLOBAL uint32_t* unc_list = (const XGM_GLOBAL uint32_t*)rd.unc_list;
@@ -564,19 +589,16 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
     live.lo = frames_in_lds ? 0u : 0xFFFFFFFFu;
     const uint32_t below = depth >= 2 ? live[depth - 2] : 0u;
     // the two-byte table of the stack below the top frame
-    const bool use_pair = depth >= 2 && sm.off[c1 - c0] - sm.off[0] >= pair_min_entries;
+    const bool have_table = pair_tables != nullptr && ((rd.pair_mask >> s) & 1u);  // computed ahead of this launch
+    const bool use_pair = depth >= 2 && (have_table || sm.off[c1 - c0] - sm.off[0] >= pair_min_entries);
     if (use_pair) {
-      for (uint32_t k = tid; k < 256u * 8u; k += kFillThreads) sm.pair[k] = 0u;
-      __syncthreads();
-      if (tid < 256u && ((first_ok[8 + (tid >> 5)] >> (tid & 31u)) & 1u)) {
-        LdsSetAcc acc{sm.pair + tid * 8u};
-        const CollectNextBytes<Tab, LdsSetAcc> collect{&T, node_first, &acc};
-        const int res = walk_token<false>(T, make_uint4(tid, 0u, 0u, 1u << 24), voc.bytes, 1, below, live, depth - 1,
-                                          (uint32_t*)nullptr, (const uint32_t*)nullptr, 0, (uint32_t*)nullptr, collect);
-        if (res == kOverflow)  // leave the decision to the walks
-          for (uint32_t w = 0; w < 8u; ++w) sm.pair[tid * 8u + w] = 0xFFFFFFFFu;
+      if (have_table) {
+        const XGM_GLOBAL uint32_t* table = pair_tables + ((size_t)b * kBatchMaxStacks + s) * kPairWords;
+        for (uint32_t k = tid; k < kPairWords; k += kFillThreads) sm.pair[k] = table[k];
+        __syncthreads();
+      } else {
+        build_pair_table<kFillThreads>(T, sm.pair, sm.hdr + kStackHdrBelow, below, live, depth, node_first, voc);
       }
-      __syncthreads();
     }
     // rounds of chunks whose lists together fit the queue (one chunk always fits)
     for (int32_t ca = c0; ca < c1;) {
@@ -683,6 +705,7 @@ struct FusedApply {
   int32_t V_logits;
   uint32_t neg_inf;
   uint32_t pair_min_entries;  // (rides along) lists shorter than this are filtered on one byte only
+  const uint32_t* pair_tables;  // (rides along) DevBatch::pair, or null
 };
 
 template <bool COUNT, int APPLY>
@@ -732,10 +755,11 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   if (has_cache) {
     if (small_sections_staged(rd.tab))
       fill_lists<COUNT, (APPLY != 0)>(LdsTabT<true>(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs,
-                                      frames, voc, log, seq, my_steps, fa.pair_min_entries);
+                                      frames, voc, log, seq, my_steps, fa.pair_min_entries,
+                                      (const XGM_GLOBAL uint32_t*)fa.pair_tables);
     else
       fill_lists<COUNT, (APPLY != 0)>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc,
-                                      log, seq, my_steps, fa.pair_min_entries);
+                                      log, seq, my_steps, fa.pair_min_entries, (const XGM_GLOBAL uint32_t*)fa.pair_tables);
   }
   if (rd.flags & 1u) {
     for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
@@ -953,7 +977,7 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
     r.flags = m.flags & 1u;
     r.frame_begin = fb;
     r.n_frames = m.n_frames;
-    r.pad = 0u;
+    r.pair_mask = 0u;
     bt.rows[b] = r;
     bt.head[b] = next;
     const int32_t o = bt.older[b] + 1;
@@ -977,6 +1001,7 @@ __global__ void batch_rollback_kernel(DevBatch bt, const int32_t* __restrict__ s
   r.n_stacks = m.n_stacks;
   r.n_frames = m.n_frames;
   r.flags = m.flags & 1u;
+  r.pair_mask = 0u;
   bt.rows[b] = r;
   bt.head[b] = head;
   bt.older[b] -= k;
@@ -1027,6 +1052,53 @@ __global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
   if (tid < (uint32_t)bt.B && first + (uint32_t)(k + plan_min_blocks(bt.n_chunk)) <= bt.plan_cap)
     plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; }, bt.plan + first);
   for (uint32_t j = n_blocks + tid; j < bt.plan_cap; j += kPlanThreads) bt.plan[j] = FillBlock{kNoRow, 0u};
+}
+
+// Ahead of the next fill: the two-byte tables (see build_pair_table) of the
+// stacks of rows whose state has changed, for stacks whose lists are long
+// enough to make the fill kernel want one.  One workgroup per row; a row that
+// has been examined since its last change is skipped.
+constexpr int kPairThreads = 256;
+__global__ __launch_bounds__(kPairThreads) void batch_pair_kernel(DevBatch bt, DevVocab voc, uint32_t pair_min_entries) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ uint32_t pair[kPairWords];
+  __shared__ uint16_t live_lds[kBatchMaxDepth];
+  const uint32_t tid = threadIdx.x;
+  const int32_t b = blockIdx.x;
+  const RowDesc rd = bt.rows[b];
+  if (rd.pair_mask & 0x80000000u) return;
+  const uint32_t hdr_stride = kStackHdrWords + (uint32_t)bt.n_chunk + 1u;
+  uint32_t need = 0u;
+  for (uint32_t s = 0; s < rd.n_stacks; ++s) {
+    const uint32_t* h = bt.hdrs + (size_t)(rd.stack_begin + s) * hdr_stride;
+    if (h[kStackHdrDepth] >= 2u && h[kStackHdrWords + bt.n_chunk] - h[kStackHdrWords] >= pair_min_entries) need |= 1u << s;
+  }
+  if (need) {
+    stage_tables(rd.tab, smem, kPairThreads);
+    __syncthreads();
+    const uint32_t* node_first = reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(rd.tab.image) + rd.tab.off_first);
+    auto body = [&](const auto& T) {
+      for (uint32_t s = 0; s < rd.n_stacks; ++s) {
+        if (!((need >> s) & 1u)) continue;
+        const uint32_t* h = bt.hdrs + (size_t)(rd.stack_begin + s) * hdr_stride;
+        const uint32_t depth = h[kStackHdrDepth];
+        const uint16_t* fr = bt.frames + h[kStackHdrFrames];
+        for (uint32_t k = tid; k < depth; k += kPairThreads) live_lds[k] = fr[k];
+        __syncthreads();
+        LiveView live;
+        live.lds = (const XGM_LDS uint16_t*)live_lds;
+        live.glob = (const XGM_GLOBAL uint16_t*)fr;
+        live.lo = 0u;
+        build_pair_table<kPairThreads>(T, pair, h + kStackHdrBelow, (uint32_t)live_lds[depth - 2], live, depth, node_first, voc);
+        uint32_t* out = bt.pair + ((size_t)b * kBatchMaxStacks + s) * kPairWords;
+        for (uint32_t k = tid; k < kPairWords; k += kPairThreads) out[k] = pair[k];
+        __syncthreads();
+      }
+    };
+    if (small_sections_staged(rd.tab)) body(LdsTabT<true>(rd.tab, smem));
+    else body(LdsTab(rd.tab, smem));
+  }
+  if (tid == 0) bt.rows[b].pair_mask = 0x80000000u | need;
 }
 
 // ---------------------------------------------------------------- kernel (c)
@@ -1149,10 +1221,11 @@ void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t 
 void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,
                  const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log,
                  uint32_t seq, unsigned long long* step_counter, hipStream_t stream, void* logits, int elem_size,
-                 uint32_t neg_inf, int32_t V_logits, int64_t row_stride, uint32_t pair_min_entries) {
+                 uint32_t neg_inf, int32_t V_logits, int64_t row_stride, uint32_t pair_min_entries,
+                 const uint32_t* pair_tables) {
   if (n_blocks <= 0) return;
   const dim3 grid(n_blocks);
-  const FusedApply fa{static_cast<unsigned char*>(logits), row_stride, V_logits, neg_inf, pair_min_entries};
+  const FusedApply fa{static_cast<unsigned char*>(logits), row_stride, V_logits, neg_inf, pair_min_entries, pair_tables};
   if (logits && elem_size == 2)
     hipLaunchKernelGGL((fill_kernel<false, 2>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
                        plan, voc, out, log, seq, step_counter, fa);
@@ -1167,18 +1240,21 @@ void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t
                        plan, voc, out, log, seq, step_counter, fa);
 }
 
-void launch_batch_plan(const DevBatch& bt, hipStream_t stream) {
+void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries, hipStream_t stream) {
   hipLaunchKernelGGL(batch_plan_kernel, dim3(1), dim3(kPlanThreads), (size_t)bt.B * (bt.n_chunk + 1) * 4, stream, bt);
+  hipLaunchKernelGGL(batch_pair_kernel, dim3(bt.B), dim3(kPairThreads), kFillLdsBudget, stream, bt, voc, pair_min_entries);
 }
 
-void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, hipStream_t stream) {
+void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, uint32_t pair_min_entries,
+                         hipStream_t stream) {
   hipLaunchKernelGGL(batch_accept_kernel, dim3(bt.B), dim3(kAcceptThreads), 0, stream, bt, voc, d_tokens);
-  launch_batch_plan(bt, stream);
+  launch_batch_plan(bt, voc, pair_min_entries, stream);
 }
 
-void launch_batch_rollback(const DevBatch& bt, const int32_t* d_steps, hipStream_t stream) {
+void launch_batch_rollback(const DevBatch& bt, const DevVocab& voc, const int32_t* d_steps, uint32_t pair_min_entries,
+                           hipStream_t stream) {
   hipLaunchKernelGGL(batch_rollback_kernel, dim3((bt.B + 255) / 256), dim3(256), 0, stream, bt, d_steps);
-  launch_batch_plan(bt, stream);
+  launch_batch_plan(bt, voc, pair_min_entries, stream);
 }
 
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,

@@ -143,7 +143,8 @@ struct RowDesc {
   uint32_t flags;            // bit 0: the text so far is a complete sentence
   uint32_t frame_begin;      // the request's frames: [frame_begin, frame_begin + n_frames) of the frame array,
   uint32_t n_frames;         // stack after stack
-  uint32_t pad;
+  uint32_t pair_mask;        // device-resident states only: bit s = the two-byte table of stack s has been computed
+                             // ahead of the fill (DevBatch::pair); bit 31 = the row has been examined for that
 };
 // A stack header is kStackHdrWords + n_chunk + 1 uint32 words:
 //   [kStackHdrTop] top node, [kStackHdrDepth] number of frames,
@@ -184,6 +185,7 @@ constexpr uint32_t kBatchMaxDepth = 128;      // frames per stack
 constexpr uint32_t kBatchMaxCandidates = 32;  // stacks a token may end in before duplicates are removed
 constexpr uint32_t kBatchRowFrames = kBatchMaxStacks * kBatchMaxDepth;
 constexpr uint32_t kBatchMaxRows = 1024;
+constexpr uint32_t kPairWords = 256 * 8;    // 256 x 256 bits: which byte can follow which
 struct SlotMeta {
   uint32_t n_stacks, n_frames;
   uint32_t flags;  // bit 0: the text so far is a complete sentence; bit 1: the stop token has been accepted
@@ -201,6 +203,7 @@ struct DevBatch {
   int32_t* status;        // [B] result of the last accept / rollback per row (XGM_OK or an error code)
   FillBlock* plan;        // [plan_cap] workgroups of the next fill, padded with kNoRow
   uint32_t plan_cap;
+  uint32_t* pair;         // [B][kBatchMaxStacks][kPairWords] two-byte tables of the current states' stacks
 };
 // workgroups a plan can have at most (see plan.hpp)
 inline uint32_t batch_plan_cap(int32_t B, int32_t n_chunk, int32_t budget) {
@@ -251,13 +254,17 @@ void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t
                  const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log,
                  uint32_t seq, unsigned long long* step_counter, hipStream_t stream, void* logits = nullptr,
                  int elem_size = 0, uint32_t neg_inf = 0, int32_t V_logits = 0, int64_t row_stride = 0,
-                 uint32_t pair_min_entries = kFillPairMinEntries);
+                 uint32_t pair_min_entries = kFillPairMinEntries, const uint32_t* pair_tables = nullptr);
 // device-resident states: move every row on by its token (ids < 0 leave a row alone), then plan the next fill
-void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, hipStream_t stream);
+// (the plan step also computes, ahead of the fill, the two-byte tables of stacks whose lists have at least
+// pair_min_entries entries)
+void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, uint32_t pair_min_entries,
+                         hipStream_t stream);
 // go back d_steps[b] tokens in every row (<= 0 leaves a row alone), then plan
-void launch_batch_rollback(const DevBatch& bt, const int32_t* d_steps, hipStream_t stream);
+void launch_batch_rollback(const DevBatch& bt, const DevVocab& voc, const int32_t* d_steps, uint32_t pair_min_entries,
+                           hipStream_t stream);
 // plan only (after the host has written states)
-void launch_batch_plan(const DevBatch& bt, hipStream_t stream);
+void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries, hipStream_t stream);
 // (c) apply; returns false if the buffer layout needs the element-wise kernel
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,
                   const uint32_t* bitmask, int32_t V_mask, const int32_t* row_index, int32_t n_rows,

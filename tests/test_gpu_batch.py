@@ -34,6 +34,15 @@ def wl():
     return workloads
 
 
+@pytest.fixture(params=["default", "two-byte tables everywhere"])
+def pair_table(request, xgm):
+    """Runs a test twice: with the default threshold for the two-byte tables (at these sizes the
+    fill kernel rarely wants one), and with tables computed ahead of every fill for every stack."""
+    old = xgm.debug_set_fill_pair_threshold(1 if request.param != "default" else -1)
+    yield request.param
+    xgm.debug_set_fill_pair_threshold(old)
+
+
 def _stream():
     return int(torch.cuda.current_stream().cuda_stream)
 
@@ -84,7 +93,7 @@ MIXED = [(si.JSON_GRAMMAR, "root"), (si.CSQL_GRAMMAR, "root"), (si.XML_GRAMMAR, 
          (si.JSON_GRAMMAR, "root"), (si.make_schema_grammar(2, string_heavy=True), "root")]
 
 
-def test_device_accept_follows_host_matchers_and_oracle(xgm, wl):
+def test_device_accept_follows_host_matchers_and_oracle(xgm, wl, pair_table):
     vocab = si.make_vocab("bpe", 32000, 0)
     rows = _Rows(xgm, wl, MIXED, vocab, history=4)
     info = wl.TokenInfo(vocab)
@@ -151,7 +160,7 @@ def test_device_accept_follows_host_matchers_and_oracle(xgm, wl):
     assert n_ok > 250 and n_rejected > 20 and n_skipped > 10 and n_host < 10
 
 
-def test_rollback_returns_to_earlier_states(xgm, wl):
+def test_rollback_returns_to_earlier_states(xgm, wl, pair_table):
     vocab = si.make_vocab("bpe", 32000, 0)
     specs = [(si.JSON_GRAMMAR, "root"), (si.make_schema_grammar(3, string_heavy=True), "root"),
              (si.CSQL_GRAMMAR, "root"), (si.JSON_GRAMMAR, "root")]
@@ -237,7 +246,7 @@ def test_batch_fused_fill_and_apply(xgm, wl, dtype_name):
         rows.batch.fill_and_apply(rows.d_dev.data_ptr(), logits.data_ptr(), code, 100, logits.stride(0), _stream())
 
 
-def test_device_limits_are_reported_and_the_host_takes_over(xgm, wl):
+def test_device_limits_are_reported_and_the_host_takes_over(xgm, wl, pair_table):
     toks = [b"x", b"p", b"q", b"xx", b"[", b"]", b"1", b","] + [b""]
     V = len(toks)
 
