@@ -299,8 +299,9 @@ int64_t xgm_overflow_total(void);
  * states per row in HBM).  The sampled token ids never leave the device: a
  * kernel moves every row's stacks on by its token and writes the row's next
  * state in the layout the fill kernel reads, another plans the workgroups of
- * the next fill; a fill is then a single launch without any host packing or
- * upload.  Going back k tokens (speculative decoding, section 3.3) re-points a
+ * the next fill, a third computes the per-stack lookup tables that the fill
+ * kernel would otherwise build in every workgroup; a fill is then a single
+ * launch without any host packing or upload.  Going back k tokens (speculative decoding, section 3.3) re-points a
  * row k states back.  Calls on one batch must be ordered by the caller (one
  * stream, or events).
  *
