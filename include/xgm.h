@@ -331,8 +331,17 @@ int xgm_batch_accept_tokens(xgm_batch* bt, const int32_t* d_token_ids, void* hip
  * tokens (<= 0: stays).  More than the row still holds: XGM_ERR_BAD_ARG in its
  * status, state unchanged. */
 int xgm_batch_rollback(xgm_batch* bt, const int32_t* d_steps, void* hip_stream);
+/* Asynchronous.  d_src_rows: [B] device int32; row b continues from the current
+ * state of row d_src_rows[b] (section 3.3: one prefix continued in several
+ * ways, as in tree decoding); negative or b itself: the row stays.  All rows
+ * take the states as they were before the call.  The new state counts as one
+ * accepted token for rollback.  Both rows must use the same mask cache
+ * (XGM_ERR_BAD_ARG in the row's status otherwise, also for a row index
+ * >= B); the batch must have been created with history >= 1 (XGM_ERR_BAD_ARG
+ * from the call otherwise). */
+int xgm_batch_fork(xgm_batch* bt, const int32_t* d_src_rows, void* hip_stream);
 /* Synchronises hip_stream and copies the per-row status of the last accept /
- * rollback into h_status[B] (host).  Returns the number of rows whose status
+ * rollback / fork into h_status[B] (host).  Returns the number of rows whose status
  * is not XGM_OK, or a negative status of the call itself. */
 int xgm_batch_status(xgm_batch* bt, int32_t* h_status, void* hip_stream);
 /* The way through the host for a row that hit a device limit (both
@@ -349,6 +358,12 @@ int xgm_batch_set_row(xgm_batch* bt, int32_t row, const xgm_matcher* m, void* hi
 int xgm_batch_fill_next_token_bitmask(xgm_batch* bt, int32_t* d_bitmask, void* hip_stream);
 int xgm_batch_fill_and_apply(xgm_batch* bt, int32_t* d_bitmask, void* d_logits, xgm_dtype dt, int32_t V_logits,
                              int64_t row_stride_elems, void* hip_stream);
+/* The plan of the next fill as the device made it (synchronises hip_stream):
+ * triples (row, first chunk, end chunk) of its workgroups in launch order,
+ * idle entries left out; h_out holds cap triples.  *h_budget (may be NULL)
+ * receives the number of workgroups the device holds at once, which the plan
+ * was made for.  Returns the number of workgroups or a negative status. */
+int32_t xgm_debug_batch_plan(xgm_batch* bt, uint32_t* h_out, int32_t cap, int32_t* h_budget, void* hip_stream);
 /* For tests without a device: accept a token with the routine the device uses
  * (a depth-first walk over the flattened tables that writes out every stack
  * the token can end in) instead of the host engine.  Same results and errors

@@ -74,12 +74,14 @@ SIGNATURES = {
     "xgm_batch_size": (_i32, [_vp]),
     "xgm_batch_accept_tokens": (_i32, [_vp, _vp, _vp]),
     "xgm_batch_rollback": (_i32, [_vp, _vp, _vp]),
+    "xgm_batch_fork": (_i32, [_vp, _vp, _vp]),
     "xgm_batch_status": (_i32, [_vp, _vp, _vp]),
     "xgm_batch_get_row": (_i32, [_vp, _i32, _vp, _vp]),
     "xgm_batch_set_row": (_i32, [_vp, _i32, _vp, _vp]),
     "xgm_batch_fill_next_token_bitmask": (_i32, [_vp, _vp, _vp]),
     "xgm_batch_fill_and_apply": (_i32, [_vp, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
     "xgm_debug_matcher_accept_token_walk": (_i32, [_vp, _i32]),
+    "xgm_debug_batch_plan": (_i32, [_vp, _vp, _i32, _vp, _vp]),
     "xgm_fill_overflow_fixup": (_i32, [_vp]),
     "xgm_overflow_total": (_i64, []),
     "xgm_apply_token_bitmask_inplace": (_i32, [_vp, _i32, _i32, _i32, _i64, _vp, _i32, _vp, _i32, _vp]),
@@ -380,6 +382,9 @@ class DeviceBatch:
     def rollback(self, d_steps: int, stream: int = 0):
         _check(load_library().xgm_batch_rollback(self._h, ctypes.c_void_p(d_steps), ctypes.c_void_p(stream)))
 
+    def fork(self, d_src_rows: int, stream: int = 0):
+        _check(load_library().xgm_batch_fork(self._h, ctypes.c_void_p(d_src_rows), ctypes.c_void_p(stream)))
+
     def status(self, stream: int = 0) -> np.ndarray:
         out = np.zeros(self.size, dtype=np.int32)
         _check(load_library().xgm_batch_status(self._h, out.ctypes.data, ctypes.c_void_p(stream)))
@@ -390,6 +395,14 @@ class DeviceBatch:
 
     def set_row(self, row: int, matcher: "Matcher", stream: int = 0):
         _check(load_library().xgm_batch_set_row(self._h, int(row), matcher._h, ctypes.c_void_p(stream)))
+
+    def debug_plan(self, stream: int = 0):
+        """(int array [n, 3] of (row, c0, c1) as planned on the device, budget)."""
+        out = np.zeros((1 << 16, 3), dtype=np.uint32)
+        budget = ctypes.c_int32(0)
+        n = _check(load_library().xgm_debug_batch_plan(self._h, out.ctypes.data, out.shape[0], ctypes.byref(budget),
+                                                       ctypes.c_void_p(stream)))
+        return out[:n].astype(np.int64), int(budget.value)
 
     def fill_next_token_bitmask(self, d_bitmask: int, stream: int = 0):
         _check(load_library().xgm_batch_fill_next_token_bitmask(self._h, ctypes.c_void_p(d_bitmask),

@@ -1335,6 +1335,16 @@ int xgm_batch_rollback(xgm_batch* bt, const int32_t* d_steps, void* hip_stream) 
   API_END
 }
 
+int xgm_batch_fork(xgm_batch* bt, const int32_t* d_src_rows, void* hip_stream) {
+  API_BEGIN
+  if (!bt || !d_src_rows) return fail(XGM_ERR_BAD_ARG, "batch_fork: null argument");
+  if (bt->H < 2) return fail(XGM_ERR_BAD_ARG, "batch_fork: the batch was created without history (a forked state is written beside the current one)");
+  launch_batch_fork(bt->dev, bt->v->dv, d_src_rows, pair_threshold(), static_cast<hipStream_t>(hip_stream));
+  HIP_OK(hipGetLastError());
+  return XGM_OK;
+  API_END
+}
+
 int xgm_batch_status(xgm_batch* bt, int32_t* h_status, void* hip_stream) {
   API_BEGIN
   if (!bt || !h_status) return fail(XGM_ERR_BAD_ARG, "batch_status: null argument");
@@ -1379,6 +1389,26 @@ int xgm_batch_set_row(xgm_batch* bt, int32_t row, const xgm_matcher* m, void* hi
   launch_batch_plan(bt->dev, bt->v->dv, pair_threshold(), stream);
   HIP_OK(hipGetLastError());
   return XGM_OK;
+  API_END
+}
+
+int32_t xgm_debug_batch_plan(xgm_batch* bt, uint32_t* h_out, int32_t cap, int32_t* h_budget, void* hip_stream) {
+  API_BEGIN
+  if (!bt || !h_out || cap < 0) return fail(XGM_ERR_BAD_ARG, "batch_plan: bad argument");
+  HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+  std::vector<FillBlock> plan(bt->dev.plan_cap);
+  HIP_OK(hipMemcpy(plan.data(), bt->dev.plan, plan.size() * sizeof(FillBlock), hipMemcpyDeviceToHost));
+  int32_t n = 0;
+  for (const FillBlock& f : plan) {
+    if (f.row == kNoRow) continue;
+    if (n >= cap) return fail(XGM_ERR_BAD_ARG, "batch_plan: the output array is too small");
+    h_out[3 * n] = f.row;
+    h_out[3 * n + 1] = f.c0c1 & 0xFFFFu;
+    h_out[3 * n + 2] = f.c0c1 >> 16;
+    ++n;
+  }
+  if (h_budget) *h_budget = bt->dev.budget;
+  return n;
   API_END
 }
 

@@ -1008,6 +1008,51 @@ __global__ void batch_rollback_kernel(DevBatch bt, const int32_t* __restrict__ s
   bt.status[b] = 0;
 }
 
+// Forking (section 3.3: one state may be continued in several ways, as in tree
+// decoding): row b takes over the current state of row src[b] as its next
+// state.  All rows read the states as they were before the call: the first
+// kernel only writes next slots, the second moves the rows over.
+__global__ __launch_bounds__(256) void batch_fork_copy_kernel(DevBatch bt, const int32_t* __restrict__ src_rows) {
+  const int32_t b = blockIdx.x;
+  const int32_t src = src_rows[b];
+  if (src < 0 || src == b) return;
+  if (src >= bt.B || bt.cache[b].acc != bt.cache[src].acc) return;  // reported by the second kernel
+  const uint32_t tid = threadIdx.x;
+  const uint32_t hdr_stride = kStackHdrWords + (uint32_t)bt.n_chunk + 1u;
+  const uint32_t from = (uint32_t)src * bt.H + bt.head[src], to = (uint32_t)b * bt.H + (bt.head[b] + 1) % bt.H;
+  const SlotMeta m = bt.meta[from];
+  const uint32_t* sh = bt.hdrs + (size_t)from * kBatchMaxStacks * hdr_stride;
+  uint32_t* dh = bt.hdrs + (size_t)to * kBatchMaxStacks * hdr_stride;
+  for (uint32_t k = tid; k < m.n_stacks * hdr_stride; k += 256u) {
+    uint32_t v = sh[k];
+    if (k % hdr_stride == kStackHdrFrames) v = v - from * kBatchRowFrames + to * kBatchRowFrames;
+    dh[k] = v;
+  }
+  for (uint32_t k = tid; k < m.n_frames; k += 256u) bt.frames[(size_t)to * kBatchRowFrames + k] = bt.frames[(size_t)from * kBatchRowFrames + k];
+  if (tid == 0) bt.meta[to] = m;
+}
+__global__ void batch_fork_commit_kernel(DevBatch bt, const int32_t* __restrict__ src_rows) {
+  const int32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= bt.B) return;
+  const int32_t src = src_rows[b];
+  if (src < 0 || src == b) return;
+  if (src >= bt.B || bt.cache[b].acc != bt.cache[src].acc) { bt.status[b] = kErrBadArg; return; }
+  const int32_t next = (bt.head[b] + 1) % bt.H;
+  const SlotMeta m = bt.meta[(size_t)b * bt.H + next];
+  RowDesc r = bt.rows[b];
+  r.stack_begin = ((uint32_t)b * bt.H + next) * kBatchMaxStacks;
+  r.frame_begin = ((uint32_t)b * bt.H + next) * kBatchRowFrames;
+  r.n_stacks = m.n_stacks;
+  r.n_frames = m.n_frames;
+  r.flags = m.flags & 1u;
+  r.pair_mask = 0u;
+  bt.rows[b] = r;
+  bt.head[b] = next;
+  const int32_t o = bt.older[b] + 1;
+  bt.older[b] = o < bt.H - 1 ? o : bt.H - 1;
+  bt.status[b] = 0;
+}
+
 // The plan of the next fill for the batch's current states (plan.hpp), by one
 // workgroup: the per-(row, chunk) running entry counts go to LDS, then one
 // thread per row cuts its row.
@@ -1248,6 +1293,13 @@ void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_mi
 void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, uint32_t pair_min_entries,
                          hipStream_t stream) {
   hipLaunchKernelGGL(batch_accept_kernel, dim3(bt.B), dim3(kAcceptThreads), 0, stream, bt, voc, d_tokens);
+  launch_batch_plan(bt, voc, pair_min_entries, stream);
+}
+
+void launch_batch_fork(const DevBatch& bt, const DevVocab& voc, const int32_t* d_src_rows, uint32_t pair_min_entries,
+                       hipStream_t stream) {
+  hipLaunchKernelGGL(batch_fork_copy_kernel, dim3(bt.B), dim3(256), 0, stream, bt, d_src_rows);
+  hipLaunchKernelGGL(batch_fork_commit_kernel, dim3((bt.B + 255) / 256), dim3(256), 0, stream, bt, d_src_rows);
   launch_batch_plan(bt, voc, pair_min_entries, stream);
 }
 

@@ -263,6 +263,9 @@ void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t*
 // go back d_steps[b] tokens in every row (<= 0 leaves a row alone), then plan
 void launch_batch_rollback(const DevBatch& bt, const DevVocab& voc, const int32_t* d_steps, uint32_t pair_min_entries,
                            hipStream_t stream);
+// row b continues from the current state of row d_src_rows[b] (< 0 or b itself: stays), then plan
+void launch_batch_fork(const DevBatch& bt, const DevVocab& voc, const int32_t* d_src_rows, uint32_t pair_min_entries,
+                       hipStream_t stream);
 // plan only (after the host has written states)
 void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries, hipStream_t stream);
 // (c) apply; returns false if the buffer layout needs the element-wise kernel

@@ -421,3 +421,96 @@ def test_stop_token_and_termination_on_the_device(xgm, wl):
     expect()
     batch.get_row(1, s, _stream())
     assert not s.is_terminated() and _stacks(s) == _stacks(ms[1])
+
+
+def test_device_plan_equals_the_host_plan(xgm, wl):
+    """The plan kernel against the host planner (whose invariants the CPU suite checks) on the
+    same list lengths, after creation, after a step of all rows, and after a rollback."""
+    vocab = si.make_vocab("bpe", 151936, 0)
+    specs = [(si.make_schema_grammar(s, string_heavy=True), "root") for s in range(6)] + [(si.JSON_GRAMMAR, "root")] * 2
+    rows = _Rows(xgm, wl, specs, vocab, history=2)
+    info = wl.TokenInfo(vocab)
+    rng = np.random.Generator(np.random.PCG64(5))
+    n_chunk = (xgm.bitmask_words(vocab.size) + 127) // 128
+
+    def check():
+        plan, budget = rows.batch.debug_plan(_stream())
+        upto = np.zeros((rows.B, n_chunk + 1), dtype=np.uint32)
+        for b, (m, c) in enumerate(zip(rows.ms, rows.caches)):
+            if m.is_terminated():
+                continue
+            for s in range(m.num_stacks()):
+                # list lengths per chunk of 4096 ids, from the node's context-dependent bitset
+                _, unc = c.copy_node_bits(m.stack(s)[-1])
+                bits = np.unpackbits(unc.view(np.uint8), bitorder="little")
+                per_chunk = np.add.reduceat(bits, np.arange(0, bits.size, 4096))[:n_chunk]
+                upto[b, 1:] += np.cumsum(per_chunk).astype(np.uint32)
+        want = xgm.debug_plan_workgroups(upto, budget)
+        assert np.array_equal(plan, want)
+        return len(plan)
+
+    n0 = check()
+    for step in range(6):
+        got, host = rows.masks(xgm)
+        assert np.array_equal(got, host)
+        allowed = wl.unpack_rows(got, vocab.size)
+        allowed[:, vocab.stop_ids] = False
+        picks = si.pick_tokens(rng, allowed, info.structural, info.is_stop, 0.35)
+        rows.batch.accept_tokens(_dev(picks).data_ptr(), _stream())
+        assert not rows.batch.status(_stream()).any()
+        for b in range(rows.B):
+            rows.ms[b].accept_token(int(picks[b]))
+        n1 = check()
+    say(f"  plans of {n0} .. {n1} workgroups equal the host planner's")
+
+
+def test_fork_continues_one_state_in_several_rows(xgm, wl, pair_table):
+    vocab = si.make_vocab("bpe", 32000, 0)
+    gj = xgm.Grammar(si.JSON_GRAMMAR, "root")
+    xv = wl.make_xgm_vocab(vocab)
+    cj, cs = xgm.Cache(gj, xv), xgm.Cache(xgm.Grammar(si.make_schema_grammar(1), "root"), xv)
+    caches = [cj, cj, cj, cj, cs]
+    ogs = [oracle.Grammar(si.JSON_GRAMMAR, "root")] * 4 + [oracle.Grammar(si.make_schema_grammar(1), "root")]
+    texts = [b'{"a": [1, ', b'[true', b'"x', b'{', b'{']
+    ms = [xgm.Matcher(cache=c) for c in caches]
+    for m, t in zip(ms, texts):
+        m.accept_bytes(t)
+    batch = xgm.DeviceBatch(ms, history=3, stream=_stream())
+    W = xgm.bitmask_words(vocab.size)
+    d = torch.zeros((5, W), dtype=torch.int32, device="cuda")
+
+    def expect(texts_now):
+        batch.fill_next_token_bitmask(d.data_ptr(), _stream())
+        got = d.cpu().numpy()
+        for b, t in enumerate(texts_now):
+            om = oracle.EarleyMatcher(ogs[b])
+            assert om.advance(t)
+            assert np.array_equal(got[b], oracle.pack_bitmask(om.mask(vocab))), f"row {b}"
+            s = xgm.Matcher(cache=caches[b])
+            batch.get_row(b, s, _stream())
+            r = xgm.Matcher(cache=caches[b])
+            r.accept_bytes(t)
+            assert _stacks(s) == _stacks(r), f"row {b}"
+
+    expect(texts)
+    # rows 1 and 2 both continue row 0; row 0 continues row 2 as it was before the call; row 3 stays;
+    # row 4 has another grammar than row 0 and is refused; an index beyond the batch is refused too
+    batch.fork(_dev([2, 0, 0, -1, 0]).data_ptr(), _stream())
+    assert list(batch.status(_stream())) == [0, 0, 0, 0, -1]
+    now = [texts[2], texts[0], texts[0], texts[3], texts[4]]
+    expect(now)
+    batch.fork(_dev([-1, -1, -1, 7, -1]).data_ptr(), _stream())
+    assert list(batch.status(_stream())) == [0, 0, 0, -1, -1]
+    expect(now)
+    # forked rows go their own ways, and a fork can be taken back like a token
+    tok = {t: i for i, t in enumerate(vocab.tokens())}
+    batch.accept_tokens(_dev([tok[b'"'], tok[b'2'], tok[b'{'], -1, -1]).data_ptr(), _stream())
+    assert list(batch.status(_stream()))[:3] == [0, 0, 0]
+    expect([now[0] + b'"', now[1] + b'2', now[2] + b'{', now[3], now[4]])
+    batch.rollback(_dev([2, 1, 2, 0, 0]).data_ptr(), _stream())
+    assert list(batch.status(_stream()))[:3] == [0, 0, 0]
+    expect([texts[0], now[1], texts[2], now[3], now[4]])
+    # a batch without history has no room for a forked state
+    flat = xgm.DeviceBatch(ms[:2], history=0, stream=_stream())
+    with pytest.raises(xgm.XgmError):
+        flat.fork(_dev([1, -1]).data_ptr(), _stream())
