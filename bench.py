@@ -202,6 +202,7 @@ def main():
                  "traffic": TRAFFIC_FILL_BYTES, "bytes_per_launch": fill_bytes,
                  "list_entries_per_launch": float(np.mean(unc_tokens)),
                  "automaton_steps_per_launch": auto_steps,
+                 "automaton_steps_per_s": auto_steps / (fill_kernel_us * 1e-6),
                  "note": "latency-bound by nature: a few dependent memory rounds per workgroup and a tail of "
                          "token walks; the byte count is what the method must move, not what limits it"}
     roof_fill["frac"] = roof_fill["achieved"] / HBM_PEAK_GBS
@@ -211,11 +212,31 @@ def main():
     roof_step["frac"] = roof_step["achieved"] / HBM_PEAK_GBS
 
     # ---- cache build throughput (kernel a), generic JSON and the C/SQL-like grammar at V = 128256
+    def mean_steps_per_pair(g, toks, rng, n=6000):
+        """Automaton steps of the classifying walk on a seeded sample of (node, token) pairs (the same
+        walk compiled for the host); a walk that fails on its first byte counts as zero steps: the
+        kernel settles such a pair with its first-byte test, without walking."""
+        total = 0
+        nodes = rng.integers(0, g.num_nodes, size=n)
+        ids = rng.integers(0, len(toks), size=n)
+        for node, i in zip(nodes, ids):
+            t = toks[int(i)]
+            if not t:
+                continue
+            rc, steps = g.debug_walk_host([int(node)], t, True, with_steps=True)
+            total += 0 if (rc == 0 and steps <= 1) else steps
+        return total / n
+
     cache_build = None
     if not args.no_build_bench:
         v128 = si.make_vocab("bpe", 128256, 0)
         xv128 = wl.make_xgm_vocab(v128)
-        cache_build = {}
+        toks128 = v128.tokens()
+        lds_rate = xgm.debug_lds_lookup_rate(stream)
+        cache_build = {"lds_dependent_lookups_per_s": lds_rate,
+                       "note": "steps_per_s = pairs_per_s x the mean automaton steps per pair of a seeded sample; a "
+                               "step is 3 to 5 dependent table lookups (header, follow set, class, shape, target); "
+                               "the ceiling is a chain of dependent LDS reads with every wave slot busy"}
         for name, text in (("json", si.JSON_GRAMMAR), ("csql", si.CSQL_GRAMMAR)):
             g = xgm.Grammar(text, "root")
             best = whole = None
@@ -225,12 +246,21 @@ def main():
                 whole = c.build_seconds if whole is None else min(whole, c.build_seconds)
                 hostc = c.host_classified
                 del c
+            sps = mean_steps_per_pair(g, toks128, np.random.Generator(np.random.PCG64(11)))
             cache_build[name] = {"positions": g.num_nodes, "tokens": 128256, "classify_kernel_ms": best * 1e3,
-                                 "pairs_per_s": g.num_nodes * 128256 / best, "whole_build_ms": whole * 1e3,
+                                 "pairs_per_s": g.num_nodes * 128256 / best, "steps_per_pair": sps,
+                                 "steps_per_s": sps * g.num_nodes * 128256 / best,
+                                 "lookups_vs_ceiling": 4.0 * sps * g.num_nodes * 128256 / best / lds_rate,
+                                 "whole_build_ms": whole * 1e3,
                                  "pairs_per_s_whole_build": g.num_nodes * 128256 / whole,
                                  "host_classified_pairs": hostc}
+        toks_s = work.vocab.tokens()
+        sps = float(np.mean([mean_steps_per_pair(work.grammars[k], toks_s, np.random.Generator(np.random.PCG64(12 + k)), 1500)
+                             for k in (0, 31, 77, 127) if k < len(work.grammars)]))
+        pps = work.build_pairs / max(work.build_kernel_seconds, 1e-12)
         cache_build["serving_set_up"] = {"pairs": work.build_pairs, "kernel_s": work.build_kernel_seconds,
-                                         "pairs_per_s": work.build_pairs / max(work.build_kernel_seconds, 1e-12)}
+                                         "pairs_per_s": pps, "steps_per_pair": sps, "steps_per_s": sps * pps,
+                                         "lookups_vs_ceiling": 4.0 * sps * pps / lds_rate}
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu_baseline = None

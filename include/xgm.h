@@ -358,6 +358,12 @@ int xgm_batch_set_row(xgm_batch* bt, int32_t row, const xgm_matcher* m, void* hi
 int xgm_batch_fill_next_token_bitmask(xgm_batch* bt, int32_t* d_bitmask, void* hip_stream);
 int xgm_batch_fill_and_apply(xgm_batch* bt, int32_t* d_bitmask, void* d_logits, xgm_dtype dt, int32_t V_logits,
                              int64_t row_stride_elems, void* hip_stream);
+/* Measurement aid for the benchmark (synchronous): dependent 4-byte LDS reads
+ * per second of the whole device with two 1024-lane workgroups per compute
+ * unit, every lane following a chain through a 32 KB table.  The table
+ * lookups of the token walks (section 3.1, 3.3) are reads of this kind, each
+ * depending on the one before. */
+int xgm_debug_lds_lookup_rate(void* hip_stream, double* h_lookups_per_second);
 /* The plan of the next fill as the device made it (synchronises hip_stream):
  * triples (row, first chunk, end chunk) of its workgroups in launch order,
  * idle entries left out; h_out holds cap triples.  *h_budget (may be NULL)

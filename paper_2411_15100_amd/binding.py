@@ -82,6 +82,7 @@ SIGNATURES = {
     "xgm_batch_fill_and_apply": (_i32, [_vp, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
     "xgm_debug_matcher_accept_token_walk": (_i32, [_vp, _i32]),
     "xgm_debug_batch_plan": (_i32, [_vp, _vp, _i32, _vp, _vp]),
+    "xgm_debug_lds_lookup_rate": (_i32, [_vp, _vp]),
     "xgm_fill_overflow_fixup": (_i32, [_vp]),
     "xgm_overflow_total": (_i64, []),
     "xgm_apply_token_bitmask_inplace": (_i32, [_vp, _i32, _i32, _i32, _i64, _vp, _i32, _vp, _i32, _vp]),
@@ -440,6 +441,13 @@ def debug_plan_workgroups(upto: np.ndarray, budget: int) -> np.ndarray:
     n = _check(load_library().xgm_debug_plan_workgroups(upto.ctypes.data, B, nc1 - 1, int(budget), out.ctypes.data,
                                                         out.shape[0]))
     return out[:n].astype(np.int64)
+
+
+def debug_lds_lookup_rate(stream: int = 0) -> float:
+    """Dependent LDS reads per second of the whole device (measurement aid)."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().xgm_debug_lds_lookup_rate(ctypes.c_void_p(stream), ctypes.byref(out)))
+    return float(out.value)
 
 
 def debug_set_fill_pair_threshold(entries: int) -> int:

@@ -1392,6 +1392,43 @@ int xgm_batch_set_row(xgm_batch* bt, int32_t row, const xgm_matcher* m, void* hi
   API_END
 }
 
+int xgm_debug_lds_lookup_rate(void* hip_stream, double* h_lookups_per_second) {
+  API_BEGIN
+  if (!h_lookups_per_second) return fail(XGM_ERR_BAD_ARG, "lds_lookup_rate: null output");
+  require_device();
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int dev = 0, cus = 0;
+  HIP_OK(hipGetDevice(&dev));
+  HIP_OK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const int32_t n_blocks = 2 * std::max(1, cus);
+  const uint32_t hops = 4096;
+  uint32_t* sink = dev_alloc<uint32_t>(1);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  try {
+    HIP_OK(hipEventCreate(&e0));
+    HIP_OK(hipEventCreate(&e1));
+    launch_lds_lookups(n_blocks, hops, sink, stream);  // warm-up
+    HIP_OK(hipEventRecord(e0, stream));
+    launch_lds_lookups(n_blocks, hops, sink, stream);
+    HIP_OK(hipEventRecord(e1, stream));
+    HIP_OK(hipGetLastError());
+    HIP_OK(hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_OK(hipEventElapsedTime(&ms, e0, e1));
+    *h_lookups_per_second = (double)n_blocks * 1024.0 * hops / (ms * 1e-3);
+  } catch (...) {
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(sink);
+    throw;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  (void)hipFree(sink);
+  return XGM_OK;
+  API_END
+}
+
 int32_t xgm_debug_batch_plan(xgm_batch* bt, uint32_t* h_out, int32_t cap, int32_t* h_budget, void* hip_stream) {
   API_BEGIN
   if (!bt || !h_out || cap < 0) return fail(XGM_ERR_BAD_ARG, "batch_plan: bad argument");

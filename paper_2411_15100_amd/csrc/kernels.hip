@@ -1189,6 +1189,22 @@ __global__ void apply_elementwise_kernel(unsigned char* __restrict__ logits, int
   else *reinterpret_cast<uint32_t*>(p) = neg_inf;
 }
 
+// ------------------------------------------------------------ measurement aid
+// Chains of dependent LDS reads with every wave slot of the device busy: the
+// ceiling for the table lookups of the token walks (each step of a walk is a
+// few such reads, each depending on the one before).
+constexpr int kLookupThreads = 1024;
+__global__ __launch_bounds__(kLookupThreads) void lds_lookup_kernel(uint32_t n_words, uint32_t hops, uint32_t* __restrict__ sink) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint32_t* table = reinterpret_cast<uint32_t*>(smem);
+  // a permutation with one long cycle: i -> (i * 5 + 1) mod n_words (n_words is a power of two)
+  for (uint32_t k = threadIdx.x; k < n_words; k += kLookupThreads) table[k] = (k * 5u + 1u) & (n_words - 1u);
+  __syncthreads();
+  uint32_t at = (threadIdx.x * 97u + blockIdx.x) & (n_words - 1u);
+  for (uint32_t h = 0; h < hops; ++h) at = table[at];
+  if (at == 0xFFFFFFFFu) sink[0] = at;  // never true: keeps the chain alive
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ launchers
@@ -1283,6 +1299,10 @@ void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t
   else
     hipLaunchKernelGGL((fill_kernel<false, 0>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
                        plan, voc, out, log, seq, step_counter, fa);
+}
+
+void launch_lds_lookups(int32_t n_blocks, uint32_t hops, uint32_t* sink, hipStream_t stream) {
+  hipLaunchKernelGGL(lds_lookup_kernel, dim3(n_blocks), dim3(kLookupThreads), 8192 * 4, stream, 8192u, hops, sink);
 }
 
 void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries, hipStream_t stream) {

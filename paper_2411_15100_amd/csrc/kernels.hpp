@@ -268,6 +268,8 @@ void launch_batch_fork(const DevBatch& bt, const DevVocab& voc, const int32_t* d
                        hipStream_t stream);
 // plan only (after the host has written states)
 void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries, hipStream_t stream);
+// measurement aid: n_blocks workgroups of 1024 lanes, each lane a chain of `hops` dependent reads in a 32 KB LDS table
+void launch_lds_lookups(int32_t n_blocks, uint32_t hops, uint32_t* sink, hipStream_t stream);
 // (c) apply; returns false if the buffer layout needs the element-wise kernel
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,
                   const uint32_t* bitmask, int32_t V_mask, const int32_t* row_index, int32_t n_rows,
