@@ -388,7 +388,7 @@ int32_t xgm_debug_plan_workgroups(const uint32_t* h_upto, int32_t B, int32_t n_c
       plan.data());
   for (int32_t k = 0; k < n; ++k) {
     h_out[3 * k] = plan[k].row;
-    h_out[3 * k + 1] = plan[k].c0c1 & 0xFFFFu;
+    h_out[3 * k + 1] = plan[k].c0c1 & 0x7FFFu;
     h_out[3 * k + 2] = plan[k].c0c1 >> 16;
   }
   return n;
@@ -1440,7 +1440,7 @@ int32_t xgm_debug_batch_plan(xgm_batch* bt, uint32_t* h_out, int32_t cap, int32_
     if (f.row == kNoRow) continue;
     if (n >= cap) return fail(XGM_ERR_BAD_ARG, "batch_plan: the output array is too small");
     h_out[3 * n] = f.row;
-    h_out[3 * n + 1] = f.c0c1 & 0xFFFFu;
+    h_out[3 * n + 1] = f.c0c1 & 0x7FFFu;
     h_out[3 * n + 2] = f.c0c1 >> 16;
     ++n;
   }

@@ -724,11 +724,11 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   const FillBlock blk = plan[blockIdx.x];
   if (blk.row == kNoRow) return;  // padding of a plan made on the device
   const int32_t b = (int32_t)blk.row;
-  const int32_t c0 = (int32_t)(blk.c0c1 & 0xFFFFu), c1 = (int32_t)(blk.c0c1 >> 16);  // this workgroup's chunks
+  const int32_t c0 = (int32_t)(blk.c0c1 & 0x7FFFu), c1 = (int32_t)(blk.c0c1 >> 16);  // this workgroup's chunks
   const int32_t w_begin = c0 * kChunkWords;
   const int32_t n_words = min(c1 * kChunkWords, voc.W) - w_begin;
   const RowDesc rd = rows[b];
-  const bool has_cache = rd.n_stacks > 0;
+  const bool has_cache = rd.n_stacks > 0 && !(blk.c0c1 & kFillBlockNoEntries);  // are there lists to resolve?
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
   // everything the row descriptor points to is fetched in one go: tables, live frames, the first stack's
   // header with its list offsets, and (below) the accepted words

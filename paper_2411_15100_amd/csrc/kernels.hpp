@@ -164,8 +164,11 @@ constexpr uint32_t kStackHdrTop = 0, kStackHdrDepth = 1, kStackHdrFrames = 2, kS
 // compute units instead of serialising on a few.
 struct FillBlock {
   uint32_t row;
-  uint32_t c0c1;  // c0 | c1 << 16
+  uint32_t c0c1;  // c0 | kFillBlockNoEntries | c1 << 16
 };
+// set by the planner when none of the request's stacks lists a token in chunks [c0, c1): the workgroup then
+// only ORs the accepted words and never touches the automaton tables
+constexpr uint32_t kFillBlockNoEntries = 0x8000u;
 constexpr int32_t kFillMaxChunks = 24;  // chunks one workgroup may own (its mask words live in LDS)
 // A workgroup builds the two-byte table of a stack only if its lists for that stack have at least this many
 // entries: building it costs about as much as one queue round of walks.

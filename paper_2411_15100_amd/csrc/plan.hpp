@@ -49,7 +49,8 @@ XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, F
     if (!cut && made + 1 < k && row_entries)
       cut = upto(c + 1) * (uint64_t)k >= row_entries * (uint64_t)(made + 1);
     if (cut) {
-      if (out) out[made] = FillBlock{(uint32_t)b, (uint32_t)c0 | ((uint32_t)(c + 1) << 16)};
+      const uint32_t idle = upto(c + 1) == upto(c0) ? kFillBlockNoEntries : 0u;  // nothing listed in these chunks
+      if (out) out[made] = FillBlock{(uint32_t)b, (uint32_t)c0 | idle | ((uint32_t)(c + 1) << 16)};
       c0 = c + 1;
       ++made;
     }
