@@ -242,6 +242,7 @@ struct Context {
   xgm_vocab* last_vocab = nullptr;
   const struct xgm_batch* last_batch = nullptr;  // set instead of last_slot when the fill read device-resident states
   // scratch of the workgroup planner (kept to avoid per-step allocation)
+  std::vector<FillBlock> plan_scratch;
   uint32_t pair_min_entries = kFillPairMinEntries;
   int32_t resident_blocks = 0;  // fill workgroups the device holds at once (two per compute unit)
 };
@@ -901,7 +902,8 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   const size_t off_stacks = (size_t)B * sizeof(RowDesc);
   const size_t off_frames = off_stacks + n_stacks * hdr_words * 4;
   const size_t off_plan = ((off_frames + n_frames * 2 + 63) / 64) * 64;
-  const size_t bytes = off_plan + (size_t)B * n_chunk * sizeof(FillBlock);  // capacity: one block per (row, chunk)
+  // capacity: one block per (row, chunk), and the padding to a multiple of kFillGridMultiple
+  const size_t bytes = off_plan + ((size_t)B * n_chunk + kFillGridMultiple) * sizeof(FillBlock);
 
   Context& C = ctx();
   std::lock_guard<std::mutex> lock(C.mu);
@@ -958,7 +960,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   }
   // Plan the workgroups (plan.hpp): two per compute unit are resident at once.
   auto* plan = reinterpret_cast<FillBlock*>((char*)slot.h_buf + off_plan);
-  const int32_t n_blocks = plan_workgroups(
+  int32_t n_blocks = plan_workgroups(
       B, n_chunk, C.resident_blocks,
       [&](int32_t b, int32_t c) {
         uint64_t run = 0;
@@ -967,6 +969,13 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
         return run;
       },
       plan);
+  {  // place the workgroups in the launch (plan_slot), idle entries in between
+    C.plan_scratch.assign(plan, plan + n_blocks);
+    const int32_t n_real = n_blocks;
+    n_blocks = (n_real + kFillGridMultiple - 1) / kFillGridMultiple * kFillGridMultiple;
+    for (int32_t k = 0; k < n_blocks; ++k) plan[k] = FillBlock{kNoRow, 0u};
+    for (int32_t p = 0; p < n_real; ++p) plan[plan_slot((uint32_t)p, (uint32_t)n_real)] = C.plan_scratch[p];
+  }
   if (timing) HIP_OK(hipEventRecord(timing[0], stream));
   launch_upload(slot.h_dev, slot.d_buf, off_plan + (size_t)n_blocks * sizeof(FillBlock), stream);
   if (timing) HIP_OK(hipEventRecord(timing[1], stream));
@@ -1435,10 +1444,13 @@ int32_t xgm_debug_batch_plan(xgm_batch* bt, uint32_t* h_out, int32_t cap, int32_
   HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
   std::vector<FillBlock> plan(bt->dev.plan_cap);
   HIP_OK(hipMemcpy(plan.data(), bt->dev.plan, plan.size() * sizeof(FillBlock), hipMemcpyDeviceToHost));
+  int32_t n_real = 0;
+  for (const FillBlock& f : plan) n_real += f.row != kNoRow;
+  if (n_real > cap) return fail(XGM_ERR_BAD_ARG, "batch_plan: the output array is too small");
   int32_t n = 0;
-  for (const FillBlock& f : plan) {
-    if (f.row == kNoRow) continue;
-    if (n >= cap) return fail(XGM_ERR_BAD_ARG, "batch_plan: the output array is too small");
+  for (int32_t p = 0; p < n_real; ++p) {  // in the planner's order
+    const FillBlock& f = plan[plan_slot((uint32_t)p, (uint32_t)n_real)];
+    if (f.row == kNoRow) return fail(XGM_ERR_INTERNAL, "batch_plan: a planned workgroup is missing from its place in the launch");
     h_out[3 * n] = f.row;
     h_out[3 * n + 1] = f.c0c1 & 0x7FFFu;
     h_out[3 * n + 2] = f.c0c1 >> 16;

@@ -727,8 +727,8 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   const XGM_GLOBAL uint16_t* frames = (const XGM_GLOBAL uint16_t*)frames_;
   unsigned long long my_steps = 0;
   const uint32_t tid = threadIdx.x;
-  const FillBlock blk = plan[blockIdx.x];
-  if (blk.row == kNoRow) return;  // padding of a plan made on the device
+  const FillBlock blk = plan[blockIdx.x];  // placed by the planner (plan_slot)
+  if (blk.row == kNoRow) return;  // padding of the plan
   const int32_t b = (int32_t)blk.row;
   const int32_t c0 = (int32_t)(blk.c0c1 & 0x7FFFu), c1 = (int32_t)(blk.c0c1 >> 16);  // this workgroup's chunks
   const int32_t w_begin = c0 * kChunkWords;
@@ -1089,7 +1089,8 @@ __global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
   uint32_t my_count = 0u;
   if (tid < (uint32_t)bt.B) {
     k = plan_row_share(bt.B, bt.n_chunk, bt.budget, mine[bt.n_chunk], total);
-    my_count = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; }, (FillBlock*)nullptr);
+    my_count = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; },
+                                  [](int32_t, const FillBlock&) {});
   }
   count[tid] = my_count;
   __syncthreads();
@@ -1100,9 +1101,11 @@ __global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
     __syncthreads();
   }
   const uint32_t n_blocks = count[kPlanThreads - 1], first = count[tid] - my_count;
-  if (tid < (uint32_t)bt.B && first + (uint32_t)(k + plan_min_blocks(bt.n_chunk)) <= bt.plan_cap)
-    plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; }, bt.plan + first);
-  for (uint32_t j = n_blocks + tid; j < bt.plan_cap; j += kPlanThreads) bt.plan[j] = FillBlock{kNoRow, 0u};
+  for (uint32_t j = tid; j < bt.plan_cap; j += kPlanThreads) bt.plan[j] = FillBlock{kNoRow, 0u};
+  __syncthreads();
+  if (tid < (uint32_t)bt.B && n_blocks <= bt.plan_cap)
+    plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; },
+             [&](int32_t made, const FillBlock& f) { bt.plan[plan_slot(first + (uint32_t)made, n_blocks)] = f; });
 }
 
 // Ahead of the next fill: the two-byte tables (see build_pair_table) of the
@@ -1290,7 +1293,7 @@ void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t
                  uint32_t seq, unsigned long long* step_counter, hipStream_t stream, void* logits, int elem_size,
                  uint32_t neg_inf, int32_t V_logits, int64_t row_stride, uint32_t pair_min_entries,
                  const uint32_t* pair_tables) {
-  if (n_blocks <= 0) return;
+  if (n_blocks <= 0 || n_blocks % kFillGridMultiple != 0) return;  // callers pad the plan with kNoRow entries
   const dim3 grid(n_blocks);
   const FusedApply fa{static_cast<unsigned char*>(logits), row_stride, V_logits, neg_inf, pair_min_entries, pair_tables};
   if (logits && elem_size == 2)

@@ -175,6 +175,7 @@ constexpr int32_t kFillMaxChunks = 24;  // chunks one workgroup may own (its mas
 constexpr uint32_t kFillPairMinEntries = 2048;
 
 constexpr uint32_t kNoRow = 0xFFFFFFFFu;  // FillBlock::row of a workgroup that has nothing to do
+constexpr int32_t kFillGridMultiple = 8;  // a plan is padded with kNoRow entries to a multiple of the number of XCDs
 
 // ---- matcher states that live on the device (section 3.3 on the GPU: the
 // sampled tokens move the stacks on without a round trip to the host).
@@ -211,7 +212,8 @@ struct DevBatch {
 // workgroups a plan can have at most (see plan.hpp)
 inline uint32_t batch_plan_cap(int32_t B, int32_t n_chunk, int32_t budget) {
   const int32_t min_blocks = (n_chunk + kFillMaxChunks - 1) / kFillMaxChunks;
-  return (uint32_t)((budget > B * min_blocks ? budget : B * min_blocks) + B * min_blocks);
+  const int32_t n = (budget > B * min_blocks ? budget : B * min_blocks) + B * min_blocks;
+  return (uint32_t)((n + kFillGridMultiple - 1) / kFillGridMultiple * kFillGridMultiple);
 }
 
 // pairs whose walk exceeded the limits
@@ -250,6 +252,7 @@ void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_
 // copy `bytes` (rounded up to 16; both buffers must hold that) from device-visible pinned host memory
 void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t stream);
 // (b) batched mask fill
+// n_blocks: entries of `plan`, a multiple of kFillGridMultiple (padded with kNoRow entries).
 // step_counter: null on the hot path; otherwise the counting instantiation is launched.
 // logits != null: the fused instantiation also applies each row's mask to its logits row
 // (elem_size 2 or 4, rows 16-byte aligned; a walk over the limits leaves its token allowed).

@@ -36,11 +36,23 @@ XGM_PLAN_HD int32_t plan_row_share(int32_t B, int32_t n_chunk, int32_t budget, u
   return k < n_chunk ? k : n_chunk;
 }
 
+// Where workgroup p of a plan of n goes in the launch.  Workgroups are handed
+// to the eight XCDs in turn by their index, and every XCD has an L2 of its
+// own: consecutive workgroups of the plan - those of one request, which stage
+// the same table image - get indices that are equal modulo 8, so that they
+// share an XCD and the image is fetched into one L2 instead of eight.  The
+// launch has (n rounded up to a multiple of 8) or more workgroups; indices
+// that no p maps to hold kNoRow.
+XGM_PLAN_HD uint32_t plan_slot(uint32_t p, uint32_t n) {
+  const uint32_t per_xcd = (n + 7u) / 8u;
+  return (p % per_xcd) * 8u + p / per_xcd;
+}
+
 // Cuts row b into (at most k + plan_min_blocks) workgroups; upto(c) = entries
 // of the row in chunks [0, c), all its stacks together (non-decreasing,
-// upto(0) == 0).  Writes them to `out` if it is not null; returns their number.
-template <class Upto>
-XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, FillBlock* out) {
+// upto(0) == 0).  emit(i, workgroup) receives the i-th of them; returns their number.
+template <class Upto, class Emit>
+XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, Emit emit) {
   const uint64_t row_entries = upto(n_chunk);
   int32_t c0 = 0, made = 0;
   for (int32_t c = 0; c < n_chunk; ++c) {
@@ -50,7 +62,7 @@ XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, F
       cut = upto(c + 1) * (uint64_t)k >= row_entries * (uint64_t)(made + 1);
     if (cut) {
       const uint32_t idle = upto(c + 1) == upto(c0) ? kFillBlockNoEntries : 0u;  // nothing listed in these chunks
-      if (out) out[made] = FillBlock{(uint32_t)b, (uint32_t)c0 | idle | ((uint32_t)(c + 1) << 16)};
+      emit(made, FillBlock{(uint32_t)b, (uint32_t)c0 | idle | ((uint32_t)(c + 1) << 16)});
       c0 = c + 1;
       ++made;
     }
@@ -61,7 +73,8 @@ XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, F
 //   upto(b, c): as above for row b;
 //   out:        room for B * n_chunk workgroups.
 // Returns the number of workgroups written.  Every (row, chunk) is covered by
-// exactly one of them; rows appear in order, chunk ranges ascending.
+// exactly one of them; rows appear in order, chunk ranges ascending (the
+// caller places them in the launch with plan_slot).
 template <class Upto>
 inline int32_t plan_workgroups(int32_t B, int32_t n_chunk, int32_t budget, Upto upto, FillBlock* out) {
   uint64_t total = 0;
@@ -69,7 +82,9 @@ inline int32_t plan_workgroups(int32_t B, int32_t n_chunk, int32_t budget, Upto 
   int32_t n_blocks = 0;
   for (int32_t b = 0; b < B; ++b) {
     const int32_t k = plan_row_share(B, n_chunk, budget, upto(b, n_chunk), total);
-    n_blocks += plan_row(b, n_chunk, k, [&](int32_t c) { return upto(b, c); }, out + n_blocks);
+    FillBlock* dst = out + n_blocks;
+    n_blocks += plan_row(b, n_chunk, k, [&](int32_t c) { return upto(b, c); },
+                         [&](int32_t i, const FillBlock& f) { dst[i] = f; });
   }
   return n_blocks;
 }
