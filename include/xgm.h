@@ -274,6 +274,14 @@ int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, vo
  * (default 2048; negative restores the default).  The masks do not depend on
  * it; tests set 1 to force that path at small sizes.  Returns the old value. */
 int32_t xgm_debug_set_fill_pair_threshold(int32_t entries);
+/* Test knob (process-wide): plan fills for this many workgroups instead of two
+ * per compute unit (0 or negative restores that).  Every request still gets
+ * the workgroups its mask words need, so a small value makes each workgroup
+ * own many blocks of token ids with long lists - the shape a large batch
+ * produces - at small batch sizes.  A batch of device-resident states takes
+ * the value at its creation.  The masks do not depend on it.  Returns the old
+ * value. */
+int32_t xgm_debug_set_fill_budget(int32_t workgroups);
 /* Instrumentation for benchmarks: the same fill (same result in d_bitmask)
  * with a kernel instantiation that also counts the automaton steps of all
  * walks; synchronous; *h_steps receives the count.  Not for the hot path. */

@@ -68,6 +68,7 @@ SIGNATURES = {
     "xgm_fill_and_apply": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
     "xgm_debug_fill_count_steps": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_debug_set_fill_pair_threshold": (_i32, [_i32]),
+    "xgm_debug_set_fill_budget": (_i32, [_i32]),
     "xgm_debug_fill_timed": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_batch_create": (_i32, [_vp, _i32, _i32, _vp, _pp]),
     "xgm_batch_destroy": (None, [_vp]),
@@ -448,6 +449,11 @@ def debug_lds_lookup_rate(stream: int = 0) -> float:
     out = ctypes.c_double(0.0)
     _check(load_library().xgm_debug_lds_lookup_rate(ctypes.c_void_p(stream), ctypes.byref(out)))
     return float(out.value)
+
+
+def debug_set_fill_budget(workgroups: int) -> int:
+    """Test knob: number of workgroups fills are planned for (0: two per compute unit); returns the old value."""
+    return int(load_library().xgm_debug_set_fill_budget(int(workgroups)))
 
 
 def debug_set_fill_pair_threshold(entries: int) -> int:

@@ -245,6 +245,7 @@ struct Context {
   std::vector<FillBlock> plan_scratch;
   uint32_t pair_min_entries = kFillPairMinEntries;
   int32_t resident_blocks = 0;  // fill workgroups the device holds at once (two per compute unit)
+  int32_t budget_override = 0;  // test knob: plan for this many workgroups instead (0: off)
 };
 Context& ctx() {
   static Context c;
@@ -961,7 +962,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   // Plan the workgroups (plan.hpp): two per compute unit are resident at once.
   auto* plan = reinterpret_cast<FillBlock*>((char*)slot.h_buf + off_plan);
   int32_t n_blocks = plan_workgroups(
-      B, n_chunk, C.resident_blocks,
+      B, n_chunk, C.budget_override > 0 ? C.budget_override : C.resident_blocks,
       [&](int32_t b, int32_t c) {
         uint64_t run = 0;
         const uint32_t* off0 = hdrs + (size_t)rows[b].stack_begin * hdr_words + kStackHdrWords;
@@ -1033,6 +1034,14 @@ int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, vo
   if (rc != XGM_OK) return rc;
   return fill_impl(ms, B, d_bitmask, hip_stream, nullptr, nullptr, &f);
   API_END
+}
+
+int32_t xgm_debug_set_fill_budget(int32_t workgroups) {
+  Context& C = ctx();
+  std::lock_guard<std::mutex> lock(C.mu);
+  const int32_t old = C.budget_override;
+  C.budget_override = workgroups > 0 ? workgroups : 0;
+  return old;
 }
 
 int32_t xgm_debug_set_fill_pair_threshold(int32_t entries) {
@@ -1279,7 +1288,7 @@ int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* h
         HIP_OK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         C.resident_blocks = 2 * std::max(1, cus);
       }
-      d.budget = C.resident_blocks;
+      d.budget = C.budget_override > 0 ? C.budget_override : C.resident_blocks;
     }
     std::vector<DevCache> caches(B);
     for (int32_t b = 0; b < B; ++b) caches[b] = ms[b]->c->host;

@@ -551,3 +551,50 @@ def test_fused_path_leaves_undecided_tokens_allowed_until_the_fixup(xgm, wl):
     assert not (int(got[0]) >> 4) & 1 and not (int(got[0]) >> 5) & 1
     assert xgm.fill_overflow_fixup(_stream()) == 2
     assert np.array_equal(d.cpu().numpy()[0], oracle.pack_bitmask(want))
+
+
+def test_fill_workgroups_with_many_chunks_and_several_rounds(xgm, wl, no_overflow, pair_table):
+    """A tight budget of workgroups (as a large batch produces) at a small batch: every workgroup owns up
+    to 24 blocks of 4096 token ids, and the lists of a stack top inside a string (tens of thousands of
+    entries) are worked off in several rounds of the queue.  Host-side and device-resident states."""
+    vocab = si.make_vocab("bpe", 151936, 0)
+    xv = wl.make_xgm_vocab(vocab)
+    specs = [(si.JSON_GRAMMAR, b'{"key": "val'), (si.make_schema_grammar(5, string_heavy=True), None), (si.JSON_GRAMMAR, b'[1, ')]
+    caches = [xgm.Cache(xgm.Grammar(t, "root"), xv) for t, _ in specs]
+    ms = [xgm.Matcher(cache=c) for c in caches]
+    oms = [oracle.EarleyMatcher(oracle.Grammar(t, "root")) for t, _ in specs]
+    toks = vocab.tokens()
+    for b, (m, om, (_, text)) in enumerate(zip(ms, oms, specs)):
+        if text is not None:
+            m.accept_bytes(text)
+            assert om.advance(text)
+        else:   # walk the schema grammar into a string value: the state with the longest lists
+            info = wl.TokenInfo(vocab)
+            rng = np.random.Generator(np.random.PCG64(3))
+            for _ in range(120):
+                tops = [m.stack(s)[-1] for s in range(m.num_stacks())]
+                if max(caches[b].num_uncertain(t) for t in tops) > 10000:
+                    break
+                want = om.mask(vocab)
+                want[vocab.stop_ids] = False
+                t = int(si.pick_tokens(rng, want[None, :], info.structural, info.is_stop, 0.35)[0])
+                m.accept_token(t)
+                assert om.advance(toks[t])
+    entries = [sum(c.num_uncertain(m.stack(s)[-1]) for s in range(m.num_stacks())) for m, c in zip(ms, caches)]
+    assert max(entries) > 10000, entries
+    want = oracle.pack_bitmask(np.stack([om.mask(vocab) for om in oms]))
+    W = xgm.bitmask_words(vocab.size)
+    d = torch.zeros((3, W), dtype=torch.int32, device="cuda")
+    old = xgm.debug_set_fill_budget(1)
+    try:
+        xgm.fill_next_token_bitmask(ms, d.data_ptr(), _stream())
+        assert np.array_equal(d.cpu().numpy(), want)
+        batch = xgm.DeviceBatch(ms, history=0, stream=_stream())
+        plan, budget = batch.debug_plan(_stream())
+        assert budget == 1 and len(plan) == 6 and max(c1 - c0 for _, c0, c1 in plan) > 12
+        d.zero_()
+        batch.fill_next_token_bitmask(d.data_ptr(), _stream())
+        assert np.array_equal(d.cpu().numpy(), want)
+    finally:
+        xgm.debug_set_fill_budget(old)
+    say(f"  list entries per row {entries}: masks bit-exact with 2 workgroups per row")
