@@ -200,6 +200,13 @@ int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t de
  * end chunk).  Returns the number of workgroups, or a negative status. */
 int32_t xgm_debug_plan_workgroups(const uint32_t* h_upto, int32_t B, int32_t n_chunk, int32_t budget, uint32_t* h_out,
                                   int32_t cap);
+/* Where workgroup p of a plan of n workgroups is placed in the launch: the
+ * device hands workgroups to its eight XCDs in turn by their index, so
+ * consecutive workgroups of the plan (those of one request, which read the
+ * same automaton tables) get indices that are equal modulo 8 and share an
+ * XCD's L2.  The launch has n rounded up to a multiple of 8 workgroups.
+ * Returns the index, or a negative status. */
+int32_t xgm_debug_plan_slot(int32_t p, int32_t n);
 /* A frame whose current node is `top` can only sit on one of the few nodes that
  * follow a reference to top's rule (directly, or through references in tail
  * position).  Returns the index of `below` among them (what the fill kernel

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     debug_plan_workgroups,
     debug_set_fill_pair_threshold,
     debug_set_fill_budget,
+    debug_plan_slot,
     debug_lds_lookup_rate,
     MatcherBatch,
     DeviceBatch,

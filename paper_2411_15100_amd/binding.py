@@ -43,6 +43,7 @@ SIGNATURES = {
     "xgm_debug_next_bytes_host": (_i32, [_vp, _vp, _i32, _i32, _vp]),
     "xgm_debug_context_index": (_i32, [_vp, _i32, _i32]),
     "xgm_debug_plan_workgroups": (_i32, [_vp, _i32, _i32, _i32, _vp, _i32]),
+    "xgm_debug_plan_slot": (_i32, [_i32, _i32]),
     "xgm_cache_build": (_i32, [_vp, _vp, _vp, _pp]),
     "xgm_cache_build_ex": (_i32, [_vp, _vp, _vp, ctypes.c_uint32, _pp]),
     "xgm_cache_num_uncertain_plain": (_i32, [_vp, _i32]),
@@ -449,6 +450,11 @@ def debug_lds_lookup_rate(stream: int = 0) -> float:
     out = ctypes.c_double(0.0)
     _check(load_library().xgm_debug_lds_lookup_rate(ctypes.c_void_p(stream), ctypes.byref(out)))
     return float(out.value)
+
+
+def debug_plan_slot(p: int, n: int) -> int:
+    """Index in the launch of workgroup p of a plan of n."""
+    return _check(load_library().xgm_debug_plan_slot(int(p), int(n)))
 
 
 def debug_set_fill_budget(workgroups: int) -> int:

@@ -397,6 +397,11 @@ int32_t xgm_debug_plan_workgroups(const uint32_t* h_upto, int32_t B, int32_t n_c
   API_END
 }
 
+int32_t xgm_debug_plan_slot(int32_t p, int32_t n) {
+  if (p < 0 || n <= 0 || p >= n) return fail(XGM_ERR_BAD_ARG, "plan_slot: need 0 <= p < n");
+  return (int32_t)plan_slot((uint32_t)p, (uint32_t)n);
+}
+
 int32_t xgm_debug_context_index(const xgm_grammar* g, int32_t top, int32_t below) {
   if (!g || top < 0 || top >= g->A.n_nodes || below < 0 || below >= g->A.n_nodes)
     return fail(XGM_ERR_BAD_ARG, "context_index: bad argument");

@@ -499,3 +499,17 @@ def test_depth_first_accept_gives_the_engines_stacks(name):
     assert n_ok > 20 and n_rejected > 20, (n_ok, n_rejected)
     if name == "ambiguous":
         assert n_multi > 3
+
+
+def test_plan_placement_is_a_bijection_that_keeps_neighbours_on_one_xcd():
+    for n in list(range(1, 70)) + [491, 512, 767, 768, 1000]:
+        slots = [xgm.debug_plan_slot(p, n) for p in range(n)]
+        launch = (n + 7) // 8 * 8
+        assert len(set(slots)) == n and min(slots) >= 0 and max(slots) < launch
+        per = (n + 7) // 8
+        # workgroups p and p + 1 go to the same XCD (index modulo 8) unless p + 1 starts the next XCD's share
+        for p in range(n - 1):
+            same = slots[p] % 8 == slots[p + 1] % 8
+            assert same == ((p + 1) % per != 0)
+    with pytest.raises(xgm.XgmError):
+        xgm.debug_plan_slot(5, 5)
