@@ -1266,7 +1266,7 @@ int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* h
     v = ms[b]->v;
   }
   const int32_t n_chunk = v->dv.n_chunk;
-  if ((size_t)B * (n_chunk + 1) * 4 > (size_t)128 * 1024)
+  if ((size_t)B * ((n_chunk + 1 + 3) & ~3) * 4 > (size_t)128 * 1024)  // the planner's running counts live in LDS
     return fail(XGM_ERR_TOO_LARGE, "batch_create: rows x vocabulary chunks beyond what the device planner holds");
   require_device();
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);

@@ -1067,17 +1067,20 @@ __global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint32_t* upto = reinterpret_cast<uint32_t*>(smem);  // [B][n_chunk + 1]
   __shared__ unsigned long long total;
-  __shared__ uint32_t count[kPlanThreads];
-  const uint32_t tid = threadIdx.x, stride = (uint32_t)bt.n_chunk + 1u;
-  const uint32_t hdr_stride = kStackHdrWords + stride;
+  __shared__ uint32_t count[kPlanThreads / 64];  // per-wave sums of the rows' workgroup counts
+  const uint32_t tid = threadIdx.x, n_off = (uint32_t)bt.n_chunk + 1u;
+  const uint32_t stride = (n_off + 3u) & ~3u;  // rows of `upto` start on 16 bytes
+  const uint32_t hdr_stride = kStackHdrWords + n_off;
   if (tid == 0) total = 0ull;
   for (uint32_t item = tid; item < (uint32_t)bt.B * stride; item += kPlanThreads) {
     const uint32_t b = item / stride, c = item % stride;
-    const uint32_t s0 = bt.rows[b].stack_begin, ns = bt.rows[b].n_stacks;
     uint32_t run = 0u;
-    for (uint32_t s = 0; s < ns; ++s) {
-      const uint32_t* off = bt.hdrs + (size_t)(s0 + s) * hdr_stride + kStackHdrWords;
-      run += off[c] - off[0];
+    if (c < n_off) {
+      const uint32_t s0 = bt.rows[b].stack_begin, ns = bt.rows[b].n_stacks;
+      for (uint32_t s = 0; s < ns; ++s) {
+        const uint32_t* off = bt.hdrs + (size_t)(s0 + s) * hdr_stride + kStackHdrWords;
+        run += off[c] - off[0];
+      }
     }
     upto[item] = run;
   }
@@ -1085,26 +1088,45 @@ __global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
   if (tid < (uint32_t)bt.B) atomicAdd(&total, (unsigned long long)upto[tid * stride + bt.n_chunk]);
   __syncthreads();
   int32_t k = 0;
-  const uint32_t* mine = upto + tid * stride;
+  // the row's running counts, read four at a time (the cuts are made by one thread per row, one chunk after
+  // the other: what it waits for is these reads)
+  const uint4* mine4 = reinterpret_cast<const uint4*>(upto + tid * stride);
+  uint4 held = make_uint4(0u, 0u, 0u, 0u);
+  int32_t held_at = -1;
+  auto upto_of = [&](int32_t c) {
+    if ((c >> 2) != held_at) {
+      held_at = c >> 2;
+      held = mine4[held_at];
+    }
+    const uint32_t lo = (c & 1) ? held.y : held.x, hi = (c & 1) ? held.w : held.z;
+    return (uint64_t)((c & 2) ? hi : lo);
+  };
   uint32_t my_count = 0u;
   if (tid < (uint32_t)bt.B) {
-    k = plan_row_share(bt.B, bt.n_chunk, bt.budget, mine[bt.n_chunk], total);
-    my_count = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; },
-                                  [](int32_t, const FillBlock&) {});
+    k = plan_row_share(bt.B, bt.n_chunk, bt.budget, upto[tid * stride + bt.n_chunk], total);
+    my_count = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, upto_of, [](int32_t, const FillBlock&) {});
   }
-  count[tid] = my_count;
+  // inclusive scan of the rows' workgroup counts: inside each wave with lane shuffles, then over the 16 wave sums
+  uint32_t incl = my_count;
+  const uint32_t lane = tid & 63u, wave = tid >> 6;
+#pragma unroll
+  for (uint32_t d = 1; d < 64u; d <<= 1) {
+    const uint32_t v = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += v;
+  }
+  if (lane == 63u) count[wave] = incl;
   __syncthreads();
-  for (uint32_t d = 1; d < (uint32_t)kPlanThreads; d <<= 1) {  // inclusive scan of the rows' workgroup counts
-    const uint32_t v = tid >= d ? count[tid - d] : 0u;
-    __syncthreads();
-    count[tid] += v;
-    __syncthreads();
+  uint32_t before = 0u, n_blocks = 0u;
+  for (uint32_t w = 0; w < (uint32_t)kPlanThreads / 64u; ++w) {
+    const uint32_t c = count[w];
+    if (w < wave) before += c;
+    n_blocks += c;
   }
-  const uint32_t n_blocks = count[kPlanThreads - 1], first = count[tid] - my_count;
+  const uint32_t first = before + incl - my_count;
   for (uint32_t j = tid; j < bt.plan_cap; j += kPlanThreads) bt.plan[j] = FillBlock{kNoRow, 0u};
   __syncthreads();
   if (tid < (uint32_t)bt.B && n_blocks <= bt.plan_cap)
-    plan_row((int32_t)tid, bt.n_chunk, k, [&](int32_t c) { return (uint64_t)mine[c]; },
+    plan_row((int32_t)tid, bt.n_chunk, k, upto_of,
              [&](int32_t made, const FillBlock& f) { bt.plan[plan_slot(first + (uint32_t)made, n_blocks)] = f; });
 }
 
@@ -1315,7 +1337,7 @@ void launch_lds_lookups(int32_t n_blocks, uint32_t hops, uint32_t* sink, hipStre
 }
 
 void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries, hipStream_t stream) {
-  hipLaunchKernelGGL(batch_plan_kernel, dim3(1), dim3(kPlanThreads), (size_t)bt.B * (bt.n_chunk + 1) * 4, stream, bt);
+  hipLaunchKernelGGL(batch_plan_kernel, dim3(1), dim3(kPlanThreads), (size_t)bt.B * ((bt.n_chunk + 1 + 3) & ~3) * 4, stream, bt);
   hipLaunchKernelGGL(batch_pair_kernel, dim3(bt.B), dim3(kPairThreads), kFillLdsBudget, stream, bt, voc, pair_min_entries);
 }
 

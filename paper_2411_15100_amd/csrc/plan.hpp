@@ -55,15 +55,17 @@ template <class Upto, class Emit>
 XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, Emit emit) {
   const uint64_t row_entries = upto(n_chunk);
   int32_t c0 = 0, made = 0;
+  uint64_t at_c0 = 0;  // upto(c0)
   for (int32_t c = 0; c < n_chunk; ++c) {
+    const uint64_t next = upto(c + 1);  // asked for in ascending order, once each
     bool cut = c + 1 == n_chunk || c + 1 - c0 == kFillMaxChunks;
     // cut after chunk c when the entries up to and including c reach the next share
-    if (!cut && made + 1 < k && row_entries)
-      cut = upto(c + 1) * (uint64_t)k >= row_entries * (uint64_t)(made + 1);
+    if (!cut && made + 1 < k && row_entries) cut = next * (uint64_t)k >= row_entries * (uint64_t)(made + 1);
     if (cut) {
-      const uint32_t idle = upto(c + 1) == upto(c0) ? kFillBlockNoEntries : 0u;  // nothing listed in these chunks
+      const uint32_t idle = next == at_c0 ? kFillBlockNoEntries : 0u;  // nothing listed in these chunks
       emit(made, FillBlock{(uint32_t)b, (uint32_t)c0 | idle | ((uint32_t)(c + 1) << 16)});
       c0 = c + 1;
+      at_c0 = next;
       ++made;
     }
   }
