@@ -1085,7 +1085,12 @@ __global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
     upto[item] = run;
   }
   __syncthreads();
-  if (tid < (uint32_t)bt.B) atomicAdd(&total, (unsigned long long)upto[tid * stride + bt.n_chunk]);
+  {  // the batch's total: per-wave sums with lane shuffles, one 64-bit atomic per wave
+    unsigned long long mine_total = tid < (uint32_t)bt.B ? (unsigned long long)upto[tid * stride + bt.n_chunk] : 0ull;
+#pragma unroll
+    for (uint32_t d = 32; d > 0; d >>= 1) mine_total += __shfl_down(mine_total, d, 64);
+    if ((tid & 63u) == 0 && mine_total) atomicAdd(&total, mine_total);
+  }
   __syncthreads();
   int32_t k = 0;
   // the row's running counts, read four at a time (the cuts are made by one thread per row, one chunk after

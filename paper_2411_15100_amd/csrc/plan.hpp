@@ -51,16 +51,15 @@ XGM_PLAN_HD uint32_t plan_slot(uint32_t p, uint32_t n) {
 // Cuts row b into (at most k + plan_min_blocks) workgroups; upto(c) = entries
 // of the row in chunks [0, c), all its stacks together (non-decreasing,
 // upto(0) == 0).  emit(i, workgroup) receives the i-th of them; returns their number.
-template <class Upto, class Emit>
-XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, Emit emit) {
-  const uint64_t row_entries = upto(n_chunk);
+template <class Wide, class Upto, class Emit>
+XGM_PLAN_HD int32_t plan_row_as(int32_t b, int32_t n_chunk, int32_t k, uint64_t row_entries, Upto upto, Emit emit) {
   int32_t c0 = 0, made = 0;
   uint64_t at_c0 = 0;  // upto(c0)
   for (int32_t c = 0; c < n_chunk; ++c) {
     const uint64_t next = upto(c + 1);  // asked for in ascending order, once each
     bool cut = c + 1 == n_chunk || c + 1 - c0 == kFillMaxChunks;
     // cut after chunk c when the entries up to and including c reach the next share
-    if (!cut && made + 1 < k && row_entries) cut = next * (uint64_t)k >= row_entries * (uint64_t)(made + 1);
+    if (!cut && made + 1 < k && row_entries) cut = (Wide)next * (Wide)k >= (Wide)row_entries * (Wide)(made + 1);
     if (cut) {
       const uint32_t idle = next == at_c0 ? kFillBlockNoEntries : 0u;  // nothing listed in these chunks
       emit(made, FillBlock{(uint32_t)b, (uint32_t)c0 | idle | ((uint32_t)(c + 1) << 16)});
@@ -70,6 +69,13 @@ XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, E
     }
   }
   return made;
+}
+template <class Upto, class Emit>
+XGM_PLAN_HD int32_t plan_row(int32_t b, int32_t n_chunk, int32_t k, Upto upto, Emit emit) {
+  const uint64_t row_entries = upto(n_chunk);
+  // the products below fit 32 bits for every list length that occurs in practice; the comparison is exact either way
+  if (row_entries * (uint64_t)(k > 0 ? k : 1) <= 0xFFFFFFFFull) return plan_row_as<uint32_t>(b, n_chunk, k, row_entries, upto, emit);
+  return plan_row_as<uint64_t>(b, n_chunk, k, row_entries, upto, emit);
 }
 
 //   upto(b, c): as above for row b;
