@@ -173,6 +173,14 @@ def main():
     torch.cuda.synchronize()
     plain_fill_us = e0.elapsed_time(e1) * 1e3 / n_fill
     plain_fill_gbs = 2.0 * B * V / (plain_fill_us * 1e-6) / 1e9
+    # ... and a plain copy between them (read + write of 38.9 MB each), the streaming rate of this machine
+    e0.record()
+    for k in range(n_fill):
+        work.logits[k % len(work.logits)].copy_(work.logits[(k + 3) % len(work.logits)])
+    e1.record()
+    torch.cuda.synchronize()
+    plain_copy_us = e0.elapsed_time(e1) * 1e3 / n_fill
+    plain_copy_gbs = 2.0 * 2.0 * B * V / (plain_copy_us * 1e-6) / 1e9
     work.refresh_logits()
 
     # ---- the fill kernel by itself: events inside the library around its two launches
@@ -215,7 +223,8 @@ def main():
     roof_apply = {"kernel": "apply_kernel<2>", "bound": "hbm", "achieved": apply_bytes / (apply_us_avg * 1e-6) / 1e9,
                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": TRAFFIC_APPLY_BYTES, "bytes_per_launch": apply_bytes,
                   "read_modify_write_bytes_per_launch": 2.0 * 2.0 * B * V + 4.0 * B * W,
-                  "plain_fill_of_the_same_buffers": {"us": plain_fill_us, "GB/s": plain_fill_gbs}}
+                  "plain_fill_of_the_same_buffers": {"us": plain_fill_us, "GB/s": plain_fill_gbs},
+                  "plain_copy_between_the_same_buffers": {"us": plain_copy_us, "GB/s": plain_copy_gbs}}
     roof_apply["frac"] = roof_apply["achieved"] / HBM_PEAK_GBS
     auto_steps = float(np.mean(steps_count))
     fill_kernel_us = fill_us_avg  # HIP events around the launch from device-resident states, on its stream
@@ -308,11 +317,36 @@ def main():
                     break
             if spent > budget_s:
                 break
+        # one thread, a few masks of the first state set (the paper's brute-force row is a single-thread figure)
+        t1s, n1 = 0.0, 0
+        for b in range(min(B, 4)):
+            om = oracle.EarleyMatcher(oracle.Grammar(work.texts[b], "root"))
+            for t in work.sets[0].history[b]:
+                assert om.advance(toks[t])
+            tt = time.perf_counter()
+            om.mask(work.vocab, 1)
+            t1s += time.perf_counter() - tt
+            n1 += 1
+        cpu_model = "unknown"
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
         cpu_baseline = {"value": checks / spent, "unit": "token checks/s", "cores": threads, "kind": "oracle",
+                        "cpu_model": cpu_model, "host_cpus": os.cpu_count(),
+                        "single_thread_us_per_mask": t1s / n1 * 1e6,
                         "sample": f"Earley brute-force masks for the first {masks} (state set, row) pairs of the pool, "
                                   f"in order ({checks} token checks, {spent:.1f} s of mask time)",
                         "us_per_mask": spent / (checks / V) * 1e6}
 
+    prop = torch.cuda.get_device_properties(0)
+    device = {"name": prop.name, "compute_units": prop.multi_processor_count,
+              "memory_GB": round(prop.total_memory / 1e9, 1),
+              "peaks_used": {"hbm_GB/s": HBM_PEAK_GBS},
+              "measured_streaming_GB/s": {"fill": plain_fill_gbs, "copy": plain_copy_gbs}}
     out = {
         "metric": "vocab token checks/sec + per-step bitmask fill+apply \u00b5s (batch\u00d7vocab)",
         "value": B * V / (ms_per_step * 1e-3),
@@ -347,6 +381,7 @@ def main():
         "roofline_fill": roof_fill,
         "roofline_apply": roof_apply,
         "roofline_two_call_step": roof_step,
+        "device": device,
         "walks_on_host_slow_path": int(overflow),
         "cache_build": cache_build,
         "cpu_baseline": cpu_baseline,
