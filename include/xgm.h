@@ -122,6 +122,26 @@ int32_t xgm_grammar_node_path(const xgm_grammar* g, int32_t node, int32_t* h_out
 /* 1 if the node is accepting in its rule (the rule may end here), else 0. */
 int32_t xgm_grammar_node_is_final(const xgm_grammar* g, int32_t node);
 
+/* JSON-schema front end (host only; the schema tasks of section 4.1): writes
+ * the grammar text for a JSON schema (UTF-8, len bytes) into h_text (cap
+ * bytes, NUL-terminated) and its length without the NUL into *h_len; with
+ * cap == 0 only the length is returned.  The root rule is `root`; compile the
+ * text with xgm_grammar_compile.  Supported: "type" (a name or a list of names:
+ * object, array, string, integer, number, boolean, null); "properties" with
+ * "required" - the members of an object appear in the order of "properties",
+ * those not listed in "required" may be left out (without "required" all are
+ * required), no other members are allowed; "items" with "minItems" /
+ * "maxItems" (at most 64); "enum" and "const" of strings, numbers, booleans
+ * and null; "anyOf" / "oneOf" (both as a union); `true` and `{}` (any JSON
+ * value); annotations are ignored.  Member names and the strings of "enum" /
+ * "const" are matched in their shortest JSON spelling (only `"`, `\` and
+ * control characters escaped); white space is allowed where JSON allows it.
+ * Keywords that would change the language and are not listed here ("pattern",
+ * "format", numeric ranges, "$ref", "allOf", "not", "additionalProperties"
+ * other than false, ...) are refused: XGM_ERR_PARSE with a message, as for
+ * malformed JSON.  XGM_ERR_BAD_ARG if cap is too small (*h_len is still set). */
+int xgm_schema_to_grammar(const char* schema_json, size_t len, char* h_text, size_t cap, size_t* h_len);
+
 /* --------------------------------------------------------------------- cache
  * 2. Once per (grammar, vocabulary): build the token mask cache of section
  * 3.1 on the GPU.  For every node n and token t, starting with n alone on the

@@ -32,6 +32,7 @@ SIGNATURES = {
     "xgm_vocab_size": (_i32, [_vp]),
     "xgm_grammar_compile": (_i32, [_cp, _sz, _cp, _pp]),
     "xgm_grammar_destroy": (None, [_vp]),
+    "xgm_schema_to_grammar": (_i32, [_cp, _sz, _vp, _sz, _vp]),
     "xgm_grammar_num_nodes": (_i32, [_vp]),
     "xgm_grammar_num_rules": (_i32, [_vp]),
     "xgm_grammar_rule_name": (_cp, [_vp, _i32]),
@@ -180,6 +181,17 @@ class Vocab:
 
     def __del__(self, _destroy=_destroy):
         _destroy("xgm_vocab_destroy", self)
+
+
+def schema_to_grammar(schema_json: str) -> str:
+    """Grammar text (root rule `root`) for a JSON schema given as text; see xgm_schema_to_grammar."""
+    lib = load_library()
+    raw = schema_json.encode("utf-8")
+    n = ctypes.c_size_t(0)
+    _check(lib.xgm_schema_to_grammar(raw, len(raw), None, 0, ctypes.byref(n)))
+    buf = ctypes.create_string_buffer(n.value + 1)
+    _check(lib.xgm_schema_to_grammar(raw, len(raw), buf, n.value + 1, ctypes.byref(n)))
+    return buf.raw[: n.value].decode("utf-8")
 
 
 class Grammar:

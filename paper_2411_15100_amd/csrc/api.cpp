@@ -15,6 +15,7 @@
 #include "automaton.hpp"
 #include "engine.hpp"
 #include "plan.hpp"
+#include "schema.hpp"
 #include "kernels.hpp"
 #include "walk.hpp"
 
@@ -394,6 +395,18 @@ int32_t xgm_debug_plan_workgroups(const uint32_t* h_upto, int32_t B, int32_t n_c
     h_out[3 * k + 2] = plan[k].c0c1 >> 16;
   }
   return n;
+  API_END
+}
+
+int xgm_schema_to_grammar(const char* schema_json, size_t len, char* h_text, size_t cap, size_t* h_len) {
+  API_BEGIN
+  if (!schema_json || !h_len || (cap > 0 && !h_text)) return fail(XGM_ERR_BAD_ARG, "schema_to_grammar: null argument");
+  const std::string text = schema_to_grammar(std::string(schema_json, len));
+  *h_len = text.size();
+  if (cap < text.size() + 1) return cap == 0 ? XGM_OK : fail(XGM_ERR_BAD_ARG, "schema_to_grammar: the output buffer is too small");
+  std::memcpy(h_text, text.data(), text.size());
+  h_text[text.size()] = 0;
+  return XGM_OK;
   API_END
 }
 
