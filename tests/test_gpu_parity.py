@@ -598,3 +598,36 @@ def test_fill_workgroups_with_many_chunks_and_several_rounds(xgm, wl, no_overflo
     finally:
         xgm.debug_set_fill_budget(old)
     say(f"  list entries per row {entries}: masks bit-exact with 2 workgroups per row")
+
+
+def test_grammars_from_the_schema_front_end_every_step(xgm, wl, pair_table):
+    """Schemas with optional members, bounded arrays, unions and free-form parts, turned into grammars by
+    xgm_schema_to_grammar: rules with empty alternatives and ambiguous white space on the HIP path."""
+    import json
+    from test_schema_frontend import HANDWRITTEN, to_json_schema
+    vocab = si.make_vocab("bpe", 32000, 0)
+    xv = wl.make_xgm_vocab(vocab)
+    rng = np.random.Generator(np.random.PCG64(8))
+    schemas = [HANDWRITTEN] + [to_json_schema(si.random_schema(s, max_depth=3, string_heavy=True), rng) for s in (11, 12, 13)]
+    texts = [xgm.schema_to_grammar(json.dumps(s, ensure_ascii=False)) for s in schemas]
+    caches = [xgm.Cache(xgm.Grammar(t, "root"), xv) for t in texts]
+    walker = wl.BatchWalker(caches, vocab, seed=21, structural_bias=0.4)
+    ogs = [oracle.Grammar(t, "root") for t in texts]
+    oms = [oracle.EarleyMatcher(o) for o in ogs]
+    toks = vocab.tokens()
+    before = xgm.overflow_total()
+    for step in range(48):
+        words = walker.fill()
+        if xgm.overflow_total() != before:          # ambiguous white space: a few walks over the limits
+            xgm.fill_overflow_fixup(_stream())
+            words = walker.d_mask.cpu().numpy()
+            before = xgm.overflow_total()
+        want = np.stack([om.mask(vocab) for om in oms])
+        assert np.array_equal(words, oracle.pack_bitmask(want)), f"step {step}: rows {np.flatnonzero((words != oracle.pack_bitmask(want)).any(axis=1))}"
+        picks = walker.step(words)
+        for b in range(len(oms)):
+            if not walker.history[b]:
+                oms[b] = oracle.EarleyMatcher(ogs[b])
+            else:
+                assert oms[b].advance(toks[int(picks[b])])
+    say(f"  4 front-end grammars x 48 steps bit-exact; most parallel stacks in a row: {max(m.num_stacks() for m in walker.matchers)}")
