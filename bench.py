@@ -29,9 +29,9 @@ HBM_PEAK_GBS = 8000.0                      # MI355X HBM3E, published
 # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
 # profiles/serving_step_counters.txt (scaled by what the counters read for a plain copy of known size).
 # Set to None whenever a kernel changes after the counters were taken.
-TRAFFIC_FILL_BYTES = 22.6e6
+TRAFFIC_FILL_BYTES = 13.9e6
 TRAFFIC_APPLY_BYTES = 33.9e6
-TRAFFIC_FUSED_BYTES = 51.7e6
+TRAFFIC_FUSED_BYTES = 44.2e6
 
 
 def log(*a):
