@@ -514,3 +514,97 @@ def test_fork_continues_one_state_in_several_rows(xgm, wl, pair_table):
     flat = xgm.DeviceBatch(ms[:2], history=0, stream=_stream())
     with pytest.raises(xgm.XgmError):
         flat.fork(_dev([1, -1]).data_ptr(), _stream())
+
+
+def test_random_grammars_cache_fill_and_device_accept(xgm, wl, pair_table):
+    """Seeded random grammars (nested groups, repetition, recursive and tail references, empty
+    alternatives, ambiguity): mask cache, fill from host-side and device-resident states, and the accept
+    kernel, against the oracle and the host matchers at every step."""
+    from test_host_library import _random_grammar_text
+    from test_oracle_misc import TinyVocab
+    rng = np.random.Generator(np.random.PCG64(777))
+    pieces = [bytes(p) for p in (b"a", b"b", b"c", b"d", b"(", b")", b"ab", b"ba", b"a(", b")b", b"cd)", b"((", b"))", b"abc", b"dcba", b"(a)")]
+    vocab = TinyVocab(pieces + [b""], [len(pieces)])
+    vocab.size = len(pieces) + 1
+    xv = xgm.Vocab(vocab.data, vocab.offsets, vocab.stop_ids)
+    texts = []
+    while len(texts) < 24:
+        text = _random_grammar_text(rng)
+        try:
+            xgm.Grammar(text, "root")
+        except xgm.XgmError:
+            continue
+        texts.append(text)
+    caches = [xgm.Cache(xgm.Grammar(t, "root"), xv) for t in texts]
+    ogs = [oracle.Grammar(t, "root") for t in texts]
+    B = len(texts)
+    n_checked = n_host = n_multi = 0
+    for walk in range(3):
+        ms = [xgm.Matcher(cache=c) for c in caches]
+        oms = [oracle.EarleyMatcher(o) for o in ogs]
+        batch = xgm.DeviceBatch(ms, history=2, stream=_stream())
+        d_dev = torch.zeros((B, 1), dtype=torch.int32, device="cuda")
+        d_host = torch.zeros((B, 1), dtype=torch.int32, device="cuda")
+        frozen = np.zeros(B, dtype=bool)
+        for step in range(10):
+            batch.fill_next_token_bitmask(d_dev.data_ptr(), _stream())
+            xgm.fill_overflow_fixup(_stream())
+            xgm.fill_next_token_bitmask(ms, d_host.data_ptr(), _stream())
+            xgm.fill_overflow_fixup(_stream())
+            want = np.stack([om.mask(vocab) for om in oms])
+            for b, m in enumerate(ms):
+                if m.is_terminated():
+                    want[b] = False
+                    want[b, vocab.stop_ids] = True
+            packed = oracle.pack_bitmask(want)
+            assert np.array_equal(d_host.cpu().numpy(), packed), (walk, step, np.flatnonzero((d_host.cpu().numpy() != packed).any(axis=1)))
+            assert np.array_equal(d_dev.cpu().numpy(), packed), (walk, step, np.flatnonzero((d_dev.cpu().numpy() != packed).any(axis=1)))
+            n_checked += B
+            tokens = np.full(B, -1, dtype=np.int64)
+            for b in range(B):
+                allowed = np.flatnonzero(want[b][: len(pieces)])
+                if frozen[b] or ms[b].is_terminated() or allowed.size == 0:
+                    frozen[b] = True
+                    continue
+                tokens[b] = int(allowed[rng.integers(0, allowed.size)])
+            batch.accept_tokens(_dev(tokens).data_ptr(), _stream())
+            status = batch.status(_stream())
+            for b in range(B):
+                t = int(tokens[b])
+                if t < 0:
+                    continue
+                rc = ms[b].try_accept_token(t)
+                if rc == -8:                      # the host's own limit of 64 stacks: the row stops here
+                    frozen[b] = True
+                    if status[b] == 0:            # the device went on: take it one step back
+                        back = np.zeros(B, dtype=np.int64)
+                        back[b] = 1
+                        batch.rollback(_dev(back).data_ptr(), _stream())
+                        assert batch.status(_stream())[b] == 0
+                    continue
+                assert rc == 0
+                assert oms[b].advance(pieces[t])
+                if status[b] in (-8, -9):         # device limits: through the host
+                    try:
+                        batch.set_row(b, ms[b], _stream())
+                    except xgm.XgmError:
+                        frozen[b] = True          # the state no longer fits the device: leave the row alone
+                        ms[b] = None
+                    n_host += 1
+                else:
+                    assert status[b] == 0, (walk, step, b, status[b])
+                n_multi += ms[b] is not None and ms[b].num_stacks() > 1
+            alive = [b for b in range(B) if ms[b] is not None]
+            if len(alive) < B:
+                # drop rows that left the device's limits: rebuild the batch from the remaining host matchers
+                ms = [ms[b] for b in alive]
+                oms = [oms[b] for b in alive]
+                frozen = frozen[alive]
+                B = len(ms)
+                batch = xgm.DeviceBatch(ms, history=2, stream=_stream())
+                d_dev = torch.zeros((B, 1), dtype=torch.int32, device="cuda")
+                d_host = torch.zeros((B, 1), dtype=torch.int32, device="cuda")
+                continue
+        B = len(texts)
+    say(f"  {n_checked} masks of random grammars bit-exact on both paths; {n_multi} steps with parallel stacks; {n_host} through the host")
+    assert n_checked > 400 and n_multi > 20

@@ -513,3 +513,90 @@ def test_plan_placement_is_a_bijection_that_keeps_neighbours_on_one_xcd():
             assert same == ((p + 1) % per != 0)
     with pytest.raises(xgm.XgmError):
         xgm.debug_plan_slot(5, 5)
+
+
+def _random_grammar_text(rng) -> str:
+    """A small random grammar over the bytes a-d, '(' and ')': nested groups, repetition, optional parts,
+    references (also recursive and in tail position), empty alternatives - the shapes that produce
+    parallel stacks, tail calls, shortcuts and returns through several frames."""
+    n_rules = int(rng.integers(2, 6))
+    names = ["root"] + [f"r{k}" for k in range(1, n_rules)]
+
+    def item(depth):
+        u = rng.random()
+        if u < 0.40 or depth > 2:
+            lit = "".join(rng.choice(list("abcd()")) for _ in range(int(rng.integers(1, 4))))
+            return '"' + lit + '"'
+        if u < 0.55:
+            return "[" + "".join(sorted(set(rng.choice(list("abcd"), size=int(rng.integers(1, 4)))))) + "]"
+        if u < 0.80:
+            return names[int(rng.integers(0, n_rules))]
+        return "( " + alts(depth + 1) + " )"
+
+    def seq(depth):
+        parts = []
+        for _ in range(int(rng.integers(1, 4))):
+            parts.append(item(depth) + rng.choice(["", "", "", "*", "+", "?"]))
+        return " ".join(parts)
+
+    def alts(depth):
+        k = int(rng.integers(1, 4))
+        out = [seq(depth) for _ in range(k)]
+        if rng.random() < 0.15:
+            out.append('""')
+        return " | ".join(out)
+
+    return "\n".join(f"{name} ::= {alts(0)}" for name in names) + "\n"
+
+
+def test_depth_first_accept_on_random_grammars():
+    """Seeded random grammars (those the library accepts: no left recursion, productive root): for random
+    byte strings fed a few bytes at a time as tokens, the depth-first accept (what the device runs), the
+    host engine and the oracle's recogniser agree on every verdict, and the two library routes on the stacks."""
+    rng = np.random.Generator(np.random.PCG64(424242))
+    pieces = [bytes(p) for p in (b"a", b"b", b"c", b"d", b"(", b")", b"ab", b"ba", b"a(", b")b", b"cd)", b"((", b"))", b"abc", b"dcba", b"(a)")]
+    vocab = TinyVocab(pieces + [b""], [len(pieces)])
+    n_grammars = n_multi = n_steps = 0
+    for trial in range(400):
+        text = _random_grammar_text(rng)
+        try:
+            g = xgm.Grammar(text, "root")
+        except xgm.XgmError as e:
+            assert e.status in (-4, -5), (text, e)    # left recursion, or nothing derivable
+            continue
+        og = oracle.Grammar(text, "root")
+        v = xgm.Vocab(vocab.data, vocab.offsets, vocab.stop_ids)
+        n_grammars += 1
+        for walk in range(6):
+            m1, m2 = xgm.Matcher(grammar=g, vocab=v), xgm.Matcher(grammar=g, vocab=v)
+            prefix = b""
+            for step in range(12):
+                assert m1.can_terminate() == (og.recognize(prefix) == 2), (text, prefix)
+                order = rng.permutation(len(pieces))
+                moved = False
+                for t in order:
+                    rc1 = m1.try_accept_token(int(t))
+                    rc2 = m2.debug_try_accept_token_walk(int(t))
+                    want = og.recognize(prefix + pieces[t]) > 0
+                    if rc1 == -8:          # more than 64 parallel stacks: the engine gives up, state unchanged
+                        assert want
+                        if rc2 == 0:       # the walk has no such limit: put its matcher back
+                            m2 = xgm.Matcher(grammar=g, vocab=v)
+                            assert prefix == b"" or m2.try_accept_bytes(prefix) == 0
+                            _same_state(m1, m2)
+                        continue
+                    assert (rc1 == 0) == want, (text, prefix, pieces[t], rc1)
+                    assert rc2 == rc1 or (rc2 == -9 and rc1 == 0), (text, prefix, pieces[t], rc1, rc2)
+                    if rc2 == -9:          # the walk's limits; take the host's state on both sides
+                        m2 = xgm.Matcher(grammar=g, vocab=v)
+                        assert m2.try_accept_bytes(prefix + pieces[t]) == 0
+                    _same_state(m1, m2)
+                    n_steps += 1
+                    if rc1 == 0:
+                        prefix += pieces[t]
+                        n_multi += m1.num_stacks() > 1
+                        moved = True
+                        break
+                if not moved:
+                    break
+    assert n_grammars > 100 and n_steps > 3000 and n_multi > 100, (n_grammars, n_steps, n_multi)
