@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0                      # MI355X HBM3E, published
 # Set to None whenever a kernel changes after the counters were taken.
 TRAFFIC_FILL_BYTES = 13.9e6
 TRAFFIC_APPLY_BYTES = 33.9e6
-TRAFFIC_FUSED_BYTES = 44.2e6
+TRAFFIC_FUSED_BYTES = 54.3e6
 
 
 def log(*a):

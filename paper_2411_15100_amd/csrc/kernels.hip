@@ -475,6 +475,42 @@ __device__ __forceinline__ void apply_group(unsigned char* p, uint32_t mk, int32
   }
 }
 
+// The logits of one workgroup of the fused kernel: its request's row, the
+// elements [e_begin, e_end) that its mask words in LDS cover (section 2.1).
+// APPLY = bytes per logit; 0 = the kernel leaves the logits alone.
+template <int APPLY>
+struct LogitsRange {
+  unsigned char* row;
+  const uint32_t* words;  // the workgroup's mask words; bit 0 of words[0] is element e_begin
+  int32_t e_begin, e_end, V, V_logits;
+  uint32_t neg_inf;
+  // thread t of nt: the range's groups t, t + nt, ...  (One group after the other: fetching the groups
+  // that must be read several at a time made the launch longer, not shorter.)
+  __device__ __forceinline__ void groups(uint32_t t, uint32_t nt) const {
+    if constexpr (APPLY != 0) {
+      constexpr int EPT = 16 / APPLY;
+      constexpr uint32_t kAll = (1u << EPT) - 1u;
+      for (int32_t e0 = e_begin + (int32_t)t * EPT; e0 < e_end; e0 += (int32_t)nt * EPT) {
+        uint32_t mk = 0u;
+        if (e0 < V) {
+          mk = (words[(e0 - e_begin) >> 5] >> (e0 & 31)) & kAll;
+          if (e0 + EPT > V) mk &= (1u << (V - e0)) - 1u;
+        }
+        apply_group<APPLY>(row + (size_t)e0 * APPLY, mk, e0, V_logits, neg_inf);
+      }
+    }
+  }
+  // one element by itself
+  __device__ __forceinline__ void reject(int32_t id) const {
+    if constexpr (APPLY != 0) {
+      if (id < V_logits) {
+        if (APPLY == 2) reinterpret_cast<uint16_t*>(row)[id] = (uint16_t)neg_inf;
+        else reinterpret_cast<uint32_t*>(row)[id] = neg_inf;
+      }
+    }
+  }
+};
+
 // ---------------------------------------------------------------- kernel (b)
 // The per-step stack upload: a plain copy from pinned host memory (which the
 // device reads over the bus) into device memory, as a kernel on the caller's
@@ -490,6 +526,7 @@ __global__ __launch_bounds__(kUploadThreads) void upload_kernel(const uint4* __r
 constexpr int kFillThreads = 1024;
 constexpr int kFillQueue = 4096;                // survivors walked per round
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
+constexpr uint32_t kQueueRejected = 1u << 23;   // in a queue entry: walked and found disallowed (see fill_lists)
 
 // accumulates a 256-bit set into 8 LDS words
 struct LdsSetAcc {
@@ -518,13 +555,19 @@ struct LdsSetAcc {
 //      an LDS queue (one LDS atomic per wave);
 //   3. the queue is walked with all lanes busy; allowed tokens are ORed into
 //      the words with LDS atomics;
-//   4. the stop tokens are added and the words stored once, coalesced.
+//   4. the words are stored once, coalesced (the stop tokens were added in 1).
 // No global atomics, no second pass over the mask.
+// When the kernel also masks the logits, the last walks of a workgroup - a
+// few tokens in one wave, as a rule, and what the whole launch ends up waiting
+// for - run beside that work instead of in front of it: queued tokens count as
+// allowed for the moment, the waves without a walk write -inf for everything
+// else in the workgroup's range, and the tokens whose walk says no get theirs
+// after the walks (one element each).
 // COUNT = true additionally sums the automaton steps of all walks into
 // *step_counter (instrumentation for the benchmark; never used on the hot path).
 struct FillShared {
   uint32_t words[kFillMaxChunks * kChunkWords];
-  uint32_t queue[kFillQueue];     // late exit position << 24 | (chunk - c0) << 16 | kind << 12 | local id
+  uint32_t queue[kFillQueue];     // late exit position << 24 | kQueueRejected | (chunk - c0) << 16 | kind << 12 | local id
   uint16_t live[kFillFramesLds];
   uint32_t hdr[kStackHdrWords];   // the current stack's header: top, depth, frame offset, and 2 x 256 bits: the
                                   // bytes consumable from the stack / from the stack without its top frame
@@ -564,15 +607,19 @@ __device__ __forceinline__ void stage_stack_header(FillShared& sm, const XGM_GLO
   else if (tid - kStackHdrWords <= (uint32_t)(c1 - c0)) sm.off[tid - kStackHdrWords] = sh[kStackHdrWords + c0 + tid - kStackHdrWords];
 }
 
-template <bool COUNT, bool KEEP_UNDECIDED, class Tab>
-__device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b,
+// Returns true if it has also written the logits of the workgroup's range (`logits`; only with APPLY != 0).
+template <bool COUNT, int APPLY, class Tab>
+__device__ __forceinline__ bool fill_lists(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b,
                                            const int32_t c0, const int32_t c1, const uint32_t frame0,
                                            const bool frames_in_lds,
                                            const XGM_GLOBAL uint32_t* __restrict__ stack_hdrs,
                                            const XGM_GLOBAL uint16_t* __restrict__ frames, const DevVocab& voc,
                                            OverflowLog* log, uint32_t seq, unsigned long long& my_steps,
                                            const uint32_t pair_min_entries,
-                                           const XGM_GLOBAL uint32_t* __restrict__ pair_tables) {
+                                           const XGM_GLOBAL uint32_t* __restrict__ pair_tables,
+                                           const LogitsRange<APPLY>& logits) {
+  constexpr bool KEEP_UNDECIDED = APPLY != 0;
+  bool logits_done = false;
   const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
   const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
   const XGM_GLOBAL uint32_t* unc_list = (const XGM_GLOBAL uint32_t*)rd.unc_list;
@@ -599,17 +646,25 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
     const bool use_pair = depth >= 2 && (have_table || sm.off[c1 - c0] - sm.off[0] >= pair_min_entries);
     if (use_pair) {
       if (have_table) {
-        const XGM_GLOBAL uint32_t* table = pair_tables + ((size_t)b * kBatchMaxStacks + s) * kPairWords;
-        for (uint32_t k = tid; k < kPairWords; k += kFillThreads) sm.pair[k] = table[k];
-        __syncthreads();
+        if (s > 0) {  // the first stack's table came in with the workgroup's first fetches
+          const XGM_GLOBAL uint32_t* table = pair_tables + ((size_t)b * kBatchMaxStacks + s) * kPairWords;
+          for (uint32_t k = tid; k < kPairWords; k += kFillThreads) sm.pair[k] = table[k];
+          __syncthreads();
+        }
       } else {
         build_pair_table<kFillThreads>(T, sm.pair, sm.hdr + kStackHdrBelow, below, live, depth, node_first, voc);
       }
     }
-    // rounds of chunks whose lists together fit the queue (one chunk always fits)
+    // The last stack's queued tokens count as allowed until they have been walked (see above).
+    const bool last_stack = APPLY != 0 && s + 1 == rd.n_stacks;
+    // Rounds of chunks whose lists together fit the queue even if every entry survived (one chunk always
+    // fits).  Few do survive, so the survivors of a round are only walked when the queue might not hold
+    // the next round's as well: as a rule a workgroup walks once, after its last round.
     for (int32_t ca = c0; ca < c1;) {
       int32_t cb = ca + 1;
       while (cb < c1 && sm.off[cb + 1 - c0] - sm.off[ca - c0] <= (uint32_t)kFillQueue) ++cb;
+      // the last walks of the workgroup: the logits are written beside them
+      const bool beside = last_stack && cb == c1;
       // 2. filter + compact: the lists of consecutive chunks are contiguous, so one flat pass reads them all
       const uint32_t j_begin = sm.off[ca - c0], j_end = sm.off[cb - c0];
       for (uint32_t j = j_begin + (tid & ~63u); j < j_end; j += kFillThreads) {
@@ -658,16 +713,28 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
           uint32_t base = 0;
           if (lane == 0) base = atomicAdd(&sm.queue_n, (uint32_t)__popcll(m));
           base = __shfl(base, 0, 64);
-          if (keep)
+          if (keep) {
             sm.queue[base + __popcll(m & ((1ull << lane) - 1ull))] = (late_exit << 24) | (cl << 16) | (meta << 12) | lid;
+            if (last_stack) atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));  // allowed for the moment
+          }
         }
       }
       __syncthreads();
-      // 3. walk the survivors
+      // 3. walk the survivors, unless the queue has room for all that the next round can add
       const uint32_t nq = sm.queue_n;
+      if (cb < c1) {
+        int32_t cn = cb + 1;
+        while (cn < c1 && sm.off[cn + 1 - c0] - sm.off[cb - c0] <= (uint32_t)kFillQueue) ++cn;
+        if (nq + (sm.off[cn - c0] - sm.off[cb - c0]) <= (uint32_t)kFillQueue) {
+          ca = cb;
+          continue;
+        }
+      }
+      const uint32_t first_free = (min(nq, (uint32_t)kFillThreads) + 63u) & ~63u;  // the waves from here on have no walk
+      if (beside && tid >= first_free) logits.groups(tid - first_free, kFillThreads - first_free);
       for (uint32_t q = tid; q < nq; q += kFillThreads) {
         const uint32_t e = sm.queue[q];
-        const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, cl = (e >> 16) & 0xFFu, late_exit = e >> 24;
+        const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, cl = (e >> 16) & 0x7Fu, late_exit = e >> 24;
         const int32_t id = (c0 + (int32_t)cl) * kChunkTokens + (int32_t)lid;
         const uint4 tk = voc.tok_by_id[id];
         int len = (int)(tk.w >> 24);
@@ -683,11 +750,28 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
         const int res = walk_token<false>(T, tk, ext, len, full ? top : below, live, full ? depth : depth - 1,
                                           COUNT ? &n_steps : nullptr, (const uint32_t*)nullptr, i0);
         if (COUNT) my_steps += n_steps;
-        if (res == kAccept) atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
-        else if (res == kOverflow) {
+        if (last_stack) {
+          if (res == kReject) {
+            atomicAnd(&sm.words[cl * kChunkWords + (lid >> 5)], ~(1u << (lid & 31)));
+            if (beside) sm.queue[q] = e | kQueueRejected;
+          } else if (res == kOverflow) {
+            record_overflow(log, seq, (uint32_t)b, (uint32_t)id);  // stays allowed until the host has decided it
+          }
+        } else if (res == kAccept) {
+          atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
+        } else if (res == kOverflow) {
           record_overflow(log, seq, (uint32_t)b, (uint32_t)id);
           if (KEEP_UNDECIDED) atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
         }
+      }
+      if (beside) {
+        if (first_free >= (uint32_t)kFillThreads) logits.groups(tid, kFillThreads);  // every wave had walks
+        __syncthreads();  // the group stores above come first
+        for (uint32_t q = tid; q < nq; q += kFillThreads) {
+          const uint32_t e = sm.queue[q];
+          if (e & kQueueRejected) logits.reject((c0 + (int32_t)((e >> 16) & 0x7Fu)) * kChunkTokens + (int32_t)(e & 0xFFFu));
+        }
+        logits_done = true;
       }
       __syncthreads();
       if (tid == 0) sm.queue_n = 0u;
@@ -695,6 +779,7 @@ __device__ __forceinline__ void fill_lists(const Tab& T, FillShared& sm, const R
       ca = cb;
     }
   }
+  return logits_done;
 }
 
 // Two workgroups of 16 waves per compute unit need 8 waves per SIMD: the second
@@ -740,11 +825,18 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   // header with its list offsets, and (below) the accepted words
   const uint32_t frame0 = rd.frame_begin, n_frames = rd.n_frames;
   const bool frames_in_lds = n_frames <= kFillFramesLds;
+  // may the request end here?  then its stop tokens are allowed (the first kFillThreads of them are fetched now)
+  const bool may_end = rd.flags & 1u;
+  const int32_t my_stop = may_end && (int32_t)tid < voc.n_stop ? voc.stop_ids[tid] : -1;
   if (has_cache) {
     stage_tables(rd.tab, smem, kFillThreads);
     if (frames_in_lds)
       for (uint32_t k = tid; k < n_frames; k += kFillThreads) sm.live[k] = frames[frame0 + k];
     stage_stack_header(sm, stack_hdrs + (size_t)rd.stack_begin * hdr_stride, c0, c1);
+    if (fa.pair_tables != nullptr && (rd.pair_mask & 1u)) {  // the first stack's two-byte table, computed ahead
+      const XGM_GLOBAL uint32_t* table = (const XGM_GLOBAL uint32_t*)fa.pair_tables + (size_t)b * kBatchMaxStacks * kPairWords;
+      for (uint32_t k = tid; k < kPairWords; k += kFillThreads) sm.pair[k] = table[k];
+    }
   }
   // 1. accepted words
   const XGM_GLOBAL uint32_t* acc = (const XGM_GLOBAL uint32_t*)rd.acc;
@@ -758,39 +850,38 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   }
   if (tid == 0) sm.queue_n = 0u;
   __syncthreads();
-  if (has_cache) {
-    if (small_sections_staged(rd.tab))
-      fill_lists<COUNT, (APPLY != 0)>(LdsTabT<true>(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs,
-                                      frames, voc, log, seq, my_steps, fa.pair_min_entries,
-                                      (const XGM_GLOBAL uint32_t*)fa.pair_tables);
-    else
-      fill_lists<COUNT, (APPLY != 0)>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs, frames, voc,
-                                      log, seq, my_steps, fa.pair_min_entries, (const XGM_GLOBAL uint32_t*)fa.pair_tables);
-  }
-  if (rd.flags & 1u) {
+  if (may_end) {
     for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
-      const int32_t rel = voc.stop_ids[k] - w_begin * 32;
+      const int32_t rel = (k == (int32_t)tid ? my_stop : voc.stop_ids[k]) - w_begin * 32;
       if (rel >= 0 && rel < n_words * 32) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31));
     }
+    __syncthreads();  // a stop token with bytes may also be listed: the lists must find its bit set
+  }
+  // this workgroup's logits: its chunks; the last workgroup of a row also takes the columns beyond the vocabulary
+  LogitsRange<APPLY> logits;
+  if (APPLY != 0) {
+    logits.row = fa.logits + (size_t)b * fa.row_stride * APPLY;
+    logits.words = sm.words;
+    logits.e_begin = w_begin * 32;
+    logits.e_end = c1 == voc.n_chunk ? fa.V_logits : min(c1 * kChunkTokens, fa.V_logits);
+    logits.V = voc.V;
+    logits.V_logits = fa.V_logits;
+    logits.neg_inf = fa.neg_inf;
+  }
+  bool logits_done = false;
+  if (has_cache) {
+    if (small_sections_staged(rd.tab))
+      logits_done = fill_lists<COUNT, APPLY>(LdsTabT<true>(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds,
+                                             stack_hdrs, frames, voc, log, seq, my_steps, fa.pair_min_entries,
+                                             (const XGM_GLOBAL uint32_t*)fa.pair_tables, logits);
+    else
+      logits_done = fill_lists<COUNT, APPLY>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs,
+                                             frames, voc, log, seq, my_steps, fa.pair_min_entries,
+                                             (const XGM_GLOBAL uint32_t*)fa.pair_tables, logits);
   }
   __syncthreads();
   for (int32_t w = tid; w < n_words; w += kFillThreads) out[(size_t)b * voc.W + w_begin + w] = sm.words[w];
-  if (APPLY != 0) {
-    constexpr int EPT = 16 / (APPLY ? APPLY : 2);
-    constexpr uint32_t kAll = (1u << EPT) - 1u;
-    // this workgroup's logits: its chunks; the last workgroup of a row also takes the columns beyond the vocabulary
-    const int32_t e_begin = w_begin * 32;
-    const int32_t e_end = c1 == voc.n_chunk ? fa.V_logits : min(c1 * kChunkTokens, fa.V_logits);
-    unsigned char* lrow = fa.logits + (size_t)b * fa.row_stride * (APPLY ? APPLY : 2);
-    for (int32_t e0 = e_begin + (int32_t)tid * EPT; e0 < e_end; e0 += kFillThreads * EPT) {
-      uint32_t mk = 0u;
-      if (e0 < voc.V) {
-        mk = (sm.words[(e0 - e_begin) >> 5] >> (e0 & 31)) & kAll;
-        if (e0 + EPT > voc.V) mk &= (1u << (voc.V - e0)) - 1u;
-      }
-      apply_group<(APPLY ? APPLY : 2)>(lrow + (size_t)e0 * (APPLY ? APPLY : 2), mk, e0, fa.V_logits, fa.neg_inf);
-    }
-  }
+  if (!logits_done) logits.groups(tid, kFillThreads);
   if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
 }
 
