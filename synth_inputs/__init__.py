@@ -15,6 +15,7 @@ from .grammars import (
     JSON_GRAMMAR,
     CSQL_GRAMMAR,
     XML_GRAMMAR,
+    PYDSL_GRAMMAR,
     make_schema_grammar,
     random_schema,
 )
@@ -29,6 +30,7 @@ __all__ = [
     "JSON_GRAMMAR",
     "CSQL_GRAMMAR",
     "XML_GRAMMAR",
+    "PYDSL_GRAMMAR",
     "make_schema_grammar",
     "random_schema",
     "make_logits",

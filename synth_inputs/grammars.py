@@ -67,6 +67,46 @@ ws1      ::= [ \t\n]+
 """
 
 # ---------------------------------------------------------------------------
+# A small scripting language in the style of Python, kept context-free by
+# giving every compound statement a one-line body.  Every sentence is also a
+# Python module (names start with one of x z u v or an underscore, so none
+# is a keyword; integers have no leading zeros; attribute access never follows
+# a number).  Word operators ("not in", "is not", "if ... else") next to
+# names and the two quote styles give the walks alternatives to carry.
+# ---------------------------------------------------------------------------
+PYDSL_GRAMMAR = r"""
+root     ::= line (nl line)* nl?
+nl       ::= "\n"+
+line     ::= stmt (sp "#" [^\n\x00-\x1f]*)?
+stmt     ::= simple | "if " expr ":" sp simple (nl "elif " expr ":" sp simple)* (nl "else:" sp simple)?
+           | "while " expr ":" sp simple | "for " name " in " expr ":" sp simple
+           | "def " name "(" sp (name (sp "," sp name)*)? sp "):" sp simple
+simple   ::= small (sp ";" sp small)*
+small    ::= "pass" | "break" | "continue" | "return" (" " expr)? | target sp assignop sp expr | expr
+target   ::= name ( "." name | "[" sp expr sp "]" )*
+assignop ::= "=" | "+=" | "-=" | "*=" | "/=" | "//=" | "%="
+expr     ::= "lambda" (" " name (sp "," sp name)*)? ":" sp expr | ternary
+ternary  ::= or_e (" if " or_e " else " expr)?
+or_e     ::= and_e (" or " and_e)*
+and_e    ::= not_e (" and " not_e)*
+not_e    ::= "not " not_e | cmp
+cmp      ::= arith (cmpop arith)*
+cmpop    ::= sp ("==" | "!=" | "<=" | ">=" | "<" | ">") sp | " in " | " not in " | " is " | " is not "
+arith    ::= term (sp [+\-] sp term)*
+term     ::= factor (sp ("*" | "//" | "/" | "%") sp factor)*
+factor   ::= [+\-~] factor | power
+power    ::= atom (sp "**" sp factor)?
+atom     ::= primary trailer* | number | string | "True" | "False" | "None"
+primary  ::= name | "(" sp expr sp ")" | "[" sp (expr (sp "," sp expr)*)? sp "]"
+           | "{" sp (expr sp ":" sp expr (sp "," sp expr sp ":" sp expr)*)? sp "}"
+trailer  ::= "(" sp (expr (sp "," sp expr)*)? sp ")" | "[" sp expr sp "]" | "." name
+name     ::= [xzuv_] [A-Za-z0-9_]*
+number   ::= ("0" | [1-9] [0-9]*) ("." [0-9]+)?
+string   ::= "\"" ([^"\\\n\x00-\x1f] | "\\" ["\\'nt])* "\"" | "'" ([^'\\\n\x00-\x1f] | "\\" ["\\'nt])* "'"
+sp       ::= " "*
+"""
+
+# ---------------------------------------------------------------------------
 # Workload 4(ii): a C/SQL-like language, about 60 rules.  Iterative (never
 # left-recursive) precedence chain, keywords, identifiers, literals with
 # escapes, blocks and embedded SELECT statements.

@@ -88,7 +88,7 @@ class _Rows:
             assert _stacks(self.scratch[b]) == _stacks(self.ms[b]), f"row {b}"
 
 
-MIXED = [(si.JSON_GRAMMAR, "root"), (si.CSQL_GRAMMAR, "root"), (si.XML_GRAMMAR, "root"), (si.ARITH_GRAMMAR, "expr"),
+MIXED = [(si.JSON_GRAMMAR, "root"), (si.CSQL_GRAMMAR, "root"), (si.XML_GRAMMAR, "root"), (si.ARITH_GRAMMAR, "expr"), (si.PYDSL_GRAMMAR, "root"),
          (si.make_schema_grammar(0, string_heavy=True), "root"), (si.make_schema_grammar(1), "root"),
          (si.JSON_GRAMMAR, "root"), (si.make_schema_grammar(2, string_heavy=True), "root")]
 

@@ -276,6 +276,39 @@ def test_markup_grammar_every_step_and_every_node(xgm, wl):
 
 
 # --------------------------------------------------------------------------
+# a third grammar family: a scripting language with word operators and one-line bodies
+# --------------------------------------------------------------------------
+def test_scripting_grammar_every_step_and_every_node(xgm, wl):
+    say("scripting grammar: V=32000 B=2 steps=160, classes at every node")
+    vocab = si.make_vocab("bpe", 32000, 0)
+    g = xgm.Grammar(si.PYDSL_GRAMMAR, "root")
+    cache = xgm.Cache(g, wl.make_xgm_vocab(vocab), keep_plain=True)
+    og = oracle.Grammar(si.PYDSL_GRAMMAR, "root")
+    _check_cache_classes(xgm, cache, g, og, vocab, range(g.num_nodes))
+    walker = wl.BatchWalker([cache, cache], vocab, seed=23, structural_bias=0.5)
+    oms = [oracle.EarleyMatcher(og) for _ in range(2)]
+    toks = vocab.tokens()
+    n_multi = n_fixed = 0
+    for step in range(160):
+        words = walker.fill()
+        fixed = xgm.fill_overflow_fixup(_stream())
+        if fixed:
+            n_fixed += fixed
+            words = walker.d_mask.cpu().numpy()
+        want = np.stack([om.mask(vocab) for om in oms])
+        assert np.array_equal(words, oracle.pack_bitmask(want)), f"step {step}"
+        n_multi += sum(m.num_stacks() > 1 for m in walker.matchers)
+        picks = walker.step(words)
+        for b in range(2):
+            if not walker.history[b]:
+                oms[b] = oracle.EarleyMatcher(og)
+            else:
+                assert oms[b].advance(toks[int(picks[b])])
+    say(f"  nodes {g.num_nodes}; (row, step) pairs with several parallel stacks: {n_multi}; build pairs on the host: "
+        f"{cache.host_classified}; fill pairs fixed up: {n_fixed}")
+
+
+# --------------------------------------------------------------------------
 # fused fill + apply: same masks, same logits as the two calls / as the oracle
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype_name,V,pad", [("bf16", 4100, 0), ("f32", 4100, 0), ("f16", 4099, 13), ("bf16", 9000, 24)])

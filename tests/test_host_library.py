@@ -24,6 +24,7 @@ GRAMMARS = {
     "json": (si.JSON_GRAMMAR, "root", b' \n"{}[],:\\/abfnrtu0123456789.eE+-\xc3\xa9\xe4\xb8\xad\xf0\x9f\x98\x80xyz'),
     "csql": (si.CSQL_GRAMMAR, "root", b" \n(){}[];,.*+-/%<>=!&|^~?:'\"\\_abcdefhilnorstuwxSELCTFROMWHNDBYGUPIAV0123459"),
     "xml": (si.XML_GRAMMAR, "root", b" \n\t<>/=\"'&;#!-._abcxyzAZ019"),
+    "pydsl": (si.PYDSL_GRAMMAR, "root", b" \n()[]{}:;,.=+-*/%<>!~#'\"\\xzuv_ab019ifelsnotrdwhpcTFNm"),
     "schema": (si.make_schema_grammar(3), "root", b' \n"{}[],:\\abcdefghijklmnopqrstuvwxyz_0123456789.eE+-tfu'),
 }
 
