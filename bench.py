@@ -292,6 +292,14 @@ def main():
         cache_build["serving_set_up"] = {"pairs": work.build_pairs, "kernel_s": work.build_kernel_seconds,
                                          "pairs_per_s": pps, "steps_per_pair": sps, "steps_per_s": sps * pps,
                                          "lookups_vs_ceiling": 4.0 * sps * pps / lds_rate}
+        nodes = sum(c.num_nodes for c in work.caches)
+        kept = sum(c.num_accept_rows for c in work.caches)
+        held = sum(c.device_bytes for c in work.caches)
+        row_bytes = 4 * xgm.bitmask_words(work.V)
+        cache_build["serving_storage"] = {"caches": len(work.caches), "nodes": nodes, "accepted_bitsets_kept": kept,
+                                          "device_bytes": held,
+                                          "accepted_bitset_bytes_saved": (nodes - kept) * row_bytes,
+                                          "note": "the distinct accepted bitsets of a grammar's nodes are kept once each"}
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu_baseline = None

@@ -195,6 +195,11 @@ double xgm_cache_build_kernel_seconds(const xgm_cache* c);
  * the copies of sizes back to the host, allocation; the vocabulary upload only
  * on the first build that uses it). */
 double xgm_cache_build_seconds(const xgm_cache* c);
+/* Section 3.1 (storage of the cache): many nodes have the same accepted bitset; the cache keeps every
+ * distinct one once.  Number of distinct bitsets (<= number of nodes), and the bytes of device memory
+ * the cache holds (bitsets, lists with their per-context classes, offsets, table image).  Negative: error. */
+int32_t xgm_cache_num_accept_rows(const xgm_cache* c);
+int64_t xgm_cache_device_bytes(const xgm_cache* c);
 
 /* The exact host routine that decides a (node, token) pair whose GPU walk
  * exceeded its limits during xgm_cache_build: 0 rejected, 1 context-dependent,

@@ -56,6 +56,8 @@ SIGNATURES = {
     "xgm_cache_host_classified": (_i64, [_vp]),
     "xgm_cache_build_kernel_seconds": (ctypes.c_double, [_vp]),
     "xgm_cache_build_seconds": (ctypes.c_double, [_vp]),
+    "xgm_cache_num_accept_rows": (_i32, [_vp]),
+    "xgm_cache_device_bytes": (ctypes.c_int64, [_vp]),
     "xgm_matcher_create": (_i32, [_vp, _pp]),
     "xgm_matcher_create_host": (_i32, [_vp, _vp, _pp]),
     "xgm_matcher_destroy": (None, [_vp]),
@@ -295,6 +297,16 @@ class Cache:
     @property
     def build_seconds(self) -> float:
         return load_library().xgm_cache_build_seconds(self._h)
+
+    @property
+    def num_accept_rows(self) -> int:
+        """Distinct accepted bitsets kept (at most one per node)."""
+        return _check(load_library().xgm_cache_num_accept_rows(self._h))
+
+    @property
+    def device_bytes(self) -> int:
+        """Bytes of device memory the cache holds."""
+        return int(load_library().xgm_cache_device_bytes(self._h))
 
     def copy_node_bits(self, node: int):
         W = bitmask_words(self.vocab.size)

@@ -9,6 +9,7 @@
 #include <numeric>
 #include <string>
 #include <set>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/xgm.h"
@@ -141,6 +142,9 @@ struct xgm_cache {
   DevCache host{};           // device pointers and table layout
   std::vector<void*> dev_ptrs;
   std::vector<uint32_t> unc_off_host;  // [n_nodes][n_chunk+1]
+  std::vector<uint16_t> acc_row_host;  // [n_nodes] the node's row among the distinct accepted bitsets
+  int32_t n_acc_rows = 0;
+  int64_t device_bytes = 0;            // device memory the cache holds
   std::vector<uint32_t> plain_count;   // [n_nodes] tokens that only section 3.1 calls context-dependent
   uint32_t* d_plain_id = nullptr;      // [n_nodes][W] their bitsets, if kept
   int64_t host_classified = 0;
@@ -571,6 +575,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     // automaton tables
     static_assert(sizeof(NodeHdr) == sizeof(uint2), "header layout");
     DevTables tab{};
+    size_t image_bytes = 0;
     {
       std::vector<unsigned char> img;
       auto put = [&](const void* src, size_t bytes, size_t align) {
@@ -589,6 +594,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       tab.off_hdr = put(A.hdr.data(), (size_t)N * sizeof(uint2), 16);
       tab.off_first = put(A.node_first_words.data(), A.node_first_words.size() * 4, 16);
       img.resize((img.size() + 15) / 16 * 16, 0);
+      image_bytes = img.size();
       std::vector<uint4> image(img.size() / 16);
       std::memcpy(image.data(), img.data(), img.size());
       tab.image = keep(slab_upload(image));
@@ -597,7 +603,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       tab.n_nodes = N;
     }
 
-    uint32_t* acc_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W));
+    uint32_t* acc_id = temp(dev_alloc<uint32_t>((size_t)N * dv.W));  // one row per node; the distinct rows are kept
     uint32_t* unc_id = temp(dev_alloc<uint32_t>((size_t)N * dv.W));
     // rank-space scratch for a batch of nodes (at most 1 GiB for both bitsets)
     const size_t row_bytes = (size_t)dv.WR * 4;
@@ -670,6 +676,47 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     }
     (void)hipEventDestroy(ev0);
     (void)hipEventDestroy(ev1);
+    // the distinct accepted bitsets: rows with equal digests are compared with the first of them
+    uint32_t* acc_rows = nullptr;
+    uint16_t* d_acc_row = nullptr;
+    {
+      unsigned long long* d_digest = temp(dev_alloc<unsigned long long>((size_t)N));
+      launch_hash_rows(acc_id, N, dv.W, d_digest, stream);
+      HIP_OK(hipGetLastError());
+      HIP_OK(hipStreamSynchronize(stream));
+      std::vector<unsigned long long> digest((size_t)N);
+      HIP_OK(hipMemcpy(digest.data(), d_digest, digest.size() * 8, hipMemcpyDeviceToHost));
+      std::unordered_map<unsigned long long, int32_t> first_with;
+      std::vector<int32_t> rep((size_t)N);
+      for (int32_t n = 0; n < N; ++n) rep[n] = first_with.emplace(digest[n], n).first->second;
+      int32_t* d_rep = temp(dev_upload(rep));
+      uint32_t* d_equal = temp(dev_alloc<uint32_t>((size_t)N));
+      launch_rows_equal(acc_id, N, dv.W, d_rep, d_equal, stream);
+      HIP_OK(hipGetLastError());
+      HIP_OK(hipStreamSynchronize(stream));
+      std::vector<uint32_t> equal((size_t)N);
+      HIP_OK(hipMemcpy(equal.data(), d_equal, equal.size() * 4, hipMemcpyDeviceToHost));
+      std::vector<int32_t> unique;
+      c->acc_row_host.assign((size_t)N, 0);
+      std::vector<int32_t> row_of_rep((size_t)N, -1);
+      for (int32_t n = 0; n < N; ++n) {
+        if (!equal[n]) rep[n] = n;  // same digest, different row: kept by itself
+        if (rep[n] == n) {
+          row_of_rep[n] = (int32_t)unique.size();
+          unique.push_back(n);
+        }
+        c->acc_row_host[n] = (uint16_t)row_of_rep[rep[n]];  // rep[n] <= n: its row is known
+      }
+      if (unique.size() > 0xFFFFu) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: more than 65535 distinct accepted bitsets");
+      c->n_acc_rows = (int32_t)unique.size();
+      acc_rows = keep(slab_alloc<uint32_t>(unique.size() * (size_t)dv.W));
+      int32_t* d_unique = temp(dev_upload(unique));
+      launch_gather_rows(acc_id, dv.W, d_unique, c->n_acc_rows, acc_rows, stream);
+      HIP_OK(hipGetLastError());
+      HIP_OK(hipStreamSynchronize(stream));
+      d_acc_row = keep(slab_upload(c->acc_row_host));
+      c->device_bytes += (int64_t)unique.size() * dv.W * 4 + (int64_t)N * 2;
+    }
     c->plain_count.resize(N);
     HIP_OK(hipMemcpy(c->plain_count.data(), d_plain_count, (size_t)N * 4, hipMemcpyDeviceToHost));
     for (int32_t n : host_plain) ++c->plain_count[n];
@@ -711,7 +758,10 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     cleanup_temps();
 
     c->host.tab = staged_for(tab, kFillLdsBudget);
-    c->host.acc = acc_id;
+    c->host.acc = acc_rows;
+    c->host.acc_row = d_acc_row;
+    c->device_bytes += (int64_t)c->unc_off_host.size() * 4 + (int64_t)total * 8 + (int64_t)image_bytes;
+    if (keep_plain) c->device_bytes += (int64_t)N * dv.W * 4;
     c->host.unc_off = d_off;
     c->host.unc_list = d_list;
     c->host.unc_ctx = d_list_ctx;
@@ -752,12 +802,15 @@ int xgm_cache_copy_node_plain(const xgm_cache* c, int32_t node, int32_t* h_plain
 int64_t xgm_cache_host_classified(const xgm_cache* c) { return c ? c->host_classified : XGM_ERR_BAD_ARG; }
 double xgm_cache_build_kernel_seconds(const xgm_cache* c) { return c ? c->kernel_seconds : -1.0; }
 double xgm_cache_build_seconds(const xgm_cache* c) { return c ? c->build_seconds : -1.0; }
+int32_t xgm_cache_num_accept_rows(const xgm_cache* c) { return c ? c->n_acc_rows : XGM_ERR_BAD_ARG; }
+int64_t xgm_cache_device_bytes(const xgm_cache* c) { return c ? c->device_bytes : XGM_ERR_BAD_ARG; }
 
 int xgm_cache_copy_node_bits(const xgm_cache* c, int32_t node, int32_t* h_acc, int32_t* h_unc) {
   API_BEGIN
   if (!c || node < 0 || node >= c->host.n_nodes) return fail(XGM_ERR_BAD_ARG, "copy_node_bits: bad cache or node");
   const DevVocab& dv = c->v->dv;
-  if (h_acc) HIP_OK(hipMemcpy(h_acc, c->host.acc + (size_t)node * dv.W, (size_t)dv.W * 4, hipMemcpyDeviceToHost));
+  if (h_acc)
+    HIP_OK(hipMemcpy(h_acc, c->host.acc + (size_t)c->acc_row_host[node] * dv.W, (size_t)dv.W * 4, hipMemcpyDeviceToHost));
   if (h_unc) {
     std::memset(h_unc, 0, (size_t)dv.W * 4);
     const uint32_t* off = &c->unc_off_host[(size_t)node * (dv.n_chunk + 1)];
@@ -869,7 +922,7 @@ struct FusedLogits {
 static void pack_stack_header(const Automaton& A, const xgm_cache& c, const Stack& s, uint32_t frame_offset, uint32_t* h) {
   const int32_t n_chunk = c.v->dv.n_chunk;
   const int32_t top = s.back();
-  h[kStackHdrTop] = (uint32_t)top;
+  h[kStackHdrTop] = (uint32_t)top | ((uint32_t)c.acc_row_host[top] << 16);
   h[kStackHdrDepth] = (uint32_t)s.size();
   h[kStackHdrFrames] = frame_offset;
   h[kStackHdrCtx] = kCtxNone;

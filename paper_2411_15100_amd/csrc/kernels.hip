@@ -411,6 +411,56 @@ __global__ __launch_bounds__(kContextThreads) void context_classes_kernel(DevTab
   else body(LdsTab(tab, smem));
 }
 
+// Many nodes of a grammar have the same accepted bitset (the inside of a string is
+// the inside of a string wherever it occurs), so the cache keeps every distinct
+// row once.  The digest only proposes which rows might be equal: the position-
+// dependent mix of every word (the finalizer of splitmix64) is summed over the
+// row; equality is then checked word for word.
+constexpr int kRowThreads = 256;
+__device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
+  x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+  x ^= x >> 27; x *= 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+__global__ __launch_bounds__(kRowThreads) void hash_rows_kernel(const uint32_t* __restrict__ rows, int32_t W,
+                                                                unsigned long long* __restrict__ digest) {
+  __shared__ unsigned long long part[kRowThreads / 64];
+  const uint32_t* row = rows + (size_t)blockIdx.x * W;
+  unsigned long long h = 0ull;
+  for (int32_t w = threadIdx.x; w < W; w += kRowThreads)
+    h += mix64(((unsigned long long)(uint32_t)w << 32 | row[w]) + 0x9E3779B97F4A7C15ull);
+#pragma unroll
+  for (uint32_t d = 32; d > 0; d >>= 1) h += __shfl_down(h, d, 64);
+  if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = h;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long t = 0ull;
+    for (int k = 0; k < kRowThreads / 64; ++k) t += part[k];
+    digest[blockIdx.x] = t;
+  }
+}
+__global__ __launch_bounds__(kRowThreads) void rows_equal_kernel(const uint32_t* __restrict__ rows, int32_t W,
+                                                                 const int32_t* __restrict__ rep,
+                                                                 uint32_t* __restrict__ equal) {
+  __shared__ uint32_t differs;
+  if (threadIdx.x == 0) differs = 0u;
+  __syncthreads();
+  const uint32_t* a = rows + (size_t)blockIdx.x * W;
+  const uint32_t* b = rows + (size_t)rep[blockIdx.x] * W;
+  bool d = false;
+  for (int32_t w = threadIdx.x; w < W; w += kRowThreads) d |= a[w] != b[w];
+  if (d) differs = 1u;
+  __syncthreads();
+  if (threadIdx.x == 0) equal[blockIdx.x] = differs ? 0u : 1u;
+}
+__global__ __launch_bounds__(kRowThreads) void gather_rows_kernel(const uint32_t* __restrict__ rows, int32_t W,
+                                                                  const int32_t* __restrict__ unique,
+                                                                  uint32_t* __restrict__ out) {
+  const uint32_t* src = rows + (size_t)unique[blockIdx.x] * W;
+  uint32_t* dst = out + (size_t)blockIdx.x * W;
+  for (int32_t w = threadIdx.x; w < W; w += kRowThreads) dst[w] = src[w];
+}
+
 __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ items, int32_t n_items,
                                      uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank) {
   const int32_t k = blockIdx.x * blockDim.x + threadIdx.x;
@@ -634,7 +684,7 @@ __device__ __forceinline__ bool fill_lists(const Tab& T, FillShared& sm, const R
       __syncthreads();
     }
     if (sm.off[c1 - c0] == sm.off[0]) continue;  // nothing listed here (uniform)
-    const uint32_t top = sm.hdr[kStackHdrTop], depth = sm.hdr[kStackHdrDepth];
+    const uint32_t top = sm.hdr[kStackHdrTop] & 0xFFFFu, depth = sm.hdr[kStackHdrDepth];
     const uint32_t ctx = sm.hdr[kStackHdrCtx];  // which context of the top's rule the frame below is, or kCtxNone
     LiveView live;
     live.lds = (const XGM_LDS uint16_t*)sm.live + (sm.hdr[kStackHdrFrames] - frame0);
@@ -843,8 +893,8 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   for (int32_t w = tid; w < n_words; w += kFillThreads) {
     uint32_t x = 0u;
     for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-      const uint32_t top = stack_hdrs[(size_t)(rd.stack_begin + s) * hdr_stride + kStackHdrTop];
-      x |= acc[(size_t)top * voc.W + w_begin + w];
+      const uint32_t acc_row = stack_hdrs[(size_t)(rd.stack_begin + s) * hdr_stride + kStackHdrTop] >> 16;
+      x |= acc[(size_t)acc_row * voc.W + w_begin + w];
     }
     sm.words[w] = x;
   }
@@ -969,7 +1019,7 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       const uint16_t* fr = bt.frames + h[kStackHdrFrames];
       LdsStackSink sink{cand, cdepth, &ccount, &coverflow, kBatchMaxCandidates, kBatchMaxDepth};
       const CollectStacks<LdsTab, LdsStackSink> collect{&T, &sink};
-      const int res = walk_token<false>(T, tk, ext, len, h[kStackHdrTop], fr, h[kStackHdrDepth], (uint32_t*)nullptr,
+      const int res = walk_token<false>(T, tk, ext, len, h[kStackHdrTop] & 0xFFFFu, fr, h[kStackHdrDepth], (uint32_t*)nullptr,
                                         (const uint32_t*)nullptr, 0, (uint32_t*)nullptr, collect);
       if (res == kOverflow) coverflow = 1u;
     }
@@ -1023,7 +1073,7 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       const uint16_t* st = cand + ci * kBatchMaxDepth;
       uint32_t* h = bt.hdrs + (size_t)(sb + tid) * hdr_stride;
       const uint32_t top = st[d - 1];
-      h[kStackHdrTop] = top;
+      h[kStackHdrTop] = top | ((uint32_t)dc.acc_row[top] << 16);
       h[kStackHdrDepth] = d;
       h[kStackHdrFrames] = fb + foff[tid];
       uint32_t ctx = kCtxNone;
@@ -1364,6 +1414,17 @@ void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* acc_rank, co
   while (per_block > 1 && (n + per_block - 1) / per_block < 512) --per_block;
   hipLaunchKernelGGL(permute_kernel, dim3((n + per_block - 1) / per_block), dim3(kPermuteThreads),
                      row_pair * per_block, stream, voc, n, per_block, acc_rank, unc_rank, acc_id, unc_id);
+}
+
+void launch_hash_rows(const uint32_t* rows, int32_t n, int32_t W, unsigned long long* digest, hipStream_t stream) {
+  if (n > 0) hipLaunchKernelGGL(hash_rows_kernel, dim3(n), dim3(kRowThreads), 0, stream, rows, W, digest);
+}
+void launch_rows_equal(const uint32_t* rows, int32_t n, int32_t W, const int32_t* rep, uint32_t* equal, hipStream_t stream) {
+  if (n > 0) hipLaunchKernelGGL(rows_equal_kernel, dim3(n), dim3(kRowThreads), 0, stream, rows, W, rep, equal);
+}
+void launch_gather_rows(const uint32_t* rows, int32_t W, const int32_t* unique, int32_t n_unique, uint32_t* out,
+                        hipStream_t stream) {
+  if (n_unique > 0) hipLaunchKernelGGL(gather_rows_kernel, dim3(n_unique), dim3(kRowThreads), 0, stream, rows, W, unique, out);
 }
 
 void launch_count_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_id, uint32_t* counts,

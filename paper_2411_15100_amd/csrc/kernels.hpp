@@ -99,7 +99,8 @@ struct DevVocab {
 // one mask cache on the device
 struct DevCache {
   DevTables tab;             // staging split for the fill kernel
-  const uint32_t* acc;       // [n_nodes][W] accepted tokens, id space
+  const uint32_t* acc;       // [n_acc_rows][W] accepted tokens, id space: the distinct rows of the nodes' bitsets
+  const uint16_t* acc_row;   // [n_nodes] which row of `acc` is the node's
   const uint32_t* unc_off;   // [n_nodes][n_chunk+1] offsets into unc_list
   const uint32_t* unc_list;  // context-dependent tokens, grouped by (node, chunk); see kEntry*
   const uint32_t* unc_ctx;   // parallel to unc_list: the entry's class in each context of its node's rule; see kCtx*
@@ -147,7 +148,7 @@ struct RowDesc {
                              // ahead of the fill (DevBatch::pair); bit 31 = the row has been examined for that
 };
 // A stack header is kStackHdrWords + n_chunk + 1 uint32 words:
-//   [kStackHdrTop] top node, [kStackHdrDepth] number of frames,
+//   [kStackHdrTop] top node | its row of DevCache::acc << 16, [kStackHdrDepth] number of frames,
 //   [kStackHdrFrames] offset of its frames (bottom first) in the uint16 frame array,
 //   [kStackHdrCtx] index of the node below the top frame among the contexts of the top node's rule, or kCtxNone,
 //   [kStackHdrFirst .. +8) 256-bit set of the bytes that can be consumed from this stack,
@@ -235,6 +236,12 @@ void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, i
 void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* a_rank, const uint32_t* b_rank,
                     uint32_t* a_id, uint32_t* b_id, hipStream_t stream);
 // per (node, chunk) number of context-dependent tokens
+// Identical rows of a [n][W] array of bitsets: a 64-bit digest of every row; whether row k equals row
+// rep[k], word for word; rows[unique[u]] -> out[u].
+void launch_hash_rows(const uint32_t* rows, int32_t n, int32_t W, unsigned long long* digest, hipStream_t stream);
+void launch_rows_equal(const uint32_t* rows, int32_t n, int32_t W, const int32_t* rep, uint32_t* equal, hipStream_t stream);
+void launch_gather_rows(const uint32_t* rows, int32_t W, const int32_t* unique, int32_t n_unique, uint32_t* out,
+                        hipStream_t stream);
 void launch_count_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_id, uint32_t* counts,
                             hipStream_t stream);
 // write the context-dependent lists; off = [n][n_chunk+1] offsets relative to list

@@ -276,6 +276,30 @@ def test_markup_grammar_every_step_and_every_node(xgm, wl):
 
 
 # --------------------------------------------------------------------------
+# storage of the cache: every distinct accepted bitset is kept once
+# --------------------------------------------------------------------------
+def test_cache_keeps_every_distinct_accepted_row_once(xgm, wl):
+    vocab = si.make_vocab("bpe", 32000, 0)
+    xv = wl.make_xgm_vocab(vocab)
+    for name, text, root in [("json", si.JSON_GRAMMAR, "root"), ("csql", si.CSQL_GRAMMAR, "root"),
+                             ("schema", si.make_schema_grammar(3, string_heavy=True), "root")]:
+        g = xgm.Grammar(text, root)
+        cache = xgm.Cache(g, xv)
+        rows = {}
+        for node in range(cache.num_nodes):
+            acc, _ = cache.copy_node_bits(node)
+            rows.setdefault(acc.tobytes(), []).append(node)
+        say(f"{name}: {cache.num_nodes} nodes, {len(rows)} distinct accepted bitsets, {cache.num_accept_rows} kept, "
+            f"{cache.device_bytes / 1e6:.1f} MB on the device")
+        # (what every node's row must be is checked against the oracle by the class tests above)
+        assert cache.num_accept_rows == len(rows)
+        assert 0 < cache.num_accept_rows <= cache.num_nodes
+        W = xgm.bitmask_words(vocab.size)
+        assert cache.device_bytes >= cache.num_accept_rows * W * 4
+        assert cache.device_bytes < cache.num_nodes * W * 4 + 8 * sum(cache.num_uncertain(n) for n in range(cache.num_nodes)) + (4 << 20)
+
+
+# --------------------------------------------------------------------------
 # a third grammar family: a scripting language with word operators and one-line bodies
 # --------------------------------------------------------------------------
 def test_scripting_grammar_every_step_and_every_node(xgm, wl):
