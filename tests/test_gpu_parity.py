@@ -652,9 +652,22 @@ def test_fill_workgroups_with_many_chunks_and_several_rounds(xgm, wl, no_overflo
         d.zero_()
         batch.fill_next_token_bitmask(d.data_ptr(), _stream())
         assert np.array_equal(d.cpu().numpy(), want)
+        # the one-launch form: logits written beside the last walks of workgroups that took several rounds
+        bits = np.unpackbits(want.view(np.uint8), axis=1, bitorder="little")[:, :vocab.size].astype(bool)
+        for fill_and_apply in (lambda lg: xgm.fill_and_apply(ms, d.data_ptr(), lg.data_ptr(), xgm.DTYPE_BF16, vocab.size,
+                                                              vocab.size, _stream()),
+                               lambda lg: batch.fill_and_apply(d.data_ptr(), lg.data_ptr(), xgm.DTYPE_BF16, vocab.size,
+                                                               vocab.size, _stream())):
+            logits = torch.from_numpy(si.make_logits(3, vocab.size, 77)).to(torch.bfloat16).cuda()
+            before = logits.view(torch.int16).cpu().numpy().view(np.uint16).copy()
+            d.zero_()
+            fill_and_apply(logits)
+            assert np.array_equal(d.cpu().numpy(), want)
+            after = logits.view(torch.int16).cpu().numpy().view(np.uint16)
+            assert np.array_equal(after, np.where(bits, before, np.uint16(0xFF80)))
     finally:
         xgm.debug_set_fill_budget(old)
-    say(f"  list entries per row {entries}: masks bit-exact with 2 workgroups per row")
+    say(f"  list entries per row {entries}: masks and logits bit-exact with 2 workgroups per row")
 
 
 def test_grammars_from_the_schema_front_end_every_step(xgm, wl, pair_table):
