@@ -608,3 +608,80 @@ def test_random_grammars_cache_fill_and_device_accept(xgm, wl, pair_table):
         B = len(texts)
     say(f"  {n_checked} masks of random grammars bit-exact on both paths; {n_multi} steps with parallel stacks; {n_host} through the host")
     assert n_checked > 400 and n_multi > 20
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_grammars_one_launch_form(xgm, wl, seed):
+    """The same family of seeded random grammars through the call that fills the mask and writes the
+    logits in one launch, from host-side and from device-resident states: masks and logits (bit
+    patterns; untouched where allowed) against the oracle at every step, with parallel stacks."""
+    from test_host_library import _random_grammar_text
+    from test_oracle_misc import TinyVocab
+    rng = np.random.Generator(np.random.PCG64(seed))
+    pieces = [bytes(p) for p in (b"a", b"b", b"c", b"d", b"(", b")", b"ab", b"ba", b"a(", b")b", b"cd)", b"((", b"))", b"abc", b"dcba",
+                                 b"(a)", b"aa", b"bb", b"ccd", b"d(", b"()", b")(", b"abcd", b"a)b(", b"ddd", b"c(c", b"b)", b"(((",
+                                 b")))", b"ad", b"da", b"cab")]
+    vocab = TinyVocab(pieces + [b""], [len(pieces)])
+    vocab.size = len(pieces) + 1
+    V = vocab.size
+    stride = (V + 3) // 4 * 4
+    W = xgm.bitmask_words(V)
+    xv = xgm.Vocab(vocab.data, vocab.offsets, vocab.stop_ids)
+    texts = []
+    while len(texts) < 24:
+        text = _random_grammar_text(rng)
+        try:
+            xgm.Grammar(text, "root")
+        except xgm.XgmError:
+            continue
+        texts.append(text)
+    caches = [xgm.Cache(xgm.Grammar(t, "root"), xv) for t in texts]
+    ogs = [oracle.Grammar(t, "root") for t in texts]
+    B = len(texts)
+    n_rows = n_multi = 0
+    for walk in range(2):
+        ms = [xgm.Matcher(cache=c) for c in caches]
+        oms = [oracle.EarleyMatcher(o) for o in ogs]
+        frozen = np.zeros(B, dtype=bool)
+        for step in range(10):
+            want = np.stack([om.mask(vocab) for om in oms])
+            for b, m in enumerate(ms):
+                if m.is_terminated():
+                    want[b] = False
+                    want[b, vocab.stop_ids] = True
+            packed = oracle.pack_bitmask(want)
+            base = rng.standard_normal((B, stride)).astype(np.float32)
+            expect = base.copy()
+            expect[:, :V][~want] = -np.inf
+            try:
+                batch = xgm.DeviceBatch(ms, history=0, stream=_stream())
+            except xgm.XgmError:      # a state beyond the device's limits: host-side states only
+                batch = None
+            for kind in ("host", "device"):
+                if kind == "device" and batch is None:
+                    continue
+                d = torch.zeros((B, W), dtype=torch.int32, device="cuda")
+                lg = torch.from_numpy(base.copy()).cuda()
+                if kind == "host":
+                    xgm.fill_and_apply(ms, d.data_ptr(), lg.data_ptr(), xgm.DTYPE_F32, V, stride, _stream())
+                else:
+                    batch.fill_and_apply(d.data_ptr(), lg.data_ptr(), xgm.DTYPE_F32, V, stride, _stream())
+                xgm.fill_overflow_fixup(_stream())
+                assert np.array_equal(d.cpu().numpy(), packed), (walk, step, kind)
+                assert np.array_equal(lg.cpu().numpy().view(np.uint32), expect.view(np.uint32)), (walk, step, kind)
+            n_rows += B
+            n_multi += sum(m.num_stacks() > 1 for m in ms)
+            for b in range(B):
+                allowed = np.flatnonzero(want[b][: len(pieces)])
+                if frozen[b] or ms[b].is_terminated() or allowed.size == 0:
+                    frozen[b] = True
+                    continue
+                t = int(allowed[rng.integers(0, allowed.size)])
+                rc = ms[b].try_accept_token(t)
+                if rc == -8:          # the host's limit of 64 stacks: the row stops here
+                    frozen[b] = True
+                    continue
+                assert rc == 0
+                assert oms[b].advance(pieces[t])
+    say(f"one-launch form on random grammars (seed {seed}): {n_rows} rows bit-exact on both paths, {n_multi} with parallel stacks")
+    assert n_multi > 10
