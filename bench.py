@@ -193,13 +193,17 @@ def main():
 
     # ---- algorithmic work per launch (averaged over the state sets in use)
     n_sets = len(work.sets)
-    rejected, acc_words, unc_tokens, steps_count = [], [], [], []
+    rejected, acc_words, unc_tokens, steps_count, sector_bytes = [], [], [], [], []
     for k in range(n_sets):
         work.fill(k, stream)
         torch.cuda.synchronize()
         words = work.d_mask.cpu().numpy()
         allowed = int(np.unpackbits(words.view(np.uint8)).sum())
         rejected.append(B * V - allowed)
+        # the same count at the memory's granularity: a 64-byte piece of a bf16 row (32 logits = one mask word)
+        # with no allowed logit is written, one with allowed and rejected logits is read and written
+        mw = words.view(np.uint32)[:, : V // 32]
+        sector_bytes.append(64.0 * int((mw == 0).sum()) + 128.0 * int(((mw != 0) & (mw != 0xFFFFFFFF)).sum()))
         w = work.sets[k]
         n_stacks = sum(m.num_stacks() for m in w.matchers)
         acc_words.append(n_stacks * W)
@@ -223,6 +227,8 @@ def main():
     roof_apply = {"kernel": "apply_kernel<2>", "bound": "hbm", "achieved": apply_bytes / (apply_us_avg * 1e-6) / 1e9,
                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": TRAFFIC_APPLY_BYTES, "bytes_per_launch": apply_bytes,
                   "read_modify_write_bytes_per_launch": 2.0 * 2.0 * B * V + 4.0 * B * W,
+                  "bytes_per_launch_in_64_byte_pieces": 4.0 * B * W + float(np.mean(sector_bytes)),
+                  "achieved_on_64_byte_pieces_GB/s": (4.0 * B * W + float(np.mean(sector_bytes))) / (apply_us_avg * 1e-6) / 1e9,
                   "plain_fill_of_the_same_buffers": {"us": plain_fill_us, "GB/s": plain_fill_gbs},
                   "plain_copy_between_the_same_buffers": {"us": plain_copy_us, "GB/s": plain_copy_gbs}}
     roof_apply["frac"] = roof_apply["achieved"] / HBM_PEAK_GBS
