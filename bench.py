@@ -221,6 +221,7 @@ def main():
     roof_fused = {"kernel": "fill_kernel<false, 2> (mask fill and -inf apply in one launch, device-resident states)",
                   "bound": "hbm", "kernel_us": fused_us_avg, "achieved": fused_bytes / (fused_us_avg * 1e-6) / 1e9,
                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": TRAFFIC_FUSED_BYTES, "bytes_per_launch": fused_bytes,
+                  "bytes_per_launch_in_64_byte_pieces": fill_bytes + float(np.mean(sector_bytes)),
                   "note": "the launch lasts as long as its slowest workgroup's token walks plus the drain of the "
                           "logits stores; the byte count is what the method must move"}
     roof_fused["frac"] = roof_fused["achieved"] / HBM_PEAK_GBS
