@@ -1204,8 +1204,7 @@ __global__ void batch_fork_commit_kernel(DevBatch bt, const int32_t* __restrict_
 // workgroup: the per-(row, chunk) running entry counts go to LDS, then one
 // thread per row cuts its row.
 constexpr int kPlanThreads = 1024;
-__global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
-  extern __shared__ __align__(16) unsigned char smem[];
+__device__ __forceinline__ void batch_plan_body(const DevBatch& bt, unsigned char* smem) {
   uint32_t* upto = reinterpret_cast<uint32_t*>(smem);  // [B][n_chunk + 1]
   __shared__ unsigned long long total;
   __shared__ uint32_t count[kPlanThreads / 64];  // per-wave sums of the rows' workgroup counts
@@ -1280,13 +1279,12 @@ __global__ __launch_bounds__(kPlanThreads) void batch_plan_kernel(DevBatch bt) {
 // stacks of rows whose state has changed, for stacks whose lists are long
 // enough to make the fill kernel want one.  One workgroup per row; a row that
 // has been examined since its last change is skipped.
-constexpr int kPairThreads = 256;
-__global__ __launch_bounds__(kPairThreads) void batch_pair_kernel(DevBatch bt, DevVocab voc, uint32_t pair_min_entries) {
-  extern __shared__ __align__(16) unsigned char smem[];
+constexpr int kPairThreads = kPlanThreads;  // the two share a launch
+__device__ __forceinline__ void batch_pair_body(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries,
+                                                int32_t b, unsigned char* smem) {
   __shared__ uint32_t pair[kPairWords];
   __shared__ uint16_t live_lds[kBatchMaxDepth];
   const uint32_t tid = threadIdx.x;
-  const int32_t b = blockIdx.x;
   const RowDesc rd = bt.rows[b];
   if (rd.pair_mask & 0x80000000u) return;
   const uint32_t hdr_stride = kStackHdrWords + (uint32_t)bt.n_chunk + 1u;
@@ -1321,6 +1319,14 @@ __global__ __launch_bounds__(kPairThreads) void batch_pair_kernel(DevBatch bt, D
     else body(LdsTab(rd.tab, smem));
   }
   if (tid == 0) bt.rows[b].pair_mask = 0x80000000u | need;
+}
+
+// After a change of state: the plan of the next fill (one workgroup) and, beside it, the two-byte tables
+// of the rows that want one (one workgroup per row).  Neither reads what the other writes.
+__global__ __launch_bounds__(kPlanThreads) void batch_plan_pair_kernel(DevBatch bt, DevVocab voc, uint32_t pair_min_entries) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  if ((int32_t)blockIdx.x == bt.B) batch_plan_body(bt, smem);
+  else batch_pair_body(bt, voc, pair_min_entries, (int32_t)blockIdx.x, smem);
 }
 
 // ---------------------------------------------------------------- kernel (c)
@@ -1494,8 +1500,9 @@ void launch_lds_lookups(int32_t n_blocks, uint32_t hops, uint32_t* sink, hipStre
 }
 
 void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries, hipStream_t stream) {
-  hipLaunchKernelGGL(batch_plan_kernel, dim3(1), dim3(kPlanThreads), (size_t)bt.B * ((bt.n_chunk + 1 + 3) & ~3) * 4, stream, bt);
-  hipLaunchKernelGGL(batch_pair_kernel, dim3(bt.B), dim3(kPairThreads), kFillLdsBudget, stream, bt, voc, pair_min_entries);
+  const size_t plan_bytes = (size_t)bt.B * ((bt.n_chunk + 1 + 3) & ~3) * 4;
+  hipLaunchKernelGGL(batch_plan_pair_kernel, dim3(bt.B + 1), dim3(kPlanThreads), std::max<size_t>(plan_bytes, kFillLdsBudget),
+                     stream, bt, voc, pair_min_entries);
 }
 
 void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, uint32_t pair_min_entries,
