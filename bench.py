@@ -137,7 +137,7 @@ def main():
     torch.cuda.synchronize()
     host_state_fused_us = (time.perf_counter() - t0f) * 1e6 / args.steps
 
-    # ---- accepting one token per row on the device (accept kernel + plan kernel), then one step back
+    # ---- accepting one token per row on the device (accept kernel, then plan and two-byte tables in one launch), then one step back
     accept_us = []
     w0 = work.sets[0]
     work.fill(0, stream)
@@ -375,7 +375,7 @@ def main():
         "host_state_path": {"fill_plus_apply_us": host_state_us, "fused_fill_and_apply_us": host_state_fused_us,
                             "note": "matcher states kept on the host: stacks packed and uploaded over PCIe every step"},
         "device_accept_us": {"mean": float(np.mean(accept_us)), "p50": float(np.median(accept_us)),
-                             "note": "one token per row accepted by the accept kernel + the plan kernel "
+                             "note": "one token per row accepted by the accept kernel, then the plan and the two-byte tables in one launch "
                                      "(events around the call); outside the fill+apply step"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32",
