@@ -1204,25 +1204,32 @@ __global__ void batch_fork_commit_kernel(DevBatch bt, const int32_t* __restrict_
 // workgroup: the per-(row, chunk) running entry counts go to LDS, then one
 // thread per row cuts its row.
 constexpr int kPlanThreads = 1024;
-__device__ __forceinline__ void batch_plan_body(const DevBatch& bt, unsigned char* smem) {
+// `keep_cuts`: there is room behind the counts for every row's workgroups ([B][n_chunk] words), so
+// that the rows are cut once; otherwise they are cut a second time when the plan is written.
+__device__ __forceinline__ void batch_plan_body(const DevBatch& bt, unsigned char* smem, bool keep_cuts) {
   uint32_t* upto = reinterpret_cast<uint32_t*>(smem);  // [B][n_chunk + 1]
   __shared__ unsigned long long total;
   __shared__ uint32_t count[kPlanThreads / 64];  // per-wave sums of the rows' workgroup counts
   const uint32_t tid = threadIdx.x, n_off = (uint32_t)bt.n_chunk + 1u;
   const uint32_t stride = (n_off + 3u) & ~3u;  // rows of `upto` start on 16 bytes
   const uint32_t hdr_stride = kStackHdrWords + n_off;
+  uint32_t* cuts = upto + (size_t)bt.B * stride;  // [B][n_chunk] the rows' workgroups (FillBlock::c0c1), if kept
   if (tid == 0) total = 0ull;
-  for (uint32_t item = tid; item < (uint32_t)bt.B * stride; item += kPlanThreads) {
-    const uint32_t b = item / stride, c = item % stride;
-    uint32_t run = 0u;
-    if (c < n_off) {
+  {  // a few threads per row: the row's descriptor is read once, the reads of its offsets are under way together
+    const uint32_t per_row = max(1u, (uint32_t)kPlanThreads / (uint32_t)bt.B), rows_at_once = (uint32_t)kPlanThreads / per_row;
+    for (uint32_t b = tid / per_row; b < (uint32_t)bt.B; b += rows_at_once) {
       const uint32_t s0 = bt.rows[b].stack_begin, ns = bt.rows[b].n_stacks;
-      for (uint32_t s = 0; s < ns; ++s) {
-        const uint32_t* off = bt.hdrs + (size_t)(s0 + s) * hdr_stride + kStackHdrWords;
-        run += off[c] - off[0];
+#pragma unroll 4
+      for (uint32_t c = tid % per_row; c < stride; c += per_row) {
+        uint32_t run = 0u;
+        if (c < n_off)
+          for (uint32_t s = 0; s < ns; ++s) {
+            const uint32_t* off = bt.hdrs + (size_t)(s0 + s) * hdr_stride + kStackHdrWords;
+            run += off[c] - off[0];
+          }
+        upto[b * stride + c] = run;
       }
     }
-    upto[item] = run;
   }
   __syncthreads();
   {  // the batch's total: per-wave sums with lane shuffles, one 64-bit atomic per wave
@@ -1249,7 +1256,9 @@ __device__ __forceinline__ void batch_plan_body(const DevBatch& bt, unsigned cha
   uint32_t my_count = 0u;
   if (tid < (uint32_t)bt.B) {
     k = plan_row_share(bt.B, bt.n_chunk, bt.budget, upto[tid * stride + bt.n_chunk], total);
-    my_count = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, upto_of, [](int32_t, const FillBlock&) {});
+    my_count = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, upto_of, [&](int32_t made, const FillBlock& f) {
+      if (keep_cuts) cuts[tid * (uint32_t)bt.n_chunk + (uint32_t)made] = f.c0c1;
+    });
   }
   // inclusive scan of the rows' workgroup counts: inside each wave with lane shuffles, then over the 16 wave sums
   uint32_t incl = my_count;
@@ -1270,9 +1279,14 @@ __device__ __forceinline__ void batch_plan_body(const DevBatch& bt, unsigned cha
   const uint32_t first = before + incl - my_count;
   for (uint32_t j = tid; j < bt.plan_cap; j += kPlanThreads) bt.plan[j] = FillBlock{kNoRow, 0u};
   __syncthreads();
-  if (tid < (uint32_t)bt.B && n_blocks <= bt.plan_cap)
-    plan_row((int32_t)tid, bt.n_chunk, k, upto_of,
-             [&](int32_t made, const FillBlock& f) { bt.plan[plan_slot(first + (uint32_t)made, n_blocks)] = f; });
+  if (tid < (uint32_t)bt.B && n_blocks <= bt.plan_cap) {
+    if (keep_cuts)
+      for (uint32_t i = 0; i < my_count; ++i)
+        bt.plan[plan_slot(first + i, n_blocks)] = FillBlock{tid, cuts[tid * (uint32_t)bt.n_chunk + i]};
+    else
+      plan_row((int32_t)tid, bt.n_chunk, k, upto_of,
+               [&](int32_t made, const FillBlock& f) { bt.plan[plan_slot(first + (uint32_t)made, n_blocks)] = f; });
+  }
 }
 
 // Ahead of the next fill: the two-byte tables (see build_pair_table) of the
@@ -1323,9 +1337,10 @@ __device__ __forceinline__ void batch_pair_body(const DevBatch& bt, const DevVoc
 
 // After a change of state: the plan of the next fill (one workgroup) and, beside it, the two-byte tables
 // of the rows that want one (one workgroup per row).  Neither reads what the other writes.
-__global__ __launch_bounds__(kPlanThreads) void batch_plan_pair_kernel(DevBatch bt, DevVocab voc, uint32_t pair_min_entries) {
+__global__ __launch_bounds__(kPlanThreads) void batch_plan_pair_kernel(DevBatch bt, DevVocab voc, uint32_t pair_min_entries,
+                                                                       bool keep_cuts) {
   extern __shared__ __align__(16) unsigned char smem[];
-  if ((int32_t)blockIdx.x == bt.B) batch_plan_body(bt, smem);
+  if ((int32_t)blockIdx.x == bt.B) batch_plan_body(bt, smem, keep_cuts);
   else batch_pair_body(bt, voc, pair_min_entries, (int32_t)blockIdx.x, smem);
 }
 
@@ -1500,9 +1515,12 @@ void launch_lds_lookups(int32_t n_blocks, uint32_t hops, uint32_t* sink, hipStre
 }
 
 void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries, hipStream_t stream) {
-  const size_t plan_bytes = (size_t)bt.B * ((bt.n_chunk + 1 + 3) & ~3) * 4;
+  size_t plan_bytes = (size_t)bt.B * ((bt.n_chunk + 1 + 3) & ~3) * 4;
+  const size_t cuts_bytes = (size_t)bt.B * bt.n_chunk * 4;
+  const bool keep_cuts = plan_bytes + cuts_bytes <= (size_t)64 * 1024;
+  if (keep_cuts) plan_bytes += cuts_bytes;
   hipLaunchKernelGGL(batch_plan_pair_kernel, dim3(bt.B + 1), dim3(kPlanThreads), std::max<size_t>(plan_bytes, kFillLdsBudget),
-                     stream, bt, voc, pair_min_entries);
+                     stream, bt, voc, pair_min_entries, keep_cuts);
 }
 
 void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, uint32_t pair_min_entries,

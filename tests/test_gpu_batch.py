@@ -464,6 +464,45 @@ def test_device_plan_equals_the_host_plan(xgm, wl):
     say(f"  plans of {n0} .. {n1} workgroups equal the host planner's")
 
 
+def test_device_plan_with_many_rows(xgm, wl):
+    """1000 rows of a mid-sized vocabulary: the plan kernel has no room to keep the rows' cuts and
+    makes them a second time when it writes the plan; several rows share a planning thread pass."""
+    vocab = si.make_vocab("bpe", 32000, 0)
+    xv = wl.make_xgm_vocab(vocab)
+    caches = [xgm.Cache(xgm.Grammar(t, "root"), xv) for t in (si.JSON_GRAMMAR, si.make_schema_grammar(1, string_heavy=True))]
+    prefixes = [b"", b'{"a": "x', b"[1, ", b'{"k', b"[", b'["abc", ']
+    ms = []
+    for b in range(1000):
+        m = xgm.Matcher(cache=caches[0] if b % 3 else caches[1])
+        if b % 3:
+            m.accept_bytes(prefixes[b % len(prefixes)])
+        ms.append(m)
+    batch = xgm.DeviceBatch(ms, history=0, stream=_stream())
+    n_chunk = (xgm.bitmask_words(vocab.size) + 127) // 128
+    plan, budget = batch.debug_plan(_stream())
+    upto = np.zeros((len(ms), n_chunk + 1), dtype=np.uint32)
+    per_node = {}
+    for b, m in enumerate(ms):
+        c = m.cache if hasattr(m, "cache") else (caches[0] if b % 3 else caches[1])
+        for s in range(m.num_stacks()):
+            key = (id(c), m.stack(s)[-1])
+            if key not in per_node:
+                _, unc = c.copy_node_bits(m.stack(s)[-1])
+                bits = np.unpackbits(unc.view(np.uint8), bitorder="little")
+                per_node[key] = np.cumsum(np.add.reduceat(bits, np.arange(0, bits.size, 4096))[:n_chunk]).astype(np.uint32)
+            upto[b, 1:] += per_node[key]
+    want = xgm.debug_plan_workgroups(upto, budget)
+    assert np.array_equal(plan, want)
+    # and the fill that runs this plan agrees with the fill from host-side states
+    W = xgm.bitmask_words(vocab.size)
+    d_dev = torch.zeros((len(ms), W), dtype=torch.int32, device="cuda")
+    d_host = torch.zeros((len(ms), W), dtype=torch.int32, device="cuda")
+    batch.fill_next_token_bitmask(d_dev.data_ptr(), _stream())
+    xgm.fill_next_token_bitmask(ms, d_host.data_ptr(), _stream())
+    assert torch.equal(d_dev, d_host)
+    say(f"  1000 rows: plan of {len(plan)} workgroups equals the host planner's; fills agree")
+
+
 def test_fork_continues_one_state_in_several_rows(xgm, wl, pair_table):
     vocab = si.make_vocab("bpe", 32000, 0)
     gj = xgm.Grammar(si.JSON_GRAMMAR, "root")
