@@ -585,7 +585,8 @@ struct LdsSetAcc {
 };
 
 // One workgroup of 16 waves serves one request and a contiguous range of its
-// chunks of 4096 token ids, as planned by the host (FillBlock).  Once per
+// chunks of 4096 token ids, as planned on the host or by the plan kernel
+// (FillBlock).  Once per
 // workgroup the request's automaton tables and live stacks are copied into
 // LDS; from then on a step of a token walk costs LDS lookups only.  The
 // workgroup owns its mask words in LDS:
@@ -597,14 +598,19 @@ struct LdsSetAcc {
 //      Whether the rest of the stack can consume those two bytes is looked up
 //      in a 256 x 256-bit table that the workgroup first computes for the
 //      stack (one lane per first byte: an enumerating walk of that byte
-//      collects the bytes that can follow it); a suffix of one or two bytes
+//      collects the bytes that can follow it) or copies, if it was computed
+//      when the state was entered; the per-context word of the entry settles
+//      it without any of this if the node below the top frame is one of the
+//      top rule's few contexts; a suffix of one or two bytes
 //      is thereby decided outright, a longer one is dropped or queued.
 //      Entries that need a walk from the top are tested on their first byte
 //      against a 256-bit set the host packed with the stack.  All these tests
 //      are exact and need only the list entry; survivors are compacted into
 //      an LDS queue (one LDS atomic per wave);
-//   3. the queue is walked with all lanes busy; allowed tokens are ORed into
-//      the words with LDS atomics;
+//   3. the queue is walked (one lane per survivor); allowed tokens are ORed
+//      into the words with LDS atomics.  Long lists take several rounds of 2;
+//      the walk waits until the queue might not hold another round's
+//      survivors, which as a rule means: one walk, after the last round;
 //   4. the words are stored once, coalesced (the stop tokens were added in 1).
 // No global atomics, no second pass over the mask.
 // When the kernel also masks the logits, the last walks of a workgroup - a
