@@ -127,7 +127,7 @@ class Grammar:
             raise OracleError(_err())
 
     def __del__(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _load is not None:   # (module globals are gone at interpreter exit)
             _load().orc_grammar_free(self._h)
             self._h = None
 
@@ -203,7 +203,7 @@ class EarleyMatcher:
             raise OracleError(_err())
 
     def __del__(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _load is not None:   # (module globals are gone at interpreter exit)
             _load().orc_earley_free(self._h)
             self._h = None
 
@@ -254,7 +254,7 @@ class PdaMatcher:
             raise OracleError(_err())
 
     def __del__(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _load is not None:   # (module globals are gone at interpreter exit)
             _load().orc_pda_free(self._h)
             self._h = None
 
