@@ -1033,7 +1033,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   // Plan the workgroups (plan.hpp): two per compute unit are resident at once.
   auto* plan = reinterpret_cast<FillBlock*>((char*)slot.h_buf + off_plan);
   int32_t n_blocks = plan_workgroups(
-      B, n_chunk, C.budget_override > 0 ? C.budget_override : C.resident_blocks,
+      B, n_chunk, C.budget_override > 0 ? C.budget_override : plan_budget(C.resident_blocks, B, n_chunk),
       [&](int32_t b, int32_t c) {
         uint64_t run = 0;
         const uint32_t* off0 = hdrs + (size_t)rows[b].stack_begin * hdr_words + kStackHdrWords;
@@ -1359,7 +1359,7 @@ int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* h
         HIP_OK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
         C.resident_blocks = 2 * std::max(1, cus);
       }
-      d.budget = C.budget_override > 0 ? C.budget_override : C.resident_blocks;
+      d.budget = C.budget_override > 0 ? C.budget_override : plan_budget(C.resident_blocks, B, n_chunk);
     }
     std::vector<DevCache> caches(B);
     for (int32_t b = 0; b < B; ++b) caches[b] = ms[b]->c->host;
