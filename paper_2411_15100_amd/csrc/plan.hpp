@@ -27,11 +27,11 @@ namespace xgm {
 XGM_PLAN_HD int32_t plan_min_blocks(int32_t n_chunk) { return (n_chunk + kFillMaxChunks - 1) / kFillMaxChunks; }
 
 // The budget for a batch: what the device holds at once (`resident`), or, for batches so large that the
-// workgroups every row needs for its mask words use that up, those plus half as many again, so that
+// workgroups every row needs for its mask words come near that, those plus three eighths of it, so that
 // rows with long lists can still be cut (the launch then runs in more than one round of workgroups;
-// measured at 256 and 512 rows of a 152 K vocabulary: fill 38 -> 28 us and 53 -> 41 us).
+// measured at 192, 256 and 512 rows of a 152 K vocabulary: fill 24.5 -> 22, 38 -> 29 and 53 -> 41 us).
 XGM_PLAN_HD int32_t plan_budget(int32_t resident, int32_t B, int32_t n_chunk) {
-  const int32_t floor_blocks = B * plan_min_blocks(n_chunk) + resident / 2;
+  const int32_t floor_blocks = B * plan_min_blocks(n_chunk) + resident * 3 / 8;
   return resident > floor_blocks ? resident : floor_blocks;
 }
 
