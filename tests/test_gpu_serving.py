@@ -1,7 +1,10 @@
 """GPU parity at the benchmark's full size: the serving decode step (batch 128,
 vocabulary 151936, 128 distinct string-heavy schema grammars) in the launch
-configuration that bench.py times, checked on sampled rows against the oracle's
-brute-force Earley masks, and apply checked on the whole batch by definition."""
+configurations that bench.py times.  Every row of every one of the 16 state
+sets is compared bit for bit with the oracle's brute-force Earley mask, for the
+fill from host-side states, the fill from device-resident states and the
+one-launch fill+apply (mask and logits); then one decode step of the whole
+batch on the device, again against the oracle for every row."""
 
 import sys
 
@@ -20,81 +23,91 @@ def say(msg):
     sys.stdout.flush()
 
 
-def test_serving_step_full_size_sampled_rows():
+def _oracle_masks(work, w, threads):
+    """The oracle's mask for every row of one state set: a fresh Earley matcher per row, advanced
+    through the row's token history; returns (bool [B, V], the matchers)."""
+    toks = work.vocab.tokens()
+    want = np.zeros((work.B, work.V), dtype=bool)
+    oms = []
+    for b in range(work.B):
+        om = oracle.EarleyMatcher(oracle.Grammar(work.texts[b], "root"))
+        for t in w.history[b]:
+            assert om.advance(toks[t])
+        want[b] = om.mask(work.vocab, threads)
+        oms.append(om)
+    return want, oms
+
+
+def test_serving_step_full_size_every_row_of_every_state_set():
     import paper_2411_15100_amd as xgm
     from paper_2411_15100_amd import workloads as wl
 
     before = xgm.overflow_total()
-    say("serving workload: building 128 caches at V=151936 (one state set)")
-    work = wl.ServingWorkload(pool=1, n_logit_buffers=1, log=lambda *a: None)
+    say("serving workload: building 128 caches at V=151936 and 16 state sets")
+    work = wl.ServingWorkload(pool=16, n_logit_buffers=1, log=lambda *a: None)
     stream = wl.current_stream()
-    work.fill(0, stream)
-    torch.cuda.synchronize()
-    words = work.d_mask.cpu().numpy()
-    w = work.sets[0]
-    toks = work.vocab.tokens()
-    entries = np.array([sum(c.num_uncertain(m.stack(s)[-1]) for s in range(m.num_stacks()))
-                        for m, c in zip(w.matchers, work.caches)])
-    # the rows with the longest context-dependent lists, the deepest stacks, and a seeded sample of the rest
-    rng = np.random.Generator(np.random.PCG64(99))
-    depth = np.array([w.depth(b) for b in range(work.B)])
-    rows = sorted(set(np.argsort(-entries)[:4].tolist()) | set(np.argsort(-depth)[:2].tolist())
-                  | set(int(x) for x in rng.choice(work.B, size=6, replace=False)))
     threads = oracle.default_threads()
-    allowed_rows = {}
-    oracle_rows = {}
-    for b in rows:
-        og = oracle.Grammar(work.texts[b], "root")
-        om = oracle.EarleyMatcher(og)
-        for t in w.history[b]:
-            assert om.advance(toks[t])
-        want = om.mask(work.vocab, threads)
-        assert np.array_equal(words[b], oracle.pack_bitmask(want)), f"row {b}"
-        allowed_rows[b] = want
-        oracle_rows[b] = om
-        say(f"  row {b}: {int(entries[b])} list entries, depth {int(depth[b])}, {int(want.sum())} allowed: bit-exact")
-    # properties that hold for every row: bits beyond V are zero, zero-byte tokens are never allowed
     V, W = work.V, work.W
-    bits = np.unpackbits(words.view(np.uint8), axis=1, bitorder="little")
-    assert not bits[:, V:].any()
+    toks = work.vocab.tokens()
     empty = np.array([len(t) == 0 for t in toks])
     stop = np.zeros(V, dtype=bool)
     stop[work.vocab.stop_ids] = True
-    assert not bits[:, :V][:, empty & ~stop].any()
-    # apply on the whole batch: by definition, from the mask the kernel produced
     t = work.logits[0]
     view = t.view(torch.int16)
-    old = view.cpu().numpy().view(np.uint16).copy()
-    work.apply(0, stream)
-    torch.cuda.synchronize()
-    new = view.cpu().numpy().view(np.uint16)
-    want = oracle.apply_mask(old, bits[:, :V].astype(bool), 0xFF80)
-    assert np.array_equal(new, want)
-    # the fused call on fresh logits: same mask, same logits
-    work.refresh_logits()
-    torch.cuda.synchronize()
-    old = view.cpu().numpy().view(np.uint16).copy()
     d_mask2 = torch.full_like(work.d_mask, -1)
-    xgm.fill_and_apply(w.batch, d_mask2.data_ptr(), t.data_ptr(), xgm.DTYPE_BF16, V, t.stride(0), stream=stream)
-    torch.cuda.synchronize()
-    assert np.array_equal(d_mask2.cpu().numpy(), words)
-    assert np.array_equal(view.cpu().numpy().view(np.uint16), oracle.apply_mask(old, bits[:, :V].astype(bool), 0xFF80))
-    # the same states resident on the device: one launch, no packing, same mask and logits
-    work.refresh_logits()
-    torch.cuda.synchronize()
-    old = view.cpu().numpy().view(np.uint16).copy()
-    d_mask2.fill_(-1)
-    work.device_sets[0].fill_next_token_bitmask(d_mask2.data_ptr(), stream)
-    assert np.array_equal(d_mask2.cpu().numpy(), words)
-    d_mask2.fill_(-1)
-    work.device_sets[0].fill_and_apply(d_mask2.data_ptr(), t.data_ptr(), xgm.DTYPE_BF16, V, t.stride(0), stream=stream)
-    torch.cuda.synchronize()
-    assert np.array_equal(d_mask2.cpu().numpy(), words)
-    assert np.array_equal(view.cpu().numpy().view(np.uint16), oracle.apply_mask(old, bits[:, :V].astype(bool), 0xFF80))
-    # one decode step of the whole batch on the device: every row accepts a token of its mask
-    # (stop tokens aside), states and next masks equal the host matchers', sampled rows the oracle's
+    n_masks = 0
+    last = None
+    for k in range(16):
+        w = work.sets[k]
+        want, oms = _oracle_masks(work, w, threads)
+        packed = oracle.pack_bitmask(want)
+        # properties that hold for every row: zero-byte tokens are never allowed (stop tokens aside)
+        assert not want[:, empty & ~stop].any()
+        # fill from host-side states, then apply
+        work.d_mask.fill_(-1)
+        work.fill(k, stream)
+        torch.cuda.synchronize()
+        words = work.d_mask.cpu().numpy()
+        bad = np.flatnonzero((words != packed).any(axis=1))
+        assert bad.size == 0, f"state set {k}, host-side states: rows {bad}"
+        work.refresh_logits()
+        torch.cuda.synchronize()
+        old = view.cpu().numpy().view(np.uint16).copy()
+        work.apply(0, stream)
+        torch.cuda.synchronize()
+        assert np.array_equal(view.cpu().numpy().view(np.uint16), oracle.apply_mask(old, want, 0xFF80)), f"state set {k}: apply"
+        # fill from the same states resident on the device
+        d_mask2.fill_(-1)
+        work.device_sets[k].fill_next_token_bitmask(d_mask2.data_ptr(), stream)
+        torch.cuda.synchronize()
+        bad = np.flatnonzero((d_mask2.cpu().numpy() != packed).any(axis=1))
+        assert bad.size == 0, f"state set {k}, resident states: rows {bad}"
+        # the one-launch form, from either kind of state: mask and logits
+        for name, call in (("host-side", lambda: xgm.fill_and_apply(w.batch, d_mask2.data_ptr(), t.data_ptr(), xgm.DTYPE_BF16, V,
+                                                                     t.stride(0), stream=stream)),
+                           ("resident", lambda: work.device_sets[k].fill_and_apply(d_mask2.data_ptr(), t.data_ptr(), xgm.DTYPE_BF16,
+                                                                                   V, t.stride(0), stream=stream))):
+            work.refresh_logits()
+            torch.cuda.synchronize()
+            old = view.cpu().numpy().view(np.uint16).copy()
+            d_mask2.fill_(-1)
+            call()
+            torch.cuda.synchronize()
+            bad = np.flatnonzero((d_mask2.cpu().numpy() != packed).any(axis=1))
+            assert bad.size == 0, f"state set {k}, one launch, {name} states: rows {bad}"
+            assert np.array_equal(view.cpu().numpy().view(np.uint16), oracle.apply_mask(old, want, 0xFF80)), \
+                f"state set {k}, one launch, {name} states: logits"
+        n_masks += work.B
+        say(f"  state set {k}: {work.B} rows bit-exact against the oracle (host-side, resident, one-launch x 2; logits x 3); "
+            f"{int(want.sum(axis=1).mean())} tokens allowed per row on average")
+        last = (w, want, oms, words)
+    assert n_masks == 2048
+    # one decode step of the whole batch on the device (state set 15): every row accepts a token of its mask
+    # (stop tokens aside); states equal the host matchers', next masks the oracle's, for every row
     import synth_inputs as si
-    allowed = wl.unpack_rows(words, V)
+    w, want, oms, words = last
+    rng = np.random.Generator(np.random.PCG64(99))
+    allowed = want.copy()
     allowed[:, work.vocab.stop_ids] = False
     picks = si.pick_tokens(rng, allowed, w.info.structural, w.info.is_stop, 0.35)
     assert (picks >= 0).sum() > work.B // 2   # rows whose text is complete have only the stop token left: they sit out
@@ -106,17 +119,16 @@ def test_serving_step_full_size_sampled_rows():
     for b in range(work.B):
         if picks[b] >= 0:
             w.matchers[b].accept_token(int(picks[b]))
+            assert oms[b].advance(toks[int(picks[b])])
         batch.get_row(b, scratch[b], stream)
         assert [scratch[b].stack(s) for s in range(scratch[b].num_stacks())] == \
                [w.matchers[b].stack(s) for s in range(w.matchers[b].num_stacks())], f"row {b}"
+    d_mask2.fill_(-1)
     batch.fill_next_token_bitmask(d_mask2.data_ptr(), stream)
-    work.fill(0, stream)
     torch.cuda.synchronize()
     words2 = d_mask2.cpu().numpy()
-    assert np.array_equal(words2, work.d_mask.cpu().numpy())
-    for b in rows:
-        if picks[b] >= 0:
-            assert oracle_rows[b].advance(toks[int(picks[b])])
-        assert np.array_equal(words2[b], oracle.pack_bitmask(oracle_rows[b].mask(work.vocab, threads))), f"row {b}"
-    say(f"  one device-side decode step of all {work.B} rows: states and masks equal the host's; {len(rows)} rows checked against the oracle")
+    want2 = np.stack([om.mask(work.vocab, threads) for om in oms])
+    bad = np.flatnonzero((words2 != oracle.pack_bitmask(want2)).any(axis=1))
+    assert bad.size == 0, f"after one device-side decode step: rows {bad}"
+    say(f"  one device-side decode step of all {work.B} rows: states equal the host's, all {work.B} next masks the oracle's")
     assert xgm.overflow_total() == before
