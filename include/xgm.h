@@ -301,6 +301,25 @@ int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bi
  * once more with xgm_apply_token_bitmask_inplace. */
 int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* d_logits, xgm_dtype dt,
                        int32_t V_logits, int64_t row_stride_elems, void* hip_stream);
+/* For callers that cannot allocate device memory where they call from (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): xgm_fill_next_token_bitmask with its per-call staging in fixed
+ * memory.  Same arguments, same result in d_bitmask, same handling of walks
+ * over the on-chip limits.  The packed stacks and the plan of workgroups are
+ * written into a fixed host array and copied, in stream order, into a fixed
+ * array of XGM_STATIC_STAGING_BYTES (1 MiB) that every device holds from the
+ * moment the library is loaded until the process ends; the call makes no
+ * hipMalloc / hipHostMalloc / hipFree and uses no event.  A batch whose stacks
+ * and plan need more than that returns XGM_ERR_TOO_LARGE (nothing is
+ * enqueued); batch 128 at a vocabulary of 151936 needs about 45 KiB.  The
+ * mask caches of the matchers must have been built before (they were, or the
+ * matchers would not exist).  All calls on one device share the array, which
+ * keeps the last call's contents: calls whose work overlaps on one device
+ * (different streams, or several host threads) race and must be ordered by
+ * the caller; calls on one stream are ordered by the stream. */
+#define XGM_STATIC_STAGING_BYTES (1 << 20)
+int xgm_fill_next_token_bitmask_static(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask,
+                                       void* hip_stream);
 /* Test knob (process-wide): a fill workgroup builds its two-byte table for a
  * stack only if its lists for that stack hold at least `entries` entries
  * (default 2048; negative restores the default).  The masks do not depend on

@@ -69,6 +69,7 @@ SIGNATURES = {
     "xgm_matcher_num_stacks": (_i32, [_vp]),
     "xgm_matcher_stack": (_i32, [_vp, _i32, _vp, _i32]),
     "xgm_fill_next_token_bitmask": (_i32, [_vp, _i32, _vp, _vp]),
+    "xgm_fill_next_token_bitmask_static": (_i32, [_vp, _i32, _vp, _vp]),
     "xgm_fill_and_apply": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
     "xgm_debug_fill_count_steps": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_debug_set_fill_pair_threshold": (_i32, [_i32]),
@@ -372,6 +373,16 @@ def fill_next_token_bitmask(matchers, d_bitmask: int, stream: int = 0):
     arr = (ctypes.c_void_p * len(matchers))(*[m._h for m in matchers])
     _check(load_library().xgm_fill_next_token_bitmask(arr, len(matchers), ctypes.c_void_p(d_bitmask),
                                                       ctypes.c_void_p(stream)))
+
+
+def fill_next_token_bitmask_static(matchers, d_bitmask: int, stream: int = 0):
+    """As fill_next_token_bitmask, staged in fixed memory (the call allocates nothing)."""
+    arr = (ctypes.c_void_p * len(matchers))(*[m._h for m in matchers])
+    _check(load_library().xgm_fill_next_token_bitmask_static(arr, len(matchers), ctypes.c_void_p(d_bitmask),
+                                                             ctypes.c_void_p(stream)))
+
+
+STATIC_STAGING_BYTES = 1 << 20
 
 
 class MatcherBatch:

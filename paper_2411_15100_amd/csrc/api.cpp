@@ -239,7 +239,7 @@ struct Context {
   FillSlot slot[kSlots];
   int next_slot = 0;
   // the most recent fill (for xgm_fill_overflow_fixup)
-  int last_slot = -1;
+  const void* last_blob = nullptr;  // its packed stacks in host memory (a ring slot, or the static staging array)
   uint32_t last_seq = 0;
   int32_t last_B = 0;
   int32_t* last_bitmask = nullptr;
@@ -948,9 +948,16 @@ static void pack_stack_header(const Automaton& A, const xgm_cache& c, const Stac
   std::memcpy(h + kStackHdrWords, &c.unc_off_host[(size_t)top * (n_chunk + 1)], (size_t)(n_chunk + 1) * 4);
 }
 
+// Host staging of the entry point that allocates nothing: the blob is packed here and copied to the device's
+// static scratch array with a stream-ordered copy (which has taken the bytes when it returns, the memory
+// being pageable).  Guarded by the context's mutex.
+alignas(64) static unsigned char g_static_host[kStaticScratchBytes];
+
+// `use_static`: stage in g_static_host and the device's static scratch array instead of the ring of
+// allocated slots; nothing is allocated on this path.
 static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream,
                      unsigned long long* d_step_counter, hipEvent_t* timing = nullptr,
-                     const FusedLogits* fused = nullptr) {
+                     const FusedLogits* fused = nullptr, bool use_static = false) {
   API_BEGIN
   if (!ms || B <= 0 || !d_bitmask) return fail(XGM_ERR_BAD_ARG, "fill: null argument or empty batch");
   xgm_vocab* v = nullptr;
@@ -979,6 +986,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
 
   Context& C = ctx();
   std::lock_guard<std::mutex> lock(C.mu);
+  if (use_static && !C.d_log) return fail(XGM_ERR_INTERNAL, "fill: the library's device context does not exist yet");
   OverflowLog* log = overflow_log();
   if (C.resident_blocks == 0) {
     int dev = 0, cus = 0;
@@ -986,21 +994,35 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     HIP_OK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     C.resident_blocks = 2 * std::max(1, cus);
   }
-  FillSlot& slot = C.slot[C.next_slot];
-  if (slot.used) HIP_OK(hipEventSynchronize(slot.done));
-  if (slot.cap < bytes) {
-    if (slot.h_buf) (void)hipHostFree(slot.h_buf);
-    if (slot.d_buf) (void)hipFree(slot.d_buf);
-    slot.h_buf = slot.d_buf = nullptr;
-    slot.cap = std::max<size_t>(bytes * 2, 1 << 16);
-    HIP_OK(hipHostMalloc(&slot.h_buf, slot.cap, hipHostMallocMapped));
-    HIP_OK(hipHostGetDevicePointer(&slot.h_dev, slot.h_buf, 0));
-    HIP_OK(hipMalloc(&slot.d_buf, slot.cap));
+  void* h_buf = nullptr;
+  void* d_buf = nullptr;
+  FillSlot* ring = nullptr;
+  if (use_static) {
+    if (bytes > kStaticScratchBytes)
+      return fail(XGM_ERR_TOO_LARGE, "fill (static staging): the batch's stacks need " + std::to_string(bytes) +
+                                         " bytes of staging, the static array holds " + std::to_string(kStaticScratchBytes));
+    HIP_OK(static_scratch(&d_buf));
+    h_buf = g_static_host;
+  } else {
+    FillSlot& slot = C.slot[C.next_slot];
+    ring = &slot;
+    if (slot.used) HIP_OK(hipEventSynchronize(slot.done));
+    if (slot.cap < bytes) {
+      if (slot.h_buf) (void)hipHostFree(slot.h_buf);
+      if (slot.d_buf) (void)hipFree(slot.d_buf);
+      slot.h_buf = slot.d_buf = nullptr;
+      slot.cap = std::max<size_t>(bytes * 2, 1 << 16);
+      HIP_OK(hipHostMalloc(&slot.h_buf, slot.cap, hipHostMallocMapped));
+      HIP_OK(hipHostGetDevicePointer(&slot.h_dev, slot.h_buf, 0));
+      HIP_OK(hipMalloc(&slot.d_buf, slot.cap));
+    }
+    if (!slot.done) HIP_OK(hipEventCreateWithFlags(&slot.done, hipEventDisableTiming));
+    h_buf = slot.h_buf;
+    d_buf = slot.d_buf;
   }
-  if (!slot.done) HIP_OK(hipEventCreateWithFlags(&slot.done, hipEventDisableTiming));
-  auto* rows = reinterpret_cast<RowDesc*>(slot.h_buf);
-  auto* hdrs = reinterpret_cast<uint32_t*>((char*)slot.h_buf + off_stacks);
-  auto* frames = reinterpret_cast<uint16_t*>((char*)slot.h_buf + off_frames);
+  auto* rows = reinterpret_cast<RowDesc*>(h_buf);
+  auto* hdrs = reinterpret_cast<uint32_t*>((char*)h_buf + off_stacks);
+  auto* frames = reinterpret_cast<uint16_t*>((char*)h_buf + off_frames);
   uint32_t si = 0, fi = 0;
   for (int32_t b = 0; b < B; ++b) {
     const xgm_matcher* m = ms[b];
@@ -1031,7 +1053,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     }
   }
   // Plan the workgroups (plan.hpp): two per compute unit are resident at once.
-  auto* plan = reinterpret_cast<FillBlock*>((char*)slot.h_buf + off_plan);
+  auto* plan = reinterpret_cast<FillBlock*>((char*)h_buf + off_plan);
   int32_t n_blocks = plan_workgroups(
       B, n_chunk, C.budget_override > 0 ? C.budget_override : plan_budget(C.resident_blocks, B, n_chunk),
       [&](int32_t b, int32_t c) {
@@ -1049,23 +1071,27 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     for (int32_t p = 0; p < n_real; ++p) plan[plan_slot((uint32_t)p, (uint32_t)n_real)] = C.plan_scratch[p];
   }
   if (timing) HIP_OK(hipEventRecord(timing[0], stream));
-  launch_upload(slot.h_dev, slot.d_buf, off_plan + (size_t)n_blocks * sizeof(FillBlock), stream);
+  const size_t blob_bytes = off_plan + (size_t)n_blocks * sizeof(FillBlock);
+  if (use_static) HIP_OK(hipMemcpyAsync(d_buf, h_buf, blob_bytes, hipMemcpyHostToDevice, stream));
+  else launch_upload(ring->h_dev, d_buf, blob_bytes, stream);
   if (timing) HIP_OK(hipEventRecord(timing[1], stream));
   const uint32_t seq = ++C.seq;
-  launch_fill(reinterpret_cast<const RowDesc*>(slot.d_buf),
-              reinterpret_cast<const uint32_t*>((char*)slot.d_buf + off_stacks),
-              reinterpret_cast<const uint16_t*>((char*)slot.d_buf + off_frames),
-              reinterpret_cast<const FillBlock*>((char*)slot.d_buf + off_plan), n_blocks, v->dv,
+  launch_fill(reinterpret_cast<const RowDesc*>(d_buf),
+              reinterpret_cast<const uint32_t*>((char*)d_buf + off_stacks),
+              reinterpret_cast<const uint16_t*>((char*)d_buf + off_frames),
+              reinterpret_cast<const FillBlock*>((char*)d_buf + off_plan), n_blocks, v->dv,
               reinterpret_cast<uint32_t*>(d_bitmask), log, seq, d_step_counter, stream,
               fused ? fused->d_logits : nullptr, fused ? fused->esize : 0, fused ? fused->neg_inf : 0u,
               fused ? fused->V_logits : 0, fused ? fused->row_stride : 0, C.pair_min_entries);
   HIP_OK(hipGetLastError());
   if (timing) HIP_OK(hipEventRecord(timing[2], stream));
-  HIP_OK(hipEventRecord(slot.done, stream));
-  slot.used = true;
-  C.last_slot = C.next_slot;
+  if (ring) {
+    HIP_OK(hipEventRecord(ring->done, stream));
+    ring->used = true;
+    C.next_slot = (C.next_slot + 1) % Context::kSlots;
+  }
+  C.last_blob = h_buf;
   C.last_batch = nullptr;
-  C.next_slot = (C.next_slot + 1) % Context::kSlots;
   C.last_seq = seq;
   C.last_B = B;
   C.last_bitmask = d_bitmask;
@@ -1078,6 +1104,11 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
 int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream) {
   return fill_impl(ms, B, d_bitmask, hip_stream, nullptr);
 }
+
+int xgm_fill_next_token_bitmask_static(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream) {
+  return fill_impl(ms, B, d_bitmask, hip_stream, nullptr, nullptr, nullptr, true);
+}
+static_assert(kStaticScratchBytes == XGM_STATIC_STAGING_BYTES, "the header states the size of the static staging array");
 
 // checks the logits arguments of a fused call and fills in `f`
 static int fused_logits(void* d_logits, xgm_dtype dt, int32_t V_logits, int64_t row_stride_elems, int32_t V, FusedLogits* f) {
@@ -1202,7 +1233,7 @@ int xgm_fill_overflow_fixup(void* hip_stream) {
   API_BEGIN
   Context& C = ctx();
   std::lock_guard<std::mutex> lock(C.mu);
-  if (C.last_slot < 0 && !C.last_batch) return 0;
+  if (!C.last_blob && !C.last_batch) return 0;
   HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
   const uint32_t count = read_overflow_count();
   const uint32_t fresh = count - C.seen_count;
@@ -1218,10 +1249,9 @@ int xgm_fill_overflow_fixup(void* hip_stream) {
       read_row_state(*C.last_batch, b, &terminated, out);
       return;
     }
-    const FillSlot& slot = C.slot[C.last_slot];
-    const auto* rows = reinterpret_cast<const RowDesc*>(slot.h_buf);
+    const auto* rows = reinterpret_cast<const RowDesc*>(C.last_blob);
     const size_t hdr_words = kStackHdrWords + (size_t)v.dv.n_chunk + 1;
-    const auto* hdrs = reinterpret_cast<const uint32_t*>((const char*)slot.h_buf + (size_t)C.last_B * sizeof(RowDesc));
+    const auto* hdrs = reinterpret_cast<const uint32_t*>((const char*)C.last_blob + (size_t)C.last_B * sizeof(RowDesc));
     size_t n_stacks = 0;
     for (int32_t r = 0; r < C.last_B; ++r) n_stacks += rows[r].n_stacks;
     const auto* frames = reinterpret_cast<const uint16_t*>(hdrs + n_stacks * hdr_words);
@@ -1552,7 +1582,7 @@ static int batch_fill_impl(xgm_batch* bt, int32_t* d_bitmask, void* hip_stream, 
               nullptr, static_cast<hipStream_t>(hip_stream), fused ? fused->d_logits : nullptr, fused ? fused->esize : 0,
               fused ? fused->neg_inf : 0u, fused ? fused->V_logits : 0, fused ? fused->row_stride : 0, C.pair_min_entries, d.pair);
   HIP_OK(hipGetLastError());
-  C.last_slot = -1;
+  C.last_blob = nullptr;
   C.last_batch = bt;
   C.last_seq = seq;
   C.last_B = bt->B;

@@ -1409,7 +1409,35 @@ __global__ __launch_bounds__(kLookupThreads) void lds_lookup_kernel(uint32_t n_w
   if (at == 0xFFFFFFFFu) sink[0] = at;  // never true: keeps the chain alive
 }
 
+// ------------------------------------------------------------ static scratch
+// Staging memory for the fill entry point that may not allocate: the per-step
+// blob (row descriptors, stack headers, frames, plan) goes here instead of into
+// a buffer from hipMalloc.  Each device holds its own copy of the array at its
+// own address until the process ends.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 }  // namespace
+
+// In host code the array's name is only a stand-in for the symbol: its device
+// address is looked up once per device, with that device current, and kept.
+hipError_t static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static void* ptr_of[kMaxDevices] = {};
+  *out = nullptr;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!ptr_of[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptr_of[dev] = p;
+  }
+  *out = ptr_of[dev];
+  return hipSuccess;
+}
 
 // ------------------------------------------------------------------ launchers
 void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, int32_t n, uint32_t* acc_rank,

@@ -225,6 +225,11 @@ struct OverflowLog {
   uint32_t entry[kCap][3]; // (sequence number, row or node, token id or rank)
 };
 
+// ---- staging memory that needs no allocation: a fixed array in every device's memory
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+// its address on the current device (looked up on the first call per device; callers serialise)
+hipError_t static_scratch(void** out);
+
 // ---- launchers (all asynchronous on `stream`)
 // (a) classify tokens [all ranks] x nodes [node0, node0+n) into rank-space bitsets
 // plain_rank (may be null): tokens that are context-dependent by section 3.1 alone
