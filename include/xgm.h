@@ -157,24 +157,33 @@ int xgm_schema_to_grammar(const char* schema_json, size_t len, char* h_text, siz
  * rejected in every context, so it is stored as rejected ("plain-only"
  * context-dependent tokens are counted, and kept with XGM_CACHE_KEEP_PLAIN);
  * final masks are unchanged.
- * The result is kept on the device as one accepted bitset per node plus, per
- * node and per block of 4096 token ids, the list of its context-dependent
- * tokens.  Each list entry also records where its token leaves the node's
- * frame (if there is exactly one such position), the first two bytes of what
- * is left of the token there, and - for rules that can sit on at most 16
- * different nodes - what that rest does when walked from each of those nodes
- * (accepted / rejected / leaves that frame too): section 3.2 taken per call
- * site.  The fill call uses these to settle most entries without a walk.
+ * The result is kept on the device in the cheapest exact form per node (the
+ * adaptive storage of section 3.1, and section 3.2 taken per call site):
+ *  - the accepted tokens as a bitset row (every distinct row once) if there
+ *    are many, as a list of token ids if there are few;
+ *  - the context-dependent tokens resolved ahead of time against what can
+ *    lie below: a frame of rule R can only sit on one of the nodes that follow
+ *    a reference to R (its contexts).  For every node n with such tokens and
+ *    every context r of n's rule there is a list of the tokens whose rest,
+ *    after leaving n's frame, is consumed from r without leaving r's frame;
+ *    for the tokens that leave r's frame as well, one more list per context
+ *    of r's rule.  Tokens that leave a third frame, and tokens whose walk at
+ *    build time exceeded a limit, are listed as entries to be walked against
+ *    the live stack at fill time.  Lists are cut at every 32768 token ids.
+ * The fill call therefore ORs one bitset or list per stack, sets the bits of
+ * two short lists, and walks only the rare remainder.
  * Synchronous: returns after the build has finished on hip_stream. */
 int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out);
 enum { XGM_CACHE_KEEP_PLAIN = 1 };
-/* Same, with flags: XGM_CACHE_KEEP_PLAIN also keeps, per node, the bitset of
- * the plain-only context-dependent tokens (for xgm_cache_copy_node_plain). */
+/* Same, with flags: XGM_CACHE_KEEP_PLAIN also keeps, per node, the bitsets of
+ * the context-dependent tokens and of the plain-only context-dependent tokens
+ * (for xgm_cache_copy_node_bits' h_unc and xgm_cache_copy_node_plain). */
 int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t flags, xgm_cache** out);
 void xgm_cache_destroy(xgm_cache* c);
 int32_t xgm_cache_num_nodes(const xgm_cache* c);
 /* Copies node's accepted and context-dependent bitsets (bitmask layout, each
- * xgm_bitmask_words(V) words) to host buffers; either pointer may be NULL. */
+ * xgm_bitmask_words(V) words) to host buffers; either pointer may be NULL.
+ * h_unc needs XGM_CACHE_KEEP_PLAIN at build time (XGM_ERR_BAD_ARG otherwise). */
 int xgm_cache_copy_node_bits(const xgm_cache* c, int32_t node, int32_t* h_acc, int32_t* h_unc);
 /* Number of context-dependent tokens cached for a node (or a negative status). */
 int32_t xgm_cache_num_uncertain(const xgm_cache* c, int32_t node);
@@ -195,11 +204,16 @@ double xgm_cache_build_kernel_seconds(const xgm_cache* c);
  * the copies of sizes back to the host, allocation; the vocabulary upload only
  * on the first build that uses it). */
 double xgm_cache_build_seconds(const xgm_cache* c);
-/* Section 3.1 (storage of the cache): many nodes have the same accepted bitset; the cache keeps every
- * distinct one once.  Number of distinct bitsets (<= number of nodes), and the bytes of device memory
- * the cache holds (bitsets, lists with their per-context classes, offsets, table image).  Negative: error. */
+/* Section 3.1 (storage of the cache): number of distinct accepted bitsets kept (nodes with few accepted
+ * tokens keep a list instead and are not counted), and the bytes of device memory the cache holds
+ * (bitsets, lists, offsets, table image).  Negative: error. */
 int32_t xgm_cache_num_accept_rows(const xgm_cache* c);
 int64_t xgm_cache_device_bytes(const xgm_cache* c);
+/* Sizes of the cache, into h_out8 (host, 8 values): [0] list keys in all, [1] keys of the first kind
+ * (node, context), [2] of the second kind (node, context, context of that context's rule), [3] list entries
+ * in all, [4] of them accepted tokens of nodes that keep a list, [5] context-dependent (node, token) pairs
+ * the lists were made from, [6] (pair, context) combinations examined at build time, [7] bitset rows. */
+int xgm_cache_stats(const xgm_cache* c, int64_t* h_out8);
 
 /* The exact host routine that decides a (node, token) pair whose GPU walk
  * exceeded its limits during xgm_cache_build: 0 rejected, 1 context-dependent,
@@ -217,37 +231,12 @@ int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h
  * h_steps (may be NULL) receives the number of automaton steps taken. */
 int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth,
                         const uint8_t* h_bytes, int32_t n, int32_t build, int32_t* h_steps);
-/* The host routine that cuts a batch into the fill kernel's workgroups, for
- * tests without a device.  h_upto: [B][n_chunk + 1], h_upto[b][c] = number of
- * context-dependent list entries of request b in its first c blocks of 4096
- * token ids (non-decreasing, h_upto[b][0] = 0).  budget: workgroups the device
- * holds at once.  h_out: cap >= B * n_chunk triples (request, first chunk,
- * end chunk).  Returns the number of workgroups, or a negative status. */
-int32_t xgm_debug_plan_workgroups(const uint32_t* h_upto, int32_t B, int32_t n_chunk, int32_t budget, uint32_t* h_out,
-                                  int32_t cap);
-/* Where workgroup p of a plan of n workgroups is placed in the launch: the
- * device hands workgroups to its eight XCDs in turn by their index, so
- * consecutive workgroups of the plan (those of one request, which read the
- * same automaton tables) get indices that are equal modulo 8 and share an
- * XCD's L2.  The launch has n rounded up to a multiple of 8 workgroups.
- * Returns the index, or a negative status. */
-int32_t xgm_debug_plan_slot(int32_t p, int32_t n);
-/* A frame whose current node is `top` can only sit on one of the few nodes that
+/* A frame whose current node is `top` can only sit on one of the nodes that
  * follow a reference to top's rule (directly, or through references in tail
- * position).  Returns the index of `below` among them (what the fill kernel
- * uses to look up per-context token classes), -1001 if the rule has more than
- * 16 such nodes (no per-context classes are kept), -1000 if `below` is not one
- * of them (never the case for a stack the matcher produced). */
+ * position): the contexts of the rule.  Returns the index of `below` among them
+ * (what names the stack's token lists in the mask cache), or -1000 if `below`
+ * is not one of them (never the case for a stack the matcher produced). */
 int32_t xgm_debug_context_index(const xgm_grammar* g, int32_t top, int32_t below);
-/* The table the fill kernel builds per stack to test two bytes at once, on the
- * host: the 256-bit set (8 words: byte c is bit c & 31 of word
- * c >> 5) of the bytes that can be consumed right after `byte` from the
- * stack h_stack (depth nodes, bottom first); all zero if `byte` itself cannot
- * be consumed.  Same source as the kernel's enumerating walk, for tests without
- * a device.  XGM_ERR_TOO_LARGE if the walk exceeded its limits. */
-int xgm_debug_next_bytes_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth, int32_t byte,
-                              uint32_t* h_set8);
-
 /* ------------------------------------------------------------------- matcher
  * Per-request state: the set of parallel stacks of section 2.2, each a list of
  * automaton nodes (return nodes below, current node on top).  Host memory. */
@@ -280,9 +269,11 @@ int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int
  *                               bytes from s with the full stack survives }
  * plus the stop tokens iff the matcher can terminate; a terminated matcher
  * gets a row with only the stop tokens.  All matchers must share one
- * vocabulary; their grammars may differ.  The call packs the stacks and a plan
- * of workgroups into pinned staging owned by the library (a ring of 8 slots),
- * enqueues a small copy kernel and the fill kernel on hip_stream, and returns.
+ * vocabulary; their grammars may differ.  B <= 65535.  The call packs the
+ * stacks (per stack: its frames and where its token lists lie in the cache)
+ * into pinned staging owned by the library (a ring of 8 slots), enqueues a
+ * small copy kernel and the fill kernel (one workgroup per row and 32768
+ * token ids) on hip_stream, and returns.
  * A walk that exceeds the on-chip bounds (64 frames pushed inside one token,
  * 24 pending alternatives, 4096 steps, tokens longer than 255 bytes) is never
  * guessed: the pair is recorded on the device, its bit is left 0, and
@@ -296,22 +287,23 @@ int xgm_fill_next_token_bitmask(xgm_matcher* const* ms, int32_t B, int32_t* d_bi
  * are masked), row stride row_stride_elems; the base address and the row pitch
  * must be multiples of 16 bytes (XGM_ERR_BAD_ARG otherwise: use the two
  * calls).  A token whose walk exceeded the on-chip limits is left allowed
- * (bit set, logit untouched) by this call; if xgm_overflow_total() moved,
- * xgm_fill_overflow_fixup() makes the bitmask exact and the caller applies it
- * once more with xgm_apply_token_bitmask_inplace. */
+ * (bit set, logit untouched) by this call; if the counter behind
+ * xgm_fill_overflow_count_device() moved, xgm_fill_overflow_fixup() makes the
+ * bitmask exact and the caller applies it once more with
+ * xgm_apply_token_bitmask_inplace. */
 int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* d_logits, xgm_dtype dt,
                        int32_t V_logits, int64_t row_stride_elems, void* hip_stream);
 /* For callers that cannot allocate device memory where they call from (code
  * under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc): xgm_fill_next_token_bitmask with its per-call staging in fixed
  * memory.  Same arguments, same result in d_bitmask, same handling of walks
- * over the on-chip limits.  The packed stacks and the plan of workgroups are
+ * over the on-chip limits.  The packed stacks are
  * written into a fixed host array and copied, in stream order, into a fixed
  * array of XGM_STATIC_STAGING_BYTES (1 MiB) that every device holds from the
  * moment the library is loaded until the process ends; the call makes no
  * hipMalloc / hipHostMalloc / hipFree and uses no event.  A batch whose stacks
- * and plan need more than that returns XGM_ERR_TOO_LARGE (nothing is
- * enqueued); batch 128 at a vocabulary of 151936 needs about 45 KiB.  The
+ * need more than that returns XGM_ERR_TOO_LARGE (nothing is
+ * enqueued); batch 128 at a vocabulary of 151936 needs about 40 KiB.  The
  * mask caches of the matchers must have been built before (they were, or the
  * matchers would not exist).  All calls on one device share the array, which
  * keeps the last call's contents: calls whose work overlaps on one device
@@ -320,19 +312,6 @@ int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, vo
 #define XGM_STATIC_STAGING_BYTES (1 << 20)
 int xgm_fill_next_token_bitmask_static(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask,
                                        void* hip_stream);
-/* Test knob (process-wide): a fill workgroup builds its two-byte table for a
- * stack only if its lists for that stack hold at least `entries` entries
- * (default 2048; negative restores the default).  The masks do not depend on
- * it; tests set 1 to force that path at small sizes.  Returns the old value. */
-int32_t xgm_debug_set_fill_pair_threshold(int32_t entries);
-/* Test knob (process-wide): plan fills for this many workgroups instead of two
- * per compute unit (0 or negative restores that).  Every request still gets
- * the workgroups its mask words need, so a small value makes each workgroup
- * own many blocks of token ids with long lists - the shape a large batch
- * produces - at small batch sizes.  A batch of device-resident states takes
- * the value at its creation.  The masks do not depend on it.  Returns the old
- * value. */
-int32_t xgm_debug_set_fill_budget(int32_t workgroups);
 /* Instrumentation for benchmarks: the same fill (same result in d_bitmask)
  * with a kernel instantiation that also counts the automaton steps of all
  * walks; synchronous; *h_steps receives the count.  Not for the hot path. */
@@ -342,14 +321,27 @@ int xgm_debug_fill_count_steps(xgm_matcher* const* ms, int32_t B, int32_t* d_bit
  * hip_stream around its two kernels; waits for them.  h_us2[0] = microseconds
  * of the stack upload kernel, h_us2[1] = of the fill kernel (host array of 2). */
 int xgm_debug_fill_timed(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream, float* h_us2);
-/* Synchronises hip_stream, then decides on the host every pair recorded by
- * the most recent fill and writes the exact bits into that fill's d_bitmask.  Returns the number
- * of pairs handled (>= 0) or a negative status.  Costs one stream
- * synchronisation; callers that never see a non-zero xgm_overflow_total() may
- * skip it. */
+/* Walks over the on-chip limits, fills from host-side matchers.  Every such
+ * fill (either entry point above, the fused one, the static one) records its
+ * pairs in one log that these fills share; each record names its fill, and the
+ * library keeps what it needs to decide the records of the last 8 fills (their
+ * packed stacks, where their masks went, their caches).
+ * xgm_fill_overflow_fixup synchronises hip_stream, decides on the host every
+ * pair recorded since the previous fixup, whichever of those fills recorded
+ * it, and writes the exact bits into that fill's d_bitmask.  Returns the
+ * number of pairs decided (>= 0).  Records of fills older than the last 8 can
+ * no longer be decided: the call then decides the others and returns
+ * XGM_ERR_TOO_LARGE with the counts in the message - never silently.
+ * Callers that never see the counter below move may skip the call. */
 int xgm_fill_overflow_fixup(void* hip_stream);
-/* Total number of pairs recorded by all fills so far (synchronises the
- * device to read the counter). */
+/* Device address of the counter of those records (uint32, only ever grows;
+ * valid until the process ends): a caller can read it in a kernel of its own
+ * or copy it on its stream, without synchronising the device.  NULL if there
+ * is no device. */
+const uint32_t* xgm_fill_overflow_count_device(void);
+/* Total number of pairs recorded so far by all cache builds and fills, of
+ * host-side and of device-resident states (synchronises the device to read
+ * the counters; for tests and reports). */
 int64_t xgm_overflow_total(void);
 
 /* ------------------------------------------- states that live on the device
@@ -357,12 +349,11 @@ int64_t xgm_overflow_total(void);
  * (section 3.3: the persistent stack and its rollback, here as a ring of
  * states per row in HBM).  The sampled token ids never leave the device: a
  * kernel moves every row's stacks on by its token and writes the row's next
- * state in the layout the fill kernel reads, another plans the workgroups of
- * the next fill, a third computes the per-stack lookup tables that the fill
- * kernel would otherwise build in every workgroup; a fill is then a single
- * launch without any host packing or upload.  Going back k tokens (speculative decoding, section 3.3) re-points a
- * row k states back.  Calls on one batch must be ordered by the caller (one
- * stream, or events).
+ * state in the layout the fill kernel reads (frames, and where each stack's
+ * token lists lie in the mask cache); a fill is then a single launch without
+ * any host packing or upload.  Going back k tokens (speculative decoding,
+ * section 3.3) re-points a row k states back.  Calls on one batch must be
+ * ordered by the caller (one stream, or events).
  *
  * xgm_batch_create: row b starts in the current state of ms[b] (host
  * matchers with mask caches over one vocabulary; they are not referenced
@@ -372,8 +363,7 @@ int64_t xgm_overflow_total(void);
  * (XGM_ERR_TOO_MANY_STACKS / XGM_ERR_TOO_LARGE at creation; at run time such
  * a row reports the code in its status and keeps its state, see
  * xgm_batch_get_row / xgm_batch_set_row for the way through the host).
- * B <= XGM_BATCH_MAX_ROWS and B * (vocabulary chunks of 4096 ids + 1) <= 32768.
- * Synchronises hip_stream. */
+ * B <= XGM_BATCH_MAX_ROWS.  Synchronises hip_stream. */
 int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* hip_stream, xgm_batch** out);
 void xgm_batch_destroy(xgm_batch* bt);
 int32_t xgm_batch_size(const xgm_batch* bt);
@@ -384,7 +374,7 @@ int32_t xgm_batch_size(const xgm_batch* bt);
  * XGM_ERR_TERMINATED, XGM_ERR_BAD_ARG (id >= V), XGM_ERR_TOO_MANY_STACKS or
  * XGM_ERR_TOO_LARGE (device limits, or the walk's limits: 64 frames pushed
  * inside one token, 24 pending alternatives, 4096 steps, 32 end
- * configurations); on any error the row keeps its state. */
+ * configurations); on any error the row keeps its state.  One kernel launch. */
 int xgm_batch_accept_tokens(xgm_batch* bt, const int32_t* d_token_ids, void* hip_stream);
 /* Asynchronous.  d_steps: [B] device int32; row b goes back d_steps[b] accepted
  * tokens (<= 0: stays).  More than the row still holds: XGM_ERR_BAD_ARG in its
@@ -412,23 +402,32 @@ int xgm_batch_get_row(xgm_batch* bt, int32_t row, xgm_matcher* m, void* hip_stre
 int xgm_batch_set_row(xgm_batch* bt, int32_t row, const xgm_matcher* m, void* hip_stream);
 /* As xgm_fill_next_token_bitmask / xgm_fill_and_apply for the batch's current
  * states: one kernel launch, nothing packed or uploaded.  Walks that exceed
- * the on-chip limits are recorded and decided by xgm_fill_overflow_fixup() as
- * for the host-state calls. */
+ * the on-chip limits are recorded in a log of the batch's own (each record
+ * names its fill and the state of its row) and decided by
+ * xgm_batch_fill_overflow_fixup(). */
 int xgm_batch_fill_next_token_bitmask(xgm_batch* bt, int32_t* d_bitmask, void* hip_stream);
 int xgm_batch_fill_and_apply(xgm_batch* bt, int32_t* d_bitmask, void* d_logits, xgm_dtype dt, int32_t V_logits,
                              int64_t row_stride_elems, void* hip_stream);
+/* Synchronises hip_stream, then decides on the host every pair that fills of
+ * this batch have recorded since the batch's previous fixup and writes the
+ * exact bits into the d_bitmask of the fill that recorded it (the last 8
+ * fills of the batch are remembered).  A record can only be decided while its
+ * row is still in the state that the fill saw: call this before the next
+ * accept / rollback / fork / set_row of such a row.  Returns the number of
+ * pairs decided (>= 0); if some records could not be decided (their row has
+ * moved on, or their fill is more than 8 fills back) the others are decided
+ * and XGM_ERR_TOO_LARGE is returned with the counts in the message.  Other
+ * batches' and the host-state fills' records are never touched. */
+int xgm_batch_fill_overflow_fixup(xgm_batch* bt, void* hip_stream);
+/* Device address of the batch's record counter (uint32, only ever grows; valid
+ * until xgm_batch_destroy): poll it without synchronising the device. */
+const uint32_t* xgm_batch_overflow_count_device(const xgm_batch* bt);
 /* Measurement aid for the benchmark (synchronous): dependent 4-byte LDS reads
  * per second of the whole device with two 1024-lane workgroups per compute
  * unit, every lane following a chain through a 32 KB table.  The table
  * lookups of the token walks (section 3.1, 3.3) are reads of this kind, each
  * depending on the one before. */
 int xgm_debug_lds_lookup_rate(void* hip_stream, double* h_lookups_per_second);
-/* The plan of the next fill as the device made it (synchronises hip_stream):
- * triples (row, first chunk, end chunk) of its workgroups in launch order,
- * idle entries left out; h_out holds cap triples.  *h_budget (may be NULL)
- * receives the number of workgroups the device holds at once, which the plan
- * was made for.  Returns the number of workgroups or a negative status. */
-int32_t xgm_debug_batch_plan(xgm_batch* bt, uint32_t* h_out, int32_t cap, int32_t* h_budget, void* hip_stream);
 /* For tests without a device: accept a token with the routine the device uses
  * (a depth-first walk over the flattened tables that writes out every stack
  * the token can end in) instead of the host engine.  Same results and errors

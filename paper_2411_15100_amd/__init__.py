@@ -12,13 +12,10 @@ from .binding import (  # noqa: F401
     fill_next_token_bitmask_static,
     STATIC_STAGING_BYTES,
     fill_overflow_fixup,
+    fill_overflow_count_device,
     debug_fill_count_steps,
     fill_and_apply,
     debug_fill_timed,
-    debug_plan_workgroups,
-    debug_set_fill_pair_threshold,
-    debug_set_fill_budget,
-    debug_plan_slot,
     debug_lds_lookup_rate,
     MatcherBatch,
     DeviceBatch,

@@ -41,10 +41,7 @@ SIGNATURES = {
     "xgm_grammar_node_is_final": (_i32, [_vp, _i32]),
     "xgm_debug_classify_host": (_i32, [_vp, _i32, _cp, _i32]),
     "xgm_debug_walk_host": (_i32, [_vp, _vp, _i32, _cp, _i32, _i32, _vp]),
-    "xgm_debug_next_bytes_host": (_i32, [_vp, _vp, _i32, _i32, _vp]),
     "xgm_debug_context_index": (_i32, [_vp, _i32, _i32]),
-    "xgm_debug_plan_workgroups": (_i32, [_vp, _i32, _i32, _i32, _vp, _i32]),
-    "xgm_debug_plan_slot": (_i32, [_i32, _i32]),
     "xgm_cache_build": (_i32, [_vp, _vp, _vp, _pp]),
     "xgm_cache_build_ex": (_i32, [_vp, _vp, _vp, ctypes.c_uint32, _pp]),
     "xgm_cache_num_uncertain_plain": (_i32, [_vp, _i32]),
@@ -58,6 +55,7 @@ SIGNATURES = {
     "xgm_cache_build_seconds": (ctypes.c_double, [_vp]),
     "xgm_cache_num_accept_rows": (_i32, [_vp]),
     "xgm_cache_device_bytes": (ctypes.c_int64, [_vp]),
+    "xgm_cache_stats": (_i32, [_vp, _vp]),
     "xgm_matcher_create": (_i32, [_vp, _pp]),
     "xgm_matcher_create_host": (_i32, [_vp, _vp, _pp]),
     "xgm_matcher_destroy": (None, [_vp]),
@@ -72,8 +70,6 @@ SIGNATURES = {
     "xgm_fill_next_token_bitmask_static": (_i32, [_vp, _i32, _vp, _vp]),
     "xgm_fill_and_apply": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
     "xgm_debug_fill_count_steps": (_i32, [_vp, _i32, _vp, _vp, _vp]),
-    "xgm_debug_set_fill_pair_threshold": (_i32, [_i32]),
-    "xgm_debug_set_fill_budget": (_i32, [_i32]),
     "xgm_debug_fill_timed": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_batch_create": (_i32, [_vp, _i32, _i32, _vp, _pp]),
     "xgm_batch_destroy": (None, [_vp]),
@@ -87,9 +83,11 @@ SIGNATURES = {
     "xgm_batch_fill_next_token_bitmask": (_i32, [_vp, _vp, _vp]),
     "xgm_batch_fill_and_apply": (_i32, [_vp, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
     "xgm_debug_matcher_accept_token_walk": (_i32, [_vp, _i32]),
-    "xgm_debug_batch_plan": (_i32, [_vp, _vp, _i32, _vp, _vp]),
     "xgm_debug_lds_lookup_rate": (_i32, [_vp, _vp]),
     "xgm_fill_overflow_fixup": (_i32, [_vp]),
+    "xgm_fill_overflow_count_device": (_vp, []),
+    "xgm_batch_fill_overflow_fixup": (_i32, [_vp, _vp]),
+    "xgm_batch_overflow_count_device": (_vp, [_vp]),
     "xgm_overflow_total": (_i64, []),
     "xgm_apply_token_bitmask_inplace": (_i32, [_vp, _i32, _i32, _i32, _i64, _vp, _i32, _vp, _i32, _vp]),
 }
@@ -248,16 +246,9 @@ class Grammar:
 
 
     def debug_context_index(self, top: int, below: int) -> int:
-        """Index of `below` among the contexts of top's rule; -1001 too many contexts, -1000 not a context."""
+        """Index of `below` among the contexts of top's rule; -1000 not a context."""
         return int(load_library().xgm_debug_context_index(self._h, int(top), int(below)))
 
-    def debug_next_bytes_host(self, stack, byte: int) -> np.ndarray:
-        """256 flags: which bytes can be consumed right after `byte` from the stack."""
-        arr = np.asarray(stack, dtype=np.int32)
-        out = np.zeros(8, dtype=np.uint32)
-        _check(load_library().xgm_debug_next_bytes_host(self._h, arr.ctypes.data, int(arr.size), int(byte),
-                                                        out.ctypes.data))
-        return np.unpackbits(out.view(np.uint8), bitorder="little").astype(bool)
 
 
 class Cache:
@@ -309,12 +300,24 @@ class Cache:
         """Bytes of device memory the cache holds."""
         return int(load_library().xgm_cache_device_bytes(self._h))
 
-    def copy_node_bits(self, node: int):
+    def copy_node_bits(self, node: int, with_uncertain: bool = True):
+        """(accepted, context-dependent) bitsets of a node; the second needs keep_plain=True at build time
+        (None with with_uncertain=False)."""
         W = bitmask_words(self.vocab.size)
         acc = np.zeros(W, dtype=np.int32)
-        unc = np.zeros(W, dtype=np.int32)
-        _check(load_library().xgm_cache_copy_node_bits(self._h, node, acc.ctypes.data, unc.ctypes.data))
+        unc = np.zeros(W, dtype=np.int32) if with_uncertain else None
+        _check(load_library().xgm_cache_copy_node_bits(self._h, node, acc.ctypes.data,
+                                                       unc.ctypes.data if with_uncertain else None))
         return acc, unc
+
+    @property
+    def stats(self) -> dict:
+        """Sizes of the cache (xgm_cache_stats)."""
+        out = np.zeros(8, dtype=np.int64)
+        _check(load_library().xgm_cache_stats(self._h, out.ctypes.data))
+        names = ["keys", "keys_level1", "keys_level2", "entries", "entries_level0", "context_dependent_pairs",
+                 "pair_context_items", "bitset_rows"]
+        return {k: int(v) for k, v in zip(names, out)}
 
 
 class Matcher:
@@ -434,13 +437,12 @@ class DeviceBatch:
     def set_row(self, row: int, matcher: "Matcher", stream: int = 0):
         _check(load_library().xgm_batch_set_row(self._h, int(row), matcher._h, ctypes.c_void_p(stream)))
 
-    def debug_plan(self, stream: int = 0):
-        """(int array [n, 3] of (row, c0, c1) as planned on the device, budget)."""
-        out = np.zeros((1 << 16, 3), dtype=np.uint32)
-        budget = ctypes.c_int32(0)
-        n = _check(load_library().xgm_debug_batch_plan(self._h, out.ctypes.data, out.shape[0], ctypes.byref(budget),
-                                                       ctypes.c_void_p(stream)))
-        return out[:n].astype(np.int64), int(budget.value)
+    def fill_overflow_fixup(self, stream: int = 0) -> int:
+        return _check(load_library().xgm_batch_fill_overflow_fixup(self._h, ctypes.c_void_p(stream)))
+
+    def overflow_count_device(self) -> int:
+        """Device address of the batch's counter of walks over the limits."""
+        return int(load_library().xgm_batch_overflow_count_device(self._h) or 0)
 
     def fill_next_token_bitmask(self, d_bitmask: int, stream: int = 0):
         _check(load_library().xgm_batch_fill_next_token_bitmask(self._h, ctypes.c_void_p(d_bitmask),
@@ -470,36 +472,11 @@ def debug_fill_count_steps(batch: "MatcherBatch", d_bitmask: int, stream: int = 
     return int(n.value)
 
 
-def debug_plan_workgroups(upto: np.ndarray, budget: int) -> np.ndarray:
-    """upto: uint32 [B, n_chunk + 1] cumulative list entries; returns int array [n, 3] of (row, c0, c1)."""
-    upto = np.ascontiguousarray(upto, dtype=np.uint32)
-    B, nc1 = upto.shape
-    out = np.zeros((B * (nc1 - 1), 3), dtype=np.uint32)
-    n = _check(load_library().xgm_debug_plan_workgroups(upto.ctypes.data, B, nc1 - 1, int(budget), out.ctypes.data,
-                                                        out.shape[0]))
-    return out[:n].astype(np.int64)
-
-
 def debug_lds_lookup_rate(stream: int = 0) -> float:
     """Dependent LDS reads per second of the whole device (measurement aid)."""
     out = ctypes.c_double(0.0)
     _check(load_library().xgm_debug_lds_lookup_rate(ctypes.c_void_p(stream), ctypes.byref(out)))
     return float(out.value)
-
-
-def debug_plan_slot(p: int, n: int) -> int:
-    """Index in the launch of workgroup p of a plan of n."""
-    return _check(load_library().xgm_debug_plan_slot(int(p), int(n)))
-
-
-def debug_set_fill_budget(workgroups: int) -> int:
-    """Test knob: number of workgroups fills are planned for (0: two per compute unit); returns the old value."""
-    return int(load_library().xgm_debug_set_fill_budget(int(workgroups)))
-
-
-def debug_set_fill_pair_threshold(entries: int) -> int:
-    """Test knob: minimum list length for the two-byte table (negative: default); returns the old value."""
-    return int(load_library().xgm_debug_set_fill_pair_threshold(int(entries)))
 
 
 def debug_fill_timed(batch: "MatcherBatch", d_bitmask: int, stream: int = 0):
@@ -512,6 +489,11 @@ def debug_fill_timed(batch: "MatcherBatch", d_bitmask: int, stream: int = 0):
 
 def fill_overflow_fixup(stream: int = 0) -> int:
     return _check(load_library().xgm_fill_overflow_fixup(ctypes.c_void_p(stream)))
+
+
+def fill_overflow_count_device() -> int:
+    """Device address of the counter of walks over the limits recorded by fills from host-side states."""
+    return int(load_library().xgm_fill_overflow_count_device() or 0)
 
 
 def overflow_total() -> int:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libxgm.so")
 SOURCES = ["automaton.cpp", "engine.cpp", "schema.cpp", "api.cpp", "kernels.hip"]
-HEADERS = ["automaton.hpp", "engine.hpp", "schema.hpp", "kernels.hpp", "plan.hpp", "walk.hpp", os.path.join("..", "..", "include", "xgm.h")]
+HEADERS = ["automaton.hpp", "engine.hpp", "schema.hpp", "kernels.hpp", "walk.hpp", os.path.join("..", "..", "include", "xgm.h")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

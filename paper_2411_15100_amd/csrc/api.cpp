@@ -2,6 +2,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <array>
 #include <atomic>
 #include <chrono>
 #include <cstring>
@@ -15,7 +16,6 @@
 #include "../../include/xgm.h"
 #include "automaton.hpp"
 #include "engine.hpp"
-#include "plan.hpp"
 #include "schema.hpp"
 #include "kernels.hpp"
 #include "walk.hpp"
@@ -141,12 +141,18 @@ struct xgm_cache {
   xgm_vocab* v = nullptr;
   DevCache host{};           // device pointers and table layout
   std::vector<void*> dev_ptrs;
-  std::vector<uint32_t> unc_off_host;  // [n_nodes][n_chunk+1]
-  std::vector<uint16_t> acc_row_host;  // [n_nodes] the node's row among the distinct accepted bitsets
+  // host copies of what packing a stack header needs (see DevCache)
+  std::vector<uint16_t> acc_row_host;  // [n_nodes]
+  std::vector<uint32_t> key_off_host;  // [n_keys * n_seg + 1]
+  std::vector<uint32_t> k1_base_host;  // [n_nodes], kNoKey for a node without context-dependent tokens
+  std::vector<uint32_t> k2_base_host;  // [n_k1] (empty: no level-2 lists)
+  std::vector<uint32_t> unc_count;     // [n_nodes] context-dependent tokens
   int32_t n_acc_rows = 0;
   int64_t device_bytes = 0;            // device memory the cache holds
+  int64_t stats[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // see xgm_cache_stats
   std::vector<uint32_t> plain_count;   // [n_nodes] tokens that only section 3.1 calls context-dependent
   uint32_t* d_plain_id = nullptr;      // [n_nodes][W] their bitsets, if kept
+  uint32_t* d_unc_id = nullptr;        // [n_nodes][W] the context-dependent tokens, if kept
   int64_t host_classified = 0;
   double kernel_seconds = 0.0;
   double build_seconds = 0.0;
@@ -166,6 +172,13 @@ struct xgm_batch {
   std::vector<xgm_cache*> caches;  // one per row (referenced)
   DevBatch dev{};
   std::vector<void*> dev_ptrs;
+  // walks over the on-chip limits: the batch's own log, how much of it has been examined, and where the last
+  // fills wrote their masks (by sequence number)
+  uint32_t seen_count = 0;
+  static constexpr int kFills = 8;
+  uint32_t fill_seq[kFills] = {};
+  int32_t* fill_bitmask[kFills] = {};
+  int next_fill = 0;
 };
 
 xgm_vocab::~xgm_vocab() { for (void* p : dev_ptrs) slab().release(p); }
@@ -217,11 +230,21 @@ void vocab_to_device(xgm_vocab* v) {
   d.V = V;
   d.W = (V + 31) / 32;
   d.WR = ((V + 63) / 64) * 2;
-  d.n_chunk = (d.W + kChunkWords - 1) / kChunkWords;
+  d.n_seg = (d.W + kSegWords - 1) / kSegWords;
   v->on_device = true;
 }
 
-// --- process-wide device context: overflow log and the fill staging ring
+// --- process-wide device context: the fill staging ring and the record of walks over the limits
+// What xgm_fill_overflow_fixup needs to decide the records of one fill from host-side states: the packed
+// stacks (in the staging memory the fill used), where the mask went, and the caches (kept alive until the
+// staging memory is used again).
+struct PendingFill {
+  uint32_t seq = 0;          // 0: none
+  int32_t B = 0;
+  int32_t* d_bitmask = nullptr;
+  const void* blob = nullptr;
+  std::vector<xgm_cache*> caches;  // referenced
+};
 struct FillSlot {
   void* h_buf = nullptr;  // pinned
   void* h_dev = nullptr;  // the same memory as the device addresses it
@@ -229,46 +252,49 @@ struct FillSlot {
   size_t cap = 0;
   hipEvent_t done = nullptr;
   bool used = false;
+  PendingFill fill;
 };
 struct Context {
   std::mutex mu;
-  OverflowLog* d_log = nullptr;
+  OverflowLog* d_log = nullptr;  // records of the fills from host-side states
   uint32_t seq = 0;
-  uint32_t seen_count = 0;  // log entries already examined by a fixup
+  uint32_t seen_count = 0;  // entries of d_log already examined by a fixup
   static constexpr int kSlots = 8;
   FillSlot slot[kSlots];
   int next_slot = 0;
-  // the most recent fill (for xgm_fill_overflow_fixup)
-  const void* last_blob = nullptr;  // its packed stacks in host memory (a ring slot, or the static staging array)
-  uint32_t last_seq = 0;
-  int32_t last_B = 0;
-  int32_t* last_bitmask = nullptr;
-  std::vector<const xgm_matcher*> last_matchers;
-  xgm_vocab* last_vocab = nullptr;
-  const struct xgm_batch* last_batch = nullptr;  // set instead of last_slot when the fill read device-resident states
-  // scratch of the workgroup planner (kept to avoid per-step allocation)
-  std::vector<FillBlock> plan_scratch;
-  uint32_t pair_min_entries = kFillPairMinEntries;
-  int32_t resident_blocks = 0;  // fill workgroups the device holds at once (two per compute unit)
-  int32_t budget_override = 0;  // test knob: plan for this many workgroups instead (0: off)
+  PendingFill static_fill;  // the last fill staged in the static arrays
+  // records of logs that no longer exist (cache builds, destroyed batches), and the batches that do
+  int64_t retired_records = 0;
+  std::set<xgm_batch*> batches;
 };
 Context& ctx() {
   static Context c;
   return c;
 }
+OverflowLog* new_log() {
+  require_device();
+  OverflowLog* log = dev_alloc<OverflowLog>(1);
+  HIP_OK(hipMemset(log, 0, sizeof(OverflowLog)));
+  return log;
+}
 OverflowLog* overflow_log() {
   Context& c = ctx();
-  if (!c.d_log) {
-    require_device();
-    c.d_log = dev_alloc<OverflowLog>(1);
-    HIP_OK(hipMemset(c.d_log, 0, sizeof(OverflowLog)));
-  }
+  if (!c.d_log) c.d_log = new_log();
   return c.d_log;
 }
-uint32_t read_overflow_count() {
+uint32_t read_overflow_count(const OverflowLog* log) {
   uint32_t n = 0;
-  HIP_OK(hipMemcpy(&n, &overflow_log()->count, sizeof(n), hipMemcpyDeviceToHost));
+  HIP_OK(hipMemcpy(&n, &log->count, sizeof(n), hipMemcpyDeviceToHost));
   return n;
+}
+void set_pending(PendingFill& f, uint32_t seq, int32_t B, int32_t* d_bitmask, const void* blob, xgm_matcher* const* ms) {
+  for (xgm_cache* c : f.caches) release(c);
+  f.caches.clear();
+  f.seq = seq;
+  f.B = B;
+  f.d_bitmask = d_bitmask;
+  f.blob = blob;
+  for (int32_t b = 0; b < B; ++b) { ++ms[b]->c->refs; f.caches.push_back(ms[b]->c); }
 }
 
 int fail(const Failure& f) {
@@ -384,24 +410,6 @@ int xgm_debug_classify_host(const xgm_grammar* g, int32_t node, const uint8_t* h
   API_END
 }
 
-int32_t xgm_debug_plan_workgroups(const uint32_t* h_upto, int32_t B, int32_t n_chunk, int32_t budget, uint32_t* h_out,
-                                  int32_t cap) {
-  API_BEGIN
-  if (!h_upto || !h_out || B <= 0 || n_chunk <= 0 || n_chunk > 65535 || budget < 0 || (int64_t)cap < (int64_t)B * n_chunk)
-    return fail(XGM_ERR_BAD_ARG, "plan_workgroups: bad argument (cap must be at least B * n_chunk)");
-  std::vector<FillBlock> plan((size_t)B * n_chunk);
-  const int32_t n = plan_workgroups(
-      B, n_chunk, budget, [&](int32_t b, int32_t c) { return (uint64_t)h_upto[(size_t)b * (n_chunk + 1) + c]; },
-      plan.data());
-  for (int32_t k = 0; k < n; ++k) {
-    h_out[3 * k] = plan[k].row;
-    h_out[3 * k + 1] = plan[k].c0c1 & 0x7FFFu;
-    h_out[3 * k + 2] = plan[k].c0c1 >> 16;
-  }
-  return n;
-  API_END
-}
-
 int xgm_schema_to_grammar(const char* schema_json, size_t len, char* h_text, size_t cap, size_t* h_len) {
   API_BEGIN
   if (!schema_json || !h_len || (cap > 0 && !h_text)) return fail(XGM_ERR_BAD_ARG, "schema_to_grammar: null argument");
@@ -414,52 +422,13 @@ int xgm_schema_to_grammar(const char* schema_json, size_t len, char* h_text, siz
   API_END
 }
 
-int32_t xgm_debug_plan_slot(int32_t p, int32_t n) {
-  if (p < 0 || n <= 0 || p >= n) return fail(XGM_ERR_BAD_ARG, "plan_slot: need 0 <= p < n");
-  return (int32_t)plan_slot((uint32_t)p, (uint32_t)n);
-}
-
 int32_t xgm_debug_context_index(const xgm_grammar* g, int32_t top, int32_t below) {
   if (!g || top < 0 || top >= g->A.n_nodes || below < 0 || below >= g->A.n_nodes)
     return fail(XGM_ERR_BAD_ARG, "context_index: bad argument");
   const auto& ctx = g->A.contexts[g->A.node_rule[top]];
   auto it = std::lower_bound(ctx.begin(), ctx.end(), below);
   if (it == ctx.end() || *it != below) return -1000;
-  if (ctx.size() > kCtxMax) return -1001;
   return (int32_t)(it - ctx.begin());
-}
-
-namespace {
-struct HostSetAcc {
-  uint32_t* words;
-  void add(uint32_t w, uint32_t bits) { words[w] |= bits; }
-};
-}  // namespace
-
-int xgm_debug_next_bytes_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth, int32_t byte,
-                              uint32_t* h_set8) {
-  API_BEGIN
-  if (!g || !h_stack || !h_set8 || depth < 1 || depth > XGM_MAX_STACK_DEPTH || byte < 0 || byte > 255)
-    return fail(XGM_ERR_BAD_ARG, "next_bytes_host: bad argument");
-  const Automaton& A = g->A;
-  std::vector<uint16_t> live(depth);
-  for (int32_t k = 0; k < depth; ++k) {
-    if (h_stack[k] < 0 || h_stack[k] >= A.n_nodes) return fail(XGM_ERR_BAD_ARG, "next_bytes_host: node out of range");
-    live[k] = (uint16_t)h_stack[k];
-  }
-  const CompactTab T{TabView{reinterpret_cast<const uint2*>(A.hdr.data()), A.n_nodes,
-                             reinterpret_cast<const uint2*>(A.hdr.data()), A.cls.data(), A.shapes.data(),
-                             A.targets.data(), A.alts.data(), A.follow_words.data(), A.n_cls}};
-  for (int w = 0; w < 8; ++w) h_set8[w] = 0u;
-  HostSetAcc acc{h_set8};
-  const CollectNextBytes<CompactTab, HostSetAcc> collect{&T, A.node_first_words.data(), &acc};
-  const uint8_t b = (uint8_t)byte;
-  const int rc = walk_token<false>(T, make_uint4((uint32_t)byte, 0u, 0u, 1u << 24), &b, 1, live[depth - 1], live.data(),
-                                   (uint32_t)depth, (uint32_t*)nullptr, (const uint32_t*)nullptr, 0, (uint32_t*)nullptr,
-                                   collect);
-  if (rc == kOverflow) return fail(XGM_ERR_TOO_LARGE, "next_bytes_host: the walk exceeded its limits");
-  return XGM_OK;
-  API_END
 }
 
 int xgm_debug_walk_host(const xgm_grammar* g, const int32_t* h_stack, int32_t depth, const uint8_t* h_bytes,
@@ -603,27 +572,27 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       tab.n_nodes = N;
     }
 
-    uint32_t* acc_id = temp(dev_alloc<uint32_t>((size_t)N * dv.W));  // one row per node; the distinct rows are kept
-    uint32_t* unc_id = temp(dev_alloc<uint32_t>((size_t)N * dv.W));
+    uint32_t* acc_id = temp(dev_alloc<uint32_t>((size_t)N * dv.W));  // one row per node
+    const bool keep_plain = (flags & XGM_CACHE_KEEP_PLAIN) != 0;
+    uint32_t* unc_id = keep_plain ? (c->d_unc_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W))) : temp(dev_alloc<uint32_t>((size_t)N * dv.W));
     // rank-space scratch for a batch of nodes (at most 1 GiB for both bitsets)
     const size_t row_bytes = (size_t)dv.WR * 4;
     int32_t batch = (int32_t)std::max<size_t>(1, std::min<size_t>((size_t)N, ((size_t)512 << 20) / row_bytes));
     uint32_t* acc_rank = temp(dev_alloc<uint32_t>((size_t)batch * dv.WR));
     uint32_t* unc_rank = temp(dev_alloc<uint32_t>((size_t)batch * dv.WR));
-    const bool keep_plain = (flags & XGM_CACHE_KEEP_PLAIN) != 0;
     uint32_t* plain_rank = keep_plain ? temp(dev_alloc<uint32_t>((size_t)batch * dv.WR)) : nullptr;
     if (keep_plain) c->d_plain_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W));
     uint32_t* d_plain_count = temp(dev_alloc<uint32_t>((size_t)N));
     HIP_OK(hipMemsetAsync(d_plain_count, 0, (size_t)N * 4, stream));
-    OverflowLog* log;
-    uint32_t seq, count_before;
+    // walks over the on-chip limits are recorded in a log of this build's own (the one that the fills from
+    // host-side states share is made here too, so that no fill has to allocate it)
+    OverflowLog* log = temp(new_log());
     {
       std::lock_guard<std::mutex> lock(ctx().mu);
-      log = overflow_log();
-      seq = ++ctx().seq;
-      HIP_OK(hipStreamSynchronize(stream));
-      count_before = read_overflow_count();
+      (void)overflow_log();
     }
+    const uint32_t seq = 1;
+    uint32_t count_before = 0;
     hipEvent_t ev0, ev1;
     HIP_OK(hipEventCreate(&ev0));
     HIP_OK(hipEventCreate(&ev1));
@@ -640,16 +609,15 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       HIP_OK(hipEventElapsedTime(&ms, ev0, ev1));
       c->kernel_seconds += ms * 1e-3;
       // pairs that hit a limit: decide them on the host, patch the bitsets
-      uint32_t count_after = read_overflow_count();
+      uint32_t count_after = read_overflow_count(log);
       uint32_t fresh = count_after - count_before;
       if (fresh > 0) {
         if (fresh > OverflowLog::kCap) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: too many walks exceeded the on-chip limits");
-        std::vector<uint32_t> ent((size_t)OverflowLog::kCap * 3);
+        std::vector<uint32_t> ent((size_t)OverflowLog::kCap * 4);
         HIP_OK(hipMemcpy(ent.data(), log->entry, ent.size() * 4, hipMemcpyDeviceToHost));
         std::vector<uint32_t> items;
         for (uint32_t k = 0; k < fresh; ++k) {
-          const uint32_t* e = &ent[(size_t)((count_before + k) % OverflowLog::kCap) * 3];
-          if (e[0] != seq) continue;
+          const uint32_t* e = &ent[(size_t)((count_before + k) % OverflowLog::kCap) * 4];
           const int32_t id = v->id_of_rank[e[2]];
           int cls = engine.classify(node0 + (int32_t)e[1], v->bytes.data() + v->off[id], (int)(v->off[id + 1] - v->off[id]));
           if (cls < 0) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: a token walk exceeds the host limits too");
@@ -664,31 +632,52 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
           (void)hipFree(d_items);
         }
         count_before = count_after;
-        std::lock_guard<std::mutex> lock(ctx().mu);
-        ctx().seen_count = count_after;
       }
       launch_permute(dv, nb, acc_rank, unc_rank, acc_id + (size_t)node0 * dv.W, unc_id + (size_t)node0 * dv.W, stream);
       if (keep_plain)
         launch_permute(dv, nb, plain_rank, plain_rank, c->d_plain_id + (size_t)node0 * dv.W,
                        c->d_plain_id + (size_t)node0 * dv.W, stream);
       HIP_OK(hipGetLastError());
-      HIP_OK(hipStreamSynchronize(stream));
     }
     (void)hipEventDestroy(ev0);
     (void)hipEventDestroy(ev1);
-    // the distinct accepted bitsets: rows with equal digests are compared with the first of them
+    {
+      std::lock_guard<std::mutex> lock(ctx().mu);
+      ctx().retired_records += count_before;
+    }
+
+    // ---- per node: accepted tokens per segment, digest of the accepted row, context-dependent tokens
+    const int32_t n_seg = dv.n_seg;
+    uint32_t* d_seg_counts = temp(dev_alloc<uint32_t>((size_t)N * n_seg));
+    unsigned long long* d_digest = temp(dev_alloc<unsigned long long>((size_t)N));
+    uint32_t* d_unc_counts = temp(dev_alloc<uint32_t>((size_t)N));
+    launch_row_stats(dv, N, acc_id, unc_id, d_seg_counts, d_digest, d_unc_counts, stream);
+    HIP_OK(hipGetLastError());
+    HIP_OK(hipStreamSynchronize(stream));
+    std::vector<uint32_t> seg_counts((size_t)N * n_seg);
+    std::vector<unsigned long long> digest((size_t)N);
+    c->unc_count.resize(N);
+    HIP_OK(hipMemcpy(seg_counts.data(), d_seg_counts, seg_counts.size() * 4, hipMemcpyDeviceToHost));
+    HIP_OK(hipMemcpy(digest.data(), d_digest, digest.size() * 8, hipMemcpyDeviceToHost));
+    HIP_OK(hipMemcpy(c->unc_count.data(), d_unc_counts, (size_t)N * 4, hipMemcpyDeviceToHost));
+    c->plain_count.resize(N);
+    HIP_OK(hipMemcpy(c->plain_count.data(), d_plain_count, (size_t)N * 4, hipMemcpyDeviceToHost));
+    for (int32_t n : host_plain) ++c->plain_count[n];
+
+    // ---- accepted tokens: a node with few of them keeps a list (its level-0 key), the others a bitset row;
+    // every distinct row is kept once (rows with equal digests are compared with the first of them)
+    std::vector<char> as_list((size_t)N, 0);
+    for (int32_t n = 0; n < N; ++n) {
+      uint64_t total = 0;
+      for (int32_t sgm = 0; sgm < n_seg; ++sgm) total += seg_counts[(size_t)n * n_seg + sgm];
+      as_list[n] = total * 2 <= (uint64_t)dv.W;
+    }
     uint32_t* acc_rows = nullptr;
     uint16_t* d_acc_row = nullptr;
     {
-      unsigned long long* d_digest = temp(dev_alloc<unsigned long long>((size_t)N));
-      launch_hash_rows(acc_id, N, dv.W, d_digest, stream);
-      HIP_OK(hipGetLastError());
-      HIP_OK(hipStreamSynchronize(stream));
-      std::vector<unsigned long long> digest((size_t)N);
-      HIP_OK(hipMemcpy(digest.data(), d_digest, digest.size() * 8, hipMemcpyDeviceToHost));
       std::unordered_map<unsigned long long, int32_t> first_with;
       std::vector<int32_t> rep((size_t)N);
-      for (int32_t n = 0; n < N; ++n) rep[n] = first_with.emplace(digest[n], n).first->second;
+      for (int32_t n = 0; n < N; ++n) rep[n] = as_list[n] ? n : first_with.emplace(digest[n], n).first->second;
       int32_t* d_rep = temp(dev_upload(rep));
       uint32_t* d_equal = temp(dev_alloc<uint32_t>((size_t)N));
       launch_rows_equal(acc_id, N, dv.W, d_rep, d_equal, stream);
@@ -697,9 +686,10 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       std::vector<uint32_t> equal((size_t)N);
       HIP_OK(hipMemcpy(equal.data(), d_equal, equal.size() * 4, hipMemcpyDeviceToHost));
       std::vector<int32_t> unique;
-      c->acc_row_host.assign((size_t)N, 0);
+      c->acc_row_host.assign((size_t)N, (uint16_t)kNoAccRow);
       std::vector<int32_t> row_of_rep((size_t)N, -1);
       for (int32_t n = 0; n < N; ++n) {
+        if (as_list[n]) continue;
         if (!equal[n]) rep[n] = n;  // same digest, different row: kept by itself
         if (rep[n] == n) {
           row_of_rep[n] = (int32_t)unique.size();
@@ -707,52 +697,128 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
         }
         c->acc_row_host[n] = (uint16_t)row_of_rep[rep[n]];  // rep[n] <= n: its row is known
       }
-      if (unique.size() > 0xFFFFu) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: more than 65535 distinct accepted bitsets");
+      if (unique.size() >= kNoAccRow) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: more than 65534 distinct accepted bitsets");
       c->n_acc_rows = (int32_t)unique.size();
       acc_rows = keep(slab_alloc<uint32_t>(unique.size() * (size_t)dv.W));
       int32_t* d_unique = temp(dev_upload(unique));
       launch_gather_rows(acc_id, dv.W, d_unique, c->n_acc_rows, acc_rows, stream);
-      HIP_OK(hipGetLastError());
-      HIP_OK(hipStreamSynchronize(stream));
       d_acc_row = keep(slab_upload(c->acc_row_host));
       c->device_bytes += (int64_t)unique.size() * dv.W * 4 + (int64_t)N * 2;
     }
-    c->plain_count.resize(N);
-    HIP_OK(hipMemcpy(c->plain_count.data(), d_plain_count, (size_t)N * 4, hipMemcpyDeviceToHost));
-    for (int32_t n : host_plain) ++c->plain_count[n];
-    // context-dependent lists
-    uint32_t* d_counts = temp(dev_alloc<uint32_t>((size_t)N * dv.n_chunk));
-    launch_count_uncertain(dv, N, unc_id, d_counts, stream);
-    HIP_OK(hipGetLastError());
-    HIP_OK(hipStreamSynchronize(stream));
-    std::vector<uint32_t> counts((size_t)N * dv.n_chunk);
-    HIP_OK(hipMemcpy(counts.data(), d_counts, counts.size() * 4, hipMemcpyDeviceToHost));
-    c->unc_off_host.assign((size_t)N * (dv.n_chunk + 1), 0);
-    uint64_t total = 0;
-    for (int32_t n = 0; n < N; ++n) {
-      for (int32_t k = 0; k < dv.n_chunk; ++k) {
-        c->unc_off_host[(size_t)n * (dv.n_chunk + 1) + k] = (uint32_t)total;
-        total += counts[(size_t)n * dv.n_chunk + k];
-      }
-      c->unc_off_host[(size_t)n * (dv.n_chunk + 1) + dv.n_chunk] = (uint32_t)total;
-      if (total >= ((uint64_t)1 << 32)) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: context-dependent lists exceed 2^32 entries");
-    }
-    uint32_t* d_off = keep(slab_upload(c->unc_off_host));
-    uint32_t* d_list = keep(slab_alloc<uint32_t>((size_t)total));
-    uint32_t* d_list_ctx = keep(slab_alloc<uint32_t>((size_t)total));
-    // contexts of the rules that have few enough of them
+
+    // ---- keys: level 1 = (node with context-dependent tokens, context of its rule), level 2 = (level-1
+    // key, context of that context node's rule)
     std::vector<uint32_t> ctx_off(A.rule_names.size() + 1, 0);
     std::vector<uint16_t> ctx_node;
     for (size_t r = 0; r < A.rule_names.size(); ++r) {
-      if (A.contexts[r].size() <= kCtxMax)
-        for (int32_t n : A.contexts[r]) ctx_node.push_back((uint16_t)n);
+      for (int32_t n : A.contexts[r]) ctx_node.push_back((uint16_t)n);
       ctx_off[r + 1] = (uint32_t)ctx_node.size();
     }
     if (ctx_node.empty()) ctx_node.push_back(0);
+    auto n_ctx = [&](int32_t rule) { return (uint64_t)(ctx_off[rule + 1] - ctx_off[rule]); };
+    c->k1_base_host.assign((size_t)N, kNoKey);
+    std::vector<uint32_t> node_off((size_t)N + 1, 0);
+    std::vector<uint64_t> item_base((size_t)N + 1, 0);
+    uint64_t n_k1 = 0, n_k2 = 0, n_base = 0, n_items = 0;
+    for (int32_t n = 0; n < N; ++n) {
+      node_off[n] = (uint32_t)n_base;
+      item_base[n] = n_items;
+      const uint64_t m = n_ctx(A.node_rule[n]);
+      if (c->unc_count[n] > 0 && m > 0) {
+        c->k1_base_host[n] = (uint32_t)n_k1;
+        n_k1 += m;
+        for (int32_t r1 : A.contexts[A.node_rule[n]]) n_k2 += n_ctx(A.node_rule[r1]);
+        n_items += (uint64_t)c->unc_count[n] * m;
+      }
+      n_base += c->unc_count[n];
+      if (n_base >= ((uint64_t)1 << 32) || n_k1 >= ((uint64_t)1 << 28))
+        throw Failure(XGM_ERR_TOO_LARGE, "cache_build: context-dependent lists beyond the supported size");
+    }
+    node_off[N] = (uint32_t)n_base;
+    item_base[N] = n_items;
+    // Level-2 lists are kept unless their keys alone would take hundreds of megabytes (grammars whose
+    // rules are each used in hundreds of places); tokens that leave a second frame are then walked at run time.
+    const bool level2 = n_k2 * (uint64_t)n_seg <= ((uint64_t)1 << 26);
+    if (!level2) n_k2 = 0;
+    if (level2) {
+      c->k2_base_host.assign((size_t)n_k1, 0u);
+      uint64_t run = 0;
+      for (int32_t n = 0; n < N; ++n) {
+        if (c->k1_base_host[n] == kNoKey) continue;
+        uint32_t k1 = c->k1_base_host[n];
+        for (int32_t r1 : A.contexts[A.node_rule[n]]) {
+          c->k2_base_host[k1++] = (uint32_t)run;
+          run += n_ctx(A.node_rule[r1]);
+        }
+      }
+    }
+    const uint64_t n_keys = (uint64_t)N + n_k1 + n_k2;
+    const size_t n_slots = (size_t)(n_keys * (uint64_t)n_seg);
+
+    // ---- base lists: every node's context-dependent tokens, and where each of them leaves the node's frame
+    uint32_t* d_node_off = temp(dev_upload(node_off));
+    uint64_t* d_item_base = temp(dev_upload(item_base));
+    uint32_t* d_k1_base = keep(slab_upload(c->k1_base_host));
+    uint32_t* d_k2_base = level2 ? keep(slab_upload(c->k2_base_host)) : nullptr;
     uint32_t* d_ctx_off = keep(slab_upload(ctx_off));
     uint16_t* d_ctx_node = keep(slab_upload(ctx_node));
-    launch_list_uncertain(dv, N, unc_id, d_off, d_list, stream);
-    launch_annotate_lists(tab, dv, N, d_off, (uint32_t)total, d_list, d_list_ctx, d_ctx_off, d_ctx_node, stream);
+    uint32_t* d_base_ids = temp(dev_alloc<uint32_t>((size_t)n_base));
+    uint32_t* d_exits = temp(dev_alloc<uint32_t>((size_t)n_base));
+    {
+      std::vector<uint32_t> identity((size_t)N);
+      std::iota(identity.begin(), identity.end(), 0u);
+      uint32_t* d_identity = temp(dev_upload(identity));
+      uint32_t* d_cursor = temp(dev_upload(node_off));
+      launch_rows_to_lists(dv, N, unc_id, d_identity, 1, d_cursor, d_base_ids, stream);
+      launch_exit_positions(tab, dv, N, d_node_off, d_base_ids, (uint32_t)n_base, d_exits, stream);
+    }
+    // ---- the entries of every (key, segment): counted, then written
+    uint32_t* d_counts = temp(dev_alloc<uint32_t>(n_slots));
+    HIP_OK(hipMemsetAsync(d_counts, 0, n_slots * 4, stream));
+    ContextListArgs args{};
+    args.node_off = d_node_off;
+    args.base_ids = d_base_ids;
+    args.exits = d_exits;
+    args.item_base = d_item_base;
+    args.k1_base = d_k1_base;
+    args.k2_base = d_k2_base;
+    args.ctx_off = d_ctx_off;
+    args.ctx_node = d_ctx_node;
+    args.n_k1 = (uint32_t)n_k1;
+    args.counts = d_counts;
+    launch_context_lists(tab, dv, N, n_items, args, false, stream);
+    HIP_OK(hipGetLastError());
+    HIP_OK(hipStreamSynchronize(stream));
+    std::vector<uint32_t> counts(n_slots);
+    HIP_OK(hipMemcpy(counts.data(), d_counts, n_slots * 4, hipMemcpyDeviceToHost));
+    uint64_t n_level0 = 0;
+    for (int32_t n = 0; n < N; ++n)
+      if (as_list[n])
+        for (int32_t sgm = 0; sgm < n_seg; ++sgm) n_level0 += counts[(size_t)n * n_seg + sgm] = seg_counts[(size_t)n * n_seg + sgm];
+    c->key_off_host.assign(n_slots + 1, 0u);
+    uint64_t total = 0;
+    for (size_t k = 0; k < n_slots; ++k) {
+      c->key_off_host[k] = (uint32_t)total;
+      total += counts[k];
+      if (total >= ((uint64_t)1 << 32)) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: token lists exceed 2^32 entries");
+    }
+    c->key_off_host[n_slots] = (uint32_t)total;
+    uint32_t* d_key_off = keep(slab_upload(c->key_off_host));
+    uint32_t* d_entries = keep(slab_alloc<uint32_t>((size_t)total));
+    {
+      uint32_t* d_front = temp(dev_alloc<uint32_t>(n_slots));
+      uint32_t* d_back = temp(dev_alloc<uint32_t>(n_slots));
+      HIP_OK(hipMemcpyAsync(d_front, d_key_off, n_slots * 4, hipMemcpyDeviceToDevice, stream));
+      HIP_OK(hipMemcpyAsync(d_back, d_key_off + 1, n_slots * 4, hipMemcpyDeviceToDevice, stream));
+      std::vector<uint32_t> list_key((size_t)N);
+      for (int32_t n = 0; n < N; ++n) list_key[n] = as_list[n] ? (uint32_t)n : kNoKey;
+      uint32_t* d_list_key = temp(dev_upload(list_key));
+      launch_rows_to_lists(dv, N, acc_id, d_list_key, n_seg, d_front, d_entries, stream);
+      args.front = d_front;
+      args.back = d_back;
+      args.entries = d_entries;
+      launch_context_lists(tab, dv, N, n_items, args, true, stream);
+    }
     HIP_OK(hipGetLastError());
     HIP_OK(hipStreamSynchronize(stream));
     cleanup_temps();
@@ -760,15 +826,27 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     c->host.tab = staged_for(tab, kFillLdsBudget);
     c->host.acc = acc_rows;
     c->host.acc_row = d_acc_row;
-    c->device_bytes += (int64_t)c->unc_off_host.size() * 4 + (int64_t)total * 8 + (int64_t)image_bytes;
-    if (keep_plain) c->device_bytes += (int64_t)N * dv.W * 4;
-    c->host.unc_off = d_off;
-    c->host.unc_list = d_list;
-    c->host.unc_ctx = d_list_ctx;
+    c->host.key_off = d_key_off;
+    c->host.entries = d_entries;
+    c->host.k1_base = d_k1_base;
+    c->host.k2_base = d_k2_base;
     c->host.ctx_off = d_ctx_off;
     c->host.ctx_node = d_ctx_node;
-    c->build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_build0).count();
     c->host.n_nodes = N;
+    c->host.n_k1 = (uint32_t)n_k1;
+    c->host.n_k2 = (uint32_t)n_k2;
+    c->device_bytes += (int64_t)(n_slots + 1) * 4 + (int64_t)total * 4 + (int64_t)image_bytes + (int64_t)(n_k1 + (level2 ? n_k1 : 0) + N) * 4 +
+                       (int64_t)ctx_off.size() * 4 + (int64_t)ctx_node.size() * 2;
+    if (keep_plain) c->device_bytes += (int64_t)N * dv.W * 8;
+    c->stats[0] = (int64_t)n_keys;
+    c->stats[1] = (int64_t)n_k1;
+    c->stats[2] = (int64_t)n_k2;
+    c->stats[3] = (int64_t)total;
+    c->stats[4] = (int64_t)n_level0;
+    c->stats[5] = (int64_t)n_base;
+    c->stats[6] = (int64_t)n_items;
+    c->stats[7] = (int64_t)c->n_acc_rows;
+    c->build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_build0).count();
   } catch (...) {
     cleanup_temps();
     release(c);
@@ -782,9 +860,7 @@ void xgm_cache_destroy(xgm_cache* c) { release(c); }
 int32_t xgm_cache_num_nodes(const xgm_cache* c) { return c ? c->host.n_nodes : XGM_ERR_BAD_ARG; }
 int32_t xgm_cache_num_uncertain(const xgm_cache* c, int32_t node) {
   if (!c || node < 0 || node >= c->host.n_nodes) return fail(XGM_ERR_BAD_ARG, "num_uncertain: bad cache or node");
-  const int32_t nc = c->v->dv.n_chunk;
-  const uint32_t* off = &c->unc_off_host[(size_t)node * (nc + 1)];
-  return (int32_t)(off[nc] - off[0]);
+  return (int32_t)c->unc_count[node];
 }
 int32_t xgm_cache_num_uncertain_plain(const xgm_cache* c, int32_t node) {
   if (!c || node < 0 || node >= c->host.n_nodes) return fail(XGM_ERR_BAD_ARG, "num_uncertain_plain: bad cache or node");
@@ -805,23 +881,33 @@ double xgm_cache_build_seconds(const xgm_cache* c) { return c ? c->build_seconds
 int32_t xgm_cache_num_accept_rows(const xgm_cache* c) { return c ? c->n_acc_rows : XGM_ERR_BAD_ARG; }
 int64_t xgm_cache_device_bytes(const xgm_cache* c) { return c ? c->device_bytes : XGM_ERR_BAD_ARG; }
 
+int xgm_cache_stats(const xgm_cache* c, int64_t* h_out8) {
+  if (!c || !h_out8) return fail(XGM_ERR_BAD_ARG, "cache_stats: null argument");
+  for (int k = 0; k < 8; ++k) h_out8[k] = c->stats[k];
+  return XGM_OK;
+}
+
 int xgm_cache_copy_node_bits(const xgm_cache* c, int32_t node, int32_t* h_acc, int32_t* h_unc) {
   API_BEGIN
   if (!c || node < 0 || node >= c->host.n_nodes) return fail(XGM_ERR_BAD_ARG, "copy_node_bits: bad cache or node");
   const DevVocab& dv = c->v->dv;
-  if (h_acc)
-    HIP_OK(hipMemcpy(h_acc, c->host.acc + (size_t)c->acc_row_host[node] * dv.W, (size_t)dv.W * 4, hipMemcpyDeviceToHost));
-  if (h_unc) {
-    std::memset(h_unc, 0, (size_t)dv.W * 4);
-    const uint32_t* off = &c->unc_off_host[(size_t)node * (dv.n_chunk + 1)];
-    const uint32_t n = off[dv.n_chunk] - off[0];
-    std::vector<uint32_t> list(n);
-    if (n) HIP_OK(hipMemcpy(list.data(), c->host.unc_list + off[0], (size_t)n * 4, hipMemcpyDeviceToHost));
-    for (int32_t k = 0; k < dv.n_chunk; ++k)
-      for (uint32_t j = off[k]; j < off[k + 1]; ++j) {
-        const uint32_t id = (uint32_t)k * kChunkTokens + (list[j - off[0]] & 0xFFFu);
-        reinterpret_cast<uint32_t*>(h_unc)[id >> 5] |= 1u << (id & 31);
+  if (h_acc) {
+    if (c->acc_row_host[node] != kNoAccRow) {
+      HIP_OK(hipMemcpy(h_acc, c->host.acc + (size_t)c->acc_row_host[node] * dv.W, (size_t)dv.W * 4, hipMemcpyDeviceToHost));
+    } else {  // the node keeps its accepted tokens as a list (its level-0 key)
+      std::memset(h_acc, 0, (size_t)dv.W * 4);
+      const uint32_t j0 = c->key_off_host[(size_t)node * dv.n_seg], j1 = c->key_off_host[(size_t)(node + 1) * dv.n_seg];
+      std::vector<uint32_t> list(j1 - j0);
+      if (j1 > j0) HIP_OK(hipMemcpy(list.data(), c->host.entries + j0, (size_t)(j1 - j0) * 4, hipMemcpyDeviceToHost));
+      for (uint32_t e : list) {
+        const uint32_t id = e & kEntryIdMask;
+        reinterpret_cast<uint32_t*>(h_acc)[id >> 5] |= 1u << (id & 31);
       }
+    }
+  }
+  if (h_unc) {
+    if (!c->d_unc_id) return fail(XGM_ERR_BAD_ARG, "copy_node_bits: the context-dependent bitsets are kept only with XGM_CACHE_KEEP_PLAIN");
+    HIP_OK(hipMemcpy(h_unc, c->d_unc_id + (size_t)node * dv.W, (size_t)dv.W * 4, hipMemcpyDeviceToHost));
   }
   return XGM_OK;
   API_END
@@ -920,32 +1006,33 @@ struct FusedLogits {
 // One stack header as the fill kernel reads it (see kStackHdr* in kernels.hpp);
 // `frame_offset`: where the stack's frames start in the frame array.
 static void pack_stack_header(const Automaton& A, const xgm_cache& c, const Stack& s, uint32_t frame_offset, uint32_t* h) {
-  const int32_t n_chunk = c.v->dv.n_chunk;
+  const int32_t n_seg = c.v->dv.n_seg;
+  const uint32_t n_off = (uint32_t)n_seg + 1u;
   const int32_t top = s.back();
   h[kStackHdrTop] = (uint32_t)top | ((uint32_t)c.acc_row_host[top] << 16);
   h[kStackHdrDepth] = (uint32_t)s.size();
   h[kStackHdrFrames] = frame_offset;
-  h[kStackHdrCtx] = kCtxNone;
-  if (s.size() >= 2) {
-    const auto& ctx = A.contexts[A.node_rule[top]];
-    if (ctx.size() <= kCtxMax) {
-      auto it = std::lower_bound(ctx.begin(), ctx.end(), s[s.size() - 2]);
-      if (it != ctx.end() && *it == s[s.size() - 2]) h[kStackHdrCtx] = (uint32_t)(it - ctx.begin());
-    }
+  h[3] = 0u;
+  // the keys of the stack's lists: the top node's own; the one for the node below the top frame; the one
+  // for the two nodes below
+  auto context_index = [&](int32_t frame_node, int32_t below) {
+    const auto& ctx = A.contexts[A.node_rule[frame_node]];
+    auto it = std::lower_bound(ctx.begin(), ctx.end(), below);
+    if (it == ctx.end() || *it != below) throw Failure(XGM_ERR_INTERNAL, "fill: a frame sits on a node that is no context of its rule");
+    return (uint32_t)(it - ctx.begin());
+  };
+  uint32_t key[kStackLists] = {(uint32_t)top, kNoKey, kNoKey};
+  if (s.size() >= 2 && c.k1_base_host[top] != kNoKey) {
+    const uint32_t key1_local = c.k1_base_host[top] + context_index(top, s[s.size() - 2]);
+    key[1] = (uint32_t)c.host.n_nodes + key1_local;
+    if (s.size() >= 3 && !c.k2_base_host.empty())
+      key[2] = (uint32_t)c.host.n_nodes + c.host.n_k1 + c.k2_base_host[key1_local] + context_index(s[s.size() - 2], s[s.size() - 3]);
   }
-  // bytes that can be consumed from this stack: at the top node, or - as
-  // long as the frames passed so far may all end here - at the frames
-  // below; and the same for the stack without its top frame
-  for (int below = 0; below < 2; ++below) {
-    uint32_t* ok = h + (below ? kStackHdrBelow : kStackHdrFirst);
-    for (int w = 0; w < 8; ++w) ok[w] = 0;
-    for (size_t k = s.size() - below; k-- > 0;) {
-      const uint32_t* fw = &A.node_first_words[(size_t)s[k] * 8];
-      for (int w = 0; w < 8; ++w) ok[w] |= fw[w];
-      if (!A.node_final[s[k]]) break;
-    }
+  for (uint32_t l = 0; l < kStackLists; ++l) {
+    uint32_t* off = h + kStackHdrWords + l * n_off;
+    if (key[l] == kNoKey) std::memset(off, 0, n_off * 4);
+    else std::memcpy(off, &c.key_off_host[(size_t)key[l] * n_seg], n_off * 4);
   }
-  std::memcpy(h + kStackHdrWords, &c.unc_off_host[(size_t)top * (n_chunk + 1)], (size_t)(n_chunk + 1) * 4);
 }
 
 // Host staging of the entry point that allocates nothing: the blob is packed here and copied to the device's
@@ -960,6 +1047,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
                      const FusedLogits* fused = nullptr, bool use_static = false) {
   API_BEGIN
   if (!ms || B <= 0 || !d_bitmask) return fail(XGM_ERR_BAD_ARG, "fill: null argument or empty batch");
+  if (B > 65535) return fail(XGM_ERR_TOO_LARGE, "fill: more than 65535 rows in one call");
   xgm_vocab* v = nullptr;
   size_t n_stacks = 0, n_frames = 0;
   for (int32_t b = 0; b < B; ++b) {
@@ -976,24 +1064,16 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   }
   require_device();
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const int32_t n_chunk = v->dv.n_chunk;
-  const size_t hdr_words = kStackHdrWords + (size_t)n_chunk + 1;
+  const size_t hdr_words = stack_hdr_stride(v->dv.n_seg);
   const size_t off_stacks = (size_t)B * sizeof(RowDesc);
   const size_t off_frames = off_stacks + n_stacks * hdr_words * 4;
-  const size_t off_plan = ((off_frames + n_frames * 2 + 63) / 64) * 64;
-  // capacity: one block per (row, chunk), and the padding to a multiple of kFillGridMultiple
-  const size_t bytes = off_plan + ((size_t)B * n_chunk + kFillGridMultiple) * sizeof(FillBlock);
+  const size_t bytes = ((off_frames + n_frames * 2 + 63) / 64) * 64;
 
   Context& C = ctx();
   std::lock_guard<std::mutex> lock(C.mu);
-  if (use_static && !C.d_log) return fail(XGM_ERR_INTERNAL, "fill: the library's device context does not exist yet");
+  // (the fills' record of walks over the limits is allocated when a mask cache is built: this path allocates nothing)
+  if (use_static && !C.d_log) return fail(XGM_ERR_INTERNAL, "fill (static staging): the library's device context does not exist yet");
   OverflowLog* log = overflow_log();
-  if (C.resident_blocks == 0) {
-    int dev = 0, cus = 0;
-    HIP_OK(hipGetDevice(&dev));
-    HIP_OK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    C.resident_blocks = 2 * std::max(1, cus);
-  }
   void* h_buf = nullptr;
   void* d_buf = nullptr;
   FillSlot* ring = nullptr;
@@ -1027,13 +1107,13 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   for (int32_t b = 0; b < B; ++b) {
     const xgm_matcher* m = ms[b];
     RowDesc& r = rows[b];
-    r.pair_mask = 0;
+    r.epoch = 0;
     r.stack_begin = si;
     r.frame_begin = fi;
     r.n_frames = 0;
     if (m->terminated) {
       r.tab = DevTables{};
-      r.acc = r.unc_list = r.unc_ctx = nullptr;
+      r.acc = r.entries = nullptr;
       r.n_stacks = 0;
       r.flags = 1;
       continue;
@@ -1041,8 +1121,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     const Automaton& A = m->g->A;
     r.tab = m->c->host.tab;
     r.acc = m->c->host.acc;
-    r.unc_list = m->c->host.unc_list;
-    r.unc_ctx = m->c->host.unc_ctx;
+    r.entries = m->c->host.entries;
     r.n_stacks = (uint32_t)m->stacks.size();
     r.flags = Engine(&A).can_terminate(m->stacks) ? 1u : 0u;
     for (auto& s : m->stacks) {
@@ -1052,37 +1131,15 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
       r.n_frames += (uint32_t)s.size();
     }
   }
-  // Plan the workgroups (plan.hpp): two per compute unit are resident at once.
-  auto* plan = reinterpret_cast<FillBlock*>((char*)h_buf + off_plan);
-  int32_t n_blocks = plan_workgroups(
-      B, n_chunk, C.budget_override > 0 ? C.budget_override : plan_budget(C.resident_blocks, B, n_chunk),
-      [&](int32_t b, int32_t c) {
-        uint64_t run = 0;
-        const uint32_t* off0 = hdrs + (size_t)rows[b].stack_begin * hdr_words + kStackHdrWords;
-        for (uint32_t s = 0; s < rows[b].n_stacks; ++s) run += off0[(size_t)s * hdr_words + c] - off0[(size_t)s * hdr_words];
-        return run;
-      },
-      plan);
-  {  // place the workgroups in the launch (plan_slot), idle entries in between
-    C.plan_scratch.assign(plan, plan + n_blocks);
-    const int32_t n_real = n_blocks;
-    n_blocks = (n_real + kFillGridMultiple - 1) / kFillGridMultiple * kFillGridMultiple;
-    for (int32_t k = 0; k < n_blocks; ++k) plan[k] = FillBlock{kNoRow, 0u};
-    for (int32_t p = 0; p < n_real; ++p) plan[plan_slot((uint32_t)p, (uint32_t)n_real)] = C.plan_scratch[p];
-  }
   if (timing) HIP_OK(hipEventRecord(timing[0], stream));
-  const size_t blob_bytes = off_plan + (size_t)n_blocks * sizeof(FillBlock);
-  if (use_static) HIP_OK(hipMemcpyAsync(d_buf, h_buf, blob_bytes, hipMemcpyHostToDevice, stream));
-  else launch_upload(ring->h_dev, d_buf, blob_bytes, stream);
+  if (use_static) HIP_OK(hipMemcpyAsync(d_buf, h_buf, bytes, hipMemcpyHostToDevice, stream));
+  else launch_upload(ring->h_dev, d_buf, bytes, stream);
   if (timing) HIP_OK(hipEventRecord(timing[1], stream));
   const uint32_t seq = ++C.seq;
-  launch_fill(reinterpret_cast<const RowDesc*>(d_buf),
-              reinterpret_cast<const uint32_t*>((char*)d_buf + off_stacks),
-              reinterpret_cast<const uint16_t*>((char*)d_buf + off_frames),
-              reinterpret_cast<const FillBlock*>((char*)d_buf + off_plan), n_blocks, v->dv,
-              reinterpret_cast<uint32_t*>(d_bitmask), log, seq, d_step_counter, stream,
-              fused ? fused->d_logits : nullptr, fused ? fused->esize : 0, fused ? fused->neg_inf : 0u,
-              fused ? fused->V_logits : 0, fused ? fused->row_stride : 0, C.pair_min_entries);
+  launch_fill(reinterpret_cast<const RowDesc*>(d_buf), reinterpret_cast<const uint32_t*>((char*)d_buf + off_stacks),
+              reinterpret_cast<const uint16_t*>((char*)d_buf + off_frames), B, v->dv, reinterpret_cast<uint32_t*>(d_bitmask),
+              log, seq, d_step_counter, stream, fused ? fused->d_logits : nullptr, fused ? fused->esize : 0,
+              fused ? fused->neg_inf : 0u, fused ? fused->V_logits : 0, fused ? fused->row_stride : 0);
   HIP_OK(hipGetLastError());
   if (timing) HIP_OK(hipEventRecord(timing[2], stream));
   if (ring) {
@@ -1090,13 +1147,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     ring->used = true;
     C.next_slot = (C.next_slot + 1) % Context::kSlots;
   }
-  C.last_blob = h_buf;
-  C.last_batch = nullptr;
-  C.last_seq = seq;
-  C.last_B = B;
-  C.last_bitmask = d_bitmask;
-  C.last_vocab = v;
-  C.last_matchers.assign(ms, ms + B);
+  set_pending(ring ? ring->fill : C.static_fill, seq, B, d_bitmask, h_buf, ms);
   return XGM_OK;
   API_END
 }
@@ -1136,22 +1187,6 @@ int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, vo
   if (rc != XGM_OK) return rc;
   return fill_impl(ms, B, d_bitmask, hip_stream, nullptr, nullptr, &f);
   API_END
-}
-
-int32_t xgm_debug_set_fill_budget(int32_t workgroups) {
-  Context& C = ctx();
-  std::lock_guard<std::mutex> lock(C.mu);
-  const int32_t old = C.budget_override;
-  C.budget_override = workgroups > 0 ? workgroups : 0;
-  return old;
-}
-
-int32_t xgm_debug_set_fill_pair_threshold(int32_t entries) {
-  Context& C = ctx();
-  std::lock_guard<std::mutex> lock(C.mu);
-  const int32_t old = (int32_t)C.pair_min_entries;
-  C.pair_min_entries = entries < 0 ? kFillPairMinEntries : (uint32_t)entries;
-  return old;
 }
 
 int xgm_debug_fill_count_steps(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void* hip_stream,
@@ -1214,7 +1249,7 @@ static void read_row_state(const xgm_batch& bt, int32_t row, bool* terminated, s
   *terminated = (m.flags & 2u) != 0;
   stacks->clear();
   if (m.n_stacks == 0) return;
-  const size_t hdr_words = kStackHdrWords + (size_t)bt.dev.n_chunk + 1;
+  const size_t hdr_words = stack_hdr_stride(bt.dev.n_seg);
   const size_t slot = (size_t)row * bt.H + head;
   std::vector<uint32_t> hdrs((size_t)m.n_stacks * hdr_words);
   HIP_OK(hipMemcpy(hdrs.data(), bt.dev.hdrs + slot * kBatchMaxStacks * hdr_words, hdrs.size() * 4, hipMemcpyDeviceToHost));
@@ -1229,76 +1264,92 @@ static void read_row_state(const xgm_batch& bt, int32_t row, bool* terminated, s
   }
 }
 
+namespace {
+// is the token allowed from some of these stacks?  (exact, on the host; throws if the host limits are exceeded too)
+bool host_decides(const Automaton& A, const xgm_vocab& v, const std::vector<Stack>& stacks, int32_t id) {
+  Engine engine(&A);
+  for (const Stack& st : stacks) {
+    std::vector<Stack> out;
+    const int rc = engine.advance({st}, v.bytes.data() + v.off[id], (int)(v.off[id + 1] - v.off[id]), &out, nullptr, (size_t)-1);
+    if (rc == XGM_OK) return true;
+    if (rc != XGM_ERR_TOKEN_REJECTED) throw Failure(rc, "fixup: a token walk exceeds the host limits too");
+  }
+  return false;
+}
+// writes the exact bit either way (a fused fill leaves such a token allowed until now)
+void patch_bit(int32_t* d_bitmask, int32_t W, int32_t row, int32_t id, bool allowed) {
+  uint32_t word = 0;
+  int32_t* p = d_bitmask + (size_t)row * W + (id >> 5);
+  HIP_OK(hipMemcpy(&word, p, 4, hipMemcpyDeviceToHost));
+  if (allowed) word |= 1u << (id & 31); else word &= ~(1u << (id & 31));
+  HIP_OK(hipMemcpy(p, &word, 4, hipMemcpyHostToDevice));
+}
+// the records [seen, count) of a log (at most kCap of them are still there)
+std::vector<std::array<uint32_t, 4>> fresh_records(const OverflowLog* log, uint32_t seen, uint32_t count) {
+  std::vector<std::array<uint32_t, 4>> out;
+  const uint32_t fresh = count - seen;
+  if (fresh == 0) return out;
+  if (fresh > OverflowLog::kCap) throw Failure(XGM_ERR_TOO_LARGE, "fixup: more recorded walks than the log holds");
+  std::vector<uint32_t> ent((size_t)OverflowLog::kCap * 4);
+  HIP_OK(hipMemcpy(ent.data(), log->entry, ent.size() * 4, hipMemcpyDeviceToHost));
+  for (uint32_t k = 0; k < fresh; ++k) {
+    const uint32_t* e = &ent[(size_t)((seen + k) % OverflowLog::kCap) * 4];
+    out.push_back({e[0], e[1], e[2], e[3]});
+  }
+  return out;
+}
+}  // namespace
+
 int xgm_fill_overflow_fixup(void* hip_stream) {
   API_BEGIN
   Context& C = ctx();
   std::lock_guard<std::mutex> lock(C.mu);
-  if (!C.last_blob && !C.last_batch) return 0;
+  if (!C.d_log) return 0;
   HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
-  const uint32_t count = read_overflow_count();
-  const uint32_t fresh = count - C.seen_count;
-  if (fresh == 0) return 0;
-  if (fresh > OverflowLog::kCap) return fail(XGM_ERR_TOO_LARGE, "fixup: more recorded walks than the log holds");
-  std::vector<uint32_t> ent((size_t)OverflowLog::kCap * 3);
-  HIP_OK(hipMemcpy(ent.data(), overflow_log()->entry, ent.size() * 4, hipMemcpyDeviceToHost));
-  const xgm_vocab& v = *C.last_vocab;
-  // the stacks of that fill: in its staging blob, or (device-resident states) read back from the device
-  auto stacks_of = [&](int32_t b, std::vector<Stack>* out) {
-    if (C.last_batch) {
-      bool terminated = false;
-      read_row_state(*C.last_batch, b, &terminated, out);
-      return;
-    }
-    const auto* rows = reinterpret_cast<const RowDesc*>(C.last_blob);
-    const size_t hdr_words = kStackHdrWords + (size_t)v.dv.n_chunk + 1;
-    const auto* hdrs = reinterpret_cast<const uint32_t*>((const char*)C.last_blob + (size_t)C.last_B * sizeof(RowDesc));
+  const uint32_t count = read_overflow_count(C.d_log);
+  const auto records = fresh_records(C.d_log, C.seen_count, count);
+  int handled = 0, lost = 0;
+  for (const auto& e : records) {
+    // the fill that recorded it: one of the last fills from the ring of staging slots, or the last one staged statically
+    const PendingFill* f = C.static_fill.seq == e[0] && e[0] != 0 ? &C.static_fill : nullptr;
+    for (const FillSlot& slot : C.slot)
+      if (slot.fill.seq == e[0] && e[0] != 0) f = &slot.fill;
+    const int32_t b = (int32_t)e[1], id = (int32_t)e[2];
+    if (!f || b >= f->B) { ++lost; continue; }
+    const xgm_cache& c = *f->caches[b];
+    const xgm_vocab& v = *c.v;
+    // the row's stacks as that fill packed them
+    const auto* rows = reinterpret_cast<const RowDesc*>(f->blob);
+    const size_t hdr_words = stack_hdr_stride(v.dv.n_seg);
+    const auto* hdrs = reinterpret_cast<const uint32_t*>((const char*)f->blob + (size_t)f->B * sizeof(RowDesc));
     size_t n_stacks = 0;
-    for (int32_t r = 0; r < C.last_B; ++r) n_stacks += rows[r].n_stacks;
+    for (int32_t r = 0; r < f->B; ++r) n_stacks += rows[r].n_stacks;
     const auto* frames = reinterpret_cast<const uint16_t*>(hdrs + n_stacks * hdr_words);
-    out->clear();
+    std::vector<Stack> stacks;
     for (uint32_t s = 0; s < rows[b].n_stacks; ++s) {
       const uint32_t* h = hdrs + (size_t)(rows[b].stack_begin + s) * hdr_words;
-      out->emplace_back(frames + h[kStackHdrFrames], frames + h[kStackHdrFrames] + h[kStackHdrDepth]);
+      stacks.emplace_back(frames + h[kStackHdrFrames], frames + h[kStackHdrFrames] + h[kStackHdrDepth]);
     }
-  };
-  const int32_t W = v.dv.W;
-  int handled = 0;
-  for (uint32_t k = 0; k < fresh; ++k) {
-    const uint32_t* e = &ent[(size_t)((C.seen_count + k) % OverflowLog::kCap) * 3];
-    if (e[0] != C.last_seq) continue;
-    const int32_t b = (int32_t)e[1], id = (int32_t)e[2];
-    Engine engine(C.last_batch ? &C.last_batch->caches[b]->g->A : &C.last_matchers[b]->g->A);
-    std::vector<Stack> stacks;
-    stacks_of(b, &stacks);
-    bool ok = false;
-    for (size_t s = 0; s < stacks.size() && !ok; ++s) {
-      std::vector<Stack> out;
-      int rc = engine.advance({stacks[s]}, v.bytes.data() + v.off[id], (int)(v.off[id + 1] - v.off[id]), &out, nullptr, (size_t)-1);
-      if (rc == XGM_OK) ok = true;
-      else if (rc != XGM_ERR_TOKEN_REJECTED) return fail(rc, "fixup: a token walk exceeds the host limits too");
-    }
-    {  // the exact bit, either way (a fused fill leaves such a token allowed until now)
-      uint32_t word = 0;
-      int32_t* p = C.last_bitmask + (size_t)b * W + (id >> 5);
-      HIP_OK(hipMemcpy(&word, p, 4, hipMemcpyDeviceToHost));
-      if (ok) word |= 1u << (id & 31); else word &= ~(1u << (id & 31));
-      HIP_OK(hipMemcpy(p, &word, 4, hipMemcpyHostToDevice));
-    }
+    patch_bit(f->d_bitmask, v.dv.W, b, id, host_decides(c.g->A, v, stacks, id));
     ++handled;
   }
   C.seen_count = count;
+  if (lost)
+    return fail(XGM_ERR_TOO_LARGE, "fixup: " + std::to_string(lost) + " recorded walks belong to fills whose staging memory has been "
+                                   "used again (more than 8 fills ago); " + std::to_string(handled) + " were decided");
   return handled;
   API_END
 }
 
-// ------------------------------------------------- device-resident states
-namespace {
-uint32_t pair_threshold() {
-  Context& C = ctx();
-  std::lock_guard<std::mutex> lock(C.mu);
-  return C.pair_min_entries;
+const uint32_t* xgm_fill_overflow_count_device(void) {
+  try {
+    std::lock_guard<std::mutex> lock(ctx().mu);
+    return &overflow_log()->count;
+  } catch (const Failure& f) { fail(f); return nullptr; }
 }
 
+// ------------------------------------------------- device-resident states
+namespace {
 // what the matcher's current state looks like in slot `slot` of row `row`
 struct PackedState {
   SlotMeta meta{};
@@ -1309,13 +1360,12 @@ struct PackedState {
 PackedState pack_state(const xgm_batch& bt, int32_t row, int32_t slot, const xgm_matcher& m) {
   const xgm_cache& c = *bt.caches[row];
   const Automaton& A = c.g->A;
-  const size_t hdr_words = kStackHdrWords + (size_t)bt.dev.n_chunk + 1;
+  const size_t hdr_words = stack_hdr_stride(bt.dev.n_seg);
   const size_t at = (size_t)row * bt.H + slot;
   PackedState p;
   p.row.tab = c.host.tab;
   p.row.acc = c.host.acc;
-  p.row.unc_list = c.host.unc_list;
-  p.row.unc_ctx = c.host.unc_ctx;
+  p.row.entries = c.host.entries;
   p.row.stack_begin = (uint32_t)(at * kBatchMaxStacks);
   p.row.frame_begin = (uint32_t)(at * kBatchRowFrames);
   if (m.terminated) {
@@ -1340,9 +1390,11 @@ PackedState pack_state(const xgm_batch& bt, int32_t row, int32_t slot, const xgm
   p.row.flags = p.meta.flags & 1u;
   return p;
 }
-void write_state(const xgm_batch& bt, int32_t row, int32_t slot, const PackedState& p) {
-  const size_t hdr_words = kStackHdrWords + (size_t)bt.dev.n_chunk + 1;
+// `epoch`: the row's count of state changes after this write
+void write_state(const xgm_batch& bt, int32_t row, int32_t slot, PackedState p, uint32_t epoch) {
+  const size_t hdr_words = stack_hdr_stride(bt.dev.n_seg);
   const size_t at = (size_t)row * bt.H + slot;
+  p.row.epoch = epoch;
   HIP_OK(hipMemcpy(bt.dev.meta + at, &p.meta, sizeof(SlotMeta), hipMemcpyHostToDevice));
   if (!p.hdrs.empty()) HIP_OK(hipMemcpy(bt.dev.hdrs + at * kBatchMaxStacks * hdr_words, p.hdrs.data(), p.hdrs.size() * 4, hipMemcpyHostToDevice));
   if (!p.frames.empty()) HIP_OK(hipMemcpy(bt.dev.frames + at * kBatchRowFrames, p.frames.data(), p.frames.size() * 2, hipMemcpyHostToDevice));
@@ -1361,9 +1413,6 @@ int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* h
     if (v && ms[b]->v != v) return fail(XGM_ERR_BAD_ARG, "batch_create: all matchers must share one vocabulary");
     v = ms[b]->v;
   }
-  const int32_t n_chunk = v->dv.n_chunk;
-  if ((size_t)B * ((n_chunk + 1 + 3) & ~3) * 4 > (size_t)128 * 1024)  // the planner's running counts live in LDS
-    return fail(XGM_ERR_TOO_LARGE, "batch_create: rows x vocabulary chunks beyond what the device planner holds");
   require_device();
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   auto* bt = new xgm_batch();
@@ -1374,23 +1423,12 @@ int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* h
     ++v->refs;
     for (int32_t b = 0; b < B; ++b) { bt->caches.push_back(ms[b]->c); ++ms[b]->c->refs; }
     auto keep = [&](auto* p) { bt->dev_ptrs.push_back((void*)p); return p; };
-    const size_t hdr_words = kStackHdrWords + (size_t)n_chunk + 1;
+    const size_t hdr_words = stack_hdr_stride(v->dv.n_seg);
     const size_t slots = (size_t)B * bt->H;
     DevBatch& d = bt->dev;
     d.B = B;
     d.H = bt->H;
-    d.n_chunk = n_chunk;
-    {
-      Context& C = ctx();
-      std::lock_guard<std::mutex> lock(C.mu);
-      if (C.resident_blocks == 0) {
-        int dev = 0, cus = 0;
-        HIP_OK(hipGetDevice(&dev));
-        HIP_OK(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        C.resident_blocks = 2 * std::max(1, cus);
-      }
-      d.budget = C.budget_override > 0 ? C.budget_override : plan_budget(C.resident_blocks, B, n_chunk);
-    }
+    d.n_seg = v->dv.n_seg;
     std::vector<DevCache> caches(B);
     for (int32_t b = 0; b < B; ++b) caches[b] = ms[b]->c->host;
     d.cache = keep(dev_upload(caches));
@@ -1401,17 +1439,15 @@ int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* h
     d.head = keep(dev_alloc<int32_t>(B));
     d.older = keep(dev_alloc<int32_t>(B));
     d.status = keep(dev_alloc<int32_t>(B));
-    d.plan_cap = batch_plan_cap(B, n_chunk, d.budget);
-    d.plan = keep(dev_alloc<FillBlock>(d.plan_cap));
-    d.pair = keep(dev_alloc<uint32_t>((size_t)B * kBatchMaxStacks * kPairWords));
+    d.log = keep(new_log());
     HIP_OK(hipMemset(d.meta, 0, slots * sizeof(SlotMeta)));
     HIP_OK(hipMemset(d.head, 0, (size_t)B * 4));
     HIP_OK(hipMemset(d.older, 0, (size_t)B * 4));
     HIP_OK(hipMemset(d.status, 0, (size_t)B * 4));
-    for (int32_t b = 0; b < B; ++b) write_state(*bt, b, 0, pack_state(*bt, b, 0, *ms[b]));
-    launch_batch_plan(d, v->dv, pair_threshold(), stream);
-    HIP_OK(hipGetLastError());
+    for (int32_t b = 0; b < B; ++b) write_state(*bt, b, 0, pack_state(*bt, b, 0, *ms[b]), 0u);
     HIP_OK(hipStreamSynchronize(stream));
+    std::lock_guard<std::mutex> lock(ctx().mu);
+    ctx().batches.insert(bt);
   } catch (...) {
     xgm_batch_destroy(bt);
     throw;
@@ -1426,7 +1462,11 @@ void xgm_batch_destroy(xgm_batch* bt) {
   {
     Context& C = ctx();
     std::lock_guard<std::mutex> lock(C.mu);
-    if (C.last_batch == bt) C.last_batch = nullptr;
+    if (C.batches.erase(bt) && bt->dev.log) {
+      uint32_t n = 0;  // its records stay in the process-wide total
+      if (hipDeviceSynchronize() == hipSuccess && hipMemcpy(&n, &bt->dev.log->count, 4, hipMemcpyDeviceToHost) == hipSuccess)
+        C.retired_records += n;
+    }
   }
   for (void* p : bt->dev_ptrs) (void)hipFree(p);
   for (xgm_cache* c : bt->caches) release(c);
@@ -1439,7 +1479,7 @@ int32_t xgm_batch_size(const xgm_batch* bt) { return bt ? bt->B : XGM_ERR_BAD_AR
 int xgm_batch_accept_tokens(xgm_batch* bt, const int32_t* d_token_ids, void* hip_stream) {
   API_BEGIN
   if (!bt || !d_token_ids) return fail(XGM_ERR_BAD_ARG, "batch_accept_tokens: null argument");
-  launch_batch_accept(bt->dev, bt->v->dv, d_token_ids, pair_threshold(), static_cast<hipStream_t>(hip_stream));
+  launch_batch_accept(bt->dev, bt->v->dv, d_token_ids, static_cast<hipStream_t>(hip_stream));
   HIP_OK(hipGetLastError());
   return XGM_OK;
   API_END
@@ -1448,7 +1488,7 @@ int xgm_batch_accept_tokens(xgm_batch* bt, const int32_t* d_token_ids, void* hip
 int xgm_batch_rollback(xgm_batch* bt, const int32_t* d_steps, void* hip_stream) {
   API_BEGIN
   if (!bt || !d_steps) return fail(XGM_ERR_BAD_ARG, "batch_rollback: null argument");
-  launch_batch_rollback(bt->dev, bt->v->dv, d_steps, pair_threshold(), static_cast<hipStream_t>(hip_stream));
+  launch_batch_rollback(bt->dev, d_steps, static_cast<hipStream_t>(hip_stream));
   HIP_OK(hipGetLastError());
   return XGM_OK;
   API_END
@@ -1458,7 +1498,7 @@ int xgm_batch_fork(xgm_batch* bt, const int32_t* d_src_rows, void* hip_stream) {
   API_BEGIN
   if (!bt || !d_src_rows) return fail(XGM_ERR_BAD_ARG, "batch_fork: null argument");
   if (bt->H < 2) return fail(XGM_ERR_BAD_ARG, "batch_fork: the batch was created without history (a forked state is written beside the current one)");
-  launch_batch_fork(bt->dev, bt->v->dv, d_src_rows, pair_threshold(), static_cast<hipStream_t>(hip_stream));
+  launch_batch_fork(bt->dev, d_src_rows, static_cast<hipStream_t>(hip_stream));
   HIP_OK(hipGetLastError());
   return XGM_OK;
   API_END
@@ -1496,17 +1536,17 @@ int xgm_batch_set_row(xgm_batch* bt, int32_t row, const xgm_matcher* m, void* hi
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   HIP_OK(hipStreamSynchronize(stream));
   int32_t head = 0, older = 0;
+  RowDesc cur{};
   HIP_OK(hipMemcpy(&head, bt->dev.head + row, 4, hipMemcpyDeviceToHost));
   HIP_OK(hipMemcpy(&older, bt->dev.older + row, 4, hipMemcpyDeviceToHost));
+  HIP_OK(hipMemcpy(&cur, bt->dev.rows + row, sizeof(RowDesc), hipMemcpyDeviceToHost));
   const int32_t next = (head + 1) % bt->H;
-  write_state(*bt, row, next, pack_state(*bt, row, next, *m));
+  write_state(*bt, row, next, pack_state(*bt, row, next, *m), cur.epoch + 1u);
   older = std::min(older + 1, bt->H - 1);
   const int32_t ok = XGM_OK;
   HIP_OK(hipMemcpy(bt->dev.head + row, &next, 4, hipMemcpyHostToDevice));
   HIP_OK(hipMemcpy(bt->dev.older + row, &older, 4, hipMemcpyHostToDevice));
   HIP_OK(hipMemcpy(bt->dev.status + row, &ok, 4, hipMemcpyHostToDevice));
-  launch_batch_plan(bt->dev, bt->v->dv, pair_threshold(), stream);
-  HIP_OK(hipGetLastError());
   return XGM_OK;
   API_END
 }
@@ -1548,47 +1588,22 @@ int xgm_debug_lds_lookup_rate(void* hip_stream, double* h_lookups_per_second) {
   API_END
 }
 
-int32_t xgm_debug_batch_plan(xgm_batch* bt, uint32_t* h_out, int32_t cap, int32_t* h_budget, void* hip_stream) {
-  API_BEGIN
-  if (!bt || !h_out || cap < 0) return fail(XGM_ERR_BAD_ARG, "batch_plan: bad argument");
-  HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
-  std::vector<FillBlock> plan(bt->dev.plan_cap);
-  HIP_OK(hipMemcpy(plan.data(), bt->dev.plan, plan.size() * sizeof(FillBlock), hipMemcpyDeviceToHost));
-  int32_t n_real = 0;
-  for (const FillBlock& f : plan) n_real += f.row != kNoRow;
-  if (n_real > cap) return fail(XGM_ERR_BAD_ARG, "batch_plan: the output array is too small");
-  int32_t n = 0;
-  for (int32_t p = 0; p < n_real; ++p) {  // in the planner's order
-    const FillBlock& f = plan[plan_slot((uint32_t)p, (uint32_t)n_real)];
-    if (f.row == kNoRow) return fail(XGM_ERR_INTERNAL, "batch_plan: a planned workgroup is missing from its place in the launch");
-    h_out[3 * n] = f.row;
-    h_out[3 * n + 1] = f.c0c1 & 0x7FFFu;
-    h_out[3 * n + 2] = f.c0c1 >> 16;
-    ++n;
-  }
-  if (h_budget) *h_budget = bt->dev.budget;
-  return n;
-  API_END
-}
-
 static int batch_fill_impl(xgm_batch* bt, int32_t* d_bitmask, void* hip_stream, const FusedLogits* fused) {
   if (!bt || !d_bitmask) return fail(XGM_ERR_BAD_ARG, "batch_fill: null argument");
-  Context& C = ctx();
-  std::lock_guard<std::mutex> lock(C.mu);
-  OverflowLog* log = overflow_log();
-  const uint32_t seq = ++C.seq;
+  uint32_t seq;
+  {
+    Context& C = ctx();
+    std::lock_guard<std::mutex> lock(C.mu);
+    seq = ++C.seq;
+  }
   const DevBatch& d = bt->dev;
-  launch_fill(d.rows, d.hdrs, d.frames, d.plan, (int32_t)d.plan_cap, bt->v->dv, reinterpret_cast<uint32_t*>(d_bitmask), log, seq,
-              nullptr, static_cast<hipStream_t>(hip_stream), fused ? fused->d_logits : nullptr, fused ? fused->esize : 0,
-              fused ? fused->neg_inf : 0u, fused ? fused->V_logits : 0, fused ? fused->row_stride : 0, C.pair_min_entries, d.pair);
+  launch_fill(d.rows, d.hdrs, d.frames, d.B, bt->v->dv, reinterpret_cast<uint32_t*>(d_bitmask), d.log, seq, nullptr,
+              static_cast<hipStream_t>(hip_stream), fused ? fused->d_logits : nullptr, fused ? fused->esize : 0,
+              fused ? fused->neg_inf : 0u, fused ? fused->V_logits : 0, fused ? fused->row_stride : 0);
   HIP_OK(hipGetLastError());
-  C.last_blob = nullptr;
-  C.last_batch = bt;
-  C.last_seq = seq;
-  C.last_B = bt->B;
-  C.last_bitmask = d_bitmask;
-  C.last_vocab = bt->v;
-  C.last_matchers.clear();
+  bt->fill_seq[bt->next_fill] = seq;
+  bt->fill_bitmask[bt->next_fill] = d_bitmask;
+  bt->next_fill = (bt->next_fill + 1) % xgm_batch::kFills;
   return XGM_OK;
 }
 
@@ -1609,11 +1624,48 @@ int xgm_batch_fill_and_apply(xgm_batch* bt, int32_t* d_bitmask, void* d_logits, 
   API_END
 }
 
+int xgm_batch_fill_overflow_fixup(xgm_batch* bt, void* hip_stream) {
+  API_BEGIN
+  if (!bt) return fail(XGM_ERR_BAD_ARG, "batch_fill_overflow_fixup: null batch");
+  HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+  const uint32_t count = read_overflow_count(bt->dev.log);
+  const auto records = fresh_records(bt->dev.log, bt->seen_count, count);
+  const xgm_vocab& v = *bt->v;
+  int handled = 0, lost = 0, stale = 0;
+  for (const auto& e : records) {
+    int32_t* d_bitmask = nullptr;
+    for (int k = 0; k < xgm_batch::kFills; ++k)
+      if (bt->fill_seq[k] == e[0] && e[0] != 0) d_bitmask = bt->fill_bitmask[k];
+    const int32_t b = (int32_t)e[1], id = (int32_t)e[2];
+    if (!d_bitmask || b >= bt->B) { ++lost; continue; }
+    RowDesc cur{};
+    HIP_OK(hipMemcpy(&cur, bt->dev.rows + b, sizeof(RowDesc), hipMemcpyDeviceToHost));
+    if (cur.epoch != e[3]) { ++stale; continue; }  // the row has moved on since that fill: its stacks are gone
+    bool terminated = false;
+    std::vector<Stack> stacks;
+    read_row_state(*bt, b, &terminated, &stacks);
+    patch_bit(d_bitmask, v.dv.W, b, id, host_decides(bt->caches[b]->g->A, v, stacks, id));
+    ++handled;
+  }
+  bt->seen_count = count;
+  if (lost || stale)
+    return fail(XGM_ERR_TOO_LARGE, "batch fixup: " + std::to_string(stale) + " recorded walks belong to states that the rows have left, " +
+                                   std::to_string(lost) + " to fills more than 8 fills ago; " + std::to_string(handled) + " were decided");
+  return handled;
+  API_END
+}
+
+const uint32_t* xgm_batch_overflow_count_device(const xgm_batch* bt) { return bt ? &bt->dev.log->count : nullptr; }
+
 int64_t xgm_overflow_total(void) {
   try {
-    std::lock_guard<std::mutex> lock(ctx().mu);
+    Context& C = ctx();
+    std::lock_guard<std::mutex> lock(C.mu);
     HIP_OK(hipDeviceSynchronize());
-    return (int64_t)read_overflow_count();
+    int64_t total = C.retired_records;
+    if (C.d_log) total += read_overflow_count(C.d_log);
+    for (const xgm_batch* bt : C.batches) total += read_overflow_count(bt->dev.log);
+    return total;
   } catch (const Failure& f) { return fail(f); }
 }
 

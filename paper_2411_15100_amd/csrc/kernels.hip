@@ -5,7 +5,6 @@
 #include <algorithm>
 
 #include "kernels.hpp"
-#include "plan.hpp"
 #include "walk.hpp"
 
 namespace xgm {
@@ -13,11 +12,12 @@ namespace xgm {
 namespace {
 
 
-__device__ __forceinline__ void record_overflow(OverflowLog* log, uint32_t seq, uint32_t a, uint32_t b) {
+__device__ __forceinline__ void record_overflow(OverflowLog* log, uint32_t seq, uint32_t a, uint32_t b, uint32_t epoch = 0u) {
   uint32_t slot = atomicAdd(&log->count, 1u) % OverflowLog::kCap;
   log->entry[slot][0] = seq;
   log->entry[slot][1] = a;
   log->entry[slot][2] = b;
+  log->entry[slot][3] = epoch;
 }
 
 // Copy the staged part of a grammar's table image into LDS, 16 bytes per load
@@ -258,159 +258,6 @@ __global__ __launch_bounds__(kPermuteThreads) void permute_kernel(DevVocab voc, 
   }
 }
 
-__global__ void count_uncertain_kernel(DevVocab voc, const uint32_t* __restrict__ unc_id, uint32_t* __restrict__ counts) {
-  // one workgroup of kChunkWords threads per (chunk, node)
-  __shared__ uint32_t s[kChunkWords];
-  const size_t node = blockIdx.y;
-  const int32_t w = blockIdx.x * kChunkWords + threadIdx.x;
-  s[threadIdx.x] = (w < voc.W) ? __popc(unc_id[node * voc.W + w]) : 0u;
-  __syncthreads();
-  for (int d = kChunkWords / 2; d > 0; d >>= 1) {
-    if ((int)threadIdx.x < d) s[threadIdx.x] += s[threadIdx.x + d];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) counts[node * voc.n_chunk + blockIdx.x] = s[0];
-}
-
-__global__ void list_uncertain_kernel(DevVocab voc, const uint32_t* __restrict__ unc_id, const uint32_t* __restrict__ off,
-                                      uint32_t* __restrict__ list) {
-  __shared__ uint32_t s[kChunkWords];
-  const size_t node = blockIdx.y;
-  const int32_t w = blockIdx.x * kChunkWords + threadIdx.x;
-  uint32_t bits = (w < voc.W) ? unc_id[node * voc.W + w] : 0u;
-  s[threadIdx.x] = __popc(bits);
-  __syncthreads();
-  // inclusive scan (Hillis-Steele) over the 128 per-word counts
-  for (int d = 1; d < kChunkWords; d <<= 1) {
-    uint32_t v = ((int)threadIdx.x >= d) ? s[threadIdx.x - d] : 0u;
-    __syncthreads();
-    s[threadIdx.x] += v;
-    __syncthreads();
-  }
-  uint32_t pos = off[node * (voc.n_chunk + 1) + blockIdx.x] + s[threadIdx.x] - __popc(bits);
-  while (bits) {
-    const uint32_t b = __ffs(bits) - 1;
-    bits &= bits - 1;
-    list[pos++] = threadIdx.x * 32 + b;
-  }
-}
-
-// One workgroup per (chunk, node) list: every entry's token is walked once
-// more from the node to find where it leaves the node's frame (the walk reads
-// the tables from global memory: most lists are empty or short, staging would
-// cost more), then the list is sorted by the number of bytes left after that
-// position, so that neighbouring lanes of the fill kernel get walks of
-// similar length.
-constexpr int kAnnotateThreads = 256;
-__global__ __launch_bounds__(kAnnotateThreads) void annotate_lists_kernel(DevTables tab, DevVocab voc, int32_t node0,
-                                                                          const uint32_t* __restrict__ off,
-                                                                          uint32_t* __restrict__ list) {
-  __shared__ uint32_t seg[kChunkTokens];
-  __shared__ uint8_t rem_of[kChunkTokens];
-  __shared__ uint32_t bucket[16];
-  const int32_t node = node0 + blockIdx.y, chunk = blockIdx.x;
-  const uint32_t j0 = off[(size_t)node * (voc.n_chunk + 1) + chunk], j1 = off[(size_t)node * (voc.n_chunk + 1) + chunk + 1];
-  const uint32_t n = j1 - j0;
-  if (n == 0) return;
-  if (threadIdx.x < 16) bucket[threadIdx.x] = 0u;
-  __syncthreads();
-  const LdsTab T(tab, nullptr);  // launched with nothing staged
-  for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
-    const uint32_t lid = list[j0 + e] & 0xFFFu;
-    const int32_t id = chunk * kChunkTokens + (int32_t)lid;
-    const uint4 tk = voc.tok_by_id[id];
-    int len = (int)(tk.w >> 24);
-    const uint8_t* ext = voc.bytes;
-    if (len >= 15) {
-      ext = voc.bytes + voc.off_by_id[id];
-      if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
-    }
-    uint32_t exits = 0;
-    const int res = walk_token<true>(T, tk, ext, len, (uint32_t)node, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node), 0, &exits);
-    uint32_t meta = kEntryFullWalk, pos = 0, late = 0;
-    if (res != kOverflow && exits != 0u && (exits & (exits - 1u)) == 0u && !(exits & 0x80000000u)) {
-      const uint32_t k = __ffs(exits) - 1;  // the single exit position, 0..30
-      const uint32_t suffix = (uint32_t)len - k;
-      if (suffix == 1u) { meta = kEntrySuffix1; pos = k; }
-      else if (suffix == 2u) { meta = kEntrySuffix2; pos = k; }
-      else if (k <= 12u) { meta = k; pos = k; }
-      else late = k;                        // kind stays kEntryFullWalk, the position goes into the second byte field
-    }
-    const uint32_t b1 = token_byte(tk, ext, (int)pos);
-    const uint32_t b2 = meta == kEntryFullWalk ? late : ((int)pos + 1 < len ? token_byte(tk, ext, (int)pos + 1) : 0u);
-    const uint32_t rem = min(15, len - (int)(late ? late : pos));
-    seg[e] = lid | (meta << 12) | (b1 << 16) | (b2 << 24);
-    rem_of[e] = (uint8_t)rem;
-    atomicAdd(&bucket[rem], 1u);
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {  // exclusive scan of the 16 bucket sizes
-    uint32_t run = 0;
-    for (int k = 0; k < 16; ++k) { const uint32_t c = bucket[k]; bucket[k] = run; run += c; }
-  }
-  __syncthreads();
-  for (uint32_t e = threadIdx.x; e < n; e += kAnnotateThreads) {
-    list[j0 + atomicAdd(&bucket[rem_of[e]], 1u)] = seg[e];
-  }
-}
-
-// The per-context classes of every list entry (see kCtx*): one thread per
-// entry over all lists of the grammar, tables staged as in the classify
-// kernel.  For each context node of the entry's rule the entry's suffix is
-// walked from that node with nothing known below it.
-constexpr int kContextThreads = 768;
-__global__ __launch_bounds__(kContextThreads) void context_classes_kernel(DevTables tab, DevVocab voc, int32_t n_nodes,
-                                                                          uint32_t total,
-                                                                          const uint32_t* __restrict__ off,
-                                                                          const uint32_t* __restrict__ list,
-                                                                          uint32_t* __restrict__ list_ctx,
-                                                                          const uint32_t* __restrict__ ctx_off,
-                                                                          const uint16_t* __restrict__ ctx_node) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  stage_tables(tab, smem, kContextThreads);
-  __syncthreads();
-  auto body = [&](const auto& T) {
-    const uint32_t j = blockIdx.x * kContextThreads + threadIdx.x;
-    if (j >= total) return;
-    // the entry's (node, chunk): the last slot of `off` that starts at or before j
-    const uint32_t stride = (uint32_t)voc.n_chunk + 1u;
-    uint32_t lo = 0u, hi = (uint32_t)n_nodes * stride;  // off[lo] <= j < off[hi - 1 + 1 ...]; the last slot equals total
-    while (hi - lo > 1u) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (off[mid] <= j) lo = mid; else hi = mid;
-    }
-    const uint32_t node = lo / stride, chunk = lo % stride;
-    const uint32_t e = list[j];
-    const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, b2 = e >> 24;
-    const int32_t id = (int32_t)(chunk * kChunkTokens + lid);
-    const uint4 tk = voc.tok_by_id[id];
-    int len = (int)(tk.w >> 24);
-    const uint8_t* ext = voc.bytes;
-    if (len >= 15) {
-      ext = voc.bytes + voc.off_by_id[id];
-      if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
-    }
-    // where the suffix starts (-1: the entry has several exits)
-    const int from = meta <= 12u ? (int)meta : meta == kEntrySuffix2 ? len - 2 : meta == kEntrySuffix1 ? len - 1
-                                                                                  : (b2 != 0u ? (int)b2 : -1);
-    const uint32_t rule = T.header(node).y >> 16;
-    const uint32_t ctx0 = ctx_off[rule], n_ctx = ctx_off[rule + 1] - ctx0;  // 0 .. kCtxMax
-    uint32_t classes = 0u;
-    for (uint32_t i = 0; i < kCtxMax; ++i) {
-      uint32_t code = kCtxWalk;
-      if (from >= 0 && i < n_ctx) {
-        const uint32_t r = ctx_node[ctx0 + i];
-        const int c = walk_token<true>(T, tk, ext, len, r, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r), from);
-        code = c == kAccept ? kCtxAccept : (c == kUncertain || c == kOverflow) ? kCtxWalk : kCtxReject;
-      }
-      classes |= code << (2u * i);
-    }
-    list_ctx[j] = classes;
-  };
-  if (small_sections_staged(tab)) body(LdsTabT<true>(tab, smem));
-  else body(LdsTab(tab, smem));
-}
-
 // Many nodes of a grammar have the same accepted bitset (the inside of a string is
 // the inside of a string wherever it occurs), so the cache keeps every distinct
 // row once.  The digest only proposes which rows might be equal: the position-
@@ -422,23 +269,232 @@ __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
   x ^= x >> 27; x *= 0x94D049BB133111EBull;
   return x ^ (x >> 31);
 }
-__global__ __launch_bounds__(kRowThreads) void hash_rows_kernel(const uint32_t* __restrict__ rows, int32_t W,
-                                                                unsigned long long* __restrict__ digest) {
+constexpr int kMaxSegs = 32;  // segments of the largest vocabulary (XGM_MAX_VOCAB / kSegTokens), rounded up
+// One workgroup per node: accepted tokens per segment, digest of the accepted row, number of
+// context-dependent tokens (one pass over the node's two id-space rows).
+__global__ __launch_bounds__(kRowThreads) void row_stats_kernel(DevVocab voc, const uint32_t* __restrict__ acc_id,
+                                                                const uint32_t* __restrict__ unc_id,
+                                                                uint32_t* __restrict__ seg_counts,
+                                                                unsigned long long* __restrict__ digest,
+                                                                uint32_t* __restrict__ unc_counts) {
   __shared__ unsigned long long part[kRowThreads / 64];
-  const uint32_t* row = rows + (size_t)blockIdx.x * W;
+  __shared__ uint32_t seg[kMaxSegs];
+  __shared__ uint32_t unc_total;
+  const size_t node = blockIdx.x;
+  if (threadIdx.x < kMaxSegs) seg[threadIdx.x] = 0u;
+  if (threadIdx.x == 0) unc_total = 0u;
+  __syncthreads();
+  const uint32_t* row = acc_id + node * voc.W;
+  const uint32_t* urow = unc_id + node * voc.W;
   unsigned long long h = 0ull;
-  for (int32_t w = threadIdx.x; w < W; w += kRowThreads)
-    h += mix64(((unsigned long long)(uint32_t)w << 32 | row[w]) + 0x9E3779B97F4A7C15ull);
+  uint32_t u = 0u;
+  for (int32_t s = 0; s < voc.n_seg; ++s) {
+    uint32_t cnt = 0u;
+    const int32_t w_end = min((s + 1) * kSegWords, voc.W);
+    for (int32_t w = s * kSegWords + (int32_t)threadIdx.x; w < w_end; w += kRowThreads) {
+      const uint32_t x = row[w];
+      cnt += __popc(x);
+      h += mix64(((unsigned long long)(uint32_t)w << 32 | x) + 0x9E3779B97F4A7C15ull);
+      u += __popc(urow[w]);
+    }
+    if (cnt) atomicAdd(&seg[s], cnt);
+  }
+  if (u) atomicAdd(&unc_total, u);
 #pragma unroll
   for (uint32_t d = 32; d > 0; d >>= 1) h += __shfl_down(h, d, 64);
   if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = h;
   __syncthreads();
+  if ((int32_t)threadIdx.x < voc.n_seg) seg_counts[node * voc.n_seg + threadIdx.x] = seg[threadIdx.x];
   if (threadIdx.x == 0) {
     unsigned long long t = 0ull;
     for (int k = 0; k < kRowThreads / 64; ++k) t += part[k];
-    digest[blockIdx.x] = t;
+    digest[node] = t;
+    unc_counts[node] = unc_total;
   }
 }
+
+// Bitset rows -> lists of token ids through cursors.  One workgroup per (segment, row); a thread takes
+// four words; a wave reserves room for all its tokens with one atomic.
+constexpr int kListThreads = kSegWords / 4;
+__global__ __launch_bounds__(kListThreads) void rows_to_lists_kernel(DevVocab voc, const uint32_t* __restrict__ rows,
+                                                                     const uint32_t* __restrict__ cursor_of, int32_t per_row,
+                                                                     uint32_t* __restrict__ cursor, uint32_t* __restrict__ out) {
+  const size_t r = blockIdx.y;
+  const uint32_t key = cursor_of[r];
+  if (key == kNoKey) return;
+  const int32_t s = blockIdx.x;
+  const int32_t w0 = s * kSegWords + (int32_t)threadIdx.x * 4;
+  uint32_t bits[4];
+  uint32_t n = 0u;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    bits[k] = w0 + k < voc.W ? rows[r * voc.W + w0 + k] : 0u;
+    n += __popc(bits[k]);
+  }
+  // exclusive prefix of n over the wave, and the wave's total
+  const uint32_t lane = threadIdx.x & 63u;
+  uint32_t incl = n;
+#pragma unroll
+  for (uint32_t d = 1; d < 64u; d <<= 1) {
+    const uint32_t v = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += v;
+  }
+  const uint32_t total = __shfl(incl, 63, 64);
+  if (total == 0u) return;
+  uint32_t base = 0u;
+  if (lane == 0) base = atomicAdd(&cursor[(size_t)key * per_row + (per_row > 1 ? s : 0)], total);
+  base = __shfl(base, 0, 64);
+  uint32_t pos = base + incl - n;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    uint32_t x = bits[k];
+    while (x) {
+      const uint32_t b = __ffs(x) - 1;
+      x &= x - 1;
+      out[pos++] = (uint32_t)(w0 + k) * 32u + b;
+    }
+  }
+}
+
+// the first 15 bytes, the length and the remaining bytes of token `id`
+struct TokenRef {
+  uint4 tk;
+  const uint8_t* ext;
+  int len;
+};
+__device__ __forceinline__ TokenRef load_token(const DevVocab& voc, int32_t id) {
+  TokenRef t;
+  t.tk = voc.tok_by_id[id];
+  t.len = (int)(t.tk.w >> 24);
+  t.ext = voc.bytes;
+  if (t.len >= 15) {
+    t.ext = voc.bytes + voc.off_by_id[id];
+    if (t.len == 255) t.len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
+  }
+  return t;
+}
+
+// Where a context-dependent token leaves its node's frame: one thread per entry of the base lists walks
+// the token once more from the node and notes the positions (tables staged as in the classify kernel).
+constexpr int kContextThreads = 768;
+__global__ __launch_bounds__(kContextThreads) void exit_positions_kernel(DevTables tab, DevVocab voc, int32_t n_nodes,
+                                                                         const uint32_t* __restrict__ node_off,
+                                                                         const uint32_t* __restrict__ base_ids, uint32_t total,
+                                                                         uint32_t* __restrict__ exits) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  stage_tables(tab, smem, kContextThreads);
+  __syncthreads();
+  auto body = [&](const auto& T) {
+    const uint32_t e = blockIdx.x * kContextThreads + threadIdx.x;
+    if (e >= total) return;
+    uint32_t lo = 0u, hi = (uint32_t)n_nodes;  // the last node whose list starts at or before e
+    while (hi - lo > 1u) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (node_off[mid] <= e) lo = mid; else hi = mid;
+    }
+    const uint32_t node = lo;
+    const TokenRef t = load_token(voc, (int32_t)base_ids[e]);
+    uint32_t x = 0u;
+    const int res = walk_token<true>(T, t.tk, t.ext, t.len, node, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node), 0, &x);
+    exits[e] = res == kOverflow ? 0x80000000u : x;
+  };
+  if (small_sections_staged(tab)) body(LdsTabT<true>(tab, smem));
+  else body(LdsTab(tab, smem));
+}
+
+// The level-1 and level-2 lists (section 3.2 per call site; see DevCache).  One thread per (base entry,
+// context i of the node's rule): the rest of the token after it has left the node's frame is walked from
+// context node i with nothing known below; if it leaves that frame too, from every context node of that
+// node's rule in turn.  The same kernel first counts the entries of every (key, segment) and then, with
+// the offsets made from the counts, writes them.
+template <bool WRITE, class Tab>
+__device__ __forceinline__ void context_lists_body(const Tab& T, const DevVocab& voc, int32_t n_nodes, uint64_t n_items,
+                                                   const ContextListArgs& a) {
+  const uint64_t item = (uint64_t)blockIdx.x * kContextThreads + threadIdx.x;
+  if (item >= n_items) return;
+  uint32_t lo = 0u, hi = (uint32_t)n_nodes;  // the last node whose items start at or before `item`
+  while (hi - lo > 1u) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (a.item_base[mid] <= item) lo = mid; else hi = mid;
+  }
+  const uint32_t node = lo;
+  const uint32_t local = (uint32_t)(item - a.item_base[node]);
+  const uint32_t n_list = a.node_off[node + 1] - a.node_off[node];
+  const uint32_t i = local / n_list, e = a.node_off[node] + local % n_list;
+  const uint32_t id = a.base_ids[e], ex0 = a.exits[e];
+  const TokenRef t = load_token(voc, (int32_t)id);
+  const uint32_t rule = T.header(node).y >> 16;
+  const uint32_t r1 = a.ctx_node[a.ctx_off[rule] + i];
+  const uint32_t key1_local = a.k1_base[node] + i;
+  const uint32_t slot_seg = id / (uint32_t)kSegTokens;
+  auto emit = [&](uint32_t key, uint32_t kind, uint32_t pos) {
+    const size_t slot = (size_t)key * voc.n_seg + slot_seg;
+    if (!WRITE) atomicAdd(&a.counts[slot], 1u);
+    else {
+      const uint32_t word = id | (pos << kEntryPosShift) | (kind << kEntryKindShift);
+      if (kind == kEntryAccepted) a.entries[atomicAdd(&a.front[slot], 1u)] = word;
+      else a.entries[atomicSub(&a.back[slot], 1u) - 1u] = word;
+    }
+  };
+  // can the suffix from position k on do anything at all at node r?  (consumed there, or r may end its
+  // rule in front of a byte that can follow the rule)
+  auto plausible = [&](uint32_t r, uint32_t k) {
+    const uint32_t c = token_byte(t.tk, t.ext, (int)k);
+    if (T.can_start(r, c)) return true;
+    const uint2 h = T.header(r);
+    return (h.y & 1u) && T.can_follow(h, c);
+  };
+  const uint32_t key1 = (uint32_t)n_nodes + key1_local;
+  if (ex0 & 0x80000000u) { emit(key1, kEntryWalkTop, 0u); return; }
+  bool accepted = false, over = false;
+  uint32_t ex1 = 0u, from1 = 0u, n_res = 0u;
+  for (uint32_t m = ex0; m != 0u && !accepted; m &= m - 1u) {
+    const uint32_t k = __ffs(m) - 1u;
+    if (!plausible(r1, k)) continue;
+    uint32_t x = 0u;
+    const int res = walk_token<true>(T, t.tk, t.ext, t.len, r1, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r1), (int)k, &x);
+    if (res == kAccept) accepted = true;
+    else if (res == kOverflow) over = true;
+    else if (res == kUncertain) { ex1 |= x; if (n_res++ == 0u) from1 = k; }
+  }
+  if (accepted) { emit(key1, kEntryAccepted, 0u); return; }
+  if (over) { emit(key1, kEntryWalkTop, 0u); return; }
+  if (ex1 == 0u) return;  // rejected in this context
+  const bool single0 = (ex0 & (ex0 - 1u)) == 0u;
+  if (a.k2_base == nullptr || (ex1 & 0x80000000u)) {
+    if (single0) emit(key1, kEntryWalkBelow1, from1); else emit(key1, kEntryWalkTop, 0u);
+    return;
+  }
+  const uint32_t rule1 = T.header(r1).y >> 16;
+  const uint32_t c0 = a.ctx_off[rule1], m2 = a.ctx_off[rule1 + 1] - c0;
+  const uint32_t key2 = (uint32_t)n_nodes + a.n_k1 + a.k2_base[key1_local];
+  const bool single1 = single0 && n_res == 1u && (ex1 & (ex1 - 1u)) == 0u;
+  for (uint32_t j = 0; j < m2; ++j) {
+    const uint32_t r2 = a.ctx_node[c0 + j];
+    bool acc2 = false, walk2 = false;
+    for (uint32_t m = ex1; m != 0u && !acc2; m &= m - 1u) {
+      const uint32_t k = __ffs(m) - 1u;
+      if (!plausible(r2, k)) continue;
+      const int res = walk_token<true>(T, t.tk, t.ext, t.len, r2, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r2), (int)k);
+      if (res == kAccept) acc2 = true;
+      else if (res == kOverflow || res == kUncertain) walk2 = true;
+    }
+    if (acc2) emit(key2 + j, kEntryAccepted, 0u);
+    else if (walk2) {
+      if (single1) emit(key2 + j, kEntryWalkBelow2, __ffs(ex1) - 1u); else emit(key2 + j, kEntryWalkTop, 0u);
+    }
+  }
+}
+template <bool WRITE>
+__global__ __launch_bounds__(kContextThreads) void context_lists_kernel(DevTables tab, DevVocab voc, int32_t n_nodes,
+                                                                        uint64_t n_items, ContextListArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  stage_tables(tab, smem, kContextThreads);
+  __syncthreads();
+  if (small_sections_staged(tab)) context_lists_body<WRITE>(LdsTabT<true>(tab, smem), voc, n_nodes, n_items, a);
+  else context_lists_body<WRITE>(LdsTab(tab, smem), voc, n_nodes, n_items, a);
+}
+
 __global__ __launch_bounds__(kRowThreads) void rows_equal_kernel(const uint32_t* __restrict__ rows, int32_t W,
                                                                  const int32_t* __restrict__ rep,
                                                                  uint32_t* __restrict__ equal) {
@@ -550,15 +606,6 @@ struct LogitsRange {
       }
     }
   }
-  // one element by itself
-  __device__ __forceinline__ void reject(int32_t id) const {
-    if constexpr (APPLY != 0) {
-      if (id < V_logits) {
-        if (APPLY == 2) reinterpret_cast<uint16_t*>(row)[id] = (uint16_t)neg_inf;
-        else reinterpret_cast<uint32_t*>(row)[id] = neg_inf;
-      }
-    }
-  }
 };
 
 // ---------------------------------------------------------------- kernel (b)
@@ -573,276 +620,80 @@ __global__ __launch_bounds__(kUploadThreads) void upload_kernel(const uint4* __r
   if (i < n16) dst[i] = src[i];
 }
 
-constexpr int kFillThreads = 1024;
-constexpr int kFillQueue = 4096;                // survivors walked per round
+constexpr int kFillThreads = 512;
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
-constexpr uint32_t kQueueRejected = 1u << 23;   // in a queue entry: walked and found disallowed (see fill_lists)
+constexpr int kFillMaxLists = 64 * 3;           // XGM_MAX_STACKS stacks, three lists each
+constexpr int kFillListsAtOnce = 6;             // lists whose first entries are fetched together
 
-// accumulates a 256-bit set into 8 LDS words
-struct LdsSetAcc {
-  uint32_t* words;
-  __device__ __forceinline__ void add(uint32_t w, uint32_t bits) { if (bits) atomicOr(words + w, bits); }
-};
-
-// One workgroup of 16 waves serves one request and a contiguous range of its
-// chunks of 4096 token ids, as planned on the host or by the plan kernel
-// (FillBlock).  Once per
-// workgroup the request's automaton tables and live stacks are copied into
-// LDS; from then on a step of a token walk costs LDS lookups only.  The
-// workgroup owns its mask words in LDS:
-//   1. every word = OR of the accepted bitsets of the tops of all stacks
-//      (Algorithm 1: the result is the union over the parallel stacks);
-//   2. per stack, the context-dependent lists of its chunks are read once,
-//      coalesced.  Most entries name the suffix of their token that is left
-//      when the token leaves the top frame, and carry its first two bytes.
-//      Whether the rest of the stack can consume those two bytes is looked up
-//      in a 256 x 256-bit table that the workgroup first computes for the
-//      stack (one lane per first byte: an enumerating walk of that byte
-//      collects the bytes that can follow it) or copies, if it was computed
-//      when the state was entered; the per-context word of the entry settles
-//      it without any of this if the node below the top frame is one of the
-//      top rule's few contexts; a suffix of one or two bytes
-//      is thereby decided outright, a longer one is dropped or queued.
-//      Entries that need a walk from the top are tested on their first byte
-//      against a 256-bit set the host packed with the stack.  All these tests
-//      are exact and need only the list entry; survivors are compacted into
-//      an LDS queue (one LDS atomic per wave);
-//   3. the queue is walked (one lane per survivor); allowed tokens are ORed
-//      into the words with LDS atomics.  Long lists take several rounds of 2;
-//      the walk waits until the queue might not hold another round's
-//      survivors, which as a rule means: one walk, after the last round;
-//   4. the words are stored once, coalesced (the stop tokens were added in 1).
+// One workgroup of 8 waves serves one request and one segment of 32768 token
+// ids = 1024 mask words, which it owns in LDS:
+//   1. every word = OR of the accepted bitsets of the tops of all stacks that
+//      keep one (Algorithm 1: the result is the union over the parallel
+//      stacks); the stop tokens if the text may end;
+//   2. the stacks' token lists for this segment (up to three per stack: the
+//      top node's own accepted tokens if it keeps a list instead of a bitset,
+//      the tokens accepted given the node below the top frame, those accepted
+//      given the two nodes below) are streamed once, coalesced; an accepted
+//      entry sets its bit with an LDS atomic, a walk entry is only counted;
+//   3. lists that have walk entries (they sit at the list's end) get them
+//      decided against the live stack: only then are the request's automaton
+//      tables and frames copied into LDS.  Most launches walk nothing;
+//   4. the words are stored once, coalesced, and - in the fused instantiation -
+//      the logits of the segment are masked straight from them.
 // No global atomics, no second pass over the mask.
-// When the kernel also masks the logits, the last walks of a workgroup - a
-// few tokens in one wave, as a rule, and what the whole launch ends up waiting
-// for - run beside that work instead of in front of it: queued tokens count as
-// allowed for the moment, the waves without a walk write -inf for everything
-// else in the workgroup's range, and the tokens whose walk says no get theirs
-// after the walks (one element each).
 // COUNT = true additionally sums the automaton steps of all walks into
 // *step_counter (instrumentation for the benchmark; never used on the hot path).
 struct FillShared {
-  uint32_t words[kFillMaxChunks * kChunkWords];
-  uint32_t queue[kFillQueue];     // late exit position << 24 | kQueueRejected | (chunk - c0) << 16 | kind << 12 | local id
+  uint32_t words[kSegWords];
+  uint2 list[kFillMaxLists];        // begin, end of every list of this segment
+  uint32_t n_walk[kFillMaxLists];   // walk entries found in each
   uint16_t live[kFillFramesLds];
-  uint32_t hdr[kStackHdrWords];   // the current stack's header: top, depth, frame offset, and 2 x 256 bits: the
-                                  // bytes consumable from the stack / from the stack without its top frame
-  uint32_t off[kFillMaxChunks + 1];  // list offsets of the current stack's top for chunks c0 .. c1
-  uint32_t pair[256 * 8];         // per first byte: the bytes that can follow it, from the stack without its top frame
-  uint32_t queue_n;
+  uint32_t any_walk;
 };
 
-// The two-byte table of a stack without its top frame, into LDS (all threads of
-// the workgroup call this; it ends with a barrier): one lane per first byte
-// that the stack can consume at all (`first_ok`, 256 bits) runs an enumerating
-// walk of that byte from `below` (the node under the top frame; `depth` counts
-// the top frame) and collects the bytes that can follow it.  A walk over the
-// limits leaves its row all ones: the decision then falls to the token walks.
-template <int kThreads, class Tab, class Live>
-__device__ __forceinline__ void build_pair_table(const Tab& T, uint32_t* pair, const uint32_t* first_ok, uint32_t below,
-                                                 const Live& live, uint32_t depth, const uint32_t* node_first,
-                                                 const DevVocab& voc) {
-  const uint32_t tid = threadIdx.x;
-  for (uint32_t k = tid; k < kPairWords; k += kThreads) pair[k] = 0u;
-  __syncthreads();
-  if (tid < 256u && ((first_ok[tid >> 5] >> (tid & 31u)) & 1u)) {
-    LdsSetAcc acc{pair + tid * 8u};
-    const CollectNextBytes<Tab, LdsSetAcc> collect{&T, node_first, &acc};
-    const int res = walk_token<false>(T, make_uint4(tid, 0u, 0u, 1u << 24), voc.bytes, 1, below, live, depth - 1,
-                                      (uint32_t*)nullptr, (const uint32_t*)nullptr, 0, (uint32_t*)nullptr, collect);
-    if (res == kOverflow)
-      for (uint32_t w = 0; w < 8u; ++w) pair[tid * 8u + w] = 0xFFFFFFFFu;
-  }
-  __syncthreads();
-}
-
-// the header of one stack and its list offsets for chunks c0 .. c1 -> LDS (a barrier must follow)
-__device__ __forceinline__ void stage_stack_header(FillShared& sm, const XGM_GLOBAL uint32_t* sh, int32_t c0, int32_t c1) {
-  const uint32_t tid = threadIdx.x;
-  if (tid < kStackHdrWords) sm.hdr[tid] = sh[tid];
-  else if (tid - kStackHdrWords <= (uint32_t)(c1 - c0)) sm.off[tid - kStackHdrWords] = sh[kStackHdrWords + c0 + tid - kStackHdrWords];
-}
-
-// Returns true if it has also written the logits of the workgroup's range (`logits`; only with APPLY != 0).
-template <bool COUNT, int APPLY, class Tab>
-__device__ __forceinline__ bool fill_lists(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b,
-                                           const int32_t c0, const int32_t c1, const uint32_t frame0,
-                                           const bool frames_in_lds,
-                                           const XGM_GLOBAL uint32_t* __restrict__ stack_hdrs,
+// Decides the walk entries of the workgroup's lists (all threads call this).
+template <bool COUNT, bool KEEP_UNDECIDED, class Tab>
+__device__ __forceinline__ void fill_walks(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b, const int32_t id0,
+                                           const uint32_t n_lists, const uint32_t frame0, const bool frames_in_lds,
+                                           const XGM_GLOBAL uint32_t* __restrict__ stack_hdrs, const uint32_t hdr_stride,
                                            const XGM_GLOBAL uint16_t* __restrict__ frames, const DevVocab& voc,
-                                           OverflowLog* log, uint32_t seq, unsigned long long& my_steps,
-                                           const uint32_t pair_min_entries,
-                                           const XGM_GLOBAL uint32_t* __restrict__ pair_tables,
-                                           const LogitsRange<APPLY>& logits) {
-  constexpr bool KEEP_UNDECIDED = APPLY != 0;
-  bool logits_done = false;
-  const uint32_t tid = threadIdx.x, lane = threadIdx.x & 63u;
-  const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
-  const XGM_GLOBAL uint32_t* unc_list = (const XGM_GLOBAL uint32_t*)rd.unc_list;
-  const XGM_GLOBAL uint32_t* unc_ctx = (const XGM_GLOBAL uint32_t*)rd.unc_ctx;
-  const uint32_t* node_first = reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(rd.tab.image) + rd.tab.off_first);
-  const uint32_t* first_ok = sm.hdr + kStackHdrFirst;
-  for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-    // the stack's header and its list offsets go to LDS with one coalesced read (the first stack's are there already)
-    if (s > 0) {
-      __syncthreads();  // the previous stack's header is no longer in use
-      stage_stack_header(sm, stack_hdrs + (size_t)(rd.stack_begin + s) * hdr_stride, c0, c1);
-      __syncthreads();
-    }
-    if (sm.off[c1 - c0] == sm.off[0]) continue;  // nothing listed here (uniform)
-    const uint32_t top = sm.hdr[kStackHdrTop] & 0xFFFFu, depth = sm.hdr[kStackHdrDepth];
-    const uint32_t ctx = sm.hdr[kStackHdrCtx];  // which context of the top's rule the frame below is, or kCtxNone
+                                           OverflowLog* log, uint32_t seq, unsigned long long& my_steps) {
+  const XGM_GLOBAL uint32_t* entries = (const XGM_GLOBAL uint32_t*)rd.entries;
+  for (uint32_t l = 0; l < n_lists; ++l) {
+    const uint32_t nw = sm.n_walk[l];
+    if (nw == 0u) continue;
+    const XGM_GLOBAL uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + l / kStackLists) * hdr_stride;
+    const uint32_t top = sh[kStackHdrTop] & 0xFFFFu, depth = sh[kStackHdrDepth], f_off = sh[kStackHdrFrames];
     LiveView live;
-    live.lds = (const XGM_LDS uint16_t*)sm.live + (sm.hdr[kStackHdrFrames] - frame0);
-    live.glob = frames + sm.hdr[kStackHdrFrames];
+    live.lds = (const XGM_LDS uint16_t*)sm.live + (f_off - frame0);
+    live.glob = frames + f_off;
     live.lo = frames_in_lds ? 0u : 0xFFFFFFFFu;
-    const uint32_t below = depth >= 2 ? live[depth - 2] : 0u;
-    // the two-byte table of the stack below the top frame
-    const bool have_table = pair_tables != nullptr && ((rd.pair_mask >> s) & 1u);  // computed ahead of this launch
-    const bool use_pair = depth >= 2 && (have_table || sm.off[c1 - c0] - sm.off[0] >= pair_min_entries);
-    if (use_pair) {
-      if (have_table) {
-        if (s > 0) {  // the first stack's table came in with the workgroup's first fetches
-          const XGM_GLOBAL uint32_t* table = pair_tables + ((size_t)b * kBatchMaxStacks + s) * kPairWords;
-          for (uint32_t k = tid; k < kPairWords; k += kFillThreads) sm.pair[k] = table[k];
-          __syncthreads();
-        }
-      } else {
-        build_pair_table<kFillThreads>(T, sm.pair, sm.hdr + kStackHdrBelow, below, live, depth, node_first, voc);
+    const uint32_t end = sm.list[l].y;
+    for (uint32_t j = end - nw + threadIdx.x; j < end; j += kFillThreads) {
+      const uint32_t e = entries[j];
+      const uint32_t id = e & kEntryIdMask, kind = e >> kEntryKindShift, pos = (e >> kEntryPosShift) & 0xFFu;
+      const uint32_t rel = id - (uint32_t)id0;
+      if ((sm.words[rel >> 5] >> (rel & 31u)) & 1u) continue;  // already allowed
+      const uint32_t drop = kind == kEntryWalkTop ? 0u : kind - 1u;  // frames above the one the walk starts in
+      int res = kReject;
+      uint32_t n_steps = 0;
+      if (depth > drop) {
+        const TokenRef t = load_token(voc, (int32_t)id);
+        const uint32_t start = drop == 0u ? top : live[depth - 1u - drop];
+        res = walk_token<false>(T, t.tk, t.ext, t.len, start, live, depth - drop, COUNT ? &n_steps : nullptr,
+                                (const uint32_t*)nullptr, drop == 0u ? 0 : (int)pos);
       }
-    }
-    // The last stack's queued tokens count as allowed until they have been walked (see above).
-    const bool last_stack = APPLY != 0 && s + 1 == rd.n_stacks;
-    // Rounds of chunks whose lists together fit the queue even if every entry survived (one chunk always
-    // fits).  Few do survive, so the survivors of a round are only walked when the queue might not hold
-    // the next round's as well: as a rule a workgroup walks once, after its last round.
-    for (int32_t ca = c0; ca < c1;) {
-      int32_t cb = ca + 1;
-      while (cb < c1 && sm.off[cb + 1 - c0] - sm.off[ca - c0] <= (uint32_t)kFillQueue) ++cb;
-      // the last walks of the workgroup: the logits are written beside them
-      const bool beside = last_stack && cb == c1;
-      // 2. filter + compact: the lists of consecutive chunks are contiguous, so one flat pass reads them all
-      const uint32_t j_begin = sm.off[ca - c0], j_end = sm.off[cb - c0];
-      for (uint32_t j = j_begin + (tid & ~63u); j < j_end; j += kFillThreads) {
-        const uint32_t jj = j + lane;
-        bool keep = false;
-        uint32_t lid = 0, meta = 0, cl = 0, late_exit = 0;
-        if (jj < j_end) {
-          const uint32_t e = unc_list[jj];
-          const uint32_t in_ctx = ctx != kCtxNone ? (unc_ctx[jj] >> (2u * ctx)) & 3u : kCtxWalk;
-          // the entry's chunk: the last one whose list starts at or before jj
-          uint32_t lo = (uint32_t)(ca - c0), hi = (uint32_t)(cb - c0);
-          while (hi - lo > 1u) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (sm.off[mid] <= jj) lo = mid; else hi = mid;
-          }
-          cl = lo;
-          uint32_t* wchunk = sm.words + cl * kChunkWords;
-          lid = e & 0xFFFu;
-          meta = (e >> 12) & 15u;
-          const uint32_t b1 = (e >> 16) & 0xFFu, b2 = e >> 24;
-          const bool seen = (wchunk[lid >> 5] >> (lid & 31)) & 1u;  // already allowed through another stack
-          if (meta == kEntryFullWalk) {
-            // b2 != 0: a single exit at position b2 after all; the context class may settle it
-            const bool ok0 = (first_ok[b1 >> 5] >> (b1 & 31)) & 1u;
-            const bool has_exit = b2 != 0u && depth >= 2u;
-            if (has_exit && in_ctx != kCtxWalk) {
-              if (!seen && ok0 && in_ctx == kCtxAccept) atomicOr(&wchunk[lid >> 5], 1u << (lid & 31));
-            } else {
-              keep = !seen && ok0;
-              late_exit = has_exit ? b2 : 0u;
-            }
-          } else {
-            const bool ok1 = (first_ok[8 + (b1 >> 5)] >> (b1 & 31)) & 1u;
-            const bool ok2 = use_pair ? ((sm.pair[b1 * 8u + (b2 >> 5)] >> (b2 & 31)) & 1u) : ok1;
-            const bool decided = in_ctx != kCtxWalk || meta == kEntrySuffix1 || (use_pair && meta == kEntrySuffix2);
-            if (decided) {
-              const bool allowed = in_ctx != kCtxWalk ? in_ctx == kCtxAccept : (meta == kEntrySuffix1 ? ok1 : ok2);
-              if (!seen && allowed) atomicOr(&wchunk[lid >> 5], 1u << (lid & 31));
-            } else {
-              keep = !seen && ok2;
-            }
-          }
-        }
-        const unsigned long long m = __ballot(keep);
-        if (m) {
-          uint32_t base = 0;
-          if (lane == 0) base = atomicAdd(&sm.queue_n, (uint32_t)__popcll(m));
-          base = __shfl(base, 0, 64);
-          if (keep) {
-            sm.queue[base + __popcll(m & ((1ull << lane) - 1ull))] = (late_exit << 24) | (cl << 16) | (meta << 12) | lid;
-            if (last_stack) atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));  // allowed for the moment
-          }
-        }
-      }
-      __syncthreads();
-      // 3. walk the survivors, unless the queue has room for all that the next round can add
-      const uint32_t nq = sm.queue_n;
-      if (cb < c1) {
-        int32_t cn = cb + 1;
-        while (cn < c1 && sm.off[cn + 1 - c0] - sm.off[cb - c0] <= (uint32_t)kFillQueue) ++cn;
-        if (nq + (sm.off[cn - c0] - sm.off[cb - c0]) <= (uint32_t)kFillQueue) {
-          ca = cb;
-          continue;
-        }
-      }
-      const uint32_t first_free = (min(nq, (uint32_t)kFillThreads) + 63u) & ~63u;  // the waves from here on have no walk
-      if (beside && tid >= first_free) logits.groups(tid - first_free, kFillThreads - first_free);
-      for (uint32_t q = tid; q < nq; q += kFillThreads) {
-        const uint32_t e = sm.queue[q];
-        const uint32_t lid = e & 0xFFFu, meta = (e >> 12) & 15u, cl = (e >> 16) & 0x7Fu, late_exit = e >> 24;
-        const int32_t id = (c0 + (int32_t)cl) * kChunkTokens + (int32_t)lid;
-        const uint4 tk = voc.tok_by_id[id];
-        int len = (int)(tk.w >> 24);
-        const uint8_t* ext = voc.bytes;
-        if (len >= 15) {
-          ext = voc.bytes + voc.off_by_id[id];
-          if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
-        }
-        uint32_t n_steps = 0;
-        // a token with a single exit continues right there, in the frame below the top
-        const bool full = meta == kEntryFullWalk && late_exit == 0u;
-        const int i0 = full ? 0 : late_exit ? (int)late_exit : (meta == kEntrySuffix2 ? len - 2 : (int)meta);
-        const int res = walk_token<false>(T, tk, ext, len, full ? top : below, live, full ? depth : depth - 1,
-                                          COUNT ? &n_steps : nullptr, (const uint32_t*)nullptr, i0);
-        if (COUNT) my_steps += n_steps;
-        if (last_stack) {
-          if (res == kReject) {
-            atomicAnd(&sm.words[cl * kChunkWords + (lid >> 5)], ~(1u << (lid & 31)));
-            if (beside) sm.queue[q] = e | kQueueRejected;
-          } else if (res == kOverflow) {
-            record_overflow(log, seq, (uint32_t)b, (uint32_t)id);  // stays allowed until the host has decided it
-          }
-        } else if (res == kAccept) {
-          atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
-        } else if (res == kOverflow) {
-          record_overflow(log, seq, (uint32_t)b, (uint32_t)id);
-          if (KEEP_UNDECIDED) atomicOr(&sm.words[cl * kChunkWords + (lid >> 5)], 1u << (lid & 31));
-        }
-      }
-      if (beside) {
-        if (first_free >= (uint32_t)kFillThreads) logits.groups(tid, kFillThreads);  // every wave had walks
-        __syncthreads();  // the group stores above come first
-        for (uint32_t q = tid; q < nq; q += kFillThreads) {
-          const uint32_t e = sm.queue[q];
-          if (e & kQueueRejected) logits.reject((c0 + (int32_t)((e >> 16) & 0x7Fu)) * kChunkTokens + (int32_t)(e & 0xFFFu));
-        }
-        logits_done = true;
-      }
-      __syncthreads();
-      if (tid == 0) sm.queue_n = 0u;
-      __syncthreads();
-      ca = cb;
+      if (COUNT) my_steps += n_steps;
+      if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, id, rd.epoch);  // decided on the host
+      if (res == kAccept || (KEEP_UNDECIDED && res == kOverflow)) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31u));
     }
   }
-  return logits_done;
 }
 
-// Two workgroups of 16 waves per compute unit need 8 waves per SIMD: the second
-// launch bound keeps the kernel within the 96 scalar and 64 vector registers
-// per wave that this takes.
+// Four workgroups of 8 waves per compute unit need 8 waves per SIMD: the second
+// launch bound keeps the kernel within the registers that this takes.
 // APPLY = 0: the mask only.  APPLY = 2 / 4 (bytes per logit): the workgroup
-// also writes -inf into the logits of its (row, chunk range) straight from its
+// also writes -inf into the logits of its (row, segment) straight from its
 // LDS words (section 2.1), which saves a launch and the re-read of the mask.
 // A token whose walk exceeded the limits is then left allowed (bit set, logit
 // untouched) until the host has decided it.
@@ -851,15 +702,12 @@ struct FusedApply {
   int64_t row_stride;     // elements
   int32_t V_logits;
   uint32_t neg_inf;
-  uint32_t pair_min_entries;  // (rides along) lists shorter than this are filtered on one byte only
-  const uint32_t* pair_tables;  // (rides along) DevBatch::pair, or null
 };
 
 template <bool COUNT, int APPLY>
 __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __restrict__ rows,
                                                             const uint32_t* __restrict__ stack_hdrs_,
-                                                            const uint16_t* __restrict__ frames_,
-                                                            const FillBlock* __restrict__ plan, DevVocab voc,
+                                                            const uint16_t* __restrict__ frames_, DevVocab voc,
                                                             uint32_t* __restrict__ out, OverflowLog* log, uint32_t seq,
                                                             unsigned long long* step_counter, FusedApply fa) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -868,76 +716,106 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   const XGM_GLOBAL uint16_t* frames = (const XGM_GLOBAL uint16_t*)frames_;
   unsigned long long my_steps = 0;
   const uint32_t tid = threadIdx.x;
-  const FillBlock blk = plan[blockIdx.x];  // placed by the planner (plan_slot)
-  if (blk.row == kNoRow) return;  // padding of the plan
-  const int32_t b = (int32_t)blk.row;
-  const int32_t c0 = (int32_t)(blk.c0c1 & 0x7FFFu), c1 = (int32_t)(blk.c0c1 >> 16);  // this workgroup's chunks
-  const int32_t w_begin = c0 * kChunkWords;
-  const int32_t n_words = min(c1 * kChunkWords, voc.W) - w_begin;
+  const int32_t b = (int32_t)blockIdx.y, seg = (int32_t)blockIdx.x;
+  const int32_t w_begin = seg * kSegWords;
+  const int32_t n_words = min(kSegWords, voc.W - w_begin);
+  const int32_t id0 = w_begin * 32;
   const RowDesc rd = rows[b];
-  const bool has_cache = rd.n_stacks > 0 && !(blk.c0c1 & kFillBlockNoEntries);  // are there lists to resolve?
-  const uint32_t hdr_stride = kStackHdrWords + voc.n_chunk + 1;
-  // everything the row descriptor points to is fetched in one go: tables, live frames, the first stack's
-  // header with its list offsets, and (below) the accepted words
-  const uint32_t frame0 = rd.frame_begin, n_frames = rd.n_frames;
-  const bool frames_in_lds = n_frames <= kFillFramesLds;
+  const uint32_t hdr_stride = kStackHdrWords + kStackLists * ((uint32_t)voc.n_seg + 1u);
+  const uint32_t n_lists = rd.n_stacks * kStackLists;
   // may the request end here?  then its stop tokens are allowed (the first kFillThreads of them are fetched now)
   const bool may_end = rd.flags & 1u;
   const int32_t my_stop = may_end && (int32_t)tid < voc.n_stop ? voc.stop_ids[tid] : -1;
-  if (has_cache) {
+  // the bounds of this segment's lists
+  for (uint32_t l = tid; l < n_lists; l += kFillThreads) {
+    const XGM_GLOBAL uint32_t* off = stack_hdrs + (size_t)(rd.stack_begin + l / kStackLists) * hdr_stride + kStackHdrWords +
+                                     (l % kStackLists) * ((uint32_t)voc.n_seg + 1u) + (uint32_t)seg;
+    sm.list[l] = make_uint2(off[0], off[1]);
+    sm.n_walk[l] = 0u;
+  }
+  if (tid == 0) sm.any_walk = 0u;
+  // 1. accepted words
+  const XGM_GLOBAL uint32_t* acc = (const XGM_GLOBAL uint32_t*)rd.acc;
+  for (int32_t w = tid; w < kSegWords; w += kFillThreads) {
+    uint32_t x = 0u;
+    if (w < n_words)
+      for (uint32_t s = 0; s < rd.n_stacks; ++s) {
+        const uint32_t acc_row = stack_hdrs[(size_t)(rd.stack_begin + s) * hdr_stride + kStackHdrTop] >> 16;
+        if (acc_row != kNoAccRow) x |= acc[(size_t)acc_row * voc.W + w_begin + w];
+      }
+    sm.words[w] = x;
+  }
+  __syncthreads();
+  if (may_end)
+    for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
+      const int32_t rel = (k == (int32_t)tid ? my_stop : voc.stop_ids[k]) - id0;
+      if (rel >= 0 && rel < n_words * 32) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31));
+    }
+  // 2. the lists: the first kFillThreads entries of several lists are fetched together (most lists are
+  // shorter than that), then what is left of them
+  const XGM_GLOBAL uint32_t* entries = (const XGM_GLOBAL uint32_t*)rd.entries;
+  auto take = [&](uint32_t e, uint32_t l) {
+    if ((e >> kEntryKindShift) == kEntryAccepted) {
+      const uint32_t rel = (e & kEntryIdMask) - (uint32_t)id0;
+      atomicOr(&sm.words[rel >> 5], 1u << (rel & 31u));
+    } else {
+      atomicAdd(&sm.n_walk[l], 1u);
+    }
+  };
+  for (uint32_t l0 = 0; l0 < n_lists; l0 += kFillListsAtOnce) {
+    uint32_t first[kFillListsAtOnce];
+    bool have[kFillListsAtOnce];
+#pragma unroll
+    for (uint32_t q = 0; q < (uint32_t)kFillListsAtOnce; ++q) {
+      have[q] = false;
+      if (l0 + q < n_lists) {
+        const uint2 r = sm.list[l0 + q];
+        have[q] = r.x + tid < r.y;
+        if (have[q]) first[q] = entries[r.x + tid];
+      }
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < (uint32_t)kFillListsAtOnce; ++q)
+      if (have[q]) take(first[q], l0 + q);
+    for (uint32_t q = 0; q < (uint32_t)kFillListsAtOnce && l0 + q < n_lists; ++q) {
+      const uint2 r = sm.list[l0 + q];
+      for (uint32_t j = r.x + kFillThreads + tid; j < r.y; j += kFillThreads) take(entries[j], l0 + q);
+    }
+  }
+  __syncthreads();
+  // 3. walk entries, if any
+  if (tid < n_lists && sm.n_walk[tid] != 0u) sm.any_walk = 1u;
+  for (uint32_t l = tid + kFillThreads; l < n_lists; l += kFillThreads)
+    if (sm.n_walk[l] != 0u) sm.any_walk = 1u;
+  __syncthreads();
+  if (sm.any_walk) {
+    const uint32_t frame0 = rd.frame_begin, n_frames = rd.n_frames;
+    const bool frames_in_lds = n_frames <= kFillFramesLds;
     stage_tables(rd.tab, smem, kFillThreads);
     if (frames_in_lds)
       for (uint32_t k = tid; k < n_frames; k += kFillThreads) sm.live[k] = frames[frame0 + k];
-    stage_stack_header(sm, stack_hdrs + (size_t)rd.stack_begin * hdr_stride, c0, c1);
-    if (fa.pair_tables != nullptr && (rd.pair_mask & 1u)) {  // the first stack's two-byte table, computed ahead
-      const XGM_GLOBAL uint32_t* table = (const XGM_GLOBAL uint32_t*)fa.pair_tables + (size_t)b * kBatchMaxStacks * kPairWords;
-      for (uint32_t k = tid; k < kPairWords; k += kFillThreads) sm.pair[k] = table[k];
-    }
+    __syncthreads();
+    if (small_sections_staged(rd.tab))
+      fill_walks<COUNT, APPLY != 0>(LdsTabT<true>(rd.tab, smem), sm, rd, b, id0, n_lists, frame0, frames_in_lds, stack_hdrs,
+                                    hdr_stride, frames, voc, log, seq, my_steps);
+    else
+      fill_walks<COUNT, APPLY != 0>(LdsTab(rd.tab, smem), sm, rd, b, id0, n_lists, frame0, frames_in_lds, stack_hdrs,
+                                    hdr_stride, frames, voc, log, seq, my_steps);
+    __syncthreads();
   }
-  // 1. accepted words
-  const XGM_GLOBAL uint32_t* acc = (const XGM_GLOBAL uint32_t*)rd.acc;
-  for (int32_t w = tid; w < n_words; w += kFillThreads) {
-    uint32_t x = 0u;
-    for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-      const uint32_t acc_row = stack_hdrs[(size_t)(rd.stack_begin + s) * hdr_stride + kStackHdrTop] >> 16;
-      x |= acc[(size_t)acc_row * voc.W + w_begin + w];
-    }
-    sm.words[w] = x;
-  }
-  if (tid == 0) sm.queue_n = 0u;
-  __syncthreads();
-  if (may_end) {
-    for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
-      const int32_t rel = (k == (int32_t)tid ? my_stop : voc.stop_ids[k]) - w_begin * 32;
-      if (rel >= 0 && rel < n_words * 32) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31));
-    }
-    __syncthreads();  // a stop token with bytes may also be listed: the lists must find its bit set
-  }
-  // this workgroup's logits: its chunks; the last workgroup of a row also takes the columns beyond the vocabulary
-  LogitsRange<APPLY> logits;
+  // 4. the words, and the logits of the segment; the last segment also takes the columns beyond the vocabulary
+  for (int32_t w = tid; w < n_words; w += kFillThreads) out[(size_t)b * voc.W + w_begin + w] = sm.words[w];
   if (APPLY != 0) {
+    LogitsRange<APPLY> logits;
     logits.row = fa.logits + (size_t)b * fa.row_stride * APPLY;
     logits.words = sm.words;
-    logits.e_begin = w_begin * 32;
-    logits.e_end = c1 == voc.n_chunk ? fa.V_logits : min(c1 * kChunkTokens, fa.V_logits);
+    logits.e_begin = id0;
+    logits.e_end = seg + 1 == voc.n_seg ? fa.V_logits : min(id0 + kSegTokens, fa.V_logits);
     logits.V = voc.V;
     logits.V_logits = fa.V_logits;
     logits.neg_inf = fa.neg_inf;
+    logits.groups(tid, kFillThreads);
   }
-  bool logits_done = false;
-  if (has_cache) {
-    if (small_sections_staged(rd.tab))
-      logits_done = fill_lists<COUNT, APPLY>(LdsTabT<true>(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds,
-                                             stack_hdrs, frames, voc, log, seq, my_steps, fa.pair_min_entries,
-                                             (const XGM_GLOBAL uint32_t*)fa.pair_tables, logits);
-    else
-      logits_done = fill_lists<COUNT, APPLY>(LdsTab(rd.tab, smem), sm, rd, b, c0, c1, frame0, frames_in_lds, stack_hdrs,
-                                             frames, voc, log, seq, my_steps, fa.pair_min_entries,
-                                             (const XGM_GLOBAL uint32_t*)fa.pair_tables, logits);
-  }
-  __syncthreads();
-  for (int32_t w = tid; w < n_words; w += kFillThreads) out[(size_t)b * voc.W + w_begin + w] = sm.words[w];
-  if (!logits_done) logits.groups(tid, kFillThreads);
   if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
 }
 
@@ -954,7 +832,17 @@ struct LdsStackSink {
 };
 
 constexpr int kAcceptThreads = 256;
-constexpr int kErrTokenRejected = -6, kErrTerminated = -7, kErrTooManyStacks = -8, kErrTooLarge = -9, kErrBadArg = -1;
+constexpr int kErrTokenRejected = -6, kErrTerminated = -7, kErrTooManyStacks = -8, kErrTooLarge = -9, kErrBadArg = -1, kErrInternal = -11;
+
+// index of `node` among the (sorted) context nodes [lo, hi) of a rule, or kNoKey
+__device__ __forceinline__ uint32_t context_index(const uint16_t* __restrict__ ctx_node, uint32_t lo, uint32_t hi, uint32_t node) {
+  const uint32_t first = lo, end = hi;
+  while (lo < hi) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (ctx_node[mid] < node) lo = mid + 1; else hi = mid;
+  }
+  return lo < end && ctx_node[lo] == node ? lo - first : kNoKey;
+}
 
 // is stack a (depth da) ordered before stack b?  element by element, the shorter first (the host's order of stacks)
 __device__ __forceinline__ int compare_stacks(const uint16_t* a, uint32_t da, const uint16_t* b, uint32_t db) {
@@ -969,17 +857,18 @@ __device__ __forceinline__ int compare_stacks(const uint16_t* a, uint32_t da, co
 // and writes out every stack it can end in; duplicates are removed, the rest
 // is put in the host's order and packed as the next state of the row's ring,
 // in the layout the fill kernel reads (stack headers with their first-byte
-// sets, context index and list offsets; frames).  A row whose token is not
+// list offsets; frames).  A row whose token is not
 // allowed, or whose new state does not fit the device limits, keeps its state
 // and gets an error code in `status`.
 __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch bt, DevVocab voc,
                                                                       const int32_t* __restrict__ tokens) {
   __shared__ uint16_t cand[kBatchMaxCandidates * kBatchMaxDepth];
   __shared__ uint32_t cdepth[kBatchMaxCandidates];
-  __shared__ uint32_t order[kBatchMaxCandidates];  // rank among the distinct stacks, or kNoRow for a duplicate
+  __shared__ uint32_t order[kBatchMaxCandidates];  // rank among the distinct stacks, or kNoKey for a duplicate
   __shared__ uint32_t foff[kBatchMaxStacks + 1];
   __shared__ uint32_t slot_of[kBatchMaxStacks];    // candidate index per rank
-  __shared__ uint32_t ccount, coverflow, n_new, can_end;
+  __shared__ uint32_t keys[kBatchMaxStacks][kStackLists];  // the three lists of every new stack
+  __shared__ uint32_t ccount, coverflow, n_new, can_end, bad_context;
   const uint32_t tid = threadIdx.x;
   const int32_t b = blockIdx.x;
   const int32_t tok = tokens[b];
@@ -987,7 +876,8 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
   const int32_t head = bt.head[b];
   const SlotMeta cur = bt.meta[(size_t)b * bt.H + head];
   const DevCache dc = bt.cache[b];
-  const uint32_t hdr_stride = kStackHdrWords + (uint32_t)bt.n_chunk + 1u;
+  const uint32_t n_off = (uint32_t)bt.n_seg + 1u;
+  const uint32_t hdr_stride = kStackHdrWords + kStackLists * n_off;
   const int32_t next = (head + 1) % bt.H;
   const uint32_t sb = ((uint32_t)b * bt.H + next) * kBatchMaxStacks;
   const uint32_t fb = ((uint32_t)b * bt.H + next) * kBatchRowFrames;
@@ -1003,7 +893,7 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
     if (tid == 0) bt.status[b] = status;
     return;
   }
-  if (tid == 0) { ccount = 0u; coverflow = 0u; n_new = 0u; can_end = 0u; }
+  if (tid == 0) { ccount = 0u; coverflow = 0u; n_new = 0u; can_end = 0u; bad_context = 0u; }
   __syncthreads();
   DevTables tab = dc.tab;
   tab.lds_end = tab.stage_bytes = tab.n_near = 0u;  // the walks read the tables where they are
@@ -1042,24 +932,24 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       bool dup = false;
       for (uint32_t j = 0; j < tid; ++j)
         dup = dup || compare_stacks(cand + j * kBatchMaxDepth, cdepth[j], cand + tid * kBatchMaxDepth, cdepth[tid]) == 0;
-      order[tid] = dup ? kNoRow : 0u;
+      order[tid] = dup ? kNoKey : 0u;
       if (!dup) atomicAdd(&n_new, 1u);
     }
     __syncthreads();
     uint32_t before = 0u;
-    if (tid < nc && order[tid] != kNoRow)
+    if (tid < nc && order[tid] != kNoKey)
       for (uint32_t j = 0; j < nc; ++j)
-        if (j != tid && order[j] != kNoRow &&
+        if (j != tid && order[j] != kNoKey &&
             compare_stacks(cand + j * kBatchMaxDepth, cdepth[j], cand + tid * kBatchMaxDepth, cdepth[tid]) < 0)
           ++before;
     __syncthreads();
-    if (tid < nc && order[tid] != kNoRow) order[tid] = before;
+    if (tid < nc && order[tid] != kNoKey) order[tid] = before;
     __syncthreads();
     if (n_new > kBatchMaxStacks) {
       if (tid == 0) bt.status[b] = kErrTooManyStacks;
       return;
     }
-    if (tid < nc && order[tid] != kNoRow) slot_of[order[tid]] = tid;
+    if (tid < nc && order[tid] != kNoKey) slot_of[order[tid]] = tid;
     __syncthreads();
     if (tid == 0) {
       uint32_t run = 0;
@@ -1073,7 +963,7 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       const uint32_t ci = slot_of[r], d = cdepth[ci];
       for (uint32_t k = tid; k < d; k += kAcceptThreads) bt.frames[fb + foff[r] + k] = cand[ci * kBatchMaxDepth + k];
     }
-    // headers: scalars, context index, whether the stack can end the text
+    // headers: scalars, the keys of the stack's three lists, whether the stack can end the text
     if (tid < ns) {
       const uint32_t ci = slot_of[tid], d = cdepth[ci];
       const uint16_t* st = cand + ci * kBatchMaxDepth;
@@ -1082,34 +972,41 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       h[kStackHdrTop] = top | ((uint32_t)dc.acc_row[top] << 16);
       h[kStackHdrDepth] = d;
       h[kStackHdrFrames] = fb + foff[tid];
-      uint32_t ctx = kCtxNone;
-      if (d >= 2u) {
+      h[3] = 0u;
+      uint32_t key1 = kNoKey, key2 = kNoKey;
+      if (d >= 2u && dc.k1_base[top] != kNoKey) {  // (a node without context-dependent tokens has no such lists)
         const uint32_t rule = T.header(top).y >> 16, below = st[d - 2];
-        for (uint32_t i = dc.ctx_off[rule]; i < dc.ctx_off[rule + 1]; ++i)
-          if (dc.ctx_node[i] == below) ctx = i - dc.ctx_off[rule];
+        const uint32_t i = context_index(dc.ctx_node, dc.ctx_off[rule], dc.ctx_off[rule + 1], below);
+        if (i == kNoKey) bad_context = 1u;
+        else {
+          const uint32_t key1_local = dc.k1_base[top] + i;
+          key1 = (uint32_t)dc.n_nodes + key1_local;
+          if (d >= 3u && dc.k2_base != nullptr) {
+            const uint32_t rule1 = T.header(below).y >> 16;
+            const uint32_t j = context_index(dc.ctx_node, dc.ctx_off[rule1], dc.ctx_off[rule1 + 1], st[d - 3]);
+            if (j == kNoKey) bad_context = 1u;
+            else key2 = (uint32_t)dc.n_nodes + dc.n_k1 + dc.k2_base[key1_local] + j;
+          }
+        }
       }
-      h[kStackHdrCtx] = ctx;
+      keys[tid][0] = top;
+      keys[tid][1] = key1;
+      keys[tid][2] = key2;
       bool all_final = true;
       for (uint32_t k = 0; k < d; ++k) all_final = all_final && T.is_final(st[k]);
       if (all_final) can_end = 1u;
     }
-    // headers: the two first-byte sets, one thread per (stack, set, word)
-    for (uint32_t item = tid; item < ns * 16u; item += kAcceptThreads) {
-      const uint32_t r = item >> 4, below = (item >> 3) & 1u, w = item & 7u;
-      const uint32_t ci = slot_of[r], d = cdepth[ci];
-      const uint16_t* st = cand + ci * kBatchMaxDepth;
-      uint32_t acc = 0u;
-      for (uint32_t k = d - below; k-- > 0u;) {
-        acc |= *(const XGM_GLOBAL uint32_t*)(T.img + T.off_first + ((size_t)st[k] * 8u + w) * 4u);
-        if (!T.is_final(st[k])) break;
-      }
-      bt.hdrs[(size_t)(sb + r) * hdr_stride + (below ? kStackHdrBelow : kStackHdrFirst) + w] = acc;
+    __syncthreads();
+    if (bad_context) {  // a frame sits on a node that is no context of its rule: never the case for stacks the walk makes
+      if (tid == 0) bt.status[b] = kErrInternal;
+      return;
     }
-    // headers: list offsets of the top node
-    for (uint32_t item = tid; item < ns * ((uint32_t)bt.n_chunk + 1u); item += kAcceptThreads) {
-      const uint32_t r = item / ((uint32_t)bt.n_chunk + 1u), c = item % ((uint32_t)bt.n_chunk + 1u);
-      const uint32_t ci = slot_of[r], top = cand[ci * kBatchMaxDepth + cdepth[ci] - 1u];
-      bt.hdrs[(size_t)(sb + r) * hdr_stride + kStackHdrWords + c] = dc.unc_off[(size_t)top * ((uint32_t)bt.n_chunk + 1u) + c];
+    // headers: where the lists' segments start
+    for (uint32_t item = tid; item < ns * kStackLists * n_off; item += kAcceptThreads) {
+      const uint32_t r = item / (kStackLists * n_off), l = item / n_off % kStackLists, sgm = item % n_off;
+      const uint32_t key = keys[r][l];
+      bt.hdrs[(size_t)(sb + r) * hdr_stride + kStackHdrWords + l * n_off + sgm] =
+          key == kNoKey ? 0u : dc.key_off[(size_t)key * (uint32_t)bt.n_seg + sgm];
     }
     __syncthreads();
   }
@@ -1123,14 +1020,13 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
     RowDesc r;
     r.tab = dc.tab;
     r.acc = dc.acc;
-    r.unc_list = dc.unc_list;
-    r.unc_ctx = dc.unc_ctx;
+    r.entries = dc.entries;
     r.stack_begin = sb;
     r.n_stacks = m.n_stacks;
     r.flags = m.flags & 1u;
     r.frame_begin = fb;
     r.n_frames = m.n_frames;
-    r.pair_mask = 0u;
+    r.epoch = bt.rows[b].epoch + 1u;
     bt.rows[b] = r;
     bt.head[b] = next;
     const int32_t o = bt.older[b] + 1;
@@ -1154,7 +1050,7 @@ __global__ void batch_rollback_kernel(DevBatch bt, const int32_t* __restrict__ s
   r.n_stacks = m.n_stacks;
   r.n_frames = m.n_frames;
   r.flags = m.flags & 1u;
-  r.pair_mask = 0u;
+  r.epoch += 1u;
   bt.rows[b] = r;
   bt.head[b] = head;
   bt.older[b] -= k;
@@ -1171,7 +1067,7 @@ __global__ __launch_bounds__(256) void batch_fork_copy_kernel(DevBatch bt, const
   if (src < 0 || src == b) return;
   if (src >= bt.B || bt.cache[b].acc != bt.cache[src].acc) return;  // reported by the second kernel
   const uint32_t tid = threadIdx.x;
-  const uint32_t hdr_stride = kStackHdrWords + (uint32_t)bt.n_chunk + 1u;
+  const uint32_t hdr_stride = kStackHdrWords + kStackLists * ((uint32_t)bt.n_seg + 1u);
   const uint32_t from = (uint32_t)src * bt.H + bt.head[src], to = (uint32_t)b * bt.H + (bt.head[b] + 1) % bt.H;
   const SlotMeta m = bt.meta[from];
   const uint32_t* sh = bt.hdrs + (size_t)from * kBatchMaxStacks * hdr_stride;
@@ -1198,156 +1094,12 @@ __global__ void batch_fork_commit_kernel(DevBatch bt, const int32_t* __restrict_
   r.n_stacks = m.n_stacks;
   r.n_frames = m.n_frames;
   r.flags = m.flags & 1u;
-  r.pair_mask = 0u;
+  r.epoch += 1u;
   bt.rows[b] = r;
   bt.head[b] = next;
   const int32_t o = bt.older[b] + 1;
   bt.older[b] = o < bt.H - 1 ? o : bt.H - 1;
   bt.status[b] = 0;
-}
-
-// The plan of the next fill for the batch's current states (plan.hpp), by one
-// workgroup: the per-(row, chunk) running entry counts go to LDS, then one
-// thread per row cuts its row.
-constexpr int kPlanThreads = 1024;
-// `keep_cuts`: there is room behind the counts for every row's workgroups ([B][n_chunk] words), so
-// that the rows are cut once; otherwise they are cut a second time when the plan is written.
-__device__ __forceinline__ void batch_plan_body(const DevBatch& bt, unsigned char* smem, bool keep_cuts) {
-  uint32_t* upto = reinterpret_cast<uint32_t*>(smem);  // [B][n_chunk + 1]
-  __shared__ unsigned long long total;
-  __shared__ uint32_t count[kPlanThreads / 64];  // per-wave sums of the rows' workgroup counts
-  const uint32_t tid = threadIdx.x, n_off = (uint32_t)bt.n_chunk + 1u;
-  const uint32_t stride = (n_off + 3u) & ~3u;  // rows of `upto` start on 16 bytes
-  const uint32_t hdr_stride = kStackHdrWords + n_off;
-  uint32_t* cuts = upto + (size_t)bt.B * stride;  // [B][n_chunk] the rows' workgroups (FillBlock::c0c1), if kept
-  if (tid == 0) total = 0ull;
-  {  // a few threads per row: the row's descriptor is read once, the reads of its offsets are under way together
-    const uint32_t per_row = max(1u, (uint32_t)kPlanThreads / (uint32_t)bt.B), rows_at_once = (uint32_t)kPlanThreads / per_row;
-    for (uint32_t b = tid / per_row; b < (uint32_t)bt.B; b += rows_at_once) {
-      const uint32_t s0 = bt.rows[b].stack_begin, ns = bt.rows[b].n_stacks;
-#pragma unroll 4
-      for (uint32_t c = tid % per_row; c < stride; c += per_row) {
-        uint32_t run = 0u;
-        if (c < n_off)
-          for (uint32_t s = 0; s < ns; ++s) {
-            const uint32_t* off = bt.hdrs + (size_t)(s0 + s) * hdr_stride + kStackHdrWords;
-            run += off[c] - off[0];
-          }
-        upto[b * stride + c] = run;
-      }
-    }
-  }
-  __syncthreads();
-  {  // the batch's total: per-wave sums with lane shuffles, one 64-bit atomic per wave
-    unsigned long long mine_total = tid < (uint32_t)bt.B ? (unsigned long long)upto[tid * stride + bt.n_chunk] : 0ull;
-#pragma unroll
-    for (uint32_t d = 32; d > 0; d >>= 1) mine_total += __shfl_down(mine_total, d, 64);
-    if ((tid & 63u) == 0 && mine_total) atomicAdd(&total, mine_total);
-  }
-  __syncthreads();
-  int32_t k = 0;
-  // the row's running counts, read four at a time (the cuts are made by one thread per row, one chunk after
-  // the other: what it waits for is these reads)
-  const uint4* mine4 = reinterpret_cast<const uint4*>(upto + tid * stride);
-  uint4 held = make_uint4(0u, 0u, 0u, 0u);
-  int32_t held_at = -1;
-  auto upto_of = [&](int32_t c) {
-    if ((c >> 2) != held_at) {
-      held_at = c >> 2;
-      held = mine4[held_at];
-    }
-    const uint32_t lo = (c & 1) ? held.y : held.x, hi = (c & 1) ? held.w : held.z;
-    return (uint64_t)((c & 2) ? hi : lo);
-  };
-  uint32_t my_count = 0u;
-  if (tid < (uint32_t)bt.B) {
-    k = plan_row_share(bt.B, bt.n_chunk, bt.budget, upto[tid * stride + bt.n_chunk], total);
-    my_count = (uint32_t)plan_row((int32_t)tid, bt.n_chunk, k, upto_of, [&](int32_t made, const FillBlock& f) {
-      if (keep_cuts) cuts[tid * (uint32_t)bt.n_chunk + (uint32_t)made] = f.c0c1;
-    });
-  }
-  // inclusive scan of the rows' workgroup counts: inside each wave with lane shuffles, then over the 16 wave sums
-  uint32_t incl = my_count;
-  const uint32_t lane = tid & 63u, wave = tid >> 6;
-#pragma unroll
-  for (uint32_t d = 1; d < 64u; d <<= 1) {
-    const uint32_t v = __shfl_up(incl, d, 64);
-    if (lane >= d) incl += v;
-  }
-  if (lane == 63u) count[wave] = incl;
-  __syncthreads();
-  uint32_t before = 0u, n_blocks = 0u;
-  for (uint32_t w = 0; w < (uint32_t)kPlanThreads / 64u; ++w) {
-    const uint32_t c = count[w];
-    if (w < wave) before += c;
-    n_blocks += c;
-  }
-  const uint32_t first = before + incl - my_count;
-  for (uint32_t j = tid; j < bt.plan_cap; j += kPlanThreads) bt.plan[j] = FillBlock{kNoRow, 0u};
-  __syncthreads();
-  if (tid < (uint32_t)bt.B && n_blocks <= bt.plan_cap) {
-    if (keep_cuts)
-      for (uint32_t i = 0; i < my_count; ++i)
-        bt.plan[plan_slot(first + i, n_blocks)] = FillBlock{tid, cuts[tid * (uint32_t)bt.n_chunk + i]};
-    else
-      plan_row((int32_t)tid, bt.n_chunk, k, upto_of,
-               [&](int32_t made, const FillBlock& f) { bt.plan[plan_slot(first + (uint32_t)made, n_blocks)] = f; });
-  }
-}
-
-// Ahead of the next fill: the two-byte tables (see build_pair_table) of the
-// stacks of rows whose state has changed, for stacks whose lists are long
-// enough to make the fill kernel want one.  One workgroup per row; a row that
-// has been examined since its last change is skipped.
-constexpr int kPairThreads = kPlanThreads;  // the two share a launch
-__device__ __forceinline__ void batch_pair_body(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries,
-                                                int32_t b, unsigned char* smem) {
-  __shared__ uint32_t pair[kPairWords];
-  __shared__ uint16_t live_lds[kBatchMaxDepth];
-  const uint32_t tid = threadIdx.x;
-  const RowDesc rd = bt.rows[b];
-  if (rd.pair_mask & 0x80000000u) return;
-  const uint32_t hdr_stride = kStackHdrWords + (uint32_t)bt.n_chunk + 1u;
-  uint32_t need = 0u;
-  for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-    const uint32_t* h = bt.hdrs + (size_t)(rd.stack_begin + s) * hdr_stride;
-    if (h[kStackHdrDepth] >= 2u && h[kStackHdrWords + bt.n_chunk] - h[kStackHdrWords] >= pair_min_entries) need |= 1u << s;
-  }
-  if (need) {
-    stage_tables(rd.tab, smem, kPairThreads);
-    __syncthreads();
-    const uint32_t* node_first = reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(rd.tab.image) + rd.tab.off_first);
-    auto body = [&](const auto& T) {
-      for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-        if (!((need >> s) & 1u)) continue;
-        const uint32_t* h = bt.hdrs + (size_t)(rd.stack_begin + s) * hdr_stride;
-        const uint32_t depth = h[kStackHdrDepth];
-        const uint16_t* fr = bt.frames + h[kStackHdrFrames];
-        for (uint32_t k = tid; k < depth; k += kPairThreads) live_lds[k] = fr[k];
-        __syncthreads();
-        LiveView live;
-        live.lds = (const XGM_LDS uint16_t*)live_lds;
-        live.glob = (const XGM_GLOBAL uint16_t*)fr;
-        live.lo = 0u;
-        build_pair_table<kPairThreads>(T, pair, h + kStackHdrBelow, (uint32_t)live_lds[depth - 2], live, depth, node_first, voc);
-        uint32_t* out = bt.pair + ((size_t)b * kBatchMaxStacks + s) * kPairWords;
-        for (uint32_t k = tid; k < kPairWords; k += kPairThreads) out[k] = pair[k];
-        __syncthreads();
-      }
-    };
-    if (small_sections_staged(rd.tab)) body(LdsTabT<true>(rd.tab, smem));
-    else body(LdsTab(rd.tab, smem));
-  }
-  if (tid == 0) bt.rows[b].pair_mask = 0x80000000u | need;
-}
-
-// After a change of state: the plan of the next fill (one workgroup) and, beside it, the two-byte tables
-// of the rows that want one (one workgroup per row).  Neither reads what the other writes.
-__global__ __launch_bounds__(kPlanThreads) void batch_plan_pair_kernel(DevBatch bt, DevVocab voc, uint32_t pair_min_entries,
-                                                                       bool keep_cuts) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  if ((int32_t)blockIdx.x == bt.B) batch_plan_body(bt, smem, keep_cuts);
-  else batch_pair_body(bt, voc, pair_min_entries, (int32_t)blockIdx.x, smem);
 }
 
 // ---------------------------------------------------------------- kernel (c)
@@ -1411,7 +1163,7 @@ __global__ __launch_bounds__(kLookupThreads) void lds_lookup_kernel(uint32_t n_w
 
 // ------------------------------------------------------------ static scratch
 // Staging memory for the fill entry point that may not allocate: the per-step
-// blob (row descriptors, stack headers, frames, plan) goes here instead of into
+// blob (row descriptors, stack headers, frames) goes here instead of into
 // a buffer from hipMalloc.  Each device holds its own copy of the array at its
 // own address until the process ends.
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
@@ -1471,8 +1223,9 @@ void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* acc_rank, co
                      row_pair * per_block, stream, voc, n, per_block, acc_rank, unc_rank, acc_id, unc_id);
 }
 
-void launch_hash_rows(const uint32_t* rows, int32_t n, int32_t W, unsigned long long* digest, hipStream_t stream) {
-  if (n > 0) hipLaunchKernelGGL(hash_rows_kernel, dim3(n), dim3(kRowThreads), 0, stream, rows, W, digest);
+void launch_row_stats(const DevVocab& voc, int32_t n, const uint32_t* acc_id, const uint32_t* unc_id, uint32_t* seg_counts,
+                      unsigned long long* digest, uint32_t* unc_counts, hipStream_t stream) {
+  if (n > 0) hipLaunchKernelGGL(row_stats_kernel, dim3(n), dim3(kRowThreads), 0, stream, voc, acc_id, unc_id, seg_counts, digest, unc_counts);
 }
 void launch_rows_equal(const uint32_t* rows, int32_t n, int32_t W, const int32_t* rep, uint32_t* equal, hipStream_t stream) {
   if (n > 0) hipLaunchKernelGGL(rows_equal_kernel, dim3(n), dim3(kRowThreads), 0, stream, rows, W, rep, equal);
@@ -1482,30 +1235,32 @@ void launch_gather_rows(const uint32_t* rows, int32_t W, const int32_t* unique, 
   if (n_unique > 0) hipLaunchKernelGGL(gather_rows_kernel, dim3(n_unique), dim3(kRowThreads), 0, stream, rows, W, unique, out);
 }
 
-void launch_count_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_id, uint32_t* counts,
-                            hipStream_t stream) {
-  if (n <= 0) return;
-  hipLaunchKernelGGL(count_uncertain_kernel, dim3(voc.n_chunk, n), dim3(kChunkWords), 0, stream, voc, unc_id, counts);
-}
-
-void launch_list_uncertain(const DevVocab& voc, int32_t n, const uint32_t* unc_id, const uint32_t* off,
-                           uint32_t* list, hipStream_t stream) {
-  if (n <= 0) return;
-  hipLaunchKernelGGL(list_uncertain_kernel, dim3(voc.n_chunk, n), dim3(kChunkWords), 0, stream, voc, unc_id, off, list);
-}
-
-void launch_annotate_lists(const DevTables& tab, const DevVocab& voc, int32_t n, const uint32_t* off, uint32_t total,
-                           uint32_t* list, uint32_t* list_ctx, const uint32_t* ctx_off, const uint16_t* ctx_node,
-                           hipStream_t stream) {
-  for (int32_t node0 = 0; node0 < n; node0 += 32768) {  // grid.y limit
-    const int32_t nb = std::min(32768, n - node0);
-    hipLaunchKernelGGL(annotate_lists_kernel, dim3(voc.n_chunk, nb), dim3(kAnnotateThreads), 0, stream,
-                       staged_for(tab, 0), voc, node0, off, list);
+void launch_rows_to_lists(const DevVocab& voc, int32_t n, const uint32_t* rows, const uint32_t* cursor_of, int32_t per_row,
+                          uint32_t* cursor, uint32_t* out, hipStream_t stream) {
+  for (int32_t r0 = 0; r0 < n; r0 += 32768) {  // grid.y limit
+    const int32_t nb = std::min(32768, n - r0);
+    hipLaunchKernelGGL(rows_to_lists_kernel, dim3(voc.n_seg, nb), dim3(kListThreads), 0, stream, voc,
+                       rows + (size_t)r0 * voc.W, cursor_of + r0, per_row, cursor, out);
   }
+}
+
+void launch_exit_positions(const DevTables& tab, const DevVocab& voc, int32_t n_nodes, const uint32_t* node_off,
+                           const uint32_t* base_ids, uint32_t total, uint32_t* exits, hipStream_t stream) {
   if (total == 0) return;
   const DevTables st = staged_for(tab, kClassifyLdsBudget);
-  hipLaunchKernelGGL(context_classes_kernel, dim3((total + kContextThreads - 1) / kContextThreads), dim3(kContextThreads),
-                     st.stage_bytes, stream, st, voc, n, total, off, list, list_ctx, ctx_off, ctx_node);
+  hipLaunchKernelGGL(exit_positions_kernel, dim3((total + kContextThreads - 1) / kContextThreads), dim3(kContextThreads),
+                     st.stage_bytes, stream, st, voc, n_nodes, node_off, base_ids, total, exits);
+}
+
+void launch_context_lists(const DevTables& tab, const DevVocab& voc, int32_t n_nodes, uint64_t n_items,
+                          const ContextListArgs& args, bool write, hipStream_t stream) {
+  if (n_items == 0) return;
+  const DevTables st = staged_for(tab, kClassifyLdsBudget);
+  const dim3 grid((uint32_t)((n_items + kContextThreads - 1) / kContextThreads));
+  if (write)
+    hipLaunchKernelGGL(context_lists_kernel<true>, grid, dim3(kContextThreads), st.stage_bytes, stream, st, voc, n_nodes, n_items, args);
+  else
+    hipLaunchKernelGGL(context_lists_kernel<false>, grid, dim3(kContextThreads), st.stage_bytes, stream, st, voc, n_nodes, n_items, args);
 }
 
 void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items, uint32_t* acc_rank,
@@ -1522,58 +1277,41 @@ void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t 
                      reinterpret_cast<const uint4*>(pinned_src), reinterpret_cast<uint4*>(dst), n16);
 }
 
-void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames,
-                 const FillBlock* plan, int32_t n_blocks, const DevVocab& voc, uint32_t* out, OverflowLog* log,
-                 uint32_t seq, unsigned long long* step_counter, hipStream_t stream, void* logits, int elem_size,
-                 uint32_t neg_inf, int32_t V_logits, int64_t row_stride, uint32_t pair_min_entries,
-                 const uint32_t* pair_tables) {
-  if (n_blocks <= 0 || n_blocks % kFillGridMultiple != 0) return;  // callers pad the plan with kNoRow entries
-  const dim3 grid(n_blocks);
-  const FusedApply fa{static_cast<unsigned char*>(logits), row_stride, V_logits, neg_inf, pair_min_entries, pair_tables};
+void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames, int32_t B, const DevVocab& voc,
+                 uint32_t* out, OverflowLog* log, uint32_t seq, unsigned long long* step_counter, hipStream_t stream,
+                 void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride) {
+  if (B <= 0) return;
+  const dim3 grid(voc.n_seg, B);
+  const FusedApply fa{static_cast<unsigned char*>(logits), row_stride, V_logits, neg_inf};
   if (logits && elem_size == 2)
     hipLaunchKernelGGL((fill_kernel<false, 2>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
-                       plan, voc, out, log, seq, step_counter, fa);
+                       voc, out, log, seq, step_counter, fa);
   else if (logits)
     hipLaunchKernelGGL((fill_kernel<false, 4>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
-                       plan, voc, out, log, seq, step_counter, fa);
+                       voc, out, log, seq, step_counter, fa);
   else if (step_counter)
     hipLaunchKernelGGL((fill_kernel<true, 0>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
-                       plan, voc, out, log, seq, step_counter, fa);
+                       voc, out, log, seq, step_counter, fa);
   else
     hipLaunchKernelGGL((fill_kernel<false, 0>), grid, dim3(kFillThreads), kFillLdsBudget, stream, rows, stack_hdrs, frames,
-                       plan, voc, out, log, seq, step_counter, fa);
+                       voc, out, log, seq, step_counter, fa);
 }
 
 void launch_lds_lookups(int32_t n_blocks, uint32_t hops, uint32_t* sink, hipStream_t stream) {
   hipLaunchKernelGGL(lds_lookup_kernel, dim3(n_blocks), dim3(kLookupThreads), 8192 * 4, stream, 8192u, hops, sink);
 }
 
-void launch_batch_plan(const DevBatch& bt, const DevVocab& voc, uint32_t pair_min_entries, hipStream_t stream) {
-  size_t plan_bytes = (size_t)bt.B * ((bt.n_chunk + 1 + 3) & ~3) * 4;
-  const size_t cuts_bytes = (size_t)bt.B * bt.n_chunk * 4;
-  const bool keep_cuts = plan_bytes + cuts_bytes <= (size_t)64 * 1024;
-  if (keep_cuts) plan_bytes += cuts_bytes;
-  hipLaunchKernelGGL(batch_plan_pair_kernel, dim3(bt.B + 1), dim3(kPlanThreads), std::max<size_t>(plan_bytes, kFillLdsBudget),
-                     stream, bt, voc, pair_min_entries, keep_cuts);
-}
-
-void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, uint32_t pair_min_entries,
-                         hipStream_t stream) {
+void launch_batch_accept(const DevBatch& bt, const DevVocab& voc, const int32_t* d_tokens, hipStream_t stream) {
   hipLaunchKernelGGL(batch_accept_kernel, dim3(bt.B), dim3(kAcceptThreads), 0, stream, bt, voc, d_tokens);
-  launch_batch_plan(bt, voc, pair_min_entries, stream);
 }
 
-void launch_batch_fork(const DevBatch& bt, const DevVocab& voc, const int32_t* d_src_rows, uint32_t pair_min_entries,
-                       hipStream_t stream) {
+void launch_batch_fork(const DevBatch& bt, const int32_t* d_src_rows, hipStream_t stream) {
   hipLaunchKernelGGL(batch_fork_copy_kernel, dim3(bt.B), dim3(256), 0, stream, bt, d_src_rows);
   hipLaunchKernelGGL(batch_fork_commit_kernel, dim3((bt.B + 255) / 256), dim3(256), 0, stream, bt, d_src_rows);
-  launch_batch_plan(bt, voc, pair_min_entries, stream);
 }
 
-void launch_batch_rollback(const DevBatch& bt, const DevVocab& voc, const int32_t* d_steps, uint32_t pair_min_entries,
-                           hipStream_t stream) {
+void launch_batch_rollback(const DevBatch& bt, const int32_t* d_steps, hipStream_t stream) {
   hipLaunchKernelGGL(batch_rollback_kernel, dim3((bt.B + 255) / 256), dim3(256), 0, stream, bt, d_steps);
-  launch_batch_plan(bt, voc, pair_min_entries, stream);
 }
 
 void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logits, int64_t row_stride,

@@ -200,43 +200,6 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
   return kReject;
 }
 
-// The bytes that can be consumed next from a configuration: what the node
-// itself can consume (byte edges and the first bytes of the rules it refers
-// to) and, as long as the nodes passed may end their rule instance, the same
-// for the frames below.  `acc.add(word, bits)` receives the 256-bit set.
-template <class Tab, class Live, class Acc>
-XGM_HD void config_next_bytes(const Tab& T, const uint32_t* node_first_words, uint32_t n, uint32_t sp,
-                              const uint32_t* arena, const Live& live, Acc& acc) {
-  for (;;) {
-    const uint32_t* fw = node_first_words + (size_t)n * 8;
-    for (uint32_t w = 0; w < 8; ++w) acc.add(w, fw[w]);
-    if (!T.is_final(n)) return;
-    if (sp < kLiveBase) {
-      const uint32_t fr = arena[sp];
-      n = fr & 0xFFFFu;
-      sp = fr >> 16;
-    } else {
-      const uint32_t d = sp - kLiveBase;
-      if (d == 0) return;
-      n = live[d - 1];
-      sp = kLiveBase + d - 1;
-    }
-  }
-}
-
-// End policy that collects the next-byte sets of all configurations a string can end in.
-template <class Tab, class Acc>
-struct CollectNextBytes {
-  static constexpr bool kEnumerate = true;
-  const Tab* T;
-  const uint32_t* node_first_words;
-  Acc* acc;
-  template <class Live>
-  XGM_HD void operator()(uint32_t n, uint32_t sp, const uint32_t* arena, const Live& live) const {
-    config_next_bytes(*T, node_first_words, n, sp, arena, live, *acc);
-  }
-};
-
 // End policy that writes out the stack of every configuration a token can end
 // in (section 3.3: the sampled token moves every parallel stack on).  A top
 // node that can only return is returned from first, so that equal states get

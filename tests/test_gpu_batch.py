@@ -34,15 +34,6 @@ def wl():
     return workloads
 
 
-@pytest.fixture(params=["default", "two-byte tables everywhere"])
-def pair_table(request, xgm):
-    """Runs a test twice: with the default threshold for the two-byte tables (at these sizes the
-    fill kernel rarely wants one), and with tables computed ahead of every fill for every stack."""
-    old = xgm.debug_set_fill_pair_threshold(1 if request.param != "default" else -1)
-    yield request.param
-    xgm.debug_set_fill_pair_threshold(old)
-
-
 def _stream():
     return int(torch.cuda.current_stream().cuda_stream)
 
@@ -77,7 +68,7 @@ class _Rows:
         walks over the on-chip limits (the markup grammar has a few) are decided after each fill."""
         self.d_dev.fill_(-1)
         self.batch.fill_next_token_bitmask(self.d_dev.data_ptr(), _stream())
-        xgm.fill_overflow_fixup(_stream())
+        self.batch.fill_overflow_fixup(_stream())
         xgm.fill_next_token_bitmask(self.ms, self.d_host.data_ptr(), _stream())
         xgm.fill_overflow_fixup(_stream())
         return self.d_dev.cpu().numpy(), self.d_host.cpu().numpy()
@@ -93,7 +84,7 @@ MIXED = [(si.JSON_GRAMMAR, "root"), (si.CSQL_GRAMMAR, "root"), (si.XML_GRAMMAR, 
          (si.JSON_GRAMMAR, "root"), (si.make_schema_grammar(2, string_heavy=True), "root")]
 
 
-def test_device_accept_follows_host_matchers_and_oracle(xgm, wl, pair_table):
+def test_device_accept_follows_host_matchers_and_oracle(xgm, wl):
     vocab = si.make_vocab("bpe", 32000, 0)
     rows = _Rows(xgm, wl, MIXED, vocab, history=4)
     info = wl.TokenInfo(vocab)
@@ -160,7 +151,7 @@ def test_device_accept_follows_host_matchers_and_oracle(xgm, wl, pair_table):
     assert n_ok > 250 and n_rejected > 20 and n_skipped > 10 and n_host < 10
 
 
-def test_rollback_returns_to_earlier_states(xgm, wl, pair_table):
+def test_rollback_returns_to_earlier_states(xgm, wl):
     vocab = si.make_vocab("bpe", 32000, 0)
     specs = [(si.JSON_GRAMMAR, "root"), (si.make_schema_grammar(3, string_heavy=True), "root"),
              (si.CSQL_GRAMMAR, "root"), (si.JSON_GRAMMAR, "root")]
@@ -246,7 +237,7 @@ def test_batch_fused_fill_and_apply(xgm, wl, dtype_name):
         rows.batch.fill_and_apply(rows.d_dev.data_ptr(), logits.data_ptr(), code, 100, logits.stride(0), _stream())
 
 
-def test_device_limits_are_reported_and_the_host_takes_over(xgm, wl, pair_table):
+def test_device_limits_are_reported_and_the_host_takes_over(xgm, wl):
     toks = [b"x", b"p", b"q", b"xx", b"[", b"]", b"1", b","] + [b""]
     V = len(toks)
 
@@ -349,16 +340,93 @@ def test_batch_fill_walks_over_the_limits_are_fixed_up(xgm, wl):
     batch.fill_next_token_bitmask(d.data_ptr(), _stream())
     torch.cuda.synchronize()
     assert xgm.overflow_total() - before == 2
-    assert xgm.fill_overflow_fixup(_stream()) == 2
+    # the batch's own counter, read without synchronising the device (a 4-byte copy on the stream)
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    import ctypes
+    import os
+    hip = ctypes.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"))   # the runtime torch has loaded
+    hip.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    assert hip.hipMemcpyAsync(count.data_ptr(), batch.overflow_count_device(), 4, 3, _stream()) == 0
+    assert int(count.cpu()[0]) == 2
+    assert xgm.fill_overflow_fixup(_stream()) == 0          # nothing of this belongs to the host-state fills
+    assert batch.fill_overflow_fixup(_stream()) == 2
     assert np.array_equal(d.cpu().numpy()[0], oracle.pack_bitmask(want))
+    assert batch.fill_overflow_fixup(_stream()) == 0         # every record is decided once
     batch.accept_tokens(_dev([4]).data_ptr(), _stream())
     assert list(batch.status(_stream())) == [-9]
     m.accept_token(4)
     assert om.advance(deep)
     batch.set_row(0, m, _stream())
     batch.fill_next_token_bitmask(d.data_ptr(), _stream())
-    xgm.fill_overflow_fixup(_stream())
+    batch.fill_overflow_fixup(_stream())
     assert np.array_equal(d.cpu().numpy()[0], oracle.pack_bitmask(om.mask(V_)))
+
+
+def test_walk_records_of_two_batches_on_two_streams_stay_apart(xgm, wl):
+    """Two batches whose fills interleave on two streams; only the first has a state in which a token's
+    walk exceeds the on-chip limits.  Each batch keeps its own records: the fixup of either decides
+    exactly its own, in any order, and a record whose row has moved on is reported, not guessed."""
+    deep = b")+" + b"(" * 30
+    toks = [b"1", b"(", b")", b"+", deep, deep + b"+", b"1" * 20, b")" * 4, b""]
+    V = len(toks)
+
+    class V_:
+        data = np.frombuffer(b"".join(toks), dtype=np.uint8).copy()
+        offsets = np.concatenate([[0], np.cumsum([len(t) for t in toks])]).astype(np.int64)
+        stop_ids = np.array([8], dtype=np.int32)
+        size = V
+
+    xv = xgm.Vocab(V_.data, V_.offsets, V_.stop_ids)
+    cache = xgm.Cache(xgm.Grammar(si.ARITH_GRAMMAR, "expr"), xv)
+    og = oracle.Grammar(si.ARITH_GRAMMAR, "expr")
+    texts_a = [b"(" * 5 + b"1", b"1+", b"((1"]      # rows 0 and 2 are inside parentheses: `deep` needs a walk there
+    texts_b = [b"1", b"1+1"]                        # no parentheses open: nothing to walk
+    ms_a, ms_b, oms_a, oms_b = [], [], [], []
+    for texts, ms, oms in ((texts_a, ms_a, oms_a), (texts_b, ms_b, oms_b)):
+        for t in texts:
+            m = xgm.Matcher(cache=cache)
+            m.accept_bytes(t)
+            om = oracle.EarleyMatcher(og)
+            assert om.advance(t)
+            ms.append(m)
+            oms.append(om)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    batch_a = xgm.DeviceBatch(ms_a, history=2, stream=s1.cuda_stream)
+    batch_b = xgm.DeviceBatch(ms_b, history=2, stream=s2.cuda_stream)
+    d_a = torch.zeros((3, 1), dtype=torch.int32, device="cuda")
+    d_a2 = torch.zeros((3, 1), dtype=torch.int32, device="cuda")
+    d_b = torch.zeros((2, 1), dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    before = xgm.overflow_total()
+    batch_a.fill_next_token_bitmask(d_a.data_ptr(), s1.cuda_stream)
+    batch_b.fill_next_token_bitmask(d_b.data_ptr(), s2.cuda_stream)
+    batch_a.fill_next_token_bitmask(d_a2.data_ptr(), s1.cuda_stream)      # a second fill of the same states, another buffer
+    batch_b.fill_next_token_bitmask(d_b.data_ptr(), s2.cuda_stream)
+    want_a = oracle.pack_bitmask(np.stack([om.mask(V_) for om in oms_a]))
+    want_b = oracle.pack_bitmask(np.stack([om.mask(V_) for om in oms_b]))
+    assert batch_b.fill_overflow_fixup(s2.cuda_stream) == 0               # the other batch's fixup first: it has nothing
+    assert np.array_equal(d_b.cpu().numpy(), want_b)
+    n = batch_a.fill_overflow_fixup(s1.cuda_stream)
+    assert n > 0 and n % 2 == 0                                           # both fills of batch a, the same pairs each
+    assert xgm.overflow_total() - before == n
+    assert np.array_equal(d_a.cpu().numpy(), want_a)
+    assert np.array_equal(d_a2.cpu().numpy(), want_a)
+    assert xgm.fill_overflow_fixup(s1.cuda_stream) == 0                   # and none of it reached the host-state fills' log
+    # a record whose row has left the state it was made in cannot be decided any more: reported as an error
+    batch_a.fill_next_token_bitmask(d_a.data_ptr(), s1.cuda_stream)
+    torch.cuda.synchronize()
+    batch_a.accept_tokens(_dev([1, -1, 1]).data_ptr(), s1.cuda_stream)    # "(" right after a digit is refused:
+    assert list(batch_a.status(s1.cuda_stream)) == [-6, 0, -6]             # the states stay, so the fixup still works
+    assert batch_a.fill_overflow_fixup(s1.cuda_stream) == n // 2
+    assert np.array_equal(d_a.cpu().numpy(), want_a)
+    batch_a.fill_next_token_bitmask(d_a.data_ptr(), s1.cuda_stream)
+    torch.cuda.synchronize()
+    batch_a.accept_tokens(_dev([3, -1, 3]).data_ptr(), s1.cuda_stream)    # "+" moves rows 0 and 2 on
+    assert not batch_a.status(s1.cuda_stream).any()
+    with pytest.raises(xgm.XgmError) as e:
+        batch_a.fill_overflow_fixup(s1.cuda_stream)
+    assert e.value.status == -9 and "left" in str(e.value)
+    assert batch_a.fill_overflow_fixup(s1.cuda_stream) == 0               # reported once
 
 
 def test_stop_token_and_termination_on_the_device(xgm, wl):
@@ -423,87 +491,40 @@ def test_stop_token_and_termination_on_the_device(xgm, wl):
     assert not s.is_terminated() and _stacks(s) == _stacks(ms[1])
 
 
-def test_device_plan_equals_the_host_plan(xgm, wl):
-    """The plan kernel against the host planner (whose invariants the CPU suite checks) on the
-    same list lengths, after creation, after a step of all rows, and after a rollback."""
-    vocab = si.make_vocab("bpe", 151936, 0)
-    specs = [(si.make_schema_grammar(s, string_heavy=True), "root") for s in range(6)] + [(si.JSON_GRAMMAR, "root")] * 2
-    rows = _Rows(xgm, wl, specs, vocab, history=2)
-    info = wl.TokenInfo(vocab)
-    rng = np.random.Generator(np.random.PCG64(5))
-    n_chunk = (xgm.bitmask_words(vocab.size) + 127) // 128
-
-    def check():
-        plan, budget = rows.batch.debug_plan(_stream())
-        upto = np.zeros((rows.B, n_chunk + 1), dtype=np.uint32)
-        for b, (m, c) in enumerate(zip(rows.ms, rows.caches)):
-            if m.is_terminated():
-                continue
-            for s in range(m.num_stacks()):
-                # list lengths per chunk of 4096 ids, from the node's context-dependent bitset
-                _, unc = c.copy_node_bits(m.stack(s)[-1])
-                bits = np.unpackbits(unc.view(np.uint8), bitorder="little")
-                per_chunk = np.add.reduceat(bits, np.arange(0, bits.size, 4096))[:n_chunk]
-                upto[b, 1:] += np.cumsum(per_chunk).astype(np.uint32)
-        want = xgm.debug_plan_workgroups(upto, budget)
-        assert np.array_equal(plan, want)
-        return len(plan)
-
-    n0 = check()
-    for step in range(6):
-        got, host = rows.masks(xgm)
-        assert np.array_equal(got, host)
-        allowed = wl.unpack_rows(got, vocab.size)
-        allowed[:, vocab.stop_ids] = False
-        picks = si.pick_tokens(rng, allowed, info.structural, info.is_stop, 0.35)
-        rows.batch.accept_tokens(_dev(picks).data_ptr(), _stream())
-        assert not rows.batch.status(_stream()).any()
-        for b in range(rows.B):
-            rows.ms[b].accept_token(int(picks[b]))
-        n1 = check()
-    say(f"  plans of {n0} .. {n1} workgroups equal the host planner's")
-
-
-def test_device_plan_with_many_rows(xgm, wl):
-    """1000 rows of a mid-sized vocabulary: the plan kernel has no room to keep the rows' cuts and
-    makes them a second time when it writes the plan; several rows share a planning thread pass."""
+def test_many_rows_fill_from_resident_states_equals_host_states(xgm, wl):
+    """1000 rows of a mid-sized vocabulary: the fill from device-resident states agrees with the fill from
+    host-side states, and both with the oracle for the distinct states."""
     vocab = si.make_vocab("bpe", 32000, 0)
     xv = wl.make_xgm_vocab(vocab)
-    caches = [xgm.Cache(xgm.Grammar(t, "root"), xv) for t in (si.JSON_GRAMMAR, si.make_schema_grammar(1, string_heavy=True))]
+    texts = (si.JSON_GRAMMAR, si.make_schema_grammar(1, string_heavy=True))
+    caches = [xgm.Cache(xgm.Grammar(t, "root"), xv) for t in texts]
     prefixes = [b"", b'{"a": "x', b"[1, ", b'{"k', b"[", b'["abc", ']
-    ms = []
+    ms, keys = [], []
     for b in range(1000):
         m = xgm.Matcher(cache=caches[0] if b % 3 else caches[1])
         if b % 3:
             m.accept_bytes(prefixes[b % len(prefixes)])
         ms.append(m)
+        keys.append((0, prefixes[b % len(prefixes)]) if b % 3 else (1, b""))
     batch = xgm.DeviceBatch(ms, history=0, stream=_stream())
-    n_chunk = (xgm.bitmask_words(vocab.size) + 127) // 128
-    plan, budget = batch.debug_plan(_stream())
-    upto = np.zeros((len(ms), n_chunk + 1), dtype=np.uint32)
-    per_node = {}
-    for b, m in enumerate(ms):
-        c = m.cache if hasattr(m, "cache") else (caches[0] if b % 3 else caches[1])
-        for s in range(m.num_stacks()):
-            key = (id(c), m.stack(s)[-1])
-            if key not in per_node:
-                _, unc = c.copy_node_bits(m.stack(s)[-1])
-                bits = np.unpackbits(unc.view(np.uint8), bitorder="little")
-                per_node[key] = np.cumsum(np.add.reduceat(bits, np.arange(0, bits.size, 4096))[:n_chunk]).astype(np.uint32)
-            upto[b, 1:] += per_node[key]
-    want = xgm.debug_plan_workgroups(upto, budget)
-    assert np.array_equal(plan, want)
-    # and the fill that runs this plan agrees with the fill from host-side states
     W = xgm.bitmask_words(vocab.size)
     d_dev = torch.zeros((len(ms), W), dtype=torch.int32, device="cuda")
     d_host = torch.zeros((len(ms), W), dtype=torch.int32, device="cuda")
     batch.fill_next_token_bitmask(d_dev.data_ptr(), _stream())
     xgm.fill_next_token_bitmask(ms, d_host.data_ptr(), _stream())
     assert torch.equal(d_dev, d_host)
-    say(f"  1000 rows: plan of {len(plan)} workgroups equals the host planner's; fills agree")
+    got = d_dev.cpu().numpy()
+    want = {}
+    for b, key in enumerate(keys):
+        if key not in want:
+            om = oracle.EarleyMatcher(oracle.Grammar(texts[key[0]], "root"))
+            assert om.advance(key[1]) or not key[1]
+            want[key] = oracle.pack_bitmask(om.mask(vocab))
+        assert np.array_equal(got[b], want[key]), f"row {b}"
+    say(f"  1000 rows ({len(want)} distinct states): resident and host-side fills agree with the oracle")
 
 
-def test_fork_continues_one_state_in_several_rows(xgm, wl, pair_table):
+def test_fork_continues_one_state_in_several_rows(xgm, wl):
     vocab = si.make_vocab("bpe", 32000, 0)
     gj = xgm.Grammar(si.JSON_GRAMMAR, "root")
     xv = wl.make_xgm_vocab(vocab)
@@ -555,7 +576,7 @@ def test_fork_continues_one_state_in_several_rows(xgm, wl, pair_table):
         flat.fork(_dev([1, -1]).data_ptr(), _stream())
 
 
-def test_random_grammars_cache_fill_and_device_accept(xgm, wl, pair_table):
+def test_random_grammars_cache_fill_and_device_accept(xgm, wl):
     """Seeded random grammars (nested groups, repetition, recursive and tail references, empty
     alternatives, ambiguity): mask cache, fill from host-side and device-resident states, and the accept
     kernel, against the oracle and the host matchers at every step."""
@@ -587,7 +608,7 @@ def test_random_grammars_cache_fill_and_device_accept(xgm, wl, pair_table):
         frozen = np.zeros(B, dtype=bool)
         for step in range(10):
             batch.fill_next_token_bitmask(d_dev.data_ptr(), _stream())
-            xgm.fill_overflow_fixup(_stream())
+            batch.fill_overflow_fixup(_stream())
             xgm.fill_next_token_bitmask(ms, d_host.data_ptr(), _stream())
             xgm.fill_overflow_fixup(_stream())
             want = np.stack([om.mask(vocab) for om in oms])
@@ -705,6 +726,7 @@ def test_random_grammars_one_launch_form(xgm, wl, seed):
                     xgm.fill_and_apply(ms, d.data_ptr(), lg.data_ptr(), xgm.DTYPE_F32, V, stride, _stream())
                 else:
                     batch.fill_and_apply(d.data_ptr(), lg.data_ptr(), xgm.DTYPE_F32, V, stride, _stream())
+                    batch.fill_overflow_fixup(_stream())
                 xgm.fill_overflow_fixup(_stream())
                 assert np.array_equal(d.cpu().numpy(), packed), (walk, step, kind)
                 assert np.array_equal(lg.cpu().numpy().view(np.uint32), expect.view(np.uint32)), (walk, step, kind)
