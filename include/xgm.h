@@ -312,6 +312,12 @@ int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, vo
 #define XGM_STATIC_STAGING_BYTES (1 << 20)
 int xgm_fill_next_token_bitmask_static(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask,
                                        void* hip_stream);
+/* What a fill has to read for this matcher's state, into h_out4 (host, 4
+ * values): [0] stacks whose top node keeps its accepted tokens as a bitset row,
+ * [1] entries of the stacks' lists of accepted tokens (top nodes that keep a
+ * list), [2] of their (node, context) lists, [3] of their (node, context,
+ * context) lists.  For the byte counts of benchmarks; needs a mask cache. */
+int xgm_debug_matcher_fill_work(const xgm_matcher* m, int64_t* h_out4);
 /* Instrumentation for benchmarks: the same fill (same result in d_bitmask)
  * with a kernel instantiation that also counts the automaton steps of all
  * walks; synchronous; *h_steps receives the count.  Not for the hot path. */

@@ -70,6 +70,7 @@ SIGNATURES = {
     "xgm_fill_next_token_bitmask_static": (_i32, [_vp, _i32, _vp, _vp]),
     "xgm_fill_and_apply": (_i32, [_vp, _i32, _vp, _vp, _i32, _i32, ctypes.c_int64, _vp]),
     "xgm_debug_fill_count_steps": (_i32, [_vp, _i32, _vp, _vp, _vp]),
+    "xgm_debug_matcher_fill_work": (_i32, [_vp, _vp]),
     "xgm_debug_fill_timed": (_i32, [_vp, _i32, _vp, _vp, _vp]),
     "xgm_batch_create": (_i32, [_vp, _i32, _i32, _vp, _pp]),
     "xgm_batch_destroy": (None, [_vp]),
@@ -343,6 +344,12 @@ class Matcher:
 
     def accept_bytes(self, data: bytes):
         _check(load_library().xgm_matcher_accept_bytes(self._h, data, len(data)))
+
+    def debug_fill_work(self) -> np.ndarray:
+        """[stacks with a bitset row, entries of the level-0 / level-1 / level-2 lists] a fill reads for this state."""
+        out = np.zeros(4, dtype=np.int64)
+        _check(load_library().xgm_debug_matcher_fill_work(self._h, out.ctypes.data))
+        return out
 
     def try_accept_bytes(self, data: bytes) -> int:
         return load_library().xgm_matcher_accept_bytes(self._h, data, len(data))

@@ -6,6 +6,7 @@
 #include <atomic>
 #include <chrono>
 #include <cstring>
+#include <deque>
 #include <mutex>
 #include <numeric>
 #include <string>
@@ -105,6 +106,64 @@ T* slab_upload(const std::vector<T>& v) {
   T* p = slab_alloc<T>(v.size());
   if (!v.empty()) HIP_OK(hipMemcpy(p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
   return p;
+}
+
+// Temporary device memory of the cache builds: one block that is reused by every build and grows to what
+// the largest build so far needed (allocating and freeing two dozen arrays per build costs more than the
+// kernels of a small grammar take).  Builds are serialised by `mu`.
+class TempArena {
+ public:
+  std::mutex mu;
+  void* alloc(size_t bytes) {
+    bytes = std::max<size_t>((bytes + 255) & ~(size_t)255, 256);
+    wanted_ += bytes;
+    if (used_ + bytes <= cap_) {
+      void* p = base_ + used_;
+      used_ += bytes;
+      return p;
+    }
+    void* p = nullptr;
+    hip_check(hipMalloc(&p, bytes), "hipMalloc");
+    extra_.push_back(p);
+    return p;
+  }
+  // after a build (the stream is idle): blocks of their own are freed and the main block grows
+  void reset() {
+    for (void* p : extra_) (void)hipFree(p);
+    extra_.clear();
+    host_keep_.clear();
+    if (wanted_ > cap_) {
+      if (base_) (void)hipFree(base_);
+      base_ = nullptr;
+      cap_ = 0;
+      void* p = nullptr;
+      const size_t want = wanted_ + wanted_ / 4;
+      if (hipMalloc(&p, want) == hipSuccess) { base_ = (char*)p; cap_ = want; }
+    }
+    used_ = wanted_ = 0;
+  }
+  template <class T>
+  T* array(size_t n) { return static_cast<T*>(alloc(std::max<size_t>(n, 1) * sizeof(T))); }
+  // (the host bytes are kept until reset(), so that the copy may run whenever the stream gets to it)
+  template <class T>
+  T* upload(const std::vector<T>& v, hipStream_t stream) {
+    T* p = array<T>(v.size());
+    if (!v.empty()) {
+      host_keep_.emplace_back((const char*)v.data(), (const char*)v.data() + v.size() * sizeof(T));
+      hip_check(hipMemcpyAsync(p, host_keep_.back().data(), v.size() * sizeof(T), hipMemcpyHostToDevice, stream), "hipMemcpyAsync");
+    }
+    return p;
+  }
+
+ private:
+  char* base_ = nullptr;
+  size_t cap_ = 0, used_ = 0, wanted_ = 0;
+  std::vector<void*> extra_;
+  std::deque<std::vector<char>> host_keep_;
+};
+TempArena& temp_arena() {
+  static TempArena a;
+  return a;
 }
 
 void require_device() {
@@ -536,11 +595,11 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
   auto c = new xgm_cache();
   c->g = g; ++g->refs;
   c->v = v; ++v->refs;
-  std::vector<void*> temps;
-  auto cleanup_temps = [&] { for (void* p : temps) (void)hipFree(p); temps.clear(); };
+  TempArena& arena = temp_arena();
+  std::lock_guard<std::mutex> build_lock(arena.mu);
+  auto cleanup_temps = [&] { (void)hipStreamSynchronize(stream); arena.reset(); };
   try {
     auto keep = [&](auto* p) { c->dev_ptrs.push_back((void*)p); return p; };
-    auto temp = [&](auto* p) { temps.push_back((void*)p); return p; };
     // automaton tables
     static_assert(sizeof(NodeHdr) == sizeof(uint2), "header layout");
     DevTables tab{};
@@ -572,21 +631,23 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       tab.n_nodes = N;
     }
 
-    uint32_t* acc_id = temp(dev_alloc<uint32_t>((size_t)N * dv.W));  // one row per node
+    const int32_t n_seg = dv.n_seg;
+    uint32_t* acc_id = arena.array<uint32_t>((size_t)N * dv.W);  // one row per node
     const bool keep_plain = (flags & XGM_CACHE_KEEP_PLAIN) != 0;
-    uint32_t* unc_id = keep_plain ? (c->d_unc_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W))) : temp(dev_alloc<uint32_t>((size_t)N * dv.W));
+    uint32_t* unc_id = keep_plain ? (c->d_unc_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W))) : arena.array<uint32_t>((size_t)N * dv.W);
     // rank-space scratch for a batch of nodes (at most 1 GiB for both bitsets)
     const size_t row_bytes = (size_t)dv.WR * 4;
-    int32_t batch = (int32_t)std::max<size_t>(1, std::min<size_t>((size_t)N, ((size_t)512 << 20) / row_bytes));
-    uint32_t* acc_rank = temp(dev_alloc<uint32_t>((size_t)batch * dv.WR));
-    uint32_t* unc_rank = temp(dev_alloc<uint32_t>((size_t)batch * dv.WR));
-    uint32_t* plain_rank = keep_plain ? temp(dev_alloc<uint32_t>((size_t)batch * dv.WR)) : nullptr;
+    const int32_t batch = (int32_t)std::max<size_t>(1, std::min<size_t>((size_t)N, ((size_t)512 << 20) / row_bytes));
+    uint32_t* acc_rank = arena.array<uint32_t>((size_t)batch * dv.WR);
+    uint32_t* unc_rank = arena.array<uint32_t>((size_t)batch * dv.WR);
+    uint32_t* plain_rank = keep_plain ? arena.array<uint32_t>((size_t)batch * dv.WR) : nullptr;
     if (keep_plain) c->d_plain_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W));
-    uint32_t* d_plain_count = temp(dev_alloc<uint32_t>((size_t)N));
+    uint32_t* d_plain_count = arena.array<uint32_t>((size_t)N);
     HIP_OK(hipMemsetAsync(d_plain_count, 0, (size_t)N * 4, stream));
     // walks over the on-chip limits are recorded in a log of this build's own (the one that the fills from
     // host-side states share is made here too, so that no fill has to allocate it)
-    OverflowLog* log = temp(new_log());
+    OverflowLog* log = arena.array<OverflowLog>(1);
+    HIP_OK(hipMemsetAsync(log, 0, 8, stream));
     {
       std::lock_guard<std::mutex> lock(ctx().mu);
       (void)overflow_log();
@@ -594,50 +655,75 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     const uint32_t seq = 1;
     uint32_t count_before = 0;
     hipEvent_t ev0, ev1;
-    HIP_OK(hipEventCreate(&ev0));
-    HIP_OK(hipEventCreate(&ev1));
+    HIP_OK(hipEventCreateWithFlags(&ev0, hipEventDefault));
+    HIP_OK(hipEventCreateWithFlags(&ev1, hipEventDefault));
     Engine engine(&A);
     std::vector<int32_t> host_plain;  // nodes of host-decided pairs that are context-dependent by section 3.1 alone
+    uint32_t* d_seg_counts = arena.array<uint32_t>((size_t)N * n_seg);
+    unsigned long long* d_digest = arena.array<unsigned long long>((size_t)N);
+    uint32_t* d_unc_counts = arena.array<uint32_t>((size_t)N);
+    auto permute = [&](int32_t node0, int32_t nb) {
+      launch_permute(dv, nb, acc_rank, unc_rank, acc_id + (size_t)node0 * dv.W, unc_id + (size_t)node0 * dv.W, stream);
+      if (keep_plain)
+        launch_permute(dv, nb, plain_rank, plain_rank, c->d_plain_id + (size_t)node0 * dv.W,
+                       c->d_plain_id + (size_t)node0 * dv.W, stream);
+    };
+    // Pairs whose walk hit a limit are decided on the host and patched into the rank-space rows of the
+    // current batch of nodes.  Returns whether there were any.
+    auto decide_recorded_pairs = [&](int32_t node0) {
+      const uint32_t count_after = read_overflow_count(log);
+      const uint32_t fresh = count_after - count_before;
+      if (fresh == 0) return false;
+      if (fresh > OverflowLog::kCap) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: too many walks exceeded the on-chip limits");
+      std::vector<uint32_t> ent((size_t)OverflowLog::kCap * 4);
+      HIP_OK(hipMemcpy(ent.data(), log->entry, ent.size() * 4, hipMemcpyDeviceToHost));
+      std::vector<uint32_t> items;
+      for (uint32_t k = 0; k < fresh; ++k) {
+        const uint32_t* e = &ent[(size_t)((count_before + k) % OverflowLog::kCap) * 4];
+        const int32_t id = v->id_of_rank[e[2]];
+        int cls = engine.classify(node0 + (int32_t)e[1], v->bytes.data() + v->off[id], (int)(v->off[id + 1] - v->off[id]));
+        if (cls < 0) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: a token walk exceeds the host limits too");
+        items.push_back(e[1]); items.push_back(e[2]); items.push_back((uint32_t)cls);
+        if (cls == kUncertainPlain) host_plain.push_back(node0 + (int32_t)e[1]);
+        ++c->host_classified;
+      }
+      uint32_t* d_items = arena.upload(items, stream);
+      launch_patch_classes(dv, d_items, (int32_t)(items.size() / 3), acc_rank, unc_rank, plain_rank, stream);
+      count_before = count_after;
+      return true;
+    };
+    // Classify, batch after batch of nodes.  A grammar that fits one batch (the rule) runs classify,
+    // the rank -> id permutation and the row statistics back to back and looks at the record of walks
+    // over the limits only afterwards; if there are any, the patched rows are permuted again.
+    const bool one_batch = batch >= N;
     for (int32_t node0 = 0; node0 < N; node0 += batch) {
       const int32_t nb = std::min(batch, N - node0);
       HIP_OK(hipEventRecord(ev0, stream));
       launch_classify(tab, dv, node0, nb, acc_rank, unc_rank, plain_rank, d_plain_count, log, seq, stream);
       HIP_OK(hipEventRecord(ev1, stream));
       HIP_OK(hipGetLastError());
-      HIP_OK(hipStreamSynchronize(stream));
+      if (!one_batch) {
+        HIP_OK(hipStreamSynchronize(stream));
+        float ms = 0.f;
+        HIP_OK(hipEventElapsedTime(&ms, ev0, ev1));
+        c->kernel_seconds += ms * 1e-3;
+        decide_recorded_pairs(node0);
+      }
+      permute(node0, nb);
+    }
+    launch_row_stats(dv, N, acc_id, unc_id, d_seg_counts, d_digest, d_unc_counts, stream);
+    HIP_OK(hipGetLastError());
+    HIP_OK(hipStreamSynchronize(stream));
+    if (one_batch) {
       float ms = 0.f;
       HIP_OK(hipEventElapsedTime(&ms, ev0, ev1));
       c->kernel_seconds += ms * 1e-3;
-      // pairs that hit a limit: decide them on the host, patch the bitsets
-      uint32_t count_after = read_overflow_count(log);
-      uint32_t fresh = count_after - count_before;
-      if (fresh > 0) {
-        if (fresh > OverflowLog::kCap) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: too many walks exceeded the on-chip limits");
-        std::vector<uint32_t> ent((size_t)OverflowLog::kCap * 4);
-        HIP_OK(hipMemcpy(ent.data(), log->entry, ent.size() * 4, hipMemcpyDeviceToHost));
-        std::vector<uint32_t> items;
-        for (uint32_t k = 0; k < fresh; ++k) {
-          const uint32_t* e = &ent[(size_t)((count_before + k) % OverflowLog::kCap) * 4];
-          const int32_t id = v->id_of_rank[e[2]];
-          int cls = engine.classify(node0 + (int32_t)e[1], v->bytes.data() + v->off[id], (int)(v->off[id + 1] - v->off[id]));
-          if (cls < 0) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: a token walk exceeds the host limits too");
-          items.push_back(e[1]); items.push_back(e[2]); items.push_back((uint32_t)cls);
-          if (cls == kUncertainPlain) host_plain.push_back(node0 + (int32_t)e[1]);
-          ++c->host_classified;
-        }
-        if (!items.empty()) {
-          uint32_t* d_items = dev_upload(items);
-          launch_patch_classes(dv, d_items, (int32_t)(items.size() / 3), acc_rank, unc_rank, plain_rank, stream);
-          HIP_OK(hipStreamSynchronize(stream));
-          (void)hipFree(d_items);
-        }
-        count_before = count_after;
+      if (decide_recorded_pairs(0)) {
+        permute(0, N);
+        launch_row_stats(dv, N, acc_id, unc_id, d_seg_counts, d_digest, d_unc_counts, stream);
+        HIP_OK(hipGetLastError());
+        HIP_OK(hipStreamSynchronize(stream));
       }
-      launch_permute(dv, nb, acc_rank, unc_rank, acc_id + (size_t)node0 * dv.W, unc_id + (size_t)node0 * dv.W, stream);
-      if (keep_plain)
-        launch_permute(dv, nb, plain_rank, plain_rank, c->d_plain_id + (size_t)node0 * dv.W,
-                       c->d_plain_id + (size_t)node0 * dv.W, stream);
-      HIP_OK(hipGetLastError());
     }
     (void)hipEventDestroy(ev0);
     (void)hipEventDestroy(ev1);
@@ -647,20 +733,13 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     }
 
     // ---- per node: accepted tokens per segment, digest of the accepted row, context-dependent tokens
-    const int32_t n_seg = dv.n_seg;
-    uint32_t* d_seg_counts = temp(dev_alloc<uint32_t>((size_t)N * n_seg));
-    unsigned long long* d_digest = temp(dev_alloc<unsigned long long>((size_t)N));
-    uint32_t* d_unc_counts = temp(dev_alloc<uint32_t>((size_t)N));
-    launch_row_stats(dv, N, acc_id, unc_id, d_seg_counts, d_digest, d_unc_counts, stream);
-    HIP_OK(hipGetLastError());
-    HIP_OK(hipStreamSynchronize(stream));
     std::vector<uint32_t> seg_counts((size_t)N * n_seg);
     std::vector<unsigned long long> digest((size_t)N);
     c->unc_count.resize(N);
+    c->plain_count.resize(N);
     HIP_OK(hipMemcpy(seg_counts.data(), d_seg_counts, seg_counts.size() * 4, hipMemcpyDeviceToHost));
     HIP_OK(hipMemcpy(digest.data(), d_digest, digest.size() * 8, hipMemcpyDeviceToHost));
     HIP_OK(hipMemcpy(c->unc_count.data(), d_unc_counts, (size_t)N * 4, hipMemcpyDeviceToHost));
-    c->plain_count.resize(N);
     HIP_OK(hipMemcpy(c->plain_count.data(), d_plain_count, (size_t)N * 4, hipMemcpyDeviceToHost));
     for (int32_t n : host_plain) ++c->plain_count[n];
 
@@ -672,39 +751,14 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       for (int32_t sgm = 0; sgm < n_seg; ++sgm) total += seg_counts[(size_t)n * n_seg + sgm];
       as_list[n] = total * 2 <= (uint64_t)dv.W;
     }
-    uint32_t* acc_rows = nullptr;
-    uint16_t* d_acc_row = nullptr;
+    std::vector<int32_t> rep((size_t)N);
     {
       std::unordered_map<unsigned long long, int32_t> first_with;
-      std::vector<int32_t> rep((size_t)N);
       for (int32_t n = 0; n < N; ++n) rep[n] = as_list[n] ? n : first_with.emplace(digest[n], n).first->second;
-      int32_t* d_rep = temp(dev_upload(rep));
-      uint32_t* d_equal = temp(dev_alloc<uint32_t>((size_t)N));
-      launch_rows_equal(acc_id, N, dv.W, d_rep, d_equal, stream);
-      HIP_OK(hipGetLastError());
-      HIP_OK(hipStreamSynchronize(stream));
-      std::vector<uint32_t> equal((size_t)N);
-      HIP_OK(hipMemcpy(equal.data(), d_equal, equal.size() * 4, hipMemcpyDeviceToHost));
-      std::vector<int32_t> unique;
-      c->acc_row_host.assign((size_t)N, (uint16_t)kNoAccRow);
-      std::vector<int32_t> row_of_rep((size_t)N, -1);
-      for (int32_t n = 0; n < N; ++n) {
-        if (as_list[n]) continue;
-        if (!equal[n]) rep[n] = n;  // same digest, different row: kept by itself
-        if (rep[n] == n) {
-          row_of_rep[n] = (int32_t)unique.size();
-          unique.push_back(n);
-        }
-        c->acc_row_host[n] = (uint16_t)row_of_rep[rep[n]];  // rep[n] <= n: its row is known
-      }
-      if (unique.size() >= kNoAccRow) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: more than 65534 distinct accepted bitsets");
-      c->n_acc_rows = (int32_t)unique.size();
-      acc_rows = keep(slab_alloc<uint32_t>(unique.size() * (size_t)dv.W));
-      int32_t* d_unique = temp(dev_upload(unique));
-      launch_gather_rows(acc_id, dv.W, d_unique, c->n_acc_rows, acc_rows, stream);
-      d_acc_row = keep(slab_upload(c->acc_row_host));
-      c->device_bytes += (int64_t)unique.size() * dv.W * 4 + (int64_t)N * 2;
     }
+    int32_t* d_rep = arena.upload(rep, stream);
+    uint32_t* d_equal = arena.array<uint32_t>((size_t)N);
+    launch_rows_equal(acc_id, N, dv.W, d_rep, d_equal, stream);
 
     // ---- keys: level 1 = (node with context-dependent tokens, context of its rule), level 2 = (level-1
     // key, context of that context node's rule)
@@ -718,11 +772,9 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     auto n_ctx = [&](int32_t rule) { return (uint64_t)(ctx_off[rule + 1] - ctx_off[rule]); };
     c->k1_base_host.assign((size_t)N, kNoKey);
     std::vector<uint32_t> node_off((size_t)N + 1, 0);
-    std::vector<uint64_t> item_base((size_t)N + 1, 0);
     uint64_t n_k1 = 0, n_k2 = 0, n_base = 0, n_items = 0;
     for (int32_t n = 0; n < N; ++n) {
       node_off[n] = (uint32_t)n_base;
-      item_base[n] = n_items;
       const uint64_t m = n_ctx(A.node_rule[n]);
       if (c->unc_count[n] > 0 && m > 0) {
         c->k1_base_host[n] = (uint32_t)n_k1;
@@ -735,7 +787,6 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
         throw Failure(XGM_ERR_TOO_LARGE, "cache_build: context-dependent lists beyond the supported size");
     }
     node_off[N] = (uint32_t)n_base;
-    item_base[N] = n_items;
     // Level-2 lists are kept unless their keys alone would take hundreds of megabytes (grammars whose
     // rules are each used in hundreds of places); tokens that leave a second frame are then walked at run time.
     const bool level2 = n_k2 * (uint64_t)n_seg <= ((uint64_t)1 << 26);
@@ -755,40 +806,87 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     const uint64_t n_keys = (uint64_t)N + n_k1 + n_k2;
     const size_t n_slots = (size_t)(n_keys * (uint64_t)n_seg);
 
-    // ---- base lists: every node's context-dependent tokens, and where each of them leaves the node's frame
-    uint32_t* d_node_off = temp(dev_upload(node_off));
-    uint64_t* d_item_base = temp(dev_upload(item_base));
+    // ---- base lists (every node's context-dependent tokens), then the entries of every (key, segment): counted
     uint32_t* d_k1_base = keep(slab_upload(c->k1_base_host));
     uint32_t* d_k2_base = level2 ? keep(slab_upload(c->k2_base_host)) : nullptr;
     uint32_t* d_ctx_off = keep(slab_upload(ctx_off));
     uint16_t* d_ctx_node = keep(slab_upload(ctx_node));
-    uint32_t* d_base_ids = temp(dev_alloc<uint32_t>((size_t)n_base));
-    uint32_t* d_exits = temp(dev_alloc<uint32_t>((size_t)n_base));
+    uint32_t* d_base_ids = arena.array<uint32_t>((size_t)n_base);
+    uint16_t* d_base_node = arena.array<uint16_t>((size_t)n_base);
+    uint32_t* d_exits = arena.array<uint32_t>((size_t)n_base);
     {
       std::vector<uint32_t> identity((size_t)N);
       std::iota(identity.begin(), identity.end(), 0u);
-      uint32_t* d_identity = temp(dev_upload(identity));
-      uint32_t* d_cursor = temp(dev_upload(node_off));
-      launch_rows_to_lists(dv, N, unc_id, d_identity, 1, d_cursor, d_base_ids, stream);
-      launch_exit_positions(tab, dv, N, d_node_off, d_base_ids, (uint32_t)n_base, d_exits, stream);
+      uint32_t* d_identity = arena.upload(identity, stream);
+      uint32_t* d_cursor = arena.upload(node_off, stream);
+      launch_rows_to_lists(dv, N, unc_id, d_identity, 1, d_cursor, d_base_ids, d_base_node, stream);
     }
-    // ---- the entries of every (key, segment): counted, then written
-    uint32_t* d_counts = temp(dev_alloc<uint32_t>(n_slots));
+    uint32_t* d_counts = arena.array<uint32_t>(n_slots);
     HIP_OK(hipMemsetAsync(d_counts, 0, n_slots * 4, stream));
+    // the level-1 kernel's tiles: the pairs of a node in blocks, its rule's contexts in blocks
+    std::vector<uint4> tiles;
+    uint32_t max_ctx = 0;
+    {
+      const uint32_t tp = context_tile_pairs(), tc = context_tile_contexts();
+      for (int32_t n = 0; n < N; ++n) {
+        if (c->k1_base_host[n] == kNoKey) continue;
+        const uint32_t L = c->unc_count[n], m = (uint32_t)n_ctx(A.node_rule[n]);
+        for (uint32_t eb = 0; eb < L; eb += tp)
+          for (uint32_t ib = 0; ib < m; ib += tc)
+            tiles.push_back(make_uint4(node_off[n] + eb, std::min(tp, L - eb) | (std::min(tc, m - ib) << 16), ib, (uint32_t)n));
+      }
+      for (size_t r = 0; r < A.rule_names.size(); ++r) max_ctx = std::max<uint32_t>(max_ctx, (uint32_t)n_ctx((int32_t)r));
+    }
     ContextListArgs args{};
-    args.node_off = d_node_off;
+    args.base_node = d_base_node;
     args.base_ids = d_base_ids;
+    args.total = (uint32_t)n_base;
     args.exits = d_exits;
-    args.item_base = d_item_base;
+    args.tiles = arena.upload(tiles, stream);
+    args.n_tiles = (uint32_t)tiles.size();
+    args.res_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>(n_base, 1u << 16), 1u << 24);
+    args.res = arena.array<uint4>(args.res_cap);
+    args.res_count = arena.array<uint32_t>(1);
+    args.max_ctx = max_ctx;
     args.k1_base = d_k1_base;
     args.k2_base = d_k2_base;
     args.ctx_off = d_ctx_off;
     args.ctx_node = d_ctx_node;
+    args.n_nodes = N;
     args.n_k1 = (uint32_t)n_k1;
     args.counts = d_counts;
-    launch_context_lists(tab, dv, N, n_items, args, false, stream);
+    launch_exit_positions(tab, dv, args, stream);
+    launch_context_lists(tab, dv, args, false, stream);
     HIP_OK(hipGetLastError());
     HIP_OK(hipStreamSynchronize(stream));
+
+    // ---- the distinct bitset rows
+    uint32_t* acc_rows = nullptr;
+    uint16_t* d_acc_row = nullptr;
+    {
+      std::vector<uint32_t> equal((size_t)N);
+      HIP_OK(hipMemcpy(equal.data(), d_equal, equal.size() * 4, hipMemcpyDeviceToHost));
+      std::vector<int32_t> unique;
+      c->acc_row_host.assign((size_t)N, (uint16_t)kNoAccRow);
+      std::vector<int32_t> row_of_rep((size_t)N, -1);
+      for (int32_t n = 0; n < N; ++n) {
+        if (as_list[n]) continue;
+        if (!equal[n]) rep[n] = n;  // same digest, different row: kept by itself
+        if (rep[n] == n) {
+          row_of_rep[n] = (int32_t)unique.size();
+          unique.push_back(n);
+        }
+        c->acc_row_host[n] = (uint16_t)row_of_rep[rep[n]];  // rep[n] <= n: its row is known
+      }
+      if (unique.size() >= kNoAccRow) throw Failure(XGM_ERR_TOO_LARGE, "cache_build: more than 65534 distinct accepted bitsets");
+      c->n_acc_rows = (int32_t)unique.size();
+      acc_rows = keep(slab_alloc<uint32_t>(unique.size() * (size_t)dv.W));
+      int32_t* d_unique = arena.upload(unique, stream);
+      launch_gather_rows(acc_id, dv.W, d_unique, c->n_acc_rows, acc_rows, stream);
+      d_acc_row = keep(slab_upload(c->acc_row_host));
+      c->device_bytes += (int64_t)unique.size() * dv.W * 4 + (int64_t)N * 2;
+    }
+    // ---- offsets from the counts, then the entries
     std::vector<uint32_t> counts(n_slots);
     HIP_OK(hipMemcpy(counts.data(), d_counts, n_slots * 4, hipMemcpyDeviceToHost));
     uint64_t n_level0 = 0;
@@ -806,22 +904,21 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     uint32_t* d_key_off = keep(slab_upload(c->key_off_host));
     uint32_t* d_entries = keep(slab_alloc<uint32_t>((size_t)total));
     {
-      uint32_t* d_front = temp(dev_alloc<uint32_t>(n_slots));
-      uint32_t* d_back = temp(dev_alloc<uint32_t>(n_slots));
+      uint32_t* d_front = arena.array<uint32_t>(n_slots);
+      uint32_t* d_back = arena.array<uint32_t>(n_slots);
       HIP_OK(hipMemcpyAsync(d_front, d_key_off, n_slots * 4, hipMemcpyDeviceToDevice, stream));
       HIP_OK(hipMemcpyAsync(d_back, d_key_off + 1, n_slots * 4, hipMemcpyDeviceToDevice, stream));
       std::vector<uint32_t> list_key((size_t)N);
       for (int32_t n = 0; n < N; ++n) list_key[n] = as_list[n] ? (uint32_t)n : kNoKey;
-      uint32_t* d_list_key = temp(dev_upload(list_key));
-      launch_rows_to_lists(dv, N, acc_id, d_list_key, n_seg, d_front, d_entries, stream);
+      uint32_t* d_list_key = arena.upload(list_key, stream);
+      launch_rows_to_lists(dv, N, acc_id, d_list_key, n_seg, d_front, d_entries, nullptr, stream);
       args.front = d_front;
       args.back = d_back;
       args.entries = d_entries;
-      launch_context_lists(tab, dv, N, n_items, args, true, stream);
+      launch_context_lists(tab, dv, args, true, stream);
     }
     HIP_OK(hipGetLastError());
-    HIP_OK(hipStreamSynchronize(stream));
-    cleanup_temps();
+    cleanup_temps();  // (synchronises the stream)
 
     c->host.tab = staged_for(tab, kFillLdsBudget);
     c->host.acc = acc_rows;
@@ -1148,6 +1245,25 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     C.next_slot = (C.next_slot + 1) % Context::kSlots;
   }
   set_pending(ring ? ring->fill : C.static_fill, seq, B, d_bitmask, h_buf, ms);
+  return XGM_OK;
+  API_END
+}
+
+int xgm_debug_matcher_fill_work(const xgm_matcher* m, int64_t* h_out4) {
+  API_BEGIN
+  if (!m || !m->c || !h_out4) return fail(XGM_ERR_BAD_ARG, "matcher_fill_work: null argument or a matcher without a cache");
+  for (int k = 0; k < 4; ++k) h_out4[k] = 0;
+  if (m->terminated) return XGM_OK;
+  const int32_t n_seg = m->v->dv.n_seg;
+  std::vector<uint32_t> h(stack_hdr_stride(n_seg));
+  for (const Stack& s : m->stacks) {
+    pack_stack_header(m->g->A, *m->c, s, 0u, h.data());
+    if ((h[kStackHdrTop] >> 16) != kNoAccRow) ++h_out4[0];
+    for (uint32_t l = 0; l < kStackLists; ++l) {
+      const uint32_t* off = &h[kStackHdrWords + l * ((uint32_t)n_seg + 1u)];
+      h_out4[1 + l] += off[n_seg] - off[0];
+    }
+  }
   return XGM_OK;
   API_END
 }

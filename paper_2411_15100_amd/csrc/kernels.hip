@@ -318,7 +318,8 @@ __global__ __launch_bounds__(kRowThreads) void row_stats_kernel(DevVocab voc, co
 constexpr int kListThreads = kSegWords / 4;
 __global__ __launch_bounds__(kListThreads) void rows_to_lists_kernel(DevVocab voc, const uint32_t* __restrict__ rows,
                                                                      const uint32_t* __restrict__ cursor_of, int32_t per_row,
-                                                                     uint32_t* __restrict__ cursor, uint32_t* __restrict__ out) {
+                                                                     uint32_t* __restrict__ cursor, uint32_t* __restrict__ out,
+                                                                     uint16_t* __restrict__ out_row, int32_t row0) {
   const size_t r = blockIdx.y;
   const uint32_t key = cursor_of[r];
   if (key == kNoKey) return;
@@ -351,6 +352,7 @@ __global__ __launch_bounds__(kListThreads) void rows_to_lists_kernel(DevVocab vo
     while (x) {
       const uint32_t b = __ffs(x) - 1;
       x &= x - 1;
+      if (out_row) out_row[pos] = (uint16_t)(row0 + (int32_t)r);
       out[pos++] = (uint32_t)(w0 + k) * 32u + b;
     }
   }
@@ -374,125 +376,188 @@ __device__ __forceinline__ TokenRef load_token(const DevVocab& voc, int32_t id) 
   return t;
 }
 
-// Where a context-dependent token leaves its node's frame: one thread per entry of the base lists walks
-// the token once more from the node and notes the positions (tables staged as in the classify kernel).
+// ---- The level-1 and level-2 lists (section 3.2 per call site; see DevCache), from the base lists: the
+// context-dependent (node, token) pairs.  Three kernels, tables staged as in the classify kernel:
+//   exit_positions_kernel  one thread per pair: the token is walked once more from the node to find the
+//                          positions at which it leaves the node's frame;
+//   context_level1_kernel  one thread per (pair, a few contexts of the node's rule): the rest of the token is
+//                          walked from the context node with nothing known below.  Accepted there: an entry
+//                          of the (node, context) list.  Leaves that frame too: a record for the next kernel;
+//   context_level2_kernel  one thread per (record, a few contexts of the context node's rule): the same one
+//                          frame further down; what leaves a third frame becomes a walk entry.
+// Most (pair, context) combinations end at the first byte of the rest, which the context node cannot
+// take.  The last two kernels run twice: first they count the entries of every (key, segment), then, with
+// the offsets made from the counts, they write them.
 constexpr int kContextThreads = 768;
-__global__ __launch_bounds__(kContextThreads) void exit_positions_kernel(DevTables tab, DevVocab voc, int32_t n_nodes,
-                                                                         const uint32_t* __restrict__ node_off,
-                                                                         const uint32_t* __restrict__ base_ids, uint32_t total,
-                                                                         uint32_t* __restrict__ exits) {
+constexpr uint32_t kContextsPerThread = 8;
+
+__global__ __launch_bounds__(kContextThreads) void exit_positions_kernel(DevTables tab, DevVocab voc, ContextListArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   stage_tables(tab, smem, kContextThreads);
   __syncthreads();
   auto body = [&](const auto& T) {
     const uint32_t e = blockIdx.x * kContextThreads + threadIdx.x;
-    if (e >= total) return;
-    uint32_t lo = 0u, hi = (uint32_t)n_nodes;  // the last node whose list starts at or before e
-    while (hi - lo > 1u) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (node_off[mid] <= e) lo = mid; else hi = mid;
-    }
-    const uint32_t node = lo;
-    const TokenRef t = load_token(voc, (int32_t)base_ids[e]);
+    if (e >= a.total) return;
+    const uint32_t node = a.base_node[e];
+    const TokenRef t = load_token(voc, (int32_t)a.base_ids[e]);
     uint32_t x = 0u;
     const int res = walk_token<true>(T, t.tk, t.ext, t.len, node, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node), 0, &x);
-    exits[e] = res == kOverflow ? 0x80000000u : x;
+    a.exits[e] = res == kOverflow ? 0x80000000u : x;
   };
   if (small_sections_staged(tab)) body(LdsTabT<true>(tab, smem));
   else body(LdsTab(tab, smem));
 }
 
-// The level-1 and level-2 lists (section 3.2 per call site; see DevCache).  One thread per (base entry,
-// context i of the node's rule): the rest of the token after it has left the node's frame is walked from
-// context node i with nothing known below; if it leaves that frame too, from every context node of that
-// node's rule in turn.  The same kernel first counts the entries of every (key, segment) and then, with
-// the offsets made from the counts, writes them.
+// What the two list kernels share: the token of one pair, and how its entries reach the lists.
 template <bool WRITE, class Tab>
-__device__ __forceinline__ void context_lists_body(const Tab& T, const DevVocab& voc, int32_t n_nodes, uint64_t n_items,
-                                                   const ContextListArgs& a) {
-  const uint64_t item = (uint64_t)blockIdx.x * kContextThreads + threadIdx.x;
-  if (item >= n_items) return;
-  uint32_t lo = 0u, hi = (uint32_t)n_nodes;  // the last node whose items start at or before `item`
-  while (hi - lo > 1u) {
-    const uint32_t mid = (lo + hi) >> 1;
-    if (a.item_base[mid] <= item) lo = mid; else hi = mid;
-  }
-  const uint32_t node = lo;
-  const uint32_t local = (uint32_t)(item - a.item_base[node]);
-  const uint32_t n_list = a.node_off[node + 1] - a.node_off[node];
-  const uint32_t i = local / n_list, e = a.node_off[node] + local % n_list;
-  const uint32_t id = a.base_ids[e], ex0 = a.exits[e];
-  const TokenRef t = load_token(voc, (int32_t)id);
-  const uint32_t rule = T.header(node).y >> 16;
-  const uint32_t r1 = a.ctx_node[a.ctx_off[rule] + i];
-  const uint32_t key1_local = a.k1_base[node] + i;
-  const uint32_t slot_seg = id / (uint32_t)kSegTokens;
-  auto emit = [&](uint32_t key, uint32_t kind, uint32_t pos) {
-    const size_t slot = (size_t)key * voc.n_seg + slot_seg;
-    if (!WRITE) atomicAdd(&a.counts[slot], 1u);
-    else {
-      const uint32_t word = id | (pos << kEntryPosShift) | (kind << kEntryKindShift);
-      if (kind == kEntryAccepted) a.entries[atomicAdd(&a.front[slot], 1u)] = word;
-      else a.entries[atomicSub(&a.back[slot], 1u) - 1u] = word;
+struct ContextWork {
+  const Tab& T;
+  const DevVocab& voc;
+  const ContextListArgs& a;
+  uint32_t id;
+  TokenRef t;
+  // One entry for list `key`.  The lanes of a wave that get here together mostly add to the same list (they hold
+  // neighbouring tokens of one node and look at the same context): they are served by one atomic per
+  // distinct (list, segment, accepted or not) among them instead of one each - atomics on one address queue up.
+  __device__ __forceinline__ void emit(uint32_t key, uint32_t kind, uint32_t pos) const {
+    const uint32_t slot = key * (uint32_t)voc.n_seg + id / (uint32_t)kSegTokens;
+    const uint32_t tag = (slot << 1) | (kind == kEntryAccepted ? 0u : 1u);
+    const uint32_t lane = threadIdx.x & 63u;
+    for (bool pending = true; pending;) {
+      const uint32_t lead = __builtin_amdgcn_readfirstlane(tag);
+      const bool mine = tag == lead;
+      const unsigned long long peers = __ballot(mine);
+      if (mine) {
+        const uint32_t n = (uint32_t)__popcll(peers), rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+        const int first = __ffsll((long long)peers) - 1;
+        if (!WRITE) {
+          if (rank == 0u) atomicAdd(&a.counts[slot], n);
+        } else {
+          uint32_t base = 0u;
+          if (rank == 0u) base = kind == kEntryAccepted ? atomicAdd(&a.front[slot], n) : atomicSub(&a.back[slot], n) - n;
+          base = __shfl(base, first, 64);
+          a.entries[base + rank] = id | (pos << kEntryPosShift) | (kind << kEntryKindShift);
+        }
+        pending = false;
+      }
     }
-  };
-  // can the suffix from position k on do anything at all at node r?  (consumed there, or r may end its
-  // rule in front of a byte that can follow the rule)
-  auto plausible = [&](uint32_t r, uint32_t k) {
+  }
+  // can the rest of the token from position k on do anything at all at node r?  (its first byte is
+  // consumed there, or r may end its rule in front of a byte that can follow the rule)
+  __device__ __forceinline__ bool plausible(uint32_t r, uint32_t k) const {
     const uint32_t c = token_byte(t.tk, t.ext, (int)k);
     if (T.can_start(r, c)) return true;
     const uint2 h = T.header(r);
     return (h.y & 1u) && T.can_follow(h, c);
-  };
-  const uint32_t key1 = (uint32_t)n_nodes + key1_local;
-  if (ex0 & 0x80000000u) { emit(key1, kEntryWalkTop, 0u); return; }
-  bool accepted = false, over = false;
-  uint32_t ex1 = 0u, from1 = 0u, n_res = 0u;
-  for (uint32_t m = ex0; m != 0u && !accepted; m &= m - 1u) {
-    const uint32_t k = __ffs(m) - 1u;
-    if (!plausible(r1, k)) continue;
-    uint32_t x = 0u;
-    const int res = walk_token<true>(T, t.tk, t.ext, t.len, r1, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r1), (int)k, &x);
-    if (res == kAccept) accepted = true;
-    else if (res == kOverflow) over = true;
-    else if (res == kUncertain) { ex1 |= x; if (n_res++ == 0u) from1 = k; }
   }
-  if (accepted) { emit(key1, kEntryAccepted, 0u); return; }
-  if (over) { emit(key1, kEntryWalkTop, 0u); return; }
-  if (ex1 == 0u) return;  // rejected in this context
+  // Level 2 for contexts [j0, j1) of rule1: the token has left the frame of a context node of that rule
+  // at the positions ex1.  key2 = the first level-2 key of its level-1 key.
+  __device__ __forceinline__ void level2(uint32_t rule1, uint32_t j0, uint32_t j1, uint32_t key2, uint32_t ex1, bool single1) const {
+    const uint32_t c2 = a.ctx_off[rule1];
+    for (uint32_t j = j0; j < j1; ++j) {
+      const uint32_t r2 = a.ctx_node[c2 + j];
+      bool acc2 = false, walk2 = false;
+      for (uint32_t m = ex1; m != 0u && !acc2; m &= m - 1u) {
+        const uint32_t k = __ffs(m) - 1u;
+        if (!plausible(r2, k)) continue;
+        const int res = walk_token<true>(T, t.tk, t.ext, t.len, r2, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r2), (int)k);
+        if (res == kAccept) acc2 = true;
+        else if (res == kOverflow || res == kUncertain) walk2 = true;
+      }
+      if (acc2) emit(key2 + j, kEntryAccepted, 0u);
+      else if (walk2) {
+        if (single1) emit(key2 + j, kEntryWalkBelow2, __ffs(ex1) - 1u); else emit(key2 + j, kEntryWalkTop, 0u);
+      }
+    }
+  }
+};
+
+// One workgroup per tile (see ContextListArgs::tiles): up to kContextThreads pairs of one node, up to
+// kContextsPerThread contexts of its rule.
+template <bool WRITE, class Tab>
+__device__ __forceinline__ void context_level1_body(const Tab& T, const DevVocab& voc, const ContextListArgs& a, const uint4 tile) {
+  if (threadIdx.x >= (tile.y & 0xFFFFu)) return;
+  const uint32_t e = tile.x + threadIdx.x, node = tile.w, i0 = tile.z, i1 = tile.z + (tile.y >> 16);
+  const uint32_t id = a.base_ids[e], ex0 = a.exits[e];
+  const ContextWork<WRITE, Tab> w{T, voc, a, id, load_token(voc, (int32_t)id)};
+  const uint32_t rule = T.header(node).y >> 16;
+  const uint32_t cb = a.ctx_off[rule];
+  const uint32_t k1b = a.k1_base[node];
   const bool single0 = (ex0 & (ex0 - 1u)) == 0u;
-  if (a.k2_base == nullptr || (ex1 & 0x80000000u)) {
-    if (single0) emit(key1, kEntryWalkBelow1, from1); else emit(key1, kEntryWalkTop, 0u);
-    return;
-  }
-  const uint32_t rule1 = T.header(r1).y >> 16;
-  const uint32_t c0 = a.ctx_off[rule1], m2 = a.ctx_off[rule1 + 1] - c0;
-  const uint32_t key2 = (uint32_t)n_nodes + a.n_k1 + a.k2_base[key1_local];
-  const bool single1 = single0 && n_res == 1u && (ex1 & (ex1 - 1u)) == 0u;
-  for (uint32_t j = 0; j < m2; ++j) {
-    const uint32_t r2 = a.ctx_node[c0 + j];
-    bool acc2 = false, walk2 = false;
-    for (uint32_t m = ex1; m != 0u && !acc2; m &= m - 1u) {
+  const uint32_t lane = threadIdx.x & 63u;
+  for (uint32_t i = i0; i < i1; ++i) {
+    const uint32_t r1 = a.ctx_node[cb + i];
+    const uint32_t key1_local = k1b + i, key1 = (uint32_t)a.n_nodes + key1_local;
+    if (ex0 & 0x80000000u) { w.emit(key1, kEntryWalkTop, 0u); continue; }
+    bool accepted = false, over = false;
+    uint32_t ex1 = 0u, from1 = 0u, n_res = 0u;
+    for (uint32_t m = ex0; m != 0u && !accepted; m &= m - 1u) {
       const uint32_t k = __ffs(m) - 1u;
-      if (!plausible(r2, k)) continue;
-      const int res = walk_token<true>(T, t.tk, t.ext, t.len, r2, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r2), (int)k);
-      if (res == kAccept) acc2 = true;
-      else if (res == kOverflow || res == kUncertain) walk2 = true;
+      if (!w.plausible(r1, k)) continue;
+      uint32_t x = 0u;
+      const int res = walk_token<true>(T, w.t.tk, w.t.ext, w.t.len, r1, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r1), (int)k, &x);
+      if (res == kAccept) accepted = true;
+      else if (res == kOverflow) over = true;
+      else if (res == kUncertain) { ex1 |= x; if (n_res++ == 0u) from1 = k; }
     }
-    if (acc2) emit(key2 + j, kEntryAccepted, 0u);
-    else if (walk2) {
-      if (single1) emit(key2 + j, kEntryWalkBelow2, __ffs(ex1) - 1u); else emit(key2 + j, kEntryWalkTop, 0u);
+    if (accepted) { w.emit(key1, kEntryAccepted, 0u); continue; }
+    if (over) { w.emit(key1, kEntryWalkTop, 0u); continue; }
+    if (ex1 == 0u) continue;  // rejected in this context
+    if (a.k2_base == nullptr || (ex1 & 0x80000000u)) {
+      if (single0) w.emit(key1, kEntryWalkBelow1, from1); else w.emit(key1, kEntryWalkTop, 0u);
+      continue;
     }
+    // it leaves the context's frame as well: a record for the level-2 kernel (or, if the record buffer is
+    // full, the same work right here)
+    const uint32_t rule1 = T.header(r1).y >> 16;
+    const bool single1 = single0 && n_res == 1u && (ex1 & (ex1 - 1u)) == 0u;
+    const unsigned long long peers = __ballot(true);
+    const uint32_t n = (uint32_t)__popcll(peers), rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+    const int first = __ffsll((long long)peers) - 1;
+    uint32_t base = 0u;
+    if (rank == 0u) base = atomicAdd(a.res_count, n);
+    base = __shfl(base, first, 64);
+    if (base + rank < a.res_cap) a.res[base + rank] = make_uint4(e, key1_local, ex1, rule1 | (single1 ? 0x10000u : 0u));
+    else w.level2(rule1, 0u, a.ctx_off[rule1 + 1] - a.ctx_off[rule1], (uint32_t)a.n_nodes + a.n_k1 + a.k2_base[key1_local], ex1, single1);
   }
 }
 template <bool WRITE>
-__global__ __launch_bounds__(kContextThreads) void context_lists_kernel(DevTables tab, DevVocab voc, int32_t n_nodes,
-                                                                        uint64_t n_items, ContextListArgs a) {
+__global__ __launch_bounds__(kContextThreads) void context_level1_kernel(DevTables tab, DevVocab voc, ContextListArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
+  const uint4 tile = a.tiles[blockIdx.x];
   stage_tables(tab, smem, kContextThreads);
   __syncthreads();
-  if (small_sections_staged(tab)) context_lists_body<WRITE>(LdsTabT<true>(tab, smem), voc, n_nodes, n_items, a);
-  else context_lists_body<WRITE>(LdsTab(tab, smem), voc, n_nodes, n_items, a);
+  if (small_sections_staged(tab)) context_level1_body<WRITE>(LdsTabT<true>(tab, smem), voc, a, tile);
+  else context_level1_body<WRITE>(LdsTab(tab, smem), voc, a, tile);
+}
+
+// A fixed grid walks over (record, chunk of kContextsPerThread contexts): consecutive threads hold
+// consecutive records (neighbouring tokens of one node and context, as a rule) and the same chunk.
+template <bool WRITE, class Tab>
+__device__ __forceinline__ void context_level2_body(const Tab& T, const DevVocab& voc, const ContextListArgs& a) {
+  const uint32_t n_res = min(*a.res_count, a.res_cap);
+  const uint32_t n_chunks = (a.max_ctx + kContextsPerThread - 1u) / kContextsPerThread;
+  const uint64_t n_items = (uint64_t)n_res * n_chunks;
+  for (uint64_t item = (uint64_t)blockIdx.x * kContextThreads + threadIdx.x; item < n_items; item += (uint64_t)gridDim.x * kContextThreads) {
+    const uint32_t r = (uint32_t)(item % n_res), jc = (uint32_t)(item / n_res);
+    const uint4 rec = a.res[r];
+    const uint32_t rule1 = rec.w & 0xFFFFu;
+    const uint32_t m2 = a.ctx_off[rule1 + 1] - a.ctx_off[rule1];
+    const uint32_t j0 = jc * kContextsPerThread;
+    if (j0 >= m2) continue;
+    const uint32_t id = a.base_ids[rec.x];
+    const ContextWork<WRITE, Tab> w{T, voc, a, id, load_token(voc, (int32_t)id)};
+    w.level2(rule1, j0, min(j0 + kContextsPerThread, m2), (uint32_t)a.n_nodes + a.n_k1 + a.k2_base[rec.y], rec.z, (rec.w & 0x10000u) != 0u);
+  }
+}
+template <bool WRITE>
+__global__ __launch_bounds__(kContextThreads) void context_level2_kernel(DevTables tab, DevVocab voc, ContextListArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  if (*a.res_count == 0u) return;
+  stage_tables(tab, smem, kContextThreads);
+  __syncthreads();
+  if (small_sections_staged(tab)) context_level2_body<WRITE>(LdsTabT<true>(tab, smem), voc, a);
+  else context_level2_body<WRITE>(LdsTab(tab, smem), voc, a);
 }
 
 __global__ __launch_bounds__(kRowThreads) void rows_equal_kernel(const uint32_t* __restrict__ rows, int32_t W,
@@ -1236,32 +1301,36 @@ void launch_gather_rows(const uint32_t* rows, int32_t W, const int32_t* unique, 
 }
 
 void launch_rows_to_lists(const DevVocab& voc, int32_t n, const uint32_t* rows, const uint32_t* cursor_of, int32_t per_row,
-                          uint32_t* cursor, uint32_t* out, hipStream_t stream) {
+                          uint32_t* cursor, uint32_t* out, uint16_t* out_row, hipStream_t stream) {
   for (int32_t r0 = 0; r0 < n; r0 += 32768) {  // grid.y limit
     const int32_t nb = std::min(32768, n - r0);
     hipLaunchKernelGGL(rows_to_lists_kernel, dim3(voc.n_seg, nb), dim3(kListThreads), 0, stream, voc,
-                       rows + (size_t)r0 * voc.W, cursor_of + r0, per_row, cursor, out);
+                       rows + (size_t)r0 * voc.W, cursor_of + r0, per_row, cursor, out, out_row, r0);
   }
 }
 
-void launch_exit_positions(const DevTables& tab, const DevVocab& voc, int32_t n_nodes, const uint32_t* node_off,
-                           const uint32_t* base_ids, uint32_t total, uint32_t* exits, hipStream_t stream) {
-  if (total == 0) return;
+void launch_exit_positions(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, hipStream_t stream) {
+  if (args.total == 0) return;
   const DevTables st = staged_for(tab, kClassifyLdsBudget);
-  hipLaunchKernelGGL(exit_positions_kernel, dim3((total + kContextThreads - 1) / kContextThreads), dim3(kContextThreads),
-                     st.stage_bytes, stream, st, voc, n_nodes, node_off, base_ids, total, exits);
+  hipLaunchKernelGGL(exit_positions_kernel, dim3((args.total + kContextThreads - 1) / kContextThreads), dim3(kContextThreads),
+                     st.stage_bytes, stream, st, voc, args);
 }
 
-void launch_context_lists(const DevTables& tab, const DevVocab& voc, int32_t n_nodes, uint64_t n_items,
-                          const ContextListArgs& args, bool write, hipStream_t stream) {
-  if (n_items == 0) return;
+void launch_context_lists(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, bool write, hipStream_t stream) {
+  if (args.total == 0 || args.n_tiles == 0) return;
   const DevTables st = staged_for(tab, kClassifyLdsBudget);
-  const dim3 grid((uint32_t)((n_items + kContextThreads - 1) / kContextThreads));
-  if (write)
-    hipLaunchKernelGGL(context_lists_kernel<true>, grid, dim3(kContextThreads), st.stage_bytes, stream, st, voc, n_nodes, n_items, args);
-  else
-    hipLaunchKernelGGL(context_lists_kernel<false>, grid, dim3(kContextThreads), st.stage_bytes, stream, st, voc, n_nodes, n_items, args);
+  (void)hipMemsetAsync(args.res_count, 0, 4, stream);
+  const dim3 g1(args.n_tiles), g2(1024);
+  if (write) {
+    hipLaunchKernelGGL(context_level1_kernel<true>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+    if (args.k2_base) hipLaunchKernelGGL(context_level2_kernel<true>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+  } else {
+    hipLaunchKernelGGL(context_level1_kernel<false>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+    if (args.k2_base) hipLaunchKernelGGL(context_level2_kernel<false>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+  }
 }
+uint32_t context_tile_pairs() { return (uint32_t)kContextThreads; }
+uint32_t context_tile_contexts() { return kContextsPerThread; }
 
 void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items, uint32_t* acc_rank,
                           uint32_t* unc_rank, uint32_t* plain_rank, hipStream_t stream) {

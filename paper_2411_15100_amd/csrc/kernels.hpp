@@ -221,36 +221,48 @@ void launch_gather_rows(const uint32_t* rows, int32_t W, const int32_t* unique, 
 // The set bits of n bitset rows as token ids, appended through cursors (any order within a cursor's list):
 // the tokens of row r and segment s go to out[cursor[cursor_of[r] * per_row + (per_row > 1 ? s : 0)]++];
 // rows with cursor_of[r] == kNoKey are skipped.  per_row = n_seg: one list per (row, segment); 1: one per row.
+// out_row (may be null) receives the row number beside every id.
 void launch_rows_to_lists(const DevVocab& voc, int32_t n, const uint32_t* rows, const uint32_t* cursor_of, int32_t per_row,
-                          uint32_t* cursor, uint32_t* out, hipStream_t stream);
-// For every context-dependent (node, token) pair of the base lists (base_ids[node_off[n] .. node_off[n+1])
-// are node n's tokens): the positions at which the token can leave the node's frame, as a bit set
+                          uint32_t* cursor, uint32_t* out, uint16_t* out_row, hipStream_t stream);
+// The level-1 and level-2 lists of a cache (see DevCache) from the base lists: the context-dependent
+// (node, token) pairs, base_node[e] / base_ids[e] for e < total, the pairs of one node side by side.
+// launch_exit_positions: exits[e] = the positions at which the token leaves the node's frame, as a bit set
 // (bit 31: some position beyond 30, or the walk hit a limit).
-void launch_exit_positions(const DevTables& tab, const DevVocab& voc, int32_t n_nodes, const uint32_t* node_off,
-                           const uint32_t* base_ids, uint32_t total, uint32_t* exits, hipStream_t stream);
-// The level-1 and level-2 lists of a cache (see DevCache).  One thread per (base entry, context of the
-// node's rule); item_base[n] = number of such items of the nodes before n.  write = false: counts[key *
-// n_seg + seg] += the entries each list will hold, accepted and walk entries separately (counts and
-// walk_counts); write = true: the entries are written, accepted ones upwards from front[slot], walk
-// entries downwards from back[slot] (both arrays are advanced).  k2_base == null: no level-2 lists;
-// tokens that leave a second frame become walk entries of level 1.
+// launch_context_lists, write = false: counts[key * n_seg + seg] += the entries each list will hold;
+// write = true: the entries are written, accepted ones upwards from front[slot], walk entries downwards from
+// back[slot] (both arrays are advanced).  k2_base == null: no level-2 lists; tokens that leave a second
+// frame become walk entries of level 1.
+// tiles: the work of the level-1 kernel, one workgroup each: x = first pair, y = pairs (at most
+// context_tile_pairs(), all of one node) | contexts << 16 (at most context_tile_contexts()), z = first
+// context, w = the node.  res / res_cap / res_count: records of the pairs that leave a second frame, for the
+// level-2 kernel (what does not fit is worked off by the level-1 kernel itself).  max_ctx: the most
+// contexts any rule has.
 struct ContextListArgs {
-  const uint32_t* node_off;    // [n_nodes + 1]
+  const uint16_t* base_node;
   const uint32_t* base_ids;
-  const uint32_t* exits;
-  const uint64_t* item_base;   // [n_nodes + 1]
+  uint32_t total;
+  uint32_t* exits;             // [total]
+  const uint4* tiles;
+  uint32_t n_tiles;
+  uint4* res;
+  uint32_t res_cap;
+  uint32_t* res_count;
+  uint32_t max_ctx;
   const uint32_t* k1_base;     // [n_nodes]
   const uint32_t* k2_base;     // [n_k1] or null
   const uint32_t* ctx_off;
   const uint16_t* ctx_node;
+  int32_t n_nodes;
   uint32_t n_k1;
   uint32_t* counts;            // [n_keys * n_seg]   write = false
   uint32_t* front;             // [n_keys * n_seg]   write = true
   uint32_t* back;              // [n_keys * n_seg]   write = true
   uint32_t* entries;
 };
-void launch_context_lists(const DevTables& tab, const DevVocab& voc, int32_t n_nodes, uint64_t n_items,
-                          const ContextListArgs& args, bool write, hipStream_t stream);
+void launch_exit_positions(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, hipStream_t stream);
+void launch_context_lists(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, bool write, hipStream_t stream);
+uint32_t context_tile_pairs();
+uint32_t context_tile_contexts();
 // set / clear single bits of rank-space rows: items = (node - node0, rank, class)
 void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items,
                           uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank, hipStream_t stream);

@@ -236,3 +236,72 @@ class ServingWorkload:
         gen.manual_seed(1)
         for t in self.logits:
             t.copy_(torch.randn(t.shape, generator=gen, device="cuda", dtype=torch.float32))
+
+    def replay_tokens(self, k: int) -> np.ndarray:
+        """The tokens that lead every row from its start state to its state in set k: int32 [steps, B],
+        -1 where a row has arrived (its walk was shorter).  Accepting row after row of this array on a
+        batch of fresh matchers replays the walk of state set k."""
+        hist = self.sets[k].history
+        steps = max(len(h) for h in hist)
+        out = np.full((steps, self.B), -1, dtype=np.int32)
+        for b, h in enumerate(hist):
+            out[: len(h), b] = h
+        return out
+
+
+class WalkedWorkload:
+    """A smaller decode workload: B rows over the given caches, a pool of state sets taken at equal
+    distances along one seeded random valid-token walk (rows that terminate start again), each kept as host
+    matchers and resident on the device; rotating logits buffers of the given dtype."""
+
+    def __init__(self, caches, vocab: si.Vocab, seed: int, total_steps: int, pool: int = 8, dtype=torch.float32,
+                 sigma: float = 1.0, n_logit_buffers: int = 4, structural_bias: float = 0.35):
+        self.vocab, self.B, self.V = vocab, len(caches), vocab.size
+        self.W = xgm.bitmask_words(self.V)
+        self.caches = list(caches)
+        walker = BatchWalker(self.caches, vocab, seed=seed, structural_bias=structural_bias)
+        every = max(1, total_steps // pool)
+        self.sets, self.device_sets, self.histories = [], [], []
+        for step in range(1, total_steps + 1):
+            walker.step()
+            if step % every == 0 and len(self.sets) < pool:
+                ms = []
+                for b, c in enumerate(self.caches):
+                    m = xgm.Matcher(cache=c)
+                    for t in walker.history[b]:
+                        m.accept_token(int(t))
+                    ms.append(m)
+                self.sets.append(xgm.MatcherBatch(ms))
+                self.device_sets.append(xgm.DeviceBatch(ms, history=0, stream=current_stream()))
+                self.histories.append([list(h) for h in walker.history])
+        self.d_mask = torch.zeros((self.B, self.W), dtype=torch.int32, device="cuda")
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(0)
+        self.dtype = dtype
+        self.dtype_code = {torch.float32: xgm.DTYPE_F32, torch.bfloat16: xgm.DTYPE_BF16, torch.float16: xgm.DTYPE_F16}[dtype]
+        self.logits = [(torch.randn((self.B, self.V), generator=gen, device="cuda", dtype=torch.float32) * sigma).to(dtype)
+                       for _ in range(n_logit_buffers)]
+
+    def refresh_logits(self):
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(1)
+        for t in self.logits:
+            t.copy_(torch.randn(t.shape, generator=gen, device="cuda", dtype=torch.float32))
+
+    def fill_device(self, k: int, stream: int):
+        self.device_sets[k % len(self.device_sets)].fill_next_token_bitmask(self.d_mask.data_ptr(), stream)
+
+    def apply(self, k: int, stream: int):
+        t = self.logits[k % len(self.logits)]
+        xgm.apply_token_bitmask_inplace(t.data_ptr(), self.dtype_code, self.B, self.V, t.stride(0), self.d_mask.data_ptr(),
+                                        self.V, stream=stream)
+
+    def fused_step_device(self, k: int, stream: int):
+        t = self.logits[k % len(self.logits)]
+        self.device_sets[k % len(self.device_sets)].fill_and_apply(self.d_mask.data_ptr(), t.data_ptr(), self.dtype_code, self.V,
+                                                                    t.stride(0), stream=stream)
+
+    def fused_step(self, k: int, stream: int):
+        t = self.logits[k % len(self.logits)]
+        xgm.fill_and_apply(self.sets[k % len(self.sets)], self.d_mask.data_ptr(), t.data_ptr(), self.dtype_code, self.V,
+                           t.stride(0), stream=stream)
