@@ -167,11 +167,12 @@ int xgm_schema_to_grammar(const char* schema_json, size_t len, char* h_text, siz
  *    every context r of n's rule there is a list of the tokens whose rest,
  *    after leaving n's frame, is consumed from r without leaving r's frame;
  *    for the tokens that leave r's frame as well, one more list per context
- *    of r's rule.  Tokens that leave a third frame, and tokens whose walk at
- *    build time exceeded a limit, are listed as entries to be walked against
- *    the live stack at fill time.  Lists are cut at every 32768 token ids.
+ *    of r's rule, and once more below that (three frames deep).  Tokens that
+ *    leave a fourth frame, and tokens whose walk at build time exceeded a
+ *    limit, are listed as entries to be walked against the live stack at
+ *    fill time.  Lists are cut at every 8192 token ids.
  * The fill call therefore ORs one bitset or list per stack, sets the bits of
- * two short lists, and walks only the rare remainder.
+ * three short lists, and walks only the rare remainder.
  * Synchronous: returns after the build has finished on hip_stream. */
 int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out);
 enum { XGM_CACHE_KEEP_PLAIN = 1 };
@@ -210,7 +211,7 @@ double xgm_cache_build_seconds(const xgm_cache* c);
 int32_t xgm_cache_num_accept_rows(const xgm_cache* c);
 int64_t xgm_cache_device_bytes(const xgm_cache* c);
 /* Sizes of the cache, into h_out8 (host, 8 values): [0] list keys in all, [1] keys of the first kind
- * (node, context), [2] of the second kind (node, context, context of that context's rule), [3] list entries
+ * (node, context), [2] of the deeper kinds (node, context, context of that context's rule, ...), [3] list entries
  * in all, [4] of them accepted tokens of nodes that keep a list, [5] context-dependent (node, token) pairs
  * the lists were made from, [6] (pair, context) combinations examined at build time, [7] bitset rows. */
 int xgm_cache_stats(const xgm_cache* c, int64_t* h_out8);
@@ -315,8 +316,8 @@ int xgm_fill_next_token_bitmask_static(xgm_matcher* const* ms, int32_t B, int32_
 /* What a fill has to read for this matcher's state, into h_out4 (host, 4
  * values): [0] stacks whose top node keeps its accepted tokens as a bitset row,
  * [1] entries of the stacks' lists of accepted tokens (top nodes that keep a
- * list), [2] of their (node, context) lists, [3] of their (node, context,
- * context) lists.  For the byte counts of benchmarks; needs a mask cache. */
+ * list), [2] of their (node, context) lists, [3] of their deeper per-context
+ * lists.  For the byte counts of benchmarks; needs a mask cache. */
 int xgm_debug_matcher_fill_work(const xgm_matcher* m, int64_t* h_out4);
 /* Instrumentation for benchmarks: the same fill (same result in d_bitmask)
  * with a kernel instantiation that also counts the automaton steps of all

@@ -203,8 +203,8 @@ struct xgm_cache {
   // host copies of what packing a stack header needs (see DevCache)
   std::vector<uint16_t> acc_row_host;  // [n_nodes]
   std::vector<uint32_t> key_off_host;  // [n_keys * n_seg + 1]
-  std::vector<uint32_t> k1_base_host;  // [n_nodes], kNoKey for a node without context-dependent tokens
-  std::vector<uint32_t> k2_base_host;  // [n_k1] (empty: no level-2 lists)
+  std::vector<uint32_t> k_base_host[kCtxLevels];  // [n_nodes] (kNoKey for a node without context-dependent tokens), [n_k[0]], ...
+  int levels = 0;                      // levels of per-context lists kept (<= kCtxLevels)
   std::vector<uint32_t> unc_count;     // [n_nodes] context-dependent tokens
   int32_t n_acc_rows = 0;
   int64_t device_bytes = 0;            // device memory the cache holds
@@ -770,45 +770,51 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     }
     if (ctx_node.empty()) ctx_node.push_back(0);
     auto n_ctx = [&](int32_t rule) { return (uint64_t)(ctx_off[rule + 1] - ctx_off[rule]); };
-    c->k1_base_host.assign((size_t)N, kNoKey);
+    // Level l + 1 has a key for every (key of level l, context of the rule of that key's context node).  A level is
+    // kept unless its keys alone would take hundreds of megabytes (grammars whose rules are each used in
+    // hundreds of places); tokens that would need it are then walked at run time.
     std::vector<uint32_t> node_off((size_t)N + 1, 0);
-    uint64_t n_k1 = 0, n_k2 = 0, n_base = 0, n_items = 0;
+    uint64_t n_base = 0, n_items = 0;
+    std::vector<uint16_t> key_node;  // the context node of every key of the current level
+    c->k_base_host[0].assign((size_t)N, kNoKey);
     for (int32_t n = 0; n < N; ++n) {
       node_off[n] = (uint32_t)n_base;
       const uint64_t m = n_ctx(A.node_rule[n]);
       if (c->unc_count[n] > 0 && m > 0) {
-        c->k1_base_host[n] = (uint32_t)n_k1;
-        n_k1 += m;
-        for (int32_t r1 : A.contexts[A.node_rule[n]]) n_k2 += n_ctx(A.node_rule[r1]);
+        c->k_base_host[0][n] = (uint32_t)key_node.size();
+        for (int32_t r1 : A.contexts[A.node_rule[n]]) key_node.push_back((uint16_t)r1);
         n_items += (uint64_t)c->unc_count[n] * m;
       }
       n_base += c->unc_count[n];
-      if (n_base >= ((uint64_t)1 << 32) || n_k1 >= ((uint64_t)1 << 28))
+      if (n_base >= ((uint64_t)1 << 32) || key_node.size() >= ((size_t)1 << 28))
         throw Failure(XGM_ERR_TOO_LARGE, "cache_build: context-dependent lists beyond the supported size");
     }
     node_off[N] = (uint32_t)n_base;
-    // Level-2 lists are kept unless their keys alone would take hundreds of megabytes (grammars whose
-    // rules are each used in hundreds of places); tokens that leave a second frame are then walked at run time.
-    const bool level2 = n_k2 * (uint64_t)n_seg <= ((uint64_t)1 << 26);
-    if (!level2) n_k2 = 0;
-    if (level2) {
-      c->k2_base_host.assign((size_t)n_k1, 0u);
-      uint64_t run = 0;
-      for (int32_t n = 0; n < N; ++n) {
-        if (c->k1_base_host[n] == kNoKey) continue;
-        uint32_t k1 = c->k1_base_host[n];
-        for (int32_t r1 : A.contexts[A.node_rule[n]]) {
-          c->k2_base_host[k1++] = (uint32_t)run;
-          run += n_ctx(A.node_rule[r1]);
-        }
+    uint64_t n_k[kCtxLevels] = {};
+    n_k[0] = key_node.size();
+    c->levels = 1;
+    for (int l = 1; l < kCtxLevels; ++l) {
+      uint64_t next = 0;
+      for (uint16_t r : key_node) next += n_ctx(A.node_rule[r]);
+      if (next * (uint64_t)n_seg > ((uint64_t)1 << 26)) break;
+      std::vector<uint16_t> next_node;
+      next_node.reserve((size_t)next);
+      c->k_base_host[l].resize(key_node.size());
+      for (size_t q = 0; q < key_node.size(); ++q) {
+        c->k_base_host[l][q] = (uint32_t)next_node.size();
+        for (int32_t r2 : A.contexts[A.node_rule[key_node[q]]]) next_node.push_back((uint16_t)r2);
       }
+      key_node.swap(next_node);
+      n_k[l] = key_node.size();
+      c->levels = l + 1;
     }
-    const uint64_t n_keys = (uint64_t)N + n_k1 + n_k2;
+    uint64_t n_keys = (uint64_t)N;
+    for (int l = 0; l < c->levels; ++l) n_keys += n_k[l];
     const size_t n_slots = (size_t)(n_keys * (uint64_t)n_seg);
 
     // ---- base lists (every node's context-dependent tokens), then the entries of every (key, segment): counted
-    uint32_t* d_k1_base = keep(slab_upload(c->k1_base_host));
-    uint32_t* d_k2_base = level2 ? keep(slab_upload(c->k2_base_host)) : nullptr;
+    const uint32_t* d_k_base[kCtxLevels] = {};
+    for (int l = 0; l < c->levels; ++l) d_k_base[l] = keep(slab_upload(c->k_base_host[l]));
     uint32_t* d_ctx_off = keep(slab_upload(ctx_off));
     uint16_t* d_ctx_node = keep(slab_upload(ctx_node));
     uint32_t* d_base_ids = arena.array<uint32_t>((size_t)n_base);
@@ -829,7 +835,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     {
       const uint32_t tp = context_tile_pairs(), tc = context_tile_contexts();
       for (int32_t n = 0; n < N; ++n) {
-        if (c->k1_base_host[n] == kNoKey) continue;
+        if (c->k_base_host[0][n] == kNoKey) continue;
         const uint32_t L = c->unc_count[n], m = (uint32_t)n_ctx(A.node_rule[n]);
         for (uint32_t eb = 0; eb < L; eb += tp)
           for (uint32_t ib = 0; ib < m; ib += tc)
@@ -844,21 +850,37 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     args.exits = d_exits;
     args.tiles = arena.upload(tiles, stream);
     args.n_tiles = (uint32_t)tiles.size();
-    args.res_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>(n_base, 1u << 16), 1u << 24);
-    args.res = arena.array<uint4>(args.res_cap);
-    args.res_count = arena.array<uint32_t>(1);
+    args.res_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>(n_base / 2, 1u << 16), 1u << 24);
+    for (int l = 0; l + 1 < c->levels; ++l) args.res[l] = arena.array<uint4>(args.res_cap);
+    args.res_count = arena.array<uint32_t>(kCtxLevels);
     args.max_ctx = max_ctx;
-    args.k1_base = d_k1_base;
-    args.k2_base = d_k2_base;
+    {
+      uint32_t key0 = (uint32_t)N;
+      for (int l = 0; l < kCtxLevels; ++l) {
+        args.k_base[l] = l < c->levels ? d_k_base[l] : nullptr;
+        args.key0[l] = key0;
+        key0 += (uint32_t)n_k[l];
+      }
+    }
     args.ctx_off = d_ctx_off;
     args.ctx_node = d_ctx_node;
-    args.n_nodes = N;
-    args.n_k1 = (uint32_t)n_k1;
     args.counts = d_counts;
     launch_exit_positions(tab, dv, args, stream);
     launch_context_lists(tab, dv, args, false, stream);
     HIP_OK(hipGetLastError());
     HIP_OK(hipStreamSynchronize(stream));
+    for (;;) {  // records that did not fit were dropped: count again with room for all of them (rare)
+      uint32_t made[kCtxLevels] = {};
+      HIP_OK(hipMemcpy(made, args.res_count, sizeof(made), hipMemcpyDeviceToHost));
+      const uint32_t most = *std::max_element(made, made + kCtxLevels);
+      if (most <= args.res_cap) break;
+      args.res_cap = most;
+      for (int l = 0; l + 1 < c->levels; ++l) args.res[l] = arena.array<uint4>(args.res_cap);
+      HIP_OK(hipMemsetAsync(d_counts, 0, n_slots * 4, stream));
+      launch_context_lists(tab, dv, args, false, stream);
+      HIP_OK(hipGetLastError());
+      HIP_OK(hipStreamSynchronize(stream));
+    }
 
     // ---- the distinct bitset rows
     uint32_t* acc_rows = nullptr;
@@ -925,19 +947,19 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     c->host.acc_row = d_acc_row;
     c->host.key_off = d_key_off;
     c->host.entries = d_entries;
-    c->host.k1_base = d_k1_base;
-    c->host.k2_base = d_k2_base;
+    for (int l = 0; l < kCtxLevels; ++l) {
+      c->host.k_base[l] = d_k_base[l];
+      c->host.n_k[l] = (uint32_t)n_k[l];
+    }
     c->host.ctx_off = d_ctx_off;
     c->host.ctx_node = d_ctx_node;
     c->host.n_nodes = N;
-    c->host.n_k1 = (uint32_t)n_k1;
-    c->host.n_k2 = (uint32_t)n_k2;
-    c->device_bytes += (int64_t)(n_slots + 1) * 4 + (int64_t)total * 4 + (int64_t)image_bytes + (int64_t)(n_k1 + (level2 ? n_k1 : 0) + N) * 4 +
+    c->device_bytes += (int64_t)(n_slots + 1) * 4 + (int64_t)total * 4 + (int64_t)image_bytes + (int64_t)(n_keys - n_k[c->levels - 1]) * 4 +
                        (int64_t)ctx_off.size() * 4 + (int64_t)ctx_node.size() * 2;
     if (keep_plain) c->device_bytes += (int64_t)N * dv.W * 8;
     c->stats[0] = (int64_t)n_keys;
-    c->stats[1] = (int64_t)n_k1;
-    c->stats[2] = (int64_t)n_k2;
+    c->stats[1] = (int64_t)n_k[0];
+    c->stats[2] = (int64_t)(n_keys - (uint64_t)N - n_k[0]);
     c->stats[3] = (int64_t)total;
     c->stats[4] = (int64_t)n_level0;
     c->stats[5] = (int64_t)n_base;
@@ -1118,12 +1140,18 @@ static void pack_stack_header(const Automaton& A, const xgm_cache& c, const Stac
     if (it == ctx.end() || *it != below) throw Failure(XGM_ERR_INTERNAL, "fill: a frame sits on a node that is no context of its rule");
     return (uint32_t)(it - ctx.begin());
   };
-  uint32_t key[kStackLists] = {(uint32_t)top, kNoKey, kNoKey};
-  if (s.size() >= 2 && c.k1_base_host[top] != kNoKey) {
-    const uint32_t key1_local = c.k1_base_host[top] + context_index(top, s[s.size() - 2]);
-    key[1] = (uint32_t)c.host.n_nodes + key1_local;
-    if (s.size() >= 3 && !c.k2_base_host.empty())
-      key[2] = (uint32_t)c.host.n_nodes + c.host.n_k1 + c.k2_base_host[key1_local] + context_index(s[s.size() - 2], s[s.size() - 3]);
+  uint32_t key[kStackLists];
+  key[0] = (uint32_t)top;
+  uint32_t local = (uint32_t)top, key0 = (uint32_t)c.host.n_nodes;
+  bool more = true;
+  for (int l = 1; l <= kCtxLevels; ++l) {
+    key[l] = kNoKey;
+    if (more && l <= c.levels && (int)s.size() >= l + 1 && c.k_base_host[l - 1][local] != kNoKey) {
+      local = c.k_base_host[l - 1][local] + context_index(s[s.size() - l], s[s.size() - l - 1]);
+      key[l] = key0 + local;
+    }
+    more = key[l] != kNoKey;
+    key0 += c.host.n_k[l - 1];
   }
   for (uint32_t l = 0; l < kStackLists; ++l) {
     uint32_t* off = h + kStackHdrWords + l * n_off;
@@ -1261,7 +1289,7 @@ int xgm_debug_matcher_fill_work(const xgm_matcher* m, int64_t* h_out4) {
     if ((h[kStackHdrTop] >> 16) != kNoAccRow) ++h_out4[0];
     for (uint32_t l = 0; l < kStackLists; ++l) {
       const uint32_t* off = &h[kStackHdrWords + l * ((uint32_t)n_seg + 1u)];
-      h_out4[1 + l] += off[n_seg] - off[0];
+      h_out4[1 + std::min<uint32_t>(l, 2u)] += off[n_seg] - off[0];
     }
   }
   return XGM_OK;

@@ -269,7 +269,7 @@ __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
   x ^= x >> 27; x *= 0x94D049BB133111EBull;
   return x ^ (x >> 31);
 }
-constexpr int kMaxSegs = 32;  // segments of the largest vocabulary (XGM_MAX_VOCAB / kSegTokens), rounded up
+constexpr int kMaxSegs = 128;  // segments of the largest vocabulary (XGM_MAX_VOCAB / kSegTokens), rounded up
 // One workgroup per node: accepted tokens per segment, digest of the accepted row, number of
 // context-dependent tokens (one pass over the node's two id-space rows).
 __global__ __launch_bounds__(kRowThreads) void row_stats_kernel(DevVocab voc, const uint32_t* __restrict__ acc_id,
@@ -376,18 +376,19 @@ __device__ __forceinline__ TokenRef load_token(const DevVocab& voc, int32_t id) 
   return t;
 }
 
-// ---- The level-1 and level-2 lists (section 3.2 per call site; see DevCache), from the base lists: the
-// context-dependent (node, token) pairs.  Three kernels, tables staged as in the classify kernel:
+// ---- The per-context lists (section 3.2 per call site; see DevCache), from the base lists: the
+// context-dependent (node, token) pairs.  Kernels, tables staged as in the classify kernel:
 //   exit_positions_kernel  one thread per pair: the token is walked once more from the node to find the
 //                          positions at which it leaves the node's frame;
 //   context_level1_kernel  one thread per (pair, a few contexts of the node's rule): the rest of the token is
 //                          walked from the context node with nothing known below.  Accepted there: an entry
-//                          of the (node, context) list.  Leaves that frame too: a record for the next kernel;
-//   context_level2_kernel  one thread per (record, a few contexts of the context node's rule): the same one
-//                          frame further down; what leaves a third frame becomes a walk entry.
+//                          of the (node, context) list.  Leaves that frame too: a record for the next level;
+//   context_deeper_kernel  for level 2, 3, ...: one thread per (record of the level above, a few contexts of
+//                          the rule of that record's context node): the same one frame further down; what
+//                          leaves a frame beyond the last level becomes a walk entry.
 // Most (pair, context) combinations end at the first byte of the rest, which the context node cannot
-// take.  The last two kernels run twice: first they count the entries of every (key, segment), then, with
-// the offsets made from the counts, they write them.
+// take.  All but the first kernel run twice: first they count the entries of every (key, segment), then,
+// with the offsets made from the counts, they write them.
 constexpr int kContextThreads = 768;
 constexpr uint32_t kContextsPerThread = 8;
 
@@ -408,13 +409,15 @@ __global__ __launch_bounds__(kContextThreads) void exit_positions_kernel(DevTabl
   else body(LdsTab(tab, smem));
 }
 
-// What the two list kernels share: the token of one pair, and how its entries reach the lists.
+// What the list kernels share: the token of one pair, how its entries reach the lists, and one (pair,
+// context) step: the rest of the token after it has left the frame above at the positions `ex`, walked
+// from context node r.
 template <bool WRITE, class Tab>
 struct ContextWork {
   const Tab& T;
   const DevVocab& voc;
   const ContextListArgs& a;
-  uint32_t id;
+  uint32_t e, id;
   TokenRef t;
   // One entry for list `key`.  The lanes of a wave that get here together mostly add to the same list (they hold
   // neighbouring tokens of one node and look at the same context): they are served by one atomic per
@@ -450,25 +453,43 @@ struct ContextWork {
     const uint2 h = T.header(r);
     return (h.y & 1u) && T.can_follow(h, c);
   }
-  // Level 2 for contexts [j0, j1) of rule1: the token has left the frame of a context node of that rule
-  // at the positions ex1.  key2 = the first level-2 key of its level-1 key.
-  __device__ __forceinline__ void level2(uint32_t rule1, uint32_t j0, uint32_t j1, uint32_t key2, uint32_t ex1, bool single1) const {
-    const uint32_t c2 = a.ctx_off[rule1];
-    for (uint32_t j = j0; j < j1; ++j) {
-      const uint32_t r2 = a.ctx_node[c2 + j];
-      bool acc2 = false, walk2 = false;
-      for (uint32_t m = ex1; m != 0u && !acc2; m &= m - 1u) {
-        const uint32_t k = __ffs(m) - 1u;
-        if (!plausible(r2, k)) continue;
-        const int res = walk_token<true>(T, t.tk, t.ext, t.len, r2, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r2), (int)k);
-        if (res == kAccept) acc2 = true;
-        else if (res == kOverflow || res == kUncertain) walk2 = true;
-      }
-      if (acc2) emit(key2 + j, kEntryAccepted, 0u);
-      else if (walk2) {
-        if (single1) emit(key2 + j, kEntryWalkBelow2, __ffs(ex1) - 1u); else emit(key2 + j, kEntryWalkTop, 0u);
-      }
+  // Level `level` (1-based), context node r, whose key is `key_local` among its level's keys.  `single`:
+  // every frame so far was left at exactly one position.
+  __device__ __forceinline__ void step(uint32_t level, uint32_t r, uint32_t key_local, uint32_t ex, bool single) const {
+    const uint32_t key = a.key0[level - 1u] + key_local;
+    // how a token that needs the live stack after all is listed here: from the frame of r on, if the way there is unique
+    const uint32_t walk_kind = single ? kEntryWalkTop + level : kEntryWalkTop;
+    const uint32_t walk_pos = single ? (uint32_t)__ffs(ex) - 1u : 0u;
+    if (ex & 0x80000000u) { emit(key, kEntryWalkTop, 0u); return; }
+    bool accepted = false, over = false;
+    uint32_t ex_next = 0u, n_res = 0u;
+    for (uint32_t m = ex; m != 0u && !accepted; m &= m - 1u) {
+      const uint32_t k = __ffs(m) - 1u;
+      if (!plausible(r, k)) continue;
+      uint32_t x = 0u;
+      const int res = walk_token<true>(T, t.tk, t.ext, t.len, r, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r), (int)k, &x);
+      if (res == kAccept) accepted = true;
+      else if (res == kOverflow) over = true;
+      else if (res == kUncertain) { ex_next |= x; ++n_res; }
     }
+    if (accepted) { emit(key, kEntryAccepted, 0u); return; }
+    if (over) { emit(key, kEntryWalkTop, 0u); return; }
+    if (ex_next == 0u) return;  // rejected in this context
+    if (level == (uint32_t)kCtxLevels || a.k_base[level] == nullptr || (ex_next & 0x80000000u)) {
+      emit(key, walk_kind, walk_pos);
+      return;
+    }
+    // it leaves this frame as well: a record for the next level
+    const uint32_t rule = T.header(r).y >> 16;
+    const bool single_next = single && n_res == 1u && (ex_next & (ex_next - 1u)) == 0u;
+    const uint32_t lane = threadIdx.x & 63u;
+    const unsigned long long peers = __ballot(true);
+    const uint32_t n = (uint32_t)__popcll(peers), rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+    const int first = __ffsll((long long)peers) - 1;
+    uint32_t base = 0u;
+    if (rank == 0u) base = atomicAdd(&a.res_count[level - 1u], n);
+    base = __shfl(base, first, 64);
+    if (base + rank < a.res_cap) a.res[level - 1u][base + rank] = make_uint4(e, key_local, ex_next, rule | (single_next ? 0x10000u : 0u));
   }
 };
 
@@ -479,47 +500,11 @@ __device__ __forceinline__ void context_level1_body(const Tab& T, const DevVocab
   if (threadIdx.x >= (tile.y & 0xFFFFu)) return;
   const uint32_t e = tile.x + threadIdx.x, node = tile.w, i0 = tile.z, i1 = tile.z + (tile.y >> 16);
   const uint32_t id = a.base_ids[e], ex0 = a.exits[e];
-  const ContextWork<WRITE, Tab> w{T, voc, a, id, load_token(voc, (int32_t)id)};
-  const uint32_t rule = T.header(node).y >> 16;
-  const uint32_t cb = a.ctx_off[rule];
-  const uint32_t k1b = a.k1_base[node];
+  const ContextWork<WRITE, Tab> w{T, voc, a, e, id, load_token(voc, (int32_t)id)};
+  const uint32_t cb = a.ctx_off[T.header(node).y >> 16];
+  const uint32_t k1b = a.k_base[0][node];
   const bool single0 = (ex0 & (ex0 - 1u)) == 0u;
-  const uint32_t lane = threadIdx.x & 63u;
-  for (uint32_t i = i0; i < i1; ++i) {
-    const uint32_t r1 = a.ctx_node[cb + i];
-    const uint32_t key1_local = k1b + i, key1 = (uint32_t)a.n_nodes + key1_local;
-    if (ex0 & 0x80000000u) { w.emit(key1, kEntryWalkTop, 0u); continue; }
-    bool accepted = false, over = false;
-    uint32_t ex1 = 0u, from1 = 0u, n_res = 0u;
-    for (uint32_t m = ex0; m != 0u && !accepted; m &= m - 1u) {
-      const uint32_t k = __ffs(m) - 1u;
-      if (!w.plausible(r1, k)) continue;
-      uint32_t x = 0u;
-      const int res = walk_token<true>(T, w.t.tk, w.t.ext, w.t.len, r1, (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(r1), (int)k, &x);
-      if (res == kAccept) accepted = true;
-      else if (res == kOverflow) over = true;
-      else if (res == kUncertain) { ex1 |= x; if (n_res++ == 0u) from1 = k; }
-    }
-    if (accepted) { w.emit(key1, kEntryAccepted, 0u); continue; }
-    if (over) { w.emit(key1, kEntryWalkTop, 0u); continue; }
-    if (ex1 == 0u) continue;  // rejected in this context
-    if (a.k2_base == nullptr || (ex1 & 0x80000000u)) {
-      if (single0) w.emit(key1, kEntryWalkBelow1, from1); else w.emit(key1, kEntryWalkTop, 0u);
-      continue;
-    }
-    // it leaves the context's frame as well: a record for the level-2 kernel (or, if the record buffer is
-    // full, the same work right here)
-    const uint32_t rule1 = T.header(r1).y >> 16;
-    const bool single1 = single0 && n_res == 1u && (ex1 & (ex1 - 1u)) == 0u;
-    const unsigned long long peers = __ballot(true);
-    const uint32_t n = (uint32_t)__popcll(peers), rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
-    const int first = __ffsll((long long)peers) - 1;
-    uint32_t base = 0u;
-    if (rank == 0u) base = atomicAdd(a.res_count, n);
-    base = __shfl(base, first, 64);
-    if (base + rank < a.res_cap) a.res[base + rank] = make_uint4(e, key1_local, ex1, rule1 | (single1 ? 0x10000u : 0u));
-    else w.level2(rule1, 0u, a.ctx_off[rule1 + 1] - a.ctx_off[rule1], (uint32_t)a.n_nodes + a.n_k1 + a.k2_base[key1_local], ex1, single1);
-  }
+  for (uint32_t i = i0; i < i1; ++i) w.step(1u, a.ctx_node[cb + i], k1b + i, ex0, single0);
 }
 template <bool WRITE>
 __global__ __launch_bounds__(kContextThreads) void context_level1_kernel(DevTables tab, DevVocab voc, ContextListArgs a) {
@@ -531,33 +516,35 @@ __global__ __launch_bounds__(kContextThreads) void context_level1_kernel(DevTabl
   else context_level1_body<WRITE>(LdsTab(tab, smem), voc, a, tile);
 }
 
-// A fixed grid walks over (record, chunk of kContextsPerThread contexts): consecutive threads hold
-// consecutive records (neighbouring tokens of one node and context, as a rule) and the same chunk.
+// Level `level` >= 2: a fixed grid walks over (record of level - 1, chunk of kContextsPerThread contexts);
+// consecutive threads hold consecutive records (neighbouring tokens of one node and context, as a rule)
+// and the same chunk.
 template <bool WRITE, class Tab>
-__device__ __forceinline__ void context_level2_body(const Tab& T, const DevVocab& voc, const ContextListArgs& a) {
-  const uint32_t n_res = min(*a.res_count, a.res_cap);
+__device__ __forceinline__ void context_deeper_body(const Tab& T, const DevVocab& voc, const ContextListArgs& a, uint32_t level) {
+  const uint32_t n_res = min(a.res_count[level - 2u], a.res_cap);
   const uint32_t n_chunks = (a.max_ctx + kContextsPerThread - 1u) / kContextsPerThread;
   const uint64_t n_items = (uint64_t)n_res * n_chunks;
   for (uint64_t item = (uint64_t)blockIdx.x * kContextThreads + threadIdx.x; item < n_items; item += (uint64_t)gridDim.x * kContextThreads) {
     const uint32_t r = (uint32_t)(item % n_res), jc = (uint32_t)(item / n_res);
-    const uint4 rec = a.res[r];
-    const uint32_t rule1 = rec.w & 0xFFFFu;
-    const uint32_t m2 = a.ctx_off[rule1 + 1] - a.ctx_off[rule1];
+    const uint4 rec = a.res[level - 2u][r];
+    const uint32_t rule = rec.w & 0xFFFFu;
+    const uint32_t cb = a.ctx_off[rule], m = a.ctx_off[rule + 1] - cb;
     const uint32_t j0 = jc * kContextsPerThread;
-    if (j0 >= m2) continue;
+    if (j0 >= m) continue;
     const uint32_t id = a.base_ids[rec.x];
-    const ContextWork<WRITE, Tab> w{T, voc, a, id, load_token(voc, (int32_t)id)};
-    w.level2(rule1, j0, min(j0 + kContextsPerThread, m2), (uint32_t)a.n_nodes + a.n_k1 + a.k2_base[rec.y], rec.z, (rec.w & 0x10000u) != 0u);
+    const ContextWork<WRITE, Tab> w{T, voc, a, rec.x, id, load_token(voc, (int32_t)id)};
+    const uint32_t kb = a.k_base[level - 1u][rec.y];
+    for (uint32_t j = j0; j < min(j0 + kContextsPerThread, m); ++j) w.step(level, a.ctx_node[cb + j], kb + j, rec.z, (rec.w & 0x10000u) != 0u);
   }
 }
 template <bool WRITE>
-__global__ __launch_bounds__(kContextThreads) void context_level2_kernel(DevTables tab, DevVocab voc, ContextListArgs a) {
+__global__ __launch_bounds__(kContextThreads) void context_deeper_kernel(DevTables tab, DevVocab voc, ContextListArgs a, uint32_t level) {
   extern __shared__ __align__(16) unsigned char smem[];
-  if (*a.res_count == 0u) return;
+  if (a.res_count[level - 2u] == 0u) return;
   stage_tables(tab, smem, kContextThreads);
   __syncthreads();
-  if (small_sections_staged(tab)) context_level2_body<WRITE>(LdsTabT<true>(tab, smem), voc, a);
-  else context_level2_body<WRITE>(LdsTab(tab, smem), voc, a);
+  if (small_sections_staged(tab)) context_deeper_body<WRITE>(LdsTabT<true>(tab, smem), voc, a, level);
+  else context_deeper_body<WRITE>(LdsTab(tab, smem), voc, a, level);
 }
 
 __global__ __launch_bounds__(kRowThreads) void rows_equal_kernel(const uint32_t* __restrict__ rows, int32_t W,
@@ -604,38 +591,44 @@ __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ 
 // allowed: nothing is touched.  None allowed: one 16-byte store of the -inf
 // pattern.  One or two disallowed: those elements are stored by themselves,
 // nothing is read.  More: the group is read, blended and stored whole (many
-// small stores cost more than the read).
+// small stores cost more than the read).  That is the stand-alone kernel, one
+// group per thread.  The one-launch kernel, where a thread has several groups
+// and waits for its fetches anyway, blends every group that has both kinds
+// (measured on the serving masks, where four rows in ten allow nearly every
+// token: 16.3 -> 15.3 us for the one-launch step, 8.3 -> 9.3 us for the
+// stand-alone kernel; blending whole 64-byte lines was slower in both).
+template <int ESIZE>
+__device__ __forceinline__ uint4 blend_group(uint4 v, uint32_t mk, uint32_t neg_inf) {
+  if (ESIZE == 2) {
+    const uint32_t two = neg_inf | (neg_inf << 16);
+    uint32_t* q = reinterpret_cast<uint32_t*>(&v);
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const uint32_t keep = ((mk >> (2 * h)) & 1u ? 0x0000FFFFu : 0u) | ((mk >> (2 * h + 1)) & 1u ? 0xFFFF0000u : 0u);
+      q[h] = (q[h] & keep) | (two & ~keep);
+    }
+  } else {
+    if (!(mk & 1u)) v.x = neg_inf;
+    if (!(mk & 2u)) v.y = neg_inf;
+    if (!(mk & 4u)) v.z = neg_inf;
+    if (!(mk & 8u)) v.w = neg_inf;
+  }
+  return v;
+}
 template <int ESIZE>
 __device__ __forceinline__ void apply_group(unsigned char* p, uint32_t mk, int32_t e0, int32_t V_logits, uint32_t neg_inf) {
   constexpr int EPT = 16 / ESIZE;
   constexpr uint32_t kAll = (1u << EPT) - 1u;
   if (mk == kAll) return;
-  const uint32_t two = neg_inf | (neg_inf << 16);
   const bool whole = e0 + EPT <= V_logits;
   if (mk == 0u && whole) {
-    // a streaming store: the line is written whole and not read again here, so it need not stay in the
-    // caches (measured on the serving masks: 10.7 -> 8.6 us for the stand-alone kernel; the same hint on
-    // the single-element stores below costs time, their lines are better merged in the cache)
+    // a streaming store: the line is written whole and not read again here, so it need not stay in the caches
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-    const uint32_t w = ESIZE == 2 ? two : neg_inf;
+    const uint32_t w = ESIZE == 2 ? (neg_inf | (neg_inf << 16)) : neg_inf;
     const v4u val = {w, w, w, w};
     __builtin_nontemporal_store(val, reinterpret_cast<v4u*>(p));
   } else if (whole && EPT - __popc(mk) > 2) {
-    uint4 v = *reinterpret_cast<const uint4*>(p);
-    if (ESIZE == 2) {
-      uint32_t* q = reinterpret_cast<uint32_t*>(&v);
-#pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        const uint32_t keep = ((mk >> (2 * h)) & 1u ? 0x0000FFFFu : 0u) | ((mk >> (2 * h + 1)) & 1u ? 0xFFFF0000u : 0u);
-        q[h] = (q[h] & keep) | (two & ~keep);
-      }
-    } else {
-      if (!(mk & 1u)) v.x = neg_inf;
-      if (!(mk & 2u)) v.y = neg_inf;
-      if (!(mk & 4u)) v.z = neg_inf;
-      if (!(mk & 8u)) v.w = neg_inf;
-    }
-    *reinterpret_cast<uint4*>(p) = v;
+    *reinterpret_cast<uint4*>(p) = blend_group<ESIZE>(*reinterpret_cast<const uint4*>(p), mk, neg_inf);
   } else {
 #pragma unroll
     for (int h = 0; h < EPT; ++h)
@@ -655,19 +648,40 @@ struct LogitsRange {
   const uint32_t* words;  // the workgroup's mask words; bit 0 of words[0] is element e_begin
   int32_t e_begin, e_end, V, V_logits;
   uint32_t neg_inf;
-  // thread t of nt: the range's groups t, t + nt, ...  (One group after the other: fetching the groups
-  // that must be read several at a time made the launch longer, not shorter.)
+  // thread t of nt: the range's groups t, t + nt, ...  Four groups at a time: the ones that must be read
+  // (allowed and disallowed logits side by side) are fetched together, then all four are written: the
+  // wave's memory counter is in order, so a fetch issued after a store would wait for that store too.
   __device__ __forceinline__ void groups(uint32_t t, uint32_t nt) const {
     if constexpr (APPLY != 0) {
       constexpr int EPT = 16 / APPLY;
       constexpr uint32_t kAll = (1u << EPT) - 1u;
-      for (int32_t e0 = e_begin + (int32_t)t * EPT; e0 < e_end; e0 += (int32_t)nt * EPT) {
-        uint32_t mk = 0u;
-        if (e0 < V) {
-          mk = (words[(e0 - e_begin) >> 5] >> (e0 & 31)) & kAll;
-          if (e0 + EPT > V) mk &= (1u << (V - e0)) - 1u;
+      constexpr int G = 4;
+      for (int32_t base = e_begin + (int32_t)t * EPT; base < e_end; base += (int32_t)nt * EPT * G) {
+        uint32_t mk[G];
+        uint4 v[G];
+        bool blend[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const int32_t e0 = base + g * (int32_t)nt * EPT;
+          mk[g] = kAll;  // (a group beyond the range: nothing to do)
+          blend[g] = false;
+          if (e0 < e_end) {
+            mk[g] = 0u;
+            if (e0 < V) {
+              mk[g] = (words[(e0 - e_begin) >> 5] >> (e0 & 31)) & kAll;
+              if (e0 + EPT > V) mk[g] &= (1u << (V - e0)) - 1u;
+            }
+            blend[g] = e0 + EPT <= V_logits && mk[g] != 0u && mk[g] != kAll;
+            if (blend[g]) v[g] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * APPLY);
+          }
         }
-        apply_group<APPLY>(row + (size_t)e0 * APPLY, mk, e0, V_logits, neg_inf);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const int32_t e0 = base + g * (int32_t)nt * EPT;
+          unsigned char* p = row + (size_t)e0 * APPLY;
+          if (blend[g]) *reinterpret_cast<uint4*>(p) = blend_group<APPLY>(v[g], mk[g], neg_inf);
+          else if (mk[g] != kAll) apply_group<APPLY>(p, mk[g], e0, V_logits, neg_inf);  // all rejected, or the ragged end
+        }
       }
     }
   }
@@ -685,9 +699,9 @@ __global__ __launch_bounds__(kUploadThreads) void upload_kernel(const uint4* __r
   if (i < n16) dst[i] = src[i];
 }
 
-constexpr int kFillThreads = 512;
+constexpr int kFillThreads = 256;
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
-constexpr int kFillMaxLists = 64 * 3;           // XGM_MAX_STACKS stacks, three lists each
+constexpr int kFillMaxLists = 64 * kStackLists;  // XGM_MAX_STACKS stacks with their lists
 constexpr int kFillListsAtOnce = 6;             // lists whose first entries are fetched together
 
 // One workgroup of 8 waves serves one request and one segment of 32768 token
@@ -785,39 +799,19 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   const int32_t w_begin = seg * kSegWords;
   const int32_t n_words = min(kSegWords, voc.W - w_begin);
   const int32_t id0 = w_begin * 32;
+  // LDS is cleared before anything is fetched (a barrier waits for what its threads have in flight)
+  for (int32_t w = tid; w < kSegWords; w += kFillThreads) sm.words[w] = 0u;
+  for (int32_t l = tid; l < kFillMaxLists; l += kFillThreads) sm.n_walk[l] = 0u;
+  if (tid == 0) sm.any_walk = 0u;
+  __syncthreads();
   const RowDesc rd = rows[b];
-  const uint32_t hdr_stride = kStackHdrWords + kStackLists * ((uint32_t)voc.n_seg + 1u);
+  const uint32_t n_off = (uint32_t)voc.n_seg + 1u;
+  const uint32_t hdr_stride = kStackHdrWords + kStackLists * n_off;
   const uint32_t n_lists = rd.n_stacks * kStackLists;
   // may the request end here?  then its stop tokens are allowed (the first kFillThreads of them are fetched now)
   const bool may_end = rd.flags & 1u;
   const int32_t my_stop = may_end && (int32_t)tid < voc.n_stop ? voc.stop_ids[tid] : -1;
-  // the bounds of this segment's lists
-  for (uint32_t l = tid; l < n_lists; l += kFillThreads) {
-    const XGM_GLOBAL uint32_t* off = stack_hdrs + (size_t)(rd.stack_begin + l / kStackLists) * hdr_stride + kStackHdrWords +
-                                     (l % kStackLists) * ((uint32_t)voc.n_seg + 1u) + (uint32_t)seg;
-    sm.list[l] = make_uint2(off[0], off[1]);
-    sm.n_walk[l] = 0u;
-  }
-  if (tid == 0) sm.any_walk = 0u;
-  // 1. accepted words
   const XGM_GLOBAL uint32_t* acc = (const XGM_GLOBAL uint32_t*)rd.acc;
-  for (int32_t w = tid; w < kSegWords; w += kFillThreads) {
-    uint32_t x = 0u;
-    if (w < n_words)
-      for (uint32_t s = 0; s < rd.n_stacks; ++s) {
-        const uint32_t acc_row = stack_hdrs[(size_t)(rd.stack_begin + s) * hdr_stride + kStackHdrTop] >> 16;
-        if (acc_row != kNoAccRow) x |= acc[(size_t)acc_row * voc.W + w_begin + w];
-      }
-    sm.words[w] = x;
-  }
-  __syncthreads();
-  if (may_end)
-    for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
-      const int32_t rel = (k == (int32_t)tid ? my_stop : voc.stop_ids[k]) - id0;
-      if (rel >= 0 && rel < n_words * 32) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31));
-    }
-  // 2. the lists: the first kFillThreads entries of several lists are fetched together (most lists are
-  // shorter than that), then what is left of them
   const XGM_GLOBAL uint32_t* entries = (const XGM_GLOBAL uint32_t*)rd.entries;
   auto take = [&](uint32_t e, uint32_t l) {
     if ((e >> kEntryKindShift) == kEntryAccepted) {
@@ -827,26 +821,62 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
       atomicAdd(&sm.n_walk[l], 1u);
     }
   };
-  for (uint32_t l0 = 0; l0 < n_lists; l0 += kFillListsAtOnce) {
-    uint32_t first[kFillListsAtOnce];
-    bool have[kFillListsAtOnce];
+  // 1 + 2. Two stacks at a time: their headers (the same words for every thread), then, in one go, this
+  // thread's words of their bitset rows (Algorithm 1: the union over the parallel stacks) and the first
+  // kFillThreads entries of their lists (most lists are shorter than that); then what is left of the lists.
+  constexpr int kWordsPerThread = kSegWords / kFillThreads;
+  for (uint32_t s0 = 0; s0 < rd.n_stacks; s0 += 2u) {
+    uint32_t acc_row[2];
+    uint2 lst[2][kStackLists];
 #pragma unroll
-    for (uint32_t q = 0; q < (uint32_t)kFillListsAtOnce; ++q) {
-      have[q] = false;
-      if (l0 + q < n_lists) {
-        const uint2 r = sm.list[l0 + q];
-        have[q] = r.x + tid < r.y;
-        if (have[q]) first[q] = entries[r.x + tid];
+    for (uint32_t q = 0; q < 2u; ++q) {
+      acc_row[q] = kNoAccRow;
+#pragma unroll
+      for (uint32_t l = 0; l < kStackLists; ++l) lst[q][l] = make_uint2(0u, 0u);
+      if (s0 + q < rd.n_stacks) {
+        const XGM_GLOBAL uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + s0 + q) * hdr_stride;
+        acc_row[q] = sh[kStackHdrTop] >> 16;
+#pragma unroll
+        for (uint32_t l = 0; l < kStackLists; ++l) {
+          const XGM_GLOBAL uint32_t* off = sh + kStackHdrWords + l * n_off + (uint32_t)seg;
+          lst[q][l] = make_uint2(off[0], off[1]);
+        }
+      }
+    }
+    uint32_t aw[2][kWordsPerThread], first[2][kStackLists];
+    bool have[2][kStackLists];
+#pragma unroll
+    for (uint32_t q = 0; q < 2u; ++q) {
+#pragma unroll
+      for (int k = 0; k < kWordsPerThread; ++k) {
+        const int32_t w = (int32_t)tid + k * kFillThreads;
+        aw[q][k] = acc_row[q] != kNoAccRow && w < n_words ? acc[(size_t)acc_row[q] * voc.W + w_begin + w] : 0u;
+      }
+#pragma unroll
+      for (uint32_t l = 0; l < kStackLists; ++l) {
+        have[q][l] = lst[q][l].x + tid < lst[q][l].y;
+        first[q][l] = have[q][l] ? entries[lst[q][l].x + tid] : 0u;
       }
     }
 #pragma unroll
-    for (uint32_t q = 0; q < (uint32_t)kFillListsAtOnce; ++q)
-      if (have[q]) take(first[q], l0 + q);
-    for (uint32_t q = 0; q < (uint32_t)kFillListsAtOnce && l0 + q < n_lists; ++q) {
-      const uint2 r = sm.list[l0 + q];
-      for (uint32_t j = r.x + kFillThreads + tid; j < r.y; j += kFillThreads) take(entries[j], l0 + q);
+    for (uint32_t q = 0; q < 2u; ++q) {
+#pragma unroll
+      for (int k = 0; k < kWordsPerThread; ++k)
+        if (aw[q][k]) atomicOr(&sm.words[tid + k * kFillThreads], aw[q][k]);
+#pragma unroll
+      for (uint32_t l = 0; l < kStackLists; ++l) {
+        const uint32_t li = (s0 + q) * kStackLists + l;
+        if (have[q][l]) take(first[q][l], li);
+        for (uint32_t j = lst[q][l].x + kFillThreads + tid; j < lst[q][l].y; j += kFillThreads) take(entries[j], li);
+        if (tid == 0 && s0 + q < rd.n_stacks) sm.list[li] = lst[q][l];  // (for the walk entries, should there be any)
+      }
     }
   }
+  if (may_end)
+    for (int32_t k = tid; k < voc.n_stop; k += kFillThreads) {
+      const int32_t rel = (k == (int32_t)tid ? my_stop : voc.stop_ids[k]) - id0;
+      if (rel >= 0 && rel < n_words * 32) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31));
+    }
   __syncthreads();
   // 3. walk entries, if any
   if (tid < n_lists && sm.n_walk[tid] != 0u) sm.any_walk = 1u;
@@ -1028,7 +1058,7 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       const uint32_t ci = slot_of[r], d = cdepth[ci];
       for (uint32_t k = tid; k < d; k += kAcceptThreads) bt.frames[fb + foff[r] + k] = cand[ci * kBatchMaxDepth + k];
     }
-    // headers: scalars, the keys of the stack's three lists, whether the stack can end the text
+    // headers: scalars, the keys of the stack's lists, whether the stack can end the text
     if (tid < ns) {
       const uint32_t ci = slot_of[tid], d = cdepth[ci];
       const uint16_t* st = cand + ci * kBatchMaxDepth;
@@ -1038,25 +1068,26 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       h[kStackHdrDepth] = d;
       h[kStackHdrFrames] = fb + foff[tid];
       h[3] = 0u;
-      uint32_t key1 = kNoKey, key2 = kNoKey;
-      if (d >= 2u && dc.k1_base[top] != kNoKey) {  // (a node without context-dependent tokens has no such lists)
-        const uint32_t rule = T.header(top).y >> 16, below = st[d - 2];
-        const uint32_t i = context_index(dc.ctx_node, dc.ctx_off[rule], dc.ctx_off[rule + 1], below);
-        if (i == kNoKey) bad_context = 1u;
-        else {
-          const uint32_t key1_local = dc.k1_base[top] + i;
-          key1 = (uint32_t)dc.n_nodes + key1_local;
-          if (d >= 3u && dc.k2_base != nullptr) {
-            const uint32_t rule1 = T.header(below).y >> 16;
-            const uint32_t j = context_index(dc.ctx_node, dc.ctx_off[rule1], dc.ctx_off[rule1 + 1], st[d - 3]);
-            if (j == kNoKey) bad_context = 1u;
-            else key2 = (uint32_t)dc.n_nodes + dc.n_k1 + dc.k2_base[key1_local] + j;
+      // the keys of the stack's lists: the top node's own, then one per frame below that a kept level reaches
+      keys[tid][0] = top;
+      uint32_t local = top, key0 = (uint32_t)dc.n_nodes;
+      bool more = true;
+#pragma unroll
+      for (uint32_t l = 1; l <= (uint32_t)kCtxLevels; ++l) {
+        uint32_t key = kNoKey;
+        if (more && d >= l + 1u && dc.k_base[l - 1u] != nullptr && dc.k_base[l - 1u][local] != kNoKey) {
+          const uint32_t rule = T.header(st[d - l]).y >> 16;
+          const uint32_t i = context_index(dc.ctx_node, dc.ctx_off[rule], dc.ctx_off[rule + 1], st[d - l - 1u]);
+          if (i == kNoKey) bad_context = 1u;
+          else {
+            local = dc.k_base[l - 1u][local] + i;
+            key = key0 + local;
           }
         }
+        more = key != kNoKey;
+        keys[tid][l] = key;
+        key0 += dc.n_k[l - 1u];
       }
-      keys[tid][0] = top;
-      keys[tid][1] = key1;
-      keys[tid][2] = key2;
       bool all_final = true;
       for (uint32_t k = 0; k < d; ++k) all_final = all_final && T.is_final(st[k]);
       if (all_final) can_end = 1u;
@@ -1319,14 +1350,13 @@ void launch_exit_positions(const DevTables& tab, const DevVocab& voc, const Cont
 void launch_context_lists(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, bool write, hipStream_t stream) {
   if (args.total == 0 || args.n_tiles == 0) return;
   const DevTables st = staged_for(tab, kClassifyLdsBudget);
-  (void)hipMemsetAsync(args.res_count, 0, 4, stream);
+  (void)hipMemsetAsync(args.res_count, 0, 4 * kCtxLevels, stream);
   const dim3 g1(args.n_tiles), g2(1024);
-  if (write) {
-    hipLaunchKernelGGL(context_level1_kernel<true>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
-    if (args.k2_base) hipLaunchKernelGGL(context_level2_kernel<true>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
-  } else {
-    hipLaunchKernelGGL(context_level1_kernel<false>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
-    if (args.k2_base) hipLaunchKernelGGL(context_level2_kernel<false>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+  if (write) hipLaunchKernelGGL(context_level1_kernel<true>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+  else hipLaunchKernelGGL(context_level1_kernel<false>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+  for (uint32_t level = 2; level <= (uint32_t)kCtxLevels && args.k_base[level - 1] != nullptr; ++level) {
+    if (write) hipLaunchKernelGGL(context_deeper_kernel<true>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args, level);
+    else hipLaunchKernelGGL(context_deeper_kernel<false>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args, level);
   }
 }
 uint32_t context_tile_pairs() { return (uint32_t)kContextThreads; }

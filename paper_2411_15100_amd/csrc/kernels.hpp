@@ -16,7 +16,7 @@ constexpr int kMaxTokenLen = 255;   // bytes
 
 // ---- id space is cut into segments of 32768 tokens = 1024 mask words; one
 // workgroup of the fill kernel owns one (row, segment)
-constexpr int kSegWords = 1024;
+constexpr int kSegWords = 256;
 constexpr int kSegTokens = kSegWords * 32;
 
 // walk results
@@ -60,7 +60,7 @@ struct TabView {
 
 // LDS budgets (bytes of dynamic shared memory) for the staged tables
 constexpr int32_t kClassifyLdsBudget = 76 * 1024;
-constexpr int32_t kFillLdsBudget = 28 * 1024;
+constexpr int32_t kFillLdsBudget = 12 * 1024;
 // The staging split for a kernel that has `budget` bytes of LDS for the tables:
 // as many whole sections as fit, then as many headers as fit.
 inline DevTables staged_for(DevTables t, int32_t budget) {
@@ -98,40 +98,43 @@ struct DevVocab {
 
 // One mask cache on the device (section 3.1, with the context expansion of
 // section 3.2 taken per call site).  What a stack contributes to a mask is kept
-// in three kinds of token lists, each addressed by a key and cut by segment:
-//   level 0, key = node n:            the tokens accepted at n whatever lies below (only for nodes with
-//                                     few of them; the others keep a bitset row in `acc`);
-//   level 1, key = (n, i):            the context-dependent tokens of n that are accepted when the frame
-//                                     below is the i-th context node of n's rule (the nodes that can sit
-//                                     right below a frame of that rule: Automaton::contexts);
-//   level 2, key = (n, i, j):         those that leave that frame as well and are accepted when the next
-//                                     frame down is the j-th context node of the rule of context i.
-// Tokens that leave a third frame, or whose walk at build time hit a limit, are listed as "walk"
+// in token lists, each addressed by a key and cut by segment:
+//   level 0, key = node n:         the tokens accepted at n whatever lies below (only for nodes with few of
+//                                  them; the others keep a bitset row in `acc`);
+//   level 1, key = (n, i):         the context-dependent tokens of n that are accepted when the frame below
+//                                  is the i-th context node of n's rule (the nodes that can sit right below
+//                                  a frame of that rule: Automaton::contexts);
+//   level 2, key = (n, i, j):      those that leave that frame as well and are accepted when the next frame
+//                                  down is the j-th context node of the rule of context i;
+//   ... and so on, kCtxLevels frames deep.
+// Tokens that leave one more frame than that, or whose walk at build time hit a limit, are listed as "walk"
 // entries: the fill kernel decides them against the live stack.
-// Keys are numbered n | n_nodes + k1_base[n] + i | n_nodes + n_k1 + k2_base[key1 - n_nodes] + j;
-// the entries of (key, segment s) are entries[key_off[key * n_seg + s] .. key_off[key * n_seg + s + 1]),
-// accepted ones first, walk entries last, in no particular order otherwise.
+// A key of level l >= 1 has a number among its level's keys; the keys of all levels share one numbering:
+// node n | n_nodes + (level-1 number) | n_nodes + n_k[0] + (level-2 number) | ...  The children of a key are
+// numbered side by side: level-1 number of (n, i) = k_base[0][n] + i, level-(l+1) number of (key q of level
+// l, context j) = k_base[l][q] + j.  The entries of (key, segment s) are
+// entries[key_off[key * n_seg + s] .. key_off[key * n_seg + s + 1]), accepted ones first, walk entries last.
+constexpr int kCtxLevels = 3;
 struct DevCache {
   DevTables tab;             // staging split for the fill kernel
   const uint32_t* acc;       // [n_acc_rows][W] accepted tokens, id space: the distinct bitset rows
   const uint16_t* acc_row;   // [n_nodes] which row of `acc` is the node's, or kNoAccRow (listed under its level-0 key)
   const uint32_t* key_off;   // [n_keys * n_seg + 1]
   const uint32_t* entries;   // see kEntry*
-  const uint32_t* k1_base;   // [n_nodes]
-  const uint32_t* k2_base;   // [n_k1], or null if the grammar keeps no level-2 lists
+  const uint32_t* k_base[kCtxLevels];  // [n_nodes], [n_k[0]], [n_k[1]], ...; null from the first level that is not kept
+  uint32_t n_k[kCtxLevels];  // keys of level 1, 2, ...
   const uint32_t* ctx_off;   // [n_rules+1] ranges of ctx_node: the contexts of every rule
   const uint16_t* ctx_node;  // context nodes, sorted within a rule
   int32_t n_nodes;
-  uint32_t n_k1, n_k2;
 };
 constexpr uint32_t kNoAccRow = 0xFFFFu;
-// A list entry: bits 0..19 token id, bits 20..27 position, bits 28..29 kind:
-//   kEntryAccepted        the token is allowed;
-//   kEntryWalkTop         walk the whole token from the top of the stack;
-//   kEntryWalkBelow1 / 2  walk it from byte `position` on, starting at the node one / two frames below the top
-//                         (the only position at which it leaves the frames above).
+// A list entry: bits 0..19 token id, bits 20..27 position, bits 28..31 kind:
+//   kEntryAccepted       the token is allowed;
+//   kEntryWalkTop        walk the whole token from the top of the stack;
+//   kEntryWalkTop + d    walk it from byte `position` on, starting at the node d frames below the top (the
+//                        only position at which it leaves the frames above), d = 1 .. kCtxLevels.
 constexpr uint32_t kEntryIdBits = 20, kEntryIdMask = (1u << kEntryIdBits) - 1u, kEntryPosShift = 20, kEntryKindShift = 28;
-constexpr uint32_t kEntryAccepted = 0, kEntryWalkTop = 1, kEntryWalkBelow1 = 2, kEntryWalkBelow2 = 3;
+constexpr uint32_t kEntryAccepted = 0, kEntryWalkTop = 1;
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 
 // per-step description of the live stacks: [RowDesc x B][stack headers][frames]
@@ -146,13 +149,13 @@ struct RowDesc {
   uint32_t n_frames;         // stack after stack
   uint32_t epoch;            // device-resident states: how often the row's state has changed (names the state in a record)
 };
-// A stack header is kStackHdrWords + 3 * (n_seg + 1) uint32 words:
+// A stack header is kStackHdrWords + kStackLists * (n_seg + 1) uint32 words:
 //   [kStackHdrTop] top node | its row of DevCache::acc (or kNoAccRow) << 16, [kStackHdrDepth] number of frames,
 //   [kStackHdrFrames] offset of its frames (bottom first) in the uint16 frame array, [3] unused,
 //   [kStackHdrWords + l * (n_seg + 1) + s] where the entries of segment s of the stack's level-l list start
 //   (s = n_seg: where the last segment's end); a stack without that list (too shallow) has all of them equal.
 constexpr uint32_t kStackHdrTop = 0, kStackHdrDepth = 1, kStackHdrFrames = 2, kStackHdrWords = 4;
-constexpr uint32_t kStackLists = 3;
+constexpr uint32_t kStackLists = 1 + kCtxLevels;
 inline uint32_t stack_hdr_stride(int32_t n_seg) { return kStackHdrWords + kStackLists * ((uint32_t)n_seg + 1u); }
 
 // ---- matcher states that live on the device (section 3.3 on the GPU: the
@@ -230,13 +233,14 @@ void launch_rows_to_lists(const DevVocab& voc, int32_t n, const uint32_t* rows, 
 // (bit 31: some position beyond 30, or the walk hit a limit).
 // launch_context_lists, write = false: counts[key * n_seg + seg] += the entries each list will hold;
 // write = true: the entries are written, accepted ones upwards from front[slot], walk entries downwards from
-// back[slot] (both arrays are advanced).  k2_base == null: no level-2 lists; tokens that leave a second
-// frame become walk entries of level 1.
+// back[slot] (both arrays are advanced).  Levels whose k_base is null are not kept: tokens that would need
+// them become walk entries of the level above.
 // tiles: the work of the level-1 kernel, one workgroup each: x = first pair, y = pairs (at most
 // context_tile_pairs(), all of one node) | contexts << 16 (at most context_tile_contexts()), z = first
-// context, w = the node.  res / res_cap / res_count: records of the pairs that leave a second frame, for the
-// level-2 kernel (what does not fit is worked off by the level-1 kernel itself).  max_ctx: the most
-// contexts any rule has.
+// context, w = the node.  res[l] / res_cap / res_count[l]: records of the (pair, key of level l + 1) that
+// leave one more frame, made by the kernel of level l + 1 for the kernel of level l + 2; a record that does
+// not fit is dropped and counted all the same (the caller then runs the pass again with more room).
+// max_ctx: the most contexts any rule has.
 struct ContextListArgs {
   const uint16_t* base_node;
   const uint32_t* base_ids;
@@ -244,16 +248,14 @@ struct ContextListArgs {
   uint32_t* exits;             // [total]
   const uint4* tiles;
   uint32_t n_tiles;
-  uint4* res;
+  uint4* res[kCtxLevels];      // (the last one is not used)
   uint32_t res_cap;
-  uint32_t* res_count;
+  uint32_t* res_count;         // [kCtxLevels]
   uint32_t max_ctx;
-  const uint32_t* k1_base;     // [n_nodes]
-  const uint32_t* k2_base;     // [n_k1] or null
+  const uint32_t* k_base[kCtxLevels];
+  uint32_t key0[kCtxLevels];   // the first key of level 1, 2, ... in the shared numbering
   const uint32_t* ctx_off;
   const uint16_t* ctx_node;
-  int32_t n_nodes;
-  uint32_t n_k1;
   uint32_t* counts;            // [n_keys * n_seg]   write = false
   uint32_t* front;             // [n_keys * n_seg]   write = true
   uint32_t* back;              // [n_keys * n_seg]   write = true
