@@ -817,6 +817,21 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     for (int l = 0; l < c->levels; ++l) d_k_base[l] = keep(slab_upload(c->k_base_host[l]));
     uint32_t* d_ctx_off = keep(slab_upload(ctx_off));
     uint16_t* d_ctx_node = keep(slab_upload(ctx_node));
+    // the same relation by node (what the accept kernel looks up: which context of a rule a frame sits on)
+    std::vector<uint32_t> node_ctx_off((size_t)N + 1, 0), node_ctx;
+    {
+      std::vector<std::vector<uint32_t>> by_node((size_t)N);
+      for (size_t r = 0; r < A.rule_names.size(); ++r)
+        for (size_t i = 0; i < A.contexts[r].size(); ++i) by_node[A.contexts[r][i]].push_back((uint32_t)(r << 16 | i));
+      for (int32_t n = 0; n < N; ++n) {
+        node_ctx_off[n] = (uint32_t)node_ctx.size();
+        node_ctx.insert(node_ctx.end(), by_node[n].begin(), by_node[n].end());
+      }
+      node_ctx_off[N] = (uint32_t)node_ctx.size();
+      if (node_ctx.empty()) node_ctx.push_back(0u);
+    }
+    c->host.node_ctx_off = keep(slab_upload(node_ctx_off));
+    c->host.node_ctx = keep(slab_upload(node_ctx));
     uint32_t* d_base_ids = arena.array<uint32_t>((size_t)n_base);
     uint16_t* d_base_node = arena.array<uint16_t>((size_t)n_base);
     uint32_t* d_exits = arena.array<uint32_t>((size_t)n_base);

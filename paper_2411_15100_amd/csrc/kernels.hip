@@ -929,16 +929,6 @@ struct LdsStackSink {
 constexpr int kAcceptThreads = 256;
 constexpr int kErrTokenRejected = -6, kErrTerminated = -7, kErrTooManyStacks = -8, kErrTooLarge = -9, kErrBadArg = -1, kErrInternal = -11;
 
-// index of `node` among the (sorted) context nodes [lo, hi) of a rule, or kNoKey
-__device__ __forceinline__ uint32_t context_index(const uint16_t* __restrict__ ctx_node, uint32_t lo, uint32_t hi, uint32_t node) {
-  const uint32_t first = lo, end = hi;
-  while (lo < hi) {
-    const uint32_t mid = (lo + hi) >> 1;
-    if (ctx_node[mid] < node) lo = mid + 1; else hi = mid;
-  }
-  return lo < end && ctx_node[lo] == node ? lo - first : kNoKey;
-}
-
 // is stack a (depth da) ordered before stack b?  element by element, the shorter first (the host's order of stacks)
 __device__ __forceinline__ int compare_stacks(const uint16_t* a, uint32_t da, const uint16_t* b, uint32_t db) {
   const uint32_t m = da < db ? da : db;
@@ -963,14 +953,19 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
   __shared__ uint32_t foff[kBatchMaxStacks + 1];
   __shared__ uint32_t slot_of[kBatchMaxStacks];    // candidate index per rank
   __shared__ uint32_t keys[kBatchMaxStacks][kStackLists];  // the three lists of every new stack
-  __shared__ uint32_t ccount, coverflow, n_new, can_end, bad_context;
+  __shared__ uint32_t cidx[kBatchMaxStacks][kCtxLevels];   // which context of its rule each of the top frames sits on
+  __shared__ uint32_t ccount, coverflow, n_new, can_end, bad_context, not_final;
   const uint32_t tid = threadIdx.x;
   const int32_t b = blockIdx.x;
+  // what the row needs is fetched before anything is decided: one round trip for the token id and the slot,
+  // one for the token's bytes and the state's size (a branch in between would make each of them wait)
   const int32_t tok = tokens[b];
-  if (tok < 0) return;  // this row is left alone (its status too)
   const int32_t head = bt.head[b];
+  const DevCache& dc = bt.cache[b];
+  const int32_t first_stop = voc.n_stop > 0 ? voc.stop_ids[0] : -1;
+  const uint4 tk = voc.tok_by_id[tok >= 0 && tok < voc.V ? tok : 0];
   const SlotMeta cur = bt.meta[(size_t)b * bt.H + head];
-  const DevCache dc = bt.cache[b];
+  if (tok < 0) return;  // this row is left alone (its status too)
   const uint32_t n_off = (uint32_t)bt.n_seg + 1u;
   const uint32_t hdr_stride = kStackHdrWords + kStackLists * n_off;
   const int32_t next = (head + 1) % bt.H;
@@ -981,20 +976,20 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
   if (tok >= voc.V) status = kErrBadArg;
   else if (cur.flags & 2u) status = kErrTerminated;
   else {
-    for (int32_t k = 0; k < voc.n_stop; ++k) stop = stop || voc.stop_ids[k] == tok;
+    stop = tok == first_stop;
+    for (int32_t k = 1; k < voc.n_stop; ++k) stop = stop || voc.stop_ids[k] == tok;
     if (stop && !(cur.flags & 1u)) status = kErrTokenRejected;
   }
   if (status != 0) {
     if (tid == 0) bt.status[b] = status;
     return;
   }
-  if (tid == 0) { ccount = 0u; coverflow = 0u; n_new = 0u; can_end = 0u; bad_context = 0u; }
+  if (tid == 0) { ccount = 0u; coverflow = 0u; n_new = 0u; can_end = 0u; bad_context = 0u; not_final = 0u; }
   __syncthreads();
   DevTables tab = dc.tab;
   tab.lds_end = tab.stage_bytes = tab.n_near = 0u;  // the walks read the tables where they are
   const LdsTab T(tab, nullptr);
   if (!stop) {
-    const uint4 tk = voc.tok_by_id[tok];
     int len = (int)(tk.w >> 24);
     const uint8_t* ext = voc.bytes;
     if (len >= 15) {
@@ -1058,7 +1053,31 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       const uint32_t ci = slot_of[r], d = cdepth[ci];
       for (uint32_t k = tid; k < d; k += kAcceptThreads) bt.frames[fb + foff[r] + k] = cand[ci * kBatchMaxDepth + k];
     }
-    // headers: scalars, the keys of the stack's lists, whether the stack can end the text
+    // which context of its rule each of the top frames sits on (one thread per stack and level)
+    if (tid < ns * (uint32_t)kCtxLevels) {
+      const uint32_t r = tid / (uint32_t)kCtxLevels, l = tid % (uint32_t)kCtxLevels + 1u;
+      const uint32_t ci = slot_of[r], d = cdepth[ci];
+      const uint16_t* st = cand + ci * kBatchMaxDepth;
+      uint32_t idx = kNoKey;
+      if (d >= l + 1u) {
+        const uint32_t rule = T.header(st[d - l]).y >> 16, below = st[d - l - 1u];
+        for (uint32_t k = dc.node_ctx_off[below]; k < dc.node_ctx_off[below + 1u]; ++k) {
+          const uint32_t x = dc.node_ctx[k];
+          if ((x >> 16) == rule) idx = x & 0xFFFFu;
+        }
+        if (idx == kNoKey) bad_context = 1u;
+      }
+      cidx[r][l - 1u] = idx;
+    }
+    // whether some stack can end the text: every frame of it may end its rule
+    for (uint32_t item = tid; item < ns * kBatchMaxDepth; item += kAcceptThreads) {
+      const uint32_t r = item / kBatchMaxDepth, k = item % kBatchMaxDepth;
+      const uint32_t ci = slot_of[r];
+      if (k < cdepth[ci] && !T.is_final(cand[ci * kBatchMaxDepth + k])) atomicOr(&not_final, 1u << r);
+    }
+    __syncthreads();
+    if (tid == 0 && (not_final & ((1u << ns) - 1u)) != ((1u << ns) - 1u)) can_end = 1u;
+    // headers: scalars, the keys of the stack's lists
     if (tid < ns) {
       const uint32_t ci = slot_of[tid], d = cdepth[ci];
       const uint16_t* st = cand + ci * kBatchMaxDepth;
@@ -1068,19 +1087,17 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       h[kStackHdrDepth] = d;
       h[kStackHdrFrames] = fb + foff[tid];
       h[3] = 0u;
-      // the keys of the stack's lists: the top node's own, then one per frame below that a kept level reaches
+      // the keys: the top node's own list, then one per frame below that a kept level reaches
       keys[tid][0] = top;
       uint32_t local = top, key0 = (uint32_t)dc.n_nodes;
       bool more = true;
 #pragma unroll
       for (uint32_t l = 1; l <= (uint32_t)kCtxLevels; ++l) {
         uint32_t key = kNoKey;
-        if (more && d >= l + 1u && dc.k_base[l - 1u] != nullptr && dc.k_base[l - 1u][local] != kNoKey) {
-          const uint32_t rule = T.header(st[d - l]).y >> 16;
-          const uint32_t i = context_index(dc.ctx_node, dc.ctx_off[rule], dc.ctx_off[rule + 1], st[d - l - 1u]);
-          if (i == kNoKey) bad_context = 1u;
-          else {
-            local = dc.k_base[l - 1u][local] + i;
+        if (more && cidx[tid][l - 1u] != kNoKey && dc.k_base[l - 1u] != nullptr) {
+          const uint32_t kb = dc.k_base[l - 1u][local];
+          if (kb != kNoKey) {
+            local = kb + cidx[tid][l - 1u];
             key = key0 + local;
           }
         }
@@ -1088,9 +1105,6 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
         keys[tid][l] = key;
         key0 += dc.n_k[l - 1u];
       }
-      bool all_final = true;
-      for (uint32_t k = 0; k < d; ++k) all_final = all_final && T.is_final(st[k]);
-      if (all_final) can_end = 1u;
     }
     __syncthreads();
     if (bad_context) {  // a frame sits on a node that is no context of its rule: never the case for stacks the walk makes

@@ -125,6 +125,10 @@ struct DevCache {
   uint32_t n_k[kCtxLevels];  // keys of level 1, 2, ...
   const uint32_t* ctx_off;   // [n_rules+1] ranges of ctx_node: the contexts of every rule
   const uint16_t* ctx_node;  // context nodes, sorted within a rule
+  // the same relation by node: node_ctx[node_ctx_off[v] .. node_ctx_off[v + 1]) = (rule << 16 | index of v among the
+  // contexts of that rule) for every rule that v is a context of
+  const uint32_t* node_ctx_off;  // [n_nodes + 1]
+  const uint32_t* node_ctx;
   int32_t n_nodes;
 };
 constexpr uint32_t kNoAccRow = 0xFFFFu;
