@@ -131,4 +131,39 @@ def test_serving_step_full_size_every_row_of_every_state_set():
     bad = np.flatnonzero((words2 != oracle.pack_bitmask(want2)).any(axis=1))
     assert bad.size == 0, f"after one device-side decode step: rows {bad}"
     say(f"  one device-side decode step of all {work.B} rows: states equal the host's, all {work.B} next masks the oracle's")
+    # the decode cycle that bench.py times: from the start states, accept the recorded tokens of state set 3 step by
+    # step on the device and fill + apply in one launch after every step; every 8th step and the last one are
+    # compared with the oracle, mask and logits, for all rows
+    k = 3
+    tokens = work.replay_tokens(k)
+    d_tokens = torch.tensor(tokens, dtype=torch.int32, device="cuda")
+    cycle = xgm.DeviceBatch([xgm.Matcher(cache=c) for c in work.caches], history=0, stream=stream)
+    oms = [oracle.EarleyMatcher(oracle.Grammar(work.texts[b], "root")) for b in range(work.B)]
+    n_steps = tokens.shape[0]
+    checked = 0
+    for s in range(n_steps):
+        cycle.accept_tokens(d_tokens[s].data_ptr(), stream)
+        for b in range(work.B):
+            if tokens[s, b] >= 0:
+                assert oms[b].advance(toks[int(tokens[s, b])])
+        sampled = s % 8 == 7 or s == n_steps - 1
+        if sampled:
+            work.refresh_logits()
+            torch.cuda.synchronize()
+            old = view.cpu().numpy().view(np.uint16).copy()
+        d_mask2.fill_(-1)
+        cycle.fill_and_apply(d_mask2.data_ptr(), t.data_ptr(), xgm.DTYPE_BF16, V, t.stride(0), stream=stream)
+        if sampled:
+            assert not cycle.status(stream).any()
+            want_s = np.stack([om.mask(work.vocab, threads) for om in oms])
+            bad = np.flatnonzero((d_mask2.cpu().numpy() != oracle.pack_bitmask(want_s)).any(axis=1))
+            assert bad.size == 0, f"decode cycle, step {s}: rows {bad}"
+            assert np.array_equal(view.cpu().numpy().view(np.uint16), oracle.apply_mask(old, want_s, 0xFF80)), f"decode cycle, step {s}: logits"
+            checked += 1
+    # ... and it ends in state set 3
+    work.device_sets[k].fill_next_token_bitmask(work.d_mask.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert torch.equal(work.d_mask, d_mask2)
+    say(f"  decode cycle of {n_steps} steps (accept on the device, then fill + apply in one launch): {checked} sampled steps x "
+        f"{work.B} rows bit-exact against the oracle, masks and logits")
     assert xgm.overflow_total() == before
