@@ -637,7 +637,8 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     uint32_t* unc_id = keep_plain ? (c->d_unc_id = keep(slab_alloc<uint32_t>((size_t)N * dv.W))) : arena.array<uint32_t>((size_t)N * dv.W);
     // rank-space scratch for a batch of nodes (at most 1 GiB for both bitsets)
     const size_t row_bytes = (size_t)dv.WR * 4;
-    const int32_t batch = (int32_t)std::max<size_t>(1, std::min<size_t>((size_t)N, ((size_t)512 << 20) / row_bytes));
+    int32_t batch = (int32_t)std::max<size_t>(32, std::min<size_t>((size_t)N, ((size_t)512 << 20) / row_bytes));
+    if (batch < N) batch &= ~31;  // (the classify kernel wants batches of nodes to begin at multiples of 32)
     uint32_t* acc_rank = arena.array<uint32_t>((size_t)batch * dv.WR);
     uint32_t* unc_rank = arena.array<uint32_t>((size_t)batch * dv.WR);
     uint32_t* plain_rank = keep_plain ? arena.array<uint32_t>((size_t)batch * dv.WR) : nullptr;
@@ -696,10 +697,12 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     // the rank -> id permutation and the row statistics back to back and looks at the record of walks
     // over the limits only afterwards; if there are any, the patched rows are permuted again.
     const bool one_batch = batch >= N;
+    uint4* d_first_byte = arena.array<uint4>((size_t)256 * first_byte_words(N));
+    launch_first_byte(tab, d_first_byte, stream);
     for (int32_t node0 = 0; node0 < N; node0 += batch) {
       const int32_t nb = std::min(batch, N - node0);
       HIP_OK(hipEventRecord(ev0, stream));
-      launch_classify(tab, dv, node0, nb, acc_rank, unc_rank, plain_rank, d_plain_count, log, seq, stream);
+      launch_classify(tab, dv, node0, nb, d_first_byte, acc_rank, unc_rank, plain_rank, d_plain_count, log, seq, stream);
       HIP_OK(hipEventRecord(ev1, stream));
       HIP_OK(hipGetLastError());
       if (!one_batch) {

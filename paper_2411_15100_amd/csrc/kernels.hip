@@ -126,7 +126,8 @@ constexpr int kClassifyThreadsSmall = 256, kClassifyThreadsLarge = 768;
 constexpr uint32_t kClassifySmallStage = 24 * 1024;
 // nodes a thread classifies its token at, one after the other: few for small tables (more, shorter-lived
 // workgroups: the slowest walks weigh less), more where every workgroup has a large table image to stage
-constexpr int kNodesPerBlockSmall = 4, kNodesPerBlockLarge = 16;
+constexpr int kNodesPerBlockSmall = 4, kNodesPerBlockMany = 16, kNodesPerBlockLarge = 64;
+constexpr int kManyNodes = 1024;  // small tables but this many nodes: plenty of workgroups anyway
 
 // One thread owns one token (byte-sorted order, so a wave's 64 tokens are
 // neighbours in the sorted vocabulary and mostly share prefixes and control
@@ -134,8 +135,37 @@ constexpr int kNodesPerBlockSmall = 4, kNodesPerBlockLarge = 16;
 // registers.  Each wave packs its 64 results per node with a ballot into two
 // mask words of the rank-space bitsets.  The automaton tables (as many node
 // headers as `n_near`) are first copied into shared memory.
+// What the first byte of a token settles at every node, as bitsets over the nodes: for byte c and the 32 nodes
+// of word w, `x` = the node can consume c inside its frame (a walk decides), `y` = it cannot, may end its rule
+// here and c can follow that rule in some context (the token leaves the frame at position 0:
+// context-dependent), `z` = the same but c follows the rule in no context (context-dependent by section 3.1
+// alone, rejected everywhere).  One 16-byte load then tells a thread of the classify kernel what its token's
+// first byte means at 32 nodes.
+constexpr int kFirstByteThreads = 256;
+__global__ __launch_bounds__(kFirstByteThreads) void first_byte_kernel(DevTables tab, uint32_t n_words, uint4* __restrict__ out) {
+  const uint32_t t = blockIdx.x * kFirstByteThreads + threadIdx.x;
+  if (t >= 256u * n_words) return;
+  const uint32_t c = t / n_words, w = t % n_words;
+  const unsigned char* img = reinterpret_cast<const unsigned char*>(tab.image);
+  const uint2* hdr = reinterpret_cast<const uint2*>(img + tab.off_hdr);
+  const uint32_t* first = reinterpret_cast<const uint32_t*>(img + tab.off_first);
+  const uint32_t* follow = reinterpret_cast<const uint32_t*>(img + tab.off_follow);
+  uint4 q = make_uint4(0u, 0u, 0u, 0u);
+  for (uint32_t j = 0; j < 32u; ++j) {
+    const uint32_t n = w * 32u + j;
+    if (n >= (uint32_t)tab.n_nodes) break;
+    if ((first[(size_t)n * 8u + (c >> 5)] >> (c & 31)) & 1u) { q.x |= 1u << j; continue; }
+    const uint2 h = hdr[n];
+    if (!(h.y & 1u)) continue;
+    if ((follow[(h.y >> 16) * 8u + (c >> 5)] >> (c & 31)) & 1u) q.y |= 1u << j;
+    else q.z |= 1u << j;
+  }
+  out[t] = q;
+}
+
 template <int kClassifyThreads, class Tab>
 __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc, int32_t node0, int32_t n_nodes,
+                                              const uint4* __restrict__ first_byte, uint32_t n_words,
                                               uint32_t* __restrict__ acc_rank, uint32_t* __restrict__ unc_rank,
                                               uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
                                               OverflowLog* log, uint32_t seq, int32_t nodes_per_block) {
@@ -158,40 +188,38 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
   const int32_t n_end = min(n_begin + nodes_per_block, n_nodes);
   // Most pairs are settled by the token's first byte: if the node cannot
   // consume it inside its frame, the token is rejected - or, at a node where
-  // the rule may end, leaves the frame at position 0.  One bit per node of the
-  // block says whether a walk is needed at all (the loads are issued together).
-  const uint32_t c0 = tk.x & 0xFFu;
-  uint32_t needs_walk = 0u;
-  if (live_lane && len > 0)
-    for (int32_t k = n_begin; k < n_end; ++k)
-      needs_walk |= (uint32_t)T.can_start((uint32_t)(node0 + k), c0) << (k - n_begin);
-  for (int32_t k = n_begin; k < n_end; ++k) {
-    int res = kReject;
-    if (live_lane && len > 0) {
-      if ((needs_walk >> (k - n_begin)) & 1u) {
+  // the rule may end, leaves the frame at position 0.  The nodes of a block lie in whole 32-node words of
+  // the first-byte bitsets, or inside one (node0 and nodes_per_block are aligned for that).
+  for (int32_t k0 = n_begin; k0 < n_end; k0 += 32) {
+    uint4 fb = make_uint4(0u, 0u, 0u, 0u);
+    if (live_lane && len > 0) fb = first_byte[(size_t)(tk.x & 0xFFu) * n_words + ((uint32_t)(node0 + k0) >> 5)];
+    const uint32_t shift = (uint32_t)(node0 + k0) & 31u;
+    const uint32_t needs_walk = fb.x >> shift, exits_follow = fb.y >> shift, exits_plain = fb.z >> shift;
+    const int32_t k1 = min(k0 + 32 - (int32_t)shift, n_end);
+    for (int32_t k = k0; k < k1; ++k) {
+      const uint32_t bit = 1u << (k - k0);
+      int res = (exits_follow & bit) ? kUncertain : (exits_plain & bit) ? kUncertainPlain : kReject;
+      if (needs_walk & bit) {
         res = walk_token<true>(T, tk, ext, len, (uint32_t)(node0 + k), (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node0 + k));
         if (res == kOverflow) { record_overflow(log, seq, (uint32_t)k, (uint32_t)r); res = kReject; }
-      } else {
-        const uint2 h = T.header((uint32_t)(node0 + k));
-        if (h.y & 1u) res = T.can_follow(h, c0) ? kUncertain : kUncertainPlain;
       }
-    }
-    const unsigned long long a = __ballot(res == kAccept);
-    const unsigned long long u = __ballot(res == kUncertain);
-    const unsigned long long p = __ballot(res == kUncertainPlain);
-    if ((threadIdx.x & 63) == 0 && word < voc.WR) {
-      uint32_t* pa = acc_rank + (size_t)k * voc.WR + word;
-      uint32_t* pu = unc_rank + (size_t)k * voc.WR + word;
-      pa[0] = (uint32_t)a;
-      pa[1] = (uint32_t)(a >> 32);
-      pu[0] = (uint32_t)u;
-      pu[1] = (uint32_t)(u >> 32);
-      if (plain_rank) {
-        uint32_t* pp = plain_rank + (size_t)k * voc.WR + word;
-        pp[0] = (uint32_t)p;
-        pp[1] = (uint32_t)(p >> 32);
+      const unsigned long long a = __ballot(res == kAccept);
+      const unsigned long long u = __ballot(res == kUncertain);
+      const unsigned long long p = __ballot(res == kUncertainPlain);
+      if ((threadIdx.x & 63) == 0 && word < voc.WR) {
+        uint32_t* pa = acc_rank + (size_t)k * voc.WR + word;
+        uint32_t* pu = unc_rank + (size_t)k * voc.WR + word;
+        pa[0] = (uint32_t)a;
+        pa[1] = (uint32_t)(a >> 32);
+        pu[0] = (uint32_t)u;
+        pu[1] = (uint32_t)(u >> 32);
+        if (plain_rank) {
+          uint32_t* pp = plain_rank + (size_t)k * voc.WR + word;
+          pp[0] = (uint32_t)p;
+          pp[1] = (uint32_t)(p >> 32);
+        }
+        if (p) atomicAdd(&plain_count[node0 + k], (uint32_t)__popcll(p));
       }
-      if (p) atomicAdd(&plain_count[node0 + k], (uint32_t)__popcll(p));
     }
   }
 }
@@ -199,18 +227,18 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
 
 template <int kClassifyThreads>
 __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
-    DevTables tab, DevVocab voc, int32_t node0, int32_t n_nodes, uint32_t* __restrict__ acc_rank,
-    uint32_t* __restrict__ unc_rank, uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
-    OverflowLog* log, uint32_t seq, int32_t nodes_per_block) {
+    DevTables tab, DevVocab voc, int32_t node0, int32_t n_nodes, const uint4* __restrict__ first_byte, uint32_t n_words,
+    uint32_t* __restrict__ acc_rank, uint32_t* __restrict__ unc_rank, uint32_t* __restrict__ plain_rank,
+    uint32_t* __restrict__ plain_count, OverflowLog* log, uint32_t seq, int32_t nodes_per_block) {
   extern __shared__ __align__(16) unsigned char smem[];
   stage_tables(tab, smem, kClassifyThreads);
   __syncthreads();
   if (small_sections_staged(tab))
-    classify_body<kClassifyThreads>(LdsTabT<true>(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank,
-                                    plain_count, log, seq, nodes_per_block);
+    classify_body<kClassifyThreads>(LdsTabT<true>(tab, smem), voc, node0, n_nodes, first_byte, n_words, acc_rank, unc_rank,
+                                    plain_rank, plain_count, log, seq, nodes_per_block);
   else
-    classify_body<kClassifyThreads>(LdsTab(tab, smem), voc, node0, n_nodes, acc_rank, unc_rank, plain_rank, plain_count,
-                                    log, seq, nodes_per_block);
+    classify_body<kClassifyThreads>(LdsTab(tab, smem), voc, node0, n_nodes, first_byte, n_words, acc_rank, unc_rank,
+                                    plain_rank, plain_count, log, seq, nodes_per_block);
 }
 
 // Rank space -> id space: bit id of the output = bit rank_of_id[id] of the
@@ -1302,23 +1330,34 @@ hipError_t static_scratch(void** out) {
 }
 
 // ------------------------------------------------------------------ launchers
-void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, int32_t n, uint32_t* acc_rank,
-                     uint32_t* unc_rank, uint32_t* plain_rank, uint32_t* plain_count, OverflowLog* log, uint32_t seq,
-                     hipStream_t stream) {
+void launch_first_byte(const DevTables& tab, uint4* first_byte, hipStream_t stream) {
+  const uint32_t n_words = first_byte_words(tab.n_nodes);
+  if (n_words == 0) return;
+  hipLaunchKernelGGL(first_byte_kernel, dim3((256u * n_words + kFirstByteThreads - 1) / kFirstByteThreads),
+                     dim3(kFirstByteThreads), 0, stream, tab, n_words, first_byte);
+}
+
+void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, int32_t n, const uint4* first_byte,
+                     uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank, uint32_t* plain_count, OverflowLog* log,
+                     uint32_t seq, hipStream_t stream) {
   if (n <= 0 || voc.V <= 0) return;
+  static_assert(32 % kNodesPerBlockSmall == 0 && 32 % kNodesPerBlockMany == 0 && kNodesPerBlockLarge % 32 == 0,
+                "a block's nodes lie in whole words, or in one");
+  const uint32_t n_words = first_byte_words(tab.n_nodes);
   const DevTables st = staged_for(tab, kClassifyLdsBudget);
   if (st.stage_bytes <= kClassifySmallStage) {
-    const int32_t ny = (n + kNodesPerBlockSmall - 1) / kNodesPerBlockSmall;
+    const int32_t per_block = n >= kManyNodes ? kNodesPerBlockMany : kNodesPerBlockSmall;
+    const int32_t ny = (n + per_block - 1) / per_block;
     hipLaunchKernelGGL(classify_kernel<kClassifyThreadsSmall>,
                        dim3((voc.V + kClassifyThreadsSmall - 1) / kClassifyThreadsSmall, ny), dim3(kClassifyThreadsSmall),
-                       st.stage_bytes, stream, st, voc, node0, n, acc_rank, unc_rank, plain_rank, plain_count, log, seq,
-                       kNodesPerBlockSmall);
+                       st.stage_bytes, stream, st, voc, node0, n, first_byte, n_words, acc_rank, unc_rank, plain_rank,
+                       plain_count, log, seq, per_block);
   } else {
     const int32_t ny = (n + kNodesPerBlockLarge - 1) / kNodesPerBlockLarge;
     hipLaunchKernelGGL(classify_kernel<kClassifyThreadsLarge>,
                        dim3((voc.V + kClassifyThreadsLarge - 1) / kClassifyThreadsLarge, ny), dim3(kClassifyThreadsLarge),
-                       st.stage_bytes, stream, st, voc, node0, n, acc_rank, unc_rank, plain_rank, plain_count, log, seq,
-                       kNodesPerBlockLarge);
+                       st.stage_bytes, stream, st, voc, node0, n, first_byte, n_words, acc_rank, unc_rank, plain_rank,
+                       plain_count, log, seq, kNodesPerBlockLarge);
   }
 }
 

@@ -210,9 +210,15 @@ hipError_t static_scratch(void** out);
 // (a) classify tokens [all ranks] x nodes [node0, node0+n) into rank-space bitsets
 // plain_rank (may be null): tokens that are context-dependent by section 3.1 alone
 // but rejected by the one-byte context refinement; plain_count[node0 + k] += their number
-void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, int32_t n,
+// first_byte: what launch_first_byte() wrote for this grammar; node0 must be a multiple of 32
+void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, int32_t n, const uint4* first_byte,
                      uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank, uint32_t* plain_count,
                      OverflowLog* log, uint32_t seq, hipStream_t stream);
+// What a token's first byte settles at every node: first_byte[c * first_byte_words(N) + w] holds, for byte c and
+// nodes 32 w .. 32 w + 31, the bitsets {walk needed, leaves the frame at once in front of a byte that may follow
+// the rule, leaves it in front of one that may not, 0}.
+inline uint32_t first_byte_words(int32_t n_nodes) { return (uint32_t)((n_nodes + 31) / 32); }
+void launch_first_byte(const DevTables& tab, uint4* first_byte, hipStream_t stream);
 // rank space -> id space for n node rows (two bitsets per node)
 void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* a_rank, const uint32_t* b_rank,
                     uint32_t* a_id, uint32_t* b_id, hipStream_t stream);

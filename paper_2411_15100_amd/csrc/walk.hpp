@@ -140,7 +140,19 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
       uint32_t k, single, base, fin, after;
       bool pooled;
       T.lookup(n, c, k, single, base, pooled, fin, after);
-      const uint32_t can_pop = fin & f & (BUILD ? 1u : after);
+      uint32_t can_pop = fin & f;
+      if (BUILD && can_pop && sp == kLiveBase) {
+        // The start frame may end here (nothing is known below it): noted at once instead of kept as a
+        // pending alternative, so that a run through a rule that may end after every byte (the inside of
+        // a string, a number) leaves nothing to come back to.
+        left_frame = true;
+        if ((follow[c >> 5] >> (c & 31)) & 1u) {
+          left_frame_follow = true;
+          if (exits_out) *exits_out |= 1u << (i < 31 ? i : 31);
+        }
+        can_pop = 0u;
+      }
+      if (!BUILD) can_pop &= after;  // a return in front of a byte that can never follow the rule leads nowhere
       const uint32_t total = k + can_pop;
       if (alt < total) {
         bool ok = true;
@@ -168,14 +180,7 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
           if (csp == 0 || ((choice[csp - 1].y >> 16) & 0xFFu) <= old) top = old;
         } else {                       // return into a live frame
           const uint32_t d = sp - kLiveBase;
-          if (d == 0) {                // nothing below: end of the start frame (BUILD) or of the root rule
-            if (BUILD) {
-              left_frame = true;
-              if ((follow[c >> 5] >> (c & 31)) & 1u) {
-                left_frame_follow = true;
-                if (exits_out) *exits_out |= 1u << (i < 31 ? i : 31);
-              }
-            }
+          if (d == 0) {                // nothing below: the end of the root rule (BUILD notes this case above)
             ok = false;
           } else {
             n = live[d - 1];
