@@ -196,6 +196,10 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
     const uint32_t shift = (uint32_t)(node0 + k0) & 31u;
     const uint32_t needs_walk = fb.x >> shift, exits_follow = fb.y >> shift, exits_plain = fb.z >> shift;
     const int32_t k1 = min(k0 + 32 - (int32_t)shift, n_end);
+    // Lane j of the wave keeps the wave's result words for the j-th of these nodes; the lanes then write
+    // them out together (a handful of store instructions per 32 nodes instead of several per node).
+    const uint32_t lane = threadIdx.x & 63u;
+    unsigned long long keep_a = 0ull, keep_u = 0ull, keep_p = 0ull;
     for (int32_t k = k0; k < k1; ++k) {
       const uint32_t bit = 1u << (k - k0);
       int res = (exits_follow & bit) ? kUncertain : (exits_plain & bit) ? kUncertainPlain : kReject;
@@ -206,20 +210,14 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
       const unsigned long long a = __ballot(res == kAccept);
       const unsigned long long u = __ballot(res == kUncertain);
       const unsigned long long p = __ballot(res == kUncertainPlain);
-      if ((threadIdx.x & 63) == 0 && word < voc.WR) {
-        uint32_t* pa = acc_rank + (size_t)k * voc.WR + word;
-        uint32_t* pu = unc_rank + (size_t)k * voc.WR + word;
-        pa[0] = (uint32_t)a;
-        pa[1] = (uint32_t)(a >> 32);
-        pu[0] = (uint32_t)u;
-        pu[1] = (uint32_t)(u >> 32);
-        if (plain_rank) {
-          uint32_t* pp = plain_rank + (size_t)k * voc.WR + word;
-          pp[0] = (uint32_t)p;
-          pp[1] = (uint32_t)(p >> 32);
-        }
-        if (p) atomicAdd(&plain_count[node0 + k], (uint32_t)__popcll(p));
-      }
+      if (lane == (uint32_t)(k - k0)) { keep_a = a; keep_u = u; keep_p = p; }
+    }
+    if ((int32_t)lane < k1 - k0 && word < voc.WR) {
+      const size_t at = (size_t)(k0 + (int32_t)lane) * voc.WR + word;  // word is even: 8-byte aligned
+      *reinterpret_cast<uint2*>(acc_rank + at) = make_uint2((uint32_t)keep_a, (uint32_t)(keep_a >> 32));
+      *reinterpret_cast<uint2*>(unc_rank + at) = make_uint2((uint32_t)keep_u, (uint32_t)(keep_u >> 32));
+      if (plain_rank) *reinterpret_cast<uint2*>(plain_rank + at) = make_uint2((uint32_t)keep_p, (uint32_t)(keep_p >> 32));
+      if (keep_p) atomicAdd(&plain_count[node0 + k0 + (int32_t)lane], (uint32_t)__popcll(keep_p));
     }
   }
 }
