@@ -663,11 +663,13 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     uint32_t* d_seg_counts = arena.array<uint32_t>((size_t)N * n_seg);
     unsigned long long* d_digest = arena.array<unsigned long long>((size_t)N);
     uint32_t* d_unc_counts = arena.array<uint32_t>((size_t)N);
+    // rank -> id space, with the rows' statistics (accepted tokens per segment, digest, context-dependent tokens)
     auto permute = [&](int32_t node0, int32_t nb) {
-      launch_permute(dv, nb, acc_rank, unc_rank, acc_id + (size_t)node0 * dv.W, unc_id + (size_t)node0 * dv.W, stream);
+      launch_permute(dv, nb, acc_rank, unc_rank, acc_id + (size_t)node0 * dv.W, unc_id + (size_t)node0 * dv.W,
+                     d_seg_counts + (size_t)node0 * n_seg, d_digest + node0, d_unc_counts + node0, stream);
       if (keep_plain)
         launch_permute(dv, nb, plain_rank, plain_rank, c->d_plain_id + (size_t)node0 * dv.W,
-                       c->d_plain_id + (size_t)node0 * dv.W, stream);
+                       c->d_plain_id + (size_t)node0 * dv.W, nullptr, nullptr, nullptr, stream);
     };
     // Pairs whose walk hit a limit are decided on the host and patched into the rank-space rows of the
     // current batch of nodes.  Returns whether there were any.
@@ -714,7 +716,6 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       }
       permute(node0, nb);
     }
-    launch_row_stats(dv, N, acc_id, unc_id, d_seg_counts, d_digest, d_unc_counts, stream);
     HIP_OK(hipGetLastError());
     HIP_OK(hipStreamSynchronize(stream));
     if (one_batch) {
@@ -723,7 +724,6 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       c->kernel_seconds += ms * 1e-3;
       if (decide_recorded_pairs(0)) {
         permute(0, N);
-        launch_row_stats(dv, N, acc_id, unc_id, d_seg_counts, d_digest, d_unc_counts, stream);
         HIP_OK(hipGetLastError());
         HIP_OK(hipStreamSynchronize(stream));
       }

@@ -239,51 +239,6 @@ __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
                                     plain_rank, plain_count, log, seq, nodes_per_block);
 }
 
-// Rank space -> id space: bit id of the output = bit rank_of_id[id] of the
-// input.  One workgroup serves up to kPermuteNodes node rows: their rank-space
-// rows sit in LDS so that the random bit lookups never leave the CU, and the
-// id -> rank table is read once for all of them.
-constexpr int kPermuteThreads = 1024;
-constexpr int kPermuteNodes = 4;
-__global__ __launch_bounds__(kPermuteThreads) void permute_kernel(DevVocab voc, int32_t n_nodes, int32_t per_block,
-                                                                  const uint32_t* __restrict__ acc_rank,
-                                                                  const uint32_t* __restrict__ unc_rank,
-                                                                  uint32_t* __restrict__ acc_id,
-                                                                  uint32_t* __restrict__ unc_id) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  uint32_t* rows = reinterpret_cast<uint32_t*>(smem);  // [per_block][2][WR]
-  const int32_t first = blockIdx.x * per_block;
-  const int32_t nb = min(per_block, n_nodes - first);
-  for (int32_t q = 0; q < nb; ++q)
-    for (int k = threadIdx.x; k < voc.WR; k += kPermuteThreads) {
-      rows[(size_t)(2 * q) * voc.WR + k] = acc_rank[(size_t)(first + q) * voc.WR + k];
-      rows[(size_t)(2 * q + 1) * voc.WR + k] = unc_rank[(size_t)(first + q) * voc.WR + k];
-    }
-  __syncthreads();
-  const int32_t v64 = (voc.V + 63) & ~63;
-  for (int32_t id = threadIdx.x; id < v64; id += kPermuteThreads) {
-    const bool in = id < voc.V;
-    const uint32_t r = in ? (uint32_t)voc.rank_of_id[id] : 0u;
-    const int32_t w = id >> 5;
-#pragma unroll
-    for (int32_t q = 0; q < kPermuteNodes; ++q) {
-      if (q >= nb) break;
-      const bool a = in && ((rows[(size_t)(2 * q) * voc.WR + (r >> 5)] >> (r & 31)) & 1u);
-      const bool u = in && ((rows[(size_t)(2 * q + 1) * voc.WR + (r >> 5)] >> (r & 31)) & 1u);
-      const unsigned long long ba = __ballot(a), bu = __ballot(u);
-      if ((threadIdx.x & 63) == 0) {
-        const size_t node = (size_t)(first + q);
-        acc_id[node * voc.W + w] = (uint32_t)ba;
-        unc_id[node * voc.W + w] = (uint32_t)bu;
-        if (w + 1 < voc.W) {
-          acc_id[node * voc.W + w + 1] = (uint32_t)(ba >> 32);
-          unc_id[node * voc.W + w + 1] = (uint32_t)(bu >> 32);
-        }
-      }
-    }
-  }
-}
-
 // Many nodes of a grammar have the same accepted bitset (the inside of a string is
 // the inside of a string wherever it occurs), so the cache keeps every distinct
 // row once.  The digest only proposes which rows might be equal: the position-
@@ -296,36 +251,74 @@ __device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
   return x ^ (x >> 31);
 }
 constexpr int kMaxSegs = 128;  // segments of the largest vocabulary (XGM_MAX_VOCAB / kSegTokens), rounded up
-// One workgroup per node: accepted tokens per segment, digest of the accepted row, number of
-// context-dependent tokens (one pass over the node's two id-space rows).
-__global__ __launch_bounds__(kRowThreads) void row_stats_kernel(DevVocab voc, const uint32_t* __restrict__ acc_id,
-                                                                const uint32_t* __restrict__ unc_id,
-                                                                uint32_t* __restrict__ seg_counts,
-                                                                unsigned long long* __restrict__ digest,
-                                                                uint32_t* __restrict__ unc_counts) {
+
+// Rank space -> id space: bit id_of_rank[r] of the output = bit r of the input.  One workgroup per node builds
+// the node's two id-space rows in LDS.  Rows are nearly empty (most nodes reject nearly every token) or nearly
+// full (the inside of a string), so only the rarer kind of bit is moved: a row with few set bits starts as zeros
+// and gets its set bits, one with many starts as ones and gets its zeros.  With the rows still in LDS the
+// workgroup also takes their statistics (all three outputs may be null): set bits of the first row per segment,
+// its digest, and the number of set bits of the second.
+__global__ __launch_bounds__(kRowThreads) void permute_kernel(DevVocab voc, const uint32_t* __restrict__ a_rank,
+                                                              const uint32_t* __restrict__ b_rank,
+                                                              uint32_t* a_id, uint32_t* b_id,  // (may be the same row)
+                                                              uint32_t* __restrict__ seg_counts,
+                                                              unsigned long long* __restrict__ digest,
+                                                              uint32_t* __restrict__ b_counts) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint32_t* rows = reinterpret_cast<uint32_t*>(smem);  // [2][W]
+  __shared__ uint32_t set_bits[2];
   __shared__ unsigned long long part[kRowThreads / 64];
   __shared__ uint32_t seg[kMaxSegs];
-  __shared__ uint32_t unc_total;
   const size_t node = blockIdx.x;
+  const uint32_t* in[2] = {a_rank + node * voc.WR, b_rank + node * voc.WR};
+  if (threadIdx.x < 2) set_bits[threadIdx.x] = 0u;
   if (threadIdx.x < kMaxSegs) seg[threadIdx.x] = 0u;
-  if (threadIdx.x == 0) unc_total = 0u;
   __syncthreads();
-  const uint32_t* row = acc_id + node * voc.W;
-  const uint32_t* urow = unc_id + node * voc.W;
-  unsigned long long h = 0ull;
-  uint32_t u = 0u;
-  for (int32_t s = 0; s < voc.n_seg; ++s) {
-    uint32_t cnt = 0u;
-    const int32_t w_end = min((s + 1) * kSegWords, voc.W);
-    for (int32_t w = s * kSegWords + (int32_t)threadIdx.x; w < w_end; w += kRowThreads) {
-      const uint32_t x = row[w];
-      cnt += __popc(x);
-      h += mix64(((unsigned long long)(uint32_t)w << 32 | x) + 0x9E3779B97F4A7C15ull);
-      u += __popc(urow[w]);
-    }
-    if (cnt) atomicAdd(&seg[s], cnt);
+  uint32_t c0 = 0u, c1 = 0u;
+  for (int32_t k = threadIdx.x; k < voc.WR; k += kRowThreads) {
+    c0 += __popc(in[0][k]);
+    c1 += __popc(in[1][k]);
   }
-  if (u) atomicAdd(&unc_total, u);
+  if (c0) atomicAdd(&set_bits[0], c0);
+  if (c1) atomicAdd(&set_bits[1], c1);
+  __syncthreads();
+  const bool full[2] = {set_bits[0] * 2u > (uint32_t)voc.V, set_bits[1] * 2u > (uint32_t)voc.V};
+  const uint32_t tail = (voc.V & 31) ? ((1u << (voc.V & 31)) - 1u) : 0xFFFFFFFFu;  // valid bits of the last word
+  for (int32_t w = threadIdx.x; w < voc.W; w += kRowThreads) {
+    const uint32_t ones = (w == voc.W - 1) ? tail : 0xFFFFFFFFu;
+    rows[w] = full[0] ? ones : 0u;
+    rows[voc.W + w] = full[1] ? ones : 0u;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    uint32_t* row = rows + (size_t)which * voc.W;
+    for (int32_t k = threadIdx.x; k < voc.WR; k += kRowThreads) {
+      uint32_t x = in[which][k];
+      if (full[which]) {
+        x = ~x;
+        const int32_t left = voc.V - k * 32;  // ranks from V on do not exist
+        if (left < 32) x &= left > 0 ? ((1u << left) - 1u) : 0u;
+      }
+      while (x) {
+        const uint32_t b = (uint32_t)__ffs((int)x) - 1u;
+        x &= x - 1u;
+        const uint32_t id = (uint32_t)voc.id_of_rank[k * 32 + (int32_t)b];
+        if (full[which]) atomicAnd(&row[id >> 5], ~(1u << (id & 31)));
+        else atomicOr(&row[id >> 5], 1u << (id & 31));
+      }
+    }
+  }
+  __syncthreads();
+  unsigned long long h = 0ull;
+  for (int32_t w = threadIdx.x; w < voc.W; w += kRowThreads) {
+    const uint32_t x = rows[w];
+    a_id[node * voc.W + w] = x;
+    b_id[node * voc.W + w] = rows[voc.W + w];
+    if (seg_counts && x) atomicAdd(&seg[w / kSegWords], (uint32_t)__popc(x));
+    h += mix64(((unsigned long long)(uint32_t)w << 32 | x) + 0x9E3779B97F4A7C15ull);
+  }
+  if (!seg_counts) return;
 #pragma unroll
   for (uint32_t d = 32; d > 0; d >>= 1) h += __shfl_down(h, d, 64);
   if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = h;
@@ -335,7 +328,7 @@ __global__ __launch_bounds__(kRowThreads) void row_stats_kernel(DevVocab voc, co
     unsigned long long t = 0ull;
     for (int k = 0; k < kRowThreads / 64; ++k) t += part[k];
     digest[node] = t;
-    unc_counts[node] = unc_total;
+    b_counts[node] = set_bits[1];
   }
 }
 
@@ -1359,21 +1352,13 @@ void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, i
   }
 }
 
-void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* acc_rank, const uint32_t* unc_rank,
-                    uint32_t* acc_id, uint32_t* unc_id, hipStream_t stream) {
+void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* a_rank, const uint32_t* b_rank, uint32_t* a_id,
+                    uint32_t* b_id, uint32_t* seg_counts, unsigned long long* digest, uint32_t* b_counts, hipStream_t stream) {
   if (n <= 0) return;
-  const size_t row_pair = (size_t)voc.WR * 8;  // LDS bytes per node
-  int32_t per_block = (int32_t)std::min<size_t>(kPermuteNodes, std::max<size_t>(1, (size_t)(144 * 1024) / row_pair));
-  // enough workgroups to fill the device before rows are grouped
-  while (per_block > 1 && (n + per_block - 1) / per_block < 512) --per_block;
-  hipLaunchKernelGGL(permute_kernel, dim3((n + per_block - 1) / per_block), dim3(kPermuteThreads),
-                     row_pair * per_block, stream, voc, n, per_block, acc_rank, unc_rank, acc_id, unc_id);
+  hipLaunchKernelGGL(permute_kernel, dim3(n), dim3(kRowThreads), (size_t)voc.W * 8, stream, voc, a_rank, b_rank, a_id, b_id,
+                     seg_counts, digest, b_counts);
 }
 
-void launch_row_stats(const DevVocab& voc, int32_t n, const uint32_t* acc_id, const uint32_t* unc_id, uint32_t* seg_counts,
-                      unsigned long long* digest, uint32_t* unc_counts, hipStream_t stream) {
-  if (n > 0) hipLaunchKernelGGL(row_stats_kernel, dim3(n), dim3(kRowThreads), 0, stream, voc, acc_id, unc_id, seg_counts, digest, unc_counts);
-}
 void launch_rows_equal(const uint32_t* rows, int32_t n, int32_t W, const int32_t* rep, uint32_t* equal, hipStream_t stream) {
   if (n > 0) hipLaunchKernelGGL(rows_equal_kernel, dim3(n), dim3(kRowThreads), 0, stream, rows, W, rep, equal);
 }

@@ -219,14 +219,11 @@ void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, i
 // the rule, leaves it in front of one that may not, 0}.
 inline uint32_t first_byte_words(int32_t n_nodes) { return (uint32_t)((n_nodes + 31) / 32); }
 void launch_first_byte(const DevTables& tab, uint4* first_byte, hipStream_t stream);
-// rank space -> id space for n node rows (two bitsets per node)
-void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* a_rank, const uint32_t* b_rank,
-                    uint32_t* a_id, uint32_t* b_id, hipStream_t stream);
-// Per node row of the two id-space bitsets: the accepted tokens per segment (seg_counts[n][n_seg]), a
-// 64-bit digest of the accepted row (equal rows have equal digests; it only proposes which rows might
-// be equal), and the number of context-dependent tokens (unc_counts[n]).
-void launch_row_stats(const DevVocab& voc, int32_t n, const uint32_t* acc_id, const uint32_t* unc_id,
-                      uint32_t* seg_counts, unsigned long long* digest, uint32_t* unc_counts, hipStream_t stream);
+// Rank space -> id space for n node rows (two bitsets per node), and - unless the pointers are null - per node the
+// set bits of the first row per segment (seg_counts[n][n_seg]), a 64-bit digest of the first row (equal rows have
+// equal digests; it only proposes which rows might be equal) and the set bits of the second row (b_counts[n]).
+void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* a_rank, const uint32_t* b_rank, uint32_t* a_id,
+                    uint32_t* b_id, uint32_t* seg_counts, unsigned long long* digest, uint32_t* b_counts, hipStream_t stream);
 // whether row k equals row rep[k], word for word (k = 0 .. n-1); rows[unique[u]] -> out[u]
 void launch_rows_equal(const uint32_t* rows, int32_t n, int32_t W, const int32_t* rep, uint32_t* equal, hipStream_t stream);
 void launch_gather_rows(const uint32_t* rows, int32_t W, const int32_t* unique, int32_t n_unique, uint32_t* out,
