@@ -883,6 +883,19 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     args.ctx_off = d_ctx_off;
     args.ctx_node = d_ctx_node;
     args.counts = d_counts;
+    // the counting pass of level 1 keeps what it found for every (pair, context), 2 bytes each, unless that
+    // would take more than 1 GiB (then the writing pass walks again)
+    if (n_items > 0 && n_items <= ((uint64_t)1 << 29)) {
+      std::vector<uint4> node_info((size_t)N, make_uint4(0u, 0u, 0u, 0u));
+      uint64_t at = 0;
+      for (int32_t n = 0; n < N; ++n) {
+        if (c->k_base_host[0][n] == kNoKey) continue;
+        node_info[n] = make_uint4((uint32_t)at, c->unc_count[n], node_off[n], 0u);
+        at += (uint64_t)c->unc_count[n] * n_ctx(A.node_rule[n]);
+      }
+      args.node_info = arena.upload(node_info, stream);
+      args.outcomes = arena.array<uint16_t>((size_t)n_items);
+    }
     launch_exit_positions(tab, dv, args, stream);
     launch_context_lists(tab, dv, args, false, stream);
     HIP_OK(hipGetLastError());

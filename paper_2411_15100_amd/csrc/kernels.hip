@@ -428,20 +428,15 @@ __global__ __launch_bounds__(kContextThreads) void exit_positions_kernel(DevTabl
   else body(LdsTab(tab, smem));
 }
 
-// What the list kernels share: the token of one pair, how its entries reach the lists, and one (pair,
-// context) step: the rest of the token after it has left the frame above at the positions `ex`, walked
-// from context node r.
-template <bool WRITE, class Tab>
-struct ContextWork {
-  const Tab& T;
+// How an entry reaches its list, counting or writing.
+template <bool WRITE>
+struct ListSink {
   const DevVocab& voc;
   const ContextListArgs& a;
-  uint32_t e, id;
-  TokenRef t;
   // One entry for list `key`.  The lanes of a wave that get here together mostly add to the same list (they hold
   // neighbouring tokens of one node and look at the same context): they are served by one atomic per
   // distinct (list, segment, accepted or not) among them instead of one each - atomics on one address queue up.
-  __device__ __forceinline__ void emit(uint32_t key, uint32_t kind, uint32_t pos) const {
+  __device__ __forceinline__ void emit(uint32_t id, uint32_t key, uint32_t kind, uint32_t pos) const {
     const uint32_t slot = key * (uint32_t)voc.n_seg + id / (uint32_t)kSegTokens;
     const uint32_t tag = (slot << 1) | (kind == kEntryAccepted ? 0u : 1u);
     const uint32_t lane = threadIdx.x & 63u;
@@ -464,6 +459,24 @@ struct ContextWork {
       }
     }
   }
+};
+__device__ __forceinline__ uint32_t outcome_code(uint32_t kind, uint32_t pos) { return (kind + 1u) | (pos << 8); }
+
+// What the list kernels share: the token of one pair, how its entries reach the lists, and one (pair,
+// context) step: the rest of the token after it has left the frame above at the positions `ex`, walked
+// from context node r.
+template <bool WRITE, class Tab>
+struct ContextWork {
+  const Tab& T;
+  const DevVocab& voc;
+  const ContextListArgs& a;
+  uint32_t e, id;
+  TokenRef t;
+  // (`outcome`, if not null, also receives what was emitted, as a code)
+  __device__ __forceinline__ void emit(uint32_t key, uint32_t kind, uint32_t pos, uint32_t* outcome) const {
+    ListSink<WRITE>{voc, a}.emit(id, key, kind, pos);
+    if (outcome) *outcome = outcome_code(kind, pos);
+  }
   // can the rest of the token from position k on do anything at all at node r?  (its first byte is
   // consumed there, or r may end its rule in front of a byte that can follow the rule)
   __device__ __forceinline__ bool plausible(uint32_t r, uint32_t k) const {
@@ -474,12 +487,13 @@ struct ContextWork {
   }
   // Level `level` (1-based), context node r, whose key is `key_local` among its level's keys.  `single`:
   // every frame so far was left at exactly one position.
-  __device__ __forceinline__ void step(uint32_t level, uint32_t r, uint32_t key_local, uint32_t ex, bool single) const {
+  __device__ __forceinline__ void step(uint32_t level, uint32_t r, uint32_t key_local, uint32_t ex, bool single,
+                                       uint32_t* outcome = nullptr) const {
     const uint32_t key = a.key0[level - 1u] + key_local;
     // how a token that needs the live stack after all is listed here: from the frame of r on, if the way there is unique
     const uint32_t walk_kind = single ? kEntryWalkTop + level : kEntryWalkTop;
     const uint32_t walk_pos = single ? (uint32_t)__ffs(ex) - 1u : 0u;
-    if (ex & 0x80000000u) { emit(key, kEntryWalkTop, 0u); return; }
+    if (ex & 0x80000000u) { emit(key, kEntryWalkTop, 0u, outcome); return; }
     bool accepted = false, over = false;
     uint32_t ex_next = 0u, n_res = 0u;
     for (uint32_t m = ex; m != 0u && !accepted; m &= m - 1u) {
@@ -491,11 +505,11 @@ struct ContextWork {
       else if (res == kOverflow) over = true;
       else if (res == kUncertain) { ex_next |= x; ++n_res; }
     }
-    if (accepted) { emit(key, kEntryAccepted, 0u); return; }
-    if (over) { emit(key, kEntryWalkTop, 0u); return; }
+    if (accepted) { emit(key, kEntryAccepted, 0u, outcome); return; }
+    if (over) { emit(key, kEntryWalkTop, 0u, outcome); return; }
     if (ex_next == 0u) return;  // rejected in this context
     if (level == (uint32_t)kCtxLevels || a.k_base[level] == nullptr || (ex_next & 0x80000000u)) {
-      emit(key, walk_kind, walk_pos);
+      emit(key, walk_kind, walk_pos, outcome);
       return;
     }
     // it leaves this frame as well: a record for the next level
@@ -523,7 +537,13 @@ __device__ __forceinline__ void context_level1_body(const Tab& T, const DevVocab
   const uint32_t cb = a.ctx_off[T.header(node).y >> 16];
   const uint32_t k1b = a.k_base[0][node];
   const bool single0 = (ex0 & (ex0 - 1u)) == 0u;
-  for (uint32_t i = i0; i < i1; ++i) w.step(1u, a.ctx_node[cb + i], k1b + i, ex0, single0);
+  const bool keep = !WRITE && a.outcomes != nullptr;
+  const uint4 info = keep ? a.node_info[node] : make_uint4(0u, 0u, 0u, 0u);
+  for (uint32_t i = i0; i < i1; ++i) {
+    uint32_t outcome = 0u;
+    w.step(1u, a.ctx_node[cb + i], k1b + i, ex0, single0, keep ? &outcome : nullptr);
+    if (keep) a.outcomes[(size_t)info.x + (size_t)i * info.y + (e - info.z)] = (uint16_t)outcome;
+  }
 }
 template <bool WRITE>
 __global__ __launch_bounds__(kContextThreads) void context_level1_kernel(DevTables tab, DevVocab voc, ContextListArgs a) {
@@ -533,6 +553,20 @@ __global__ __launch_bounds__(kContextThreads) void context_level1_kernel(DevTabl
   __syncthreads();
   if (small_sections_staged(tab)) context_level1_body<WRITE>(LdsTabT<true>(tab, smem), voc, a, tile);
   else context_level1_body<WRITE>(LdsTab(tab, smem), voc, a, tile);
+}
+// The writing pass of level 1 when the counting pass kept its outcomes: the same tiles, no walks, no tables.
+__global__ __launch_bounds__(kContextThreads) void context_level1_write_kernel(DevVocab voc, ContextListArgs a) {
+  const uint4 tile = a.tiles[blockIdx.x];
+  if (threadIdx.x >= (tile.y & 0xFFFFu)) return;
+  const uint32_t e = tile.x + threadIdx.x, node = tile.w, i0 = tile.z, i1 = tile.z + (tile.y >> 16);
+  const uint32_t id = a.base_ids[e];
+  const uint32_t k1b = a.key0[0] + a.k_base[0][node];
+  const uint4 info = a.node_info[node];
+  const ListSink<true> sink{voc, a};
+  for (uint32_t i = i0; i < i1; ++i) {
+    const uint32_t code = a.outcomes[(size_t)info.x + (size_t)i * info.y + (e - info.z)];
+    if (code) sink.emit(id, k1b + i, (code & 0xFFu) - 1u, code >> 8);
+  }
 }
 
 // Level `level` >= 2: a fixed grid walks over (record of level - 1, chunk of kContextsPerThread contexts);
@@ -1386,10 +1420,16 @@ void launch_exit_positions(const DevTables& tab, const DevVocab& voc, const Cont
 void launch_context_lists(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, bool write, hipStream_t stream) {
   if (args.total == 0 || args.n_tiles == 0) return;
   const DevTables st = staged_for(tab, kClassifyLdsBudget);
-  (void)hipMemsetAsync(args.res_count, 0, 4 * kCtxLevels, stream);
   const dim3 g1(args.n_tiles), g2(1024);
-  if (write) hipLaunchKernelGGL(context_level1_kernel<true>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
-  else hipLaunchKernelGGL(context_level1_kernel<false>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+  if (write && args.outcomes) {
+    // level 1 from the kept outcomes; its records for level 2 are still there from the counting pass
+    (void)hipMemsetAsync(args.res_count + 1, 0, 4 * (kCtxLevels - 1), stream);
+    hipLaunchKernelGGL(context_level1_write_kernel, g1, dim3(kContextThreads), 0, stream, voc, args);
+  } else {
+    (void)hipMemsetAsync(args.res_count, 0, 4 * kCtxLevels, stream);
+    if (write) hipLaunchKernelGGL(context_level1_kernel<true>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+    else hipLaunchKernelGGL(context_level1_kernel<false>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+  }
   for (uint32_t level = 2; level <= (uint32_t)kCtxLevels && args.k_base[level - 1] != nullptr; ++level) {
     if (write) hipLaunchKernelGGL(context_deeper_kernel<true>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args, level);
     else hipLaunchKernelGGL(context_deeper_kernel<false>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args, level);

@@ -14,7 +14,7 @@ constexpr int kChoicePoints = 24;   // pending alternatives
 constexpr int kMaxSteps = 4096;     // automaton steps per (position, token)
 constexpr int kMaxTokenLen = 255;   // bytes
 
-// ---- id space is cut into segments of 32768 tokens = 1024 mask words; one
+// ---- id space is cut into segments of 8192 tokens = 256 mask words; one
 // workgroup of the fill kernel owns one (row, segment)
 constexpr int kSegWords = 256;
 constexpr int kSegTokens = kSegWords * 32;
@@ -267,6 +267,12 @@ struct ContextListArgs {
   uint32_t* front;             // [n_keys * n_seg]   write = true
   uint32_t* back;              // [n_keys * n_seg]   write = true
   uint32_t* entries;
+  // What the level-1 kernel found for every (pair, context) when it counted, kept so that the writing pass
+  // need not walk again (null: it walks again).  node_info[n] = {first outcome of node n, its pairs L, its
+  // first pair, 0}; the outcome of pair e and context i of node n is outcomes[info.x + i * L + (e - info.z)]:
+  // 0 = no entry, else (kind + 1) | pos << 8.
+  const uint4* node_info;
+  uint16_t* outcomes;
 };
 void launch_exit_positions(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, hipStream_t stream);
 void launch_context_lists(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, bool write, hipStream_t stream);
