@@ -868,7 +868,9 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     args.exits = d_exits;
     args.tiles = arena.upload(tiles, stream);
     args.n_tiles = (uint32_t)tiles.size();
-    args.res_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>(n_base / 2, 1u << 16), 1u << 24);
+    // (a pair leaves at most about one record per level on the grammars measured: 0.02 per pair for schema
+    // grammars, 0.8 for a C-like one; the pass is run again with more room if this is not enough)
+    args.res_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>(n_base, 1u << 16), 1u << 25);
     for (int l = 0; l + 1 < c->levels; ++l) args.res[l] = arena.array<uint4>(args.res_cap);
     args.res_count = arena.array<uint32_t>(kCtxLevels);
     args.max_ctx = max_ctx;
