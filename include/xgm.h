@@ -205,6 +205,12 @@ double xgm_cache_build_kernel_seconds(const xgm_cache* c);
  * the copies of sizes back to the host, allocation; the vocabulary upload only
  * on the first build that uses it). */
 double xgm_cache_build_seconds(const xgm_cache* c);
+/* The part of those seconds that the classification of section 3.1 took: from the start of the call until
+ * every node's accepted and context-dependent tokens lie in id-space bitsets on the device and their
+ * per-node statistics on the host (first-byte bitsets, classification kernel, rank -> id permutation with
+ * the row statistics, one synchronisation).  The rest of the call resolves the context-dependent tokens
+ * per call site (section 3.2) and lays out the lists. */
+double xgm_cache_build_classify_seconds(const xgm_cache* c);
 /* Section 3.1 (storage of the cache): number of distinct accepted bitsets kept (nodes with few accepted
  * tokens keep a list instead and are not counted), and the bytes of device memory the cache holds
  * (bitsets, lists, offsets, table image).  Negative: error. */

@@ -53,6 +53,7 @@ SIGNATURES = {
     "xgm_cache_host_classified": (_i64, [_vp]),
     "xgm_cache_build_kernel_seconds": (ctypes.c_double, [_vp]),
     "xgm_cache_build_seconds": (ctypes.c_double, [_vp]),
+    "xgm_cache_build_classify_seconds": (ctypes.c_double, [_vp]),
     "xgm_cache_num_accept_rows": (_i32, [_vp]),
     "xgm_cache_device_bytes": (ctypes.c_int64, [_vp]),
     "xgm_cache_stats": (_i32, [_vp, _vp]),
@@ -290,6 +291,11 @@ class Cache:
     @property
     def build_seconds(self) -> float:
         return load_library().xgm_cache_build_seconds(self._h)
+
+    @property
+    def build_classify_seconds(self) -> float:
+        """The part of build_seconds spent until the section 3.1 classes of every node were known."""
+        return load_library().xgm_cache_build_classify_seconds(self._h)
 
     @property
     def num_accept_rows(self) -> int:

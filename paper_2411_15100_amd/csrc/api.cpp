@@ -215,6 +215,7 @@ struct xgm_cache {
   int64_t host_classified = 0;
   double kernel_seconds = 0.0;
   double build_seconds = 0.0;
+  double classify_seconds = 0.0;
 };
 struct xgm_matcher {
   xgm_cache* c = nullptr;
@@ -745,6 +746,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     HIP_OK(hipMemcpy(c->unc_count.data(), d_unc_counts, (size_t)N * 4, hipMemcpyDeviceToHost));
     HIP_OK(hipMemcpy(c->plain_count.data(), d_plain_count, (size_t)N * 4, hipMemcpyDeviceToHost));
     for (int32_t n : host_plain) ++c->plain_count[n];
+    c->classify_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_build0).count();
 
     // ---- accepted tokens: a node with few of them keeps a list (its level-0 key), the others a bitset row;
     // every distinct row is kept once (rows with equal digests are compared with the first of them)
@@ -1030,6 +1032,7 @@ int xgm_cache_copy_node_plain(const xgm_cache* c, int32_t node, int32_t* h_plain
 int64_t xgm_cache_host_classified(const xgm_cache* c) { return c ? c->host_classified : XGM_ERR_BAD_ARG; }
 double xgm_cache_build_kernel_seconds(const xgm_cache* c) { return c ? c->kernel_seconds : -1.0; }
 double xgm_cache_build_seconds(const xgm_cache* c) { return c ? c->build_seconds : -1.0; }
+double xgm_cache_build_classify_seconds(const xgm_cache* c) { return c ? c->classify_seconds : -1.0; }
 int32_t xgm_cache_num_accept_rows(const xgm_cache* c) { return c ? c->n_acc_rows : XGM_ERR_BAD_ARG; }
 int64_t xgm_cache_device_bytes(const xgm_cache* c) { return c ? c->device_bytes : XGM_ERR_BAD_ARG; }
 
