@@ -211,6 +211,10 @@ double xgm_cache_build_seconds(const xgm_cache* c);
  * the row statistics, one synchronisation).  The rest of the call resolves the context-dependent tokens
  * per call site (section 3.2) and lays out the lists. */
 double xgm_cache_build_classify_seconds(const xgm_cache* c);
+/* Test knob: the following builds classify their nodes in batches of `nodes` (rounded down to a multiple of
+ * 32, at least 32) instead of all at once; 0 restores the default (as many nodes as 1 GiB of rank-space rows
+ * holds: every grammar of this repository in one batch).  The caches built are the same. */
+void xgm_debug_set_build_batch_nodes(int32_t nodes);
 /* Section 3.1 (storage of the cache): number of distinct accepted bitsets kept (nodes with few accepted
  * tokens keep a list instead and are not counted), and the bytes of device memory the cache holds
  * (bitsets, lists, offsets, table image).  Negative: error. */

@@ -54,6 +54,7 @@ SIGNATURES = {
     "xgm_cache_build_kernel_seconds": (ctypes.c_double, [_vp]),
     "xgm_cache_build_seconds": (ctypes.c_double, [_vp]),
     "xgm_cache_build_classify_seconds": (ctypes.c_double, [_vp]),
+    "xgm_debug_set_build_batch_nodes": (None, [ctypes.c_int32]),
     "xgm_cache_num_accept_rows": (_i32, [_vp]),
     "xgm_cache_device_bytes": (ctypes.c_int64, [_vp]),
     "xgm_cache_stats": (_i32, [_vp, _vp]),
@@ -483,6 +484,11 @@ def debug_fill_count_steps(batch: "MatcherBatch", d_bitmask: int, stream: int = 
     _check(load_library().xgm_debug_fill_count_steps(batch._arr, len(batch.matchers), ctypes.c_void_p(d_bitmask),
                                                      ctypes.c_void_p(stream), ctypes.byref(n)))
     return int(n.value)
+
+
+def debug_set_build_batch_nodes(nodes: int) -> None:
+    """Test knob: the following cache builds classify `nodes` nodes per batch (0: the default, all at once)."""
+    load_library().xgm_debug_set_build_batch_nodes(int(nodes))
 
 
 def debug_lds_lookup_rate(stream: int = 0) -> float:

@@ -576,6 +576,11 @@ int xgm_debug_matcher_accept_token_walk(xgm_matcher* m, int32_t token_id) {
 }
 
 // --------------------------------------------------------------------- cache
+namespace {
+std::atomic<int32_t> g_build_batch_nodes{0};  // test knob: nodes classified per batch (0: as many as 1 GiB of rows holds)
+}
+void xgm_debug_set_build_batch_nodes(int32_t nodes) { g_build_batch_nodes = nodes > 0 ? nodes : 0; }
+
 int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out) {
   return xgm_cache_build_ex(g, v, hip_stream, 0, out);
 }
@@ -639,6 +644,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     // rank-space scratch for a batch of nodes (at most 1 GiB for both bitsets)
     const size_t row_bytes = (size_t)dv.WR * 4;
     int32_t batch = (int32_t)std::max<size_t>(32, std::min<size_t>((size_t)N, ((size_t)512 << 20) / row_bytes));
+    if (g_build_batch_nodes > 0) batch = std::max(32, std::min(N, g_build_batch_nodes.load()));
     if (batch < N) batch &= ~31;  // (the classify kernel wants batches of nodes to begin at multiples of 32)
     uint32_t* acc_rank = arena.array<uint32_t>((size_t)batch * dv.WR);
     uint32_t* unc_rank = arena.array<uint32_t>((size_t)batch * dv.WR);

@@ -184,6 +184,39 @@ def test_workload4_cache_build_json_all_nodes(xgm, wl, no_overflow):
         f"context-dependent pairs {n1 + n4} by section 3.1, {n1} after the one-byte narrowing")
 
 
+def test_cache_build_in_batches_of_nodes_gives_the_same_classes(xgm, wl):
+    """A grammar too large for one batch of rank-space rows is classified batch after batch; forced here with 32
+    nodes per batch.  The markup grammar also has walks over the on-chip limits, which are then decided on the
+    host per batch."""
+    say("cache build in batches of 32 nodes: JSON (every node) and markup (a seeded sample), V=32000")
+    vocab = si.make_vocab("bpe", 32000, 0)
+    xv = wl.make_xgm_vocab(vocab)
+    xgm.debug_set_build_batch_nodes(32)
+    try:
+        for text, count in ((si.JSON_GRAMMAR, None), (si.XML_GRAMMAR, 24)):
+            g = xgm.Grammar(text, "root")
+            assert g.num_nodes > 64
+            before = xgm.overflow_total()
+            cache = xgm.Cache(g, xv, keep_plain=True)
+            assert cache.host_classified == xgm.overflow_total() - before
+            og = oracle.Grammar(text, "root")
+            nodes = range(g.num_nodes) if count is None else sorted(
+                int(n) for n in np.random.Generator(np.random.PCG64(9)).choice(g.num_nodes, size=count, replace=False))
+            n1, n4 = _check_cache_classes(xgm, cache, g, og, vocab, nodes)
+            # and the masks that come out of such a cache
+            m = xgm.Matcher(cache=cache)
+            om = oracle.EarleyMatcher(og)
+            d_mask = torch.zeros(1, xgm.bitmask_words(vocab.size), dtype=torch.int32, device="cuda")
+            xgm.fill_next_token_bitmask([m], d_mask.data_ptr(), _stream())
+            xgm.fill_overflow_fixup(_stream())
+            torch.cuda.synchronize()
+            assert np.array_equal(d_mask.cpu().numpy(), oracle.pack_bitmask(om.mask(vocab))[None, :])
+            say(f"  {g.num_nodes} nodes in {-(-g.num_nodes // 32)} batches: classes of {len(nodes)} nodes and the first mask "
+                f"bit-exact ({cache.host_classified} pairs decided on the host)")
+    finally:
+        xgm.debug_set_build_batch_nodes(0)
+
+
 def test_workload4_cache_build_csql_sample(xgm, wl):
     say("workload 4(ii): C/SQL-like cache, V=128256, 8 % of the nodes (the longest lists + a seeded sample)")
     vocab = si.make_vocab("bpe", 128256, 0)
