@@ -11,6 +11,7 @@
         runs: the figures are dropped (null) once a kernel has changed.  The counters are in KiB per
         dispatch and are scaled by what they read for a plain copy of known size in the same run
         (torch's bf16 <- fp32 copy of the logits buffers: 4 bytes read and 2 written per element).
+        "-" as <traffic.json> writes the text only (runs of other workloads than the serving step).
 """
 
 from __future__ import annotations
@@ -106,9 +107,10 @@ def counters(out: str, traffic_json: str, note: str, runs):
                 text.append(f"# {key}: fetched {f_[0][1] * f_scale * 1024 / 1e6:.2f} MB + written {w_[0][1] * 1024 / 1e6:.2f} MB per launch")
     with open(out, "w") as f:
         f.write("\n".join(text) + "\n")
-    with open(traffic_json, "w") as f:
-        json.dump(traffic, f, indent=1)
-        f.write("\n")
+    if traffic_json != "-":
+        with open(traffic_json, "w") as f:
+            json.dump(traffic, f, indent=1)
+            f.write("\n")
     print("\n".join(text))
 
 
