@@ -512,17 +512,31 @@ struct ContextWork {
       emit(key, walk_kind, walk_pos, outcome);
       return;
     }
-    // it leaves this frame as well: a record for the next level
+    // It leaves this frame as well: records for the next level, one per chunk of kContextsPerThread contexts
+    // of this context node's rule (a rule without contexts has nothing below it: the token ends there).
+    // The lanes that get here together are taken rule by rule, each group with one atomic.
     const uint32_t rule = T.header(r).y >> 16;
+    const uint32_t n_ch = (a.ctx_off[rule + 1] - a.ctx_off[rule] + kContextsPerThread - 1u) / kContextsPerThread;
     const bool single_next = single && n_res == 1u && (ex_next & (ex_next - 1u)) == 0u;
     const uint32_t lane = threadIdx.x & 63u;
-    const unsigned long long peers = __ballot(true);
-    const uint32_t n = (uint32_t)__popcll(peers), rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
-    const int first = __ffsll((long long)peers) - 1;
-    uint32_t base = 0u;
-    if (rank == 0u) base = atomicAdd(&a.res_count[level - 1u], n);
-    base = __shfl(base, first, 64);
-    if (base + rank < a.res_cap) a.res[level - 1u][base + rank] = make_uint4(e, key_local, ex_next, rule | (single_next ? 0x10000u : 0u));
+    for (bool pending = true; pending;) {
+      const uint32_t lead = __builtin_amdgcn_readfirstlane(rule);
+      const bool mine = rule == lead;
+      const unsigned long long peers = __ballot(mine);
+      if (mine) {
+        if (n_ch != 0u) {
+          const uint32_t n = (uint32_t)__popcll(peers), rank = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+          const int first = __ffsll((long long)peers) - 1;
+          uint32_t base = 0u;
+          if (rank == 0u) base = atomicAdd(&a.res_count[level - 1u], n * n_ch);
+          base = __shfl(base, first, 64) + rank * n_ch;
+          for (uint32_t ch = 0; ch < n_ch; ++ch)
+            if (base + ch < a.res_cap)
+              a.res[level - 1u][base + ch] = make_uint4(e, key_local, ex_next, rule | (single_next ? 0x10000u : 0u) | (ch << 17));
+        }
+        pending = false;
+      }
+    }
   }
 };
 
@@ -569,21 +583,17 @@ __global__ __launch_bounds__(kContextThreads) void context_level1_write_kernel(D
   }
 }
 
-// Level `level` >= 2: a fixed grid walks over (record of level - 1, chunk of kContextsPerThread contexts);
-// consecutive threads hold consecutive records (neighbouring tokens of one node and context, as a rule)
-// and the same chunk.
+// Level `level` >= 2: a fixed grid walks over the records of level - 1, each of which names a chunk of
+// kContextsPerThread contexts; consecutive threads hold consecutive records (neighbouring tokens of one
+// node and context, as a rule).
 template <bool WRITE, class Tab>
 __device__ __forceinline__ void context_deeper_body(const Tab& T, const DevVocab& voc, const ContextListArgs& a, uint32_t level) {
   const uint32_t n_res = min(a.res_count[level - 2u], a.res_cap);
-  const uint32_t n_chunks = (a.max_ctx + kContextsPerThread - 1u) / kContextsPerThread;
-  const uint64_t n_items = (uint64_t)n_res * n_chunks;
-  for (uint64_t item = (uint64_t)blockIdx.x * kContextThreads + threadIdx.x; item < n_items; item += (uint64_t)gridDim.x * kContextThreads) {
-    const uint32_t r = (uint32_t)(item % n_res), jc = (uint32_t)(item / n_res);
-    const uint4 rec = a.res[level - 2u][r];
+  for (uint32_t item = blockIdx.x * kContextThreads + threadIdx.x; item < n_res; item += gridDim.x * kContextThreads) {
+    const uint4 rec = a.res[level - 2u][item];
     const uint32_t rule = rec.w & 0xFFFFu;
     const uint32_t cb = a.ctx_off[rule], m = a.ctx_off[rule + 1] - cb;
-    const uint32_t j0 = jc * kContextsPerThread;
-    if (j0 >= m) continue;
+    const uint32_t j0 = (rec.w >> 17) * kContextsPerThread;
     const uint32_t id = a.base_ids[rec.x];
     const ContextWork<WRITE, Tab> w{T, voc, a, rec.x, id, load_token(voc, (int32_t)id)};
     const uint32_t kb = a.k_base[level - 1u][rec.y];

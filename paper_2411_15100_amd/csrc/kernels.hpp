@@ -245,9 +245,11 @@ void launch_rows_to_lists(const DevVocab& voc, int32_t n, const uint32_t* rows, 
 // tiles: the work of the level-1 kernel, one workgroup each: x = first pair, y = pairs (at most
 // context_tile_pairs(), all of one node) | contexts << 16 (at most context_tile_contexts()), z = first
 // context, w = the node.  res[l] / res_cap / res_count[l]: records of the (pair, key of level l + 1) that
-// leave one more frame, made by the kernel of level l + 1 for the kernel of level l + 2; a record that does
-// not fit is dropped and counted all the same (the caller then runs the pass again with more room).
-// max_ctx: the most contexts any rule has.
+// leave one more frame, made by the kernel of level l + 1 for the kernel of level l + 2 - one record for
+// every chunk of context_tile_contexts() contexts of the rule whose frame comes next: x = pair, y = number of
+// the key among its level's keys, z = the positions at which the frame is left, w = that rule | the way so
+// far is unique << 16 | chunk << 17; a record that does not fit is dropped and counted all the same (the
+// caller then runs the pass again with more room).
 struct ContextListArgs {
   const uint16_t* base_node;
   const uint32_t* base_ids;
@@ -258,7 +260,6 @@ struct ContextListArgs {
   uint4* res[kCtxLevels];      // (the last one is not used)
   uint32_t res_cap;
   uint32_t* res_count;         // [kCtxLevels]
-  uint32_t max_ctx;
   const uint32_t* k_base[kCtxLevels];
   uint32_t key0[kCtxLevels];   // the first key of level 1, 2, ... in the shared numbering
   const uint32_t* ctx_off;
