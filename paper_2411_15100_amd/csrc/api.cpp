@@ -851,7 +851,10 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       std::iota(identity.begin(), identity.end(), 0u);
       uint32_t* d_identity = arena.upload(identity, stream);
       uint32_t* d_cursor = arena.upload(node_off, stream);
-      launch_rows_to_lists(dv, N, unc_id, d_identity, 1, d_cursor, d_base_ids, d_base_node, stream);
+      // In byte-sorted order where the rank-space rows of all nodes are still there (one batch): the walks of
+      // neighbouring lanes then share prefixes, as in the classify kernel.
+      if (one_batch) launch_rows_to_lists(unc_rank, dv.WR, dv.id_of_rank, N, d_identity, 1, d_cursor, d_base_ids, d_base_node, stream);
+      else launch_rows_to_lists(unc_id, dv.W, nullptr, N, d_identity, 1, d_cursor, d_base_ids, d_base_node, stream);
     }
     uint32_t* d_counts = arena.array<uint32_t>(n_slots);
     HIP_OK(hipMemsetAsync(d_counts, 0, n_slots * 4, stream));
@@ -971,7 +974,7 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       std::vector<uint32_t> list_key((size_t)N);
       for (int32_t n = 0; n < N; ++n) list_key[n] = as_list[n] ? (uint32_t)n : kNoKey;
       uint32_t* d_list_key = arena.upload(list_key, stream);
-      launch_rows_to_lists(dv, N, acc_id, d_list_key, n_seg, d_front, d_entries, nullptr, stream);
+      launch_rows_to_lists(acc_id, dv.W, nullptr, N, d_list_key, n_seg, d_front, d_entries, nullptr, stream);
       args.front = d_front;
       args.back = d_back;
       args.entries = d_entries;

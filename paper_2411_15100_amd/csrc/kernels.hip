@@ -332,10 +332,12 @@ __global__ __launch_bounds__(kRowThreads) void permute_kernel(DevVocab voc, cons
   }
 }
 
-// Bitset rows -> lists of token ids through cursors.  One workgroup per (segment, row); a thread takes
-// four words; a wave reserves room for all its tokens with one atomic.
+// Bitset rows (row_words words each) -> lists through cursors.  One workgroup per (segment, row); a thread
+// takes four words; a wave reserves room for all its tokens with one atomic.  What is listed for bit v is
+// map[v] if a map is given (rank-space rows: the token ids, in byte-sorted order within a segment), else v.
 constexpr int kListThreads = kSegWords / 4;
-__global__ __launch_bounds__(kListThreads) void rows_to_lists_kernel(DevVocab voc, const uint32_t* __restrict__ rows,
+__global__ __launch_bounds__(kListThreads) void rows_to_lists_kernel(const uint32_t* __restrict__ rows, int32_t row_words,
+                                                                     const int32_t* __restrict__ map,
                                                                      const uint32_t* __restrict__ cursor_of, int32_t per_row,
                                                                      uint32_t* __restrict__ cursor, uint32_t* __restrict__ out,
                                                                      uint16_t* __restrict__ out_row, int32_t row0) {
@@ -348,7 +350,7 @@ __global__ __launch_bounds__(kListThreads) void rows_to_lists_kernel(DevVocab vo
   uint32_t n = 0u;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    bits[k] = w0 + k < voc.W ? rows[r * voc.W + w0 + k] : 0u;
+    bits[k] = w0 + k < row_words ? rows[r * (size_t)row_words + w0 + k] : 0u;
     n += __popc(bits[k]);
   }
   // exclusive prefix of n over the wave, and the wave's total
@@ -372,7 +374,8 @@ __global__ __launch_bounds__(kListThreads) void rows_to_lists_kernel(DevVocab vo
       const uint32_t b = __ffs(x) - 1;
       x &= x - 1;
       if (out_row) out_row[pos] = (uint16_t)(row0 + (int32_t)r);
-      out[pos++] = (uint32_t)(w0 + k) * 32u + b;
+      const uint32_t v = (uint32_t)(w0 + k) * 32u + b;
+      out[pos++] = map ? (uint32_t)map[v] : v;
     }
   }
 }
@@ -472,9 +475,12 @@ struct ContextWork {
   const ContextListArgs& a;
   uint32_t e, id;
   TokenRef t;
-  // (`outcome`, if not null, also receives what was emitted, as a code)
-  __device__ __forceinline__ void emit(uint32_t key, uint32_t kind, uint32_t pos, uint32_t* outcome) const {
-    ListSink<WRITE>{voc, a}.emit(id, key, kind, pos);
+  // (`outcome`, if not null, also receives what was emitted, as a code; `lds_counts`, if not null, are the
+  // workgroup's own counters per segment for this list: the entry is then only counted there)
+  __device__ __forceinline__ void emit(uint32_t key, uint32_t kind, uint32_t pos, uint32_t* outcome,
+                                       uint32_t* lds_counts) const {
+    if (!WRITE && lds_counts) atomicAdd(&lds_counts[id / (uint32_t)kSegTokens], 1u);
+    else ListSink<WRITE>{voc, a}.emit(id, key, kind, pos);
     if (outcome) *outcome = outcome_code(kind, pos);
   }
   // can the rest of the token from position k on do anything at all at node r?  (its first byte is
@@ -488,12 +494,12 @@ struct ContextWork {
   // Level `level` (1-based), context node r, whose key is `key_local` among its level's keys.  `single`:
   // every frame so far was left at exactly one position.
   __device__ __forceinline__ void step(uint32_t level, uint32_t r, uint32_t key_local, uint32_t ex, bool single,
-                                       uint32_t* outcome = nullptr) const {
+                                       uint32_t* outcome = nullptr, uint32_t* lds_counts = nullptr) const {
     const uint32_t key = a.key0[level - 1u] + key_local;
     // how a token that needs the live stack after all is listed here: from the frame of r on, if the way there is unique
     const uint32_t walk_kind = single ? kEntryWalkTop + level : kEntryWalkTop;
     const uint32_t walk_pos = single ? (uint32_t)__ffs(ex) - 1u : 0u;
-    if (ex & 0x80000000u) { emit(key, kEntryWalkTop, 0u, outcome); return; }
+    if (ex & 0x80000000u) { emit(key, kEntryWalkTop, 0u, outcome, lds_counts); return; }
     bool accepted = false, over = false;
     uint32_t ex_next = 0u, n_res = 0u;
     for (uint32_t m = ex; m != 0u && !accepted; m &= m - 1u) {
@@ -505,11 +511,11 @@ struct ContextWork {
       else if (res == kOverflow) over = true;
       else if (res == kUncertain) { ex_next |= x; ++n_res; }
     }
-    if (accepted) { emit(key, kEntryAccepted, 0u, outcome); return; }
-    if (over) { emit(key, kEntryWalkTop, 0u, outcome); return; }
+    if (accepted) { emit(key, kEntryAccepted, 0u, outcome, lds_counts); return; }
+    if (over) { emit(key, kEntryWalkTop, 0u, outcome, lds_counts); return; }
     if (ex_next == 0u) return;  // rejected in this context
     if (level == (uint32_t)kCtxLevels || a.k_base[level] == nullptr || (ex_next & 0x80000000u)) {
-      emit(key, walk_kind, walk_pos, outcome);
+      emit(key, walk_kind, walk_pos, outcome, lds_counts);
       return;
     }
     // It leaves this frame as well: records for the next level, one per chunk of kContextsPerThread contexts
@@ -541,45 +547,90 @@ struct ContextWork {
 };
 
 // One workgroup per tile (see ContextListArgs::tiles): up to kContextThreads pairs of one node, up to
-// kContextsPerThread contexts of its rule.
+// kContextsPerThread contexts of its rule.  All entries of a tile go to the lists of those few contexts, so the
+// counting pass counts them per (context, segment) in LDS and adds each counter to the global one once; the
+// writing pass does the same to reserve room in every list and then hands out the places from LDS - the
+// global counters of a list are touched once per workgroup instead of once per wave and segment.
+constexpr uint32_t kTileCounters = kContextsPerThread * kMaxSegs;
 template <bool WRITE, class Tab>
-__device__ __forceinline__ void context_level1_body(const Tab& T, const DevVocab& voc, const ContextListArgs& a, const uint4 tile) {
-  if (threadIdx.x >= (tile.y & 0xFFFFu)) return;
-  const uint32_t e = tile.x + threadIdx.x, node = tile.w, i0 = tile.z, i1 = tile.z + (tile.y >> 16);
-  const uint32_t id = a.base_ids[e], ex0 = a.exits[e];
-  const ContextWork<WRITE, Tab> w{T, voc, a, e, id, load_token(voc, (int32_t)id)};
-  const uint32_t cb = a.ctx_off[T.header(node).y >> 16];
+__device__ __forceinline__ void context_level1_body(const Tab& T, const DevVocab& voc, const ContextListArgs& a, const uint4 tile,
+                                                    uint32_t* tile_counts) {
+  const uint32_t node = tile.w, i0 = tile.z, i1 = tile.z + (tile.y >> 16);
   const uint32_t k1b = a.k_base[0][node];
-  const bool single0 = (ex0 & (ex0 - 1u)) == 0u;
-  const bool keep = !WRITE && a.outcomes != nullptr;
-  const uint4 info = keep ? a.node_info[node] : make_uint4(0u, 0u, 0u, 0u);
-  for (uint32_t i = i0; i < i1; ++i) {
-    uint32_t outcome = 0u;
-    w.step(1u, a.ctx_node[cb + i], k1b + i, ex0, single0, keep ? &outcome : nullptr);
-    if (keep) a.outcomes[(size_t)info.x + (size_t)i * info.y + (e - info.z)] = (uint16_t)outcome;
+  if (threadIdx.x < (tile.y & 0xFFFFu)) {
+    const uint32_t e = tile.x + threadIdx.x;
+    const uint32_t id = a.base_ids[e], ex0 = a.exits[e];
+    const ContextWork<WRITE, Tab> w{T, voc, a, e, id, load_token(voc, (int32_t)id)};
+    const uint32_t cb = a.ctx_off[T.header(node).y >> 16];
+    const bool single0 = (ex0 & (ex0 - 1u)) == 0u;
+    const bool keep = !WRITE && a.outcomes != nullptr;
+    const uint4 info = keep ? a.node_info[node] : make_uint4(0u, 0u, 0u, 0u);
+    for (uint32_t i = i0; i < i1; ++i) {
+      uint32_t outcome = 0u;
+      w.step(1u, a.ctx_node[cb + i], k1b + i, ex0, single0, keep ? &outcome : nullptr,
+             WRITE ? nullptr : tile_counts + (i - i0) * (uint32_t)voc.n_seg);
+      if (keep) a.outcomes[(size_t)info.x + (size_t)i * info.y + (e - info.z)] = (uint16_t)outcome;
+    }
+  }
+  if (WRITE) return;
+  __syncthreads();
+  for (uint32_t t = threadIdx.x; t < (i1 - i0) * (uint32_t)voc.n_seg; t += kContextThreads) {
+    const uint32_t n = tile_counts[t];
+    if (n) atomicAdd(&a.counts[(a.key0[0] + k1b + i0 + t / (uint32_t)voc.n_seg) * (uint32_t)voc.n_seg + t % (uint32_t)voc.n_seg], n);
   }
 }
 template <bool WRITE>
 __global__ __launch_bounds__(kContextThreads) void context_level1_kernel(DevTables tab, DevVocab voc, ContextListArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ uint32_t tile_counts[WRITE ? 1 : kTileCounters];
   const uint4 tile = a.tiles[blockIdx.x];
+  if (!WRITE)
+    for (uint32_t t = threadIdx.x; t < kTileCounters; t += kContextThreads) tile_counts[t] = 0u;
   stage_tables(tab, smem, kContextThreads);
   __syncthreads();
-  if (small_sections_staged(tab)) context_level1_body<WRITE>(LdsTabT<true>(tab, smem), voc, a, tile);
-  else context_level1_body<WRITE>(LdsTab(tab, smem), voc, a, tile);
+  if (small_sections_staged(tab)) context_level1_body<WRITE>(LdsTabT<true>(tab, smem), voc, a, tile, tile_counts);
+  else context_level1_body<WRITE>(LdsTab(tab, smem), voc, a, tile, tile_counts);
 }
 // The writing pass of level 1 when the counting pass kept its outcomes: the same tiles, no walks, no tables.
 __global__ __launch_bounds__(kContextThreads) void context_level1_write_kernel(DevVocab voc, ContextListArgs a) {
+  __shared__ uint32_t next[2 * kTileCounters];   // per (context, segment, accepted or walk entry): entries, then places handed out
+  __shared__ uint32_t base[2 * kTileCounters];   // where the workgroup's entries of that kind begin in the list
   const uint4 tile = a.tiles[blockIdx.x];
-  if (threadIdx.x >= (tile.y & 0xFFFFu)) return;
-  const uint32_t e = tile.x + threadIdx.x, node = tile.w, i0 = tile.z, i1 = tile.z + (tile.y >> 16);
-  const uint32_t id = a.base_ids[e];
-  const uint32_t k1b = a.key0[0] + a.k_base[0][node];
-  const uint4 info = a.node_info[node];
-  const ListSink<true> sink{voc, a};
-  for (uint32_t i = i0; i < i1; ++i) {
-    const uint32_t code = a.outcomes[(size_t)info.x + (size_t)i * info.y + (e - info.z)];
-    if (code) sink.emit(id, k1b + i, (code & 0xFFu) - 1u, code >> 8);
+  const uint32_t node = tile.w, i0 = tile.z, n_ctx = tile.y >> 16, n_seg = (uint32_t)voc.n_seg;
+  const uint32_t k1b = a.key0[0] + a.k_base[0][node] + i0;
+  const bool active = threadIdx.x < (tile.y & 0xFFFFu);
+  for (uint32_t t = threadIdx.x; t < 2u * n_ctx * n_seg; t += kContextThreads) next[t] = 0u;
+  __syncthreads();
+  uint32_t code[kContextsPerThread], id = 0u, seg = 0u;
+  if (active) {
+    const uint32_t e = tile.x + threadIdx.x;
+    const uint4 info = a.node_info[node];
+    id = a.base_ids[e];
+    seg = id / (uint32_t)kSegTokens;
+#pragma unroll
+    for (uint32_t q = 0; q < kContextsPerThread; ++q) {
+      code[q] = q < n_ctx ? a.outcomes[(size_t)info.x + (size_t)(i0 + q) * info.y + (e - info.z)] : 0u;
+      if (code[q]) atomicAdd(&next[2u * (q * n_seg + seg) + ((code[q] & 0xFFu) - 1u == kEntryAccepted ? 0u : 1u)], 1u);
+    }
+  }
+  __syncthreads();
+  for (uint32_t t = threadIdx.x; t < 2u * n_ctx * n_seg; t += kContextThreads) {
+    const uint32_t n = next[t];
+    if (n) {
+      const uint32_t slot = (k1b + (t >> 1) / n_seg) * n_seg + (t >> 1) % n_seg;
+      base[t] = (t & 1u) ? atomicSub(&a.back[slot], n) - n : atomicAdd(&a.front[slot], n);
+      next[t] = 0u;
+    }
+  }
+  __syncthreads();
+  if (active) {
+#pragma unroll
+    for (uint32_t q = 0; q < kContextsPerThread; ++q) {
+      if (!code[q]) continue;
+      const uint32_t kind = (code[q] & 0xFFu) - 1u, pos = code[q] >> 8;
+      const uint32_t t = 2u * (q * n_seg + seg) + (kind == kEntryAccepted ? 0u : 1u);
+      a.entries[base[t] + atomicAdd(&next[t], 1u)] = id | (pos << kEntryPosShift) | (kind << kEntryKindShift);
+    }
   }
 }
 
@@ -1411,25 +1462,26 @@ void launch_gather_rows(const uint32_t* rows, int32_t W, const int32_t* unique, 
   if (n_unique > 0) hipLaunchKernelGGL(gather_rows_kernel, dim3(n_unique), dim3(kRowThreads), 0, stream, rows, W, unique, out);
 }
 
-void launch_rows_to_lists(const DevVocab& voc, int32_t n, const uint32_t* rows, const uint32_t* cursor_of, int32_t per_row,
-                          uint32_t* cursor, uint32_t* out, uint16_t* out_row, hipStream_t stream) {
+void launch_rows_to_lists(const uint32_t* rows, int32_t row_words, const int32_t* map, int32_t n, const uint32_t* cursor_of,
+                          int32_t per_row, uint32_t* cursor, uint32_t* out, uint16_t* out_row, hipStream_t stream) {
+  const int32_t n_seg = (row_words + kSegWords - 1) / kSegWords;
   for (int32_t r0 = 0; r0 < n; r0 += 32768) {  // grid.y limit
     const int32_t nb = std::min(32768, n - r0);
-    hipLaunchKernelGGL(rows_to_lists_kernel, dim3(voc.n_seg, nb), dim3(kListThreads), 0, stream, voc,
-                       rows + (size_t)r0 * voc.W, cursor_of + r0, per_row, cursor, out, out_row, r0);
+    hipLaunchKernelGGL(rows_to_lists_kernel, dim3(n_seg, nb), dim3(kListThreads), 0, stream, rows + (size_t)r0 * row_words,
+                       row_words, map, cursor_of + r0, per_row, cursor, out, out_row, r0);
   }
 }
 
 void launch_exit_positions(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, hipStream_t stream) {
   if (args.total == 0) return;
-  const DevTables st = staged_for(tab, kClassifyLdsBudget);
+  const DevTables st = staged_for(tab, kContextLdsBudget);
   hipLaunchKernelGGL(exit_positions_kernel, dim3((args.total + kContextThreads - 1) / kContextThreads), dim3(kContextThreads),
                      st.stage_bytes, stream, st, voc, args);
 }
 
 void launch_context_lists(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, bool write, hipStream_t stream) {
   if (args.total == 0 || args.n_tiles == 0) return;
-  const DevTables st = staged_for(tab, kClassifyLdsBudget);
+  const DevTables st = staged_for(tab, kContextLdsBudget);
   const dim3 g1(args.n_tiles), g2(1024);
   if (write && args.outcomes) {
     // level 1 from the kept outcomes; its records for level 2 are still there from the counting pass

@@ -60,6 +60,7 @@ struct TabView {
 
 // LDS budgets (bytes of dynamic shared memory) for the staged tables
 constexpr int32_t kClassifyLdsBudget = 76 * 1024;
+constexpr int32_t kContextLdsBudget = 68 * 1024;  // the list kernels keep 8 KB of counters beside the tables
 constexpr int32_t kFillLdsBudget = 12 * 1024;
 // The staging split for a kernel that has `budget` bytes of LDS for the tables:
 // as many whole sections as fit, then as many headers as fit.
@@ -228,12 +229,14 @@ void launch_permute(const DevVocab& voc, int32_t n, const uint32_t* a_rank, cons
 void launch_rows_equal(const uint32_t* rows, int32_t n, int32_t W, const int32_t* rep, uint32_t* equal, hipStream_t stream);
 void launch_gather_rows(const uint32_t* rows, int32_t W, const int32_t* unique, int32_t n_unique, uint32_t* out,
                         hipStream_t stream);
-// The set bits of n bitset rows as token ids, appended through cursors (any order within a cursor's list):
-// the tokens of row r and segment s go to out[cursor[cursor_of[r] * per_row + (per_row > 1 ? s : 0)]++];
-// rows with cursor_of[r] == kNoKey are skipped.  per_row = n_seg: one list per (row, segment); 1: one per row.
-// out_row (may be null) receives the row number beside every id.
-void launch_rows_to_lists(const DevVocab& voc, int32_t n, const uint32_t* rows, const uint32_t* cursor_of, int32_t per_row,
-                          uint32_t* cursor, uint32_t* out, uint16_t* out_row, hipStream_t stream);
+// The set bits of n bitset rows of row_words words as lists, appended through cursors: bit v of row r, in
+// segment s = v / kSegTokens, goes to out[cursor[cursor_of[r] * per_row + (per_row > 1 ? s : 0)]++] as
+// map[v] (map not null: rank-space rows with map = id_of_rank list token ids, neighbours in the list being
+// neighbours in byte-sorted order) or as v; rows with cursor_of[r] == kNoKey are skipped.  per_row = the
+// segments of a row: one list per (row, segment); 1: one per row.  out_row (may be null) receives the row
+// number beside every entry.
+void launch_rows_to_lists(const uint32_t* rows, int32_t row_words, const int32_t* map, int32_t n, const uint32_t* cursor_of,
+                          int32_t per_row, uint32_t* cursor, uint32_t* out, uint16_t* out_row, hipStream_t stream);
 // The level-1 and level-2 lists of a cache (see DevCache) from the base lists: the context-dependent
 // (node, token) pairs, base_node[e] / base_ids[e] for e < total, the pairs of one node side by side.
 // launch_exit_positions: exits[e] = the positions at which the token leaves the node's frame, as a bit set
