@@ -392,6 +392,17 @@ def main():
                                  "steps_per_pair": sps, "steps_per_s": sps * g.num_nodes * 128256 / best,
                                  "lookups_vs_ceiling": 4.0 * sps * g.num_nodes * 128256 / best / lds_rate,
                                  "host_classified_pairs": hostc, "cache": stats, "cache_device_bytes": held}
+        # the same C/SQL cache resolved one frame deep only (XGM_CACHE_DEPTH(1)): faster to build, more to walk per fill
+        g = xgm.Grammar(si.CSQL_GRAMMAR, "root")
+        shallow = None
+        for _ in range(3):
+            c = xgm.Cache(g, xv128, stream, depth=1)
+            shallow = c.build_seconds if shallow is None else min(shallow, c.build_seconds)
+            shallow_stats, shallow_bytes = c.stats, c.device_bytes
+            del c
+        cache_build["csql_one_frame_deep"] = {"whole_build_ms": shallow * 1e3,
+                                              "pairs_per_s_whole_build": g.num_nodes * 128256 / shallow,
+                                              "cache": shallow_stats, "cache_device_bytes": shallow_bytes}
         toks_s = work.vocab.tokens()
         sps = float(np.mean([mean_steps_per_pair(work.grammars[k], toks_s, np.random.Generator(np.random.PCG64(12 + k)), 1500)
                              for k in (0, 31, 77, 127) if k < len(work.grammars)]))

@@ -175,10 +175,16 @@ int xgm_schema_to_grammar(const char* schema_json, size_t len, char* h_text, siz
  * three short lists, and walks only the rare remainder.
  * Synchronous: returns after the build has finished on hip_stream. */
 int xgm_cache_build(xgm_grammar* g, xgm_vocab* v, void* hip_stream, xgm_cache** out);
-enum { XGM_CACHE_KEEP_PLAIN = 1 };
+enum { XGM_CACHE_KEEP_PLAIN = 1, XGM_CACHE_DEPTH_SHIFT = 4, XGM_CACHE_DEPTH_MASK = 0x70 };
 /* Same, with flags: XGM_CACHE_KEEP_PLAIN also keeps, per node, the bitsets of
  * the context-dependent tokens and of the plain-only context-dependent tokens
- * (for xgm_cache_copy_node_bits' h_unc and xgm_cache_copy_node_plain). */
+ * (for xgm_cache_copy_node_bits' h_unc and xgm_cache_copy_node_plain).
+ * XGM_CACHE_DEPTH(d), d = 1 .. 3: resolve the context-dependent tokens at most d
+ * frames deep at build time instead of three (0: the default).  A shallower cache is
+ * built faster and is smaller (grammars whose rules are used in many places have long
+ * lists at the deeper levels); the tokens that leave more frames than that are walked
+ * against the live stack by every fill.  The masks are the same. */
+#define XGM_CACHE_DEPTH(d) ((uint32_t)(d) << XGM_CACHE_DEPTH_SHIFT)
 int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t flags, xgm_cache** out);
 void xgm_cache_destroy(xgm_cache* c);
 int32_t xgm_cache_num_nodes(const xgm_cache* c);

@@ -255,10 +255,13 @@ class Grammar:
 
 
 class Cache:
-    def __init__(self, grammar: Grammar, vocab: Vocab, stream: int = 0, keep_plain: bool = False):
+    def __init__(self, grammar: Grammar, vocab: Vocab, stream: int = 0, keep_plain: bool = False, depth: int = 0):
+        """depth: resolve context-dependent tokens at most that many frames deep at build time (0: the default, 3)."""
         h = ctypes.c_void_p()
+        if not 0 <= depth <= 7:
+            raise ValueError("depth")
         _check(load_library().xgm_cache_build_ex(grammar._h, vocab._h, ctypes.c_void_p(stream),
-                                                 1 if keep_plain else 0, ctypes.byref(h)))
+                                                 (1 if keep_plain else 0) | (depth << 4), ctypes.byref(h)))
         self._h = h
         self.grammar = grammar
         self.vocab = vocab

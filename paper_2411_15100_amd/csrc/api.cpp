@@ -804,7 +804,9 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
     uint64_t n_k[kCtxLevels] = {};
     n_k[0] = key_node.size();
     c->levels = 1;
-    for (int l = 1; l < kCtxLevels; ++l) {
+    int max_levels = (int)((flags & XGM_CACHE_DEPTH_MASK) >> XGM_CACHE_DEPTH_SHIFT);
+    if (max_levels == 0 || max_levels > kCtxLevels) max_levels = kCtxLevels;
+    for (int l = 1; l < max_levels; ++l) {
       uint64_t next = 0;
       for (uint16_t r : key_node) next += n_ctx(A.node_rule[r]);
       if (next * (uint64_t)n_seg > ((uint64_t)1 << 26)) break;

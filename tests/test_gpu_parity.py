@@ -377,6 +377,52 @@ def test_scripting_grammar_every_step_and_every_node(xgm, wl):
 
 
 # --------------------------------------------------------------------------
+# caches resolved fewer frames deep at build time: more is walked at fill time, the masks are the same
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("depth", [1, 2])
+def test_shallower_caches_give_the_same_masks(xgm, wl, depth):
+    say(f"caches built {depth} frame(s) deep: JSON, a schema grammar and the scripting grammar, V=32000, 96 steps")
+    vocab = si.make_vocab("bpe", 32000, 0)
+    xv = wl.make_xgm_vocab(vocab)
+    texts = [si.JSON_GRAMMAR, si.make_schema_grammar(1, string_heavy=True), si.PYDSL_GRAMMAR]
+    grammars = [xgm.Grammar(t, "root") for t in texts]
+    caches = [xgm.Cache(g, xv, depth=depth) for g in grammars]
+    full = [xgm.Cache(g, xv) for g in grammars]
+    for c, f in zip(caches, full):
+        assert c.stats["keys"] < f.stats["keys"]   # (not fewer entries: what the deeper levels reject stays listed, to be walked)
+    walker = wl.BatchWalker(caches, vocab, seed=31 + depth, structural_bias=0.4)
+    oms = [oracle.EarleyMatcher(oracle.Grammar(t, "root")) for t in texts]
+    toks = vocab.tokens()
+    B, W = len(texts), xgm.bitmask_words(vocab.size)
+    d_mask2 = torch.zeros((B, W), dtype=torch.int32, device="cuda")
+    steps_walked = n_fixed = 0
+    for step in range(96):
+        words = walker.fill()
+        fixed = xgm.fill_overflow_fixup(_stream())
+        if fixed:
+            n_fixed += fixed
+            words = walker.d_mask.cpu().numpy()
+        want = np.stack([om.mask(vocab) for om in oms])
+        assert np.array_equal(words, oracle.pack_bitmask(want)), f"step {step}"
+        if step % 8 == 0:   # the same states resident on the device, and how much was walked
+            db = xgm.DeviceBatch(walker.matchers, history=0, stream=_stream())
+            db.fill_next_token_bitmask(d_mask2.data_ptr(), _stream())
+            db.fill_overflow_fixup(_stream())
+            torch.cuda.synchronize()
+            assert np.array_equal(d_mask2.cpu().numpy(), oracle.pack_bitmask(want)), f"step {step}, resident states"
+            steps_walked += xgm.debug_fill_count_steps(walker.batch, d_mask2.data_ptr(), _stream())
+        picks = walker.step(words)
+        for b in range(B):
+            if not walker.history[b]:
+                oms[b] = oracle.EarleyMatcher(oracle.Grammar(texts[b], "root"))
+            else:
+                assert oms[b].advance(toks[int(picks[b])])
+    assert steps_walked > 0   # (with all three levels these states need next to no walks)
+    say(f"  96 steps x {B} rows bit-exact from host-side and resident states; automaton steps walked in 12 sampled fills: "
+        f"{steps_walked}; pairs fixed up on the host: {n_fixed}")
+
+
+# --------------------------------------------------------------------------
 # fused fill + apply: same masks, same logits as the two calls / as the oracle
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype_name,V,pad", [("bf16", 4100, 0), ("f32", 4100, 0), ("f16", 4099, 13), ("bf16", 9000, 24)])
