@@ -289,7 +289,7 @@ int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int
  * vocabulary; their grammars may differ.  B <= 65535.  The call packs the
  * stacks (per stack: its frames and where its token lists lie in the cache)
  * into pinned staging owned by the library (a ring of 8 slots), enqueues a
- * small copy kernel and the fill kernel (one workgroup per row and 32768
+ * small copy kernel and the fill kernel (one workgroup per row and 8192
  * token ids) on hip_stream, and returns.
  * A walk that exceeds the on-chip bounds (64 frames pushed inside one token,
  * 24 pending alternatives, 4096 steps, tokens longer than 255 bytes) is never

@@ -816,18 +816,18 @@ __global__ __launch_bounds__(kUploadThreads) void upload_kernel(const uint4* __r
 constexpr int kFillThreads = 256;
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
 constexpr int kFillMaxLists = 64 * kStackLists;  // XGM_MAX_STACKS stacks with their lists
-constexpr int kFillListsAtOnce = 6;             // lists whose first entries are fetched together
 
-// One workgroup of 8 waves serves one request and one segment of 32768 token
-// ids = 1024 mask words, which it owns in LDS:
+// One workgroup of 4 waves serves one request and one segment of 8192 token
+// ids = 256 mask words, which it owns in LDS:
 //   1. every word = OR of the accepted bitsets of the tops of all stacks that
 //      keep one (Algorithm 1: the result is the union over the parallel
 //      stacks); the stop tokens if the text may end;
-//   2. the stacks' token lists for this segment (up to three per stack: the
+//   2. the stacks' token lists for this segment (up to four per stack: the
 //      top node's own accepted tokens if it keeps a list instead of a bitset,
 //      the tokens accepted given the node below the top frame, those accepted
-//      given the two nodes below) are streamed once, coalesced; an accepted
-//      entry sets its bit with an LDS atomic, a walk entry is only counted;
+//      given the two and the three nodes below) are streamed once, coalesced;
+//      an accepted entry sets its bit with an LDS atomic, a walk entry is only
+//      counted;
 //   3. lists that have walk entries (they sit at the list's end) get them
 //      decided against the live stack: only then are the request's automaton
 //      tables and frames copied into LDS.  Most launches walk nothing;
@@ -883,7 +883,7 @@ __device__ __forceinline__ void fill_walks(const Tab& T, FillShared& sm, const R
   }
 }
 
-// Four workgroups of 8 waves per compute unit need 8 waves per SIMD: the second
+// Eight workgroups of 4 waves per compute unit need 8 waves per SIMD: the second
 // launch bound keeps the kernel within the registers that this takes.
 // APPLY = 0: the mask only.  APPLY = 2 / 4 (bytes per logit): the workgroup
 // also writes -inf into the logits of its (row, segment) straight from its
