@@ -287,9 +287,10 @@ int32_t xgm_matcher_stack(const xgm_matcher* m, int32_t s, int32_t* h_nodes, int
  * plus the stop tokens iff the matcher can terminate; a terminated matcher
  * gets a row with only the stop tokens.  All matchers must share one
  * vocabulary; their grammars may differ.  B <= 65535.  The call packs the
- * stacks (per stack: its frames and where its token lists lie in the cache)
+ * stacks (per stack: its frames and which token lists of the cache are its)
  * into pinned staging owned by the library (a ring of 8 slots), enqueues a
- * small copy kernel and the fill kernel (one workgroup per row and 8192
+ * small kernel that copies them and looks up where those lists lie, and the
+ * fill kernel (one workgroup per row and 8192
  * token ids) on hip_stream, and returns.
  * A walk that exceeds the on-chip bounds (64 frames pushed inside one token,
  * 24 pending alternatives, 4096 steps, tokens longer than 255 bytes) is never
@@ -317,10 +318,11 @@ int xgm_fill_and_apply(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, vo
  * over the on-chip limits.  The packed stacks are
  * written into a fixed host array and copied, in stream order, into a fixed
  * array of XGM_STATIC_STAGING_BYTES (1 MiB) that every device holds from the
- * moment the library is loaded until the process ends; the call makes no
- * hipMalloc / hipHostMalloc / hipFree and uses no event.  A batch whose stacks
- * need more than that returns XGM_ERR_TOO_LARGE (nothing is
- * enqueued); batch 128 at a vocabulary of 151936 needs about 40 KiB.  The
+ * moment the library is loaded until the process ends, where a kernel writes
+ * them out in the form the fill kernel reads (both forms lie in the array);
+ * the call makes no hipMalloc / hipHostMalloc / hipFree and uses no event.  A
+ * batch whose stacks need more than that returns XGM_ERR_TOO_LARGE (nothing is
+ * enqueued); batch 128 at a vocabulary of 151936 needs about 110 KiB.  The
  * mask caches of the matchers must have been built before (they were, or the
  * matchers would not exist).  All calls on one device share the array, which
  * keeps the last call's contents: calls whose work overlaps on one device

@@ -167,10 +167,13 @@ TempArena& temp_arena() {
 }
 
 void require_device() {
+  static std::atomic<bool> found{false};  // (asked once: the per-step calls come through here too)
+  if (found.load(std::memory_order_relaxed)) return;
   int n = 0;
   hipError_t e = hipGetDeviceCount(&n);
   if (e != hipSuccess || n <= 0)
     throw Failure(XGM_ERR_HIP, "no HIP device: the mask kernels have no CPU path");
+  found.store(true, std::memory_order_relaxed);
 }
 
 }  // namespace
@@ -1166,25 +1169,22 @@ struct FusedLogits {
   int32_t V_logits;
   int64_t row_stride;
 };
-// One stack header as the fill kernel reads it (see kStackHdr* in kernels.hpp);
-// `frame_offset`: where the stack's frames start in the frame array.
-static void pack_stack_header(const Automaton& A, const xgm_cache& c, const Stack& s, uint32_t frame_offset, uint32_t* h) {
-  const int32_t n_seg = c.v->dv.n_seg;
-  const uint32_t n_off = (uint32_t)n_seg + 1u;
+// The scalar words of a stack's header and the keys of its lists (see kStackHdr* and kStackKeysWords in
+// kernels.hpp): h[0 .. kStackHdrWords) and key[0 .. kStackLists).  `frame_offset`: where the stack's frames
+// start in the frame array.
+static void stack_keys(const Automaton& A, const xgm_cache& c, const Stack& s, uint32_t frame_offset, uint32_t* h, uint32_t* key) {
   const int32_t top = s.back();
   h[kStackHdrTop] = (uint32_t)top | ((uint32_t)c.acc_row_host[top] << 16);
   h[kStackHdrDepth] = (uint32_t)s.size();
   h[kStackHdrFrames] = frame_offset;
   h[3] = 0u;
-  // the keys of the stack's lists: the top node's own; the one for the node below the top frame; the one
-  // for the two nodes below
+  // the keys of the stack's lists: the top node's own; then one per frame below the top that a kept level reaches
   auto context_index = [&](int32_t frame_node, int32_t below) {
     const auto& ctx = A.contexts[A.node_rule[frame_node]];
     auto it = std::lower_bound(ctx.begin(), ctx.end(), below);
     if (it == ctx.end() || *it != below) throw Failure(XGM_ERR_INTERNAL, "fill: a frame sits on a node that is no context of its rule");
     return (uint32_t)(it - ctx.begin());
   };
-  uint32_t key[kStackLists];
   key[0] = (uint32_t)top;
   uint32_t local = (uint32_t)top, key0 = (uint32_t)c.host.n_nodes;
   bool more = true;
@@ -1197,6 +1197,14 @@ static void pack_stack_header(const Automaton& A, const xgm_cache& c, const Stac
     more = key[l] != kNoKey;
     key0 += c.host.n_k[l - 1];
   }
+}
+// One stack header as the fill kernel reads it, written out on the host (device-resident batches are set up
+// this way; the fills from host-side states send the keys and let the device look the offsets up).
+static void pack_stack_header(const Automaton& A, const xgm_cache& c, const Stack& s, uint32_t frame_offset, uint32_t* h) {
+  const int32_t n_seg = c.v->dv.n_seg;
+  const uint32_t n_off = (uint32_t)n_seg + 1u;
+  uint32_t key[kStackLists];
+  stack_keys(A, c, s, frame_offset, h, key);
   for (uint32_t l = 0; l < kStackLists; ++l) {
     uint32_t* off = h + kStackHdrWords + l * n_off;
     if (key[l] == kNoKey) std::memset(off, 0, n_off * 4);
@@ -1233,10 +1241,16 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   }
   require_device();
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // On the host: row descriptors | per stack its scalar words and list keys | frames.  On the device: row
+  // descriptors | full stack headers | frames (the static staging keeps the host's bytes behind that).
+  static_assert(sizeof(RowDesc) % 16 == 0, "the sections of the staging memory are 16-byte aligned");
   const size_t hdr_words = stack_hdr_stride(v->dv.n_seg);
   const size_t off_stacks = (size_t)B * sizeof(RowDesc);
+  const size_t h_off_frames = off_stacks + n_stacks * kStackKeysWords * 4;
+  const size_t h_bytes = ((h_off_frames + n_frames * 2 + 63) / 64) * 64;
   const size_t off_frames = off_stacks + n_stacks * hdr_words * 4;
-  const size_t bytes = ((off_frames + n_frames * 2 + 63) / 64) * 64;
+  const size_t d_bytes = ((off_frames + n_frames * 2 + 63) / 64) * 64;
+  const size_t bytes = use_static ? d_bytes + h_bytes : std::max(d_bytes, h_bytes);
 
   Context& C = ctx();
   std::lock_guard<std::mutex> lock(C.mu);
@@ -1271,7 +1285,7 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
   }
   auto* rows = reinterpret_cast<RowDesc*>(h_buf);
   auto* hdrs = reinterpret_cast<uint32_t*>((char*)h_buf + off_stacks);
-  auto* frames = reinterpret_cast<uint16_t*>((char*)h_buf + off_frames);
+  auto* frames = reinterpret_cast<uint16_t*>((char*)h_buf + h_off_frames);
   uint32_t si = 0, fi = 0;
   for (int32_t b = 0; b < B; ++b) {
     const xgm_matcher* m = ms[b];
@@ -1294,15 +1308,22 @@ static int fill_impl(xgm_matcher* const* ms, int32_t B, int32_t* d_bitmask, void
     r.n_stacks = (uint32_t)m->stacks.size();
     r.flags = Engine(&A).can_terminate(m->stacks) ? 1u : 0u;
     for (auto& s : m->stacks) {
-      pack_stack_header(A, *m->c, s, fi, hdrs + (size_t)si * hdr_words);
+      uint32_t* h = hdrs + (size_t)si * kStackKeysWords;
+      stack_keys(A, *m->c, s, fi, h, h + kStackHdrWords);
+      const uintptr_t key_off = reinterpret_cast<uintptr_t>(m->c->host.key_off);
+      h[kStackHdrWords + kStackLists] = (uint32_t)key_off;
+      h[kStackHdrWords + kStackLists + 1] = (uint32_t)((uint64_t)key_off >> 32);
+      for (uint32_t w = kStackHdrWords + kStackLists + 2; w < kStackKeysWords; ++w) h[w] = 0u;
       ++si;
       for (int32_t n : s) frames[fi++] = (uint16_t)n;
       r.n_frames += (uint32_t)s.size();
     }
   }
   if (timing) HIP_OK(hipEventRecord(timing[0], stream));
-  if (use_static) HIP_OK(hipMemcpyAsync(d_buf, h_buf, bytes, hipMemcpyHostToDevice, stream));
-  else launch_upload(ring->h_dev, d_buf, bytes, stream);
+  const void* src = ring ? ring->h_dev : (const void*)((char*)d_buf + d_bytes);
+  if (use_static) HIP_OK(hipMemcpyAsync((char*)d_buf + d_bytes, h_buf, h_bytes, hipMemcpyHostToDevice, stream));
+  launch_upload_stacks(src, d_buf, off_stacks, (const char*)src + off_stacks, (uint32_t)n_stacks, v->dv.n_seg,
+                       (char*)d_buf + off_stacks, (const char*)src + h_off_frames, (char*)d_buf + off_frames, n_frames * 2, stream);
   if (timing) HIP_OK(hipEventRecord(timing[1], stream));
   const uint32_t seq = ++C.seq;
   launch_fill(reinterpret_cast<const RowDesc*>(d_buf), reinterpret_cast<const uint32_t*>((char*)d_buf + off_stacks),
@@ -1508,7 +1529,7 @@ int xgm_fill_overflow_fixup(void* hip_stream) {
     const xgm_vocab& v = *c.v;
     // the row's stacks as that fill packed them
     const auto* rows = reinterpret_cast<const RowDesc*>(f->blob);
-    const size_t hdr_words = stack_hdr_stride(v.dv.n_seg);
+    const size_t hdr_words = kStackKeysWords;  // (the staging memory holds the stacks as the host packed them)
     const auto* hdrs = reinterpret_cast<const uint32_t*>((const char*)f->blob + (size_t)f->B * sizeof(RowDesc));
     size_t n_stacks = 0;
     for (int32_t r = 0; r < f->B; ++r) n_stacks += rows[r].n_stacks;

@@ -813,6 +813,50 @@ __global__ __launch_bounds__(kUploadThreads) void upload_kernel(const uint4* __r
   if (i < n16) dst[i] = src[i];
 }
 
+// The same with the stack headers written out in full on the way: the host sends, per stack, the keys of its
+// lists; the offsets of the lists' segments are read from the cache's key_off here (what the host is spared:
+// copying four rows of offsets per stack out of a table that does not fit its caches).  Blocks [0, copy_blocks)
+// copy the row descriptors and the frames, the others expand kStacksPerBlock stacks each, whose key words go
+// through LDS (one read over the bus per 16 bytes).
+constexpr uint32_t kStacksPerBlock = 2;
+__global__ __launch_bounds__(kUploadThreads) void upload_stacks_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                                       uint32_t plain16, const uint4* __restrict__ src_frames,
+                                                                       uint4* __restrict__ dst_frames, uint32_t frames16,
+                                                                       uint32_t copy_blocks, const uint4* __restrict__ src_stacks,
+                                                                       uint32_t n_stacks, uint32_t n_seg,
+                                                                       uint32_t* __restrict__ dst_hdrs) {
+  __shared__ uint32_t keys[kStacksPerBlock][kStackKeysWords];
+  if (blockIdx.x < copy_blocks) {
+    const uint32_t i = blockIdx.x * kUploadThreads + threadIdx.x;
+    if (i < plain16) dst[i] = src[i];
+    else if (i < plain16 + frames16) dst_frames[i - plain16] = src_frames[i - plain16];
+    return;
+  }
+  const uint32_t s0 = (blockIdx.x - copy_blocks) * kStacksPerBlock;
+  constexpr uint32_t kQuads = kStackKeysWords / 4;
+  if (threadIdx.x < kStacksPerBlock * kQuads && s0 + threadIdx.x / kQuads < n_stacks) {
+    const uint4 q = src_stacks[(size_t)s0 * kQuads + threadIdx.x];
+    uint32_t* k = &keys[threadIdx.x / kQuads][(threadIdx.x % kQuads) * 4];
+    k[0] = q.x; k[1] = q.y; k[2] = q.z; k[3] = q.w;
+  }
+  __syncthreads();
+  const uint32_t n_off = n_seg + 1u, stride = kStackHdrWords + kStackLists * n_off;  // = stack_hdr_stride(n_seg)
+  for (uint32_t t = threadIdx.x; t < kStacksPerBlock * stride; t += kUploadThreads) {
+    const uint32_t st = t / stride, w = t % stride;
+    if (s0 + st >= n_stacks) break;
+    const uint32_t* k = keys[st];
+    uint32_t out;
+    if (w < kStackHdrWords) out = k[w];
+    else {
+      const uint32_t l = (w - kStackHdrWords) / n_off, sgm = (w - kStackHdrWords) % n_off, key = k[kStackHdrWords + l];
+      const uint32_t* key_off = reinterpret_cast<const uint32_t*>((uintptr_t)k[kStackHdrWords + kStackLists] |
+                                                                  ((uintptr_t)k[kStackHdrWords + kStackLists + 1] << 32));
+      out = key == kNoKey ? 0u : key_off[(size_t)key * n_seg + sgm];
+    }
+    dst_hdrs[(size_t)(s0 + st) * stride + w] = out;
+  }
+}
+
 constexpr int kFillThreads = 256;
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
 constexpr int kFillMaxLists = 64 * kStackLists;  // XGM_MAX_STACKS stacks with their lists
@@ -1512,6 +1556,20 @@ void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t 
   if (n16 == 0) return;
   hipLaunchKernelGGL(upload_kernel, dim3((n16 + kUploadThreads - 1) / kUploadThreads), dim3(kUploadThreads), 0, stream,
                      reinterpret_cast<const uint4*>(pinned_src), reinterpret_cast<uint4*>(dst), n16);
+}
+
+void launch_upload_stacks(const void* src, void* dst, size_t plain_bytes, const void* src_stacks, uint32_t n_stacks,
+                          int32_t n_seg, void* dst_hdrs, const void* src_frames, void* dst_frames, size_t frames_bytes,
+                          hipStream_t stream) {
+  static_assert(kStackKeysWords % 4 == 0 && kStackKeysWords >= kStackHdrWords + kStackLists + 2, "the key words of a stack");
+  const uint32_t plain16 = (uint32_t)(plain_bytes / 16), frames16 = (uint32_t)((frames_bytes + 15) / 16);
+  const uint32_t copy_blocks = (plain16 + frames16 + kUploadThreads - 1) / kUploadThreads;
+  const uint32_t stack_blocks = (n_stacks + kStacksPerBlock - 1) / kStacksPerBlock;
+  if (copy_blocks + stack_blocks == 0) return;
+  hipLaunchKernelGGL(upload_stacks_kernel, dim3(copy_blocks + stack_blocks), dim3(kUploadThreads), 0, stream,
+                     reinterpret_cast<const uint4*>(src), reinterpret_cast<uint4*>(dst), plain16,
+                     reinterpret_cast<const uint4*>(src_frames), reinterpret_cast<uint4*>(dst_frames), frames16, copy_blocks,
+                     reinterpret_cast<const uint4*>(src_stacks), n_stacks, (uint32_t)n_seg, reinterpret_cast<uint32_t*>(dst_hdrs));
 }
 
 void launch_fill(const RowDesc* rows, const uint32_t* stack_hdrs, const uint16_t* frames, int32_t B, const DevVocab& voc,

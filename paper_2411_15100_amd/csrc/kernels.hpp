@@ -287,6 +287,16 @@ void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_
                           uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank, hipStream_t stream);
 // copy `bytes` (rounded up to 16; both buffers must hold that) from device-visible pinned host memory
 void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t stream);
+// A stack as the host hands it over (kStackKeysWords words): the header's four scalar words, then the keys of
+// the stack's kStackLists lists (kNoKey: none), then the device address of the cache's key_off (two words).
+// launch_upload_stacks copies `plain_bytes` bytes (a multiple of 16: the row descriptors) and `frames_bytes`
+// bytes of frames as they are and writes every stack's full header (stack_hdr_stride(n_seg) words: the
+// offsets of the lists' segments looked up in key_off on the device) at dst_hdrs; src may be pinned host
+// memory or device memory.
+constexpr uint32_t kStackKeysWords = 12;
+void launch_upload_stacks(const void* src, void* dst, size_t plain_bytes, const void* src_stacks, uint32_t n_stacks,
+                          int32_t n_seg, void* dst_hdrs, const void* src_frames, void* dst_frames, size_t frames_bytes,
+                          hipStream_t stream);
 // (b) batched mask fill: one workgroup per (segment, row)
 // step_counter: null on the hot path; otherwise the counting instantiation is launched.
 // logits != null: the fused instantiation also applies each row's mask to its logits row
