@@ -802,22 +802,13 @@ struct LogitsRange {
 };
 
 // ---------------------------------------------------------------- kernel (b)
-// The per-step stack upload: a plain copy from pinned host memory (which the
-// device reads over the bus) into device memory, as a kernel on the caller's
-// stream.  For the few tens of kilobytes of a step this takes a fraction of
-// the time a copy-engine transfer with its cross-queue synchronisation does.
+// The per-step stack upload, as a kernel on the caller's stream that reads pinned host memory over the bus
+// (for the few tens of kilobytes of a step this takes a fraction of the time a copy-engine transfer with
+// its cross-queue synchronisation does).  The stack headers are written out in full on the way: the host
+// sends, per stack, the keys of its lists; the offsets of the lists' segments are read from the cache's
+// key_off here.  Blocks [0, copy_blocks) copy the row descriptors and the frames, the others expand
+// kStacksPerBlock stacks each, whose key words go through LDS (one read over the bus per 16 bytes).
 constexpr int kUploadThreads = 256;
-__global__ __launch_bounds__(kUploadThreads) void upload_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                                                uint32_t n16) {
-  const uint32_t i = blockIdx.x * kUploadThreads + threadIdx.x;
-  if (i < n16) dst[i] = src[i];
-}
-
-// The same with the stack headers written out in full on the way: the host sends, per stack, the keys of its
-// lists; the offsets of the lists' segments are read from the cache's key_off here (what the host is spared:
-// copying four rows of offsets per stack out of a table that does not fit its caches).  Blocks [0, copy_blocks)
-// copy the row descriptors and the frames, the others expand kStacksPerBlock stacks each, whose key words go
-// through LDS (one read over the bus per 16 bytes).
 constexpr uint32_t kStacksPerBlock = 2;
 __global__ __launch_bounds__(kUploadThreads) void upload_stacks_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
                                                                        uint32_t plain16, const uint4* __restrict__ src_frames,
@@ -1549,13 +1540,6 @@ void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_
   if (n_items <= 0) return;
   hipLaunchKernelGGL(patch_classes_kernel, dim3((n_items + 255) / 256), dim3(256), 0, stream, voc, items, n_items,
                      acc_rank, unc_rank, plain_rank);
-}
-
-void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t stream) {
-  const uint32_t n16 = (uint32_t)((bytes + 15) / 16);
-  if (n16 == 0) return;
-  hipLaunchKernelGGL(upload_kernel, dim3((n16 + kUploadThreads - 1) / kUploadThreads), dim3(kUploadThreads), 0, stream,
-                     reinterpret_cast<const uint4*>(pinned_src), reinterpret_cast<uint4*>(dst), n16);
 }
 
 void launch_upload_stacks(const void* src, void* dst, size_t plain_bytes, const void* src_stacks, uint32_t n_stacks,

@@ -285,8 +285,6 @@ uint32_t context_tile_contexts();
 // set / clear single bits of rank-space rows: items = (node - node0, rank, class)
 void launch_patch_classes(const DevVocab& voc, const uint32_t* items, int32_t n_items,
                           uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank, hipStream_t stream);
-// copy `bytes` (rounded up to 16; both buffers must hold that) from device-visible pinned host memory
-void launch_upload(const void* pinned_src, void* dst, size_t bytes, hipStream_t stream);
 // A stack as the host hands it over (kStackKeysWords words): the header's four scalar words, then the keys of
 // the stack's kStackLists lists (kNoKey: none), then the device address of the cache's key_off (two words).
 // launch_upload_stacks copies `plain_bytes` bytes (a multiple of 16: the row descriptors) and `frames_bytes`
