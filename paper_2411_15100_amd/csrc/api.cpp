@@ -910,6 +910,8 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       }
       args.node_info = arena.upload(node_info, stream);
       args.outcomes = arena.array<uint16_t>((size_t)n_items);
+      // (the deeper levels keep theirs per record: 16 bytes each)
+      for (int l = 1; l < c->levels; ++l) args.deep_outcomes[l] = arena.array<uint4>(args.res_cap);
     }
     launch_exit_positions(tab, dv, args, stream);
     launch_context_lists(tab, dv, args, false, stream);
@@ -922,6 +924,8 @@ int xgm_cache_build_ex(xgm_grammar* g, xgm_vocab* v, void* hip_stream, uint32_t 
       if (most <= args.res_cap) break;
       args.res_cap = most;
       for (int l = 0; l + 1 < c->levels; ++l) args.res[l] = arena.array<uint4>(args.res_cap);
+      if (args.outcomes)
+        for (int l = 1; l < c->levels; ++l) args.deep_outcomes[l] = arena.array<uint4>(args.res_cap);
       HIP_OK(hipMemsetAsync(d_counts, 0, n_slots * 4, stream));
       launch_context_lists(tab, dv, args, false, stream);
       HIP_OK(hipGetLastError());

@@ -648,7 +648,18 @@ __device__ __forceinline__ void context_deeper_body(const Tab& T, const DevVocab
     const uint32_t id = a.base_ids[rec.x];
     const ContextWork<WRITE, Tab> w{T, voc, a, rec.x, id, load_token(voc, (int32_t)id)};
     const uint32_t kb = a.k_base[level - 1u][rec.y];
-    for (uint32_t j = j0; j < min(j0 + kContextsPerThread, m); ++j) w.step(level, a.ctx_node[cb + j], kb + j, rec.z, (rec.w & 0x10000u) != 0u);
+    uint4* keep = WRITE ? nullptr : a.deep_outcomes[level - 1u];
+    static_assert(kContextsPerThread == 8, "a record's outcomes are eight 16-bit codes in one uint4");
+    uint32_t codes[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (uint32_t q = 0; q < kContextsPerThread; ++q) {
+      const uint32_t j = j0 + q;
+      if (j >= m) break;
+      uint32_t outcome = 0u;
+      w.step(level, a.ctx_node[cb + j], kb + j, rec.z, (rec.w & 0x10000u) != 0u, keep ? &outcome : nullptr);
+      codes[q >> 1] |= outcome << ((q & 1u) * 16u);
+    }
+    if (keep) keep[item] = make_uint4(codes[0], codes[1], codes[2], codes[3]);
   }
 }
 template <bool WRITE>
@@ -659,6 +670,25 @@ __global__ __launch_bounds__(kContextThreads) void context_deeper_kernel(DevTabl
   __syncthreads();
   if (small_sections_staged(tab)) context_deeper_body<WRITE>(LdsTabT<true>(tab, smem), voc, a, level);
   else context_deeper_body<WRITE>(LdsTab(tab, smem), voc, a, level);
+}
+
+// The writing pass of a deeper level when the counting pass kept its outcomes: the same records, no walks, no tables.
+__global__ __launch_bounds__(256) void context_deeper_write_kernel(DevVocab voc, ContextListArgs a, uint32_t level) {
+  const uint32_t n_res = min(a.res_count[level - 2u], a.res_cap);
+  const ListSink<true> sink{voc, a};
+  for (uint32_t item = blockIdx.x * 256u + threadIdx.x; item < n_res; item += gridDim.x * 256u) {
+    const uint4 c = a.deep_outcomes[level - 1u][item];
+    if ((c.x | c.y | c.z | c.w) == 0u) continue;
+    const uint4 rec = a.res[level - 2u][item];
+    const uint32_t id = a.base_ids[rec.x];
+    const uint32_t key = a.key0[level - 1u] + a.k_base[level - 1u][rec.y] + (rec.w >> 17) * kContextsPerThread;
+    const uint32_t codes[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+    for (uint32_t q = 0; q < kContextsPerThread; ++q) {
+      const uint32_t code = (codes[q >> 1] >> ((q & 1u) * 16u)) & 0xFFFFu;
+      if (code) sink.emit(id, key + q, (code & 0xFFu) - 1u, code >> 8);
+    }
+  }
 }
 
 __global__ __launch_bounds__(kRowThreads) void rows_equal_kernel(const uint32_t* __restrict__ rows, int32_t W,
@@ -1519,14 +1549,23 @@ void launch_context_lists(const DevTables& tab, const DevVocab& voc, const Conte
   const DevTables st = staged_for(tab, kContextLdsBudget);
   const dim3 g1(args.n_tiles), g2(1024);
   if (write && args.outcomes) {
-    // level 1 from the kept outcomes; its records for level 2 are still there from the counting pass
-    (void)hipMemsetAsync(args.res_count + 1, 0, 4 * (kCtxLevels - 1), stream);
+    // Level 1 from the kept outcomes; its records for level 2 are still there from the counting pass, and so
+    // are the deeper levels' records if their outcomes were kept too (levels that walk again make the records
+    // of the next level again: those counts start at zero).
     hipLaunchKernelGGL(context_level1_write_kernel, g1, dim3(kContextThreads), 0, stream, voc, args);
-  } else {
-    (void)hipMemsetAsync(args.res_count, 0, 4 * kCtxLevels, stream);
-    if (write) hipLaunchKernelGGL(context_level1_kernel<true>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
-    else hipLaunchKernelGGL(context_level1_kernel<false>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+    bool deep = true;  // all deeper levels from kept outcomes, or all of them by walking again
+    for (uint32_t level = 2; level <= (uint32_t)kCtxLevels && args.k_base[level - 1] != nullptr; ++level)
+      deep = deep && args.deep_outcomes[level - 1] != nullptr;
+    if (!deep) (void)hipMemsetAsync(args.res_count + 1, 0, 4 * (kCtxLevels - 1), stream);
+    for (uint32_t level = 2; level <= (uint32_t)kCtxLevels && args.k_base[level - 1] != nullptr; ++level) {
+      if (deep) hipLaunchKernelGGL(context_deeper_write_kernel, g2, dim3(256), 0, stream, voc, args, level);
+      else hipLaunchKernelGGL(context_deeper_kernel<true>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args, level);
+    }
+    return;
   }
+  (void)hipMemsetAsync(args.res_count, 0, 4 * kCtxLevels, stream);
+  if (write) hipLaunchKernelGGL(context_level1_kernel<true>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
+  else hipLaunchKernelGGL(context_level1_kernel<false>, g1, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args);
   for (uint32_t level = 2; level <= (uint32_t)kCtxLevels && args.k_base[level - 1] != nullptr; ++level) {
     if (write) hipLaunchKernelGGL(context_deeper_kernel<true>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args, level);
     else hipLaunchKernelGGL(context_deeper_kernel<false>, g2, dim3(kContextThreads), st.stage_bytes, stream, st, voc, args, level);

@@ -277,6 +277,10 @@ struct ContextListArgs {
   // 0 = no entry, else (kind + 1) | pos << 8.
   const uint4* node_info;
   uint16_t* outcomes;
+  // The same for the deeper levels: deep_outcomes[l][r] holds the outcomes (8 x 16 bits, coded as above) of
+  // record r of res[l - 1], that is of level l + 1, for the contexts of the record's chunk; null: the writing
+  // pass of that level walks again.  Used together with `outcomes` only.
+  uint4* deep_outcomes[kCtxLevels];
 };
 void launch_exit_positions(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, hipStream_t stream);
 void launch_context_lists(const DevTables& tab, const DevVocab& voc, const ContextListArgs& args, bool write, hipStream_t stream);
