@@ -1206,13 +1206,11 @@ static void stack_keys(const Automaton& A, const xgm_cache& c, const Stack& s, u
 // this way; the fills from host-side states send the keys and let the device look the offsets up).
 static void pack_stack_header(const Automaton& A, const xgm_cache& c, const Stack& s, uint32_t frame_offset, uint32_t* h) {
   const int32_t n_seg = c.v->dv.n_seg;
-  const uint32_t n_off = (uint32_t)n_seg + 1u;
   uint32_t key[kStackLists];
   stack_keys(A, c, s, frame_offset, h, key);
   for (uint32_t l = 0; l < kStackLists; ++l) {
-    uint32_t* off = h + kStackHdrWords + l * n_off;
-    if (key[l] == kNoKey) std::memset(off, 0, n_off * 4);
-    else std::memcpy(off, &c.key_off_host[(size_t)key[l] * n_seg], n_off * 4);
+    const uint32_t* ko = key[l] == kNoKey ? nullptr : &c.key_off_host[(size_t)key[l] * n_seg];
+    for (int32_t sgm = 0; sgm <= n_seg; ++sgm) h[stack_hdr_off((uint32_t)sgm, l)] = ko ? ko[sgm] : 0u;
   }
 }
 
@@ -1357,8 +1355,7 @@ int xgm_debug_matcher_fill_work(const xgm_matcher* m, int64_t* h_out4) {
     pack_stack_header(m->g->A, *m->c, s, 0u, h.data());
     if ((h[kStackHdrTop] >> 16) != kNoAccRow) ++h_out4[0];
     for (uint32_t l = 0; l < kStackLists; ++l) {
-      const uint32_t* off = &h[kStackHdrWords + l * ((uint32_t)n_seg + 1u)];
-      h_out4[1 + std::min<uint32_t>(l, 2u)] += off[n_seg] - off[0];
+      h_out4[1 + std::min<uint32_t>(l, 2u)] += h[stack_hdr_off((uint32_t)n_seg, l)] - h[stack_hdr_off(0u, l)];
     }
   }
   return XGM_OK;

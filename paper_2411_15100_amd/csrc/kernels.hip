@@ -861,7 +861,7 @@ __global__ __launch_bounds__(kUploadThreads) void upload_stacks_kernel(const uin
     k[0] = q.x; k[1] = q.y; k[2] = q.z; k[3] = q.w;
   }
   __syncthreads();
-  const uint32_t n_off = n_seg + 1u, stride = kStackHdrWords + kStackLists * n_off;  // = stack_hdr_stride(n_seg)
+  const uint32_t stride = stack_hdr_stride((int32_t)n_seg);
   for (uint32_t t = threadIdx.x; t < kStacksPerBlock * stride; t += kUploadThreads) {
     const uint32_t st = t / stride, w = t % stride;
     if (s0 + st >= n_stacks) break;
@@ -869,7 +869,7 @@ __global__ __launch_bounds__(kUploadThreads) void upload_stacks_kernel(const uin
     uint32_t out;
     if (w < kStackHdrWords) out = k[w];
     else {
-      const uint32_t l = (w - kStackHdrWords) / n_off, sgm = (w - kStackHdrWords) % n_off, key = k[kStackHdrWords + l];
+      const uint32_t sgm = (w - kStackHdrWords) / kStackLists, l = (w - kStackHdrWords) % kStackLists, key = k[kStackHdrWords + l];
       const uint32_t* key_off = reinterpret_cast<const uint32_t*>((uintptr_t)k[kStackHdrWords + kStackLists] |
                                                                   ((uintptr_t)k[kStackHdrWords + kStackLists + 1] << 32));
       out = key == kNoKey ? 0u : key_off[(size_t)key * n_seg + sgm];
@@ -984,8 +984,7 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   if (tid == 0) sm.any_walk = 0u;
   __syncthreads();
   const RowDesc rd = rows[b];
-  const uint32_t n_off = (uint32_t)voc.n_seg + 1u;
-  const uint32_t hdr_stride = kStackHdrWords + kStackLists * n_off;
+  const uint32_t hdr_stride = stack_hdr_stride(voc.n_seg);
   const uint32_t n_lists = rd.n_stacks * kStackLists;
   // may the request end here?  then its stop tokens are allowed (the first kFillThreads of them are fetched now)
   const bool may_end = rd.flags & 1u;
@@ -1015,11 +1014,14 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
       if (s0 + q < rd.n_stacks) {
         const XGM_GLOBAL uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + s0 + q) * hdr_stride;
         acc_row[q] = sh[kStackHdrTop] >> 16;
-#pragma unroll
-        for (uint32_t l = 0; l < kStackLists; ++l) {
-          const XGM_GLOBAL uint32_t* off = sh + kStackHdrWords + l * n_off + (uint32_t)seg;
-          lst[q][l] = make_uint2(off[0], off[1]);
-        }
+        static_assert(kStackLists == 4, "the offsets of a segment's four lists are one 16-byte load");
+        const uint4* off = reinterpret_cast<const uint4*>(stack_hdrs_ + (size_t)(rd.stack_begin + s0 + q) * hdr_stride +
+                                                          stack_hdr_off((uint32_t)seg, 0u));
+        const uint4 o0 = off[0], o1 = off[1];  // where the lists begin in this segment, and in the next
+        lst[q][0] = make_uint2(o0.x, o1.x);
+        lst[q][1] = make_uint2(o0.y, o1.y);
+        lst[q][2] = make_uint2(o0.z, o1.z);
+        lst[q][3] = make_uint2(o0.w, o1.w);
       }
     }
     uint32_t aw[2][kWordsPerThread], first[2][kStackLists];
@@ -1146,7 +1148,7 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
   const SlotMeta cur = bt.meta[(size_t)b * bt.H + head];
   if (tok < 0) return;  // this row is left alone (its status too)
   const uint32_t n_off = (uint32_t)bt.n_seg + 1u;
-  const uint32_t hdr_stride = kStackHdrWords + kStackLists * n_off;
+  const uint32_t hdr_stride = stack_hdr_stride(bt.n_seg);
   const int32_t next = (head + 1) % bt.H;
   const uint32_t sb = ((uint32_t)b * bt.H + next) * kBatchMaxStacks;
   const uint32_t fb = ((uint32_t)b * bt.H + next) * kBatchRowFrames;
@@ -1292,9 +1294,9 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
     }
     // headers: where the lists' segments start
     for (uint32_t item = tid; item < ns * kStackLists * n_off; item += kAcceptThreads) {
-      const uint32_t r = item / (kStackLists * n_off), l = item / n_off % kStackLists, sgm = item % n_off;
+      const uint32_t r = item / (kStackLists * n_off), sgm = item / kStackLists % n_off, l = item % kStackLists;
       const uint32_t key = keys[r][l];
-      bt.hdrs[(size_t)(sb + r) * hdr_stride + kStackHdrWords + l * n_off + sgm] =
+      bt.hdrs[(size_t)(sb + r) * hdr_stride + stack_hdr_off(sgm, l)] =
           key == kNoKey ? 0u : dc.key_off[(size_t)key * (uint32_t)bt.n_seg + sgm];
     }
     __syncthreads();
@@ -1356,7 +1358,7 @@ __global__ __launch_bounds__(256) void batch_fork_copy_kernel(DevBatch bt, const
   if (src < 0 || src == b) return;
   if (src >= bt.B || bt.cache[b].acc != bt.cache[src].acc) return;  // reported by the second kernel
   const uint32_t tid = threadIdx.x;
-  const uint32_t hdr_stride = kStackHdrWords + kStackLists * ((uint32_t)bt.n_seg + 1u);
+  const uint32_t hdr_stride = stack_hdr_stride(bt.n_seg);
   const uint32_t from = (uint32_t)src * bt.H + bt.head[src], to = (uint32_t)b * bt.H + (bt.head[b] + 1) % bt.H;
   const SlotMeta m = bt.meta[from];
   const uint32_t* sh = bt.hdrs + (size_t)from * kBatchMaxStacks * hdr_stride;

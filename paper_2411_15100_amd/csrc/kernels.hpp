@@ -154,14 +154,17 @@ struct RowDesc {
   uint32_t n_frames;         // stack after stack
   uint32_t epoch;            // device-resident states: how often the row's state has changed (names the state in a record)
 };
-// A stack header is kStackHdrWords + kStackLists * (n_seg + 1) uint32 words:
+// A stack header is kStackHdrWords + (n_seg + 1) * kStackLists uint32 words (a multiple of 16 bytes):
 //   [kStackHdrTop] top node | its row of DevCache::acc (or kNoAccRow) << 16, [kStackHdrDepth] number of frames,
 //   [kStackHdrFrames] offset of its frames (bottom first) in the uint16 frame array, [3] unused,
-//   [kStackHdrWords + l * (n_seg + 1) + s] where the entries of segment s of the stack's level-l list start
-//   (s = n_seg: where the last segment's end); a stack without that list (too shallow) has all of them equal.
+//   [stack_hdr_off(s, l)] where the entries of segment s of the stack's level-l list start (s = n_seg: where
+//   the last segment's end); a stack without that list (too shallow, or a level that is not kept) has all of
+//   them equal.  The lists' offsets of one segment lie side by side, so that the workgroup of (row, segment)
+//   finds the begin and the end of all its lists of a stack in 32 consecutive bytes.
 constexpr uint32_t kStackHdrTop = 0, kStackHdrDepth = 1, kStackHdrFrames = 2, kStackHdrWords = 4;
 constexpr uint32_t kStackLists = 1 + kCtxLevels;
-inline uint32_t stack_hdr_stride(int32_t n_seg) { return kStackHdrWords + kStackLists * ((uint32_t)n_seg + 1u); }
+constexpr uint32_t stack_hdr_stride(int32_t n_seg) { return kStackHdrWords + kStackLists * ((uint32_t)n_seg + 1u); }
+constexpr uint32_t stack_hdr_off(uint32_t seg, uint32_t l) { return kStackHdrWords + seg * kStackLists + l; }
 
 // ---- matcher states that live on the device (section 3.3 on the GPU: the
 // sampled tokens move the stacks on without a round trip to the host).
