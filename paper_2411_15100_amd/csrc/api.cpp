@@ -1474,6 +1474,7 @@ static void read_row_state(const xgm_batch& bt, int32_t row, bool* terminated, s
   }
 }
 
+extern "C++" {  // (helpers that return C++ types)
 namespace {
 // is the token allowed from some of these stacks?  (exact, on the host; throws if the host limits are exceeded too)
 bool host_decides(const Automaton& A, const xgm_vocab& v, const std::vector<Stack>& stacks, int32_t id) {
@@ -1509,6 +1510,7 @@ std::vector<std::array<uint32_t, 4>> fresh_records(const OverflowLog* log, uint3
   return out;
 }
 }  // namespace
+}  // extern "C++"
 
 int xgm_fill_overflow_fixup(void* hip_stream) {
   API_BEGIN
@@ -1559,6 +1561,7 @@ const uint32_t* xgm_fill_overflow_count_device(void) {
 }
 
 // ------------------------------------------------- device-resident states
+extern "C++" {  // (helpers that return C++ types)
 namespace {
 // what the matcher's current state looks like in slot `slot` of row `row`
 struct PackedState {
@@ -1611,6 +1614,7 @@ void write_state(const xgm_batch& bt, int32_t row, int32_t slot, PackedState p, 
   HIP_OK(hipMemcpy(bt.dev.rows + row, &p.row, sizeof(RowDesc), hipMemcpyHostToDevice));
 }
 }  // namespace
+}  // extern "C++"
 
 int xgm_batch_create(xgm_matcher* const* ms, int32_t B, int32_t history, void* hip_stream, xgm_batch** out) {
   API_BEGIN
