@@ -567,7 +567,7 @@ int xgm_debug_matcher_accept_token_walk(xgm_matcher* m, int32_t token_id) {
     std::vector<uint16_t> live(s.begin(), s.end());
     count = 0;
     const int rc = walk_token<false>(T, tk, bytes, n, live.back(), live.data(), (uint32_t)live.size(), (uint32_t*)nullptr,
-                                     (const uint32_t*)nullptr, 0, (uint32_t*)nullptr, collect);
+                                     0u, 0, (uint32_t*)nullptr, collect);
     if (rc == kOverflow || overflow) return fail(XGM_ERR_TOO_LARGE, "accept_token_walk: the walk exceeded its limits");
     for (uint32_t k = 0; k < count; ++k)
       next.insert(Stack(cand.begin() + (size_t)k * kBatchMaxDepth, cand.begin() + (size_t)k * kBatchMaxDepth + depth[k]));

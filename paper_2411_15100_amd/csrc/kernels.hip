@@ -86,6 +86,20 @@ struct LdsTabT {
       if (c >= lo && c <= hi) { k = 1; single = (0xFFFFu << 16) | (h.x >> 16); }
     }
   }
+  __device__ __forceinline__ bool plain_move(uint32_t n, uint32_t c, uint32_t& dst, uint32_t& fin, uint32_t& after) const {
+    const uint2 h = header(n);
+    fin = h.y & 1u;
+    after = (rd32(off_follow + ((h.y >> 16) * 8u + (c >> 5)) * 4u, follow_lds) >> (c & 31)) & 1u;
+    if (h.y & 2u) {
+      const uint32_t cl = rd8(c, cls_lds);
+      const uint32_t si = rd8(off_shapes + (h.x & 0xFFFFu) * n_cls + cl, shapes_lds);
+      if (si == 0xFFu) return false;
+      dst = rd16(off_targets + ((h.x >> 16) + si) * 2u, targets_lds);
+      return dst < 0x8000u;
+    }
+    dst = h.x >> 16;
+    return c >= (h.x & 0xFFu) && c <= ((h.x >> 8) & 0xFFu);
+  }
   __device__ __forceinline__ uint32_t alt(uint32_t idx) const { return rd32(off_alts + idx * 4u, alts_lds); }
   __device__ __forceinline__ bool is_final(uint32_t n) const { return header(n).y & 1u; }
   __device__ __forceinline__ bool is_dead_end(uint32_t n) const { return header(n).y & 4u; }
@@ -97,11 +111,10 @@ struct LdsTabT {
   __device__ __forceinline__ bool can_follow(const uint2& h, uint32_t c) const {
     return (rd32(off_follow + ((h.y >> 16) * 8u + (c >> 5)) * 4u, follow_lds) >> (c & 31)) & 1u;
   }
-  // generic pointer to the 256-bit FOLLOW set of node n's rule (read on the rare exit from the start frame)
-  __device__ __forceinline__ const uint32_t* follow_of(uint32_t n) const {
-    const uint32_t off = off_follow + (header(n).y >> 16) * 32u;
-    return (kSmallInLds || follow_lds) ? (const uint32_t*)(const XGM_LDS uint32_t*)(lds + off)
-                                       : (const uint32_t*)(const XGM_GLOBAL uint32_t*)(img + off);
+  // the rule of node n, as the handle of its 256-bit FOLLOW set; is byte c in the set of rule r?
+  __device__ __forceinline__ uint32_t follow_of(uint32_t n) const { return header(n).y >> 16; }
+  __device__ __forceinline__ uint32_t follows(uint32_t r, uint32_t c) const {
+    return (rd32(off_follow + (r * 8u + (c >> 5)) * 4u, follow_lds) >> (c & 31)) & 1u;
   }
 };
 using LdsTab = LdsTabT<false>;
@@ -732,47 +745,25 @@ __global__ void patch_classes_kernel(DevVocab voc, const uint32_t* __restrict__ 
 
 // One 16-byte group of a logits row (section 2.1): `mk` holds the mask bits of
 // its EPT = 16 / ESIZE elements, e0 is the index of its first element.  All
-// allowed: nothing is touched.  None allowed: one 16-byte store of the -inf
-// pattern.  One or two disallowed: those elements are stored by themselves,
-// nothing is read.  More: the group is read, blended and stored whole (many
-// small stores cost more than the read).  That is the stand-alone kernel, one
-// group per thread.  The one-launch kernel, where a thread has several groups
-// and waits for its fetches anyway, blends every group that has both kinds
-// (measured on the serving masks, where four rows in ten allow nearly every
-// token: 16.3 -> 15.3 us for the one-launch step, 8.3 -> 9.3 us for the
-// stand-alone kernel; blending whole 64-byte lines was slower in both).
-template <int ESIZE>
-__device__ __forceinline__ uint4 blend_group(uint4 v, uint32_t mk, uint32_t neg_inf) {
-  if (ESIZE == 2) {
-    const uint32_t two = neg_inf | (neg_inf << 16);
-    uint32_t* q = reinterpret_cast<uint32_t*>(&v);
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const uint32_t keep = ((mk >> (2 * h)) & 1u ? 0x0000FFFFu : 0u) | ((mk >> (2 * h + 1)) & 1u ? 0xFFFF0000u : 0u);
-      q[h] = (q[h] & keep) | (two & ~keep);
-    }
-  } else {
-    if (!(mk & 1u)) v.x = neg_inf;
-    if (!(mk & 2u)) v.y = neg_inf;
-    if (!(mk & 4u)) v.z = neg_inf;
-    if (!(mk & 8u)) v.w = neg_inf;
-  }
-  return v;
-}
+// allowed: nothing is touched.  None allowed: one 16-byte streaming store of the
+// -inf pattern.  Both kinds: every disallowed element is stored by itself.  The
+// logits are never read: a group that is fetched, blended and stored whole makes
+// its wave wait for the fetch, while stores are issued and forgotten (measured
+// on the serving masks, where four rows in ten allow nearly every token and the
+// others nearly none: 15.6 -> 13.5 us for the one-launch step and 7.9 -> 7.5 us
+// for the stand-alone kernel against blending; merging neighbouring elements
+// into 4-byte stores, or streaming stores for single elements, were slower).
 template <int ESIZE>
 __device__ __forceinline__ void apply_group(unsigned char* p, uint32_t mk, int32_t e0, int32_t V_logits, uint32_t neg_inf) {
   constexpr int EPT = 16 / ESIZE;
   constexpr uint32_t kAll = (1u << EPT) - 1u;
   if (mk == kAll) return;
-  const bool whole = e0 + EPT <= V_logits;
-  if (mk == 0u && whole) {
+  if (mk == 0u && e0 + EPT <= V_logits) {
     // a streaming store: the line is written whole and not read again here, so it need not stay in the caches
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
     const uint32_t w = ESIZE == 2 ? (neg_inf | (neg_inf << 16)) : neg_inf;
     const v4u val = {w, w, w, w};
     __builtin_nontemporal_store(val, reinterpret_cast<v4u*>(p));
-  } else if (whole && EPT - __popc(mk) > 2) {
-    *reinterpret_cast<uint4*>(p) = blend_group<ESIZE>(*reinterpret_cast<const uint4*>(p), mk, neg_inf);
   } else {
 #pragma unroll
     for (int h = 0; h < EPT; ++h)
@@ -792,40 +783,18 @@ struct LogitsRange {
   const uint32_t* words;  // the workgroup's mask words; bit 0 of words[0] is element e_begin
   int32_t e_begin, e_end, V, V_logits;
   uint32_t neg_inf;
-  // thread t of nt: the range's groups t, t + nt, ...  Four groups at a time: the ones that must be read
-  // (allowed and disallowed logits side by side) are fetched together, then all four are written: the
-  // wave's memory counter is in order, so a fetch issued after a store would wait for that store too.
+  // thread t of nt: the range's groups t, t + nt, ...
   __device__ __forceinline__ void groups(uint32_t t, uint32_t nt) const {
     if constexpr (APPLY != 0) {
       constexpr int EPT = 16 / APPLY;
       constexpr uint32_t kAll = (1u << EPT) - 1u;
-      constexpr int G = 4;
-      for (int32_t base = e_begin + (int32_t)t * EPT; base < e_end; base += (int32_t)nt * EPT * G) {
-        uint32_t mk[G];
-        uint4 v[G];
-        bool blend[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          const int32_t e0 = base + g * (int32_t)nt * EPT;
-          mk[g] = kAll;  // (a group beyond the range: nothing to do)
-          blend[g] = false;
-          if (e0 < e_end) {
-            mk[g] = 0u;
-            if (e0 < V) {
-              mk[g] = (words[(e0 - e_begin) >> 5] >> (e0 & 31)) & kAll;
-              if (e0 + EPT > V) mk[g] &= (1u << (V - e0)) - 1u;
-            }
-            blend[g] = e0 + EPT <= V_logits && mk[g] != 0u && mk[g] != kAll;
-            if (blend[g]) v[g] = *reinterpret_cast<const uint4*>(row + (size_t)e0 * APPLY);
-          }
+      for (int32_t e0 = e_begin + (int32_t)t * EPT; e0 < e_end; e0 += (int32_t)nt * EPT) {
+        uint32_t mk = 0u;  // (columns beyond the vocabulary are masked)
+        if (e0 < V) {
+          mk = (words[(e0 - e_begin) >> 5] >> (e0 & 31)) & kAll;
+          if (e0 + EPT > V) mk &= (1u << (V - e0)) - 1u;
         }
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          const int32_t e0 = base + g * (int32_t)nt * EPT;
-          unsigned char* p = row + (size_t)e0 * APPLY;
-          if (blend[g]) *reinterpret_cast<uint4*>(p) = blend_group<APPLY>(v[g], mk[g], neg_inf);
-          else if (mk[g] != kAll) apply_group<APPLY>(p, mk[g], e0, V_logits, neg_inf);  // all rejected, or the ragged end
-        }
+        apply_group<APPLY>(row + (size_t)e0 * APPLY, mk, e0, V_logits, neg_inf);
       }
     }
   }
@@ -939,7 +908,7 @@ __device__ __forceinline__ void fill_walks(const Tab& T, FillShared& sm, const R
         const TokenRef t = load_token(voc, (int32_t)id);
         const uint32_t start = drop == 0u ? top : live[depth - 1u - drop];
         res = walk_token<false>(T, t.tk, t.ext, t.len, start, live, depth - drop, COUNT ? &n_steps : nullptr,
-                                (const uint32_t*)nullptr, drop == 0u ? 0 : (int)pos);
+                                0u, drop == 0u ? 0 : (int)pos);
       }
       if (COUNT) my_steps += n_steps;
       if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, id, rd.epoch);  // decided on the host
@@ -1187,7 +1156,7 @@ __global__ __launch_bounds__(kAcceptThreads) void batch_accept_kernel(DevBatch b
       LdsStackSink sink{cand, cdepth, &ccount, &coverflow, kBatchMaxCandidates, kBatchMaxDepth};
       const CollectStacks<LdsTab, LdsStackSink> collect{&T, &sink};
       const int res = walk_token<false>(T, tk, ext, len, h[kStackHdrTop] & 0xFFFFu, fr, h[kStackHdrDepth], (uint32_t*)nullptr,
-                                        (const uint32_t*)nullptr, 0, (uint32_t*)nullptr, collect);
+                                        0u, 0, (uint32_t*)nullptr, collect);
       if (res == kOverflow) coverflow = 1u;
     }
     __syncthreads();

@@ -46,14 +46,27 @@ struct CompactTab {
       if (c >= lo && c <= hi) { k = 1; single = (0xFFFFu << 16) | (h.x >> 16); }
     }
   }
+  // The step at (n, c) when it is nothing but a move along a byte edge (one alternative, no rule reference):
+  // true, the node moved to, and `fin` / `after` as in lookup().  False for every other kind of step.
+  XGM_HD bool plain_move(uint32_t n, uint32_t c, uint32_t& dst, uint32_t& fin, uint32_t& after) const {
+    const uint2 h = (n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n];
+    fin = h.y & 1u;
+    after = (v.follow_rules[(h.y >> 16) * 8 + (c >> 5)] >> (c & 31)) & 1u;
+    if (h.y & 2u) {
+      const uint32_t si = v.shapes[(h.x & 0xFFFFu) * v.n_cls + v.cls[c]];
+      if (si == 0xFFu) return false;
+      dst = v.targets[(h.x >> 16) + si];
+      return dst < 0x8000u;
+    }
+    dst = h.x >> 16;
+    return c >= (h.x & 0xFFu) && c <= ((h.x >> 8) & 0xFFu);
+  }
   XGM_HD uint32_t alt(uint32_t idx) const { return v.alts[idx]; }
   XGM_HD bool is_final(uint32_t n) const { return ((n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n]).y & 1u; }
   XGM_HD bool is_dead_end(uint32_t n) const { return ((n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n]).y & 4u; }
-  // the 256-bit FOLLOW set of node n's rule
-  XGM_HD const uint32_t* follow_of(uint32_t n) const {
-    const uint2 h = (n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n];
-    return v.follow_rules + (h.y >> 16) * 8;
-  }
+  // the rule of node n, as the handle of its 256-bit FOLLOW set; is byte c in the set of rule r?
+  XGM_HD uint32_t follow_of(uint32_t n) const { return ((n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n]).y >> 16; }
+  XGM_HD uint32_t follows(uint32_t r, uint32_t c) const { return (v.follow_rules[r * 8 + (c >> 5)] >> (c & 31)) & 1u; }
 };
 
 // The first 15 bytes of a token as four plain words (kept in registers: the
@@ -92,9 +105,9 @@ XGM_HD uint32_t token_byte(const uint4& tk, const uint8_t* ext, int i) { return 
 //                result kAccept / kUncertain / kReject as in section 3.1,
 //                refined by one byte of context (section 3.2 in miniature):
 //                leaving the start frame while bytes remain only counts if
-//                the next byte is in `follow` (256-bit set: the bytes that can
-//                come right after an instance of the start node's rule in any
-//                context); a token that left the frame only in front of other
+//                the next byte is in the FOLLOW set of rule `follow` (the bytes
+//                that can come right after an instance of the start node's rule
+//                in any context; `T.follow_of(start_node)`); a token that left the frame only in front of other
 //                bytes is kUncertainPlain: context-dependent by section 3.1
 //                alone, rejected in every context by the refinement.
 // BUILD = false: frames below are live[0 .. depth-2]; result kAccept (token
@@ -119,7 +132,7 @@ struct FirstPathEnds {
 template <bool BUILD, class Tab, class Live, class End = FirstPathEnds>
 XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const int len,
                       const uint32_t start_node, const Live& live, const uint32_t depth,
-                      uint32_t* steps_out = nullptr, const uint32_t* follow = nullptr, const int i0 = 0,
+                      uint32_t* steps_out = nullptr, const uint32_t follow = 0u, const int i0 = 0,
                       uint32_t* exits_out = nullptr, const End& at_end = End()) {
   if (len > kMaxTokenLen) return kOverflow;
   const TokenWords tw(tk);
@@ -146,7 +159,7 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
         // pending alternative, so that a run through a rule that may end after every byte (the inside of
         // a string, a number) leaves nothing to come back to.
         left_frame = true;
-        if ((follow[c >> 5] >> (c & 31)) & 1u) {
+        if (T.follows(follow, c)) {
           left_frame_follow = true;
           if (exits_out) *exits_out |= 1u << (i < 31 ? i : 31);
         }
