@@ -798,6 +798,46 @@ struct LogitsRange {
       }
     }
   }
+  // The same for a range of kSegTokens elements that lies inside both the vocabulary and the row (every
+  // segment but a row's last), written for the fewest instructions: with 2432 workgroups of four waves on
+  // 1024 SIMDs the launch is bound by instruction issue, and each 60 instructions per thread cost a
+  // microsecond.  Thread t of NT takes the groups t, t + NT, ...: their mask bits are fetched from LDS
+  // first (one byte each for 2-byte logits), then a group with nothing allowed is one streaming store and a
+  // group with both kinds one 2- or 4-byte store per disallowed element, in a loop that runs as often as
+  // the lane of the wave with the most of them needs.
+  template <int NT>
+  __device__ __forceinline__ void whole_segment(uint32_t t) const {
+    if constexpr (APPLY != 0) {
+      constexpr int EPT = 16 / APPLY;
+      constexpr uint32_t kAll = (1u << EPT) - 1u;
+      constexpr int kGroups = kSegTokens / EPT / NT;  // per thread
+      static_assert(kSegTokens % (EPT * NT) == 0, "every thread takes the same number of groups");
+      typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+      const uint32_t fill = APPLY == 2 ? (neg_inf | (neg_inf << 16)) : neg_inf;
+      const v4u val = {fill, fill, fill, fill};
+      unsigned char* p = row + ((size_t)e_begin * APPLY + (size_t)t * 16u);
+      uint32_t mk[kGroups];
+#pragma unroll
+      for (int k = 0; k < kGroups; ++k) {
+        const uint32_t g = (uint32_t)k * NT + t;
+        if (APPLY == 2) mk[k] = reinterpret_cast<const unsigned char*>(words)[g];
+        else mk[k] = (words[g >> 3] >> ((g & 7u) * 4u)) & kAll;
+      }
+#pragma unroll
+      for (int k = 0; k < kGroups; ++k) {
+        unsigned char* q = p + (size_t)k * NT * 16u;
+        if (mk[k] == 0u) {
+          __builtin_nontemporal_store(val, reinterpret_cast<v4u*>(q));
+        } else {
+          for (uint32_t x = ~mk[k] & kAll; x; x &= x - 1u) {
+            const uint32_t h = (uint32_t)__ffs(x) - 1u;
+            if (APPLY == 2) reinterpret_cast<uint16_t*>(q)[h] = (uint16_t)neg_inf;
+            else reinterpret_cast<uint32_t*>(q)[h] = neg_inf;
+          }
+        }
+      }
+    }
+  }
 };
 
 // ---------------------------------------------------------------- kernel (b)
@@ -1059,7 +1099,8 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
     logits.V = voc.V;
     logits.V_logits = fa.V_logits;
     logits.neg_inf = fa.neg_inf;
-    logits.groups(tid, kFillThreads);
+    if (n_words == kSegWords && id0 + kSegTokens <= min(voc.V, fa.V_logits)) logits.template whole_segment<kFillThreads>(tid);
+    else logits.groups(tid, kFillThreads);
   }
   if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
 }
