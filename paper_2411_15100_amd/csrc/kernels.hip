@@ -1099,7 +1099,7 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
     logits.V = voc.V;
     logits.V_logits = fa.V_logits;
     logits.neg_inf = fa.neg_inf;
-    if (n_words == kSegWords && id0 + kSegTokens <= min(voc.V, fa.V_logits)) logits.template whole_segment<kFillThreads>(tid);
+    if (logits.e_end == id0 + kSegTokens && logits.e_end <= voc.V) logits.template whole_segment<kFillThreads>(tid);
     else logits.groups(tid, kFillThreads);
   }
   if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
@@ -1406,27 +1406,28 @@ __global__ void batch_fork_commit_kernel(DevBatch bt, const int32_t* __restrict_
 // ---------------------------------------------------------------- kernel (c)
 constexpr int kApplyThreads = 256;
 
-// Section 2.1: logits of disallowed tokens become -inf.  A thread owns one
-// group: 16 bytes of a logits row (8 bf16/fp16 or 4 fp32 elements) with its
-// mask bits; the 64 groups of a wave are contiguous (1 KiB); see apply_group.
-// ESIZE = bytes per element.
+// Section 2.1: logits of disallowed tokens become -inf.  One workgroup per
+// (segment of kSegTokens elements, row), as in the one-launch kernel, and with
+// its code (LogitsRange): a thread takes 16-byte groups (8 bf16/fp16 or 4 fp32
+// elements), the 64 groups of a wave are contiguous (1 KiB); the mask bits come
+// straight from the bitmask in global memory.  ESIZE = bytes per element.
 template <int ESIZE>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(unsigned char* __restrict__ logits, int64_t row_stride,
                                                               const uint32_t* __restrict__ bitmask, int32_t W_mask,
                                                               int32_t V_logits, int32_t V_mask,
                                                               const int32_t* __restrict__ row_index, uint32_t neg_inf) {
-  constexpr int EPT = 16 / ESIZE;            // elements per group
-  constexpr uint32_t kAll = (1u << EPT) - 1u;
-  const int32_t j = blockIdx.y;
+  const int32_t j = blockIdx.y, seg = blockIdx.x;
   const int64_t lrow = row_index ? row_index[j] : j;
-  const int32_t e0 = (blockIdx.x * kApplyThreads + threadIdx.x) * EPT;
-  if (e0 >= V_logits) return;
-  uint32_t mk = 0u;
-  if (e0 < V_mask) {
-    mk = (bitmask[(size_t)j * W_mask + (e0 >> 5)] >> (e0 & 31)) & kAll;
-    if (e0 + EPT > V_mask) mk &= (1u << (V_mask - e0)) - 1u;
-  }
-  apply_group<ESIZE>(logits + ((size_t)lrow * row_stride + e0) * ESIZE, mk, e0, V_logits, neg_inf);
+  LogitsRange<ESIZE> r;
+  r.row = logits + (size_t)lrow * row_stride * ESIZE;
+  r.words = bitmask + (size_t)j * W_mask + (size_t)seg * kSegWords;
+  r.e_begin = seg * kSegTokens;
+  r.e_end = min(r.e_begin + kSegTokens, V_logits);
+  r.V = V_mask;
+  r.V_logits = V_logits;
+  r.neg_inf = neg_inf;
+  if (r.e_begin + kSegTokens <= min(V_mask, V_logits)) r.template whole_segment<kApplyThreads>(threadIdx.x);
+  else r.groups(threadIdx.x, kApplyThreads);
 }
 
 // any alignment, any stride: one element per thread
@@ -1652,10 +1653,7 @@ void launch_apply(void* logits, int elem_size, uint32_t neg_inf, int32_t V_logit
   const bool aligned = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && ((row_stride * elem_size) % 16 == 0);
   unsigned char* p = static_cast<unsigned char*>(logits);
   if (aligned) {
-    const int ept = 16 / elem_size;
-    const int32_t groups = (V_logits + ept - 1) / ept;
-    const int32_t per_block = kApplyThreads;
-    dim3 grid((groups + per_block - 1) / per_block, n_rows);
+    dim3 grid((V_logits + kSegTokens - 1) / kSegTokens, n_rows);
     if (elem_size == 2)
       hipLaunchKernelGGL(apply_kernel<2>, grid, dim3(kApplyThreads), 0, stream, p, row_stride, bitmask, W_mask,
                          V_logits, V_mask, row_index, neg_inf);
