@@ -889,7 +889,6 @@ __global__ __launch_bounds__(kUploadThreads) void upload_stacks_kernel(const uin
 
 constexpr int kFillThreads = 256;
 constexpr int kFillFramesLds = 1024;            // live frames kept in LDS (deeper stacks: global memory)
-constexpr int kFillMaxLists = 64 * kStackLists;  // XGM_MAX_STACKS stacks with their lists
 
 // One workgroup of 4 waves serves one request and one segment of 8192 token
 // ids = 256 mask words, which it owns in LDS:
@@ -901,44 +900,46 @@ constexpr int kFillMaxLists = 64 * kStackLists;  // XGM_MAX_STACKS stacks with t
 //      the tokens accepted given the node below the top frame, those accepted
 //      given the two and the three nodes below) are streamed once, coalesced;
 //      an accepted entry sets its bit with an LDS atomic, a walk entry is only
-//      counted;
-//   3. lists that have walk entries (they sit at the list's end) get them
-//      decided against the live stack: only then are the request's automaton
+//      noted (one flag for the workgroup);
+//   3. if there was a walk entry, the lists are gone through again and theirs
+//      are decided against the live stack: only then are the request's automaton
 //      tables and frames copied into LDS.  Most launches walk nothing;
 //   4. the words are stored once, coalesced, and - in the fused instantiation -
 //      the logits of the segment are masked straight from them.
-// No global atomics, no second pass over the mask.
+// No global atomics, no second pass over the mask.  The launch is bound by
+// instruction issue as much as by memory (2432 workgroups of four waves on 1024
+// SIMDs): what every thread would do for nothing is kept behind tests that are
+// the same for the whole workgroup (an empty list costs a scalar compare).
 // COUNT = true additionally sums the automaton steps of all walks into
 // *step_counter (instrumentation for the benchmark; never used on the hot path).
 struct FillShared {
   uint32_t words[kSegWords];
-  uint2 list[kFillMaxLists];        // begin, end of every list of this segment
-  uint32_t n_walk[kFillMaxLists];   // walk entries found in each
   uint16_t live[kFillFramesLds];
   uint32_t any_walk;
 };
 
 // Decides the walk entries of the workgroup's lists (all threads call this).
 template <bool COUNT, bool KEEP_UNDECIDED, class Tab>
-__device__ __forceinline__ void fill_walks(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b, const int32_t id0,
+__device__ __forceinline__ void fill_walks(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b, const int32_t seg,
                                            const uint32_t n_lists, const uint32_t frame0, const bool frames_in_lds,
                                            const XGM_GLOBAL uint32_t* __restrict__ stack_hdrs, const uint32_t hdr_stride,
                                            const XGM_GLOBAL uint16_t* __restrict__ frames, const DevVocab& voc,
                                            OverflowLog* log, uint32_t seq, unsigned long long& my_steps) {
   const XGM_GLOBAL uint32_t* entries = (const XGM_GLOBAL uint32_t*)rd.entries;
+  const int32_t id0 = seg * kSegTokens;
   for (uint32_t l = 0; l < n_lists; ++l) {
-    const uint32_t nw = sm.n_walk[l];
-    if (nw == 0u) continue;
     const XGM_GLOBAL uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + l / kStackLists) * hdr_stride;
     const uint32_t top = sh[kStackHdrTop] & 0xFFFFu, depth = sh[kStackHdrDepth], f_off = sh[kStackHdrFrames];
     LiveView live;
     live.lds = (const XGM_LDS uint16_t*)sm.live + (f_off - frame0);
     live.glob = frames + f_off;
     live.lo = frames_in_lds ? 0u : 0xFFFFFFFFu;
-    const uint32_t end = sm.list[l].y;
-    for (uint32_t j = end - nw + threadIdx.x; j < end; j += kFillThreads) {
+    // the list's entries of this segment (it ends where its next segment begins); the accepted ones are done
+    const uint32_t begin = sh[stack_hdr_off((uint32_t)seg, l % kStackLists)], end = sh[stack_hdr_off((uint32_t)seg + 1u, l % kStackLists)];
+    for (uint32_t j = begin + threadIdx.x; j < end; j += kFillThreads) {
       const uint32_t e = entries[j];
       const uint32_t id = e & kEntryIdMask, kind = e >> kEntryKindShift, pos = (e >> kEntryPosShift) & 0xFFu;
+      if (kind == kEntryAccepted) continue;
       const uint32_t rel = id - (uint32_t)id0;
       if ((sm.words[rel >> 5] >> (rel & 31u)) & 1u) continue;  // already allowed
       const uint32_t drop = kind == kEntryWalkTop ? 0u : kind - 1u;  // frames above the one the walk starts in
@@ -955,6 +956,51 @@ __device__ __forceinline__ void fill_walks(const Tab& T, FillShared& sm, const R
       if (res == kAccept || (KEEP_UNDECIDED && res == kOverflow)) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31u));
     }
   }
+}
+
+// The whole of step 3, kept out of line: the request's tables and live frames into LDS, then the walks.  Nearly
+// no workgroup comes here, and inlined the walk's registers and code would weigh on every workgroup's path
+// (the kernel ran out of scalar registers and kept them in lanes of a vector register).  What it needs it
+// reads again: the row descriptor, and of the vocabulary the three arrays a token is fetched from.
+struct FillWalkArgs {
+  const RowDesc* row;
+  const uint32_t* stack_hdrs;
+  const uint16_t* frames;
+  const uint4* tok_by_id;
+  const uint32_t* off_by_id;
+  const uint8_t* bytes;
+  OverflowLog* log;
+  unsigned long long* step_counter;
+  int32_t b, seg, n_seg;
+  uint32_t seq;
+};
+template <bool COUNT, bool KEEP_UNDECIDED>
+__device__ __noinline__ void fill_walk_path(const FillWalkArgs a, FillShared XGM_LDS* shared, unsigned char XGM_LDS* staged) {
+  FillShared& sm = *(FillShared*)shared;
+  unsigned char* smem = (unsigned char*)staged;
+  const RowDesc rd = *a.row;
+  const XGM_GLOBAL uint32_t* stack_hdrs = (const XGM_GLOBAL uint32_t*)a.stack_hdrs;
+  const XGM_GLOBAL uint16_t* frames = (const XGM_GLOBAL uint16_t*)a.frames;
+  DevVocab voc{};
+  voc.tok_by_id = a.tok_by_id;
+  voc.off_by_id = a.off_by_id;
+  voc.bytes = a.bytes;
+  unsigned long long my_steps = 0;
+  const uint32_t frame0 = rd.frame_begin, n_frames = rd.n_frames, n_lists = rd.n_stacks * kStackLists;
+  const uint32_t hdr_stride = stack_hdr_stride(a.n_seg);
+  const bool frames_in_lds = n_frames <= kFillFramesLds;
+  stage_tables(rd.tab, smem, kFillThreads);
+  if (frames_in_lds)
+    for (uint32_t k = threadIdx.x; k < n_frames; k += kFillThreads) sm.live[k] = frames[frame0 + k];
+  __syncthreads();
+  if (small_sections_staged(rd.tab))
+    fill_walks<COUNT, KEEP_UNDECIDED>(LdsTabT<true>(rd.tab, smem), sm, rd, a.b, a.seg, n_lists, frame0, frames_in_lds, stack_hdrs,
+                                      hdr_stride, frames, voc, a.log, a.seq, my_steps);
+  else
+    fill_walks<COUNT, KEEP_UNDECIDED>(LdsTab(rd.tab, smem), sm, rd, a.b, a.seg, n_lists, frame0, frames_in_lds, stack_hdrs,
+                                      hdr_stride, frames, voc, a.log, a.seq, my_steps);
+  __syncthreads();
+  if (COUNT && my_steps) atomicAdd(a.step_counter, my_steps);
 }
 
 // Eight workgroups of 4 waves per compute unit need 8 waves per SIMD: the second
@@ -980,8 +1026,6 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ FillShared sm;
   const XGM_GLOBAL uint32_t* stack_hdrs = (const XGM_GLOBAL uint32_t*)stack_hdrs_;
-  const XGM_GLOBAL uint16_t* frames = (const XGM_GLOBAL uint16_t*)frames_;
-  unsigned long long my_steps = 0;
   const uint32_t tid = threadIdx.x;
   const int32_t b = (int32_t)blockIdx.y, seg = (int32_t)blockIdx.x;
   const int32_t w_begin = seg * kSegWords;
@@ -989,23 +1033,21 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
   const int32_t id0 = w_begin * 32;
   // LDS is cleared before anything is fetched (a barrier waits for what its threads have in flight)
   for (int32_t w = tid; w < kSegWords; w += kFillThreads) sm.words[w] = 0u;
-  for (int32_t l = tid; l < kFillMaxLists; l += kFillThreads) sm.n_walk[l] = 0u;
   if (tid == 0) sm.any_walk = 0u;
   __syncthreads();
   const RowDesc rd = rows[b];
   const uint32_t hdr_stride = stack_hdr_stride(voc.n_seg);
-  const uint32_t n_lists = rd.n_stacks * kStackLists;
   // may the request end here?  then its stop tokens are allowed (the first kFillThreads of them are fetched now)
   const bool may_end = rd.flags & 1u;
   const int32_t my_stop = may_end && (int32_t)tid < voc.n_stop ? voc.stop_ids[tid] : -1;
   const XGM_GLOBAL uint32_t* acc = (const XGM_GLOBAL uint32_t*)rd.acc;
   const XGM_GLOBAL uint32_t* entries = (const XGM_GLOBAL uint32_t*)rd.entries;
-  auto take = [&](uint32_t e, uint32_t l) {
+  auto take = [&](uint32_t e) {
     if ((e >> kEntryKindShift) == kEntryAccepted) {
       const uint32_t rel = (e & kEntryIdMask) - (uint32_t)id0;
       atomicOr(&sm.words[rel >> 5], 1u << (rel & 31u));
     } else {
-      atomicAdd(&sm.n_walk[l], 1u);
+      sm.any_walk = 1u;
     }
   };
   // 1 + 2. Two stacks at a time: their headers (the same words for every thread), then, in one go, this
@@ -1044,8 +1086,12 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
       }
 #pragma unroll
       for (uint32_t l = 0; l < kStackLists; ++l) {
-        have[q][l] = lst[q][l].x + tid < lst[q][l].y;
-        first[q][l] = have[q][l] ? entries[lst[q][l].x + tid] : 0u;
+        have[q][l] = false;
+        first[q][l] = 0u;
+        if (lst[q][l].x < lst[q][l].y) {  // (the same for every thread: an empty list costs a scalar compare)
+          have[q][l] = lst[q][l].x + tid < lst[q][l].y;
+          if (have[q][l]) first[q][l] = entries[lst[q][l].x + tid];
+        }
       }
     }
 #pragma unroll
@@ -1055,10 +1101,11 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
         if (aw[q][k]) atomicOr(&sm.words[tid + k * kFillThreads], aw[q][k]);
 #pragma unroll
       for (uint32_t l = 0; l < kStackLists; ++l) {
-        const uint32_t li = (s0 + q) * kStackLists + l;
-        if (have[q][l]) take(first[q][l], li);
-        for (uint32_t j = lst[q][l].x + kFillThreads + tid; j < lst[q][l].y; j += kFillThreads) take(entries[j], li);
-        if (tid == 0 && s0 + q < rd.n_stacks) sm.list[li] = lst[q][l];  // (for the walk entries, should there be any)
+        if (lst[q][l].x < lst[q][l].y) {
+          if (have[q][l]) take(first[q][l]);
+          if (lst[q][l].y - lst[q][l].x > (uint32_t)kFillThreads)
+            for (uint32_t j = lst[q][l].x + kFillThreads + tid; j < lst[q][l].y; j += kFillThreads) take(entries[j]);
+        }
       }
     }
   }
@@ -1069,24 +1116,21 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
     }
   __syncthreads();
   // 3. walk entries, if any
-  if (tid < n_lists && sm.n_walk[tid] != 0u) sm.any_walk = 1u;
-  for (uint32_t l = tid + kFillThreads; l < n_lists; l += kFillThreads)
-    if (sm.n_walk[l] != 0u) sm.any_walk = 1u;
-  __syncthreads();
   if (sm.any_walk) {
-    const uint32_t frame0 = rd.frame_begin, n_frames = rd.n_frames;
-    const bool frames_in_lds = n_frames <= kFillFramesLds;
-    stage_tables(rd.tab, smem, kFillThreads);
-    if (frames_in_lds)
-      for (uint32_t k = tid; k < n_frames; k += kFillThreads) sm.live[k] = frames[frame0 + k];
-    __syncthreads();
-    if (small_sections_staged(rd.tab))
-      fill_walks<COUNT, APPLY != 0>(LdsTabT<true>(rd.tab, smem), sm, rd, b, id0, n_lists, frame0, frames_in_lds, stack_hdrs,
-                                    hdr_stride, frames, voc, log, seq, my_steps);
-    else
-      fill_walks<COUNT, APPLY != 0>(LdsTab(rd.tab, smem), sm, rd, b, id0, n_lists, frame0, frames_in_lds, stack_hdrs,
-                                    hdr_stride, frames, voc, log, seq, my_steps);
-    __syncthreads();
+    FillWalkArgs wa;
+    wa.row = rows + b;
+    wa.stack_hdrs = stack_hdrs_;
+    wa.frames = frames_;
+    wa.tok_by_id = voc.tok_by_id;
+    wa.off_by_id = voc.off_by_id;
+    wa.bytes = voc.bytes;
+    wa.log = log;
+    wa.step_counter = step_counter;
+    wa.b = b;
+    wa.seg = seg;
+    wa.n_seg = voc.n_seg;
+    wa.seq = seq;
+    fill_walk_path<COUNT, APPLY != 0>(wa, (FillShared XGM_LDS*)&sm, (unsigned char XGM_LDS*)smem);
   }
   // 4. the words, and the logits of the segment; the last segment also takes the columns beyond the vocabulary
   for (int32_t w = tid; w < n_words; w += kFillThreads) out[(size_t)b * voc.W + w_begin + w] = sm.words[w];
@@ -1102,7 +1146,6 @@ __global__ __launch_bounds__(kFillThreads, 8) void fill_kernel(const RowDesc* __
     if (logits.e_end == id0 + kSegTokens && logits.e_end <= voc.V) logits.template whole_segment<kFillThreads>(tid);
     else logits.groups(tid, kFillThreads);
   }
-  if (COUNT && my_steps) atomicAdd(step_counter, my_steps);
 }
 
 
