@@ -918,42 +918,52 @@ struct FillShared {
   uint32_t any_walk;
 };
 
+
 // Decides the walk entries of the workgroup's lists (all threads call this).
 template <bool COUNT, bool KEEP_UNDECIDED, class Tab>
 __device__ __forceinline__ void fill_walks(const Tab& T, FillShared& sm, const RowDesc& rd, const int32_t b, const int32_t seg,
-                                           const uint32_t n_lists, const uint32_t frame0, const bool frames_in_lds,
+                                           const uint32_t n_stacks, const uint32_t frame0, const bool frames_in_lds,
                                            const XGM_GLOBAL uint32_t* __restrict__ stack_hdrs, const uint32_t hdr_stride,
                                            const XGM_GLOBAL uint16_t* __restrict__ frames, const DevVocab& voc,
                                            OverflowLog* log, uint32_t seq, unsigned long long& my_steps) {
   const XGM_GLOBAL uint32_t* entries = (const XGM_GLOBAL uint32_t*)rd.entries;
   const int32_t id0 = seg * kSegTokens;
-  for (uint32_t l = 0; l < n_lists; ++l) {
-    const XGM_GLOBAL uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + l / kStackLists) * hdr_stride;
-    const uint32_t top = sh[kStackHdrTop] & 0xFFFFu, depth = sh[kStackHdrDepth], f_off = sh[kStackHdrFrames];
+  for (uint32_t st = 0; st < n_stacks; ++st) {
+    // one round of loads per stack: its scalars and where its four lists begin in this segment and in the next
+    const XGM_GLOBAL uint32_t* sh = stack_hdrs + (size_t)(rd.stack_begin + st) * hdr_stride;
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    const XGM_GLOBAL v4u* off = (const XGM_GLOBAL v4u*)(sh + stack_hdr_off((uint32_t)seg, 0u));
+    const v4u scalars = *(const XGM_GLOBAL v4u*)sh, o0 = off[0], o1 = off[1];
+    const uint32_t top = scalars.x & 0xFFFFu, depth = scalars.y, f_off = scalars.z;
+    static_assert(kStackHdrTop == 0 && kStackHdrDepth == 1 && kStackHdrFrames == 2 && kStackHdrWords == 4 && kStackLists == 4,
+                  "a stack's scalars are one 16-byte load, a segment's list offsets another");
     LiveView live;
     live.lds = (const XGM_LDS uint16_t*)sm.live + (f_off - frame0);
     live.glob = frames + f_off;
     live.lo = frames_in_lds ? 0u : 0xFFFFFFFFu;
-    // the list's entries of this segment (it ends where its next segment begins); the accepted ones are done
-    const uint32_t begin = sh[stack_hdr_off((uint32_t)seg, l % kStackLists)], end = sh[stack_hdr_off((uint32_t)seg + 1u, l % kStackLists)];
-    for (uint32_t j = begin + threadIdx.x; j < end; j += kFillThreads) {
-      const uint32_t e = entries[j];
-      const uint32_t id = e & kEntryIdMask, kind = e >> kEntryKindShift, pos = (e >> kEntryPosShift) & 0xFFu;
-      if (kind == kEntryAccepted) continue;
-      const uint32_t rel = id - (uint32_t)id0;
-      if ((sm.words[rel >> 5] >> (rel & 31u)) & 1u) continue;  // already allowed
-      const uint32_t drop = kind == kEntryWalkTop ? 0u : kind - 1u;  // frames above the one the walk starts in
-      int res = kReject;
-      uint32_t n_steps = 0;
-      if (depth > drop) {
-        const TokenRef t = load_token(voc, (int32_t)id);
-        const uint32_t start = drop == 0u ? top : live[depth - 1u - drop];
-        res = walk_token<false>(T, t.tk, t.ext, t.len, start, live, depth - drop, COUNT ? &n_steps : nullptr,
-                                0u, drop == 0u ? 0 : (int)pos);
+    for (uint32_t l = 0; l < kStackLists; ++l) {  // (not unrolled: one copy of the walk)
+      // the list's entries of this segment; the accepted ones are done
+      const uint32_t begin = l == 0u ? o0.x : l == 1u ? o0.y : l == 2u ? o0.z : o0.w;
+      const uint32_t end = l == 0u ? o1.x : l == 1u ? o1.y : l == 2u ? o1.z : o1.w;
+      for (uint32_t j = begin + threadIdx.x; j < end; j += kFillThreads) {
+        const uint32_t e = entries[j];
+        const uint32_t id = e & kEntryIdMask, kind = e >> kEntryKindShift, pos = (e >> kEntryPosShift) & 0xFFu;
+        if (kind == kEntryAccepted) continue;
+        const uint32_t rel = id - (uint32_t)id0;
+        if ((sm.words[rel >> 5] >> (rel & 31u)) & 1u) continue;  // already allowed
+        const uint32_t drop = kind == kEntryWalkTop ? 0u : kind - 1u;  // frames above the one the walk starts in
+        int res = kReject;
+        uint32_t n_steps = 0;
+        if (depth > drop) {
+          const TokenRef t = load_token(voc, (int32_t)id);
+          const uint32_t start = drop == 0u ? top : live[depth - 1u - drop];
+          res = walk_token<false>(T, t.tk, t.ext, t.len, start, live, depth - drop, COUNT ? &n_steps : nullptr,
+                                  0u, drop == 0u ? 0 : (int)pos);
+        }
+        if (COUNT) my_steps += n_steps;
+        if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, id, rd.epoch);  // decided on the host
+        if (res == kAccept || (KEEP_UNDECIDED && res == kOverflow)) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31u));
       }
-      if (COUNT) my_steps += n_steps;
-      if (res == kOverflow) record_overflow(log, seq, (uint32_t)b, id, rd.epoch);  // decided on the host
-      if (res == kAccept || (KEEP_UNDECIDED && res == kOverflow)) atomicOr(&sm.words[rel >> 5], 1u << (rel & 31u));
     }
   }
 }
@@ -961,7 +971,8 @@ __device__ __forceinline__ void fill_walks(const Tab& T, FillShared& sm, const R
 // The whole of step 3, kept out of line: the request's tables and live frames into LDS, then the walks.  Nearly
 // no workgroup comes here, and inlined the walk's registers and code would weigh on every workgroup's path
 // (the kernel ran out of scalar registers and kept them in lanes of a vector register).  What it needs it
-// reads again: the row descriptor, and of the vocabulary the three arrays a token is fetched from.
+// reads again: the row descriptor, and of the vocabulary the three arrays a token is fetched from.  The call
+// itself costs a workgroup that walks about a microsecond (registers saved and restored through memory).
 struct FillWalkArgs {
   const RowDesc* row;
   const uint32_t* stack_hdrs;
@@ -986,7 +997,7 @@ __device__ __noinline__ void fill_walk_path(const FillWalkArgs a, FillShared XGM
   voc.off_by_id = a.off_by_id;
   voc.bytes = a.bytes;
   unsigned long long my_steps = 0;
-  const uint32_t frame0 = rd.frame_begin, n_frames = rd.n_frames, n_lists = rd.n_stacks * kStackLists;
+  const uint32_t frame0 = rd.frame_begin, n_frames = rd.n_frames;
   const uint32_t hdr_stride = stack_hdr_stride(a.n_seg);
   const bool frames_in_lds = n_frames <= kFillFramesLds;
   stage_tables(rd.tab, smem, kFillThreads);
@@ -994,10 +1005,10 @@ __device__ __noinline__ void fill_walk_path(const FillWalkArgs a, FillShared XGM
     for (uint32_t k = threadIdx.x; k < n_frames; k += kFillThreads) sm.live[k] = frames[frame0 + k];
   __syncthreads();
   if (small_sections_staged(rd.tab))
-    fill_walks<COUNT, KEEP_UNDECIDED>(LdsTabT<true>(rd.tab, smem), sm, rd, a.b, a.seg, n_lists, frame0, frames_in_lds, stack_hdrs,
+    fill_walks<COUNT, KEEP_UNDECIDED>(LdsTabT<true>(rd.tab, smem), sm, rd, a.b, a.seg, rd.n_stacks, frame0, frames_in_lds, stack_hdrs,
                                       hdr_stride, frames, voc, a.log, a.seq, my_steps);
   else
-    fill_walks<COUNT, KEEP_UNDECIDED>(LdsTab(rd.tab, smem), sm, rd, a.b, a.seg, n_lists, frame0, frames_in_lds, stack_hdrs,
+    fill_walks<COUNT, KEEP_UNDECIDED>(LdsTab(rd.tab, smem), sm, rd, a.b, a.seg, rd.n_stacks, frame0, frames_in_lds, stack_hdrs,
                                       hdr_stride, frames, voc, a.log, a.seq, my_steps);
   __syncthreads();
   if (COUNT && my_steps) atomicAdd(a.step_counter, my_steps);
