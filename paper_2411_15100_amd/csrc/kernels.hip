@@ -86,20 +86,6 @@ struct LdsTabT {
       if (c >= lo && c <= hi) { k = 1; single = (0xFFFFu << 16) | (h.x >> 16); }
     }
   }
-  __device__ __forceinline__ bool plain_move(uint32_t n, uint32_t c, uint32_t& dst, uint32_t& fin, uint32_t& after) const {
-    const uint2 h = header(n);
-    fin = h.y & 1u;
-    after = (rd32(off_follow + ((h.y >> 16) * 8u + (c >> 5)) * 4u, follow_lds) >> (c & 31)) & 1u;
-    if (h.y & 2u) {
-      const uint32_t cl = rd8(c, cls_lds);
-      const uint32_t si = rd8(off_shapes + (h.x & 0xFFFFu) * n_cls + cl, shapes_lds);
-      if (si == 0xFFu) return false;
-      dst = rd16(off_targets + ((h.x >> 16) + si) * 2u, targets_lds);
-      return dst < 0x8000u;
-    }
-    dst = h.x >> 16;
-    return c >= (h.x & 0xFFu) && c <= ((h.x >> 8) & 0xFFu);
-  }
   __device__ __forceinline__ uint32_t alt(uint32_t idx) const { return rd32(off_alts + idx * 4u, alts_lds); }
   __device__ __forceinline__ bool is_final(uint32_t n) const { return header(n).y & 1u; }
   __device__ __forceinline__ bool is_dead_end(uint32_t n) const { return header(n).y & 4u; }

@@ -46,21 +46,6 @@ struct CompactTab {
       if (c >= lo && c <= hi) { k = 1; single = (0xFFFFu << 16) | (h.x >> 16); }
     }
   }
-  // The step at (n, c) when it is nothing but a move along a byte edge (one alternative, no rule reference):
-  // true, the node moved to, and `fin` / `after` as in lookup().  False for every other kind of step.
-  XGM_HD bool plain_move(uint32_t n, uint32_t c, uint32_t& dst, uint32_t& fin, uint32_t& after) const {
-    const uint2 h = (n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n];
-    fin = h.y & 1u;
-    after = (v.follow_rules[(h.y >> 16) * 8 + (c >> 5)] >> (c & 31)) & 1u;
-    if (h.y & 2u) {
-      const uint32_t si = v.shapes[(h.x & 0xFFFFu) * v.n_cls + v.cls[c]];
-      if (si == 0xFFu) return false;
-      dst = v.targets[(h.x >> 16) + si];
-      return dst < 0x8000u;
-    }
-    dst = h.x >> 16;
-    return c >= (h.x & 0xFFu) && c <= ((h.x >> 8) & 0xFFu);
-  }
   XGM_HD uint32_t alt(uint32_t idx) const { return v.alts[idx]; }
   XGM_HD bool is_final(uint32_t n) const { return ((n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n]).y & 1u; }
   XGM_HD bool is_dead_end(uint32_t n) const { return ((n < (uint32_t)v.n_near) ? v.hdr_near[n] : v.hdr_far[n]).y & 4u; }
@@ -140,7 +125,7 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
   uint2 choice[kChoicePoints];   // x = node | sp << 16 ; y = i | alt << 8 | top << 16 | f << 24
   uint32_t n = start_node, sp = kLiveBase + depth - 1, f = 1, alt = 0, top = 0, csp = 0;
   int i = i0;
-  bool left_frame = false, left_frame_follow = false;
+  uint32_t left_frame = 0u;  // bit 0: the start frame was left with bytes remaining, bit 1: in front of a byte of `follow`
   for (int steps = 0;; ++steps) {
     if (steps_out) *steps_out = (uint32_t)steps;
     if (i == len && !End::kEnumerate) return kAccept;
@@ -158,15 +143,20 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
         // The start frame may end here (nothing is known below it): noted at once instead of kept as a
         // pending alternative, so that a run through a rule that may end after every byte (the inside of
         // a string, a number) leaves nothing to come back to.
-        left_frame = true;
-        if (T.follows(follow, c)) {
-          left_frame_follow = true;
-          if (exits_out) *exits_out |= 1u << (i < 31 ? i : 31);
-        }
+        const uint32_t fo = T.follows(follow, c);
+        left_frame |= 1u | (fo << 1);
+        if (exits_out && fo) *exits_out |= 1u << (i < 31 ? i : 31);
         can_pop = 0u;
       }
       if (!BUILD) can_pop &= after;  // a return in front of a byte that can never follow the rule leads nowhere
       const uint32_t total = k + can_pop;
+      // nothing but a move along a byte edge (most steps inside a string, a number, a name): taken at once
+      if (alt == 0u && total == 1u && k == 1u && !pooled) {
+        n = single & 0xFFFFu;
+        ++i;
+        f = 1;
+        continue;
+      }
       if (alt < total) {
         bool ok = true;
         if (alt + 1 < total) {
@@ -214,7 +204,7 @@ XGM_HD int walk_token(const Tab& T, const uint4 tk, const uint8_t* ext, const in
       f = (ch.y >> 24) & 1u;
     }
   }
-  if (BUILD && left_frame) return left_frame_follow ? kUncertain : kUncertainPlain;
+  if (BUILD && left_frame) return (left_frame & 2u) ? kUncertain : kUncertainPlain;
   return kReject;
 }
 
