@@ -183,6 +183,13 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
     }
   }
   const int32_t word = (blockIdx.x * kClassifyThreads + (threadIdx.x & ~63)) >> 5;  // even
+  // Do all tokens of the wave begin with the same byte?  (In byte-sorted order most waves' do.)  Then what the
+  // first byte settles at a node is the same for every lane, and the nodes that need no walk need no loop.
+  const bool has = live_lane && len > 0;
+  const unsigned long long has_mask = __ballot(has);
+  const uint32_t c0 = tk.x & 0xFFu;
+  const uint32_t c_wave = has_mask ? (uint32_t)__shfl((int)c0, __ffsll((long long)has_mask) - 1, 64) : 0u;
+  const bool one_first_byte = has_mask != 0ull && __ballot(has && c0 == c_wave) == has_mask;
   const int32_t n_begin = blockIdx.y * nodes_per_block;
   const int32_t n_end = min(n_begin + nodes_per_block, n_nodes);
   // Most pairs are settled by the token's first byte: if the node cannot
@@ -199,6 +206,25 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
     // them out together (a handful of store instructions per 32 nodes instead of several per node).
     const uint32_t lane = threadIdx.x & 63u;
     unsigned long long keep_a = 0ull, keep_u = 0ull, keep_p = 0ull;
+    if (one_first_byte) {
+      // the lane's own node, settled by the first byte unless it is walked below
+      const uint4 fbw = first_byte[(size_t)c_wave * n_words + ((uint32_t)(node0 + k0) >> 5)];  // (the same for the wave)
+      const uint32_t span = k1 - k0 >= 32 ? 0xFFFFFFFFu : (1u << (k1 - k0)) - 1u;
+      if (lane < 32u && (((fbw.y >> shift) >> lane) & 1u)) keep_u = has_mask;
+      if (lane < 32u && (((fbw.z >> shift) >> lane) & 1u)) keep_p = has_mask;
+      for (uint32_t todo = (fbw.x >> shift) & span; todo; todo &= todo - 1u) {
+        const int32_t k = k0 + __ffs(todo) - 1;
+        int res = kReject;
+        if (has) {
+          res = walk_token<true>(T, tk, ext, len, (uint32_t)(node0 + k), (const uint16_t*)nullptr, 1u, nullptr, T.follow_of(node0 + k));
+          if (res == kOverflow) { record_overflow(log, seq, (uint32_t)k, (uint32_t)r); res = kReject; }
+        }
+        const unsigned long long a = __ballot(res == kAccept);
+        const unsigned long long u = __ballot(res == kUncertain);
+        const unsigned long long p = __ballot(res == kUncertainPlain);
+        if (lane == (uint32_t)(k - k0)) { keep_a = a; keep_u = u; keep_p = p; }
+      }
+    } else
     for (int32_t k = k0; k < k1; ++k) {
       const uint32_t bit = 1u << (k - k0);
       int res = (exits_follow & bit) ? kUncertain : (exits_plain & bit) ? kUncertainPlain : kReject;
