@@ -167,8 +167,19 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
                                               const uint4* __restrict__ first_byte, uint32_t n_words,
                                               uint32_t* __restrict__ acc_rank, uint32_t* __restrict__ unc_rank,
                                               uint32_t* __restrict__ plain_rank, uint32_t* __restrict__ plain_count,
-                                              OverflowLog* log, uint32_t seq, int32_t nodes_per_block) {
-  const int32_t r = blockIdx.x * kClassifyThreads + threadIdx.x;
+                                              OverflowLog* log, uint32_t seq, int32_t nodes_per_block,
+                                              int32_t items_per_wave, uint32_t* next_item) {
+  // A workgroup owns a run of kClassifyThreads * items_per_wave tokens, cut into items of 64; its waves draw
+  // items from a counter in LDS, so that none of them waits for the slowest walks of another (a workgroup keeps
+  // its LDS, and so its place on the compute unit, until its last wave is done).
+  const int32_t chunk0 = blockIdx.x * kClassifyThreads * items_per_wave;
+  const int32_t n_items = min((kClassifyThreads / 64) * items_per_wave, (voc.V - chunk0 + 63) / 64);
+  for (;;) {
+  int32_t item = 0;
+  if ((threadIdx.x & 63u) == 0u) item = (int32_t)atomicAdd(next_item, 1u);
+  item = __builtin_amdgcn_readfirstlane(item);
+  if (item >= n_items) break;
+  const int32_t r = chunk0 + item * 64 + (int32_t)(threadIdx.x & 63u);
   const bool live_lane = r < voc.V;
   uint4 tk = make_uint4(0, 0, 0, 0);
   const uint8_t* ext = voc.bytes;
@@ -182,7 +193,7 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
       if (len == 255) len = (int)(voc.off_by_id[id + 1] - voc.off_by_id[id]);
     }
   }
-  const int32_t word = (blockIdx.x * kClassifyThreads + (threadIdx.x & ~63)) >> 5;  // even
+  const int32_t word = (chunk0 + item * 64) >> 5;  // even
   // Do all tokens of the wave begin with the same byte?  (In byte-sorted order most waves' do.)  Then what the
   // first byte settles at a node is the same for every lane, and the nodes that need no walk need no loop.
   const bool has = live_lane && len > 0;
@@ -245,6 +256,7 @@ __device__ __forceinline__ void classify_body(const Tab& T, const DevVocab& voc,
       if (keep_p) atomicAdd(&plain_count[node0 + k0 + (int32_t)lane], (uint32_t)__popcll(keep_p));
     }
   }
+  }
 }
 
 
@@ -252,16 +264,18 @@ template <int kClassifyThreads>
 __global__ __launch_bounds__(kClassifyThreads) void classify_kernel(
     DevTables tab, DevVocab voc, int32_t node0, int32_t n_nodes, const uint4* __restrict__ first_byte, uint32_t n_words,
     uint32_t* __restrict__ acc_rank, uint32_t* __restrict__ unc_rank, uint32_t* __restrict__ plain_rank,
-    uint32_t* __restrict__ plain_count, OverflowLog* log, uint32_t seq, int32_t nodes_per_block) {
+    uint32_t* __restrict__ plain_count, OverflowLog* log, uint32_t seq, int32_t nodes_per_block, int32_t items_per_wave) {
   extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ uint32_t next_item;
+  if (threadIdx.x == 0) next_item = 0u;
   stage_tables(tab, smem, kClassifyThreads);
   __syncthreads();
   if (small_sections_staged(tab))
     classify_body<kClassifyThreads>(LdsTabT<true>(tab, smem), voc, node0, n_nodes, first_byte, n_words, acc_rank, unc_rank,
-                                    plain_rank, plain_count, log, seq, nodes_per_block);
+                                    plain_rank, plain_count, log, seq, nodes_per_block, items_per_wave, &next_item);
   else
     classify_body<kClassifyThreads>(LdsTab(tab, smem), voc, node0, n_nodes, first_byte, n_words, acc_rank, unc_rank,
-                                    plain_rank, plain_count, log, seq, nodes_per_block);
+                                    plain_rank, plain_count, log, seq, nodes_per_block, items_per_wave, &next_item);
 }
 
 // Many nodes of a grammar have the same accepted bitset (the inside of a string is
@@ -1567,6 +1581,16 @@ void launch_first_byte(const DevTables& tab, uint4* first_byte, hipStream_t stre
                      dim3(kFirstByteThreads), 0, stream, tab, n_words, first_byte);
 }
 
+// Items of 64 tokens that a wave of the classify kernel takes on average.  Measured at 128256 tokens: the large
+// workgroups (whose LDS holds a compute unit's place until their slowest wave is done) gain from four
+// (11867-node schema grammar 1.68 -> 1.42 ms; eight: the same); the small ones from two when the grid has few
+// node groups (JSON, 19 groups: 0.18 -> 0.14 ms) and from none when it has many (C/SQL, 187 groups: 1.62 ms
+// with one, 1.66 with two, 2.0 with four).
+static int32_t classify_items_per_wave(int threads, int32_t ny) {
+  if (threads == kClassifyThreadsLarge) return 4;
+  return ny < 64 ? 2 : 1;
+}
+
 void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, int32_t n, const uint4* first_byte,
                      uint32_t* acc_rank, uint32_t* unc_rank, uint32_t* plain_rank, uint32_t* plain_count, OverflowLog* log,
                      uint32_t seq, hipStream_t stream) {
@@ -1578,16 +1602,18 @@ void launch_classify(const DevTables& tab, const DevVocab& voc, int32_t node0, i
   if (st.stage_bytes <= kClassifySmallStage) {
     const int32_t per_block = n >= kManyNodes ? kNodesPerBlockMany : kNodesPerBlockSmall;
     const int32_t ny = (n + per_block - 1) / per_block;
-    hipLaunchKernelGGL(classify_kernel<kClassifyThreadsSmall>,
-                       dim3((voc.V + kClassifyThreadsSmall - 1) / kClassifyThreadsSmall, ny), dim3(kClassifyThreadsSmall),
+    const int32_t items = classify_items_per_wave(kClassifyThreadsSmall, ny);
+    const int32_t chunk = kClassifyThreadsSmall * items;
+    hipLaunchKernelGGL(classify_kernel<kClassifyThreadsSmall>, dim3((voc.V + chunk - 1) / chunk, ny), dim3(kClassifyThreadsSmall),
                        st.stage_bytes, stream, st, voc, node0, n, first_byte, n_words, acc_rank, unc_rank, plain_rank,
-                       plain_count, log, seq, per_block);
+                       plain_count, log, seq, per_block, items);
   } else {
     const int32_t ny = (n + kNodesPerBlockLarge - 1) / kNodesPerBlockLarge;
-    hipLaunchKernelGGL(classify_kernel<kClassifyThreadsLarge>,
-                       dim3((voc.V + kClassifyThreadsLarge - 1) / kClassifyThreadsLarge, ny), dim3(kClassifyThreadsLarge),
+    const int32_t items = classify_items_per_wave(kClassifyThreadsLarge, ny);
+    const int32_t chunk = kClassifyThreadsLarge * items;
+    hipLaunchKernelGGL(classify_kernel<kClassifyThreadsLarge>, dim3((voc.V + chunk - 1) / chunk, ny), dim3(kClassifyThreadsLarge),
                        st.stage_bytes, stream, st, voc, node0, n, first_byte, n_words, acc_rank, unc_rank, plain_rank,
-                       plain_count, log, seq, kNodesPerBlockLarge);
+                       plain_count, log, seq, kNodesPerBlockLarge, items);
   }
 }
 
