@@ -689,16 +689,17 @@ __device__ __forceinline__ void context_deeper_body(const Tab& T, const DevVocab
     const uint32_t kb = a.k_base[level - 1u][rec.y];
     uint4* keep = WRITE ? nullptr : a.deep_outcomes[level - 1u];
     static_assert(kContextsPerThread == 8, "a record's outcomes are eight 16-bit codes in one uint4");
-    uint32_t codes[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
+    unsigned long long lo = 0ull, hi = 0ull;  // (the loop is not unrolled: one copy of the walk, not eight)
+#pragma unroll 1
     for (uint32_t q = 0; q < kContextsPerThread; ++q) {
       const uint32_t j = j0 + q;
       if (j >= m) break;
       uint32_t outcome = 0u;
       w.step(level, a.ctx_node[cb + j], kb + j, rec.z, (rec.w & 0x10000u) != 0u, keep ? &outcome : nullptr);
-      codes[q >> 1] |= outcome << ((q & 1u) * 16u);
+      if (q < 4u) lo |= (unsigned long long)outcome << (q * 16u);
+      else hi |= (unsigned long long)outcome << ((q - 4u) * 16u);
     }
-    if (keep) keep[item] = make_uint4(codes[0], codes[1], codes[2], codes[3]);
+    if (keep) keep[item] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
   }
 }
 template <bool WRITE>
