@@ -6,8 +6,8 @@ fill (kernel b) + in-place -inf apply (kernel c) for the serving workload
 bf16 logits), with everything it reads resident in device memory: the mask
 caches, the logits and the matcher states (xgm_batch_*), done in one launch
 (xgm_batch_fill_and_apply: mask written, logits masked).  The headline is the
-median of several passes of exactly K such steps, each pass between two
-synchronisations.  Timed beside it, in the same JSON line: the same step as
+median of several passes of exactly K such steps, each pass on freshly drawn
+logits, after W untimed warm-up steps, between two synchronisations.  Timed beside it, in the same JSON line: the same step as
 two calls (fill, then apply), both forms from host-side matcher states, the
 whole decode cycle (accept the sampled tokens on the device, then fill and
 apply), the smaller workloads (configs 1-3), the mask-cache build (config 4)
@@ -89,12 +89,13 @@ def main():
     traffic = counter_traffic()
 
     def timed_passes(step, refresh, passes=P, warmup=0):
-        """`passes` passes of exactly K steps, each between two synchronisations: microseconds per step of each."""
-        for k in range(warmup):
-            step(k, stream)
+        """`passes` passes of exactly K steps, each between two synchronisations and after `warmup` untimed
+        steps on freshly drawn logits: microseconds per step of each."""
         out = []
         for _ in range(passes):
             refresh()
+            for k in range(warmup):
+                step(k, stream)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for k in range(K):
@@ -104,10 +105,13 @@ def main():
         return out
 
     def event_us(step, refresh, passes=3):
-        """Average duration of one launch by HIP events on the launch stream around K back-to-back launches."""
+        """Average duration of one launch by HIP events on the launch stream around K back-to-back launches
+        (passes as in timed_passes: freshly drawn logits, then the warm-up steps)."""
         out = []
         for _ in range(passes):
             refresh()
+            for k in range(args.warmup):
+                step(k, stream)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
@@ -513,8 +517,9 @@ def main():
         "ms_per_step": us_per_step * 1e-3,
         "fill_plus_apply_us": us_per_step,
         "fill_plus_apply_us_per_pass": fused_passes,
-        "step_form": "one launch (xgm_batch_fill_and_apply); median of `passes` passes of exactly `steps` steps, each between "
-                     "two synchronisations; the two-call form is timed in two_call_path",
+        "step_form": "one launch (xgm_batch_fill_and_apply); median of `passes` passes of exactly `steps` steps, each on "
+                     "freshly drawn logits, after `warmup` untimed steps, between two synchronisations; the two-call form is "
+                     "timed in two_call_path",
         "two_call_path": {"fill_plus_apply_us": two_call_us, "fill_alone_us": fill_only_us, "apply_alone_us": apply_only_us,
                           "note": "xgm_batch_fill_next_token_bitmask, then xgm_apply_token_bitmask_inplace"},
         "host_state_path": {"fill_plus_apply_us": host_state_us, "fused_fill_and_apply_us": host_state_fused_us,
